@@ -1,0 +1,214 @@
+"""CPU oracle (test infrastructure only).
+
+Thin ctypes wrapper over ``mqg_oracle.c``: the plain single-threaded C
+statement of cache build, L-hop neighbour sampling into bipartite blocks,
+feature gather and mean aggregation.  Only the tests, the smoke check and the
+benchmark's CPU-baseline leg may import this package; it shares nothing with
+the GPU implementation and never imports it.
+
+Inputs and outputs are numpy arrays.  Node ids, offsets and counts are int64.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mqg_oracle.c")
+_LIB = os.path.join(_HERE, "liboracle.so")
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (a few hundred lines of C; under a second)."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fno-fast-math",
+                               "-Wall", "-Wextra", "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    lib = ctypes.CDLL(build())
+    i64, u64, i32, vp = ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p
+    lib.orc_mix.restype = u64
+    lib.orc_mix.argtypes = [u64]
+    lib.orc_key.restype = u64
+    lib.orc_key.argtypes = [u64, i64, i64, i64]
+    lib.orc_build_cache.restype = ctypes.c_int
+    lib.orc_build_cache.argtypes = [i64, vp, i64, vp, vp]
+    lib.orc_fill_cache_rows.restype = None
+    lib.orc_fill_cache_rows.argtypes = [vp, i64, vp, i64, i64, vp, i64]
+    lib.orc_sample_row.restype = i64
+    lib.orc_sample_row.argtypes = [u64, i64, i64, i64, i64, vp]
+    lib.orc_sample_block.restype = i64
+    lib.orc_sample_block.argtypes = [vp, vp, vp, i64, i64, i64, u64, i64, i64, vp, vp, vp, vp]
+    lib.orc_gather.restype = None
+    lib.orc_gather.argtypes = [vp, i64, vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]
+    lib.orc_half_to_double.restype = ctypes.c_double
+    lib.orc_half_to_double.argtypes = [ctypes.c_uint16]
+    lib.orc_float_to_half.restype = ctypes.c_uint16
+    lib.orc_float_to_half.argtypes = [ctypes.c_float]
+    lib.orc_mean_aggregate.restype = None
+    lib.orc_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, ctypes.c_int]
+    _lib = lib
+    return lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _i64(a) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a), dtype=np.int64)
+
+
+# ------------------------------------------------------------------ keys
+
+def mix(z: int) -> int:
+    return int(_load().orc_mix(ctypes.c_uint64(z & 0xFFFFFFFFFFFFFFFF)))
+
+
+def key(rng_seed: int, layer: int, node: int, slot: int) -> int:
+    return int(_load().orc_key(ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), layer, node, slot))
+
+
+def sample_row(rng_seed: int, layer: int, node: int, degree: int, fanout: int) -> np.ndarray:
+    out = np.empty(max(1, fanout), dtype=np.int64)
+    c = _load().orc_sample_row(ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), layer, node,
+                               degree, fanout, _p(out))
+    return out[:c].copy()
+
+
+# ----------------------------------------------------------------- cache
+
+@dataclass
+class Cache:
+    cached_ids: np.ndarray      # int64[num_cached], slot order
+    slot_of: np.ndarray         # int32[N], -1 when not cached
+    cache_rows: Optional[np.ndarray] = None   # [num_cached, dim] copy of the cached feature rows
+
+
+def build_cache(row_ptr, num_cached: int, feats: Optional[np.ndarray] = None) -> Cache:
+    rp = _i64(row_ptr)
+    n = rp.shape[0] - 1
+    ids = np.empty(max(1, num_cached), dtype=np.int64)
+    slot_of = np.empty(max(1, n), dtype=np.int32)
+    rc = _load().orc_build_cache(n, _p(rp), num_cached, _p(ids), _p(slot_of))
+    if rc != 0:
+        raise ValueError(f"orc_build_cache failed ({rc})")
+    ids = ids[:num_cached]
+    slot_of = slot_of[:n]
+    rows = None
+    if feats is not None:
+        assert feats.ndim == 2 and feats.strides[1] == feats.itemsize
+        rows = np.zeros((num_cached, feats.shape[1]), dtype=feats.dtype)
+        _load().orc_fill_cache_rows(_p(ids), num_cached, _p(feats), feats.strides[0],
+                                    feats.shape[1] * feats.itemsize, _p(rows),
+                                    rows.strides[0] if num_cached else 0)
+    return Cache(ids, slot_of, rows)
+
+
+# -------------------------------------------------------------- sampling
+
+@dataclass
+class Block:
+    num_dst: int
+    src_ids: np.ndarray     # int64[num_src]; src_ids[:num_dst] are the destination nodes
+    indptr: np.ndarray      # int64[num_dst+1]
+    indices: np.ndarray     # int32[nnz], positions in src_ids
+    nbr_global: np.ndarray  # int64[nnz], global ids of the sampled neighbours
+
+    @property
+    def num_src(self) -> int:
+        return int(self.src_ids.shape[0])
+
+    @property
+    def nnz(self) -> int:
+        return int(self.indices.shape[0])
+
+
+def sample_blocks(row_ptr, col_idx, seeds, fanouts: Sequence[int], rng_seed: int) -> List[Block]:
+    """blocks[l] feeds GNN layer l; blocks[L-1] has the seeds as destinations and
+    uses fanouts[L-1]; the destinations of blocks[l-1] are the sources of blocks[l]."""
+    rp, ci, dst = _i64(row_ptr), _i64(col_idx), _i64(seeds)
+    n = rp.shape[0] - 1
+    L = len(fanouts)
+    blocks: List[Optional[Block]] = [None] * L
+    lib = _load()
+    for l in range(L - 1, -1, -1):
+        k = int(fanouts[l])
+        nd = dst.shape[0]
+        cap_nnz = nd * k
+        cap_src = min(n, nd + cap_nnz) if n > 0 else nd
+        cap_src = max(cap_src, nd)
+        indptr = np.empty(nd + 1, dtype=np.int64)
+        nbr = np.empty(max(1, cap_nnz), dtype=np.int64)
+        src = np.empty(max(1, cap_src), dtype=np.int64)
+        idx = np.empty(max(1, cap_nnz), dtype=np.int32)
+        ns = lib.orc_sample_block(_p(rp), _p(ci), _p(dst), nd, k, l,
+                                  ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), cap_nnz, cap_src,
+                                  _p(indptr), _p(nbr), _p(src), _p(idx))
+        if ns < 0:
+            raise RuntimeError(f"orc_sample_block failed ({ns})")
+        nnz = int(indptr[nd])
+        blocks[l] = Block(nd, src[:ns].copy(), indptr, idx[:nnz].copy(), nbr[:nnz].copy())
+        dst = blocks[l].src_ids
+    return blocks  # type: ignore[return-value]
+
+
+# ---------------------------------------------------------------- gather
+
+def gather(ids, feats: np.ndarray, cache: Optional[Cache] = None):
+    """Return (rows[len(ids), dim], hits, misses)."""
+    ids = _i64(ids)
+    assert feats.ndim == 2 and feats.strides[1] == feats.itemsize
+    out = np.zeros((ids.shape[0], feats.shape[1]), dtype=feats.dtype)
+    hits, misses = ctypes.c_int64(0), ctypes.c_int64(0)
+    slot_of = rows = None
+    cstride = 0
+    if cache is not None:
+        slot_of = np.ascontiguousarray(cache.slot_of, dtype=np.int32)
+        rows = cache.cache_rows
+        assert rows is not None
+        cstride = rows.strides[0] if rows.shape[0] else 0
+    _load().orc_gather(_p(ids), ids.shape[0], _p(feats), feats.strides[0], _p(slot_of), _p(rows),
+                       cstride, feats.shape[1] * feats.itemsize, _p(out),
+                       out.strides[0] if ids.shape[0] else 0, ctypes.byref(hits),
+                       ctypes.byref(misses))
+    return out, int(hits.value), int(misses.value)
+
+
+# ------------------------------------------------------------- aggregate
+
+def mean_aggregate(indptr, indices, x: np.ndarray) -> np.ndarray:
+    """x: [num_src, dim] float32 or float16; returns [num_dst, dim] of the same dtype."""
+    ip = _i64(indptr)
+    ix = np.ascontiguousarray(np.asarray(indices), dtype=np.int32)
+    assert x.dtype in (np.float32, np.float16) and x.ndim == 2
+    x = np.ascontiguousarray(x)
+    nd = ip.shape[0] - 1
+    out = np.zeros((nd, x.shape[1]), dtype=x.dtype)
+    _load().orc_mean_aggregate(_p(ip), _p(ix), nd, _p(x), x.shape[1], _p(out), x.shape[1],
+                               x.shape[1], 1 if x.dtype == np.float16 else 0)
+    return out
+
+
+def half_to_double(bits: int) -> float:
+    return float(_load().orc_half_to_double(ctypes.c_uint16(bits)))
+
+
+def float_to_half(f: float) -> int:
+    return int(_load().orc_float_to_half(ctypes.c_float(f)))

@@ -1,0 +1,355 @@
+/*
+ * CPU oracle for mini-batch generation in sampled GNN training.
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the slow, single-threaded,
+ * plainly written statement of what the GPU library must compute.  It is
+ * used by the tests, by the smoke check and by the benchmark's CPU-baseline
+ * leg; no product code path may call it.  It shares no code, header, table
+ * or helper with the GPU implementation.
+ *
+ * All node ids, offsets and counts are int64 here; every floating-point
+ * reduction is carried out in double.
+ *
+ * What each function follows in the paper (MQ-GNN):
+ *   - orc_build_cache      : Sec. III "Feature Cache" (node cache C of
+ *                            high-degree nodes whose features are preloaded
+ *                            on the GPU; Eq. 13 ranks by in-degree).  Read
+ *                            deterministically: the num_cached nodes of
+ *                            highest degree, ties to the lower id.
+ *   - orc_sample_blocks    : Sec. III-A "Node-wise Sampling", GraphSAGE
+ *                            paragraph: for every node of a layer a fixed
+ *                            number s_node of its neighbours is drawn
+ *                            uniformly at random; the sampled set carries a
+ *                            layer superscript (text after Eq. 3), so a node
+ *                            is re-sampled in every layer it appears in.
+ *                            Sec. IV "Mini-Batch Transfer": a mini-batch
+ *                            carries topology and features.
+ *   - orc_gather           : Sec. IV "Mini-Batch Transfer To GPU": features
+ *                            of nodes absent from the GPU cache come from
+ *                            host memory, the rest from the cache; the
+ *                            result is the feature rows of the block's
+ *                            source nodes.
+ *   - orc_mean_aggregate   : Eq. 16, Z_agg(v) = Mean(H(v)) over the sampled
+ *                            neighbours of v (the GA step, "AH").
+ *
+ * Randomness is a pure function of its coordinates: the key of slot j in
+ * the adjacency row of node v at block l under seed s is
+ *     key = mix(mix(mix(mix(s + GOLDEN) ^ l) ^ v) ^ j)
+ * where mix is the 64-bit finaliser of the SplitMix64 generator (Steele,
+ * Lea, Flood 2014).  A row of d > k entries keeps the k slots with the
+ * smallest (key, slot) pairs - a uniform k-subset when keys are i.i.d.
+ * uniform, the equal-weights case of sampling by random keys (Efraimidis
+ * and Spirakis, cited by the paper in Sec. III-B).
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_GOLDEN 0x9E3779B97F4A7C15ULL
+
+uint64_t orc_mix(uint64_t z)
+{
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+uint64_t orc_key(uint64_t rng_seed, int64_t layer, int64_t node, int64_t slot)
+{
+    uint64_t h = orc_mix(rng_seed + ORC_GOLDEN);
+    h = orc_mix(h ^ (uint64_t)layer);
+    h = orc_mix(h ^ (uint64_t)node);
+    return orc_mix(h ^ (uint64_t)slot);
+}
+
+/* ---------------------------------------------------------------- cache */
+
+typedef struct { int64_t deg; int64_t id; } orc_deg_id;
+
+static int cmp_deg_desc_id_asc(const void *a, const void *b)
+{
+    const orc_deg_id *x = a, *y = b;
+    if (x->deg != y->deg) return x->deg > y->deg ? -1 : 1;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return 0;
+}
+
+/* Rank all nodes by (degree descending, id ascending); the first num_cached
+ * are cached, slot s holding the s-th ranked node.  slot_of[v] = s or -1. */
+int orc_build_cache(int64_t num_nodes, const int64_t *row_ptr, int64_t num_cached,
+                    int64_t *cached_ids, int32_t *slot_of)
+{
+    if (num_cached < 0 || num_cached > num_nodes) return -1;
+    orc_deg_id *all = malloc((size_t)(num_nodes > 0 ? num_nodes : 1) * sizeof *all);
+    if (!all) return -2;
+    for (int64_t v = 0; v < num_nodes; ++v) {
+        all[v].deg = row_ptr[v + 1] - row_ptr[v];
+        all[v].id = v;
+    }
+    qsort(all, (size_t)num_nodes, sizeof *all, cmp_deg_desc_id_asc);
+    for (int64_t v = 0; v < num_nodes; ++v) slot_of[v] = -1;
+    for (int64_t s = 0; s < num_cached; ++s) {
+        cached_ids[s] = all[s].id;
+        slot_of[all[s].id] = (int32_t)s;
+    }
+    free(all);
+    return 0;
+}
+
+/* cache_rows[s] = feats[cached_ids[s]] as bytes */
+void orc_fill_cache_rows(const int64_t *cached_ids, int64_t num_cached, const uint8_t *feats,
+                         int64_t feat_stride_bytes, int64_t row_bytes, uint8_t *cache_rows,
+                         int64_t cache_stride_bytes)
+{
+    for (int64_t s = 0; s < num_cached; ++s)
+        memcpy(cache_rows + s * cache_stride_bytes, feats + cached_ids[s] * feat_stride_bytes,
+               (size_t)row_bytes);
+}
+
+/* ------------------------------------------------------------- sampling */
+
+typedef struct { uint64_t key; int64_t slot; } orc_key_slot;
+
+static int cmp_key_slot(const void *a, const void *b)
+{
+    const orc_key_slot *x = a, *y = b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->slot != y->slot) return x->slot < y->slot ? -1 : 1;
+    return 0;
+}
+
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return x < y ? -1 : (x > y ? 1 : 0);
+}
+
+/* Chosen slots of one adjacency row of length d, ascending; returns their
+ * number min(k, d).  out_slots has room for k entries. */
+int64_t orc_sample_row(uint64_t rng_seed, int64_t layer, int64_t node, int64_t d, int64_t k,
+                       int64_t *out_slots)
+{
+    if (d <= k) {
+        for (int64_t j = 0; j < d; ++j) out_slots[j] = j;
+        return d;
+    }
+    orc_key_slot *ks = malloc((size_t)d * sizeof *ks);
+    for (int64_t j = 0; j < d; ++j) {
+        ks[j].key = orc_key(rng_seed, layer, node, j);
+        ks[j].slot = j;
+    }
+    qsort(ks, (size_t)d, sizeof *ks, cmp_key_slot);
+    for (int64_t j = 0; j < k; ++j) out_slots[j] = ks[j].slot;
+    free(ks);
+    qsort(out_slots, (size_t)k, sizeof *out_slots, cmp_i64);
+    return k;
+}
+
+typedef struct { int64_t id; int64_t pos; } orc_id_pos;
+
+static int cmp_id_pos(const void *a, const void *b)
+{
+    const orc_id_pos *x = a, *y = b;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return x->pos < y->pos ? -1 : (x->pos > y->pos ? 1 : 0);
+}
+
+/* position of id in a sorted orc_id_pos array, or -1 */
+static int64_t find_id(const orc_id_pos *a, int64_t n, int64_t id)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (a[mid].id < id) lo = mid + 1; else hi = mid;
+    }
+    return (lo < n && a[lo].id == id) ? lo : -1;
+}
+
+static int64_t find_i64(const int64_t *a, int64_t n, int64_t x)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        int64_t mid = lo + (hi - lo) / 2;
+        if (a[mid] < x) lo = mid + 1; else hi = mid;
+    }
+    return (lo < n && a[lo] == x) ? lo : -1;
+}
+
+/*
+ * One block: destination nodes dst[0..num_dst) with fanout k at block index
+ * `layer`.  Outputs:
+ *   indptr[num_dst+1]   running count of sampled neighbours per destination
+ *   nbr[nnz]            sampled neighbours (global ids), rows in destination
+ *                       order, within a row in ascending adjacency slot
+ *   src[num_src]        dst, followed by the sampled neighbours that are not
+ *                       in dst, each once, ascending
+ *   indices[nnz]        position of nbr[e] in src
+ * Returns num_src, or a negative value on capacity overflow / no memory.
+ */
+int64_t orc_sample_block(const int64_t *row_ptr, const int64_t *col_idx, const int64_t *dst,
+                         int64_t num_dst, int64_t k, int64_t layer, uint64_t rng_seed,
+                         int64_t cap_nnz, int64_t cap_src, int64_t *indptr, int64_t *nbr,
+                         int64_t *src, int32_t *indices)
+{
+    int64_t *slots = malloc((size_t)(k > 0 ? k : 1) * sizeof *slots);
+    int64_t nnz = 0;
+    indptr[0] = 0;
+    for (int64_t i = 0; i < num_dst; ++i) {
+        int64_t v = dst[i];
+        int64_t start = row_ptr[v], d = row_ptr[v + 1] - start;
+        int64_t c = orc_sample_row(rng_seed, layer, v, d, k, slots);
+        if (nnz + c > cap_nnz) { free(slots); return -2; }
+        for (int64_t j = 0; j < c; ++j) nbr[nnz + j] = col_idx[start + slots[j]];
+        nnz += c;
+        indptr[i + 1] = nnz;
+    }
+    free(slots);
+
+    /* destination nodes sorted by id, remembering their position */
+    orc_id_pos *dsorted = malloc((size_t)(num_dst > 0 ? num_dst : 1) * sizeof *dsorted);
+    for (int64_t i = 0; i < num_dst; ++i) { dsorted[i].id = dst[i]; dsorted[i].pos = i; }
+    qsort(dsorted, (size_t)num_dst, sizeof *dsorted, cmp_id_pos);
+
+    /* the set of sampled neighbours, ascending, minus the destinations */
+    int64_t *uniq = malloc((size_t)(nnz > 0 ? nnz : 1) * sizeof *uniq);
+    memcpy(uniq, nbr, (size_t)nnz * sizeof *uniq);
+    qsort(uniq, (size_t)nnz, sizeof *uniq, cmp_i64);
+    int64_t num_new = 0;
+    for (int64_t e = 0; e < nnz; ++e) {
+        if (e > 0 && uniq[e] == uniq[e - 1]) continue;
+        if (find_id(dsorted, num_dst, uniq[e]) >= 0) continue;
+        uniq[num_new++] = uniq[e];
+    }
+    if (num_dst + num_new > cap_src) { free(uniq); free(dsorted); return -2; }
+    for (int64_t i = 0; i < num_dst; ++i) src[i] = dst[i];
+    for (int64_t r = 0; r < num_new; ++r) src[num_dst + r] = uniq[r];
+
+    for (int64_t e = 0; e < nnz; ++e) {
+        int64_t p = find_id(dsorted, num_dst, nbr[e]);
+        if (p >= 0) {
+            indices[e] = (int32_t)dsorted[p].pos;
+        } else {
+            int64_t r = find_i64(uniq, num_new, nbr[e]);
+            indices[e] = (int32_t)(num_dst + r);
+        }
+    }
+    free(uniq);
+    free(dsorted);
+    return num_dst + num_new;
+}
+
+/* ---------------------------------------------------------------- gather */
+
+/* out[i] = F[ids[i]] byte for byte.  A row with slot_of[id] >= 0 is read
+ * from cache_rows (a hit), otherwise from feats (a miss).  slot_of may be
+ * NULL: then every row is read from feats and counted as a miss. */
+void orc_gather(const int64_t *ids, int64_t n, const uint8_t *feats, int64_t feat_stride_bytes,
+                const int32_t *slot_of, const uint8_t *cache_rows, int64_t cache_stride_bytes,
+                int64_t row_bytes, uint8_t *out, int64_t out_stride_bytes, int64_t *hits,
+                int64_t *misses)
+{
+    int64_t h = 0, m = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int64_t id = ids[i];
+        const uint8_t *srcrow;
+        if (slot_of && slot_of[id] >= 0) {
+            srcrow = cache_rows + (int64_t)slot_of[id] * cache_stride_bytes;
+            ++h;
+        } else {
+            srcrow = feats + id * feat_stride_bytes;
+            ++m;
+        }
+        memcpy(out + i * out_stride_bytes, srcrow, (size_t)row_bytes);
+    }
+    *hits = h;
+    *misses = m;
+}
+
+/* --------------------------------------------------------- fp16 helpers */
+
+/* IEEE 754 binary16 -> double, exact */
+double orc_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int e = (h >> 10) & 0x1F;
+    int m = h & 0x3FF;
+    double v;
+    if (e == 0) {
+        v = (double)m * (1.0 / 16777216.0);            /* m * 2^-24 (subnormal or zero) */
+    } else if (e == 31) {
+        if (m == 0) { union { uint64_t u; double d; } inf = { 0x7FF0000000000000ULL }; v = inf.d; }
+        else { union { uint64_t u; double d; } nan = { 0x7FF8000000000000ULL }; v = nan.d; }
+    } else {
+        double scale = 1.0;
+        int p = e - 15;
+        if (p >= 0) for (int i = 0; i < p; ++i) scale *= 2.0;
+        else for (int i = 0; i < -p; ++i) scale *= 0.5;
+        v = (1.0 + (double)m / 1024.0) * scale;
+    }
+    return sign ? -v : v;
+}
+
+/* float -> IEEE 754 binary16, round to nearest, ties to even */
+uint16_t orc_float_to_half(float f)
+{
+    union { float f; uint32_t u; } in = { f };
+    uint32_t x = in.u;
+    uint16_t sign = (uint16_t)((x >> 16) & 0x8000u);
+    uint32_t expo = (x >> 23) & 0xFFu;
+    uint32_t mant = x & 0x7FFFFFu;
+    if (expo == 0xFFu) return (uint16_t)(sign | 0x7C00u | (mant ? 0x200u : 0u));
+    int32_t e = (int32_t)expo - 127 + 15;
+    if (e >= 31) return (uint16_t)(sign | 0x7C00u);                 /* overflow -> inf */
+    if (e <= 0) {
+        if (e < -10) return sign;                                   /* below half of min subnormal */
+        mant |= 0x800000u;                                          /* implicit one */
+        int shift = 14 - e;                                         /* 14..24 */
+        uint32_t q = mant >> shift;
+        uint32_t rem = mant & ((1u << shift) - 1u);
+        uint32_t halfway = 1u << (shift - 1);
+        if (rem > halfway || (rem == halfway && (q & 1u))) ++q;
+        return (uint16_t)(sign | q);
+    }
+    uint32_t q = ((uint32_t)e << 10) | (mant >> 13);
+    uint32_t rem = mant & 0x1FFFu;
+    if (rem > 0x1000u || (rem == 0x1000u && (q & 1u))) ++q;         /* carry may reach inf: correct */
+    return (uint16_t)(sign | q);
+}
+
+/* ------------------------------------------------------------ aggregate */
+
+/*
+ * out[i, :] = mean over e in [indptr[i], indptr[i+1]) of x[indices[e], :]
+ * accumulated in double in row order, divided by the count, rounded once to
+ * float (and then once to half for is_half).  An empty row gives zeros.
+ * Strides are in elements.
+ */
+void orc_mean_aggregate(const int64_t *indptr, const int32_t *indices, int64_t num_dst,
+                        const void *x, int64_t x_stride, void *out, int64_t out_stride,
+                        int64_t dim, int is_half)
+{
+    double *acc = malloc((size_t)(dim > 0 ? dim : 1) * sizeof *acc);
+    for (int64_t i = 0; i < num_dst; ++i) {
+        int64_t b = indptr[i], e = indptr[i + 1], n = e - b;
+        for (int64_t c = 0; c < dim; ++c) acc[c] = 0.0;
+        for (int64_t p = b; p < e; ++p) {
+            int64_t r = indices[p];
+            if (is_half) {
+                const uint16_t *row = (const uint16_t *)x + r * x_stride;
+                for (int64_t c = 0; c < dim; ++c) acc[c] += orc_half_to_double(row[c]);
+            } else {
+                const float *row = (const float *)x + r * x_stride;
+                for (int64_t c = 0; c < dim; ++c) acc[c] += (double)row[c];
+            }
+        }
+        for (int64_t c = 0; c < dim; ++c) {
+            double m = n > 0 ? acc[c] / (double)n : 0.0;
+            if (is_half) ((uint16_t *)out)[i * out_stride + c] = orc_float_to_half((float)m);
+            else ((float *)out)[i * out_stride + c] = (float)m;
+        }
+    }
+    free(acc);
+}

@@ -1,0 +1,424 @@
+"""Pins for the CPU oracle: it is checked here against things other than itself -
+published known-answer vectors, brute force written independently in Python,
+closed forms, textbook special cases and library routines - so that a slip in
+any of its functions (a dropped term, a wrong index, a wrong sign, a wrong
+order) fails at least one test.  CPU only.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+import scipy.sparse as sp
+
+import oracle
+from paper_2601_04707_amd import synth
+
+M64 = (1 << 64) - 1
+GOLDEN = 0x9E3779B97F4A7C15
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+# ------------------------------------------------------------ independent Python restatement
+
+def py_mix(z):
+    z &= M64
+    z ^= z >> 30
+    z = (z * 0xBF58476D1CE4E5B9) & M64
+    z ^= z >> 27
+    z = (z * 0x94D049BB133111EB) & M64
+    z ^= z >> 31
+    return z
+
+
+def py_key(seed, layer, node, slot):
+    h = py_mix((seed + GOLDEN) & M64)
+    h = py_mix(h ^ layer)
+    h = py_mix(h ^ node)
+    return py_mix(h ^ slot)
+
+
+def py_sample_row(seed, layer, node, d, k):
+    if d <= k:
+        return list(range(d))
+    ranked = sorted((py_key(seed, layer, node, j), j) for j in range(d))
+    return sorted(j for _, j in ranked[:k])
+
+
+def py_sample_blocks(row_ptr, col_idx, seeds, fanouts, rng_seed):
+    """Whole L-hop expansion with Python sets/dicts; returns list of dicts per block."""
+    L = len(fanouts)
+    blocks = [None] * L
+    dst = [int(s) for s in seeds]
+    for l in range(L - 1, -1, -1):
+        rows = []
+        for v in dst:
+            s, e = int(row_ptr[v]), int(row_ptr[v + 1])
+            slots = py_sample_row(rng_seed, l, v, e - s, fanouts[l])
+            rows.append([int(col_idx[s + j]) for j in slots])
+        dset = set(dst)
+        new = sorted({u for r in rows for u in r} - dset)
+        src = dst + new
+        pos = {}
+        for i, v in enumerate(src):
+            pos.setdefault(v, i)
+        indptr = [0]
+        for r in rows:
+            indptr.append(indptr[-1] + len(r))
+        blocks[l] = dict(num_dst=len(dst), src=src, indptr=indptr,
+                         indices=[pos[u] for r in rows for u in r],
+                         nbr=[u for r in rows for u in r])
+        dst = src
+    return blocks
+
+
+def tiny_graph(n=300, edges=3000, seed=0):
+    rp, ci = synth.chung_lu_graph(n, edges, seed=seed)
+    return rp.numpy(), ci.numpy()
+
+
+# ------------------------------------------------------------ key function
+
+def test_mix_matches_published_splitmix64_vectors():
+    """golden/splitmix64_kat.txt: outputs of the public-domain SplitMix64 reference."""
+    rows = [l.split() for l in open(os.path.join(HERE, "golden", "splitmix64_kat.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 8
+    for seed, n, out in rows:
+        state = (int(seed) + int(n) * GOLDEN) & M64
+        assert oracle.mix(state) == int(out, 16)
+
+
+def test_mix_is_a_bijection_on_small_domain_and_fixes_zero():
+    assert oracle.mix(0) == 0
+    outs = {oracle.mix(z) for z in range(1, 5000)}
+    assert len(outs) == 4999 and 0 not in outs
+
+
+def test_key_composition_matches_bigint_arithmetic():
+    rng = np.random.default_rng(0)
+    for _ in range(300):
+        seed = int(rng.integers(0, 1 << 63)) * 2 + int(rng.integers(0, 2))
+        layer = int(rng.integers(0, 8))
+        node = int(rng.integers(0, 1 << 40))
+        slot = int(rng.integers(0, 1 << 31))
+        assert oracle.key(seed, layer, node, slot) == py_key(seed, layer, node, slot)
+    # each coordinate matters
+    base = oracle.key(5, 1, 7, 3)
+    assert len({base, oracle.key(6, 1, 7, 3), oracle.key(5, 2, 7, 3), oracle.key(5, 1, 8, 3),
+                oracle.key(5, 1, 7, 4)}) == 5
+
+
+def test_keys_look_uniform():
+    """Top byte of 64k consecutive-slot keys: chi-square against the flat law (255 dof)."""
+    keys = np.array([oracle.key(42, 0, 17, j) for j in range(65536)], dtype=np.uint64)
+    counts = np.bincount((keys >> np.uint64(56)).astype(np.int64), minlength=256)
+    chi2 = ((counts - 256.0) ** 2 / 256.0).sum()
+    assert chi2 < 255 + 6 * math.sqrt(2 * 255)
+    low = np.bincount((keys & np.uint64(0xFF)).astype(np.int64), minlength=256)
+    chi2 = ((low - 256.0) ** 2 / 256.0).sum()
+    assert chi2 < 255 + 6 * math.sqrt(2 * 255)
+
+
+# ------------------------------------------------------------ row selection
+
+@pytest.mark.parametrize("d,k", [(1, 1), (3, 5), (5, 5), (6, 5), (7, 1), (40, 10), (64, 25),
+                                 (65, 25), (300, 25), (2000, 15), (9, 64), (130, 64)])
+def test_sample_row_equals_bruteforce_full_sort(d, k):
+    for seed in (0, 1, 0xDEADBEEF, M64):
+        for node in (0, 12345, 2**33 + 7):
+            for layer in (0, 2):
+                got = oracle.sample_row(seed, layer, node, d, k).tolist()
+                want = py_sample_row(seed, layer, node, d, k)
+                assert got == want
+                assert len(got) == min(k, d) and len(set(got)) == len(got)
+                assert got == sorted(got) and all(0 <= j < d for j in got)
+
+
+def test_k_equals_one_is_argmin_of_keys():
+    for node in range(50):
+        d = 37
+        keys = [py_key(9, 1, node, j) for j in range(d)]
+        assert oracle.sample_row(9, 1, node, d, 1).tolist() == [int(np.argmin(np.array(keys, dtype=np.uint64)))]
+
+
+@pytest.mark.parametrize("d,k", [(4, 2), (5, 2), (6, 3), (5, 4)])
+def test_subsets_are_uniform(d, k):
+    """Every k-subset of a short row appears with frequency 1/C(d,k) (4 sigma), and
+    every slot is included with probability k/d."""
+    trials = 60000
+    subsets = {c: 0 for c in itertools.combinations(range(d), k)}
+    incl = np.zeros(d)
+    for s in range(trials):
+        got = tuple(oracle.sample_row(s, 0, 11, d, k).tolist())
+        subsets[got] += 1
+        incl[list(got)] += 1
+    p = 1.0 / len(subsets)
+    sigma = math.sqrt(trials * p * (1 - p))
+    for c, cnt in subsets.items():
+        assert abs(cnt - trials * p) < 4.5 * sigma, (c, cnt, trials * p)
+    q = k / d
+    assert np.all(np.abs(incl - trials * q) < 4.5 * math.sqrt(trials * q * (1 - q)))
+
+
+def test_resampled_per_layer_and_per_seed():
+    a = oracle.sample_row(1, 0, 5, 200, 10).tolist()
+    b = oracle.sample_row(1, 1, 5, 200, 10).tolist()
+    c = oracle.sample_row(2, 0, 5, 200, 10).tolist()
+    assert a != b and a != c
+
+
+# ------------------------------------------------------------ blocks
+
+@pytest.mark.parametrize("fanouts", [[3], [4, 2], [5, 3, 2], [64, 64]])
+def test_blocks_equal_python_set_dict_bruteforce(fanouts):
+    rp, ci = tiny_graph()
+    seeds = synth.seed_batches(len(rp) - 1, 16, 1, seed=5)[0].numpy()
+    for rng_seed in (0, 77):
+        got = oracle.sample_blocks(rp, ci, seeds, fanouts, rng_seed)
+        want = py_sample_blocks(rp, ci, seeds, fanouts, rng_seed)
+        assert len(got) == len(fanouts)
+        for g, w in zip(got, want):
+            assert g.num_dst == w["num_dst"]
+            assert g.src_ids.tolist() == w["src"]
+            assert g.indptr.tolist() == w["indptr"]
+            assert g.indices.tolist() == w["indices"]
+            assert g.nbr_global.tolist() == w["nbr"]
+
+
+def test_block_invariants():
+    rp, ci = tiny_graph(2000, 40000, seed=3)
+    n = len(rp) - 1
+    seeds = synth.seed_batches(n, 64, 1, seed=9)[0].numpy()
+    fanouts = [10, 5, 3]
+    blocks = oracle.sample_blocks(rp, ci, seeds, fanouts, 123)
+    dst = seeds
+    for l in range(len(fanouts) - 1, -1, -1):
+        b = blocks[l]
+        nd = b.num_dst
+        assert np.array_equal(b.src_ids[:nd], dst)                     # destinations are the prefix
+        new = b.src_ids[nd:]
+        assert np.all(np.diff(new) > 0)                                # strictly ascending
+        assert len(np.intersect1d(new, dst)) == 0                      # disjoint from destinations
+        assert len(np.unique(b.src_ids)) == b.num_src                  # relabel is a bijection
+        assert np.array_equal(b.src_ids[b.indices], b.nbr_global)      # local -> global
+        assert set(new.tolist()) == set(b.nbr_global.tolist()) - set(dst.tolist())
+        for i, v in enumerate(dst):
+            row = b.nbr_global[b.indptr[i]:b.indptr[i + 1]]
+            adj = ci[rp[v]:rp[v + 1]]
+            assert len(row) == min(fanouts[l], len(adj))               # min(fanout, degree)
+            assert len(set(row.tolist())) == len(row)                  # distinct
+            assert np.all(np.isin(row, adj))                           # true neighbours
+            assert np.all(np.diff(np.searchsorted(adj, row)) > 0)      # ascending adjacency slot
+        dst = b.src_ids
+
+
+def test_full_fanout_is_exact_khop_expansion():
+    """fanout >= max degree: blocks are the textbook frontier expansion (sparse A products)."""
+    rp, ci = tiny_graph(400, 3000, seed=4)
+    n = len(rp) - 1
+    A = sp.csr_matrix((np.ones(len(ci)), ci, rp), shape=(n, n))
+    maxdeg = int(np.diff(rp).max())
+    seeds = np.array([3, 50, 7, 120], dtype=np.int64)
+    blocks = oracle.sample_blocks(rp, ci, seeds, [maxdeg, maxdeg + 5], 1)
+    reach = np.zeros(n)
+    reach[seeds] = 1
+    for l in (1, 0):
+        b = blocks[l]
+        reach = ((A.T @ reach) + reach > 0).astype(float)              # one more hop, keep self
+        assert set(b.src_ids.tolist()) == set(np.nonzero(reach)[0].tolist())
+        sub = A[b.src_ids[:b.num_dst]]
+        assert np.array_equal(b.indptr, sub.indptr)
+        assert np.array_equal(b.nbr_global, sub.indices)
+
+
+def test_empty_rows_and_empty_batch():
+    rp = np.array([0, 0, 2, 3, 3], dtype=np.int64)       # node 0 and 3 isolated
+    ci = np.array([2, 3, 1], dtype=np.int64)             # (not symmetric on purpose: rows are in-neighbours)
+    b = oracle.sample_blocks(rp, ci, np.array([0, 1], dtype=np.int64), [2, 2], 0)
+    assert b[1].indptr.tolist() == [0, 0, 2] and b[1].src_ids.tolist() == [0, 1, 2, 3]
+    assert b[0].num_dst == 4 and b[0].indptr.tolist() == [0, 0, 2, 3, 3]
+    assert b[0].indices.tolist() == [2, 3, 1] and b[0].num_src == 4
+    e = oracle.sample_blocks(rp, ci, np.array([], dtype=np.int64), [2], 0)
+    assert e[0].num_dst == 0 and e[0].num_src == 0 and e[0].nnz == 0
+
+
+# ------------------------------------------------------------ cache
+
+def test_cache_equals_lexsort_bruteforce():
+    rp, _ = tiny_graph(1000, 12000, seed=6)
+    n = len(rp) - 1
+    deg = np.diff(rp)
+    order = np.lexsort((np.arange(n), -deg))             # degree descending, id ascending
+    feats = np.random.default_rng(0).standard_normal((n, 7)).astype(np.float32)
+    for num_cached in (0, 1, 137, n):
+        c = oracle.build_cache(rp, num_cached, feats)
+        assert np.array_equal(c.cached_ids, order[:num_cached])
+        want = np.full(n, -1, dtype=np.int32)
+        want[order[:num_cached]] = np.arange(num_cached, dtype=np.int32)
+        assert np.array_equal(c.slot_of, want)
+        assert np.array_equal(c.cache_rows, feats[order[:num_cached]])
+    # ties: equal degrees go to the lower id
+    rp2 = np.array([0, 2, 4, 6, 7], dtype=np.int64)
+    assert oracle.build_cache(rp2, 2).cached_ids.tolist() == [0, 1]
+
+
+def test_cache_covers_most_edge_endpoints_on_power_law_graph():
+    """Skew argument of the paper's cache section: a small top-degree cache holds a much
+    larger share of edge endpoints than of nodes."""
+    rp, _ = tiny_graph(5000, 100000, seed=8)
+    n = len(rp) - 1
+    deg = np.diff(rp)
+    c = oracle.build_cache(rp, n // 10)
+    share = deg[c.cached_ids].sum() / deg.sum()
+    assert share > 0.3
+
+
+# ------------------------------------------------------------ gather
+
+@pytest.mark.parametrize("dtype", [np.float32, np.float16])
+def test_gather_is_fancy_indexing_whatever_the_cache(dtype):
+    rp, _ = tiny_graph(800, 9000, seed=2)
+    n = len(rp) - 1
+    rng = np.random.default_rng(1)
+    feats = rng.standard_normal((n, 13)).astype(dtype)
+    ids = rng.permutation(n)[:300].astype(np.int64)
+    ref = feats[ids]
+    out, h, m = oracle.gather(ids, feats, None)
+    assert out.tobytes() == ref.tobytes() and (h, m) == (0, 300)
+    for num_cached in (0, 80, n):
+        c = oracle.build_cache(rp, num_cached, feats)
+        out, h, m = oracle.gather(ids, feats, c)
+        assert out.tobytes() == ref.tobytes()
+        assert h == int((c.slot_of[ids] >= 0).sum()) and h + m == 300
+    # a cache row that differs from the host row proves hits really read the cache
+    c = oracle.build_cache(rp, 80, feats)
+    c.cache_rows[:] = 0
+    out, _, _ = oracle.gather(ids, feats, c)
+    hit = c.slot_of[ids] >= 0
+    assert np.all(out[hit] == 0) and out[~hit].tobytes() == ref[~hit].tobytes()
+
+
+# ------------------------------------------------------------ fp16 helpers
+
+def test_half_to_double_all_bit_patterns_match_numpy():
+    bits = np.arange(65536, dtype=np.uint16)
+    want = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.half_to_double(int(b)) for b in bits])
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], want[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(want[~nan]))
+
+
+def test_float_to_half_rounds_to_nearest_even_like_numpy():
+    rng = np.random.default_rng(3)
+    vals = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32),
+        (rng.standard_normal(5000) * 1e-6).astype(np.float32),      # subnormal halves
+        (rng.standard_normal(5000) * 3e4).astype(np.float32),       # near overflow
+        np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 1e9, -1e9, 5.96e-8, 2.98e-8, 2.99e-8,
+                  6.1e-5, 6.1035156e-5, 1.0009766, 1.0004883, 1.0014648, np.inf, -np.inf],
+                 dtype=np.float32)])
+    # exact ties between two halves
+    h = rng.integers(0, 0x7BFF, 4000).astype(np.uint16)
+    a = h.view(np.float16).astype(np.float64)
+    b = (h + 1).astype(np.uint16).view(np.float16).astype(np.float64)
+    vals = np.concatenate([vals, ((a + b) / 2).astype(np.float32)])
+    with np.errstate(over="ignore"):
+        want = vals.astype(np.float16).view(np.uint16)
+    got = np.array([oracle.float_to_half(float(v)) for v in vals], dtype=np.uint16)
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------ aggregate
+
+def _random_block(rng, num_dst, num_src, max_row):
+    counts = rng.integers(0, max_row + 1, num_dst)
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    indices = rng.integers(0, num_src, indptr[-1]).astype(np.int32)
+    return indptr, indices
+
+
+@pytest.mark.parametrize("dtype,tol", [(np.float32, 1e-6), (np.float16, 1e-3)])
+def test_mean_aggregate_equals_dense_row_normalised_product(dtype, tol):
+    rng = np.random.default_rng(5)
+    nd, ns, dim = 40, 90, 19
+    indptr, indices = _random_block(rng, nd, ns, 7)
+    x = rng.standard_normal((ns, dim)).astype(dtype)
+    A = np.zeros((nd, ns))
+    for i in range(nd):
+        for e in range(indptr[i], indptr[i + 1]):
+            A[i, indices[e]] += 1.0
+    deg = A.sum(1, keepdims=True)
+    want = np.where(deg > 0, (A @ x.astype(np.float64)) / np.maximum(deg, 1), 0.0)
+    got = oracle.mean_aggregate(indptr, indices, x).astype(np.float64)
+    assert np.allclose(got, want, rtol=tol, atol=tol)
+    assert np.all(got[np.diff(indptr) == 0] == 0)                       # empty rows are zero
+    # library routine: scipy CSR product
+    S = sp.csr_matrix((np.ones(len(indices)), indices, indptr), shape=(nd, ns))
+    want2 = (S @ x.astype(np.float64)) / np.maximum(np.diff(indptr), 1)[:, None]
+    assert np.allclose(got, want2, rtol=tol, atol=tol)
+    # fp32 result is the correctly rounded double mean
+    if dtype == np.float32:
+        assert np.array_equal(got.astype(np.float32), want.astype(np.float32))
+
+
+def test_mean_aggregate_closed_forms():
+    rng = np.random.default_rng(6)
+    indptr, indices = _random_block(rng, 30, 50, 9)
+    nonempty = np.diff(indptr) > 0
+    const = np.full((50, 5), 3.25, dtype=np.float32)
+    out = oracle.mean_aggregate(indptr, indices, const)
+    assert np.all(out[nonempty] == 3.25) and np.all(out[~nonempty] == 0)
+    # node-id features: the mean of the selected ids, exactly representable
+    ids = np.arange(50, dtype=np.float32)[:, None] * np.array([[1.0, -2.0]], dtype=np.float32)
+    out = oracle.mean_aggregate(indptr, indices, ids)
+    for i in range(30):
+        sel = indices[indptr[i]:indptr[i + 1]]
+        if len(sel):
+            assert out[i, 0] == np.float32(sel.astype(np.float64).mean())
+            assert out[i, 1] == np.float32(-2.0 * sel.astype(np.float64).mean())
+    # one-hot features reveal exactly which rows were summed and how often
+    eye = np.eye(50, dtype=np.float32)
+    out = oracle.mean_aggregate(indptr, indices, eye)
+    for i in range(30):
+        sel = indices[indptr[i]:indptr[i + 1]]
+        if len(sel):
+            want = np.bincount(sel, minlength=50) / len(sel)
+            assert np.allclose(out[i], want, rtol=1e-7)
+
+
+def test_full_fanout_aggregation_is_D_inv_A_X():
+    rp, ci = tiny_graph(300, 2500, seed=7)
+    n = len(rp) - 1
+    x = np.random.default_rng(2).standard_normal((n, 6)).astype(np.float32)
+    seeds = np.arange(0, n, 7, dtype=np.int64)
+    b = oracle.sample_blocks(rp, ci, seeds, [int(np.diff(rp).max())], 0)[0]
+    out = oracle.mean_aggregate(b.indptr, b.indices, x[b.src_ids])
+    A = sp.csr_matrix((np.ones(len(ci)), ci, rp), shape=(n, n))
+    deg = np.maximum(np.diff(rp), 1)[:, None]
+    want = ((A @ x.astype(np.float64)) / deg)[seeds]
+    assert np.allclose(out, want, rtol=1e-6, atol=1e-7)
+
+
+def test_sampled_mean_is_unbiased_for_full_mean():
+    """GraphSAGE paragraph of the paper: uniform neighbour sampling gives an unbiased
+    estimate of the full-neighbourhood aggregate.  Average over many sampling seeds."""
+    rp, ci = tiny_graph(200, 4000, seed=11)
+    n = len(rp) - 1
+    deg = np.diff(rp)
+    v = int(np.argmax(deg))
+    assert deg[v] > 20
+    x = np.random.default_rng(4).standard_normal((n, 4))
+    full = x[ci[rp[v]:rp[v + 1]]].mean(0)
+    k, trials = 5, 4000
+    acc = np.zeros(4)
+    for s in range(trials):
+        slots = oracle.sample_row(s, 0, v, int(deg[v]), k)
+        acc += x[ci[rp[v] + slots]].mean(0)
+    est = acc / trials
+    # sd of one estimate <= sd(x)/sqrt(k); 5 sigma of the averaged estimate
+    bound = 5 * x[ci[rp[v]:rp[v + 1]]].std(0) / math.sqrt(k * trials)
+    assert np.all(np.abs(est - full) < bound)
