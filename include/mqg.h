@@ -1,0 +1,228 @@
+/*
+ * mqg - mini-batch generation for sampled GNN training on one MI355X (gfx950).
+ *
+ * C ABI of the library.  The four operations are the per-mini-batch data path
+ * that the MQ-GNN paper describes around its pipeline: node-wise neighbour
+ * sampling, the mini-batch's topology and feature parts, the GPU feature
+ * cache with host fallback, and the gather/aggregate (GA) step of GraphSAGE.
+ *
+ * Conventions
+ *   - Every pointer named *_dev / documented "device" must be dereferenceable
+ *     by a GPU kernel of the current device (hipMalloc memory, or pinned host
+ *     memory from hipHostMalloc where stated).  Pointers documented "host" are
+ *     read by the CPU during the call only.
+ *   - The caller owns every data buffer (graph, features, cache storage,
+ *     block outputs, gathered rows).  A context owns only its private scratch.
+ *     The library keeps no caller pointer after a call returns.
+ *   - All calls only enqueue work on the given HIP stream and return; results
+ *     (including the sizes that depend on the data) are complete when the
+ *     stream has been synchronised.  One context serves one stream at a time;
+ *     concurrent mini-batches use one context each.
+ *   - Every function returns an mqg_status (0 = ok, negative = error).  Errors
+ *     that the host can see (null pointers, bad enums, capacities below the
+ *     bounds stated below) are returned before anything is enqueued.  No
+ *     exception or abort crosses this boundary.
+ *   - Blocks are indexed by the GNN layer they feed: block L-1 has the seed
+ *     nodes as destinations, block 0 is the outermost and its source nodes
+ *     are the rows whose input features are gathered.  fanouts[l] belongs to
+ *     block l, so sampling (which walks outward from the seeds) uses
+ *     fanouts[L-1] first.
+ */
+#ifndef MQG_H
+#define MQG_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mqg_ctx mqg_ctx;          /* opaque; owns scratch memory only            */
+typedef void *mqg_stream;                /* a hipStream_t; NULL is the default stream    */
+
+typedef enum {
+    MQG_OK = 0,
+    MQG_ERR_INVALID_ARG = -1,            /* null pointer, bad enum, negative size ...    */
+    MQG_ERR_CAPACITY = -2,               /* an output buffer is below its stated bound   */
+    MQG_ERR_HIP = -3,                    /* a HIP runtime call failed                    */
+    MQG_ERR_UNSUPPORTED = -4             /* valid request outside the built limits       */
+} mqg_status;
+
+typedef enum { MQG_F32 = 0, MQG_F16 = 1 } mqg_dtype;
+typedef enum { MQG_I32 = 0, MQG_I64 = 1 } mqg_itype;
+
+#define MQG_MAX_FANOUT 64                /* per-node neighbour budget of one block       */
+#define MQG_MAX_LAYERS 8
+
+/*
+ * Graph G = (V, E) in CSR form (paper Sec. III, notation paragraph).  Row v
+ * lists the in-neighbours of v (the nodes whose features v aggregates); the
+ * cache ranks nodes by this in-degree (Eq. 13).  Preconditions: rows hold no
+ * duplicate entry (so distinct adjacency slots are distinct neighbours) and
+ * every entry lies in [0, num_nodes); num_nodes < 2^31; every degree < 2^31.
+ * Both arrays are device memory and are only read.
+ */
+typedef struct mqg_graph {
+    int64_t num_nodes;
+    int64_t num_edges;                   /* length of col_idx                            */
+    int32_t ptr_type;                    /* mqg_itype of row_ptr                         */
+    int32_t idx_type;                    /* mqg_itype of col_idx and of all node-id I/O  */
+    const void *row_ptr;                 /* device [num_nodes + 1]                       */
+    const void *col_idx;                 /* device [num_edges]                           */
+} mqg_graph;
+
+/*
+ * Node feature storage F and the GPU-resident cache C of hot nodes (paper
+ * Sec. III "Feature Cache"; Sec. IV "Mini-Batch Transfer To GPU").
+ *   feats        the full feature matrix, row v at feats + v*feat_stride
+ *                elements.  Pinned host memory (hipHostMalloc) or device
+ *                memory; read by GPU kernels directly, so misses travel over
+ *                the host link without a staging copy.
+ *   cache_rows   device [num_cached x cache_stride]; slot s holds the row of
+ *                node cached_ids[s].  NULL together with slot_of == NULL
+ *                means "no cache": every row is read from feats (use this
+ *                when feats itself is in HBM).
+ *   slot_of      device [num_nodes]; cache slot of a node or -1.
+ *   cached_ids   device [num_cached], graph idx_type; may be NULL if not wanted.
+ * Strides are in elements of dtype.  Rows are moved as opaque bytes.
+ */
+typedef struct mqg_cache {
+    int64_t num_nodes;
+    int64_t num_cached;
+    int32_t dim;
+    int32_t dtype;                       /* mqg_dtype                                    */
+    const void *feats;
+    int64_t feat_stride;
+    void *cache_rows;
+    int64_t cache_stride;
+    int32_t *slot_of;
+    void *cached_ids;
+} mqg_cache;
+
+/*
+ * One bipartite block (the topology part of a mini-batch, Sec. IV
+ * "Mini-Batch Transfer To GPU").  Caller-allocated device buffers:
+ *   src_ids  [cap_src]    global ids of the source nodes.  The first num_dst
+ *                         entries are the destination nodes, in order, so a
+ *                         destination's own previous-layer row (the second
+ *                         half of the concatenation in Eq. 16) is row i of the
+ *                         source matrix.  The remaining entries are the
+ *                         sampled neighbours not among the destinations,
+ *                         each once, ascending by id.
+ *   indptr   [cap_dst+1]  CSR offsets of the sampled neighbours per destination.
+ *   indices  [cap_nnz]    position in src_ids of each sampled neighbour; within
+ *                         a row in ascending order of adjacency slot.
+ *   sizes    [4]          int64, written on the device: num_dst, num_src, nnz,
+ *                         and a flags word (0 = ok).
+ * Capacity bounds checked by mqg_sample_blocks (MQG_ERR_CAPACITY otherwise):
+ *   cap_dst(L-1) >= num_seeds,  cap_dst(l) >= cap_src(l+1),
+ *   cap_nnz >= cap_dst * fanouts[l],  cap_src >= min(num_nodes, cap_dst + cap_nnz).
+ */
+typedef struct mqg_block {
+    int64_t cap_dst;
+    int64_t cap_src;
+    int64_t cap_nnz;
+    void *src_ids;
+    int32_t *indptr;
+    int32_t *indices;
+    int64_t *sizes;
+} mqg_block;
+
+/* Library version (major*10000 + minor*100 + patch). */
+int32_t mqg_version(void);
+
+/*
+ * Create a context for graphs of g's size and batches of at most max_seeds
+ * seeds expanded with at most max_fanouts[l] (host array, length L) neighbours
+ * per node in block l.  Allocates the private scratch on the current HIP
+ * device (about 4.2 bytes per graph node plus a few words per sampled edge of
+ * the largest batch).  g's array pointers are not read here and may be NULL.
+ */
+int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds,
+                   const int32_t *max_fanouts, int32_t num_layers);
+int mqg_ctx_destroy(mqg_ctx *ctx);
+
+/* Message of the last failing call on ctx (or of the last failing
+ * mqg_ctx_create on this thread when ctx is NULL).  Never NULL. */
+const char *mqg_last_error(const mqg_ctx *ctx);
+
+/* Tuning and test switches; see the MQG_OPT_* constants. */
+typedef enum {
+    MQG_OPT_FORCE_SLOW_SELECT = 1,       /* value != 0: every row with degree > fanout uses the
+                                            repeated-minimum selection (test of the rare path) */
+    MQG_OPT_PROFILE = 2                  /* value != 0: bracket every kernel with HIP events
+                                            (adds a few microseconds per kernel)              */
+} mqg_option;
+int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value);
+
+/*
+ * With MQG_OPT_PROFILE on: sum of the HIP-event durations (milliseconds) and
+ * number of launches of the kernel called `name` since the last reset.  The
+ * call synchronises with the recorded events.  Unknown names give 0 launches.
+ */
+int mqg_ctx_kernel_time(mqg_ctx *ctx, const char *name, double *total_ms, int64_t *launches);
+int mqg_ctx_reset_profile(mqg_ctx *ctx);
+/* Names of the kernels seen so far, separated by '\n', into buf (host). */
+int mqg_ctx_kernel_names(mqg_ctx *ctx, char *buf, int64_t buf_len);
+
+/*
+ * Feature cache (paper Sec. III "Feature Cache", Eq. 13: nodes enter the cache
+ * by in-degree; here deterministically).  Ranks all nodes by (degree
+ * descending, id ascending), assigns cache slot s to the s-th ranked node for
+ * s < cache->num_cached, fills slot_of (-1 elsewhere), cached_ids (if not
+ * NULL) and copies the cached rows from cache->feats into cache->cache_rows.
+ * In: every field of *cache (buffers allocated by the caller).  Temporary
+ * device memory (16 bytes per node) is allocated and freed inside the call,
+ * which is therefore synchronous with respect to the host.
+ */
+int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream);
+
+/*
+ * L-hop fixed-fanout node-wise neighbour sampling into blocks (paper Sec.
+ * III-A, GraphSAGE paragraph: a fixed number of neighbours of every node of a
+ * layer, drawn uniformly at random, a fresh draw per layer).
+ *   seeds_dev  device [num_seeds], graph idx_type, distinct, in [0, num_nodes)
+ *   fanouts    host [num_layers], 1..MQG_MAX_FANOUT, indexed by block
+ *   blocks     host array of num_layers descriptors (see mqg_block)
+ * For each destination v of block l with adjacency row of length d: all d
+ * neighbours if d <= fanouts[l]; otherwise the fanouts[l] adjacency slots j
+ * with the smallest (key, j), key = mix(mix(mix(mix(rng_seed + G) ^ l) ^ v) ^ j)
+ * with mix the SplitMix64 finaliser and G = 0x9E3779B97F4A7C15 - sampling
+ * without replacement, a pure function of (rng_seed, l, v, j).
+ */
+int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                      const int32_t *fanouts, int32_t num_layers, uint64_t rng_seed,
+                      mqg_block *blocks, mqg_stream stream);
+
+/*
+ * Feature gather through the cache (paper Sec. IV "Mini-Batch Transfer To
+ * GPU": rows of cached nodes come from GPU memory, the others from host
+ * memory).  out[i, 0:dim] = F[ids[i], 0:dim] byte for byte.
+ *   ids_dev      device [cap_ids], graph idx_type (normally blocks[0].src_ids)
+ *   num_ids_dev  device int64: number of valid ids (normally &blocks[0].sizes[1]);
+ *                values above cap_ids are clamped to cap_ids
+ *   out_dev      device [cap_ids x out_stride] elements of cache->dtype
+ *   stats_dev    device int64[2]: rows served from the cache, rows served
+ *                from feats; may be NULL
+ */
+int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
+                        const void *ids_dev, const int64_t *num_ids_dev, int64_t cap_ids,
+                        void *out_dev, int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
+
+/*
+ * GraphSAGE mean aggregation over one block (paper Eq. 16,
+ * Z_agg(v) = Mean(H(v)); the GA step "AH" of Sec. IV "Computation").
+ *   out[i, c] = (1/n_i) * sum_{e in row i} x_src[indices[e], c],  n_i = row length;
+ *   a destination with no sampled neighbour gets zeros.
+ * x_src: device [num_src x x_stride]; out: device [cap_dst x out_stride];
+ * strides in elements; sums are accumulated in fp32 in row order; MQG_F16
+ * rounds once, to nearest even, at the store.
+ */
+int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_src,
+                            int64_t x_stride, void *out, int64_t out_stride, int32_t dim,
+                            int32_t dtype, mqg_stream stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MQG_H */

@@ -1,0 +1,318 @@
+// Host side of the C ABI: contexts, argument checks, profiling, dispatch to the kernel launchers.
+#include <algorithm>
+#include <cstring>
+
+#include "common.h"
+
+namespace {
+thread_local std::string g_create_error = "";
+
+bool valid_itype(int32_t t) { return t == MQG_I32 || t == MQG_I64; }
+bool valid_dtype(int32_t t) { return t == MQG_F32 || t == MQG_F16; }
+
+template <typename T>
+hipError_t dev_alloc(T **p, int64_t n) {
+    return hipMalloc(reinterpret_cast<void **>(p), static_cast<size_t>(std::max<int64_t>(n, 1)) * sizeof(T));
+}
+}  // namespace
+
+namespace mqg {
+
+int fail(mqg_ctx *ctx, int code, const std::string &msg) {
+    if (ctx) ctx->last_error = msg; else g_create_error = msg;
+    return code;
+}
+
+int prof_name_id(mqg_ctx *ctx, const char *name) {
+    for (size_t i = 0; i < ctx->prof_names.size(); ++i)
+        if (ctx->prof_names[i] == name) return static_cast<int>(i);
+    ctx->prof_names.emplace_back(name);
+    ctx->prof_total_ms.push_back(0.0);
+    ctx->prof_launches.push_back(0);
+    return static_cast<int>(ctx->prof_names.size()) - 1;
+}
+
+static hipEvent_t take_event(mqg_ctx *ctx) {
+    if (!ctx->event_pool.empty()) {
+        hipEvent_t e = ctx->event_pool.back();
+        ctx->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    (void)hipEventCreate(&e);
+    return e;
+}
+
+void prof_begin(mqg_ctx *ctx, const char *name, hipStream_t s) {
+    ProfRec r;
+    r.name_id = prof_name_id(ctx, name);
+    r.start = take_event(ctx);
+    r.stop = take_event(ctx);
+    (void)hipEventRecord(r.start, s);
+    ctx->prof_recs.push_back(r);
+}
+
+void prof_end(mqg_ctx *ctx, hipStream_t s) {
+    (void)hipEventRecord(ctx->prof_recs.back().stop, s);
+}
+
+// Fold finished event pairs into the per-kernel totals and recycle the events.
+static int prof_collect(mqg_ctx *ctx) {
+    for (auto &r : ctx->prof_recs) {
+        hipError_t e = hipEventSynchronize(r.stop);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("hipEventSynchronize: ") + hipGetErrorString(e));
+        float ms = 0.f;
+        e = hipEventElapsedTime(&ms, r.start, r.stop);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("hipEventElapsedTime: ") + hipGetErrorString(e));
+        ctx->prof_total_ms[r.name_id] += ms;
+        ctx->prof_launches[r.name_id] += 1;
+        ctx->event_pool.push_back(r.start);
+        ctx->event_pool.push_back(r.stop);
+    }
+    ctx->prof_recs.clear();
+    return MQG_OK;
+}
+
+}  // namespace mqg
+
+using mqg::fail;
+
+extern "C" {
+
+int32_t mqg_version(void) { return 100; }
+
+const char *mqg_last_error(const mqg_ctx *ctx) {
+    return ctx ? ctx->last_error.c_str() : g_create_error.c_str();
+}
+
+int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const int32_t *max_fanouts,
+                   int32_t L) {
+    if (!out) return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_ctx_create: out is NULL");
+    *out = nullptr;
+    if (!g || !max_fanouts) return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_ctx_create: NULL graph or fanouts");
+    if (g->num_nodes < 0 || g->num_edges < 0 || !valid_itype(g->ptr_type) || !valid_itype(g->idx_type))
+        return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_ctx_create: bad graph descriptor");
+    if (g->num_nodes >= (int64_t(1) << 31))
+        return fail(nullptr, MQG_ERR_UNSUPPORTED, "mqg_ctx_create: num_nodes must be below 2^31");
+    if (L < 1 || L > MQG_MAX_LAYERS) return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_ctx_create: num_layers out of range");
+    if (max_seeds < 0) return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_ctx_create: negative max_seeds");
+    for (int l = 0; l < L; ++l)
+        if (max_fanouts[l] < 1 || max_fanouts[l] > MQG_MAX_FANOUT)
+            return fail(nullptr, MQG_ERR_UNSUPPORTED, "mqg_ctx_create: fanout outside 1..MQG_MAX_FANOUT");
+
+    mqg_ctx *c = new (std::nothrow) mqg_ctx();
+    if (!c) return fail(nullptr, MQG_ERR_HIP, "mqg_ctx_create: out of host memory");
+    hipError_t e = hipGetDevice(&c->device);
+    if (e != hipSuccess) {
+        delete c;
+        return fail(nullptr, MQG_ERR_HIP, std::string("hipGetDevice: ") + hipGetErrorString(e));
+    }
+    c->num_nodes = g->num_nodes;
+    c->ptr_type = g->ptr_type;
+    c->idx_type = g->idx_type;
+    c->max_seeds = max_seeds;
+    c->num_layers = L;
+    int64_t dst = max_seeds;
+    for (int l = L - 1; l >= 0; --l) {
+        c->max_fanouts[l] = max_fanouts[l];
+        c->bound_dst[l] = dst;
+        c->bound_nnz[l] = dst * max_fanouts[l];
+        c->bound_src[l] = std::max(dst, std::min<int64_t>(g->num_nodes, dst + c->bound_nnz[l]));
+        c->max_dst = std::max(c->max_dst, c->bound_dst[l]);
+        c->max_nnz = std::max(c->max_nnz, c->bound_nnz[l]);
+        c->max_src = std::max(c->max_src, c->bound_src[l]);
+        dst = c->bound_src[l];
+    }
+    if (c->max_nnz >= (int64_t(1) << 31)) {
+        delete c;
+        return fail(nullptr, MQG_ERR_UNSUPPORTED, "mqg_ctx_create: more than 2^31 sampled edges per block");
+    }
+    c->bitmap_words = mqg::ceil_div(mqg::ceil_div(g->num_nodes, 32), mqg::kBitmapTileWords) * mqg::kBitmapTileWords;
+    c->max_tiles = std::max<int64_t>(mqg::ceil_div(c->max_dst, mqg::kBlock), c->bitmap_words / mqg::kBitmapTileWords) + 1;
+
+    bool ok = true;
+    ok = ok && dev_alloc(&c->local_of, c->num_nodes) == hipSuccess;
+    ok = ok && dev_alloc(&c->bitmap, c->bitmap_words) == hipSuccess;
+    ok = ok && dev_alloc(&c->tile_vals, c->max_tiles) == hipSuccess;
+    ok = ok && dev_alloc(&c->row_start, c->max_dst) == hipSuccess;
+    ok = ok && dev_alloc(&c->row_deg, c->max_dst) == hipSuccess;
+    ok = ok && dev_alloc(reinterpret_cast<int32_t **>(&c->nbr), c->max_nnz) == hipSuccess;
+    ok = ok && dev_alloc(&c->hit_list, c->max_src) == hipSuccess;
+    ok = ok && dev_alloc(&c->miss_list, c->max_src) == hipSuccess;
+    ok = ok && dev_alloc(&c->counters, 8) == hipSuccess;
+    if (ok) ok = hipMemset(c->local_of, 0xFF, std::max<int64_t>(c->num_nodes, 1) * sizeof(int32_t)) == hipSuccess;
+    if (ok) ok = hipMemset(c->bitmap, 0, std::max<int64_t>(c->bitmap_words, 1) * sizeof(uint32_t)) == hipSuccess;
+    if (ok) ok = hipMemset(c->counters, 0, 8 * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) ok = hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        std::string msg = std::string("mqg_ctx_create: scratch allocation failed: ") + hipGetErrorString(hipGetLastError());
+        mqg_ctx_destroy(c);
+        return fail(nullptr, MQG_ERR_HIP, msg);
+    }
+    *out = c;
+    return MQG_OK;
+}
+
+int mqg_ctx_destroy(mqg_ctx *c) {
+    if (!c) return MQG_OK;
+    (void)hipFree(c->local_of);
+    (void)hipFree(c->bitmap);
+    (void)hipFree(c->tile_vals);
+    (void)hipFree(c->row_start);
+    (void)hipFree(c->row_deg);
+    (void)hipFree(c->nbr);
+    (void)hipFree(c->hit_list);
+    (void)hipFree(c->miss_list);
+    (void)hipFree(c->counters);
+    for (auto &r : c->prof_recs) {
+        (void)hipEventDestroy(r.start);
+        (void)hipEventDestroy(r.stop);
+    }
+    for (auto e : c->event_pool) (void)hipEventDestroy(e);
+    delete c;
+    return MQG_OK;
+}
+
+int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    switch (option) {
+        case MQG_OPT_FORCE_SLOW_SELECT: ctx->force_slow_select = value != 0; return MQG_OK;
+        case MQG_OPT_PROFILE: ctx->profile = value != 0; return MQG_OK;
+        default: return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: unknown option");
+    }
+}
+
+int mqg_ctx_kernel_time(mqg_ctx *ctx, const char *name, double *total_ms, int64_t *launches) {
+    if (!ctx || !name || !total_ms || !launches) return MQG_ERR_INVALID_ARG;
+    int rc = mqg::prof_collect(ctx);
+    if (rc != MQG_OK) return rc;
+    *total_ms = 0.0;
+    *launches = 0;
+    for (size_t i = 0; i < ctx->prof_names.size(); ++i)
+        if (ctx->prof_names[i] == name) {
+            *total_ms = ctx->prof_total_ms[i];
+            *launches = ctx->prof_launches[i];
+        }
+    return MQG_OK;
+}
+
+int mqg_ctx_reset_profile(mqg_ctx *ctx) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    int rc = mqg::prof_collect(ctx);
+    if (rc != MQG_OK) return rc;
+    std::fill(ctx->prof_total_ms.begin(), ctx->prof_total_ms.end(), 0.0);
+    std::fill(ctx->prof_launches.begin(), ctx->prof_launches.end(), 0);
+    return MQG_OK;
+}
+
+int mqg_ctx_kernel_names(mqg_ctx *ctx, char *buf, int64_t buf_len) {
+    if (!ctx || !buf || buf_len < 1) return MQG_ERR_INVALID_ARG;
+    std::string all;
+    for (auto &n : ctx->prof_names) {
+        if (!all.empty()) all += "\n";
+        all += n;
+    }
+    if (static_cast<int64_t>(all.size()) + 1 > buf_len) return fail(ctx, MQG_ERR_CAPACITY, "mqg_ctx_kernel_names: buffer too small");
+    std::memcpy(buf, all.c_str(), all.size() + 1);
+    return MQG_OK;
+}
+
+static int check_graph(mqg_ctx *ctx, const mqg_graph *g, const char *who) {
+    if (!g) return fail(ctx, MQG_ERR_INVALID_ARG, std::string(who) + ": graph is NULL");
+    if (!valid_itype(g->ptr_type) || !valid_itype(g->idx_type))
+        return fail(ctx, MQG_ERR_INVALID_ARG, std::string(who) + ": bad index type");
+    if (g->num_nodes != ctx->num_nodes || g->ptr_type != ctx->ptr_type || g->idx_type != ctx->idx_type)
+        return fail(ctx, MQG_ERR_INVALID_ARG, std::string(who) + ": graph does not match the context");
+    if (!g->row_ptr || (g->num_edges > 0 && !g->col_idx))
+        return fail(ctx, MQG_ERR_INVALID_ARG, std::string(who) + ": NULL graph arrays");
+    return MQG_OK;
+}
+
+int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    int rc = check_graph(ctx, g, "mqg_build_cache");
+    if (rc != MQG_OK) return rc;
+    if (!cache) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: cache is NULL");
+    if (cache->num_nodes != g->num_nodes) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: cache->num_nodes differs from the graph");
+    if (cache->num_cached < 0 || cache->num_cached > cache->num_nodes)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: num_cached outside [0, num_nodes]");
+    if (!valid_dtype(cache->dtype) || cache->dim < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: bad dtype or dim");
+    if (!cache->slot_of || !cache->feats || (cache->num_cached > 0 && !cache->cache_rows))
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: NULL cache buffers");
+    if (cache->feat_stride < cache->dim || cache->cache_stride < cache->dim)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: stride below dim");
+    return mqg::run_build_cache(ctx, g, cache, static_cast<hipStream_t>(stream));
+}
+
+int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks,
+                      mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    int rc = check_graph(ctx, g, "mqg_sample_blocks");
+    if (rc != MQG_OK) return rc;
+    if (!fanouts || !blocks) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: NULL fanouts or blocks");
+    if (L != ctx->num_layers) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: num_layers differs from the context");
+    if (num_seeds < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: negative num_seeds");
+    if (num_seeds > ctx->max_seeds) return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_blocks: num_seeds above the context's max_seeds");
+    if (num_seeds > 0 && !seeds_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: seeds_dev is NULL");
+    int64_t dst = num_seeds;
+    for (int l = L - 1; l >= 0; --l) {
+        if (fanouts[l] < 1 || fanouts[l] > MQG_MAX_FANOUT)
+            return fail(ctx, MQG_ERR_UNSUPPORTED, "mqg_sample_blocks: fanout outside 1..MQG_MAX_FANOUT");
+        if (fanouts[l] > ctx->max_fanouts[l])
+            return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_blocks: fanout above the context's max_fanouts");
+        const mqg_block &b = blocks[l];
+        if (!b.src_ids || !b.indptr || !b.indices || !b.sizes)
+            return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: NULL block buffer");
+        int64_t nnz = dst * fanouts[l];
+        int64_t src = std::max(dst, std::min<int64_t>(g->num_nodes, dst + nnz));
+        if (b.cap_dst < dst || b.cap_nnz < nnz || b.cap_src < src)
+            return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_blocks: block " + std::to_string(l) +
+                        " needs cap_dst>=" + std::to_string(dst) + " cap_nnz>=" + std::to_string(nnz) +
+                        " cap_src>=" + std::to_string(src));
+        dst = src;
+    }
+    return mqg::run_sample_blocks(ctx, g, seeds_dev, num_seeds, fanouts, L, rng_seed, blocks,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                        const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
+                        int64_t *stats_dev, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!cache || !num_ids_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL cache or num_ids_dev");
+    if (!valid_itype(idx_type) || !valid_dtype(cache->dtype) || cache->dim < 1)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: bad idx_type, dtype or dim");
+    if (cap_ids < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: negative cap_ids");
+    if (cap_ids > 0 && (!ids_dev || !out_dev)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL ids or out");
+    if (!cache->feats) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: feats is NULL");
+    if (out_stride < cache->dim || cache->feat_stride < cache->dim)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: stride below dim");
+    bool has_cache = cache->slot_of != nullptr;
+    if (has_cache) {
+        if (cache->num_cached > 0 && !cache->cache_rows) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: slot_of without cache_rows");
+        if (cache->cache_stride < cache->dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_stride below dim");
+        if (cap_ids > ctx->max_src)
+            return fail(ctx, MQG_ERR_CAPACITY, "mqg_gather_features: cap_ids above the context's largest source list (" +
+                        std::to_string(ctx->max_src) + ")");
+    } else if (cache->cache_rows) {
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_rows without slot_of");
+    }
+    return mqg::run_gather(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride,
+                           stats_dev, static_cast<hipStream_t>(stream));
+}
+
+int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_src, int64_t x_stride,
+                            void *out, int64_t out_stride, int32_t dim, int32_t dtype, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!block || !block->indptr || !block->indices || !block->sizes)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: NULL block buffers");
+    if (!valid_dtype(dtype) || dim < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: bad dtype or dim");
+    if (block->cap_dst < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: negative cap_dst");
+    if (block->cap_dst > 0 && (!x_src || !out)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: NULL x_src or out");
+    if (x_stride < dim || out_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: stride below dim");
+    return mqg::run_mean_aggregate(ctx, block, x_src, x_stride, out, out_stride, dim, dtype,
+                                   static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

@@ -1,0 +1,103 @@
+// Internal declarations shared by the library's translation units (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <string>
+#include <vector>
+
+#include "mqg.h"
+
+namespace mqg {
+
+constexpr int kWave = 64;                // CDNA wavefront width
+constexpr int kBlock = 256;              // default workgroup: 4 wavefronts
+constexpr int kWavesPerBlock = kBlock / kWave;
+constexpr int kBitmapTileWords = 1024;   // words of the frontier bitmap handled by one workgroup
+constexpr int kCandidates = 256;         // per-wavefront candidate slots of the threshold selection
+
+struct ProfRec {
+    int name_id;
+    hipEvent_t start, stop;
+};
+
+}  // namespace mqg
+
+struct mqg_ctx {
+    int device = 0;
+    int64_t num_nodes = 0;
+    int32_t ptr_type = 0, idx_type = 0;
+    int32_t max_seeds = 0, num_layers = 0;
+    int32_t max_fanouts[MQG_MAX_LAYERS] = {0};
+    int64_t bound_dst[MQG_MAX_LAYERS] = {0};   // worst-case sizes per block for this context
+    int64_t bound_src[MQG_MAX_LAYERS] = {0};
+    int64_t bound_nnz[MQG_MAX_LAYERS] = {0};
+    int64_t max_dst = 0, max_src = 0, max_nnz = 0;
+
+    // scratch (device)
+    int32_t *local_of = nullptr;         // [num_nodes] position of a node in the current source list, -1 if absent
+    uint32_t *bitmap = nullptr;          // [bitmap_words] nodes first seen in the current layer
+    int64_t bitmap_words = 0;            // padded to a multiple of kBitmapTileWords
+    int32_t *tile_vals = nullptr;        // [max_tiles] per-tile sums, then their exclusive scan
+    int64_t max_tiles = 0;
+    int64_t *row_start = nullptr;        // [max_dst] first adjacency slot of each destination
+    int32_t *row_deg = nullptr;          // [max_dst] degree of each destination
+    void *nbr = nullptr;                 // [max_nnz] sampled neighbours, global ids, 32-bit
+    int2 *hit_list = nullptr;            // [max_src] (output row, cache slot)
+    int2 *miss_list = nullptr;           // [max_src] (output row, node id)
+    unsigned long long *counters = nullptr;  // [8] gather hit/miss counters when the caller wants none
+
+    // options
+    bool force_slow_select = false;
+    bool profile = false;
+
+    // profiling
+    std::vector<std::string> prof_names;
+    std::vector<mqg::ProfRec> prof_recs;
+    std::vector<hipEvent_t> event_pool;
+    std::vector<double> prof_total_ms;
+    std::vector<int64_t> prof_launches;
+
+    std::string last_error;
+};
+
+namespace mqg {
+
+int fail(mqg_ctx *ctx, int code, const std::string &msg);
+int prof_name_id(mqg_ctx *ctx, const char *name);
+void prof_begin(mqg_ctx *ctx, const char *name, hipStream_t s);
+void prof_end(mqg_ctx *ctx, hipStream_t s);
+
+// Launch wrapper: optional event bracketing, error check.  Usage:
+//   MQG_LAUNCH(ctx, "k_name", stream, (k_name<<<grid, block, 0, stream>>>(args...)));
+#define MQG_LAUNCH(ctx, name, stream, launch_expr)                                  \
+    do {                                                                            \
+        if ((ctx)->profile) mqg::prof_begin((ctx), (name), (stream));               \
+        launch_expr;                                                                \
+        if ((ctx)->profile) mqg::prof_end((ctx), (stream));                         \
+        hipError_t _e = hipGetLastError();                                          \
+        if (_e != hipSuccess)                                                       \
+            return mqg::fail((ctx), MQG_ERR_HIP,                                    \
+                             std::string(name) + ": " + hipGetErrorString(_e));     \
+    } while (0)
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// ---- steps implemented in the other translation units ----------------------------------
+int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds,
+                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks,
+                      hipStream_t s);
+int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids,
+               const int64_t *num_ids, int64_t cap_ids, void *out, int64_t out_stride,
+               int64_t *stats, hipStream_t s);
+int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
+                       int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
+int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t s);
+
+// Exclusive scan of vals[0..n) in place by one workgroup; the total (plus *addend if given) is
+// stored to *total_a and *total_b where non-null.
+int launch_scan_tiles(mqg_ctx *ctx, int32_t *vals, int64_t n, const int64_t *addend,
+                      int64_t *total_a, int64_t *total_b, hipStream_t s);
+
+}  // namespace mqg

@@ -1,0 +1,82 @@
+// Wavefront- and workgroup-level building blocks for gfx950 (64-wide wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mqg {
+
+__device__ __forceinline__ int lane_id() { return static_cast<int>(threadIdx.x) & 63; }
+
+__device__ __forceinline__ uint64_t lanes_below(int lane) { return (uint64_t(1) << lane) - 1; }
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __ballot(p); }
+
+__device__ __forceinline__ int popc64(uint64_t m) { return __popcll(m); }
+
+// Value of v in lane `l`; l must be the same in every lane.
+__device__ __forceinline__ uint32_t readlane32(uint32_t v, int l) {
+    return static_cast<uint32_t>(__builtin_amdgcn_readlane(static_cast<int>(v), l));
+}
+__device__ __forceinline__ uint64_t readlane64(uint64_t v, int l) {
+    uint32_t lo = readlane32(static_cast<uint32_t>(v), l);
+    uint32_t hi = readlane32(static_cast<uint32_t>(v >> 32), l);
+    return (uint64_t(hi) << 32) | lo;
+}
+
+// Orders LDS traffic of one wavefront: writes before, reads after.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// Inclusive prefix sum over the 64 lanes of a wavefront.
+__device__ __forceinline__ int wave_incl_scan(int v) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        int t = __shfl_up(v, off, 64);
+        if (lane >= off) v += t;
+    }
+    return v;
+}
+
+__device__ __forceinline__ int wave_sum(int v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// Exclusive prefix sum over a workgroup of NWAVES*64 threads; *total gets the workgroup sum.
+// `lds` needs NWAVES ints.  Every thread of the workgroup must call it.
+template <int NWAVES>
+__device__ __forceinline__ int block_excl_scan(int v, int *total, int *lds) {
+    const int lane = lane_id();
+    const int wave = static_cast<int>(threadIdx.x) >> 6;
+    int incl = wave_incl_scan(v);
+    __syncthreads();                       // lds may still be read from a previous call
+    if (lane == 63) lds[wave] = incl;
+    __syncthreads();
+    int base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < NWAVES; ++w) {
+        int t = lds[w];
+        if (w < wave) base += t;
+        sum += t;
+    }
+    *total = sum;
+    return base + incl - v;
+}
+
+// SplitMix64 finaliser (Steele, Lea, Flood 2014): the mixing function of the sampling keys.
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+}  // namespace mqg

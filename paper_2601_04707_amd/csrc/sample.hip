@@ -1,0 +1,432 @@
+// L-hop fixed-fanout neighbour sampling into bipartite blocks (paper Sec. III-A, GraphSAGE
+// paragraph; block layout after Sec. IV "Mini-Batch Transfer To GPU" and Eq. 16).
+//
+// Per block, outward from the seeds:
+//   k_row_info     adjacency start/degree of every destination, copy of the destinations into the
+//                  block's source list, per-tile sums of min(fanout, degree)
+//   k_scan_tiles   exclusive scan of the tile sums (one workgroup), total = nnz
+//   k_row_offsets  indptr
+//   k_sample       one wavefront per destination: smallest-k random keys, neighbours written in
+//                  ascending adjacency slot, first-seen nodes marked in an N-bit bitmap
+//   k_bitmap_count / k_scan_tiles / k_bitmap_emit
+//                  popcount-rank the bitmap: new source nodes come out ascending by id, get their
+//                  position recorded in local_of[], the bitmap is cleared on the way
+//   k_relabel      indices[e] = local_of[neighbour e]
+// All sizes that depend on the data stay on the device; grids are sized by worst-case bounds.
+#include "common.h"
+#include "device_utils.h"
+
+namespace mqg {
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
+constexpr uint64_t kMaxKey = ~uint64_t(0);
+
+uint64_t host_mix64(uint64_t z) {
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+// ------------------------------------------------------------------------------------------
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_init_seeds(const IdxT *__restrict__ seeds, int num_seeds, int32_t *__restrict__ local_of,
+             int64_t *__restrict__ sizes_last) {
+    int i = blockIdx.x * kBlock + threadIdx.x;
+    if (i < num_seeds) local_of[seeds[i]] = i;
+    if (i == 0) sizes_last[0] = num_seeds;
+}
+
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const int64_t *__restrict__ sizes,
+           IdxT *__restrict__ src_out, int fanout, int64_t *__restrict__ row_start,
+           int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *__restrict__ sizes_rw) {
+    __shared__ int lds[kWavesPerBlock];
+    const int64_t n = sizes[0];
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int cnt = 0;
+    if (i < n) {
+        IdxT v = dst[i];
+        int64_t s = static_cast<int64_t>(row_ptr[v]);
+        int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - s;
+        row_start[i] = s;
+        row_deg[i] = static_cast<int32_t>(d);
+        src_out[i] = v;
+        cnt = d < fanout ? static_cast<int>(d) : fanout;
+    }
+    int w = wave_sum(cnt);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = w;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
+        tile_sums[blockIdx.x] = t;
+        if (blockIdx.x == 0) sizes_rw[3] = 0;
+    }
+}
+
+// One workgroup of 1024 threads: vals[0..n) -> exclusive scan in place; totals stored.
+__global__ void __launch_bounds__(1024)
+k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ addend,
+             int64_t *__restrict__ total_a, int64_t *__restrict__ total_b) {
+    __shared__ int lds[16];
+    int64_t carry = 0;
+    for (int64_t base = 0; base < n; base += 1024) {
+        int64_t i = base + threadIdx.x;
+        int v = i < n ? vals[i] : 0;
+        int total;
+        int ex = block_excl_scan<16>(v, &total, lds);
+        if (i < n) vals[i] = static_cast<int32_t>(carry + ex);
+        carry += total;
+    }
+    if (threadIdx.x == 0) {
+        int64_t t = carry + (addend ? *addend : 0);
+        if (total_a) *total_a = t;
+        if (total_b) *total_b = t;
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, const int64_t *__restrict__ sizes,
+              const int32_t *__restrict__ tile_base, int32_t *__restrict__ indptr) {
+    __shared__ int lds[kWavesPerBlock];
+    const int64_t n = sizes[0];
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int cnt = 0;
+    if (i < n) {
+        int d = row_deg[i];
+        cnt = d < fanout ? d : fanout;
+    }
+    int total;
+    int ex = block_excl_scan<kWavesPerBlock>(cnt, &total, lds);
+    int off = tile_base[blockIdx.x] + ex;
+    if (i < n) {
+        indptr[i] = off;
+        if (i == n - 1) indptr[n] = off + cnt;
+    }
+    if (n == 0 && i == 0) indptr[0] = 0;
+}
+
+// ------------------------------------------------------------------------------------------
+// Neighbour selection.  One wavefront owns one destination node.
+
+struct SampleArgs {
+    const int64_t *row_start;
+    const int32_t *row_deg;
+    const int32_t *indptr;
+    const int64_t *sizes;
+    int32_t *nbr;
+    const int32_t *local_of;
+    uint32_t *bitmap;
+    uint64_t layer_hash;      // mix(mix(rng_seed + golden) ^ block index)
+    int fanout;
+    int force_slow;
+};
+
+template <typename IdxT>
+__device__ __forceinline__ void emit_neighbour(const IdxT *__restrict__ col_idx, int64_t start, int slot,
+                                               int32_t out_pos, const SampleArgs &a) {
+    int32_t u = static_cast<int32_t>(col_idx[start + slot]);
+    a.nbr[out_pos] = u;
+    if (a.local_of[u] < 0) {
+        uint32_t bit = 1u << (u & 31);
+        uint32_t *w = a.bitmap + (u >> 5);
+        (void)__hip_atomic_fetch_or(w, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// lexicographic (key, slot) order
+__device__ __forceinline__ bool pair_less(uint64_t ka, int sa, uint64_t kb, int sb) {
+    return ka < kb || (ka == kb && sa < sb);
+}
+
+// Unconditional selection: k rounds, each finding the smallest (key, slot) pair above the
+// previous round's.  O(k*d/64) key evaluations; used when the threshold pass cannot be
+// trusted (fewer than k or more than kCandidates keys under the threshold) and in tests.
+template <typename IdxT>
+__device__ void select_by_repeated_min(const IdxT *__restrict__ col_idx, int64_t start, int d, int k,
+                                       uint64_t hv, int32_t out_base, const SampleArgs &a) {
+    const int lane = lane_id();
+    uint64_t prev_key = 0;
+    int prev_slot = -1;
+    int my_slot = -1;                                // lane r keeps the r-th selected slot
+    for (int r = 0; r < k; ++r) {
+        uint64_t best_key = kMaxKey;
+        int best_slot = 0x7FFFFFFF;
+        for (int base = 0; base < d; base += kWave) {
+            int j = base + lane;
+            if (j < d) {
+                uint64_t key = mix64(hv ^ uint64_t(j));
+                bool above = (r == 0) || pair_less(prev_key, prev_slot, key, j);
+                if (above && pair_less(key, j, best_key, best_slot)) {
+                    best_key = key;
+                    best_slot = j;
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            uint64_t ok = __shfl_xor(best_key, off, 64);
+            int os = __shfl_xor(best_slot, off, 64);
+            if (pair_less(ok, os, best_key, best_slot)) {
+                best_key = ok;
+                best_slot = os;
+            }
+        }
+        prev_key = best_key;
+        prev_slot = best_slot;
+        if (lane == r) my_slot = best_slot;
+    }
+    // order the k chosen slots ascending
+    int rank = 0;
+    for (int t = 0; t < k; ++t) {
+        int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
+        rank += (other < my_slot) ? 1 : 0;
+    }
+    if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, SampleArgs a) {
+    __shared__ uint64_t cand_key[kWavesPerBlock][kCandidates];
+    __shared__ int32_t cand_slot[kWavesPerBlock][kCandidates];
+    const int lane = lane_id();
+    const int wave = static_cast<int>(threadIdx.x) >> 6;
+    const int64_t n = a.sizes[0];
+    const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+    if (row >= n) return;                                  // whole wavefront leaves together
+
+    const int64_t start = a.row_start[row];
+    const int d = a.row_deg[row];
+    const int k = a.fanout;
+    const int32_t out_base = a.indptr[row];
+
+    if (d <= k) {                                          // the whole row, no randomness
+        if (lane < d) emit_neighbour(col_idx, start, lane, out_base + lane, a);
+        return;
+    }
+    const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
+    if (a.force_slow) {
+        select_by_repeated_min(col_idx, start, d, k, hv, out_base, a);
+        return;
+    }
+    if (d <= kWave) {
+        // one key per lane; rank every key against all others
+        uint64_t key = lane < d ? mix64(hv ^ uint64_t(lane)) : kMaxKey;
+        int rank = 0;
+        for (int t = 0; t < d; ++t) {
+            uint64_t other = readlane64(key, t);
+            rank += pair_less(other, t, key, lane) ? 1 : 0;
+        }
+        bool sel = lane < d && rank < k;
+        uint64_t m = ballot64(sel);
+        if (sel) emit_neighbour(col_idx, start, lane, out_base + popc64(m & lanes_below(lane)), a);
+        return;
+    }
+
+    // d > 64: keep the slots whose key falls under a threshold expected to pass 2k+32 of them,
+    // then rank only those candidates.  Candidates are stored in ascending slot order.
+    uint64_t *ck = cand_key[wave];
+    int32_t *cs = cand_slot[wave];
+    const int expect = 2 * k + 32;
+    uint64_t thr = kMaxKey;
+    if (d > expect) thr = static_cast<uint64_t>((double(expect) / double(d)) * 18446744073709551616.0);
+    int cnt = 0;
+    for (int base = 0; base < d; base += kWave) {
+        int j = base + lane;
+        uint64_t key = mix64(hv ^ uint64_t(j));
+        bool c = j < d && key <= thr;
+        uint64_t m = ballot64(c);
+        if (c) {
+            int p = cnt + popc64(m & lanes_below(lane));
+            if (p < kCandidates) {
+                ck[p] = key;
+                cs[p] = j;
+            }
+        }
+        cnt += popc64(m);
+    }
+    if (cnt < k || cnt > kCandidates) {                    // wavefront-uniform
+        select_by_repeated_min(col_idx, start, d, k, hv, out_base, a);
+        return;
+    }
+    wave_lds_sync();
+    int out_pos = out_base;
+    for (int cbase = 0; cbase < cnt; cbase += kWave) {
+        int ci = cbase + lane;
+        bool valid = ci < cnt;
+        uint64_t my_key = valid ? ck[ci] : kMaxKey;
+        int rank = 0;
+        for (int t = 0; t < cnt; ++t) {
+            uint64_t other = ck[t];                        // same address in every lane: broadcast
+            rank += pair_less(other, t, my_key, ci) ? 1 : 0;
+        }
+        bool sel = valid && rank < k;
+        uint64_t m = ballot64(sel);
+        if (sel) emit_neighbour(col_idx, start, cs[ci], out_pos + popc64(m & lanes_below(lane)), a);
+        out_pos += popc64(m);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Bitmap -> ascending list of new source nodes.
+
+__global__ void __launch_bounds__(kBlock)
+k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_sums) {
+    __shared__ int lds[kWavesPerBlock];
+    const int64_t w0 = int64_t(blockIdx.x) * kBitmapTileWords + threadIdx.x * 4;
+    uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
+    int c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    int s = wave_sum(c);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
+        tile_sums[blockIdx.x] = t;
+    }
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_bitmap_emit(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
+              const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
+    __shared__ int lds[kWavesPerBlock];
+    const int64_t w0 = int64_t(blockIdx.x) * kBitmapTileWords + threadIdx.x * 4;
+    uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
+    int c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    int total;
+    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+    if (c == 0) return;
+    const int64_t num_dst = sizes[0];
+    int64_t pos = num_dst + tile_base[blockIdx.x] + ex;
+    uint32_t words[4] = {w.x, w.y, w.z, w.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        uint32_t bits = words[q];
+        while (bits) {
+            int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            int32_t v = static_cast<int32_t>((w0 + q) * 32 + b);
+            src_ids[pos] = static_cast<IdxT>(v);
+            local_of[v] = static_cast<int32_t>(pos);
+            ++pos;
+        }
+    }
+    *reinterpret_cast<uint4 *>(bitmap + w0) = make_uint4(0, 0, 0, 0);
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_relabel(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes,
+          const int32_t *__restrict__ local_of, int32_t *__restrict__ indices) {
+    const int64_t nnz = sizes[2];
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t e = int64_t(blockIdx.x) * kBlock + threadIdx.x; e < nnz; e += stride)
+        indices[e] = local_of[nbr[e]];
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of) {
+    const int64_t n = sizes[1];
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
+        local_of[src_ids[i]] = -1;
+}
+
+template <typename PtrT, typename IdxT>
+int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
+                       const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks, hipStream_t s) {
+    const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
+    const IdxT *col_idx = static_cast<const IdxT *>(g->col_idx);
+    const IdxT *seeds = static_cast<const IdxT *>(seeds_v);
+    int32_t *nbr = static_cast<int32_t *>(ctx->nbr);
+    const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
+
+    {
+        int grid = static_cast<int>(std::max<int64_t>(1, ceil_div(num_seeds, kBlock)));
+        MQG_LAUNCH(ctx, "k_init_seeds", s,
+                   (k_init_seeds<IdxT><<<grid, kBlock, 0, s>>>(seeds, num_seeds, ctx->local_of, blocks[L - 1].sizes)));
+    }
+    int64_t need_dst = num_seeds;
+    const int bitmap_tiles = static_cast<int>(ctx->bitmap_words / kBitmapTileWords);
+    for (int l = L - 1; l >= 0; --l) {
+        mqg_block &b = blocks[l];
+        const int k = fanouts[l];
+        const IdxT *dst = (l == L - 1) ? seeds : static_cast<const IdxT *>(blocks[l + 1].src_ids);
+        IdxT *src_ids = static_cast<IdxT *>(b.src_ids);
+        const int64_t need_nnz = need_dst * k;
+        const int row_tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)));
+
+        MQG_LAUNCH(ctx, "k_row_info", s,
+                   (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
+                                                                          ctx->row_deg, ctx->tile_vals, b.sizes)));
+        int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
+        if (rc != MQG_OK) return rc;
+        MQG_LAUNCH(ctx, "k_row_offsets", s,
+                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, b.indptr)));
+
+        SampleArgs a;
+        a.row_start = ctx->row_start;
+        a.row_deg = ctx->row_deg;
+        a.indptr = b.indptr;
+        a.sizes = b.sizes;
+        a.nbr = nbr;
+        a.local_of = ctx->local_of;
+        a.bitmap = ctx->bitmap;
+        a.layer_hash = host_mix64(seed_hash ^ uint64_t(l));
+        a.fanout = k;
+        a.force_slow = ctx->force_slow_select ? 1 : 0;
+        int sample_grid = static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kWavesPerBlock)));
+        MQG_LAUNCH(ctx, "k_sample", s, (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a)));
+
+        MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<<<std::max(1, bitmap_tiles), kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
+        // num_src = num_dst + number of new nodes; it is also the next block's num_dst
+        rc = launch_scan_tiles(ctx, ctx->tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1],
+                               l > 0 ? &blocks[l - 1].sizes[0] : nullptr, s);
+        if (rc != MQG_OK) return rc;
+        MQG_LAUNCH(ctx, "k_bitmap_emit", s,
+                   (k_bitmap_emit<IdxT><<<std::max(1, bitmap_tiles), kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids,
+                                                                                      ctx->local_of)));
+        int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
+        MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, ctx->local_of, b.indices)));
+
+        need_dst = std::max(need_dst, std::min<int64_t>(g->num_nodes, need_dst + need_nnz));
+    }
+    {
+        int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)), 4096));
+        MQG_LAUNCH(ctx, "k_reset_local", s,
+                   (k_reset_local<IdxT><<<grid, kBlock, 0, s>>>(static_cast<const IdxT *>(blocks[0].src_ids), blocks[0].sizes,
+                                                                 ctx->local_of)));
+    }
+    return MQG_OK;
+}
+
+}  // namespace
+
+int launch_scan_tiles(mqg_ctx *ctx, int32_t *vals, int64_t n, const int64_t *addend, int64_t *total_a,
+                      int64_t *total_b, hipStream_t s) {
+    MQG_LAUNCH(ctx, "k_scan_tiles", s, (k_scan_tiles<<<1, 1024, 0, s>>>(vals, n, addend, total_a, total_b)));
+    return MQG_OK;
+}
+
+int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds,
+                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks, hipStream_t s) {
+    const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
+    if (p64 && i64) return sample_blocks_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+    if (p64 && !i64) return sample_blocks_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+    if (!p64 && i64) return sample_blocks_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+    return sample_blocks_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+}
+
+}  // namespace mqg

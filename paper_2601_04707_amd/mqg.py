@@ -1,0 +1,272 @@
+"""ctypes binding of libmqg.so - argument marshalling only.
+
+The four operations keep the names of the C ABI (``include/mqg.h``):
+``mqg_build_cache``, ``mqg_sample_blocks``, ``mqg_gather_features`` and
+``mqg_sage_mean_aggregate``.  Torch is used for device memory, pinned host
+memory and streams; every step of the path runs in the library's kernels.
+There is no fallback: if the shared library is missing, importing this module
+raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import List, Optional, Sequence
+
+import torch
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libmqg.so")
+
+MQG_OK, MQG_ERR_INVALID_ARG, MQG_ERR_CAPACITY, MQG_ERR_HIP, MQG_ERR_UNSUPPORTED = 0, -1, -2, -3, -4
+MQG_F32, MQG_F16 = 0, 1
+MQG_I32, MQG_I64 = 0, 1
+MQG_OPT_FORCE_SLOW_SELECT, MQG_OPT_PROFILE = 1, 2
+MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
+
+EXPORTS = [
+    "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
+    "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
+    "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate",
+]
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_04707_amd.build` "
+                      "(hipcc, gfx950).  There is no CPU fallback.")
+
+lib = ctypes.CDLL(LIB_PATH)
+
+_i64, _i32, _vp = ctypes.c_int64, ctypes.c_int32, ctypes.c_void_p
+
+
+class CGraph(ctypes.Structure):
+    _fields_ = [("num_nodes", _i64), ("num_edges", _i64), ("ptr_type", _i32), ("idx_type", _i32),
+                ("row_ptr", _vp), ("col_idx", _vp)]
+
+
+class CCache(ctypes.Structure):
+    _fields_ = [("num_nodes", _i64), ("num_cached", _i64), ("dim", _i32), ("dtype", _i32),
+                ("feats", _vp), ("feat_stride", _i64), ("cache_rows", _vp), ("cache_stride", _i64),
+                ("slot_of", _vp), ("cached_ids", _vp)]
+
+
+class CBlock(ctypes.Structure):
+    _fields_ = [("cap_dst", _i64), ("cap_src", _i64), ("cap_nnz", _i64), ("src_ids", _vp),
+                ("indptr", _vp), ("indices", _vp), ("sizes", _vp)]
+
+
+lib.mqg_version.restype = _i32
+lib.mqg_version.argtypes = []
+lib.mqg_ctx_create.restype = ctypes.c_int
+lib.mqg_ctx_create.argtypes = [ctypes.POINTER(_vp), ctypes.POINTER(CGraph), _i32, ctypes.POINTER(_i32), _i32]
+lib.mqg_ctx_destroy.restype = ctypes.c_int
+lib.mqg_ctx_destroy.argtypes = [_vp]
+lib.mqg_last_error.restype = ctypes.c_char_p
+lib.mqg_last_error.argtypes = [_vp]
+lib.mqg_ctx_set_option.restype = ctypes.c_int
+lib.mqg_ctx_set_option.argtypes = [_vp, _i32, _i64]
+lib.mqg_ctx_kernel_time.restype = ctypes.c_int
+lib.mqg_ctx_kernel_time.argtypes = [_vp, ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]
+lib.mqg_ctx_reset_profile.restype = ctypes.c_int
+lib.mqg_ctx_reset_profile.argtypes = [_vp]
+lib.mqg_ctx_kernel_names.restype = ctypes.c_int
+lib.mqg_ctx_kernel_names.argtypes = [_vp, ctypes.c_char_p, _i64]
+lib.mqg_build_cache.restype = ctypes.c_int
+lib.mqg_build_cache.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), _vp]
+lib.mqg_sample_blocks.restype = ctypes.c_int
+lib.mqg_sample_blocks.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32,
+                                  ctypes.c_uint64, ctypes.POINTER(CBlock), _vp]
+lib.mqg_gather_features.restype = ctypes.c_int
+lib.mqg_gather_features.argtypes = [_vp, ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
+lib.mqg_sage_mean_aggregate.restype = ctypes.c_int
+lib.mqg_sage_mean_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
+
+
+class MqgError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"mqg error {code}: {msg}")
+        self.code = code
+
+
+def _itype(t: torch.Tensor) -> int:
+    if t.dtype == torch.int32:
+        return MQG_I32
+    if t.dtype == torch.int64:
+        return MQG_I64
+    raise TypeError(f"index tensors must be int32 or int64, got {t.dtype}")
+
+
+def _dtype(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return MQG_F32
+    if t.dtype == torch.float16:
+        return MQG_F16
+    raise TypeError(f"features must be float32 or float16, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, torch.cuda.Stream):
+        return stream.cuda_stream
+    return int(stream)
+
+
+class Graph:
+    """CSR graph resident on the GPU (the tensors are kept alive here)."""
+
+    def __init__(self, row_ptr: torch.Tensor, col_idx: torch.Tensor):
+        assert row_ptr.is_cuda and col_idx.is_cuda and row_ptr.is_contiguous() and col_idx.is_contiguous()
+        self.row_ptr, self.col_idx = row_ptr, col_idx
+        self.num_nodes = row_ptr.numel() - 1
+        self.c = CGraph(self.num_nodes, col_idx.numel(), _itype(row_ptr), _itype(col_idx),
+                        row_ptr.data_ptr(), col_idx.data_ptr())
+
+    @property
+    def idx_dtype(self):
+        return self.col_idx.dtype
+
+
+class Context:
+    def __init__(self, graph: Graph, max_seeds: int, max_fanouts: Sequence[int]):
+        self.graph = graph
+        self.max_fanouts = list(max_fanouts)
+        self.max_seeds = int(max_seeds)
+        h = _vp()
+        arr = (_i32 * len(max_fanouts))(*max_fanouts)
+        rc = lib.mqg_ctx_create(ctypes.byref(h), ctypes.byref(graph.c), max_seeds, arr, len(max_fanouts))
+        if rc != MQG_OK:
+            raise MqgError(rc, lib.mqg_last_error(None).decode())
+        self.h = h
+
+    def check(self, rc: int):
+        if rc != MQG_OK:
+            raise MqgError(rc, lib.mqg_last_error(self.h).decode())
+
+    def set_option(self, option: int, value: int):
+        self.check(lib.mqg_ctx_set_option(self.h, option, value))
+
+    def kernel_time(self, name: str):
+        ms, n = ctypes.c_double(0), _i64(0)
+        self.check(lib.mqg_ctx_kernel_time(self.h, name.encode(), ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value
+
+    def kernel_names(self) -> List[str]:
+        buf = ctypes.create_string_buffer(8192)
+        self.check(lib.mqg_ctx_kernel_names(self.h, buf, 8192))
+        return [s for s in buf.value.decode().split("\n") if s]
+
+    def reset_profile(self):
+        self.check(lib.mqg_ctx_reset_profile(self.h))
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.mqg_ctx_destroy(self.h)
+            self.h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def block_bounds(num_nodes: int, num_seeds: int, fanouts: Sequence[int]):
+    """Worst-case (cap_dst, cap_src, cap_nnz) per block, the bounds the library checks."""
+    L = len(fanouts)
+    out = [None] * L
+    dst = num_seeds
+    for l in range(L - 1, -1, -1):
+        nnz = dst * fanouts[l]
+        src = max(dst, min(num_nodes, dst + nnz))
+        out[l] = (dst, src, nnz)
+        dst = src
+    return out
+
+
+class Blocks:
+    """Device buffers of the L blocks of one mini-batch, sized by the worst-case bounds."""
+
+    def __init__(self, graph: Graph, max_seeds: int, fanouts: Sequence[int], device=None):
+        device = device or graph.col_idx.device
+        self.fanouts = list(fanouts)
+        self.L = len(fanouts)
+        self.bounds = block_bounds(graph.num_nodes, max_seeds, fanouts)
+        self.src_ids, self.indptr, self.indices = [], [], []
+        self.sizes = torch.zeros((self.L, 4), dtype=torch.int64, device=device)
+        self.c = (CBlock * self.L)()
+        for l, (cd, cs, cn) in enumerate(self.bounds):
+            self.src_ids.append(torch.empty(max(cs, 1), dtype=graph.idx_dtype, device=device))
+            self.indptr.append(torch.empty(cd + 1, dtype=torch.int32, device=device))
+            self.indices.append(torch.empty(max(cn, 1), dtype=torch.int32, device=device))
+            self.c[l] = CBlock(cd, cs, cn, self.src_ids[l].data_ptr(), self.indptr[l].data_ptr(),
+                               self.indices[l].data_ptr(), self.sizes[l].data_ptr())
+
+    def host_sizes(self):
+        """[(num_dst, num_src, nnz, flags)] - synchronises."""
+        return [tuple(int(x) for x in row) for row in self.sizes.cpu().tolist()]
+
+
+class Cache:
+    """Feature storage plus the HBM cache of hot rows.  `feats` may be a pinned host tensor
+    or a device tensor; with num_cached=None there is no cache and feats is read directly."""
+
+    def __init__(self, graph: Graph, feats: torch.Tensor, num_cached: Optional[int], cache_stride: Optional[int] = None):
+        assert feats.dim() == 2 and feats.stride(1) == 1
+        assert feats.is_cuda or feats.is_pinned(), "feats must be device or pinned host memory"
+        self.feats = feats
+        self.dim = feats.shape[1]
+        dev = graph.col_idx.device
+        self.num_cached = num_cached
+        if num_cached is None:
+            self.cache_rows = self.slot_of = self.cached_ids = None
+            self.cache_stride = 0
+            nc = 0
+        else:
+            nc = int(num_cached)
+            self.cache_stride = int(cache_stride or self.dim)
+            self.cache_rows = torch.zeros((max(nc, 1), self.cache_stride), dtype=feats.dtype, device=dev)
+            self.slot_of = torch.empty(max(graph.num_nodes, 1), dtype=torch.int32, device=dev)
+            self.cached_ids = torch.empty(max(nc, 1), dtype=graph.idx_dtype, device=dev)
+        self.c = CCache(graph.num_nodes, nc, self.dim, _dtype(feats), feats.data_ptr(), feats.stride(0),
+                        _ptr(self.cache_rows), self.cache_stride, _ptr(self.slot_of), _ptr(self.cached_ids))
+
+
+# ---------------------------------------------------------------------------------- the four calls
+
+def mqg_build_cache(ctx: Context, graph: Graph, cache: Cache, stream=None) -> None:
+    ctx.check(lib.mqg_build_cache(ctx.h, ctypes.byref(graph.c), ctypes.byref(cache.c), _stream(stream)))
+
+
+def mqg_sample_blocks(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequence[int], rng_seed: int,
+                      blocks: Blocks, stream=None) -> None:
+    assert seeds.is_cuda and seeds.dtype == graph.idx_dtype and seeds.is_contiguous()
+    arr = (_i32 * len(fanouts))(*fanouts)
+    ctx.check(lib.mqg_sample_blocks(ctx.h, ctypes.byref(graph.c), seeds.data_ptr(), seeds.numel(), arr,
+                                    len(fanouts), ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), blocks.c,
+                                    _stream(stream)))
+
+
+def mqg_gather_features(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,
+                        stats: Optional[torch.Tensor] = None, cap_ids: Optional[int] = None, stream=None) -> None:
+    """ids: device id tensor; num_ids: device int64 scalar tensor (e.g. blocks.sizes[0, 1:2])."""
+    assert ids.is_cuda and num_ids.is_cuda and num_ids.dtype == torch.int64 and out.is_cuda
+    assert out.dtype == cache.feats.dtype and out.stride(1) == 1
+    cap = int(cap_ids if cap_ids is not None else min(ids.numel(), out.shape[0]))
+    assert cap <= ids.numel() and cap <= out.shape[0]
+    ctx.check(lib.mqg_gather_features(ctx.h, ctypes.byref(cache.c), _itype(ids), ids.data_ptr(), num_ids.data_ptr(),
+                                      cap, out.data_ptr(), out.stride(0), _ptr(stats), _stream(stream)))
+
+
+def mqg_sage_mean_aggregate(ctx: Context, blocks: Blocks, l: int, x_src: torch.Tensor, out: torch.Tensor,
+                            stream=None) -> None:
+    assert x_src.is_cuda and out.is_cuda and x_src.dtype == out.dtype
+    assert x_src.stride(1) == 1 and out.stride(1) == 1 and x_src.shape[1] == out.shape[1]
+    assert out.shape[0] >= blocks.c[l].cap_dst
+    ctx.check(lib.mqg_sage_mean_aggregate(ctx.h, ctypes.byref(blocks.c[l]), x_src.data_ptr(), x_src.stride(0),
+                                          out.data_ptr(), out.stride(0), x_src.shape[1], _dtype(x_src),
+                                          _stream(stream)))
