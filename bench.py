@@ -1,0 +1,241 @@
+#!/usr/bin/env python3
+"""Mini-batch generation benchmark on one MI355X.
+
+A step is one pass of the whole hot path over one mini-batch: L-hop neighbour
+sampling into blocks, feature gather through the HBM cache (misses read from
+pinned host memory), and the chain of mean aggregations, on the "medium"
+workload (Reddit-shaped synthetic power-law graph, 602-dim fp32 features,
+fanouts [25, 10], 1,024 seeds, top 30 % of nodes by degree cached in HBM).
+Inputs are resident (graph and cache in HBM, features in pinned host memory)
+before the timed region starts.
+
+Prints one JSON line; see the design doc for the meaning of every field.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+HOST_LINK_PEAK_GBPS = 64.0      # PCIe Gen5 x16, one direction, nominal
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="medium")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
+    ap.add_argument("--cache-pct", type=int, default=None)
+    ap.add_argument("--in-flight", type=int, default=1, help="mini-batches in flight (contexts x streams)")
+    ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-copy", action="store_true",
+                    help="also launch one plain 1 GiB read + 1 GiB write elementwise kernel, the known-size "
+                         "reference that hardware-counter runs are scaled by")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no sharding or collectives); "
+              f"--gpus {args.gpus} is not supported", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    from paper_2601_04707_amd import mqg, synth
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    dev = "cuda"
+    w = synth.WORKLOADS[args.workload]
+    if args.scale != 1.0:
+        w = synth.scaled(w, args.scale)
+    cache_pct = args.cache_pct if args.cache_pct is not None else w.cache_pct
+    K, W = args.steps, args.warmup
+    nfl = max(1, args.in_flight)
+    L = len(w.fanouts)
+    elt = 2 if w.feat_dtype == torch.float16 else 4
+    row_bytes = w.dim * elt
+
+    # ---------------------------------------------------------------- inputs (untimed)
+    t0 = time.time()
+    rp, ci = synth.build_graph(w, seed=0, device=dev)
+    n = rp.numel() - 1
+    feats = torch.empty((n, w.dim), dtype=w.feat_dtype).pin_memory()
+    synth.node_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev, out=feats)
+    torch.cuda.synchronize()
+    g = mqg.Graph(rp, ci)
+    batches = synth.seed_batches(n, w.batch, K + W, seed=2, train_fraction=w.train_fraction)
+    seeds_dev = [b.to(g.idx_dtype).to(dev) for b in batches]
+    gen_s = time.time() - t0
+
+    ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
+    blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]
+    streams = [torch.cuda.Stream() for _ in range(nfl)] if nfl > 1 else [torch.cuda.current_stream()]
+    if cache_pct is None:
+        cache = mqg.Cache(g, feats.to(dev), None)
+        num_cached = 0
+    else:
+        num_cached = n * cache_pct // 100
+        cache = mqg.Cache(g, feats, num_cached)
+        t0 = time.time()
+        mqg.mqg_build_cache(ctxs[0], g, cache)
+        torch.cuda.synchronize()
+    build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0
+
+    bounds = blks[0].bounds
+    x0 = [torch.empty((bounds[0][1], w.dim), dtype=w.feat_dtype, device=dev) for _ in range(nfl)]
+    hs = [[torch.empty((bounds[l][0], w.dim), dtype=w.feat_dtype, device=dev) for l in range(L)] for _ in range(nfl)]
+    stats = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(nfl)]
+    sizes_log = torch.zeros((K + W, L, 4), dtype=torch.int64, device=dev)
+    stats_log = torch.zeros((K + W, 2), dtype=torch.int64, device=dev)
+    base_seed = 3
+
+    def step(i: int):
+        j = i % nfl
+        s = streams[j]
+        with torch.cuda.stream(s):
+            mqg.mqg_sample_blocks(ctxs[j], g, seeds_dev[i], w.fanouts, base_seed + i, blks[j], stream=s)
+            mqg.mqg_gather_features(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s)
+            x = x0[j]
+            for l in range(L):
+                mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s)
+                x = hs[j][l]
+            sizes_log[i].copy_(blks[j].sizes, non_blocking=True)
+            stats_log[i].copy_(stats[j], non_blocking=True)
+
+    # ---------------------------------------------------------------- timed region
+    for i in range(W):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(W, W + K):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    sizes_host = sizes_log[W:].cpu().numpy()
+    stats_host = stats_log[W:].cpu().numpy()
+    edges = int(sizes_host[:, :, 2].sum())
+    rows = int(sizes_host[:, 0, 1].sum())
+    hits, misses = int(stats_host[:, 0].sum()), int(stats_host[:, 1].sum())
+    ms_per_step = elapsed / K * 1e3
+    edges_per_s = edges / elapsed
+    gather_bytes = rows * row_bytes
+
+    # ---------------------------------------------------------------- per-kernel durations (HIP events on the launch stream)
+    for c in ctxs:
+        c.set_option(mqg.MQG_OPT_PROFILE, 1)
+    for i in range(W, W + K):
+        step(i)
+    torch.cuda.synchronize()
+    kernels = {}
+    for c in ctxs:
+        for name in c.kernel_names():
+            ms, cnt = c.kernel_time(name)
+            a = kernels.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += cnt
+        c.set_option(mqg.MQG_OPT_PROFILE, 0)
+    kern = {k: {"launches": v[1], "avg_us": round(v[0] / max(v[1], 1) * 1e3, 3),
+                "us_per_step": round(v[0] / K * 1e3, 3)} for k, v in sorted(kernels.items())}
+
+    def roof(name, bytes_per_launch, peak, traffic=None):
+        if name not in kernels or kernels[name][1] == 0:
+            return None
+        avg_s = kernels[name][0] / kernels[name][1] * 1e-3
+        ach = bytes_per_launch / avg_s / 1e9
+        return {"kernel": name, "bound": "hbm", "achieved": round(ach, 1), "peak": peak, "unit": "GB/s",
+                "frac": round(ach / peak, 4), "traffic": traffic,
+                "avg_kernel_us": round(avg_s * 1e6, 2), "bytes_per_launch": int(bytes_per_launch)}
+
+    if cache_pct is None:
+        # direct gather: row read + row written + the id
+        roofline = roof("k_gather_direct", rows / K * (2 * row_bytes + ci.element_size()), HBM_PEAK_GBPS)
+        host_link = None
+    else:
+        # hit gather: row read from the HBM cache + row written + the 8-byte (row, slot) list entry
+        roofline = roof("k_gather_hit", hits / K * (2 * row_bytes + 8), HBM_PEAK_GBPS)
+        host_link = roof("k_gather_miss", misses / K * row_bytes, HOST_LINK_PEAK_GBPS)
+        if host_link:
+            host_link["bound"] = "host-link"
+
+    sample_us = sum(v["us_per_step"] for k, v in kern.items()
+                    if k in ("k_init_seeds", "k_row_info", "k_scan_tiles", "k_row_offsets", "k_sample",
+                             "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local"))
+    gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
+    agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
+
+    # ---------------------------------------------------------------- CPU baseline: the oracle, one thread
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        rp_np, ci_np = rp.cpu().numpy().astype(np.int64), ci.cpu().numpy().astype(np.int64)
+        feats_np = feats.numpy()
+        ocache = oracle.build_cache(rp_np, num_cached, feats_np) if cache_pct is not None else None
+        nb = args.cpu_batches
+        t_cpu, e_cpu, done = 0.0, 0, 0
+        budget_s = 20.0
+        for i in range(W, W + K):
+            t1 = time.perf_counter()
+            ob = oracle.sample_blocks(rp_np, ci_np, batches[i].numpy(), w.fanouts, base_seed + i)
+            x, _, _ = oracle.gather(ob[0].src_ids, feats_np, ocache)
+            for l in range(L):
+                x = oracle.mean_aggregate(ob[l].indptr, ob[l].indices, x)
+            t_cpu += time.perf_counter() - t1
+            e_cpu += sum(b.nnz for b in ob)
+            done += 1
+            if i == W:   # the first oracle batch doubles as an end-to-end check of the timed GPU path
+                assert [b.nnz for b in ob] == sizes_host[0, :, 2].tolist(), "GPU and oracle disagree on batch sizes"
+            if (nb is not None and done >= nb) or (nb is None and t_cpu > budget_s):
+                break
+        cpu = {"value": round(e_cpu / t_cpu, 1), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {done} of the {K} timed mini-batches, whole path (sample+gather+aggregate), "
+                         f"{t_cpu:.1f} s; host has {os.cpu_count()} logical cores"}
+
+    if args.pmc_copy:
+        a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        torch.mul(a, 2.0, out=b)
+        torch.cuda.synchronize()
+
+    out = {
+        "metric": "sampled edges/sec + feature-gather GB/s (% of HBM peak) per mini-batch",
+        "value": round(edges_per_s, 1),
+        "unit": "sampled edges/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int64+f32" if elt == 4 else "int64+f16",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: Chung-Lu power-law graph, {n} nodes, {ci.numel()} directed edges, "
+                               f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
+                               f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes, "
+                               f"rest in pinned host memory",
+                   "in_flight": nfl, "global_batch": w.batch},
+        "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
+        "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
+        "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),
+        "cache_hit_rate": round(hits / max(1, hits + misses), 4),
+        "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1)},
+        "roofline": roofline,
+        "roofline_host_link": host_link,
+        "cpu_baseline": cpu,
+        "kernels": kern,
+        "build_cache_ms": round(build_cache_ms, 2),
+        "input_generation_s": round(gen_s, 1),
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
