@@ -35,7 +35,9 @@ def main() -> int:
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--cache-pct", type=int, default=None)
-    ap.add_argument("--in-flight", type=int, default=1, help="mini-batches in flight (contexts x streams)")
+    ap.add_argument("--in-flight", type=int, default=3, help="mini-batches in flight (contexts x streams)")
+    ap.add_argument("--miss-inflight-kb", type=int, default=None, help="KiB of host reads the miss gather keeps outstanding")
+    ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -77,6 +79,7 @@ def main() -> int:
     seeds_dev = [b.to(g.idx_dtype).to(dev) for b in batches]
     gen_s = time.time() - t0
 
+    pad_dim = (row_bytes + 15) // 16 * 16 // elt      # row stride that keeps every row 16-byte aligned
     ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]
     streams = [torch.cuda.Stream() for _ in range(nfl)] if nfl > 1 else [torch.cuda.current_stream()]
@@ -85,15 +88,20 @@ def main() -> int:
         num_cached = 0
     else:
         num_cached = n * cache_pct // 100
-        cache = mqg.Cache(g, feats, num_cached)
+        cache = mqg.Cache(g, feats, num_cached, cache_stride=pad_dim)
         t0 = time.time()
         mqg.mqg_build_cache(ctxs[0], g, cache)
         torch.cuda.synchronize()
     build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0
 
+    for c in ctxs:
+        if args.miss_inflight_kb is not None:
+            c.set_option(mqg.MQG_OPT_MISS_INFLIGHT_BYTES, args.miss_inflight_kb * 1024)
+        if args.heavy_degree is not None:
+            c.set_option(mqg.MQG_OPT_HEAVY_DEGREE, args.heavy_degree)
     bounds = blks[0].bounds
-    x0 = [torch.empty((bounds[0][1], w.dim), dtype=w.feat_dtype, device=dev) for _ in range(nfl)]
-    hs = [[torch.empty((bounds[l][0], w.dim), dtype=w.feat_dtype, device=dev) for l in range(L)] for _ in range(nfl)]
+    x0 = [torch.zeros((bounds[0][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for _ in range(nfl)]
+    hs = [[torch.zeros((bounds[l][0], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)] for _ in range(nfl)]
     stats = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(nfl)]
     sizes_log = torch.zeros((K + W, L, 4), dtype=torch.int64, device=dev)
     stats_log = torch.zeros((K + W, 2), dtype=torch.int64, device=dev)

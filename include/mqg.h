@@ -114,9 +114,10 @@ typedef struct mqg_cache {
  *                         a row in ascending order of adjacency slot.
  *   sizes    [4]          int64, written on the device: num_dst, num_src, nnz,
  *                         and a flags word (0 = ok).
- * Capacity bounds checked by mqg_sample_blocks (MQG_ERR_CAPACITY otherwise):
- *   cap_dst(L-1) >= num_seeds,  cap_dst(l) >= cap_src(l+1),
- *   cap_nnz >= cap_dst * fanouts[l],  cap_src >= min(num_nodes, cap_dst + cap_nnz).
+ * Capacity bounds checked by mqg_sample_blocks (MQG_ERR_CAPACITY otherwise), with
+ * need_dst(L-1) = num_seeds and need_dst(l) = need_src(l+1):
+ *   cap_dst >= need_dst,  cap_nnz >= need_nnz = need_dst * fanouts[l],
+ *   cap_src >= need_src = max(need_dst, min(num_nodes, need_dst + need_nnz)).
  */
 typedef struct mqg_block {
     int64_t cap_dst;
@@ -150,8 +151,15 @@ const char *mqg_last_error(const mqg_ctx *ctx);
 typedef enum {
     MQG_OPT_FORCE_SLOW_SELECT = 1,       /* value != 0: every row with degree > fanout uses the
                                             repeated-minimum selection (test of the rare path) */
-    MQG_OPT_PROFILE = 2                  /* value != 0: bracket every kernel with HIP events
+    MQG_OPT_PROFILE = 2,                 /* value != 0: bracket every kernel with HIP events
                                             (adds a few microseconds per kernel)              */
+    MQG_OPT_MISS_INFLIGHT_BYTES = 3,     /* bytes of host-memory reads the miss gather keeps
+                                            outstanding (1 KiB..1 GiB, default 512 KiB): sizes
+                                            its grid; enough to saturate the host link without
+                                            crowding concurrent streams out of the memory system */
+    MQG_OPT_HEAVY_DEGREE = 4             /* destinations with more neighbours than this (>= 64,
+                                            default 2048) are sampled by a whole workgroup
+                                            instead of one wavefront; results do not change   */
 } mqg_option;
 int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value);
 
@@ -201,7 +209,10 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
  *   ids_dev      device [cap_ids], graph idx_type (normally blocks[0].src_ids)
  *   num_ids_dev  device int64: number of valid ids (normally &blocks[0].sizes[1]);
  *                values above cap_ids are clamped to cap_ids
- *   out_dev      device [cap_ids x out_stride] elements of cache->dtype
+ *   out_dev      device [cap_ids x out_stride] elements of cache->dtype; in a written row
+ *                the elements from dim up to out_stride (padding) are unspecified: when
+ *                source and destination rows are 16-byte aligned the copy is rounded up
+ *                to whole 16-byte words
  *   stats_dev    device int64[2]: rows served from the cache, rows served
  *                from feats; may be NULL
  */
@@ -215,7 +226,9 @@ int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
  *   out[i, c] = (1/n_i) * sum_{e in row i} x_src[indices[e], c],  n_i = row length;
  *   a destination with no sampled neighbour gets zeros.
  * x_src: device [num_src x x_stride]; out: device [cap_dst x out_stride];
- * strides in elements; sums are accumulated in fp32 in row order; MQG_F16
+ * strides in elements (columns from dim up to out_stride of a written row are
+ * unspecified: with 16-byte aligned rows on both sides whole 16-byte words are
+ * processed); sums are accumulated in fp32 in row order; MQG_F16
  * rounds once, to nearest even, at the store.
  */
 int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_src,

@@ -137,6 +137,8 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const i
     ok = ok && dev_alloc(&c->row_start, c->max_dst) == hipSuccess;
     ok = ok && dev_alloc(&c->row_deg, c->max_dst) == hipSuccess;
     ok = ok && dev_alloc(reinterpret_cast<int32_t **>(&c->nbr), c->max_nnz) == hipSuccess;
+    ok = ok && dev_alloc(&c->heavy_rows, c->max_dst) == hipSuccess;
+    ok = ok && dev_alloc(&c->heavy_count, MQG_MAX_LAYERS) == hipSuccess;
     ok = ok && dev_alloc(&c->hit_list, c->max_src) == hipSuccess;
     ok = ok && dev_alloc(&c->miss_list, c->max_src) == hipSuccess;
     ok = ok && dev_alloc(&c->counters, 8) == hipSuccess;
@@ -161,6 +163,8 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->row_start);
     (void)hipFree(c->row_deg);
     (void)hipFree(c->nbr);
+    (void)hipFree(c->heavy_rows);
+    (void)hipFree(c->heavy_count);
     (void)hipFree(c->hit_list);
     (void)hipFree(c->miss_list);
     (void)hipFree(c->counters);
@@ -178,6 +182,14 @@ int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value) {
     switch (option) {
         case MQG_OPT_FORCE_SLOW_SELECT: ctx->force_slow_select = value != 0; return MQG_OK;
         case MQG_OPT_PROFILE: ctx->profile = value != 0; return MQG_OK;
+        case MQG_OPT_HEAVY_DEGREE:
+            if (value < 64 || value > 0x7FFFFFFF) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: MQG_OPT_HEAVY_DEGREE outside 64..2^31-1");
+            ctx->heavy_degree = static_cast<int>(value);
+            return MQG_OK;
+        case MQG_OPT_MISS_INFLIGHT_BYTES:
+            if (value < 1024 || value > (int64_t(1) << 30)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: MQG_OPT_MISS_INFLIGHT_BYTES outside 1 KiB..1 GiB");
+            ctx->miss_inflight_bytes = value;
+            return MQG_OK;
         default: return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: unknown option");
     }
 }

@@ -44,6 +44,8 @@ struct mqg_ctx {
     int64_t *row_start = nullptr;        // [max_dst] first adjacency slot of each destination
     int32_t *row_deg = nullptr;          // [max_dst] degree of each destination
     void *nbr = nullptr;                 // [max_nnz] sampled neighbours, global ids, 32-bit
+    int32_t *heavy_rows = nullptr;       // [max_dst] destinations whose degree exceeds heavy_degree
+    int32_t *heavy_count = nullptr;      // [MQG_MAX_LAYERS] their number, per block
     int2 *hit_list = nullptr;            // [max_src] (output row, cache slot)
     int2 *miss_list = nullptr;           // [max_src] (output row, node id)
     unsigned long long *counters = nullptr;  // [8] gather hit/miss counters when the caller wants none
@@ -51,6 +53,8 @@ struct mqg_ctx {
     // options
     bool force_slow_select = false;
     bool profile = false;
+    int64_t miss_inflight_bytes = 512 * 1024;   // read bytes the host-link gather keeps outstanding
+    int heavy_degree = 2048;             // rows longer than this get a whole workgroup in sampling
 
     // profiling
     std::vector<std::string> prof_names;

@@ -32,83 +32,150 @@ __global__ void k_direct_stats(unsigned long long *counters, const int64_t *num_
     }
 }
 
+constexpr int kClassifyItems = 4;                       // ids per thread and tile
+constexpr int kClassifyTile = kBlock * kClassifyItems;
+
+// Splits the ids into a hit list (output row, cache slot) and a miss list (output row, node id).
+// A workgroup classifies a tile of 1024 ids, scans its hit and miss counts together (packed in
+// one int) and reserves its share of both lists with one atomic each, so the two counters see
+// about a hundred atomics per mini-batch instead of one per wavefront.  The order of the list
+// entries is arbitrary; the gather does not depend on it.
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
            const int32_t *__restrict__ slot_of, int2 *__restrict__ hit_list, int2 *__restrict__ miss_list,
            unsigned long long *__restrict__ counters) {
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ unsigned long long base[2];
     int64_t n = *num_ids;
     if (n > cap) n = cap;
+    for (int64_t t0 = int64_t(blockIdx.x) * kClassifyTile; t0 < n; t0 += int64_t(gridDim.x) * kClassifyTile) {
+        int32_t id[kClassifyItems], slot[kClassifyItems];
+        int h = 0, m = 0;
+#pragma unroll
+        for (int q = 0; q < kClassifyItems; ++q) {
+            int64_t i = t0 + q * kBlock + threadIdx.x;
+            id[q] = -1;
+            slot[q] = -1;
+            if (i < n) {
+                id[q] = static_cast<int32_t>(ids[i]);
+                slot[q] = slot_of[id[q]];
+                if (slot[q] >= 0) ++h; else ++m;
+            }
+        }
+        int total;
+        int ex = block_excl_scan<kWavesPerBlock>(h | (m << 16), &total, lds);
+        if (threadIdx.x == 0) {
+            base[0] = atomicAdd(&counters[0], static_cast<unsigned long long>(total & 0xFFFF));
+            base[1] = atomicAdd(&counters[1], static_cast<unsigned long long>(total >> 16));
+        }
+        __syncthreads();
+        unsigned long long ph = base[0] + (ex & 0xFFFF), pm = base[1] + (ex >> 16);
+#pragma unroll
+        for (int q = 0; q < kClassifyItems; ++q) {
+            int i = static_cast<int>(t0 + q * kBlock + threadIdx.x);
+            if (slot[q] >= 0) hit_list[ph++] = make_int2(i, slot[q]);
+            else if (id[q] >= 0) miss_list[pm++] = make_int2(i, id[q]);
+        }
+        __syncthreads();                                // base[] is rewritten by the next tile
+    }
+}
+
+// Which rows to copy: entry r of a (output row, source row) list, or row ids[r] to output row r.
+struct ListRows {
+    const int2 *list;
+    __device__ __forceinline__ void get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
+        int2 e = list[r];
+        *src_row = e.y;
+        *dst_row = e.x;
+    }
+};
+template <typename IdxT>
+struct DirectRows {
+    const IdxT *ids;
+    __device__ __forceinline__ void get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
+        *src_row = static_cast<int64_t>(ids[r]);
+        *dst_row = r;
+    }
+};
+
+constexpr int kRowUnroll = 4;                            // row loads in flight per lane
+
+// Row copies by one wavefront.  Rows of up to 64 vectors: the wavefront is split into 64/LPR
+// groups of LPR lanes (LPR = 2^log2_lpr >= vecs), every group copies one row per step and
+// kRowUnroll steps are in flight, so a wavefront moves 4*64/LPR short rows at a time.  Longer
+// rows: all 64 lanes walk one row, four vectors per lane in flight.
+template <typename VecT, typename Rows>
+__device__ __forceinline__ void copy_rows(const Rows &rows, int64_t n, const char *__restrict__ src,
+                                          int64_t src_stride_bytes, char *__restrict__ dst,
+                                          int64_t dst_stride_bytes, int vecs, int log2_lpr) {
     const int lane = lane_id();
-    const int64_t stride = int64_t(gridDim.x) * kBlock;
-    // the loop bound is the same for every lane of a wavefront, so ballots see all 64 lanes
-    for (int64_t base = int64_t(blockIdx.x) * kBlock + (threadIdx.x & ~63); base < n; base += stride) {
-        int64_t i = base + lane;
-        bool valid = i < n;
-        int32_t id = 0, slot = -1;
-        if (valid) {
-            id = static_cast<int32_t>(ids[i]);
-            slot = slot_of[id];
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    if (vecs <= kWave) {
+        const int groups = kWave >> log2_lpr;
+        const int g = lane >> log2_lpr;
+        const int gl = lane & ((1 << log2_lpr) - 1);
+        const int64_t per_wave = int64_t(groups) * kRowUnroll;
+        for (int64_t base = wave0 * per_wave; base < n; base += nwaves * per_wave) {
+            const VecT *sp[kRowUnroll];
+            VecT *dp[kRowUnroll];
+            bool ok[kRowUnroll];
+            VecT v[kRowUnroll];
+#pragma unroll
+            for (int u = 0; u < kRowUnroll; ++u) {
+                const int64_t r = base + u * groups + g;
+                ok[u] = r < n && gl < vecs;
+                int64_t srow = 0, drow = 0;
+                if (r < n) rows.get(r, &srow, &drow);
+                sp[u] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes) + gl;
+                dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + gl;
+            }
+#pragma unroll
+            for (int u = 0; u < kRowUnroll; ++u)
+                if (ok[u]) v[u] = *sp[u];
+#pragma unroll
+            for (int u = 0; u < kRowUnroll; ++u)
+                if (ok[u]) *dp[u] = v[u];
         }
-        bool hit = valid && slot >= 0, miss = valid && slot < 0;
-        uint64_t mh = ballot64(hit), mm = ballot64(miss);
-        unsigned long long bh = 0, bm = 0;
-        if (lane == 0) {
-            if (mh) bh = atomicAdd(&counters[0], static_cast<unsigned long long>(popc64(mh)));
-            if (mm) bm = atomicAdd(&counters[1], static_cast<unsigned long long>(popc64(mm)));
+    } else {
+        for (int64_t r = wave0; r < n; r += nwaves) {
+            int64_t srow, drow;
+            rows.get(r, &srow, &drow);
+            const VecT *sp = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes);
+            VecT *dp = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes);
+            int c = lane;
+            for (; c + 3 * kWave < vecs; c += 4 * kWave) {
+                VecT a = sp[c], b = sp[c + kWave], d = sp[c + 2 * kWave], e = sp[c + 3 * kWave];
+                dp[c] = a;
+                dp[c + kWave] = b;
+                dp[c + 2 * kWave] = d;
+                dp[c + 3 * kWave] = e;
+            }
+            for (; c < vecs; c += kWave) dp[c] = sp[c];
         }
-        bh = __shfl(bh, 0, 64);
-        bm = __shfl(bm, 0, 64);
-        if (hit) hit_list[bh + popc64(mh & lanes_below(lane))] = make_int2(static_cast<int>(i), slot);
-        if (miss) miss_list[bm + popc64(mm & lanes_below(lane))] = make_int2(static_cast<int>(i), id);
     }
 }
 
-template <typename VecT>
-__device__ __forceinline__ void copy_row(const VecT *__restrict__ src, VecT *__restrict__ dst, int vecs, int lane) {
-    int c = lane;
-    for (; c + 3 * kWave < vecs; c += 4 * kWave) {          // four loads in flight per lane
-        VecT a = src[c], b = src[c + kWave], d = src[c + 2 * kWave], e = src[c + 3 * kWave];
-        dst[c] = a;
-        dst[c + kWave] = b;
-        dst[c + 2 * kWave] = d;
-        dst[c + 3 * kWave] = e;
-    }
-    for (; c < vecs; c += kWave) dst[c] = src[c];
-}
-
-// One wavefront per listed row; list entries are (output row, source row).
+// MISS only names the launch: 0 = rows from the HBM cache, 1 = rows from the feature matrix in
+// pinned host memory.  The code is the same; profiles tell the two apart by symbol.
 template <typename VecT, int MISS>
 __global__ void __launch_bounds__(kBlock)
 k_gather_rows(const int2 *__restrict__ list, const unsigned long long *__restrict__ count,
               const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
-              int64_t dst_stride_bytes, int vecs) {
+              int64_t dst_stride_bytes, int vecs, int log2_lpr) {
     const int64_t n = static_cast<int64_t>(*count);
-    const int lane = lane_id();
-    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
-    for (int64_t r = wave0; r < n; r += nwaves) {
-        int2 e = list[r];
-        copy_row(reinterpret_cast<const VecT *>(src + int64_t(e.y) * src_stride_bytes),
-                 reinterpret_cast<VecT *>(dst + int64_t(e.x) * dst_stride_bytes), vecs, lane);
-    }
+    copy_rows<VecT>(ListRows{list}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
 }
 
 template <typename VecT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_gather_direct(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
                 const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
-                int64_t dst_stride_bytes, int vecs) {
+                int64_t dst_stride_bytes, int vecs, int log2_lpr) {
     int64_t n = *num_ids;
     if (n > cap) n = cap;
-    const int lane = lane_id();
-    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
-    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
-    for (int64_t r = wave0; r < n; r += nwaves) {
-        int64_t id = static_cast<int64_t>(ids[r]);
-        copy_row(reinterpret_cast<const VecT *>(src + id * src_stride_bytes),
-                 reinterpret_cast<VecT *>(dst + r * dst_stride_bytes), vecs, lane);
-    }
+    copy_rows<VecT>(DirectRows<IdxT>{ids}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
 }
 
 // Widest power-of-two access (16, 8, 4 or 2 bytes) that keeps every row of both sides aligned.
@@ -120,44 +187,104 @@ int pick_vec_bytes(int64_t row_bytes, int64_t a_stride, int64_t b_stride, const 
     return 2;
 }
 
-int gather_grid(int64_t rows) {
-    // persistent-style grid: enough wavefronts to fill 256 CUs several times over
-    return static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows, kWavesPerBlock)), 256 * 16));
+// Bytes to move per row.  When both sides keep rows 16-byte aligned and have room for it, the row
+// is rounded up to whole 16-byte words so that 128-bit accesses can be used; the few bytes past
+// the row that are then copied come from the source row's own padding and land in the
+// destination row's own padding.
+int64_t copy_bytes(int64_t row_bytes, int64_t a_stride, int64_t b_stride, const void *a, const void *b) {
+    uint64_t bits = static_cast<uint64_t>(a_stride) | static_cast<uint64_t>(b_stride) |
+                    reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b);
+    int64_t r16 = (row_bytes + 15) & ~int64_t(15);
+    if ((bits & 15) == 0 && r16 <= a_stride && r16 <= b_stride) return r16;
+    return row_bytes;
+}
+
+// Geometry of a row-copy launch.
+struct RowGeom {
+    int vb;          // bytes per vector
+    int vecs;        // vectors per row
+    int log2_lpr;    // lanes per row group (rows of at most 64 vectors)
+    int64_t rows_per_wave;       // rows a wavefront has in flight
+    int64_t bytes_per_wave;      // bytes a wavefront has in flight
+};
+
+RowGeom row_geom(int64_t row_bytes, int64_t a_stride, int64_t b_stride, const void *a, const void *b) {
+    RowGeom g;
+    g.vb = pick_vec_bytes(row_bytes, a_stride, b_stride, a, b);
+    g.vecs = static_cast<int>(row_bytes / g.vb);
+    g.log2_lpr = 0;
+    while ((1 << g.log2_lpr) < g.vecs && g.log2_lpr < 6) ++g.log2_lpr;
+    if (g.vecs <= kWave) {
+        g.rows_per_wave = int64_t(kWave >> g.log2_lpr) * kRowUnroll;
+        g.bytes_per_wave = g.rows_per_wave * row_bytes;
+    } else {
+        g.rows_per_wave = 1;
+        g.bytes_per_wave = std::min<int64_t>(row_bytes, int64_t(4) * kWave * g.vb);
+    }
+    return g;
+}
+
+// HBM-side copies: enough wavefronts to cover the rows, capped at several per SIMD of 256 CUs.
+int hbm_grid(int64_t rows, const RowGeom &g) {
+    int64_t waves = ceil_div(rows, g.rows_per_wave);
+    return static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(waves, kWavesPerBlock)), 256 * 16));
+}
+
+// Host-link copies: only as many wavefronts as keep `inflight_bytes` of reads outstanding.  The
+// link is saturated by little more than a hundred kilobytes in flight; more only queues up in
+// the memory system in front of the HBM traffic of whatever runs beside this kernel.
+int link_grid(int64_t rows, const RowGeom &g, int64_t inflight_bytes) {
+    int64_t waves = std::max<int64_t>(1, ceil_div(inflight_bytes, g.bytes_per_wave));
+    int64_t blocks = ceil_div(waves, kWavesPerBlock);
+    return static_cast<int>(std::min<int64_t>(blocks, hbm_grid(rows, g)));
 }
 
 template <int MISS>
 int launch_rows(mqg_ctx *ctx, const char *name, const int2 *list, const unsigned long long *count, int64_t cap,
                 const void *src, int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes,
                 int64_t row_bytes, hipStream_t s) {
-    const int vb = pick_vec_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
-    const int vecs = static_cast<int>(row_bytes / vb);
-    const int grid = gather_grid(cap);
+    row_bytes = copy_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
+    const RowGeom g = row_geom(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
+    const int grid = MISS ? link_grid(cap, g, ctx->miss_inflight_bytes) : hbm_grid(cap, g);
     const char *sp = static_cast<const char *>(src);
     char *dp = static_cast<char *>(dst);
-    switch (vb) {
-        case 16: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint4, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        case 8: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint2, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        case 4: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint32_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        default: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint16_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
+    switch (g.vb) {
+        case 16: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint4, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        case 8: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint2, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        case 4: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint32_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        default: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint16_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
     }
     return MQG_OK;
 }
 
+// from_host: the source is host memory, so the launch is sized for the link
 template <typename IdxT>
 int launch_direct(mqg_ctx *ctx, const IdxT *ids, const int64_t *num_ids, int64_t cap, const void *src,
-                  int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes, hipStream_t s) {
-    const int vb = pick_vec_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
-    const int vecs = static_cast<int>(row_bytes / vb);
-    const int grid = gather_grid(cap);
+                  int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes, bool from_host,
+                  hipStream_t s) {
+    row_bytes = copy_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
+    const RowGeom g = row_geom(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
+    const int grid = from_host ? link_grid(cap, g, ctx->miss_inflight_bytes) : hbm_grid(cap, g);
     const char *sp = static_cast<const char *>(src);
     char *dp = static_cast<char *>(dst);
-    switch (vb) {
-        case 16: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint4, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        case 8: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint2, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        case 4: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint32_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
-        default: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint16_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, vecs))); break;
+    switch (g.vb) {
+        case 16: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint4, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        case 8: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint2, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        case 4: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint32_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        default: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint16_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
     }
     return MQG_OK;
+}
+
+// Is p host memory (as opposed to memory of a GPU)?  Unknown pointers count as host.
+bool is_host_memory(const void *p) {
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return true;
+    }
+    return attr.type != hipMemoryTypeDevice;
 }
 
 }  // namespace
@@ -166,7 +293,8 @@ int launch_direct(mqg_ctx *ctx, const IdxT *ids, const int64_t *num_ids, int64_t
 int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, int64_t cap, const void *src,
                       int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes,
                       hipStream_t s) {
-    return launch_direct<int32_t>(ctx, ids, num_ids, cap, src, src_stride_bytes, dst, dst_stride_bytes, row_bytes, s);
+    return launch_direct<int32_t>(ctx, ids, num_ids, cap, src, src_stride_bytes, dst, dst_stride_bytes, row_bytes,
+                                  is_host_memory(src), s);
 }
 
 int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids, const int64_t *num_ids,
@@ -179,19 +307,20 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
 
     if (!c->slot_of) {                                   // no cache: everything from feats
         int rc;
+        const bool from_host = is_host_memory(c->feats);
         if (idx_type == MQG_I64)
             rc = launch_direct<int64_t>(ctx, static_cast<const int64_t *>(ids), num_ids, cap_ids, c->feats,
-                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, s);
+                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
         else
             rc = launch_direct<int32_t>(ctx, static_cast<const int32_t *>(ids), num_ids, cap_ids, c->feats,
-                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, s);
+                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
         if (rc != MQG_OK) return rc;
         // every row counts as served from feats
         MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(counters, num_ids, cap_ids)));
         return MQG_OK;
     }
 
-    const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(cap_ids, kBlock)), 2048));
+    const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(cap_ids, kClassifyTile)), 1024));
     if (idx_type == MQG_I64)
         MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
     else

@@ -8,6 +8,9 @@
 //   k_row_offsets  indptr
 //   k_sample       one wavefront per destination: smallest-k random keys, neighbours written in
 //                  ascending adjacency slot, first-seen nodes marked in an N-bit bitmap
+//                  (destinations whose degree exceeds heavy_degree, listed by k_row_info, are
+//                  taken by whole workgroups in the same launch, so that a hub's key evaluation
+//                  is spread over four wavefronts instead of stretching the kernel's tail)
 //   k_bitmap_count / k_scan_tiles / k_bitmap_emit
 //                  popcount-rank the bitmap: new source nodes come out ascending by id, get their
 //                  position recorded in local_of[], the bitmap is cleared on the way
@@ -37,21 +40,24 @@ uint64_t host_mix64(uint64_t z) {
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_init_seeds(const IdxT *__restrict__ seeds, int num_seeds, int32_t *__restrict__ local_of,
-             int64_t *__restrict__ sizes_last) {
+             int64_t *__restrict__ sizes_last, int32_t *__restrict__ heavy_count) {
     int i = blockIdx.x * kBlock + threadIdx.x;
     if (i < num_seeds) local_of[seeds[i]] = i;
     if (i == 0) sizes_last[0] = num_seeds;
+    if (i < MQG_MAX_LAYERS) heavy_count[i] = 0;
 }
 
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const int64_t *__restrict__ sizes,
+k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const int64_t *sizes,
            IdxT *__restrict__ src_out, int fanout, int64_t *__restrict__ row_start,
-           int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *__restrict__ sizes_rw) {
+           int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *sizes_rw,
+           int heavy_degree, int32_t *__restrict__ heavy_rows, int32_t *__restrict__ heavy_count) {
     __shared__ int lds[kWavesPerBlock];
     const int64_t n = sizes[0];
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     int cnt = 0;
+    bool heavy = false;
     if (i < n) {
         IdxT v = dst[i];
         int64_t s = static_cast<int64_t>(row_ptr[v]);
@@ -60,6 +66,16 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
         row_deg[i] = static_cast<int32_t>(d);
         src_out[i] = v;
         cnt = d < fanout ? static_cast<int>(d) : fanout;
+        heavy = d > heavy_degree;
+    }
+    {   // list the hubs: one atomic per wavefront that has any
+        uint64_t m = ballot64(heavy);
+        if (m) {
+            int base = 0;
+            if (lane_id() == 0) base = atomicAdd(heavy_count, popc64(m));
+            base = __shfl(base, 0, 64);
+            if (heavy) heavy_rows[base + popc64(m & lanes_below(lane_id()))] = static_cast<int32_t>(i);
+        }
     }
     int w = wave_sum(cnt);
     if (lane_id() == 0) lds[threadIdx.x >> 6] = w;
@@ -129,6 +145,7 @@ struct SampleArgs {
     uint64_t layer_hash;      // mix(mix(rng_seed + golden) ^ block index)
     int fanout;
     int force_slow;
+    int heavy_degree;         // rows longer than this are sampled by whole workgroups
 };
 
 template <typename IdxT>
@@ -194,15 +211,96 @@ __device__ void select_by_repeated_min(const IdxT *__restrict__ col_idx, int64_t
     if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
 }
 
+// Hubs (degree > heavy_degree, listed by k_row_info): the four wavefronts of a workgroup share
+// one row.  Candidates under the threshold are appended to one LDS list in arrival order (an LDS
+// atomic per wavefront and chunk); the result does not depend on that order because the
+// candidates are ranked by (key, slot) and the k winners are then ordered by slot.
+template <typename IdxT>
+__device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, const SampleArgs &a,
+                            const int32_t *__restrict__ heavy_rows, int nheavy, int first, int step,
+                            uint64_t *ck, int32_t *cs, int32_t *sel_slot, int *cnt_s) {
+    const int tid = threadIdx.x;
+    const int lane = lane_id();
+    const int wave = tid >> 6;
+    const int k = a.fanout;
+    for (int h = first; h < nheavy; h += step) {
+        const int row = heavy_rows[h];
+        const int64_t start = a.row_start[row];
+        const int d = a.row_deg[row];
+        const int32_t out_base = a.indptr[row];
+        const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
+        if (tid == 0) *cnt_s = 0;
+        __syncthreads();
+        const int expect = 2 * k + 32;
+        uint64_t thr = kMaxKey;
+        if (d > expect) thr = static_cast<uint64_t>((double(expect) / double(d)) * 18446744073709551616.0);
+        for (int base = wave * kWave; base < d; base += kBlock) {
+            int j = base + lane;
+            uint64_t key = mix64(hv ^ uint64_t(j));
+            bool c = j < d && key <= thr;
+            uint64_t m = ballot64(c);
+            if (m) {
+                int p0 = 0;
+                if (lane == 0) p0 = atomicAdd(cnt_s, popc64(m));
+                p0 = __shfl(p0, 0, 64);
+                if (c) {
+                    int p = p0 + popc64(m & lanes_below(lane));
+                    if (p < kCandidates) {
+                        ck[p] = key;
+                        cs[p] = j;
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int cnt = *cnt_s;
+        if (cnt < k || cnt > kCandidates) {                // workgroup-uniform; practically never
+            if (wave == 0) select_by_repeated_min(col_idx, start, d, k, hv, out_base, a);
+            __syncthreads();
+            continue;
+        }
+        if (tid < cnt) {                                   // kCandidates == workgroup size
+            const uint64_t my_key = ck[tid];
+            const int my_slot = cs[tid];
+            int rank = 0;
+            for (int t = 0; t < cnt; ++t) rank += pair_less(ck[t], cs[t], my_key, my_slot) ? 1 : 0;
+            if (rank < k) sel_slot[rank] = my_slot;
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int my_slot = lane < k ? sel_slot[lane] : 0x7FFFFFFF;
+            int rank = 0;
+            for (int t = 0; t < k; ++t) {
+                int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
+                rank += (other < my_slot) ? 1 : 0;
+            }
+            if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
+        }
+        __syncthreads();                                   // LDS is reused by the next row
+    }
+}
+
+static_assert(kCandidates == kBlock, "hub ranking uses one thread per candidate");
+
+// The first hub_blocks workgroups take the hubs (they are dispatched first and run the longest);
+// every other workgroup gives each of its four wavefronts one destination.
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, SampleArgs a) {
+k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, SampleArgs a,
+         const int32_t *__restrict__ heavy_rows, const int32_t *__restrict__ heavy_count, int hub_blocks) {
     __shared__ uint64_t cand_key[kWavesPerBlock][kCandidates];
     __shared__ int32_t cand_slot[kWavesPerBlock][kCandidates];
+    __shared__ int32_t sel_slot[kWave];
+    __shared__ int cnt_s;
+    if (static_cast<int>(blockIdx.x) < hub_blocks) {
+        sample_hubs(col_idx, dst_ids, a, heavy_rows, *heavy_count, static_cast<int>(blockIdx.x), hub_blocks,
+                    cand_key[0], cand_slot[0], sel_slot, &cnt_s);
+        return;
+    }
     const int lane = lane_id();
     const int wave = static_cast<int>(threadIdx.x) >> 6;
     const int64_t n = a.sizes[0];
-    const int64_t row = int64_t(blockIdx.x) * kWavesPerBlock + wave;
+    const int64_t row = (int64_t(blockIdx.x) - hub_blocks) * kWavesPerBlock + wave;
     if (row >= n) return;                                  // whole wavefront leaves together
 
     const int64_t start = a.row_start[row];
@@ -214,6 +312,7 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
         if (lane < d) emit_neighbour(col_idx, start, lane, out_base + lane, a);
         return;
     }
+    if (d > a.heavy_degree) return;                        // a hub: sampled by the first workgroups
     const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
     if (a.force_slow) {
         select_by_repeated_min(col_idx, start, d, k, hv, out_base, a);
@@ -356,7 +455,7 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     {
         int grid = static_cast<int>(std::max<int64_t>(1, ceil_div(num_seeds, kBlock)));
         MQG_LAUNCH(ctx, "k_init_seeds", s,
-                   (k_init_seeds<IdxT><<<grid, kBlock, 0, s>>>(seeds, num_seeds, ctx->local_of, blocks[L - 1].sizes)));
+                   (k_init_seeds<IdxT><<<grid, kBlock, 0, s>>>(seeds, num_seeds, ctx->local_of, blocks[L - 1].sizes, ctx->heavy_count)));
     }
     int64_t need_dst = num_seeds;
     const int bitmap_tiles = static_cast<int>(ctx->bitmap_words / kBitmapTileWords);
@@ -368,9 +467,11 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         const int64_t need_nnz = need_dst * k;
         const int row_tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)));
 
+        const int heavy_degree = ctx->force_slow_select ? 0x7FFFFFFF : ctx->heavy_degree;
         MQG_LAUNCH(ctx, "k_row_info", s,
                    (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
-                                                                          ctx->row_deg, ctx->tile_vals, b.sizes)));
+                                                                          ctx->row_deg, ctx->tile_vals, b.sizes, heavy_degree,
+                                                                          ctx->heavy_rows, ctx->heavy_count + l)));
         int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
         if (rc != MQG_OK) return rc;
         MQG_LAUNCH(ctx, "k_row_offsets", s,
@@ -387,8 +488,11 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         a.layer_hash = host_mix64(seed_hash ^ uint64_t(l));
         a.fanout = k;
         a.force_slow = ctx->force_slow_select ? 1 : 0;
-        int sample_grid = static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kWavesPerBlock)));
-        MQG_LAUNCH(ctx, "k_sample", s, (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a)));
+        a.heavy_degree = heavy_degree;
+        const int hub_blocks = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, need_dst), 512));
+        int sample_grid = hub_blocks + static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kWavesPerBlock)));
+        MQG_LAUNCH(ctx, "k_sample", s,
+                   (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
 
         MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<<<std::max(1, bitmap_tiles), kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
         // num_src = num_dst + number of new nodes; it is also the next block's num_dst
