@@ -1,0 +1,168 @@
+"""The five workloads at their full sizes, in the launch configuration bench.py times
+(three mini-batches in flight on three streams, one context each).
+
+Blocks and gathered rows are compared with the oracle element by element (the oracle only
+touches a batch's sampled neighbourhood, so it stays affordable at any graph size); the cache
+tables are checked through properties that hold at any size (and against the oracle where a full
+CPU sort is cheap); aggregation is checked on sampled destination rows.
+"""
+import gc
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_04707_amd import synth
+from gpu_util import agg_tolerance_ok
+
+pytestmark = pytest.mark.gpu
+
+IN_FLIGHT = 3
+TOL = {torch.float32: 1e-5, torch.float16: 2e-3}
+
+
+@pytest.fixture(scope="module")
+def mqg():
+    from paper_2601_04707_amd import mqg as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def check_cache_properties(rp, cache, num_cached):
+    """Any size: slots are a partial bijection, ranked by (degree desc, id asc), and no uncached
+    node outranks the last cached one."""
+    n = rp.numel() - 1
+    deg = (rp[1:] - rp[:-1]).to(torch.int64)
+    ids = cache.cached_ids[:num_cached].to(torch.int64)
+    slot_of = cache.slot_of[:n].to(torch.int64)
+    assert int((slot_of >= 0).sum()) == num_cached
+    if num_cached == 0:
+        return
+    assert torch.equal(slot_of[ids], torch.arange(num_cached, device=ids.device))
+    d = deg[ids]
+    dd, di = d[1:] - d[:-1], ids[1:] - ids[:-1]
+    assert bool(((dd < 0) | ((dd == 0) & (di > 0))).all())
+    last_deg, last_id = int(d[-1]), int(ids[-1])
+    unc = slot_of < 0
+    node = torch.arange(n, device=ids.device)
+    assert not bool((unc & ((deg > last_deg) | ((deg == last_deg) & (node < last_id)))).any())
+
+
+def check_block_properties(blocks, l, dst, rp, ci, fanout):
+    """Structural invariants of one block, computed with torch on the GPU."""
+    nd, ns, nnz, flags = [int(x) for x in blocks.sizes[l].tolist()]
+    assert flags == 0 and nd == dst.numel()
+    src = blocks.src_ids[l][:ns].to(torch.int64)
+    indptr = blocks.indptr[l][:nd + 1].to(torch.int64)
+    indices = blocks.indices[l][:nnz].to(torch.int64)
+    assert torch.equal(src[:nd], dst.to(torch.int64))
+    new = src[nd:]
+    assert bool((new[1:] > new[:-1]).all())
+    assert torch.unique(src).numel() == ns
+    deg = (rp[dst.to(torch.int64) + 1] - rp[dst.to(torch.int64)]).to(torch.int64)
+    assert torch.equal(indptr[1:] - indptr[:-1], torch.clamp(deg, max=fanout))
+    assert int(indptr[-1]) == nnz and int(indices.max()) < ns and int(indices.min()) >= 0
+    # every new node is referenced by some edge
+    seen = torch.zeros(ns, dtype=torch.bool, device=src.device)
+    seen[indices] = True
+    assert bool(seen[nd:].all())
+    return src
+
+
+@pytest.mark.parametrize("name", ["medium", "large", "stress", "xlarge"])
+def test_full_size_workload(mqg, name):
+    w = synth.WORKLOADS[name]
+    dev = "cuda"
+    rp, ci = synth.build_graph(w, seed=0, device=dev)
+    n = rp.numel() - 1
+    assert n == w.num_nodes and ci.numel() > 0.9 * w.target_edges
+    feats = torch.empty((n, w.dim), dtype=w.feat_dtype).pin_memory()
+    synth.node_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev, out=feats)
+    torch.cuda.synchronize()
+    g = mqg.Graph(rp, ci)
+    L = len(w.fanouts)
+    ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(IN_FLIGHT)]
+    blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(IN_FLIGHT)]
+    streams = [torch.cuda.Stream() for _ in range(IN_FLIGHT)]
+    num_cached = n * w.cache_pct // 100
+    cache = mqg.Cache(g, feats, num_cached)
+    mqg.mqg_build_cache(ctxs[0], g, cache)
+    torch.cuda.synchronize()
+    check_cache_properties(rp, cache, num_cached)
+
+    batches = synth.seed_batches(n, w.batch, IN_FLIGHT, seed=2, train_fraction=w.train_fraction)
+    seeds_dev = [b.to(g.idx_dtype).to(dev) for b in batches]
+    bounds = blks[0].bounds
+    x0 = [torch.zeros((bounds[0][1], w.dim), dtype=w.feat_dtype, device=dev) for _ in range(IN_FLIGHT)]
+    hs = [[torch.zeros((bounds[l][0], w.dim), dtype=w.feat_dtype, device=dev) for l in range(L)]
+          for _ in range(IN_FLIGHT)]
+    stats = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(IN_FLIGHT)]
+    torch.cuda.synchronize()
+    for j in range(IN_FLIGHT):                                  # all three in flight, as in bench.py
+        s = streams[j]
+        mqg.mqg_sample_blocks(ctxs[j], g, seeds_dev[j], w.fanouts, 3 + j, blks[j], stream=s)
+        mqg.mqg_gather_features(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s)
+        x = x0[j]
+        for l in range(L):
+            mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s)
+            x = hs[j][l]
+    torch.cuda.synchronize()
+
+    # --- properties of every batch (GPU side, any size)
+    for j in range(IN_FLIGHT):
+        dst = seeds_dev[j]
+        for l in range(L - 1, -1, -1):
+            dst = check_block_properties(blks[j], l, dst, rp, ci, w.fanouts[l])
+        ns = int(blks[j].sizes[0, 1])
+        hits = int((cache.slot_of[blks[j].src_ids[0][:ns].to(torch.int64)] >= 0).sum())
+        assert stats[j].tolist() == [hits, ns - hits]
+
+    # --- element-by-element against the oracle
+    rp_np = rp.cpu().numpy().astype(np.int64)
+    ci_np = ci.cpu().numpy()
+    if ci_np.dtype != np.int64:
+        ci_np = ci_np.astype(np.int64)
+    feats_np = feats.numpy()
+    if n <= 3_000_000:                                          # a full CPU sort is cheap here
+        oc = oracle.build_cache(rp_np, num_cached)
+        assert np.array_equal(cache.slot_of.cpu().numpy(), oc.slot_of)
+        assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), oc.cached_ids)
+    sample_ids = torch.randint(0, max(1, num_cached), (4096,), generator=torch.Generator().manual_seed(0))
+    if num_cached:
+        ids = cache.cached_ids[sample_ids.to(dev)].cpu().numpy()
+        assert cache.cache_rows[sample_ids.to(dev)].cpu().numpy().tobytes() == feats_np[ids].tobytes()
+
+    full = range(IN_FLIGHT) if name != "stress" else [1]        # the 8,192-seed batches are slow on one CPU thread
+    for j in full:
+        want = oracle.sample_blocks(rp_np, ci_np, batches[j].numpy(), w.fanouts, 3 + j)
+        sizes = blks[j].host_sizes()
+        for l, wb in enumerate(want):
+            nd, ns, nnz, _ = sizes[l]
+            assert (nd, ns, nnz) == (wb.num_dst, wb.num_src, wb.nnz), (name, j, l)
+            assert np.array_equal(blks[j].src_ids[l][:ns].cpu().numpy(), wb.src_ids)
+            assert np.array_equal(blks[j].indptr[l][:nd + 1].cpu().numpy(), wb.indptr)
+            assert np.array_equal(blks[j].indices[l][:nnz].cpu().numpy(), wb.indices)
+        ns = want[0].num_src
+        assert x0[j][:ns].cpu().numpy().tobytes() == feats_np[want[0].src_ids].tobytes()
+
+        # aggregation on sampled destination rows, each layer fed with the GPU's own input
+        rng = np.random.default_rng(j)
+        x_in = x0[j]
+        for l in range(L):
+            wb = want[l]
+            rows = np.unique(rng.integers(0, wb.num_dst, 1500))
+            counts = (wb.indptr[rows + 1] - wb.indptr[rows]).astype(np.int64)
+            sub_ptr = np.concatenate([[0], np.cumsum(counts)])
+            sub_idx = np.concatenate([wb.indices[wb.indptr[r]:wb.indptr[r + 1]] for r in rows]) if len(rows) else np.zeros(0, np.int32)
+            used, inv = np.unique(sub_idx, return_inverse=True)
+            x_used = x_in[torch.from_numpy(used.astype(np.int64)).to(dev)].cpu().numpy()
+            ref = oracle.mean_aggregate(sub_ptr, inv.astype(np.int32), x_used)
+            got = hs[j][l][torch.from_numpy(rows).to(dev)].cpu().numpy()
+            ok, worst = agg_tolerance_ok(got, ref, float(np.abs(x_used.astype(np.float64)).mean()), TOL[w.feat_dtype])
+            assert ok, (name, j, l, worst)
+            x_in = hs[j][l]
+
+    del ctxs, blks, cache, x0, hs, g, rp, ci, feats
+    gc.collect()
+    torch.cuda.empty_cache()
