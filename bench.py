@@ -139,12 +139,14 @@ def main() -> int:
     edges_per_s = edges / elapsed
     gather_bytes = rows * row_bytes
 
-    # ---------------------------------------------------------------- per-kernel durations (HIP events on the launch stream)
+    # ---------------------------------------------------------------- per-kernel durations
+    # HIP events on the launch stream around every kernel (MQG_OPT_PROFILE), one mini-batch at a
+    # time so that a kernel's duration is its own and not that of whatever overlaps it.
     for c in ctxs:
         c.set_option(mqg.MQG_OPT_PROFILE, 1)
     for i in range(W, W + K):
         step(i)
-    torch.cuda.synchronize()
+        torch.cuda.synchronize()
     kernels = {}
     for c in ctxs:
         for name in c.kernel_names():
@@ -155,6 +157,17 @@ def main() -> int:
         c.set_option(mqg.MQG_OPT_PROFILE, 0)
     kern = {k: {"launches": v[1], "avg_us": round(v[0] / max(v[1], 1) * 1e3, 3),
                 "us_per_step": round(v[0] / K * 1e3, 3)} for k, v in sorted(kernels.items())}
+
+    def pmc_traffic(kernel):
+        """HBM bytes per launch from the committed rocprofv3 FETCH_SIZE/WRITE_SIZE summary, if it
+        covers this workload (lines `traffic <workload> <kernel> <bytes>` in profiles/*.md)."""
+        import glob
+        for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "*.md"))):
+            for line in open(path):
+                f = line.split()
+                if len(f) == 4 and f[0] == "traffic" and f[1] == w.name and f[2] == kernel:
+                    return int(f[3])
+        return None
 
     def roof(name, bytes_per_launch, peak, traffic=None):
         if name not in kernels or kernels[name][1] == 0:
@@ -167,11 +180,12 @@ def main() -> int:
 
     if cache_pct is None:
         # direct gather: row read + row written + the id
-        roofline = roof("k_gather_direct", rows / K * (2 * row_bytes + ci.element_size()), HBM_PEAK_GBPS)
+        roofline = roof("k_gather_direct", rows / K * (2 * row_bytes + ci.element_size()), HBM_PEAK_GBPS,
+                        pmc_traffic("k_gather_direct"))
         host_link = None
     else:
         # hit gather: row read from the HBM cache + row written + the 8-byte (row, slot) list entry
-        roofline = roof("k_gather_hit", hits / K * (2 * row_bytes + 8), HBM_PEAK_GBPS)
+        roofline = roof("k_gather_hit", hits / K * (2 * row_bytes + 8), HBM_PEAK_GBPS, pmc_traffic("k_gather_hit"))
         host_link = roof("k_gather_miss", misses / K * row_bytes, HOST_LINK_PEAK_GBPS)
         if host_link:
             host_link["bound"] = "host-link"
@@ -209,6 +223,28 @@ def main() -> int:
                "sample": f"first {done} of the {K} timed mini-batches, whole path (sample+gather+aggregate), "
                          f"{t_cpu:.1f} s; host has {os.cpu_count()} logical cores"}
 
+    # ---------------------------------------------------------------- what plain copies reach on this machine (context)
+    def timed(fn, reps=5):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e-3
+    ca = torch.ones(1 << 27, dtype=torch.float32, device=dev)          # 512 MiB
+    cb = torch.empty_like(ca)
+    t_copy = timed(lambda: torch.mul(ca, 2.0, out=cb))
+    nb = min(feats.numel() * feats.element_size(), 1 << 29)
+    hsrc = feats.view(-1)[: nb // feats.element_size()]
+    hdst = torch.empty_like(hsrc, device=dev)
+    t_h2d = timed(lambda: hdst.copy_(hsrc, non_blocking=True))
+    measured = {"hbm_read_plus_write_GBps": round(2 * ca.numel() * 4 / t_copy / 1e9, 1),
+                "pinned_host_to_device_GBps": round(nb / t_h2d / 1e9, 1)}
+    del ca, cb, hdst
+
     if args.pmc_copy:
         a = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         b = torch.empty_like(a)
@@ -236,6 +272,7 @@ def main() -> int:
         "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1)},
         "roofline": roofline,
         "roofline_host_link": host_link,
+        "measured_plain_copies": measured,
         "cpu_baseline": cpu,
         "kernels": kern,
         "build_cache_ms": round(build_cache_ms, 2),

@@ -145,6 +145,7 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const i
     if (ok) ok = hipMemset(c->local_of, 0xFF, std::max<int64_t>(c->num_nodes, 1) * sizeof(int32_t)) == hipSuccess;
     if (ok) ok = hipMemset(c->bitmap, 0, std::max<int64_t>(c->bitmap_words, 1) * sizeof(uint32_t)) == hipSuccess;
     if (ok) ok = hipMemset(c->counters, 0, 8 * sizeof(unsigned long long)) == hipSuccess;
+    if (ok) ok = hipMemset(c->heavy_count, 0, MQG_MAX_LAYERS * sizeof(int32_t)) == hipSuccess;
     if (ok) ok = hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         std::string msg = std::string("mqg_ctx_create: scratch allocation failed: ") + hipGetErrorString(hipGetLastError());

@@ -48,7 +48,8 @@ struct mqg_ctx {
     int32_t *heavy_count = nullptr;      // [MQG_MAX_LAYERS] their number, per block
     int2 *hit_list = nullptr;            // [max_src] (output row, cache slot)
     int2 *miss_list = nullptr;           // [max_src] (output row, node id)
-    unsigned long long *counters = nullptr;  // [8] gather hit/miss counters when the caller wants none
+    unsigned long long *counters = nullptr;  // [8] two alternating (hits, misses) pairs: a gather uses one and clears the other
+    uint64_t gather_calls = 0;
 
     // options
     bool force_slow_select = false;

@@ -18,17 +18,12 @@ namespace mqg {
 
 namespace {
 
-__global__ void k_fill_u64(unsigned long long *p, int n, unsigned long long v) {
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
-}
-
-__global__ void k_direct_stats(unsigned long long *counters, const int64_t *num_ids, int64_t cap) {
+__global__ void k_direct_stats(int64_t *stats, const int64_t *num_ids, int64_t cap) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         int64_t n = *num_ids;
         if (n > cap) n = cap;
-        counters[0] = 0;
-        counters[1] = static_cast<unsigned long long>(n < 0 ? 0 : n);
+        stats[0] = 0;
+        stats[1] = n < 0 ? 0 : n;
     }
 }
 
@@ -44,9 +39,10 @@ template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
            const int32_t *__restrict__ slot_of, int2 *__restrict__ hit_list, int2 *__restrict__ miss_list,
-           unsigned long long *__restrict__ counters) {
+           unsigned long long *__restrict__ counters, unsigned long long *__restrict__ next_counters) {
     __shared__ int lds[kWavesPerBlock];
     __shared__ unsigned long long base[2];
+    if (blockIdx.x == 0 && threadIdx.x < 2) next_counters[threadIdx.x] = 0;   // the pair the next gather counts in
     int64_t n = *num_ids;
     if (n > cap) n = cap;
     for (int64_t t0 = int64_t(blockIdx.x) * kClassifyTile; t0 < n; t0 += int64_t(gridDim.x) * kClassifyTile) {
@@ -163,7 +159,9 @@ template <typename VecT, int MISS>
 __global__ void __launch_bounds__(kBlock)
 k_gather_rows(const int2 *__restrict__ list, const unsigned long long *__restrict__ count,
               const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
-              int64_t dst_stride_bytes, int vecs, int log2_lpr) {
+              int64_t dst_stride_bytes, int vecs, int log2_lpr, int64_t *__restrict__ stats,
+              const unsigned long long *__restrict__ counters) {
+    if (stats && blockIdx.x == 0 && threadIdx.x < 2) stats[threadIdx.x] = static_cast<int64_t>(counters[threadIdx.x]);
     const int64_t n = static_cast<int64_t>(*count);
     copy_rows<VecT>(ListRows{list}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
 }
@@ -242,17 +240,17 @@ int link_grid(int64_t rows, const RowGeom &g, int64_t inflight_bytes) {
 template <int MISS>
 int launch_rows(mqg_ctx *ctx, const char *name, const int2 *list, const unsigned long long *count, int64_t cap,
                 const void *src, int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes,
-                int64_t row_bytes, hipStream_t s) {
+                int64_t row_bytes, int64_t *stats, const unsigned long long *counters, hipStream_t s) {
     row_bytes = copy_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
     const RowGeom g = row_geom(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
     const int grid = MISS ? link_grid(cap, g, ctx->miss_inflight_bytes) : hbm_grid(cap, g);
     const char *sp = static_cast<const char *>(src);
     char *dp = static_cast<char *>(dst);
     switch (g.vb) {
-        case 16: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint4, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
-        case 8: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint2, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
-        case 4: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint32_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
-        default: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint16_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr))); break;
+        case 16: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint4, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters))); break;
+        case 8: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint2, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters))); break;
+        case 4: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint32_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters))); break;
+        default: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint16_t, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters))); break;
     }
     return MQG_OK;
 }
@@ -301,9 +299,10 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
                int64_t cap_ids, void *out, int64_t out_stride, int64_t *stats, hipStream_t s) {
     const int64_t elt = c->dtype == MQG_F16 ? 2 : 4;
     const int64_t row_bytes = int64_t(c->dim) * elt;
-    unsigned long long *counters = stats ? reinterpret_cast<unsigned long long *>(stats) : ctx->counters;
-    MQG_LAUNCH(ctx, "k_fill_u64", s, (k_fill_u64<<<1, 64, 0, s>>>(counters, 2, 0ull)));
-    if (cap_ids == 0) return MQG_OK;
+    if (cap_ids == 0) {
+        if (stats) MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, 0)));
+        return MQG_OK;
+    }
 
     if (!c->slot_of) {                                   // no cache: everything from feats
         int rc;
@@ -316,21 +315,25 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
                                         c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
         if (rc != MQG_OK) return rc;
         // every row counts as served from feats
-        MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(counters, num_ids, cap_ids)));
+        if (stats) MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, cap_ids)));
         return MQG_OK;
     }
 
+    // two (hits, misses) counter pairs take turns: this call counts in one and clears the other
+    unsigned long long *counters = ctx->counters + 2 * (ctx->gather_calls & 1);
+    unsigned long long *next_counters = ctx->counters + 2 * ((ctx->gather_calls + 1) & 1);
+    ctx->gather_calls++;
     const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(cap_ids, kClassifyTile)), 1024));
     if (idx_type == MQG_I64)
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters, next_counters)));
     else
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters, next_counters)));
 
     int rc = launch_rows<0>(ctx, "k_gather_hit", ctx->hit_list, &counters[0], cap_ids, c->cache_rows,
-                            c->cache_stride * elt, out, out_stride * elt, row_bytes, s);
+                            c->cache_stride * elt, out, out_stride * elt, row_bytes, stats, counters, s);
     if (rc != MQG_OK) return rc;
     return launch_rows<1>(ctx, "k_gather_miss", ctx->miss_list, &counters[1], cap_ids, c->feats,
-                          c->feat_stride * elt, out, out_stride * elt, row_bytes, s);
+                          c->feat_stride * elt, out, out_stride * elt, row_bytes, nullptr, counters, s);
 }
 
 }  // namespace mqg

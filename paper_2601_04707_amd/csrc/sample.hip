@@ -37,29 +37,23 @@ uint64_t host_mix64(uint64_t z) {
 
 // ------------------------------------------------------------------------------------------
 
-template <typename IdxT>
-__global__ void __launch_bounds__(kBlock)
-k_init_seeds(const IdxT *__restrict__ seeds, int num_seeds, int32_t *__restrict__ local_of,
-             int64_t *__restrict__ sizes_last, int32_t *__restrict__ heavy_count) {
-    int i = blockIdx.x * kBlock + threadIdx.x;
-    if (i < num_seeds) local_of[seeds[i]] = i;
-    if (i == 0) sizes_last[0] = num_seeds;
-    if (i < MQG_MAX_LAYERS) heavy_count[i] = 0;
-}
-
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const int64_t *sizes,
            IdxT *__restrict__ src_out, int fanout, int64_t *__restrict__ row_start,
            int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *sizes_rw,
-           int heavy_degree, int32_t *__restrict__ heavy_rows, int32_t *__restrict__ heavy_count) {
+           int heavy_degree, int32_t *__restrict__ heavy_rows, int32_t *__restrict__ heavy_count,
+           int64_t n_seeds, int32_t *__restrict__ local_of) {
     __shared__ int lds[kWavesPerBlock];
-    const int64_t n = sizes[0];
+    // innermost block (n_seeds >= 0): the destinations are the caller's seeds; their number comes
+    // from the host and their positions are entered into local_of here
+    const int64_t n = n_seeds >= 0 ? n_seeds : sizes[0];
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     int cnt = 0;
     bool heavy = false;
     if (i < n) {
         IdxT v = dst[i];
+        if (n_seeds >= 0) local_of[v] = static_cast<int32_t>(i);
         int64_t s = static_cast<int64_t>(row_ptr[v]);
         int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - s;
         row_start[i] = s;
@@ -85,7 +79,10 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
 #pragma unroll
         for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
         tile_sums[blockIdx.x] = t;
-        if (blockIdx.x == 0) sizes_rw[3] = 0;
+        if (blockIdx.x == 0) {
+            sizes_rw[3] = 0;
+            if (n_seeds >= 0) sizes_rw[0] = n_seeds;
+        }
     }
 }
 
@@ -160,6 +157,38 @@ __device__ __forceinline__ void emit_neighbour(const IdxT *__restrict__ col_idx,
     }
 }
 
+// key(j) = mix64(hv ^ j) for the slots j of one row, with everything that depends only on the row
+// hoisted out: j < 2^31 touches only the low word of hv ^ j, so the high word after the first
+// xor-shift and its share of the first multiply are per-row constants.  Written on 32-bit halves
+// (funnel shifts are one v_alignbit each): 5 multiplies per key instead of 6.
+struct RowKeys {
+    static constexpr uint32_t kC1Lo = 0x1CE4E5B9u, kC1Hi = 0xBF58476Du;
+    static constexpr uint32_t kC2Lo = 0x133111EBu, kC2Hi = 0x94D049BBu;
+    uint32_t lo, hi_shl2, a_hi, c1_term;
+    __device__ __forceinline__ explicit RowKeys(uint64_t hv) {
+        const uint32_t hi = static_cast<uint32_t>(hv >> 32);
+        lo = static_cast<uint32_t>(hv);
+        hi_shl2 = hi << 2;
+        a_hi = hi ^ (hi >> 30);
+        c1_term = a_hi * kC1Lo;
+    }
+    __device__ __forceinline__ uint64_t operator()(int j) const {
+        const uint32_t lo0 = lo ^ static_cast<uint32_t>(j);
+        const uint32_t a_lo = lo0 ^ (hi_shl2 | (lo0 >> 30));                       // z ^= z >> 30
+        const uint64_t p = static_cast<uint64_t>(a_lo) * kC1Lo;                      // z *= C1
+        const uint32_t b_lo = static_cast<uint32_t>(p);
+        const uint32_t b_hi = static_cast<uint32_t>(p >> 32) + a_lo * kC1Hi + c1_term;
+        const uint32_t c_lo = b_lo ^ __builtin_amdgcn_alignbit(b_hi, b_lo, 27);      // z ^= z >> 27
+        const uint32_t c_hi = b_hi ^ (b_hi >> 27);
+        const uint64_t q = static_cast<uint64_t>(c_lo) * kC2Lo;                      // z *= C2
+        const uint32_t d_lo = static_cast<uint32_t>(q);
+        const uint32_t d_hi = static_cast<uint32_t>(q >> 32) + c_lo * kC2Hi + c_hi * kC2Lo;
+        const uint32_t e_lo = d_lo ^ __builtin_amdgcn_alignbit(d_hi, d_lo, 31);      // z ^= z >> 31
+        const uint32_t e_hi = d_hi ^ (d_hi >> 31);
+        return (static_cast<uint64_t>(e_hi) << 32) | e_lo;
+    }
+};
+
 // lexicographic (key, slot) order
 __device__ __forceinline__ bool pair_less(uint64_t ka, int sa, uint64_t kb, int sb) {
     return ka < kb || (ka == kb && sa < sb);
@@ -172,6 +201,7 @@ template <typename IdxT>
 __device__ void select_by_repeated_min(const IdxT *__restrict__ col_idx, int64_t start, int d, int k,
                                        uint64_t hv, int32_t out_base, const SampleArgs &a) {
     const int lane = lane_id();
+    const RowKeys key_of(hv);
     uint64_t prev_key = 0;
     int prev_slot = -1;
     int my_slot = -1;                                // lane r keeps the r-th selected slot
@@ -181,7 +211,7 @@ __device__ void select_by_repeated_min(const IdxT *__restrict__ col_idx, int64_t
         for (int base = 0; base < d; base += kWave) {
             int j = base + lane;
             if (j < d) {
-                uint64_t key = mix64(hv ^ uint64_t(j));
+                uint64_t key = key_of(j);
                 bool above = (r == 0) || pair_less(prev_key, prev_slot, key, j);
                 if (above && pair_less(key, j, best_key, best_slot)) {
                     best_key = key;
@@ -229,6 +259,7 @@ __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__rest
         const int d = a.row_deg[row];
         const int32_t out_base = a.indptr[row];
         const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
+        const RowKeys key_of(hv);
         if (tid == 0) *cnt_s = 0;
         __syncthreads();
         const int expect = 2 * k + 32;
@@ -236,7 +267,7 @@ __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__rest
         if (d > expect) thr = static_cast<uint64_t>((double(expect) / double(d)) * 18446744073709551616.0);
         for (int base = wave * kWave; base < d; base += kBlock) {
             int j = base + lane;
-            uint64_t key = mix64(hv ^ uint64_t(j));
+            uint64_t key = key_of(j);
             bool c = j < d && key <= thr;
             uint64_t m = ballot64(c);
             if (m) {
@@ -320,7 +351,7 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
     }
     if (d <= kWave) {
         // one key per lane; rank every key against all others
-        uint64_t key = lane < d ? mix64(hv ^ uint64_t(lane)) : kMaxKey;
+        uint64_t key = lane < d ? RowKeys(hv)(lane) : kMaxKey;
         int rank = 0;
         for (int t = 0; t < d; ++t) {
             uint64_t other = readlane64(key, t);
@@ -340,9 +371,10 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
     uint64_t thr = kMaxKey;
     if (d > expect) thr = static_cast<uint64_t>((double(expect) / double(d)) * 18446744073709551616.0);
     int cnt = 0;
+    const RowKeys key_of(hv);
     for (int base = 0; base < d; base += kWave) {
         int j = base + lane;
-        uint64_t key = mix64(hv ^ uint64_t(j));
+        uint64_t key = key_of(j);
         bool c = j < d && key <= thr;
         uint64_t m = ballot64(c);
         if (c) {
@@ -436,7 +468,9 @@ k_relabel(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes,
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of) {
+k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of,
+              int32_t *__restrict__ heavy_count) {
+    if (blockIdx.x == 0 && threadIdx.x < MQG_MAX_LAYERS) heavy_count[threadIdx.x] = 0;   // for the next call
     const int64_t n = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
     for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
@@ -452,11 +486,6 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     int32_t *nbr = static_cast<int32_t *>(ctx->nbr);
     const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
 
-    {
-        int grid = static_cast<int>(std::max<int64_t>(1, ceil_div(num_seeds, kBlock)));
-        MQG_LAUNCH(ctx, "k_init_seeds", s,
-                   (k_init_seeds<IdxT><<<grid, kBlock, 0, s>>>(seeds, num_seeds, ctx->local_of, blocks[L - 1].sizes, ctx->heavy_count)));
-    }
     int64_t need_dst = num_seeds;
     const int bitmap_tiles = static_cast<int>(ctx->bitmap_words / kBitmapTileWords);
     for (int l = L - 1; l >= 0; --l) {
@@ -471,7 +500,8 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         MQG_LAUNCH(ctx, "k_row_info", s,
                    (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
                                                                           ctx->row_deg, ctx->tile_vals, b.sizes, heavy_degree,
-                                                                          ctx->heavy_rows, ctx->heavy_count + l)));
+                                                                          ctx->heavy_rows, ctx->heavy_count + l,
+                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), ctx->local_of)));
         int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
         if (rc != MQG_OK) return rc;
         MQG_LAUNCH(ctx, "k_row_offsets", s,
@@ -489,7 +519,7 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         a.fanout = k;
         a.force_slow = ctx->force_slow_select ? 1 : 0;
         a.heavy_degree = heavy_degree;
-        const int hub_blocks = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, need_dst), 512));
+        const int hub_blocks = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, need_dst), 2048));
         int sample_grid = hub_blocks + static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kWavesPerBlock)));
         MQG_LAUNCH(ctx, "k_sample", s,
                    (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
@@ -511,7 +541,7 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)), 4096));
         MQG_LAUNCH(ctx, "k_reset_local", s,
                    (k_reset_local<IdxT><<<grid, kBlock, 0, s>>>(static_cast<const IdxT *>(blocks[0].src_ids), blocks[0].sizes,
-                                                                 ctx->local_of)));
+                                                                 ctx->local_of, ctx->heavy_count)));
     }
     return MQG_OK;
 }
