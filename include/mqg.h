@@ -113,7 +113,10 @@ typedef struct mqg_cache {
  *   indices  [cap_nnz]    position in src_ids of each sampled neighbour; within
  *                         a row in ascending order of adjacency slot.
  *   sizes    [4]          int64, written on the device: num_dst, num_src, nnz,
- *                         and a flags word (0 = ok).
+ *                         and a flags word (0 = ok; in the innermost block bit 0
+ *                         = some seed id was outside [0, num_nodes) and has been
+ *                         replaced by node 0, bit 1 = a seed id occurs more
+ *                         than once; the batch is then not a valid sample).
  * Capacity bounds checked by mqg_sample_blocks (MQG_ERR_CAPACITY otherwise), with
  * need_dst(L-1) = num_seeds and need_dst(l) = need_src(l+1):
  *   cap_dst >= need_dst,  cap_nnz >= need_nnz = need_dst * fanouts[l],
@@ -190,6 +193,8 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
  * III-A, GraphSAGE paragraph: a fixed number of neighbours of every node of a
  * layer, drawn uniformly at random, a fresh draw per layer).
  *   seeds_dev  device [num_seeds], graph idx_type, distinct, in [0, num_nodes)
+ *              (violations are flagged in blocks[L-1].sizes[3]; an id out of range
+ *              is never used as an index)
  *   fanouts    host [num_layers], 1..MQG_MAX_FANOUT, indexed by block
  *   blocks     host array of num_layers descriptors (see mqg_block)
  * For each destination v of block l with adjacency row of length d: all d

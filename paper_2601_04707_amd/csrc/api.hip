@@ -138,14 +138,14 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const i
     ok = ok && dev_alloc(&c->row_deg, c->max_dst) == hipSuccess;
     ok = ok && dev_alloc(reinterpret_cast<int32_t **>(&c->nbr), c->max_nnz) == hipSuccess;
     ok = ok && dev_alloc(&c->heavy_rows, c->max_dst) == hipSuccess;
-    ok = ok && dev_alloc(&c->heavy_count, MQG_MAX_LAYERS) == hipSuccess;
+    ok = ok && dev_alloc(&c->heavy_count, MQG_MAX_LAYERS + 1) == hipSuccess;
     ok = ok && dev_alloc(&c->hit_list, c->max_src) == hipSuccess;
     ok = ok && dev_alloc(&c->miss_list, c->max_src) == hipSuccess;
     ok = ok && dev_alloc(&c->counters, 8) == hipSuccess;
     if (ok) ok = hipMemset(c->local_of, 0xFF, std::max<int64_t>(c->num_nodes, 1) * sizeof(int32_t)) == hipSuccess;
     if (ok) ok = hipMemset(c->bitmap, 0, std::max<int64_t>(c->bitmap_words, 1) * sizeof(uint32_t)) == hipSuccess;
     if (ok) ok = hipMemset(c->counters, 0, 8 * sizeof(unsigned long long)) == hipSuccess;
-    if (ok) ok = hipMemset(c->heavy_count, 0, MQG_MAX_LAYERS * sizeof(int32_t)) == hipSuccess;
+    if (ok) ok = hipMemset(c->heavy_count, 0, (MQG_MAX_LAYERS + 1) * sizeof(int32_t)) == hipSuccess;
     if (ok) ok = hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
         std::string msg = std::string("mqg_ctx_create: scratch allocation failed: ") + hipGetErrorString(hipGetLastError());
@@ -268,6 +268,7 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
     if (num_seeds < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: negative num_seeds");
     if (num_seeds > ctx->max_seeds) return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_blocks: num_seeds above the context's max_seeds");
     if (num_seeds > 0 && !seeds_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: seeds_dev is NULL");
+    if (num_seeds > 0 && g->num_nodes == 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks: seeds given for an empty graph");
     int64_t dst = num_seeds;
     for (int l = L - 1; l >= 0; --l) {
         if (fanouts[l] < 1 || fanouts[l] > MQG_MAX_FANOUT)

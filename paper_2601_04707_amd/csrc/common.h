@@ -45,7 +45,7 @@ struct mqg_ctx {
     int32_t *row_deg = nullptr;          // [max_dst] degree of each destination
     void *nbr = nullptr;                 // [max_nnz] sampled neighbours, global ids, 32-bit
     int32_t *heavy_rows = nullptr;       // [max_dst] destinations whose degree exceeds heavy_degree
-    int32_t *heavy_count = nullptr;      // [MQG_MAX_LAYERS] their number, per block
+    int32_t *heavy_count = nullptr;      // [MQG_MAX_LAYERS] their number, per block; [MQG_MAX_LAYERS] seed-check flags
     int2 *hit_list = nullptr;            // [max_src] (output row, cache slot)
     int2 *miss_list = nullptr;           // [max_src] (output row, node id)
     unsigned long long *counters = nullptr;  // [8] two alternating (hits, misses) pairs: a gather uses one and clears the other

@@ -43,7 +43,7 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
            IdxT *__restrict__ src_out, int fanout, int64_t *__restrict__ row_start,
            int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *sizes_rw,
            int heavy_degree, int32_t *__restrict__ heavy_rows, int32_t *__restrict__ heavy_count,
-           int64_t n_seeds, int32_t *__restrict__ local_of) {
+           int64_t n_seeds, int32_t *__restrict__ local_of, int64_t num_nodes, int32_t *__restrict__ seed_flags) {
     __shared__ int lds[kWavesPerBlock];
     // innermost block (n_seeds >= 0): the destinations are the caller's seeds; their number comes
     // from the host and their positions are entered into local_of here
@@ -53,7 +53,16 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
     bool heavy = false;
     if (i < n) {
         IdxT v = dst[i];
-        if (n_seeds >= 0) local_of[v] = static_cast<int32_t>(i);
+        if (n_seeds >= 0) {
+            // caller-supplied ids: an id outside the graph is flagged and replaced by node 0, so that
+            // nothing downstream ever indexes with it; a repeated id is flagged (its rows are kept and
+            // share one position in the source lists)
+            if (v < 0 || static_cast<int64_t>(v) >= num_nodes) {
+                v = 0;
+                atomicOr(seed_flags, 1);
+            }
+            if (atomicCAS(&local_of[v], -1, static_cast<int32_t>(i)) != -1) atomicOr(seed_flags, 2);
+        }
         int64_t s = static_cast<int64_t>(row_ptr[v]);
         int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - s;
         row_start[i] = s;
@@ -79,10 +88,7 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
 #pragma unroll
         for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
         tile_sums[blockIdx.x] = t;
-        if (blockIdx.x == 0) {
-            sizes_rw[3] = 0;
-            if (n_seeds >= 0) sizes_rw[0] = n_seeds;
-        }
+        if (blockIdx.x == 0 && n_seeds >= 0) sizes_rw[0] = n_seeds;
     }
 }
 
@@ -108,10 +114,13 @@ k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ 
 }
 
 __global__ void __launch_bounds__(kBlock)
-k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, const int64_t *__restrict__ sizes,
-              const int32_t *__restrict__ tile_base, int32_t *__restrict__ indptr) {
+k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
+              const int32_t *__restrict__ tile_base, int32_t *__restrict__ indptr,
+              const int32_t *__restrict__ seed_flags) {
     __shared__ int lds[kWavesPerBlock];
     const int64_t n = sizes[0];
+    // the block's flags word: what the seed check found (innermost block), 0 otherwise
+    if (blockIdx.x == 0 && threadIdx.x == 0) sizes[3] = seed_flags ? *seed_flags : 0;
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     int cnt = 0;
     if (i < n) {
@@ -470,11 +479,12 @@ template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of,
               int32_t *__restrict__ heavy_count) {
-    if (blockIdx.x == 0 && threadIdx.x < MQG_MAX_LAYERS) heavy_count[threadIdx.x] = 0;   // for the next call
+    if (blockIdx.x == 0 && threadIdx.x <= MQG_MAX_LAYERS) heavy_count[threadIdx.x] = 0;  // hub counts and seed flags of the next call
     const int64_t n = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
-    for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride)
+    for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) {
         local_of[src_ids[i]] = -1;
+    }
 }
 
 template <typename PtrT, typename IdxT>
@@ -501,11 +511,13 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
                    (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
                                                                           ctx->row_deg, ctx->tile_vals, b.sizes, heavy_degree,
                                                                           ctx->heavy_rows, ctx->heavy_count + l,
-                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), ctx->local_of)));
+                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), ctx->local_of,
+                                                                          g->num_nodes, ctx->heavy_count + MQG_MAX_LAYERS)));
         int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
         if (rc != MQG_OK) return rc;
         MQG_LAUNCH(ctx, "k_row_offsets", s,
-                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, b.indptr)));
+                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, b.indptr,
+                                                               l == L - 1 ? ctx->heavy_count + MQG_MAX_LAYERS : nullptr)));
 
         SampleArgs a;
         a.row_start = ctx->row_start;

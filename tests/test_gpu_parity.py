@@ -359,6 +359,31 @@ def test_scaled_workloads_whole_path(mqg, name, factor, batches):
 
 # ------------------------------------------------------------------------- error handling
 
+def test_bad_seeds_are_flagged_on_the_device_not_dereferenced(mqg):
+    rp, ci = hub_graph(n=3000, edges=40_000, max_degree=300)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts = [4, 3]
+    ctx = mqg.Context(g, 8, fanouts)
+    blocks = mqg.Blocks(g, 8, fanouts)
+
+    def flags_of(seeds):
+        mqg.mqg_sample_blocks(ctx, g, to_dev(torch.tensor(seeds, dtype=torch.int64)), fanouts, 5, blocks)
+        torch.cuda.synchronize()
+        return blocks.host_sizes()
+
+    sz = flags_of([5, n + 7, 9, -3])                              # two ids outside the graph
+    assert sz[1][3] & 1 and sz[0][3] == 0
+    assert blocks.src_ids[1][:4].tolist() == [5, 0, 9, 0]         # replaced by node 0 (and now repeated)
+    assert sz[1][3] & 2
+    sz = flags_of([5, 9, 5])                                      # a repeated id
+    assert sz[1][3] == 2
+    # the context is clean afterwards: a good batch is bit-exact and unflagged
+    got = hip_sample(mqg, ctx, g, blocks, torch.tensor([1, 2, 3, 4]), fanouts, 6)
+    want = oracle.sample_blocks(rp.numpy(), ci.numpy(), np.array([1, 2, 3, 4]), fanouts, 6)
+    assert_blocks_equal(got, want)
+
+
 def test_host_side_errors(mqg):
     rp, ci = hub_graph(n=2000, edges=20_000, max_degree=200)
     g = mqg.Graph(to_dev(rp), to_dev(ci))
