@@ -63,6 +63,8 @@ def _load():
     lib.orc_float_to_half.argtypes = [ctypes.c_float]
     lib.orc_mean_aggregate.restype = None
     lib.orc_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, ctypes.c_int]
+    lib.orc_mean_aggregate_backward.restype = ctypes.c_int
+    lib.orc_mean_aggregate_backward.argtypes = [vp, vp, i64, i64, vp, i64, vp, i64, i64, ctypes.c_int]
     _lib = lib
     return lib
 
@@ -203,6 +205,22 @@ def mean_aggregate(indptr, indices, x: np.ndarray) -> np.ndarray:
     out = np.zeros((nd, x.shape[1]), dtype=x.dtype)
     _load().orc_mean_aggregate(_p(ip), _p(ix), nd, _p(x), x.shape[1], _p(out), x.shape[1],
                                x.shape[1], 1 if x.dtype == np.float16 else 0)
+    return out
+
+
+def mean_aggregate_backward(indptr, indices, num_src: int, grad_out: np.ndarray) -> np.ndarray:
+    """grad_out: [num_dst, dim] float32 or float16; returns grad_x [num_src, dim], same dtype."""
+    ip = _i64(indptr)
+    ix = np.ascontiguousarray(np.asarray(indices), dtype=np.int32)
+    assert grad_out.dtype in (np.float32, np.float16) and grad_out.ndim == 2
+    g = np.ascontiguousarray(grad_out)
+    nd = ip.shape[0] - 1
+    assert g.shape[0] >= nd
+    out = np.zeros((num_src, g.shape[1]), dtype=g.dtype)
+    rc = _load().orc_mean_aggregate_backward(_p(ip), _p(ix), nd, num_src, _p(g), g.shape[1], _p(out),
+                                             g.shape[1], g.shape[1], 1 if g.dtype == np.float16 else 0)
+    if rc != 0:
+        raise MemoryError("orc_mean_aggregate_backward")
     return out
 
 

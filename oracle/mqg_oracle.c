@@ -31,6 +31,10 @@
  *                            source nodes.
  *   - orc_mean_aggregate   : Eq. 16, Z_agg(v) = Mean(H(v)) over the sampled
  *                            neighbours of v (the GA step, "AH").
+ *   - orc_mean_aggregate_backward : Sec. IV "Computation", backward pass: the
+ *                            gradient of the GA step is the transposed
+ *                            product ("AG" with G the gradient matrix), here
+ *                            the transpose of the row-mean operator.
  *
  * Randomness is a pure function of its coordinates: the key of slot j in
  * the adjacency row of node v at block l under seed s is
@@ -352,4 +356,40 @@ void orc_mean_aggregate(const int64_t *indptr, const int32_t *indices, int64_t n
         }
     }
     free(acc);
+}
+
+/*
+ * Backward of the mean aggregation: with out = M x, M[i, s] = (number of edges
+ * of row i that point to s) / n_i, this computes grad_x = M^T grad_out, i.e.
+ *   grad_x[s, :] = sum over rows i and edges e of row i with indices[e] == s
+ *                  of grad_out[i, :] / n_i,
+ * accumulated in double in row order and rounded once to float (and then once
+ * to half for is_half).  Sources without an incoming edge get zeros.
+ */
+int orc_mean_aggregate_backward(const int64_t *indptr, const int32_t *indices, int64_t num_dst,
+                                int64_t num_src, const void *grad_out, int64_t go_stride,
+                                void *grad_x, int64_t gx_stride, int64_t dim, int is_half)
+{
+    size_t total = (size_t)(num_src > 0 ? num_src : 1) * (size_t)(dim > 0 ? dim : 1);
+    double *acc = calloc(total, sizeof *acc);
+    if (!acc) return -2;
+    for (int64_t i = 0; i < num_dst; ++i) {
+        int64_t b = indptr[i], e = indptr[i + 1], n = e - b;
+        for (int64_t p = b; p < e; ++p) {
+            int64_t s = indices[p];
+            for (int64_t c = 0; c < dim; ++c) {
+                double g = is_half ? orc_half_to_double(((const uint16_t *)grad_out)[i * go_stride + c])
+                                   : (double)((const float *)grad_out)[i * go_stride + c];
+                acc[s * dim + c] += g / (double)n;
+            }
+        }
+    }
+    for (int64_t s = 0; s < num_src; ++s)
+        for (int64_t c = 0; c < dim; ++c) {
+            double v = acc[s * dim + c];
+            if (is_half) ((uint16_t *)grad_x)[s * gx_stride + c] = orc_float_to_half((float)v);
+            else ((float *)grad_x)[s * gx_stride + c] = (float)v;
+        }
+    free(acc);
+    return 0;
 }

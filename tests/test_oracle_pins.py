@@ -422,3 +422,54 @@ def test_sampled_mean_is_unbiased_for_full_mean():
     # sd of one estimate <= sd(x)/sqrt(k); 5 sigma of the averaged estimate
     bound = 5 * x[ci[rp[v]:rp[v + 1]]].std(0) / math.sqrt(k * trials)
     assert np.all(np.abs(est - full) < bound)
+
+
+# ------------------------------------------------------------ backward of the aggregation
+
+@pytest.mark.parametrize("dtype,tol", [(np.float32, 1e-6), (np.float16, 2e-3)])
+def test_backward_is_the_transposed_row_mean_operator(dtype, tol):
+    rng = np.random.default_rng(8)
+    nd, ns, dim = 60, 110, 9
+    indptr, indices = _random_block(rng, nd, ns, 6)
+    g = rng.standard_normal((nd, dim)).astype(dtype)
+    M = np.zeros((nd, ns))
+    for i in range(nd):
+        for e in range(indptr[i], indptr[i + 1]):
+            M[i, indices[e]] += 1.0 / (indptr[i + 1] - indptr[i])
+    want = M.T @ g.astype(np.float64)
+    got = oracle.mean_aggregate_backward(indptr, indices, ns, g).astype(np.float64)
+    assert np.allclose(got, want, rtol=tol, atol=tol)
+    # library routine: scipy's transposed CSR product
+    S = sp.csr_matrix((np.repeat(1.0 / np.maximum(np.diff(indptr), 1), np.diff(indptr)), indices, indptr),
+                      shape=(nd, ns))
+    assert np.allclose(got, S.T @ g.astype(np.float64), rtol=tol, atol=tol)
+    untouched = np.setdiff1d(np.arange(ns), indices)
+    assert len(untouched) and np.all(got[untouched] == 0)
+    if dtype == np.float32:
+        assert np.array_equal(got.astype(np.float32), want.astype(np.float32))
+
+
+def test_backward_is_adjoint_of_forward():
+    """<M x, g> == <x, M^T g>: ties the backward oracle to the pinned forward oracle."""
+    rng = np.random.default_rng(9)
+    nd, ns, dim = 80, 150, 5
+    indptr, indices = _random_block(rng, nd, ns, 8)
+    x = rng.standard_normal((ns, dim)).astype(np.float32)
+    g = rng.standard_normal((nd, dim)).astype(np.float32)
+    fwd = oracle.mean_aggregate(indptr, indices, x).astype(np.float64)
+    bwd = oracle.mean_aggregate_backward(indptr, indices, ns, g).astype(np.float64)
+    lhs, rhs = (fwd * g).sum(), (x * bwd).sum()
+    assert abs(lhs - rhs) < 1e-5 * max(1.0, abs(lhs))
+
+
+def test_backward_closed_forms():
+    indptr = np.array([0, 2, 2, 5], dtype=np.int64)             # row 1 is empty
+    indices = np.array([0, 3, 3, 1, 0], dtype=np.int32)
+    ones = np.ones((3, 2), dtype=np.float32)
+    got = oracle.mean_aggregate_backward(indptr, indices, 5, ones)
+    # source 0: 1/2 + 1/3, source 1: 1/3, source 3: 1/2 + 1/3, sources 2 and 4 untouched
+    want = np.array([1 / 2 + 1 / 3, 1 / 3, 0, 1 / 2 + 1 / 3, 0])
+    assert np.allclose(got[:, 0], want, rtol=1e-7) and np.array_equal(got[:, 0], got[:, 1])
+    g = np.array([[6.0], [100.0], [9.0]], dtype=np.float32)      # the empty row's gradient goes nowhere
+    got = oracle.mean_aggregate_backward(indptr, indices, 5, g)
+    assert got[:, 0].tolist() == [6.0, 3.0, 0.0, 6.0, 0.0]
