@@ -240,6 +240,25 @@ int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_
                             int64_t x_stride, void *out, int64_t out_stride, int32_t dim,
                             int32_t dtype, mqg_stream stream);
 
+/*
+ * Backward of the mean aggregation (paper Sec. IV "Computation": the gradient
+ * of the GA step is the transposed product "AG", G the gradient matrix).  With
+ * out = M x_src the forward operator of the block, M[i, s] = 1/n_i for every
+ * edge of destination i that points to source s, this computes
+ *   grad_x[s, c] = sum over edges (i -> s) of grad_out[i, c] / n_i
+ * for all num_src sources (zeros where no edge points).
+ * grad_out: device [num_dst x go_stride]; grad_x: device [cap_src x gx_stride];
+ * strides in elements, padding columns of written rows unspecified as in the
+ * forward.  The edges are first ordered by source with a stable radix sort and
+ * each source's terms are added in ascending destination order in fp32, so
+ * the result is reproducible bit for bit.  The first call (and any call with
+ * larger block capacities than seen before) allocates context scratch of
+ * about 20 bytes per edge and synchronises the stream once to do so.
+ */
+int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const void *grad_out,
+                                     int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim,
+                                     int32_t dtype, mqg_stream stream);
+
 #ifdef __cplusplus
 }
 #endif

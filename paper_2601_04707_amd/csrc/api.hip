@@ -73,6 +73,20 @@ static int prof_collect(mqg_ctx *ctx) {
     return MQG_OK;
 }
 
+void free_backward_scratch(mqg_ctx *ctx) {
+    (void)hipFree(ctx->bwd.keys[0]);
+    (void)hipFree(ctx->bwd.keys[1]);
+    (void)hipFree(ctx->bwd.vals[0]);
+    (void)hipFree(ctx->bwd.vals[1]);
+    (void)hipFree(ctx->bwd.hist);
+    (void)hipFree(ctx->bwd.tile_sums);
+    (void)hipFree(ctx->bwd_dst_row);
+    (void)hipFree(ctx->bwd_col_ptr);
+    ctx->bwd = RadixBufs{};
+    ctx->bwd_dst_row = ctx->bwd_col_ptr = nullptr;
+    ctx->bwd_nnz_cap = ctx->bwd_src_cap = 0;
+}
+
 }  // namespace mqg
 
 using mqg::fail;
@@ -169,6 +183,7 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->hit_list);
     (void)hipFree(c->miss_list);
     (void)hipFree(c->counters);
+    mqg::free_backward_scratch(c);
     for (auto &r : c->prof_recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -327,6 +342,20 @@ int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_
     if (x_stride < dim || out_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate: stride below dim");
     return mqg::run_mean_aggregate(ctx, block, x_src, x_stride, out, out_stride, dim, dtype,
                                    static_cast<hipStream_t>(stream));
+}
+
+int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const void *grad_out, int64_t go_stride,
+                                     void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!block || !block->indptr || !block->indices || !block->sizes)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: NULL block buffers");
+    if (!valid_dtype(dtype) || dim < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: bad dtype or dim");
+    if (block->cap_dst < 0 || block->cap_src < 0 || block->cap_nnz < 0 || block->cap_nnz >= (int64_t(1) << 31))
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: bad block capacities");
+    if (block->cap_src > 0 && (!grad_out || !grad_x)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: NULL grad_out or grad_x");
+    if (go_stride < dim || gx_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: stride below dim");
+    return mqg::run_mean_aggregate_backward(ctx, block, grad_out, go_stride, grad_x, gx_stride, dim, dtype,
+                                            static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -8,10 +8,7 @@
 // degrees.  Only as many 8-bit passes run as max_degree has bytes.
 //   k_degrees        degree per node, running maximum
 //   k_sort_keys      key = max_degree - degree, payload = id
-//   k_radix_hist     per-workgroup digit histogram, laid out [digit][workgroup]
-//   k_scan_*         exclusive scan of that table (reduce / one-workgroup scan / apply)
-//   k_radix_scatter  stable scatter: ballot match inside a wavefront, LDS counts across the four
-//                    wavefronts and across the rounds of a tile
+//   (radix passes)   see radix.hip
 //   k_assign_slots   slot_of / cached_ids
 // then the cached rows are copied with the direct gather kernel.
 #include <algorithm>
@@ -19,6 +16,7 @@
 
 #include "common.h"
 #include "device_utils.h"
+#include "radix.h"
 
 namespace mqg {
 
@@ -27,9 +25,6 @@ int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, 
 
 namespace {
 
-constexpr int kRadixItems = 8;                       // rounds per tile
-constexpr int kRadixTile = kBlock * kRadixItems;     // keys per workgroup
-constexpr int kScanTile = 1024;                      // elements per workgroup in the generic scan
 
 template <typename PtrT>
 __global__ void __launch_bounds__(kBlock)
@@ -54,112 +49,6 @@ k_sort_keys(uint32_t *__restrict__ keys, int32_t *__restrict__ vals, int64_t n, 
     if (v < n) {
         keys[v] = max_deg - keys[v];                 // in: degree, out: sort key
         vals[v] = static_cast<int32_t>(v);
-    }
-}
-
-__global__ void __launch_bounds__(kBlock)
-k_radix_hist(const uint32_t *__restrict__ keys, int64_t n, int shift, int32_t *__restrict__ hist, int nblocks) {
-    __shared__ int h[256];
-    h[threadIdx.x] = 0;
-    __syncthreads();
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-#pragma unroll
-    for (int r = 0; r < kRadixItems; ++r) {
-        int64_t i = base + r * kBlock + threadIdx.x;
-        if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255], 1);
-    }
-    __syncthreads();
-    hist[int64_t(threadIdx.x) * nblocks + blockIdx.x] = h[threadIdx.x];
-}
-
-__global__ void __launch_bounds__(kBlock)
-k_scan_reduce(const int32_t *__restrict__ in, int64_t n, int32_t *__restrict__ tile_sums) {
-    __shared__ int lds[kWavesPerBlock];
-    const int64_t base = int64_t(blockIdx.x) * kScanTile + threadIdx.x * 4;
-    int c = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-        if (base + q < n) c += in[base + q];
-    int s = wave_sum(c);
-    if (lane_id() == 0) lds[threadIdx.x >> 6] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) tile_sums[blockIdx.x] = lds[0] + lds[1] + lds[2] + lds[3];
-}
-
-__global__ void __launch_bounds__(kBlock)
-k_scan_apply(int32_t *__restrict__ data, int64_t n, const int32_t *__restrict__ tile_base) {
-    __shared__ int lds[kWavesPerBlock];
-    const int64_t base = int64_t(blockIdx.x) * kScanTile + threadIdx.x * 4;
-    int v[4];
-    int c = 0;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        v[q] = base + q < n ? data[base + q] : 0;
-        c += v[q];
-    }
-    int total;
-    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds) + tile_base[blockIdx.x];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        if (base + q < n) data[base + q] = ex;
-        ex += v[q];
-    }
-}
-
-__global__ void __launch_bounds__(kBlock)
-k_radix_scatter(const uint32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in, int64_t n, int shift,
-                const int32_t *__restrict__ offsets, int nblocks, uint32_t *__restrict__ keys_out,
-                int32_t *__restrict__ vals_out) {
-    __shared__ int run[256];                         // keys of this digit placed in earlier rounds
-    __shared__ int wcnt[kWavesPerBlock][256];        // per wavefront, this round
-    __shared__ int gbase[256];                       // first output position of this workgroup per digit
-    const int tid = threadIdx.x;
-    const int lane = lane_id();
-    const int wave = tid >> 6;
-    run[tid] = 0;
-    gbase[tid] = offsets[int64_t(tid) * nblocks + blockIdx.x];
-#pragma unroll
-    for (int w = 0; w < kWavesPerBlock; ++w) wcnt[w][tid] = 0;
-    __syncthreads();
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-    for (int r = 0; r < kRadixItems; ++r) {
-        const int64_t i = base + r * kBlock + tid;
-        const bool valid = i < n;
-        uint32_t key = 0;
-        int32_t val = 0;
-        if (valid) {
-            key = keys_in[i];
-            val = vals_in[i];
-        }
-        const int digit = (key >> shift) & 255;
-        // lanes of this wavefront holding the same digit
-        uint64_t peers = ballot64(valid);
-#pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            uint64_t m = ballot64((digit >> bit) & 1);
-            peers &= ((digit >> bit) & 1) ? m : ~m;
-        }
-        const int rank_in_wave = popc64(peers & lanes_below(lane));
-        if (valid && rank_in_wave == 0) wcnt[wave][digit] = popc64(peers);
-        __syncthreads();
-        if (valid) {
-            int before = run[digit];
-            for (int w = 0; w < wave; ++w) before += wcnt[w][digit];
-            int64_t o = int64_t(gbase[digit]) + before + rank_in_wave;
-            keys_out[o] = key;
-            vals_out[o] = val;
-        }
-        __syncthreads();
-        {
-            int add = 0;
-#pragma unroll
-            for (int w = 0; w < kWavesPerBlock; ++w) {
-                add += wcnt[w][tid];
-                wcnt[w][tid] = 0;
-            }
-            run[tid] += add;
-        }
-        __syncthreads();
     }
 }
 
@@ -194,16 +83,6 @@ struct Temp {
     }
 };
 
-// exclusive scan of data[0..n) in place
-int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipStream_t s) {
-    const int tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kScanTile)));
-    MQG_LAUNCH(ctx, "k_scan_reduce", s, (k_scan_reduce<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
-    int rc = launch_scan_tiles(ctx, tile_sums, tiles, nullptr, nullptr, nullptr, s);
-    if (rc != MQG_OK) return rc;
-    MQG_LAUNCH(ctx, "k_scan_apply", s, (k_scan_apply<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
-    return MQG_OK;
-}
-
 }  // namespace
 
 int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t s) {
@@ -217,14 +96,13 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t 
     }
 
     Temp tmp;
-    uint32_t *keys_a, *keys_b, *max_deg_dev;
-    int32_t *vals_a, *vals_b, *hist, *tile_sums;
+    uint32_t *keys_a, *max_deg_dev;
+    int32_t *vals_a;
     int64_t *count_dev;
-    const int nblocks = static_cast<int>(ceil_div(n, kRadixTile));
-    const int64_t hist_len = int64_t(256) * nblocks;
-    bool ok = tmp.alloc(&keys_a, n) && tmp.alloc(&keys_b, n) && tmp.alloc(&vals_a, n) && tmp.alloc(&vals_b, n) &&
-              tmp.alloc(&hist, hist_len) && tmp.alloc(&tile_sums, ceil_div(hist_len, kScanTile) + 1) &&
-              tmp.alloc(&max_deg_dev, 1) && tmp.alloc(&count_dev, 1);
+    RadixBufs rb;
+    bool ok = tmp.alloc(&keys_a, n) && tmp.alloc(&vals_a, n) && tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) &&
+              tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) && tmp.alloc(&rb.hist, radix_hist_len(n)) &&
+              tmp.alloc(&rb.tile_sums, radix_scan_tiles(n)) && tmp.alloc(&max_deg_dev, 1) && tmp.alloc(&count_dev, 1);
     if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
 
     const int ngrid = static_cast<int>(ceil_div(n, kBlock));
@@ -240,20 +118,12 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t 
     if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
 
     MQG_LAUNCH(ctx, "k_sort_keys", s, (k_sort_keys<<<ngrid, kBlock, 0, s>>>(keys_a, vals_a, n, max_deg)));
-    int passes = 0;
-    while (passes < 4 && (max_deg >> (8 * passes)) != 0) ++passes;
-    uint32_t *kin = keys_a, *kout = keys_b;
-    int32_t *vin = vals_a, *vout = vals_b;
-    for (int p = 0; p < passes; ++p) {
-        const int shift = 8 * p;
-        MQG_LAUNCH(ctx, "k_radix_hist", s, (k_radix_hist<<<nblocks, kBlock, 0, s>>>(kin, n, shift, hist, nblocks)));
-        int rc = device_scan(ctx, hist, hist_len, tile_sums, s);
-        if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_radix_scatter", s,
-                   (k_radix_scatter<<<nblocks, kBlock, 0, s>>>(kin, vin, n, shift, hist, nblocks, kout, vout)));
-        std::swap(kin, kout);
-        std::swap(vin, vout);
-    }
+    int bits = 0;
+    while (bits < 32 && (max_deg >> bits) != 0) bits += 8;
+    int which = -1;
+    int rc0 = radix_sort_pairs(ctx, keys_a, vals_a, rb, n, nullptr, bits, s, &which);
+    if (rc0 != MQG_OK) return rc0;
+    const int32_t *vin = which < 0 ? vals_a : rb.vals[which];
     // vin: node ids by (degree descending, id ascending)
     const int cgrid = static_cast<int>(ceil_div(c->num_cached, kBlock));
     if (g->idx_type == MQG_I64)

@@ -17,6 +17,14 @@ constexpr int kWavesPerBlock = kBlock / kWave;
 constexpr int kBitmapTileWords = 1024;   // words of the frontier bitmap handled by one workgroup
 constexpr int kCandidates = 256;         // per-wavefront candidate slots of the threshold selection
 
+// Ping-pong buffers of the radix sort (see radix.h)
+struct RadixBufs {
+    uint32_t *keys[2] = {nullptr, nullptr};     // [n_cap] each
+    int32_t *vals[2] = {nullptr, nullptr};      // [n_cap] each
+    int32_t *hist = nullptr;                    // [radix_hist_len(n_cap)]
+    int32_t *tile_sums = nullptr;               // [radix_scan_tiles(n_cap)]
+};
+
 struct ProfRec {
     int name_id;
     hipEvent_t start, stop;
@@ -50,6 +58,11 @@ struct mqg_ctx {
     int2 *miss_list = nullptr;           // [max_src] (output row, node id)
     unsigned long long *counters = nullptr;  // [8] two alternating (hits, misses) pairs: a gather uses one and clears the other
     uint64_t gather_calls = 0;
+    // backward aggregation: edges ordered by source; allocated at the first backward call
+    mqg::RadixBufs bwd;
+    int32_t *bwd_dst_row = nullptr;      // [bwd_nnz_cap] destination row of every edge
+    int32_t *bwd_col_ptr = nullptr;      // [bwd_src_cap + 2] offsets of every source in the sorted edge list
+    int64_t bwd_nnz_cap = 0, bwd_src_cap = 0;
 
     // options
     bool force_slow_select = false;
@@ -99,6 +112,9 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
 int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
                        int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t s);
+int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *grad_out, int64_t go_stride,
+                                void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s);
+void free_backward_scratch(mqg_ctx *ctx);
 
 // Exclusive scan of vals[0..n) in place by one workgroup; the total (plus *addend if given) is
 // stored to *total_a and *total_b where non-null.

@@ -27,7 +27,7 @@ MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
 EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
-    "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate",
+    "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -80,6 +80,8 @@ lib.mqg_gather_features.restype = ctypes.c_int
 lib.mqg_gather_features.argtypes = [_vp, ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
 lib.mqg_sage_mean_aggregate.restype = ctypes.c_int
 lib.mqg_sage_mean_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
+lib.mqg_sage_mean_aggregate_backward.restype = ctypes.c_int
+lib.mqg_sage_mean_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 
 
 class MqgError(RuntimeError):
@@ -270,3 +272,15 @@ def mqg_sage_mean_aggregate(ctx: Context, blocks: Blocks, l: int, x_src: torch.T
     ctx.check(lib.mqg_sage_mean_aggregate(ctx.h, ctypes.byref(blocks.c[l]), x_src.data_ptr(), x_src.stride(0),
                                           out.data_ptr(), out.stride(0), x_src.shape[1], _dtype(x_src),
                                           _stream(stream)))
+
+
+def mqg_sage_mean_aggregate_backward(ctx: Context, blocks: Blocks, l: int, grad_out: torch.Tensor, grad_x: torch.Tensor,
+                                     stream=None) -> None:
+    """grad_out: [>= num_dst, dim] gradient of the block's output; grad_x: [>= cap_src, dim] receives the
+    gradient with respect to the block's source rows."""
+    assert grad_out.is_cuda and grad_x.is_cuda and grad_out.dtype == grad_x.dtype
+    assert grad_out.stride(1) == 1 and grad_x.stride(1) == 1 and grad_out.shape[1] == grad_x.shape[1]
+    assert grad_x.shape[0] >= blocks.c[l].cap_src
+    ctx.check(lib.mqg_sage_mean_aggregate_backward(ctx.h, ctypes.byref(blocks.c[l]), grad_out.data_ptr(),
+                                                   grad_out.stride(0), grad_x.data_ptr(), grad_x.stride(0),
+                                                   grad_x.shape[1], _dtype(grad_x), _stream(stream)))

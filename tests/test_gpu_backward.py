@@ -1,0 +1,150 @@
+"""Backward of the mean aggregation on the GPU versus the oracle, through the C ABI.
+
+Tolerance: |gpu - oracle| <= tol * max(|oracle|, mass_s), tol = 1e-5 (fp32) / 2e-3 (fp16), where
+mass_s = mean|grad_out| * sum over the edges into source s of 1/n_dst is the magnitude of the
+terms that were added for source s.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_04707_amd import synth
+from gpu_util import hip_sample, to_dev
+
+pytestmark = pytest.mark.gpu
+
+TOL = {np.float32: 1e-5, np.float16: 2e-3}
+
+
+@pytest.fixture(scope="module")
+def mqg():
+    from paper_2601_04707_amd import mqg as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def source_mass(indptr, indices, num_src, g):
+    n = np.diff(indptr).astype(np.float64)
+    w = np.repeat(1.0 / np.maximum(n, 1), np.diff(indptr))
+    return np.bincount(indices, weights=w, minlength=num_src) * float(np.abs(g.astype(np.float64)).mean())
+
+
+def bare_blocks(mqg, indptr, indices, nd, ns):
+    """A context and a block descriptor around hand-made indptr/indices."""
+    rp = torch.tensor([0, 0], dtype=torch.int64)
+    g = mqg.Graph(to_dev(rp), torch.zeros(1, dtype=torch.int64, device="cuda"))
+    ctx = mqg.Context(g, 1, [1])
+    blocks = mqg.Blocks(g, 1, [1])
+    nnz = int(indptr[-1])
+    ip = to_dev(torch.from_numpy(indptr.astype(np.int32)))
+    ix = torch.zeros(max(nnz, 1), dtype=torch.int32, device="cuda")          # never an empty (NULL) buffer
+    ix[:nnz] = torch.from_numpy(indices.astype(np.int32)).cuda()
+    sizes = torch.tensor([nd, ns, nnz, 0], dtype=torch.int64, device="cuda")
+    blocks.c[0] = mqg.CBlock(nd, ns, max(nnz, 1), None, ip.data_ptr(), ix.data_ptr(), sizes.data_ptr())
+    blocks.bounds[0] = (nd, ns, nnz)
+    blocks._keep = (ip, ix, sizes, g)
+    return ctx, blocks
+
+
+def check(got, ref, mass, tol):
+    err = np.abs(got.astype(np.float64) - ref.astype(np.float64))
+    bound = tol * np.maximum(np.abs(ref.astype(np.float64)), mass[:, None])
+    assert np.all(err <= bound), float((err / np.maximum(bound, 1e-300)).max())
+
+
+@pytest.mark.parametrize("dim,dtype", [(64, np.float32), (100, np.float32), (602, np.float32), (128, np.float16),
+                                       (256, np.float16), (7, np.float32), (9, np.float16), (1030, np.float32)])
+def test_backward_parity_random_blocks(mqg, dim, dtype):
+    rng = np.random.default_rng(dim + 1)
+    nd, ns = 900, 2500
+    counts = rng.integers(0, 26, nd)
+    counts[::40] = 0
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    # a skewed choice of sources: a few hubs collect hundreds of edges, many sources none
+    p = 1.0 / (np.arange(ns) + 5.0) ** 1.2
+    p[ns // 2:] = 0
+    p /= p.sum()
+    indices = np.concatenate([rng.choice(ns, size=c, replace=False, p=p) for c in counts]).astype(np.int32) \
+        if indptr[-1] else np.zeros(0, np.int32)
+    assert np.bincount(indices, minlength=ns).max() > 128
+    gout = rng.standard_normal((nd, dim)).astype(dtype)
+    ref = oracle.mean_aggregate_backward(indptr, indices, ns, gout)
+    ctx, blocks = bare_blocks(mqg, indptr, indices, nd, ns)
+    gd = to_dev(torch.from_numpy(gout))
+    gx = torch.full((ns + 3, dim), 9.0, dtype=gd.dtype, device="cuda")
+    mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, 0, gd, gx)
+    torch.cuda.synchronize()
+    got = gx[:ns].cpu().numpy()
+    check(got, ref, source_mass(indptr, indices, ns, gout), TOL[dtype])
+    assert torch.all(gx[ns:] == 9.0)                              # nothing past num_src
+    assert np.all(got[ns // 2:] == 0)                             # sources nobody points to
+    # reproducible bit for bit, also after another block went through the same context
+    gx2 = torch.zeros_like(gx)
+    mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, 0, gd, gx2)
+    torch.cuda.synchronize()
+    assert torch.equal(gx2[:ns], gx[:ns])
+
+
+def test_backward_empty_block_and_single_edges(mqg):
+    indptr = np.array([0, 0, 0], dtype=np.int64)
+    ctx, blocks = bare_blocks(mqg, indptr, np.zeros(0, np.int32), 2, 5)
+    gd = torch.ones((2, 4), dtype=torch.float32, device="cuda")
+    gx = torch.full((5, 4), 3.0, dtype=torch.float32, device="cuda")
+    mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, 0, gd, gx)
+    torch.cuda.synchronize()
+    assert torch.all(gx == 0)
+    indptr = np.array([0, 2, 2, 5], dtype=np.int64)
+    indices = np.array([0, 3, 3, 1, 0], dtype=np.int32)
+    ctx, blocks = bare_blocks(mqg, indptr, indices, 3, 5)
+    gd = torch.tensor([[6.0], [100.0], [9.0]], dtype=torch.float32, device="cuda")
+    gx = torch.zeros((5, 1), dtype=torch.float32, device="cuda")
+    mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, 0, gd, gx)
+    torch.cuda.synchronize()
+    assert gx[:, 0].tolist() == [6.0, 3.0, 0.0, 6.0, 0.0]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.float16])
+def test_backward_on_sampled_blocks_and_adjoint_identity(mqg, dtype):
+    rp, ci = synth.chung_lu_graph(20000, 400_000, max_degree=3000, seed=1)
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts = [15, 10, 5]
+    batch, dim = 512, 48
+    ctx = mqg.Context(g, batch, fanouts)
+    blocks = mqg.Blocks(g, batch, fanouts)
+    seeds = synth.seed_batches(rp.numel() - 1, batch, 1, seed=5)[0]
+    got_blocks = hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 77)
+    npdt = np.float16 if dtype == torch.float16 else np.float32
+    rng = np.random.default_rng(3)
+    for l in range(3):
+        b = got_blocks[l]
+        nd, ns = b["num_dst"], b["num_src"]
+        gout = rng.standard_normal((nd, dim)).astype(npdt)
+        ref = oracle.mean_aggregate_backward(b["indptr"], b["indices"], ns, gout)
+        gd = to_dev(torch.from_numpy(gout))
+        gx = torch.zeros((blocks.bounds[l][1], dim), dtype=dtype, device="cuda")
+        mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, l, gd, gx)
+        torch.cuda.synchronize()
+        check(gx[:ns].cpu().numpy(), ref, source_mass(b["indptr"], b["indices"], ns, gout), TOL[npdt])
+        if dtype == torch.float32:
+            # <M x, g> == <x, M^T g> with both sides computed on the GPU
+            x = torch.randn((blocks.bounds[l][1], dim), device="cuda")
+            out = torch.zeros((blocks.bounds[l][0], dim), device="cuda")
+            mqg.mqg_sage_mean_aggregate(ctx, blocks, l, x, out)
+            torch.cuda.synchronize()
+            lhs = float((out[:nd].double() * gd.double()).sum())
+            rhs = float((x[:ns].double() * gx[:ns].double()).sum())
+            assert abs(lhs - rhs) < 1e-4 * max(1.0, abs(lhs))
+
+
+def test_backward_argument_errors(mqg):
+    indptr = np.array([0, 1], dtype=np.int64)
+    ctx, blocks = bare_blocks(mqg, indptr, np.zeros(1, np.int32), 1, 1)
+    gd = torch.ones((1, 4), dtype=torch.float32, device="cuda")
+    gx = torch.ones((1, 4), dtype=torch.float32, device="cuda")
+    rc = mqg.lib.mqg_sage_mean_aggregate_backward(ctx.h, blocks.c[0], gd.data_ptr(), 2, gx.data_ptr(), 4, 4, 0, None)
+    assert rc == mqg.MQG_ERR_INVALID_ARG                          # stride below dim
+    rc = mqg.lib.mqg_sage_mean_aggregate_backward(ctx.h, blocks.c[0], None, 4, gx.data_ptr(), 4, 4, 0, None)
+    assert rc == mqg.MQG_ERR_INVALID_ARG
+    rc = mqg.lib.mqg_sage_mean_aggregate_backward(ctx.h, blocks.c[0], gd.data_ptr(), 4, gx.data_ptr(), 4, 4, 7, None)
+    assert rc == mqg.MQG_ERR_INVALID_ARG
