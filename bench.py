@@ -195,6 +195,39 @@ def main() -> int:
                              "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local"))
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
+    # ---------------------------------------------------------------- backward of the aggregation chain
+    # Not part of a step.  A pass of its own (so that it does not disturb the caches of the kernels
+    # timed above): per mini-batch the forward path, then the gradient of the last block's output
+    # pushed back through every block to the gathered rows, one mini-batch at a time.
+    for c in ctxs:
+        c.reset_profile()
+        c.set_option(mqg.MQG_OPT_PROFILE, 1)
+    gx = [torch.zeros((bounds[l][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)]
+    g_top = torch.randn((bounds[L - 1][0], pad_dim), device=dev).to(w.feat_dtype)[:, :w.dim]
+    KB = min(K, 50)
+    for i in range(W, W + KB):
+        step(i)
+        j = i % nfl
+        with torch.cuda.stream(streams[j]):
+            gcur = g_top
+            for l in range(L - 1, -1, -1):
+                mqg.mqg_sage_mean_aggregate_backward(ctxs[j], blks[j], l, gcur, gx[l], stream=streams[j])
+                gcur = gx[l]
+        torch.cuda.synchronize()
+    bwd_names = ("k_edge_dst_rows", "k_radix_hist", "k_scan_reduce", "k_scan_tiles(radix)", "k_scan_apply",
+                 "k_radix_scatter", "k_col_ptr", "k_mean_aggregate_backward")
+    bk = {}
+    for c in ctxs:
+        for name in bwd_names:
+            ms, cnt = c.kernel_time(name)
+            a = bk.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += cnt
+        c.set_option(mqg.MQG_OPT_PROFILE, 0)
+    bwd_us = sum(v[0] for v in bk.values()) / KB * 1e3
+    bwd_kernel_us = bk["k_mean_aggregate_backward"][0] / KB * 1e3
+    # reduction kernel: every edge reads one gradient row, every source row of every block is written once
+    bwd_bytes = (edges + int(sizes_host[:, :, 1].sum())) / K * row_bytes
 
     # ---------------------------------------------------------------- CPU baseline: the oracle, one thread
     cpu = None
@@ -270,6 +303,9 @@ def main() -> int:
         "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),
         "cache_hit_rate": round(hits / max(1, hits + misses), 4),
         "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1)},
+        "backward_aggregation": {"us_per_step": round(bwd_us, 1), "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
+                                 "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
+                                 "note": "all blocks of a mini-batch, one at a time; not part of a step"},
         "roofline": roofline,
         "roofline_host_link": host_link,
         "measured_plain_copies": measured,

@@ -119,6 +119,6 @@ void free_backward_scratch(mqg_ctx *ctx);
 // Exclusive scan of vals[0..n) in place by one workgroup; the total (plus *addend if given) is
 // stored to *total_a and *total_b where non-null.
 int launch_scan_tiles(mqg_ctx *ctx, int32_t *vals, int64_t n, const int64_t *addend,
-                      int64_t *total_a, int64_t *total_b, hipStream_t s);
+                      int64_t *total_a, int64_t *total_b, hipStream_t s, const char *name = "k_scan_tiles");
 
 }  // namespace mqg

@@ -137,7 +137,7 @@ int64_t radix_scan_tiles(int64_t n_cap) { return ceil_div(radix_hist_len(n_cap),
 int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipStream_t s) {
     const int tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kScanTile)));
     MQG_LAUNCH(ctx, "k_scan_reduce", s, (k_scan_reduce<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
-    int rc = launch_scan_tiles(ctx, tile_sums, tiles, nullptr, nullptr, nullptr, s);
+    int rc = launch_scan_tiles(ctx, tile_sums, tiles, nullptr, nullptr, nullptr, s, "k_scan_tiles(radix)");
     if (rc != MQG_OK) return rc;
     MQG_LAUNCH(ctx, "k_scan_apply", s, (k_scan_apply<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
     return MQG_OK;

@@ -561,8 +561,8 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
 }  // namespace
 
 int launch_scan_tiles(mqg_ctx *ctx, int32_t *vals, int64_t n, const int64_t *addend, int64_t *total_a,
-                      int64_t *total_b, hipStream_t s) {
-    MQG_LAUNCH(ctx, "k_scan_tiles", s, (k_scan_tiles<<<1, 1024, 0, s>>>(vals, n, addend, total_a, total_b)));
+                      int64_t *total_b, hipStream_t s, const char *name) {
+    MQG_LAUNCH(ctx, name, s, (k_scan_tiles<<<1, 1024, 0, s>>>(vals, n, addend, total_a, total_b)));
     return MQG_OK;
 }
 
