@@ -141,8 +141,8 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const i
         delete c;
         return fail(nullptr, MQG_ERR_UNSUPPORTED, "mqg_ctx_create: more than 2^31 sampled edges per block");
     }
-    c->bitmap_words = mqg::ceil_div(mqg::ceil_div(g->num_nodes, 32), mqg::kBitmapTileWords) * mqg::kBitmapTileWords;
-    c->max_tiles = std::max<int64_t>(mqg::ceil_div(c->max_dst, mqg::kBlock), c->bitmap_words / mqg::kBitmapTileWords) + 1;
+    c->bitmap_words = std::max<int64_t>(1, mqg::ceil_div(mqg::ceil_div(g->num_nodes, 32), mqg::kBitmapTileWords)) * mqg::kBitmapTileWords;
+    c->max_tiles = std::max<int64_t>(mqg::ceil_div(c->max_dst, mqg::kBlock), c->bitmap_words / mqg::kBlock) + 1;
 
     bool ok = true;
     ok = ok && dev_alloc(&c->local_of, c->num_nodes) == hipSuccess;

@@ -14,7 +14,7 @@ namespace mqg {
 constexpr int kWave = 64;                // CDNA wavefront width
 constexpr int kBlock = 256;              // default workgroup: 4 wavefronts
 constexpr int kWavesPerBlock = kBlock / kWave;
-constexpr int kBitmapTileWords = 1024;   // words of the frontier bitmap handled by one workgroup
+constexpr int kBitmapTileWords = 1024;   // the frontier bitmap is padded to a multiple of this many words
 constexpr int kCandidates = 256;         // per-wavefront candidate slots of the threshold selection
 
 // Ping-pong buffers of the radix sort (see radix.h)

@@ -420,12 +420,22 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
 // ------------------------------------------------------------------------------------------
 // Bitmap -> ascending list of new source nodes.
 
+// Two tile shapes.  Dense bitmaps (up to 32 M nodes): one word per thread, 256 words per
+// workgroup, ids staged through LDS so that the source list is written coalesced.  Larger graphs:
+// four words per thread (one 16-byte load), ids written straight from the bit loop - their bitmaps
+// are sparse, a thread rarely has more than a bit or two.
+template <int WPT>
 __global__ void __launch_bounds__(kBlock)
 k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_sums) {
     __shared__ int lds[kWavesPerBlock];
-    const int64_t w0 = int64_t(blockIdx.x) * kBitmapTileWords + threadIdx.x * 4;
-    uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
-    int c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * WPT;
+    int c;
+    if (WPT == 4) {
+        uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
+        c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    } else {
+        c = __popc(bitmap[w0]);
+    }
     int s = wave_sum(c);
     if (lane_id() == 0) lds[threadIdx.x >> 6] = s;
     __syncthreads();
@@ -439,10 +449,10 @@ k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_s
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_bitmap_emit(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
-              const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
+k_bitmap_emit4(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
+               const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
     __shared__ int lds[kWavesPerBlock];
-    const int64_t w0 = int64_t(blockIdx.x) * kBitmapTileWords + threadIdx.x * 4;
+    const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * 4;
     uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
     int c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
     int total;
@@ -464,6 +474,36 @@ k_bitmap_emit(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_ba
         }
     }
     *reinterpret_cast<uint4 *>(bitmap + w0) = make_uint4(0, 0, 0, 0);
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
+               const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ int32_t staged[kBlock * 32];                // every id of the tile, ascending
+    const int64_t w0 = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    uint32_t bits = bitmap[w0];
+    const int c = __popc(bits);
+    int total;
+    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+    if (total == 0) return;                                // workgroup-uniform
+    if (c) {
+        bitmap[w0] = 0;
+        const int32_t v0 = static_cast<int32_t>(w0 * 32);
+        while (bits) {
+            int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            staged[ex++] = v0 + b;
+        }
+    }
+    __syncthreads();
+    const int64_t base = sizes[0] + tile_base[blockIdx.x];
+    for (int k = threadIdx.x; k < total; k += kBlock) {
+        const int32_t v = staged[k];
+        src_ids[base + k] = static_cast<IdxT>(v);
+        local_of[v] = static_cast<int32_t>(base + k);
+    }
 }
 
 __global__ void __launch_bounds__(kBlock)
@@ -497,7 +537,8 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
 
     int64_t need_dst = num_seeds;
-    const int bitmap_tiles = static_cast<int>(ctx->bitmap_words / kBitmapTileWords);
+    const int bitmap_wpt = ctx->bitmap_words <= (int64_t(1) << 20) ? 1 : 4;     // words per thread, see k_bitmap_emit*
+    const int bitmap_tiles = static_cast<int>(std::max<int64_t>(1, ctx->bitmap_words / (int64_t(kBlock) * bitmap_wpt)));
     for (int l = L - 1; l >= 0; --l) {
         mqg_block &b = blocks[l];
         const int k = fanouts[l];
@@ -536,14 +577,22 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         MQG_LAUNCH(ctx, "k_sample", s,
                    (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
 
-        MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<<<std::max(1, bitmap_tiles), kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
         // num_src = num_dst + number of new nodes; it is also the next block's num_dst
+        if (bitmap_wpt == 1) {
+            MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<1><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
+        } else {
+            MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<4><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
+        }
         rc = launch_scan_tiles(ctx, ctx->tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1],
                                l > 0 ? &blocks[l - 1].sizes[0] : nullptr, s);
         if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                   (k_bitmap_emit<IdxT><<<std::max(1, bitmap_tiles), kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids,
-                                                                                      ctx->local_of)));
+        if (bitmap_wpt == 1) {
+            MQG_LAUNCH(ctx, "k_bitmap_emit", s,
+                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids, ctx->local_of)));
+        } else {
+            MQG_LAUNCH(ctx, "k_bitmap_emit", s,
+                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids, ctx->local_of)));
+        }
         int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
         MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, ctx->local_of, b.indices)));
 
