@@ -195,6 +195,17 @@ def main() -> int:
                              "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local"))
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
+    # ---------------------------------------------------------------- the paper's queue-depth rule on these timings
+    whole = lambda t: t._base if t._base is not None else t       # the padded allocation behind a column view
+    per_batch_bytes = sum(t.numel() * t.element_size() for t in
+                          [whole(x0[0])] + [whole(h) for h in hs[0]] + blks[0].src_ids + blks[0].indptr + blks[0].indices)
+    try:
+        q_rule, q_cap = mqg.mqg_queue_size(max((sample_us + gather_us) * 1e-3, 1e-6), max(agg_us * 1e-3, 1e-6),
+                                           torch.cuda.get_device_properties(0).total_memory,
+                                           torch.cuda.max_memory_allocated(), 10, per_batch_bytes)
+    except mqg.MqgError:
+        q_rule, q_cap = None, None
+
     # ---------------------------------------------------------------- backward of the aggregation chain
     # Not part of a step.  A pass of its own (so that it does not disturb the caches of the kernels
     # timed above): per mini-batch the forward path, then the gradient of the last block's output
@@ -306,6 +317,10 @@ def main() -> int:
         "backward_aggregation": {"us_per_step": round(bwd_us, 1), "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
                                  "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
                                  "note": "all blocks of a mini-batch, one at a time; not part of a step"},
+        "paper_queue_rule": {"queue_size": q_rule, "memory_cap": q_cap, "bytes_per_queued_batch": per_batch_bytes,
+                             "note": "Eq. 22-23 on mean prepare (sample+gather) / consume (aggregate) times of this run; "
+                                     "the depth actually used is config.in_flight: the path is bound by the host link, "
+                                     "which three mini-batches already keep busy"},
         "roofline": roofline,
         "roofline_host_link": host_link,
         "measured_plain_copies": measured,

@@ -259,6 +259,24 @@ int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const
                                      int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim,
                                      int32_t dtype, mqg_stream stream);
 
+/*
+ * Depth of the mini-batch queue, i.e. how many mini-batches to keep in flight
+ * (paper Sec. IV "Determining Optimal Queue Size", Eq. 22 and 23):
+ *   C = floor(M_Q / M_batch),  M_Q = total_mem - peak_mem * (1 + margin_percent/100)
+ *   Q = min(C, max(2, ceil(max_prepare_ms / mean_compute_ms)))
+ * max_prepare_ms is the largest observed sampling + transfer time of a
+ * mini-batch, mean_compute_ms the mean time of the stage that consumes it,
+ * peak_mem the measured peak device memory of one training epoch, margin the
+ * paper's 5-10 % safety margin, mem_per_batch the device memory one queued
+ * mini-batch holds.  Host arithmetic only (doubles for the times, integers
+ * for the memory); no GPU is touched.  *cap_out (may be NULL) receives C,
+ * *queue_size_out receives Q.  MQG_ERR_INVALID_ARG for non-positive times or
+ * sizes, a margin outside 0..100, or peak memory above the total.
+ */
+int mqg_queue_size(double max_prepare_ms, double mean_compute_ms, int64_t total_mem_bytes,
+                   int64_t peak_mem_bytes, int32_t margin_percent, int64_t mem_per_batch_bytes,
+                   int64_t *cap_out, int64_t *queue_size_out);
+
 #ifdef __cplusplus
 }
 #endif

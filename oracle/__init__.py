@@ -224,6 +224,19 @@ def mean_aggregate_backward(indptr, indices, num_src: int, grad_out: np.ndarray)
     return out
 
 
+def queue_size(max_prepare_ms: float, mean_compute_ms: float, total_mem_bytes: int, peak_mem_bytes: int,
+               margin_percent: int, mem_per_batch_bytes: int):
+    """Queue depth of the paper's Sec. IV "Determining Optimal Queue Size" (Eq. 22, 23), written out:
+    C = floor(M_Q / M_batch) with M_Q = total - peak*(1 + margin/100) (exact rational arithmetic),
+    Q = min(C, max(2, ceil(max_prepare / mean_compute))).  Returns (Q, C)."""
+    import math
+    from fractions import Fraction
+    m_q = Fraction(total_mem_bytes) - Fraction(peak_mem_bytes) * (1 + Fraction(margin_percent, 100))
+    cap = math.floor(m_q / mem_per_batch_bytes)
+    want = max(2, math.ceil(max_prepare_ms / mean_compute_ms))
+    return min(cap, want), cap
+
+
 def half_to_double(bits: int) -> float:
     return float(_load().orc_half_to_double(ctypes.c_uint16(bits)))
 

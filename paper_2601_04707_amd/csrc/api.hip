@@ -1,5 +1,7 @@
 // Host side of the C ABI: contexts, argument checks, profiling, dispatch to the kernel launchers.
 #include <algorithm>
+#include <cmath>
+#include <cstdint>
 #include <cstring>
 
 #include "common.h"
@@ -356,6 +358,25 @@ int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const
     if (go_stride < dim || gx_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: stride below dim");
     return mqg::run_mean_aggregate_backward(ctx, block, grad_out, go_stride, grad_x, gx_stride, dim, dtype,
                                             static_cast<hipStream_t>(stream));
+}
+
+int mqg_queue_size(double max_prepare_ms, double mean_compute_ms, int64_t total_mem_bytes, int64_t peak_mem_bytes,
+                   int32_t margin_percent, int64_t mem_per_batch_bytes, int64_t *cap_out, int64_t *queue_size_out) {
+    if (!queue_size_out) return MQG_ERR_INVALID_ARG;
+    if (!(max_prepare_ms > 0.0) || !(mean_compute_ms > 0.0) || total_mem_bytes <= 0 || peak_mem_bytes < 0 ||
+        mem_per_batch_bytes <= 0 || margin_percent < 0 || margin_percent > 100)
+        return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_queue_size: non-positive time or size, or margin outside 0..100");
+    // peak * (1 + margin/100) in integers, rounded up so that the margin is never short
+    const int64_t reserved = peak_mem_bytes + (peak_mem_bytes / 100) * margin_percent +
+                             ((peak_mem_bytes % 100) * margin_percent + 99) / 100;
+    if (reserved > total_mem_bytes) return fail(nullptr, MQG_ERR_INVALID_ARG, "mqg_queue_size: peak memory (with margin) above the total");
+    const int64_t cap = (total_mem_bytes - reserved) / mem_per_batch_bytes;
+    const double ratio = std::ceil(max_prepare_ms / mean_compute_ms);
+    int64_t want = ratio >= 9.0e18 ? INT64_MAX : static_cast<int64_t>(ratio);
+    if (want < 2) want = 2;
+    if (cap_out) *cap_out = cap;
+    *queue_size_out = std::min(cap, want);
+    return MQG_OK;
 }
 
 }  // extern "C"

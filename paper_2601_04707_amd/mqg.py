@@ -28,6 +28,7 @@ EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
+    "mqg_queue_size",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -82,6 +83,9 @@ lib.mqg_sage_mean_aggregate.restype = ctypes.c_int
 lib.mqg_sage_mean_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_sage_mean_aggregate_backward.restype = ctypes.c_int
 lib.mqg_sage_mean_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
+lib.mqg_queue_size.restype = ctypes.c_int
+lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
+                               ctypes.POINTER(_i64)]
 
 
 class MqgError(RuntimeError):
@@ -284,3 +288,14 @@ def mqg_sage_mean_aggregate_backward(ctx: Context, blocks: Blocks, l: int, grad_
     ctx.check(lib.mqg_sage_mean_aggregate_backward(ctx.h, ctypes.byref(blocks.c[l]), grad_out.data_ptr(),
                                                    grad_out.stride(0), grad_x.data_ptr(), grad_x.stride(0),
                                                    grad_x.shape[1], _dtype(grad_x), _stream(stream)))
+
+
+def mqg_queue_size(max_prepare_ms: float, mean_compute_ms: float, total_mem_bytes: int, peak_mem_bytes: int,
+                   margin_percent: int, mem_per_batch_bytes: int):
+    """Returns (queue_size, cap) of the paper's queue-sizing rule; host arithmetic in the library."""
+    cap, q = _i64(0), _i64(0)
+    rc = lib.mqg_queue_size(max_prepare_ms, mean_compute_ms, total_mem_bytes, peak_mem_bytes, margin_percent,
+                            mem_per_batch_bytes, ctypes.byref(cap), ctypes.byref(q))
+    if rc != MQG_OK:
+        raise MqgError(rc, lib.mqg_last_error(None).decode())
+    return q.value, cap.value
