@@ -144,9 +144,20 @@ def main() -> int:
     # time so that a kernel's duration is its own and not that of whatever overlaps it.
     for c in ctxs:
         c.set_option(mqg.MQG_OPT_PROFILE, 1)
+    keys_eval, keys_batches = 0, 0
     for i in range(W, W + K):
         step(i)
         torch.cuda.synchronize()
+        if keys_batches < 8:
+            # random keys the sampler must evaluate: the whole adjacency row of every destination
+            # whose degree exceeds the fanout (a row that fits is copied without any key)
+            j = i % nfl
+            for l in range(L):
+                nd = int(blks[j].sizes[l, 0])
+                dst = blks[j].src_ids[l][:nd].to(torch.int64)
+                deg = (rp[dst + 1] - rp[dst]).to(torch.int64)
+                keys_eval += int(deg[deg > w.fanouts[l]].sum())
+            keys_batches += 1
     kernels = {}
     for c in ctxs:
         for name in c.kernel_names():
@@ -195,6 +206,27 @@ def main() -> int:
                              "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local"))
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
+    # ---------------------------------------------------------------- sampling against its own bounds
+    # Integer ALU: one key costs 5 32-bit multiplies (quarter rate) and about 17 full-rate integer
+    # operations = 37 lane-cycles; the chip has 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz.
+    keys_per_step = keys_eval / max(keys_batches, 1)
+    alu_peak_keys = 256 * 4 * 16 * 2.4e9 / 37.0
+    k_sample_us = kern.get("k_sample", {}).get("us_per_step", 0.0)
+    sampling = {
+        "edges_per_s_sampling_alone": round(edges / K / max(sample_us, 1e-9) * 1e6, 1),
+        "us_per_step": round(sample_us, 1), "kernel_launches_per_step": sum(
+            v["launches"] for k, v in kern.items() if k in ("k_row_info", "k_scan_tiles", "k_row_offsets", "k_sample",
+                                                            "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local")) / K,
+        "keys_evaluated_per_step": round(keys_per_step, 1),
+        "k_sample": {"bound": "alu", "achieved": round(keys_per_step / max(k_sample_us, 1e-9) * 1e-3, 2),
+                     "peak": round(alu_peak_keys / 1e9, 1), "unit": "Gkeys/s",
+                     "frac": round(keys_per_step / max(k_sample_us, 1e-9) * 1e6 / alu_peak_keys, 4)},
+        # 12 B of row information per destination plus, per sampled edge, the index read, the
+        # neighbour written and read back, one local_of probe and the relabelled index written
+        "hbm_frac_of_algorithmic_bytes": round(((edges / K) * (ci.element_size() + 16) + (sizes_host[:, :, 0].sum() / K) * 12)
+                                               / max(sample_us, 1e-9) * 1e6 / (HBM_PEAK_GBPS * 1e9), 5),
+    }
+
     # ---------------------------------------------------------------- the paper's queue-depth rule on these timings
     whole = lambda t: t._base if t._base is not None else t       # the padded allocation behind a column view
     per_batch_bytes = sum(t.numel() * t.element_size() for t in
@@ -317,6 +349,7 @@ def main() -> int:
         "backward_aggregation": {"us_per_step": round(bwd_us, 1), "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
                                  "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
                                  "note": "all blocks of a mini-batch, one at a time; not part of a step"},
+        "sampling": sampling,
         "paper_queue_rule": {"queue_size": q_rule, "memory_cap": q_cap, "bytes_per_queued_batch": per_batch_bytes,
                              "note": "Eq. 22-23 on mean prepare (sample+gather) / consume (aggregate) times of this run; "
                                      "the depth actually used is config.in_flight: the path is bound by the host link, "
