@@ -65,6 +65,12 @@ def _load():
     lib.orc_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, ctypes.c_int]
     lib.orc_mean_aggregate_backward.restype = ctypes.c_int
     lib.orc_mean_aggregate_backward.argtypes = [vp, vp, i64, i64, vp, i64, vp, i64, i64, ctypes.c_int]
+    lib.orc_build_cache_sampled.restype = ctypes.c_int
+    lib.orc_build_cache_sampled.argtypes = [i64, vp, i64, u64, vp, vp]
+    lib.orc_random_walk_scores.restype = ctypes.c_int
+    lib.orc_random_walk_scores.argtypes = [i64, vp, vp, vp, i64, vp, i64, vp]
+    lib.orc_build_cache_by_score.restype = ctypes.c_int
+    lib.orc_build_cache_by_score.argtypes = [i64, vp, i64, vp, vp]
     _lib = lib
     return lib
 
@@ -121,6 +127,52 @@ def build_cache(row_ptr, num_cached: int, feats: Optional[np.ndarray] = None) ->
                                     feats.shape[1] * feats.itemsize, _p(rows),
                                     rows.strides[0] if num_cached else 0)
     return Cache(ids, slot_of, rows)
+
+
+def _finish_cache(ids, slot_of, num_cached, n, feats):
+    ids, slot_of = ids[:num_cached], slot_of[:n]
+    rows = None
+    if feats is not None:
+        rows = np.zeros((num_cached, feats.shape[1]), dtype=feats.dtype)
+        _load().orc_fill_cache_rows(_p(ids), num_cached, _p(feats), feats.strides[0],
+                                    feats.shape[1] * feats.itemsize, _p(rows), rows.strides[0] if num_cached else 0)
+    return Cache(ids, slot_of, rows)
+
+
+def build_cache_sampled(row_ptr, num_cached: int, seed: int, feats: Optional[np.ndarray] = None) -> Cache:
+    """Membership drawn with probability proportional to degree, without replacement (Eq. 13)."""
+    rp = _i64(row_ptr)
+    n = rp.shape[0] - 1
+    ids = np.empty(max(1, num_cached), dtype=np.int64)
+    slot_of = np.empty(max(1, n), dtype=np.int32)
+    rc = _load().orc_build_cache_sampled(n, _p(rp), num_cached, ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF),
+                                         _p(ids), _p(slot_of))
+    if rc != 0:
+        raise ValueError(f"orc_build_cache_sampled failed ({rc})")
+    return _finish_cache(ids, slot_of, num_cached, n, feats)
+
+
+def random_walk_scores(row_ptr, col_idx, train_ids, step_fanouts: Sequence[int]) -> np.ndarray:
+    """P^(L) of Eq. 14-15; step_fanouts[l-1] is the fanout of walk step l."""
+    rp, ci, tr = _i64(row_ptr), _i64(col_idx), _i64(train_ids)
+    fo = _i64(list(step_fanouts))
+    n = rp.shape[0] - 1
+    out = np.zeros(max(1, n), dtype=np.float64)
+    rc = _load().orc_random_walk_scores(n, _p(rp), _p(ci), _p(tr), tr.shape[0], _p(fo), fo.shape[0], _p(out))
+    if rc != 0:
+        raise MemoryError("orc_random_walk_scores")
+    return out[:n]
+
+
+def build_cache_by_score(scores: np.ndarray, num_cached: int, feats: Optional[np.ndarray] = None) -> Cache:
+    sc = np.ascontiguousarray(scores, dtype=np.float64)
+    n = sc.shape[0]
+    ids = np.empty(max(1, num_cached), dtype=np.int64)
+    slot_of = np.empty(max(1, n), dtype=np.int32)
+    rc = _load().orc_build_cache_by_score(n, _p(sc), num_cached, _p(ids), _p(slot_of))
+    if rc != 0:
+        raise ValueError(f"orc_build_cache_by_score failed ({rc})")
+    return _finish_cache(ids, slot_of, num_cached, n, feats)
 
 
 # -------------------------------------------------------------- sampling

@@ -16,6 +16,13 @@
  *                            on the GPU; Eq. 13 ranks by in-degree).  Read
  *                            deterministically: the num_cached nodes of
  *                            highest degree, ties to the lower id.
+ *   - orc_build_cache_sampled : the same section, Eq. 13 read as the paper
+ *                            states it: cache membership is *drawn* with
+ *                            probability proportional to in-degree (weighted
+ *                            sampling without replacement, redrawn per epoch).
+ *   - orc_random_walk_scores / orc_build_cache_by_score : Eq. 14-15, the
+ *                            short-random-walk probabilities P^(L) used when
+ *                            the training set is a small part of the graph.
  *   - orc_sample_blocks    : Sec. III-A "Node-wise Sampling", GraphSAGE
  *                            paragraph: for every node of a layer a fixed
  *                            number s_node of its neighbours is drawn
@@ -391,5 +398,121 @@ int orc_mean_aggregate_backward(const int64_t *indptr, const int32_t *indices, i
             else ((float *)grad_x)[s * gx_stride + c] = (float)v;
         }
     free(acc);
+    return 0;
+}
+
+/* --------------------------------------------- sampled / random-walk cache */
+
+typedef struct { uint64_t key; int64_t id; } orc_key_id;
+
+static int cmp_key_id(const void *a, const void *b)
+{
+    const orc_key_id *x = a, *y = b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return 0;
+}
+
+/* Domain tag that keeps the cache draw apart from every block's neighbour draw. */
+#define ORC_CACHE_LAYER (-1)
+
+/*
+ * Cache membership drawn with probability proportional to in-degree (Eq. 13),
+ * without replacement.  Every adjacency slot of a node is a ticket with an
+ * independent uniform 64-bit key; a node's key is the smallest of its tickets
+ * (nodes without neighbours get the largest possible key); the num_cached
+ * nodes with the smallest (key, id) are cached, slot s holding the s-th
+ * smallest.  The minimum of d independent uniforms is distributed as an
+ * exponential race with rate d, so this is weighted sampling without
+ * replacement with weight = degree (Efraimidis and Spirakis 2006), in integer
+ * arithmetic only.
+ */
+int orc_build_cache_sampled(int64_t num_nodes, const int64_t *row_ptr, int64_t num_cached,
+                            uint64_t seed, int64_t *cached_ids, int32_t *slot_of)
+{
+    if (num_cached < 0 || num_cached > num_nodes) return -1;
+    orc_key_id *all = malloc((size_t)(num_nodes > 0 ? num_nodes : 1) * sizeof *all);
+    if (!all) return -2;
+    for (int64_t v = 0; v < num_nodes; ++v) {
+        int64_t d = row_ptr[v + 1] - row_ptr[v];
+        uint64_t best = ~(uint64_t)0;
+        for (int64_t j = 0; j < d; ++j) {
+            uint64_t k = orc_key(seed, ORC_CACHE_LAYER, v, j);
+            if (k < best) best = k;
+        }
+        all[v].key = best;
+        all[v].id = v;
+    }
+    qsort(all, (size_t)num_nodes, sizeof *all, cmp_key_id);
+    for (int64_t v = 0; v < num_nodes; ++v) slot_of[v] = -1;
+    for (int64_t s = 0; s < num_cached; ++s) {
+        cached_ids[s] = all[s].id;
+        slot_of[all[s].id] = (int32_t)s;
+    }
+    free(all);
+    return 0;
+}
+
+/*
+ * Short-random-walk scores (Eq. 14-15): P^(0) = 1/|V_t| on the training
+ * nodes, 0 elsewhere; P^(l) = (D A + I) P^(l-1), D = diag(d),
+ * d_i = min(fanout_l, deg_i) / deg_i (the share of a node's neighbours that
+ * sampling keeps; 0 for a node without neighbours), for l = 1..L, taken as
+ * written with A's row i = the adjacency row of node i:
+ *   P^(l)[i] = P^(l-1)[i] + d_i * sum_{j in row(i)} P^(l-1)[j].
+ * Double precision, each row summed in adjacency order, product and sum
+ * rounded separately.  step_fanouts[l-1] is the fanout of walk step l.
+ */
+int orc_random_walk_scores(int64_t num_nodes, const int64_t *row_ptr, const int64_t *col_idx,
+                           const int64_t *train_ids, int64_t num_train, const int64_t *step_fanouts,
+                           int64_t num_steps, double *scores)
+{
+    double *cur = calloc((size_t)(num_nodes > 0 ? num_nodes : 1), sizeof *cur);
+    double *next = calloc((size_t)(num_nodes > 0 ? num_nodes : 1), sizeof *next);
+    if (!cur || !next) { free(cur); free(next); return -2; }
+    for (int64_t t = 0; t < num_train; ++t) cur[train_ids[t]] = 1.0 / (double)num_train;
+    for (int64_t l = 0; l < num_steps; ++l) {
+        for (int64_t i = 0; i < num_nodes; ++i) {
+            int64_t b = row_ptr[i], e = row_ptr[i + 1], deg = e - b;
+            double acc = 0.0;
+            for (int64_t p = b; p < e; ++p) acc += cur[col_idx[p]];
+            double keep = deg < step_fanouts[l] ? (double)deg : (double)step_fanouts[l];
+            double d = deg > 0 ? keep / (double)deg : 0.0;
+            volatile double prod = d * acc;           /* rounded on its own, never fused */
+            next[i] = cur[i] + prod;
+        }
+        double *t = cur; cur = next; next = t;
+    }
+    for (int64_t i = 0; i < num_nodes; ++i) scores[i] = cur[i];
+    free(cur);
+    free(next);
+    return 0;
+}
+
+typedef struct { double score; int64_t id; } orc_score_id;
+
+static int cmp_score_desc_id_asc(const void *a, const void *b)
+{
+    const orc_score_id *x = a, *y = b;
+    if (x->score != y->score) return x->score > y->score ? -1 : 1;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return 0;
+}
+
+/* The num_cached nodes of highest score, ties to the lower id; slot s = s-th ranked. */
+int orc_build_cache_by_score(int64_t num_nodes, const double *scores, int64_t num_cached,
+                             int64_t *cached_ids, int32_t *slot_of)
+{
+    if (num_cached < 0 || num_cached > num_nodes) return -1;
+    orc_score_id *all = malloc((size_t)(num_nodes > 0 ? num_nodes : 1) * sizeof *all);
+    if (!all) return -2;
+    for (int64_t v = 0; v < num_nodes; ++v) { all[v].score = scores[v]; all[v].id = v; }
+    qsort(all, (size_t)num_nodes, sizeof *all, cmp_score_desc_id_asc);
+    for (int64_t v = 0; v < num_nodes; ++v) slot_of[v] = -1;
+    for (int64_t s = 0; s < num_cached; ++s) {
+        cached_ids[s] = all[s].id;
+        slot_of[all[s].id] = (int32_t)s;
+    }
+    free(all);
     return 0;
 }

@@ -473,3 +473,93 @@ def test_backward_closed_forms():
     g = np.array([[6.0], [100.0], [9.0]], dtype=np.float32)      # the empty row's gradient goes nowhere
     got = oracle.mean_aggregate_backward(indptr, indices, 5, g)
     assert got[:, 0].tolist() == [6.0, 3.0, 0.0, 6.0, 0.0]
+
+
+# ------------------------------------------------------------ sampled and random-walk cache
+
+def test_sampled_cache_equals_python_restatement():
+    rp, _ = tiny_graph(400, 5000, seed=12)
+    n = len(rp) - 1
+    for seed in (0, 99):
+        keys = []
+        for v in range(n):
+            d = int(rp[v + 1] - rp[v])
+            keys.append((min((py_key(seed, M64, v, j) for j in range(d)), default=M64), v))   # layer tag -1
+        order = [v for _, v in sorted(keys)]
+        for num_cached in (0, 1, 57, n):
+            c = oracle.build_cache_sampled(rp, num_cached, seed)
+            assert c.cached_ids.tolist() == order[:num_cached]
+            want = np.full(n, -1, dtype=np.int32)
+            want[order[:num_cached]] = np.arange(num_cached)
+            assert np.array_equal(c.slot_of, want)
+    assert oracle.build_cache_sampled(rp, 57, 1).cached_ids.tolist() != oracle.build_cache_sampled(rp, 57, 2).cached_ids.tolist()
+
+
+def test_sampled_cache_is_weighted_sampling_without_replacement():
+    """Eq. 13: membership probability proportional to in-degree.  On a 5-node degree sequence the
+    first slot must be node a with probability w_a/W and every pair {a,b} must appear with the
+    successive-sampling probability w_a/W*w_b/(W-w_a) + w_b/W*w_a/(W-w_b)."""
+    w = np.array([1, 2, 3, 4, 2, 0])                              # node 5 has no neighbours
+    rp = np.concatenate([[0], np.cumsum(w)]).astype(np.int64)
+    W = w.sum()
+    trials = 40000
+    first = np.zeros(6)
+    pairs = {}
+    for seed in range(trials):
+        ids = oracle.build_cache_sampled(rp, 2, seed).cached_ids.tolist()
+        first[ids[0]] += 1
+        key = tuple(sorted(ids))
+        pairs[key] = pairs.get(key, 0) + 1
+    p1 = w / W
+    assert first[5] == 0
+    assert np.all(np.abs(first - trials * p1) < 4.5 * np.sqrt(trials * p1 * (1 - p1)) + 1e-9)
+    for a in range(5):
+        for b in range(a + 1, 5):
+            p = w[a] / W * w[b] / (W - w[a]) + w[b] / W * w[a] / (W - w[b])
+            cnt = pairs.get((a, b), 0)
+            assert abs(cnt - trials * p) < 4.5 * math.sqrt(trials * p * (1 - p)), (a, b, cnt, trials * p)
+
+
+def test_random_walk_scores_equal_dense_matrix_power():
+    rp, ci = tiny_graph(250, 2500, seed=13)
+    n = len(rp) - 1
+    A = np.zeros((n, n))
+    for i in range(n):
+        A[i, ci[rp[i]:rp[i + 1]]] = 1.0
+    deg = np.diff(rp).astype(np.float64)
+    train = np.array([3, 17, 100, 249, 42], dtype=np.int64)
+    for fanouts in ([5], [5, 5], [4, 9, 2], [1000, 1000]):
+        P = np.zeros(n)
+        P[train] = 1.0 / len(train)
+        for k in fanouts:
+            d = np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0)
+            P = (np.diag(d) @ A + np.eye(n)) @ P
+        got = oracle.random_walk_scores(rp, ci, train, fanouts)
+        assert np.allclose(got, P, rtol=1e-12, atol=1e-15)
+    # fanout above every degree: D = I, so the scores count walks: (A + I)^L P0
+    got = oracle.random_walk_scores(rp, ci, train, [10 ** 6, 10 ** 6])
+    P0 = np.zeros(n)
+    P0[train] = 1.0 / len(train)
+    assert np.allclose(got, np.linalg.matrix_power(A + np.eye(n), 2) @ P0, rtol=1e-12)
+    # zero steps: the training distribution itself
+    assert np.array_equal(oracle.random_walk_scores(rp, ci, train, []), P0)
+
+
+def test_random_walk_worked_by_hand():
+    # rows: 0:[1,2] 1:[0] 2:[0,3] 3:[]; training set {0}; fanout 1 -> d = [1/2, 1, 1/2, 0]
+    rp = np.array([0, 2, 3, 5, 5], dtype=np.int64)
+    ci = np.array([1, 2, 0, 0, 3], dtype=np.int64)
+    assert oracle.random_walk_scores(rp, ci, [0], [1]).tolist() == [1.0, 1.0, 0.5, 0.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1]).tolist() == [1.75, 2.0, 1.0, 0.0]
+
+
+def test_cache_by_score_equals_lexsort():
+    rng = np.random.default_rng(14)
+    scores = np.round(rng.random(500), 2)                        # many ties
+    order = np.lexsort((np.arange(500), -scores))
+    for num_cached in (0, 1, 123, 500):
+        c = oracle.build_cache_by_score(scores, num_cached)
+        assert np.array_equal(c.cached_ids, order[:num_cached])
+        want = np.full(500, -1, dtype=np.int32)
+        want[order[:num_cached]] = np.arange(num_cached)
+        assert np.array_equal(c.slot_of, want)
