@@ -189,6 +189,44 @@ int mqg_ctx_kernel_names(mqg_ctx *ctx, char *buf, int64_t buf_len);
 int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream);
 
 /*
+ * The other two ways the paper fills the cache (Sec. III "Feature Cache").
+ *   MQG_CACHE_TOP_DEGREE      what mqg_build_cache does.
+ *   MQG_CACHE_DEGREE_SAMPLED  Eq. 13 as stated: membership is drawn with probability proportional
+ *                             to in-degree, without replacement - a fresh draw for every `seed`
+ *                             (the paper rebuilds the cache every epoch).  Every adjacency slot j
+ *                             of node v is a ticket with the uniform key
+ *                             mix(mix(mix(mix(seed + G) ^ ~0) ^ v) ^ j); a node's key is the minimum
+ *                             over its tickets (all ones without neighbours); the num_cached nodes
+ *                             with the smallest (key, id) are cached, slot s = s-th smallest.
+ *   MQG_CACHE_RANDOM_WALK     Eq. 14-15, for training sets that are a small part of the graph:
+ *                             P(0) = 1/num_train on train_ids, 0 elsewhere;
+ *                             P(l)[i] = P(l-1)[i] + d_i * sum_{j in row(i)} P(l-1)[j],
+ *                             d_i = min(step_fanouts[l-1], deg_i) / deg_i, l = 1..num_steps, in
+ *                             double precision with every row summed in adjacency order; the
+ *                             num_cached nodes of highest P(num_steps) are cached (ties: lower id).
+ *                             scores_out (device double [num_nodes], may be NULL) receives
+ *                             P(num_steps).  Membership is the deterministic top of the score, not
+ *                             a draw from it.
+ * train_ids: device [num_train], graph idx_type, ids in [0, num_nodes); step_fanouts: host.
+ */
+typedef enum { MQG_CACHE_TOP_DEGREE = 0, MQG_CACHE_DEGREE_SAMPLED = 1, MQG_CACHE_RANDOM_WALK = 2 } mqg_cache_policy;
+
+typedef struct mqg_cache_plan {
+    int32_t policy;                      /* mqg_cache_policy                             */
+    int32_t num_steps;                   /* RANDOM_WALK: number of steps L, 0..MQG_MAX_LAYERS */
+    uint64_t seed;                       /* DEGREE_SAMPLED                               */
+    const void *train_ids;               /* RANDOM_WALK                                  */
+    int64_t num_train;
+    const int32_t *step_fanouts;         /* RANDOM_WALK: host [num_steps], each >= 1     */
+    double *scores_out;                  /* RANDOM_WALK: optional                        */
+} mqg_cache_plan;
+
+/* mqg_build_cache with a choice of policy; plan == NULL means MQG_CACHE_TOP_DEGREE.  Otherwise as
+ * mqg_build_cache (buffers in *cache, temporary device memory, synchronous with the host). */
+int mqg_build_cache_ex(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, const mqg_cache_plan *plan,
+                       mqg_stream stream);
+
+/*
  * L-hop fixed-fanout node-wise neighbour sampling into blocks (paper Sec.
  * III-A, GraphSAGE paragraph: a fixed number of neighbours of every node of a
  * layer, drawn uniformly at random, a fresh draw per layer).

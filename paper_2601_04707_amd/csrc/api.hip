@@ -258,7 +258,7 @@ static int check_graph(mqg_ctx *ctx, const mqg_graph *g, const char *who) {
     return MQG_OK;
 }
 
-int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream) {
+int mqg_build_cache_ex(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, const mqg_cache_plan *plan, mqg_stream stream) {
     if (!ctx) return MQG_ERR_INVALID_ARG;
     int rc = check_graph(ctx, g, "mqg_build_cache");
     if (rc != MQG_OK) return rc;
@@ -271,7 +271,23 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: NULL cache buffers");
     if (cache->feat_stride < cache->dim || cache->cache_stride < cache->dim)
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: stride below dim");
-    return mqg::run_build_cache(ctx, g, cache, static_cast<hipStream_t>(stream));
+    if (plan) {
+        if (plan->policy != MQG_CACHE_TOP_DEGREE && plan->policy != MQG_CACHE_DEGREE_SAMPLED && plan->policy != MQG_CACHE_RANDOM_WALK)
+            return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: unknown policy");
+        if (plan->policy == MQG_CACHE_RANDOM_WALK) {
+            if (plan->num_steps < 0 || plan->num_steps > MQG_MAX_LAYERS) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: num_steps outside 0..MQG_MAX_LAYERS");
+            if (plan->num_train < 0 || (plan->num_train > 0 && !plan->train_ids)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: bad training set");
+            if (plan->num_steps > 0 && !plan->step_fanouts) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: step_fanouts is NULL");
+            for (int l = 0; l < plan->num_steps; ++l)
+                if (plan->step_fanouts[l] < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: step fanout below 1");
+            if (g->num_edges > 0 && !g->col_idx) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: col_idx is NULL");
+        }
+    }
+    return mqg::run_build_cache(ctx, g, cache, plan, static_cast<hipStream_t>(stream));
+}
+
+int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream) {
+    return mqg_build_cache_ex(ctx, g, cache, nullptr, stream);
 }
 
 int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,

@@ -1,7 +1,15 @@
 // Hot-node feature cache construction (paper Sec. III "Feature Cache": the features of a small
-// set of high-degree nodes are preloaded on the GPU; Eq. 13 weights nodes by in-degree).
-// Deterministic reading: rank all nodes by (degree descending, id ascending) and cache the first
-// num_cached; slot s holds the s-th ranked node.
+// set of high-degree nodes are preloaded on the GPU).  Three ways to rank the nodes; the first
+// num_cached of the ranking are cached, slot s holding the s-th ranked node:
+//   top degree       (degree descending, id ascending) - deterministic reading of Eq. 13
+//   degree-sampled   Eq. 13 as stated: membership drawn with probability proportional to in-degree,
+//                    without replacement.  Every adjacency slot is a ticket with a uniform 64-bit
+//                    key, a node's key is the minimum over its tickets (k_ticket_keys), nodes are
+//                    ranked by (key, id) ascending - an exponential race in integer arithmetic
+//   random walk      Eq. 14-15: P^(l) = (D A + I) P^(l-1) from the training set (k_rw_step, double
+//                    precision, every row summed in adjacency order so that the result does not
+//                    depend on the schedule), ranked by (P^(L) descending, id ascending)
+// 64-bit keys are ordered by two stable 32-bit radix sorts (low word, then high word).
 //
 // The ranking is a stable least-significant-digit radix sort of (max_degree - degree) with the
 // node id as payload: ids start ascending, stable passes keep them ascending inside equal
@@ -52,6 +60,138 @@ k_sort_keys(uint32_t *__restrict__ keys, int32_t *__restrict__ vals, int64_t n, 
     }
 }
 
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
+
+uint64_t host_mix64(uint64_t z) {
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ uint64_t wave_min_u64(uint64_t v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        uint64_t o = __shfl_xor(v, off, 64);
+        v = o < v ? o : v;
+    }
+    return v;
+}
+
+// key64[v] = min over the adjacency slots j of node v of mix(mix(tag_hash ^ v) ^ j); all ones for
+// a node without neighbours.  A lane owns a node; rows of up to 32 slots are walked by their
+// lane, longer rows by the whole wavefront, one after the other.
+template <typename PtrT>
+__global__ void __launch_bounds__(kBlock)
+k_ticket_keys(const PtrT *__restrict__ row_ptr, int64_t n, uint64_t tag_hash, uint64_t *__restrict__ key64) {
+    const int lane = lane_id();
+    const int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int d = 0;
+    if (v < n) d = static_cast<int>(row_ptr[v + 1] - row_ptr[v]);
+    const uint64_t hv = mix64(tag_hash ^ static_cast<uint64_t>(v));
+    uint64_t best = ~uint64_t(0);
+    if (d <= 32)
+        for (int j = 0; j < d; ++j) {
+            uint64_t k = mix64(hv ^ static_cast<uint64_t>(j));
+            best = k < best ? k : best;
+        }
+    uint64_t big = ballot64(d > 32);
+    while (big) {
+        const int l = __ffsll(static_cast<long long>(big)) - 1;
+        big &= big - 1;
+        const int dl = static_cast<int>(readlane32(static_cast<uint32_t>(d), l));
+        const uint64_t hl = readlane64(hv, l);
+        uint64_t m = ~uint64_t(0);
+        for (int j = lane; j < dl; j += kWave) {
+            uint64_t k = mix64(hl ^ static_cast<uint64_t>(j));
+            m = k < m ? k : m;
+        }
+        m = wave_min_u64(m);
+        if (lane == l) best = m;
+    }
+    if (v < n) key64[v] = best;
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_rw_seed(const IdxT *__restrict__ train_ids, int64_t num_train, double *__restrict__ p) {
+    int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (t < num_train) p[train_ids[t]] = 1.0 / static_cast<double>(num_train);
+}
+
+// One step of P_next[i] = P[i] + d_i * sum_{j in row(i)} P[j], d_i = min(fanout, deg_i) / deg_i.
+// Every row is summed strictly in adjacency order (rows of up to 16 entries by their lane, longer
+// rows by the wavefront: 64 values are fetched in parallel and then added one after the other),
+// product and sum are rounded separately: bit for bit the plain sequential loop.
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n, int fanout,
+          const double *__restrict__ cur, double *__restrict__ next) {
+#pragma clang fp contract(off)                             // d * acc and the sum are rounded separately
+    const int lane = lane_id();
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int64_t b = 0;
+    int deg = 0;
+    if (i < n) {
+        b = static_cast<int64_t>(row_ptr[i]);
+        deg = static_cast<int>(static_cast<int64_t>(row_ptr[i + 1]) - b);
+    }
+    double acc = 0.0;
+    if (deg <= 16)
+        for (int p = 0; p < deg; ++p) acc = acc + cur[col_idx[b + p]];
+    uint64_t big = ballot64(deg > 16);
+    while (big) {
+        const int l = __ffsll(static_cast<long long>(big)) - 1;
+        big &= big - 1;
+        const int dl = static_cast<int>(readlane32(static_cast<uint32_t>(deg), l));
+        const int64_t bl = static_cast<int64_t>(readlane64(static_cast<uint64_t>(b), l));
+        double a = 0.0;
+        for (int c0 = 0; c0 < dl; c0 += kWave) {
+            const int m = dl - c0 < kWave ? dl - c0 : kWave;
+            double val = 0.0;
+            if (lane < m) val = cur[col_idx[bl + c0 + lane]];
+            const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(val));
+            for (int t = 0; t < m; ++t) a = a + __longlong_as_double(static_cast<long long>(readlane64(bits, t)));
+        }
+        if (lane == l) acc = a;
+    }
+    if (i < n) {
+        const double keep = deg < fanout ? static_cast<double>(deg) : static_cast<double>(fanout);
+        const double d = deg > 0 ? keep / static_cast<double>(deg) : 0.0;
+        const double prod = d * acc;                       // plain operators: the pragma above governs them
+        next[i] = cur[i] + prod;
+    }
+}
+
+// ascending radix order of ~bits(score) = descending score (scores are non-negative)
+__global__ void __launch_bounds__(kBlock)
+k_score_keys(const double *__restrict__ score, int64_t n, uint64_t *__restrict__ key64) {
+    int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (v < n) key64[v] = ~static_cast<uint64_t>(__double_as_longlong(score[v]));
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_split_low(const uint64_t *__restrict__ key64, int64_t n, uint32_t *__restrict__ lo, int32_t *__restrict__ ids) {
+    int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (v < n) {
+        lo[v] = static_cast<uint32_t>(key64[v]);
+        ids[v] = static_cast<int32_t>(v);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_gather_high(const uint64_t *__restrict__ key64, const int32_t *__restrict__ ids_in, int64_t n,
+              uint32_t *__restrict__ hi, int32_t *__restrict__ ids_out) {
+    int64_t p = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (p < n) {
+        int32_t v = ids_in[p];
+        hi[p] = static_cast<uint32_t>(key64[v] >> 32);
+        ids_out[p] = v;
+    }
+}
+
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_assign_slots(const int32_t *__restrict__ ranked, int64_t num_cached, int32_t *__restrict__ slot_of,
@@ -85,55 +225,131 @@ struct Temp {
 
 }  // namespace
 
-int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t s) {
+// node ids ranked by ascending 64-bit key (ties: ascending id), into *ranked (a buffer owned by tmp)
+static int rank_by_key64(mqg_ctx *ctx, Temp &tmp, const uint64_t *key64, int64_t n, const int32_t **ranked, hipStream_t s) {
+    uint32_t *lo, *hi;
+    int32_t *ids0, *ids1;
+    RadixBufs rb;
+    bool ok = tmp.alloc(&lo, n) && tmp.alloc(&hi, n) && tmp.alloc(&ids0, n) && tmp.alloc(&ids1, n) &&
+              tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) && tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) &&
+              tmp.alloc(&rb.hist, radix_hist_len(n)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles(n));
+    if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
+    const int ngrid = static_cast<int>(ceil_div(n, kBlock));
+    MQG_LAUNCH(ctx, "k_split_low", s, (k_split_low<<<ngrid, kBlock, 0, s>>>(key64, n, lo, ids0)));
+    int which = -1;
+    int rc = radix_sort_pairs(ctx, lo, ids0, rb, n, nullptr, 32, s, &which);
+    if (rc != MQG_OK) return rc;
+    MQG_LAUNCH(ctx, "k_gather_high", s, (k_gather_high<<<ngrid, kBlock, 0, s>>>(key64, rb.vals[which], n, hi, ids1)));
+    rc = radix_sort_pairs(ctx, hi, ids1, rb, n, nullptr, 32, s, &which);
+    if (rc != MQG_OK) return rc;
+    *ranked = rb.vals[which];
+    return MQG_OK;
+}
+
+int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_cache_plan *plan, hipStream_t s) {
     const int64_t n = g->num_nodes;
     const int64_t elt = c->dtype == MQG_F16 ? 2 : 4;
+    const int policy = plan ? plan->policy : MQG_CACHE_TOP_DEGREE;
     hipError_t e = hipMemsetAsync(c->slot_of, 0xFF, static_cast<size_t>(std::max<int64_t>(n, 1)) * sizeof(int32_t), s);
     if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
-    if (n == 0 || c->num_cached == 0) {
+    const bool want_scores = policy == MQG_CACHE_RANDOM_WALK && plan->scores_out;
+    if (n == 0 || (c->num_cached == 0 && !want_scores)) {
         e = hipStreamSynchronize(s);
         return e == hipSuccess ? MQG_OK : fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
     }
 
     Temp tmp;
-    uint32_t *keys_a, *max_deg_dev;
-    int32_t *vals_a;
-    int64_t *count_dev;
-    RadixBufs rb;
-    bool ok = tmp.alloc(&keys_a, n) && tmp.alloc(&vals_a, n) && tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) &&
-              tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) && tmp.alloc(&rb.hist, radix_hist_len(n)) &&
-              tmp.alloc(&rb.tile_sums, radix_scan_tiles(n)) && tmp.alloc(&max_deg_dev, 1) && tmp.alloc(&count_dev, 1);
-    if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
-
     const int ngrid = static_cast<int>(ceil_div(n, kBlock));
-    e = hipMemsetAsync(max_deg_dev, 0, sizeof(uint32_t), s);
-    if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
-    if (g->ptr_type == MQG_I64)
-        MQG_LAUNCH(ctx, "k_degrees", s, (k_degrees<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, keys_a, max_deg_dev)));
-    else
-        MQG_LAUNCH(ctx, "k_degrees", s, (k_degrees<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, keys_a, max_deg_dev)));
-    uint32_t max_deg = 0;
-    e = hipMemcpyAsync(&max_deg, max_deg_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, s);
-    if (e == hipSuccess) e = hipStreamSynchronize(s);
-    if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
+    const int32_t *ranked = nullptr;
 
-    MQG_LAUNCH(ctx, "k_sort_keys", s, (k_sort_keys<<<ngrid, kBlock, 0, s>>>(keys_a, vals_a, n, max_deg)));
-    int bits = 0;
-    while (bits < 32 && (max_deg >> bits) != 0) bits += 8;
-    int which = -1;
-    int rc0 = radix_sort_pairs(ctx, keys_a, vals_a, rb, n, nullptr, bits, s, &which);
-    if (rc0 != MQG_OK) return rc0;
-    const int32_t *vin = which < 0 ? vals_a : rb.vals[which];
-    // vin: node ids by (degree descending, id ascending)
-    const int cgrid = static_cast<int>(ceil_div(c->num_cached, kBlock));
-    if (g->idx_type == MQG_I64)
-        MQG_LAUNCH(ctx, "k_assign_slots", s, (k_assign_slots<int64_t><<<cgrid, kBlock, 0, s>>>(vin, c->num_cached, c->slot_of, static_cast<int64_t *>(c->cached_ids))));
-    else
-        MQG_LAUNCH(ctx, "k_assign_slots", s, (k_assign_slots<int32_t><<<cgrid, kBlock, 0, s>>>(vin, c->num_cached, c->slot_of, static_cast<int32_t *>(c->cached_ids))));
-    MQG_LAUNCH(ctx, "k_store_i64", s, (k_store_i64<<<1, 64, 0, s>>>(count_dev, c->num_cached)));
-    int rc = gather_direct_i32(ctx, vin, count_dev, c->num_cached, c->feats, c->feat_stride * elt, c->cache_rows,
-                               c->cache_stride * elt, int64_t(c->dim) * elt, s);
-    if (rc != MQG_OK) return rc;
+    if (policy == MQG_CACHE_TOP_DEGREE) {
+        uint32_t *keys_a, *max_deg_dev;
+        int32_t *vals_a;
+        RadixBufs rb;
+        bool ok = tmp.alloc(&keys_a, n) && tmp.alloc(&vals_a, n) && tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) &&
+                  tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) && tmp.alloc(&rb.hist, radix_hist_len(n)) &&
+                  tmp.alloc(&rb.tile_sums, radix_scan_tiles(n)) && tmp.alloc(&max_deg_dev, 1);
+        if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
+        e = hipMemsetAsync(max_deg_dev, 0, sizeof(uint32_t), s);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
+        if (g->ptr_type == MQG_I64)
+            MQG_LAUNCH(ctx, "k_degrees", s, (k_degrees<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, keys_a, max_deg_dev)));
+        else
+            MQG_LAUNCH(ctx, "k_degrees", s, (k_degrees<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, keys_a, max_deg_dev)));
+        uint32_t max_deg = 0;
+        e = hipMemcpyAsync(&max_deg, max_deg_dev, sizeof(uint32_t), hipMemcpyDeviceToHost, s);
+        if (e == hipSuccess) e = hipStreamSynchronize(s);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
+        MQG_LAUNCH(ctx, "k_sort_keys", s, (k_sort_keys<<<ngrid, kBlock, 0, s>>>(keys_a, vals_a, n, max_deg)));
+        int bits = 0;
+        while (bits < 32 && (max_deg >> bits) != 0) bits += 8;
+        int which = -1;
+        int rc0 = radix_sort_pairs(ctx, keys_a, vals_a, rb, n, nullptr, bits, s, &which);
+        if (rc0 != MQG_OK) return rc0;
+        ranked = which < 0 ? vals_a : rb.vals[which];
+    } else if (policy == MQG_CACHE_DEGREE_SAMPLED) {
+        uint64_t *key64;
+        if (!tmp.alloc(&key64, n)) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
+        // the tag keeps this draw apart from every block's neighbour draw (block index -1)
+        const uint64_t tag_hash = host_mix64(host_mix64(plan->seed + kGolden) ^ ~uint64_t(0));
+        if (g->ptr_type == MQG_I64)
+            MQG_LAUNCH(ctx, "k_ticket_keys", s, (k_ticket_keys<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, tag_hash, key64)));
+        else
+            MQG_LAUNCH(ctx, "k_ticket_keys", s, (k_ticket_keys<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, tag_hash, key64)));
+        int rc0 = rank_by_key64(ctx, tmp, key64, n, &ranked, s);
+        if (rc0 != MQG_OK) return rc0;
+    } else {  // MQG_CACHE_RANDOM_WALK
+        double *pa, *pb;
+        uint64_t *key64;
+        if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&key64, n)))
+            return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
+        e = hipMemsetAsync(pa, 0, static_cast<size_t>(n) * sizeof(double), s);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
+        if (plan->num_train > 0) {
+            const int tgrid = static_cast<int>(ceil_div(plan->num_train, kBlock));
+            if (g->idx_type == MQG_I64)
+                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int64_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(plan->train_ids), plan->num_train, pa)));
+            else
+                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int32_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(plan->train_ids), plan->num_train, pa)));
+        }
+        double *cur = pa, *next = pb;
+        for (int l = 0; l < plan->num_steps; ++l) {
+            const int fo = plan->step_fanouts[l];
+            const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
+            if (p64 && i64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, fo, cur, next)));
+            else if (p64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, fo, cur, next)));
+            else if (i64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, fo, cur, next)));
+            else
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, fo, cur, next)));
+            std::swap(cur, next);
+        }
+        if (plan->scores_out) {
+            e = hipMemcpyAsync(plan->scores_out, cur, static_cast<size_t>(n) * sizeof(double), hipMemcpyDeviceToDevice, s);
+            if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
+        }
+        if (c->num_cached > 0) {
+            MQG_LAUNCH(ctx, "k_score_keys", s, (k_score_keys<<<ngrid, kBlock, 0, s>>>(cur, n, key64)));
+            int rc0 = rank_by_key64(ctx, tmp, key64, n, &ranked, s);
+            if (rc0 != MQG_OK) return rc0;
+        }
+    }
+
+    if (c->num_cached > 0) {
+        int64_t *count_dev;
+        if (!tmp.alloc(&count_dev, 1)) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
+        const int cgrid = static_cast<int>(ceil_div(c->num_cached, kBlock));
+        if (g->idx_type == MQG_I64)
+            MQG_LAUNCH(ctx, "k_assign_slots", s, (k_assign_slots<int64_t><<<cgrid, kBlock, 0, s>>>(ranked, c->num_cached, c->slot_of, static_cast<int64_t *>(c->cached_ids))));
+        else
+            MQG_LAUNCH(ctx, "k_assign_slots", s, (k_assign_slots<int32_t><<<cgrid, kBlock, 0, s>>>(ranked, c->num_cached, c->slot_of, static_cast<int32_t *>(c->cached_ids))));
+        MQG_LAUNCH(ctx, "k_store_i64", s, (k_store_i64<<<1, 64, 0, s>>>(count_dev, c->num_cached)));
+        int rc = gather_direct_i32(ctx, ranked, count_dev, c->num_cached, c->feats, c->feat_stride * elt, c->cache_rows,
+                                   c->cache_stride * elt, int64_t(c->dim) * elt, s);
+        if (rc != MQG_OK) return rc;
+    }
     e = hipStreamSynchronize(s);                     // temporaries are freed on return
     if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
     return MQG_OK;

@@ -111,7 +111,7 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
                int64_t *stats, hipStream_t s);
 int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
                        int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
-int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, hipStream_t s);
+int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_cache_plan *plan, hipStream_t s);
 int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *grad_out, int64_t go_stride,
                                 void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);

@@ -23,12 +23,13 @@ MQG_F32, MQG_F16 = 0, 1
 MQG_I32, MQG_I64 = 0, 1
 MQG_OPT_FORCE_SLOW_SELECT, MQG_OPT_PROFILE, MQG_OPT_MISS_INFLIGHT_BYTES, MQG_OPT_HEAVY_DEGREE = 1, 2, 3, 4
 MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
+MQG_CACHE_TOP_DEGREE, MQG_CACHE_DEGREE_SAMPLED, MQG_CACHE_RANDOM_WALK = 0, 1, 2
 
 EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
-    "mqg_queue_size",
+    "mqg_queue_size", "mqg_build_cache_ex",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -56,6 +57,11 @@ class CBlock(ctypes.Structure):
                 ("indptr", _vp), ("indices", _vp), ("sizes", _vp)]
 
 
+class CCachePlan(ctypes.Structure):
+    _fields_ = [("policy", _i32), ("num_steps", _i32), ("seed", ctypes.c_uint64), ("train_ids", _vp),
+                ("num_train", _i64), ("step_fanouts", ctypes.POINTER(_i32)), ("scores_out", _vp)]
+
+
 lib.mqg_version.restype = _i32
 lib.mqg_version.argtypes = []
 lib.mqg_ctx_create.restype = ctypes.c_int
@@ -74,6 +80,8 @@ lib.mqg_ctx_kernel_names.restype = ctypes.c_int
 lib.mqg_ctx_kernel_names.argtypes = [_vp, ctypes.c_char_p, _i64]
 lib.mqg_build_cache.restype = ctypes.c_int
 lib.mqg_build_cache.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), _vp]
+lib.mqg_build_cache_ex.restype = ctypes.c_int
+lib.mqg_build_cache_ex.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), ctypes.POINTER(CCachePlan), _vp]
 lib.mqg_sample_blocks.restype = ctypes.c_int
 lib.mqg_sample_blocks.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32,
                                   ctypes.c_uint64, ctypes.POINTER(CBlock), _vp]
@@ -246,6 +254,21 @@ class Cache:
 
 def mqg_build_cache(ctx: Context, graph: Graph, cache: Cache, stream=None) -> None:
     ctx.check(lib.mqg_build_cache(ctx.h, ctypes.byref(graph.c), ctypes.byref(cache.c), _stream(stream)))
+
+
+def mqg_build_cache_ex(ctx: Context, graph: Graph, cache: Cache, policy: int, *, seed: int = 0,
+                       train_ids: Optional[torch.Tensor] = None, step_fanouts: Sequence[int] = (),
+                       scores_out: Optional[torch.Tensor] = None, stream=None) -> None:
+    """Cache filled by one of the three policies (MQG_CACHE_*)."""
+    fo = (_i32 * max(1, len(step_fanouts)))(*step_fanouts)
+    if train_ids is not None:
+        assert train_ids.is_cuda and train_ids.dtype == graph.idx_dtype and train_ids.is_contiguous()
+    if scores_out is not None:
+        assert scores_out.is_cuda and scores_out.dtype == torch.float64 and scores_out.numel() >= graph.num_nodes
+    plan = CCachePlan(policy, len(step_fanouts), seed & 0xFFFFFFFFFFFFFFFF, _ptr(train_ids),
+                      0 if train_ids is None else train_ids.numel(), fo, _ptr(scores_out))
+    ctx.check(lib.mqg_build_cache_ex(ctx.h, ctypes.byref(graph.c), ctypes.byref(cache.c), ctypes.byref(plan),
+                                     _stream(stream)))
 
 
 def mqg_sample_blocks(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequence[int], rng_seed: int,
