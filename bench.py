@@ -35,6 +35,9 @@ def main() -> int:
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--cache-pct", type=int, default=None)
+    ap.add_argument("--cache-policy", choices=["top", "sampled", "walk"], default="top",
+                    help="how the cache is filled: top degree (the workloads' definition), drawn in proportion "
+                         "to degree (paper Eq. 13), or by random-walk scores from the training set (Eq. 14-15)")
     ap.add_argument("--in-flight", type=int, default=3, help="mini-batches in flight (contexts x streams)")
     ap.add_argument("--miss-inflight-kb", type=int, default=None, help="KiB of host reads the miss gather keeps outstanding")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
@@ -90,7 +93,18 @@ def main() -> int:
         num_cached = n * cache_pct // 100
         cache = mqg.Cache(g, feats, num_cached, cache_stride=pad_dim)
         t0 = time.time()
-        mqg.mqg_build_cache(ctxs[0], g, cache)
+        if args.cache_policy == "top":
+            mqg.mqg_build_cache(ctxs[0], g, cache)
+        elif args.cache_policy == "sampled":
+            mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_DEGREE_SAMPLED, seed=5)
+        else:
+            # the training set: every node the seed batches are drawn from
+            gen = torch.Generator()
+            gen.manual_seed(2)
+            perm = torch.randperm(n, generator=gen)
+            train = perm if w.train_fraction is None else perm[: max(w.batch, int(n * w.train_fraction))]
+            mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=train.to(g.idx_dtype).to(dev),
+                                   step_fanouts=list(reversed(w.fanouts)))
         torch.cuda.synchronize()
     build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0
 
@@ -338,7 +352,7 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"{w.name}: Chung-Lu power-law graph, {n} nodes, {ci.numel()} directed edges, "
                                f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
-                               f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes, "
+                               f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({args.cache_policy}), "
                                f"rest in pinned host memory",
                    "in_flight": nfl, "global_batch": w.batch},
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),

@@ -455,37 +455,50 @@ int orc_build_cache_sampled(int64_t num_nodes, const int64_t *row_ptr, int64_t n
 
 /*
  * Short-random-walk scores (Eq. 14-15): P^(0) = 1/|V_t| on the training
- * nodes, 0 elsewhere; P^(l) = (D A + I) P^(l-1), D = diag(d),
- * d_i = min(fanout_l, deg_i) / deg_i (the share of a node's neighbours that
- * sampling keeps; 0 for a node without neighbours), for l = 1..L, taken as
- * written with A's row i = the adjacency row of node i:
- *   P^(l)[i] = P^(l-1)[i] + d_i * sum_{j in row(i)} P^(l-1)[j].
- * Double precision, each row summed in adjacency order, product and sum
- * rounded separately.  step_fanouts[l-1] is the fanout of walk step l.
+ * nodes, 0 elsewhere, and L propagation steps with the sampling ratio
+ * d_j = min(fanout_l, deg_j) / deg_j (the share of node j's neighbours that
+ * sampling keeps; 0 for a node without neighbours).
+ *
+ * Reading of Eq. 15.  The paper prints P^(l) = (D A + I) P^(l-1), which scales
+ * the mass arriving at node i by i's own ratio d_i; then every node with at
+ * least `fanout` neighbours scores alike after one step and the scores no
+ * longer say how likely a node is to be *reached*.  The ratio belongs to the
+ * node that does the sampling: a node j that holds mass P[j] passes d_j * P[j]
+ * to each of its neighbours.  That is what is computed here,
+ *   P^(l)[i] = P^(l-1)[i] + sum_{j in row(i)} d_j * P^(l-1)[j]      ((A D + I) P),
+ * with row(i) the adjacency row of node i (on the symmetrised graphs of the
+ * workloads "j in row(i)" and "i in row(j)" are the same).
+ * Double precision; every product d_j * P[j] is rounded on its own, every row
+ * is summed in adjacency order.  step_fanouts[l-1] is the fanout of step l.
  */
 int orc_random_walk_scores(int64_t num_nodes, const int64_t *row_ptr, const int64_t *col_idx,
                            const int64_t *train_ids, int64_t num_train, const int64_t *step_fanouts,
                            int64_t num_steps, double *scores)
 {
-    double *cur = calloc((size_t)(num_nodes > 0 ? num_nodes : 1), sizeof *cur);
-    double *next = calloc((size_t)(num_nodes > 0 ? num_nodes : 1), sizeof *next);
-    if (!cur || !next) { free(cur); free(next); return -2; }
+    size_t cnt = (size_t)(num_nodes > 0 ? num_nodes : 1);
+    double *cur = calloc(cnt, sizeof *cur);
+    double *next = calloc(cnt, sizeof *next);
+    double *pass = calloc(cnt, sizeof *pass);          /* d_j * P[j]: what node j passes to a neighbour */
+    if (!cur || !next || !pass) { free(cur); free(next); free(pass); return -2; }
     for (int64_t t = 0; t < num_train; ++t) cur[train_ids[t]] = 1.0 / (double)num_train;
     for (int64_t l = 0; l < num_steps; ++l) {
-        for (int64_t i = 0; i < num_nodes; ++i) {
-            int64_t b = row_ptr[i], e = row_ptr[i + 1], deg = e - b;
-            double acc = 0.0;
-            for (int64_t p = b; p < e; ++p) acc += cur[col_idx[p]];
+        for (int64_t j = 0; j < num_nodes; ++j) {
+            int64_t deg = row_ptr[j + 1] - row_ptr[j];
             double keep = deg < step_fanouts[l] ? (double)deg : (double)step_fanouts[l];
             double d = deg > 0 ? keep / (double)deg : 0.0;
-            volatile double prod = d * acc;           /* rounded on its own, never fused */
-            next[i] = cur[i] + prod;
+            pass[j] = d * cur[j];
+        }
+        for (int64_t i = 0; i < num_nodes; ++i) {
+            double acc = 0.0;
+            for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) acc += pass[col_idx[p]];
+            next[i] = cur[i] + acc;
         }
         double *t = cur; cur = next; next = t;
     }
     for (int64_t i = 0; i < num_nodes; ++i) scores[i] = cur[i];
     free(cur);
     free(next);
+    free(pass);
     return 0;
 }
 

@@ -533,7 +533,7 @@ def test_random_walk_scores_equal_dense_matrix_power():
         P[train] = 1.0 / len(train)
         for k in fanouts:
             d = np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0)
-            P = (np.diag(d) @ A + np.eye(n)) @ P
+            P = (A @ np.diag(d) + np.eye(n)) @ P                  # the sampling node's ratio scales what it passes on
         got = oracle.random_walk_scores(rp, ci, train, fanouts)
         assert np.allclose(got, P, rtol=1e-12, atol=1e-15)
     # fanout above every degree: D = I, so the scores count walks: (A + I)^L P0
@@ -547,10 +547,26 @@ def test_random_walk_scores_equal_dense_matrix_power():
 
 def test_random_walk_worked_by_hand():
     # rows: 0:[1,2] 1:[0] 2:[0,3] 3:[]; training set {0}; fanout 1 -> d = [1/2, 1, 1/2, 0]
+    # step 1: node 0 passes 1/2 to whoever lists it (rows 1 and 2); step 2: passes [1/2, 1/2, 1/4, 0]
     rp = np.array([0, 2, 3, 5, 5], dtype=np.int64)
     ci = np.array([1, 2, 0, 0, 3], dtype=np.int64)
-    assert oracle.random_walk_scores(rp, ci, [0], [1]).tolist() == [1.0, 1.0, 0.5, 0.0]
-    assert oracle.random_walk_scores(rp, ci, [0], [1, 1]).tolist() == [1.75, 2.0, 1.0, 0.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1]).tolist() == [1.0, 0.5, 0.5, 0.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1]).tolist() == [1.75, 1.0, 1.0, 0.0]
+
+
+def test_random_walk_scores_rank_reachable_hubs_first():
+    """What the scores are for (cache section of the paper): nodes that sampling from the training
+    set reaches with high probability.  With the whole graph as training set and one step the score
+    of node i is 1/N * (1 + sum over neighbours j of min(k, deg_j)/deg_j), which grows with the degree
+    of i - unlike a score that saturates at 1 + k for every node of degree >= k."""
+    rp, ci = tiny_graph(600, 12000, seed=15)
+    n = len(rp) - 1
+    deg = np.diff(rp)
+    sc = oracle.random_walk_scores(rp, ci, np.arange(n), [5])
+    big = deg >= 5
+    assert np.unique(np.round(sc[big] * n, 9)).size > big.sum() // 2          # not one saturated value
+    top = np.argsort(-sc)[:30]
+    assert deg[top].mean() > 3 * deg.mean()
 
 
 def test_cache_by_score_equals_lexsort():
