@@ -92,18 +92,22 @@ def main() -> int:
     else:
         num_cached = n * cache_pct // 100
         cache = mqg.Cache(g, feats, num_cached, cache_stride=pad_dim)
+        train_dev = None
+        if args.cache_policy == "walk":
+            # the training set: every node the seed batches are drawn from
+            gen = torch.Generator()
+            gen.manual_seed(2)
+            perm = torch.randperm(n, generator=gen)
+            train = perm if w.train_fraction is None else perm[: max(w.batch, int(n * w.train_fraction))]
+            train_dev = train.to(g.idx_dtype).to(dev)
+            torch.cuda.synchronize()
         t0 = time.time()
         if args.cache_policy == "top":
             mqg.mqg_build_cache(ctxs[0], g, cache)
         elif args.cache_policy == "sampled":
             mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_DEGREE_SAMPLED, seed=5)
         else:
-            # the training set: every node the seed batches are drawn from
-            gen = torch.Generator()
-            gen.manual_seed(2)
-            perm = torch.randperm(n, generator=gen)
-            train = perm if w.train_fraction is None else perm[: max(w.batch, int(n * w.train_fraction))]
-            mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=train.to(g.idx_dtype).to(dev),
+            mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=train_dev,
                                    step_fanouts=list(reversed(w.fanouts)))
         torch.cuda.synchronize()
     build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0

@@ -200,10 +200,13 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
  *                             with the smallest (key, id) are cached, slot s = s-th smallest.
  *   MQG_CACHE_RANDOM_WALK     Eq. 14-15, for training sets that are a small part of the graph:
  *                             P(0) = 1/num_train on train_ids, 0 elsewhere;
- *                             P(l)[i] = P(l-1)[i] + d_i * sum_{j in row(i)} P(l-1)[j],
- *                             d_i = min(step_fanouts[l-1], deg_i) / deg_i, l = 1..num_steps, in
- *                             double precision with every row summed in adjacency order; the
- *                             num_cached nodes of highest P(num_steps) are cached (ties: lower id).
+ *                             P(l)[i] = P(l-1)[i] + sum_{j in row(i)} d_j * P(l-1)[j],
+ *                             d_j = min(step_fanouts[l-1], deg_j) / deg_j, l = 1..num_steps, in
+ *                             double precision, products rounded on their own, every row summed
+ *                             in adjacency order.  (The sampling ratio is that of the node that
+ *                             passes mass on, (A D + I) P; the paper prints (D A + I) P, which
+ *                             makes all nodes of degree >= fanout score alike.)  The num_cached
+ *                             nodes of highest P(num_steps) are cached (ties: lower id).
  *                             scores_out (device double [num_nodes], may be NULL) receives
  *                             P(num_steps).  Membership is the deterministic top of the score, not
  *                             a draw from it.

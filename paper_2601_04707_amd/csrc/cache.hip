@@ -6,9 +6,10 @@
 //                    without replacement.  Every adjacency slot is a ticket with a uniform 64-bit
 //                    key, a node's key is the minimum over its tickets (k_ticket_keys), nodes are
 //                    ranked by (key, id) ascending - an exponential race in integer arithmetic
-//   random walk      Eq. 14-15: P^(l) = (D A + I) P^(l-1) from the training set (k_rw_step, double
-//                    precision, every row summed in adjacency order so that the result does not
-//                    depend on the schedule), ranked by (P^(L) descending, id ascending)
+//   random walk      Eq. 14-15: L propagation steps from the training set, every node passing
+//                    d_j * P[j] to its neighbours (k_rw_pass, k_rw_step; double precision, every
+//                    row summed in adjacency order so that the result does not depend on the
+//                    schedule), ranked by (P^(L) descending, id ascending)
 // 64-bit keys are ordered by two stable 32-bit radix sorts (low word, then high word).
 //
 // The ranking is a stable least-significant-digit radix sort of (max_degree - degree) with the
@@ -48,7 +49,8 @@ k_degrees(const PtrT *__restrict__ row_ptr, int64_t n, uint32_t *__restrict__ de
         uint32_t o = __shfl_xor(d, off, 64);
         d = o > d ? o : d;
     }
-    if (lane_id() == 0 && d > 0) atomicMax(max_deg, d);
+    // a plain read first: once the running maximum is high almost no wavefront needs the atomic
+    if (lane_id() == 0 && d > *reinterpret_cast<volatile uint32_t *>(max_deg)) atomicMax(max_deg, d);
 }
 
 __global__ void __launch_bounds__(kBlock)
@@ -121,15 +123,33 @@ k_rw_seed(const IdxT *__restrict__ train_ids, int64_t num_train, double *__restr
     if (t < num_train) p[train_ids[t]] = 1.0 / static_cast<double>(num_train);
 }
 
-// One step of P_next[i] = P[i] + d_i * sum_{j in row(i)} P[j], d_i = min(fanout, deg_i) / deg_i.
-// Every row is summed strictly in adjacency order (rows of up to 16 entries by their lane, longer
-// rows by the wavefront: 64 values are fetched in parallel and then added one after the other),
-// product and sum are rounded separately: bit for bit the plain sequential loop.
+// A step of the random-walk scores, in two kernels.
+//   k_rw_pass   pass[j] = d_j * P[j], d_j = min(fanout, deg_j) / deg_j: what a node that holds mass
+//               P[j] hands to each of its neighbours (the sampling ratio belongs to the node that
+//               samples; see the header for this reading of Eq. 15)
+//   k_rw_step   P_next[i] = P[i] + sum_{j in row(i)} pass[j], every row summed strictly in adjacency
+//               order (rows of up to 16 entries by their lane, longer rows by the wavefront: 64
+//               values are fetched in parallel and then added one after the other) - bit for bit
+//               the plain sequential loop, whatever the schedule
+template <typename PtrT>
+__global__ void __launch_bounds__(kBlock)
+k_rw_pass(const PtrT *__restrict__ row_ptr, int64_t n, int fanout, const double *__restrict__ cur,
+          double *__restrict__ pass) {
+#pragma clang fp contract(off)
+    const int64_t j = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (j < n) {
+        const int64_t deg = static_cast<int64_t>(row_ptr[j + 1]) - static_cast<int64_t>(row_ptr[j]);
+        const double keep = deg < fanout ? static_cast<double>(deg) : static_cast<double>(fanout);
+        const double d = deg > 0 ? keep / static_cast<double>(deg) : 0.0;
+        pass[j] = d * cur[j];
+    }
+}
+
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n, int fanout,
-          const double *__restrict__ cur, double *__restrict__ next) {
-#pragma clang fp contract(off)                             // d * acc and the sum are rounded separately
+k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n,
+          const double *__restrict__ cur, const double *__restrict__ pass, double *__restrict__ next) {
+#pragma clang fp contract(off)
     const int lane = lane_id();
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     int64_t b = 0;
@@ -140,7 +160,7 @@ k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, in
     }
     double acc = 0.0;
     if (deg <= 16)
-        for (int p = 0; p < deg; ++p) acc = acc + cur[col_idx[b + p]];
+        for (int p = 0; p < deg; ++p) acc = acc + pass[col_idx[b + p]];
     uint64_t big = ballot64(deg > 16);
     while (big) {
         const int l = __ffsll(static_cast<long long>(big)) - 1;
@@ -151,18 +171,13 @@ k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, in
         for (int c0 = 0; c0 < dl; c0 += kWave) {
             const int m = dl - c0 < kWave ? dl - c0 : kWave;
             double val = 0.0;
-            if (lane < m) val = cur[col_idx[bl + c0 + lane]];
+            if (lane < m) val = pass[col_idx[bl + c0 + lane]];
             const uint64_t bits = static_cast<uint64_t>(__double_as_longlong(val));
             for (int t = 0; t < m; ++t) a = a + __longlong_as_double(static_cast<long long>(readlane64(bits, t)));
         }
         if (lane == l) acc = a;
     }
-    if (i < n) {
-        const double keep = deg < fanout ? static_cast<double>(deg) : static_cast<double>(fanout);
-        const double d = deg > 0 ? keep / static_cast<double>(deg) : 0.0;
-        const double prod = d * acc;                       // plain operators: the pragma above governs them
-        next[i] = cur[i] + prod;
-    }
+    if (i < n) next[i] = cur[i] + acc;
 }
 
 // ascending radix order of ~bits(score) = descending score (scores are non-negative)
@@ -299,9 +314,9 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         int rc0 = rank_by_key64(ctx, tmp, key64, n, &ranked, s);
         if (rc0 != MQG_OK) return rc0;
     } else {  // MQG_CACHE_RANDOM_WALK
-        double *pa, *pb;
+        double *pa, *pb, *pass;
         uint64_t *key64;
-        if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&key64, n)))
+        if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&pass, n) && tmp.alloc(&key64, n)))
             return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
         e = hipMemsetAsync(pa, 0, static_cast<size_t>(n) * sizeof(double), s);
         if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
@@ -316,14 +331,18 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         for (int l = 0; l < plan->num_steps; ++l) {
             const int fo = plan->step_fanouts[l];
             const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-            if (p64 && i64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, fo, cur, next)));
-            else if (p64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, fo, cur, next)));
-            else if (i64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, fo, cur, next)));
+            if (p64)
+                MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, fo, cur, pass)));
             else
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, fo, cur, next)));
+                MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, fo, cur, pass)));
+            if (p64 && i64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, pass, next)));
+            else if (p64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, pass, next)));
+            else if (i64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, pass, next)));
+            else
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, pass, next)));
             std::swap(cur, next);
         }
         if (plan->scores_out) {
