@@ -40,6 +40,8 @@ def main() -> int:
                          "to degree (paper Eq. 13), or by random-walk scores from the training set (Eq. 14-15)")
     ap.add_argument("--in-flight", type=int, default=3, help="mini-batches in flight (contexts x streams)")
     ap.add_argument("--miss-inflight-kb", type=int, default=None, help="KiB of host reads the miss gather keeps outstanding")
+    ap.add_argument("--dedup", choices=["bitmap", "hash"], default="bitmap",
+                    help="frontier dedup: node-indexed bitmap and position table (default) or hash table and sort")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -117,6 +119,8 @@ def main() -> int:
             c.set_option(mqg.MQG_OPT_MISS_INFLIGHT_BYTES, args.miss_inflight_kb * 1024)
         if args.heavy_degree is not None:
             c.set_option(mqg.MQG_OPT_HEAVY_DEGREE, args.heavy_degree)
+        if args.dedup == "hash":
+            c.set_option(mqg.MQG_OPT_DEDUP_HASH, 1)
     bounds = blks[0].bounds
     x0 = [torch.zeros((bounds[0][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for _ in range(nfl)]
     hs = [[torch.zeros((bounds[l][0], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)] for _ in range(nfl)]
@@ -219,9 +223,16 @@ def main() -> int:
         if host_link:
             host_link["bound"] = "host-link"
 
-    sample_us = sum(v["us_per_step"] for k, v in kern.items()
-                    if k in ("k_init_seeds", "k_row_info", "k_scan_tiles", "k_row_offsets", "k_sample",
-                             "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local"))
+    # the forward profile pass launches nothing else through the radix/scan kernels than the hash dedup
+    dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local", "k_zero_u64", "k_scan_tiles(radix)",
+                     "k_scan_reduce", "k_scan_apply")
+    dedup_us = sum(v["us_per_step"] for k, v in kern.items()
+                   if k in dedup_kernels or k.startswith("k_hash_") or k.startswith("k_radix_"))
+    if args.dedup == "bitmap":                             # its one scan per block goes by the shared name
+        dedup_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / 2
+    sample_us = dedup_us + sum(v["us_per_step"] for k, v in kern.items()
+                               if k in ("k_init_seeds", "k_row_info", "k_row_offsets", "k_sample"))
+    sample_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / (2 if args.dedup == "bitmap" else 1)
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
     # ---------------------------------------------------------------- sampling against its own bounds
@@ -358,12 +369,13 @@ def main() -> int:
                                f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
                                f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({args.cache_policy}), "
                                f"rest in pinned host memory",
-                   "in_flight": nfl, "global_batch": w.batch},
+                   "in_flight": nfl, "global_batch": w.batch, "dedup": args.dedup},
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
         "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
         "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),
         "cache_hit_rate": round(hits / max(1, hits + misses), 4),
-        "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1)},
+        "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1),
+                              "dedup_relabel_part_of_sample": round(dedup_us, 1)},
         "backward_aggregation": {"us_per_step": round(bwd_us, 1), "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
                                  "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
                                  "note": "all blocks of a mini-batch, one at a time; not part of a step"},

@@ -160,9 +160,15 @@ typedef enum {
                                             outstanding (1 KiB..1 GiB, default 512 KiB): sizes
                                             its grid; enough to saturate the host link without
                                             crowding concurrent streams out of the memory system */
-    MQG_OPT_HEAVY_DEGREE = 4             /* destinations with more neighbours than this (>= 64,
+    MQG_OPT_HEAVY_DEGREE = 4,            /* destinations with more neighbours than this (>= 64,
                                             default 2048) are sampled by a whole workgroup
                                             instead of one wavefront; results do not change   */
+    MQG_OPT_DEDUP_HASH = 5               /* value != 0: frontier dedup and relabel through a hash
+                                            table and a sort (memory proportional to the
+                                            mini-batch) instead of the node-indexed bitmap and
+                                            position table (4.2 bytes per graph node); same
+                                            blocks, more kernel launches.  The first use
+                                            allocates the table (synchronous)                */
 } mqg_option;
 int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value);
 

@@ -186,6 +186,7 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->miss_list);
     (void)hipFree(c->counters);
     mqg::free_backward_scratch(c);
+    mqg::free_hash_scratch(c);
     for (auto &r : c->prof_recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -200,6 +201,13 @@ int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value) {
     switch (option) {
         case MQG_OPT_FORCE_SLOW_SELECT: ctx->force_slow_select = value != 0; return MQG_OK;
         case MQG_OPT_PROFILE: ctx->profile = value != 0; return MQG_OK;
+        case MQG_OPT_DEDUP_HASH:
+            if (value != 0) {
+                int rc = mqg::ensure_hash_scratch(ctx);
+                if (rc != MQG_OK) return rc;
+            }
+            ctx->dedup_hash = value != 0;
+            return MQG_OK;
         case MQG_OPT_HEAVY_DEGREE:
             if (value < 64 || value > 0x7FFFFFFF) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: MQG_OPT_HEAVY_DEGREE outside 64..2^31-1");
             ctx->heavy_degree = static_cast<int>(value);

@@ -63,6 +63,13 @@ struct mqg_ctx {
     int32_t *bwd_dst_row = nullptr;      // [bwd_nnz_cap] destination row of every edge
     int32_t *bwd_col_ptr = nullptr;      // [bwd_src_cap + 2] offsets of every source in the sorted edge list
     int64_t bwd_nnz_cap = 0, bwd_src_cap = 0;
+    // hash-table dedup (MQG_OPT_DEDUP_HASH); allocated when the option is first used
+    bool dedup_hash = false;
+    unsigned long long *hash_table = nullptr;      // [hash_capacity] (id << 32 | position), all ones = empty
+    int64_t hash_capacity = 0;
+    uint32_t *hash_new_keys = nullptr;             // [max_nnz] ids first seen in the current block
+    unsigned long long *hash_new_count = nullptr;  // their number
+    mqg::RadixBufs hash_sort;
 
     // options
     bool force_slow_select = false;
@@ -115,6 +122,13 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
 int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *grad_out, int64_t go_stride,
                                 void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
+// hash-table dedup (dedup_hash.hip)
+int ensure_hash_scratch(mqg_ctx *ctx);
+void free_hash_scratch(mqg_ctx *ctx);
+int hash_put_seeds(mqg_ctx *ctx, const void *seeds, int idx_type, int64_t need_dst, const int64_t *sizes, hipStream_t s);
+int hash_dedup_block(mqg_ctx *ctx, const int32_t *nbr, int64_t need_nnz, int64_t num_nodes, int idx_type, void *src_ids,
+                     int64_t *sizes, int64_t *sizes_next, int32_t *indices, hipStream_t s);
+int hash_clear(mqg_ctx *ctx, hipStream_t s);
 
 // Exclusive scan of vals[0..n) in place by one workgroup; the total (plus *addend if given) is
 // stored to *total_a and *total_b where non-null.

@@ -61,7 +61,7 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
                 v = 0;
                 atomicOr(seed_flags, 1);
             }
-            if (atomicCAS(&local_of[v], -1, static_cast<int32_t>(i)) != -1) atomicOr(seed_flags, 2);
+            if (local_of && atomicCAS(&local_of[v], -1, static_cast<int32_t>(i)) != -1) atomicOr(seed_flags, 2);
         }
         int64_t s = static_cast<int64_t>(row_ptr[v]);
         int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - s;
@@ -159,7 +159,7 @@ __device__ __forceinline__ void emit_neighbour(const IdxT *__restrict__ col_idx,
                                                int32_t out_pos, const SampleArgs &a) {
     int32_t u = static_cast<int32_t>(col_idx[start + slot]);
     a.nbr[out_pos] = u;
-    if (a.local_of[u] < 0) {
+    if (a.local_of && a.local_of[u] < 0) {                 // (no marking when the hash path dedups)
         uint32_t bit = 1u << (u & 31);
         uint32_t *w = a.bitmap + (u >> 5);
         (void)__hip_atomic_fetch_or(w, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -520,6 +520,7 @@ __global__ void __launch_bounds__(kBlock)
 k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of,
               int32_t *__restrict__ heavy_count) {
     if (blockIdx.x == 0 && threadIdx.x <= MQG_MAX_LAYERS) heavy_count[threadIdx.x] = 0;  // hub counts and seed flags of the next call
+    if (!local_of) return;
     const int64_t n = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
     for (int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x; i < n; i += stride) {
@@ -536,6 +537,8 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     int32_t *nbr = static_cast<int32_t *>(ctx->nbr);
     const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
 
+    const bool use_hash = ctx->dedup_hash;
+    int32_t *local_of = use_hash ? nullptr : ctx->local_of;
     int64_t need_dst = num_seeds;
     const int bitmap_wpt = ctx->bitmap_words <= (int64_t(1) << 20) ? 1 : 4;     // words per thread, see k_bitmap_emit*
     const int bitmap_tiles = static_cast<int>(std::max<int64_t>(1, ctx->bitmap_words / (int64_t(kBlock) * bitmap_wpt)));
@@ -552,10 +555,14 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
                    (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
                                                                           ctx->row_deg, ctx->tile_vals, b.sizes, heavy_degree,
                                                                           ctx->heavy_rows, ctx->heavy_count + l,
-                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), ctx->local_of,
+                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), local_of,
                                                                           g->num_nodes, ctx->heavy_count + MQG_MAX_LAYERS)));
         int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
         if (rc != MQG_OK) return rc;
+        if (use_hash && l == L - 1) {                      // the seeds enter the table (and repeated ones are flagged) first
+            rc = hash_put_seeds(ctx, b.src_ids, g->idx_type, need_dst, b.sizes, s);   // ids as k_row_info checked them
+            if (rc != MQG_OK) return rc;
+        }
         MQG_LAUNCH(ctx, "k_row_offsets", s,
                    (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, b.indptr,
                                                                l == L - 1 ? ctx->heavy_count + MQG_MAX_LAYERS : nullptr)));
@@ -566,7 +573,7 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         a.indptr = b.indptr;
         a.sizes = b.sizes;
         a.nbr = nbr;
-        a.local_of = ctx->local_of;
+        a.local_of = local_of;
         a.bitmap = ctx->bitmap;
         a.layer_hash = host_mix64(seed_hash ^ uint64_t(l));
         a.fanout = k;
@@ -577,6 +584,13 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         MQG_LAUNCH(ctx, "k_sample", s,
                    (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
 
+        if (use_hash) {
+            rc = hash_dedup_block(ctx, nbr, need_nnz, g->num_nodes, g->idx_type, b.src_ids, b.sizes,
+                                  l > 0 ? blocks[l - 1].sizes : nullptr, b.indices, s);
+            if (rc != MQG_OK) return rc;
+            need_dst = std::max(need_dst, std::min<int64_t>(g->num_nodes, need_dst + need_nnz));
+            continue;
+        }
         // num_src = num_dst + number of new nodes; it is also the next block's num_dst
         if (bitmap_wpt == 1) {
             MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<1><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
@@ -602,8 +616,9 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)), 4096));
         MQG_LAUNCH(ctx, "k_reset_local", s,
                    (k_reset_local<IdxT><<<grid, kBlock, 0, s>>>(static_cast<const IdxT *>(blocks[0].src_ids), blocks[0].sizes,
-                                                                 ctx->local_of, ctx->heavy_count)));
+                                                                 local_of, ctx->heavy_count)));
     }
+    if (use_hash) return hash_clear(ctx, s);
     return MQG_OK;
 }
 
