@@ -29,7 +29,7 @@ def build(force: bool = False) -> str:
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fno-fast-math",
-                               "-Wall", "-Wextra", "-o", tmp, _SRC])
+                               "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -65,6 +65,12 @@ def _load():
     lib.orc_mean_aggregate.argtypes = [vp, vp, i64, vp, i64, vp, i64, i64, ctypes.c_int]
     lib.orc_mean_aggregate_backward.restype = ctypes.c_int
     lib.orc_mean_aggregate_backward.argtypes = [vp, vp, i64, i64, vp, i64, vp, i64, i64, ctypes.c_int]
+    lib.orc_gcn_edge_weights.restype = None
+    lib.orc_gcn_edge_weights.argtypes = [vp, vp, vp, vp, i64, vp, vp]
+    lib.orc_weighted_aggregate.restype = None
+    lib.orc_weighted_aggregate.argtypes = [vp, vp, i64, vp, vp, vp, i64, vp, i64, i64, ctypes.c_int]
+    lib.orc_weighted_aggregate_backward.restype = ctypes.c_int
+    lib.orc_weighted_aggregate_backward.argtypes = [vp, vp, i64, i64, vp, vp, vp, i64, vp, i64, i64, ctypes.c_int]
     lib.orc_build_cache_sampled.restype = ctypes.c_int
     lib.orc_build_cache_sampled.argtypes = [i64, vp, i64, u64, vp, vp]
     lib.orc_random_walk_scores.restype = ctypes.c_int
@@ -273,6 +279,50 @@ def mean_aggregate_backward(indptr, indices, num_src: int, grad_out: np.ndarray)
                                              g.shape[1], g.shape[1], 1 if g.dtype == np.float16 else 0)
     if rc != 0:
         raise MemoryError("orc_mean_aggregate_backward")
+    return out
+
+
+def gcn_edge_weights(row_ptr, src_ids, indptr, indices):
+    """Weights of the sampled estimator of P H (Eq. 1-3) for one block.
+    Returns (edge_w [nnz] float64, self_w [num_dst] float64)."""
+    rp, sid, ip = _i64(row_ptr), _i64(src_ids), _i64(indptr)
+    ix = np.ascontiguousarray(np.asarray(indices), dtype=np.int32)
+    nd = ip.shape[0] - 1
+    ew = np.zeros(max(int(ip[-1]), 1), dtype=np.float64)
+    sw = np.zeros(max(nd, 1), dtype=np.float64)
+    _load().orc_gcn_edge_weights(_p(rp), _p(sid), _p(ip), _p(ix), nd, _p(ew), _p(sw))
+    return ew[:int(ip[-1])], sw[:nd]
+
+
+def weighted_aggregate(indptr, indices, edge_w, self_w, x: np.ndarray) -> np.ndarray:
+    """out[i] = self_w[i] x[i] + sum_p edge_w[p] x[indices[p]]; self_w may be None."""
+    ip = _i64(indptr)
+    ix = np.ascontiguousarray(np.asarray(indices), dtype=np.int32)
+    ew = np.ascontiguousarray(np.asarray(edge_w), dtype=np.float64)
+    sw = None if self_w is None else np.ascontiguousarray(np.asarray(self_w), dtype=np.float64)
+    assert x.dtype in (np.float32, np.float16) and x.ndim == 2
+    x = np.ascontiguousarray(x)
+    nd = ip.shape[0] - 1
+    out = np.zeros((nd, x.shape[1]), dtype=x.dtype)
+    _load().orc_weighted_aggregate(_p(ip), _p(ix), nd, _p(ew), None if sw is None else _p(sw), _p(x), x.shape[1],
+                                   _p(out), x.shape[1], x.shape[1], 1 if x.dtype == np.float16 else 0)
+    return out
+
+
+def weighted_aggregate_backward(indptr, indices, num_src: int, edge_w, self_w, grad_out: np.ndarray) -> np.ndarray:
+    ip = _i64(indptr)
+    ix = np.ascontiguousarray(np.asarray(indices), dtype=np.int32)
+    ew = np.ascontiguousarray(np.asarray(edge_w), dtype=np.float64)
+    sw = None if self_w is None else np.ascontiguousarray(np.asarray(self_w), dtype=np.float64)
+    g = np.ascontiguousarray(grad_out)
+    assert g.dtype in (np.float32, np.float16) and g.ndim == 2
+    nd = ip.shape[0] - 1
+    out = np.zeros((num_src, g.shape[1]), dtype=g.dtype)
+    rc = _load().orc_weighted_aggregate_backward(_p(ip), _p(ix), nd, num_src, _p(ew), None if sw is None else _p(sw),
+                                                 _p(g), g.shape[1], _p(out), g.shape[1], g.shape[1],
+                                                 1 if g.dtype == np.float16 else 0)
+    if rc != 0:
+        raise MemoryError("orc_weighted_aggregate_backward")
     return out
 
 

@@ -38,6 +38,11 @@
  *                            source nodes.
  *   - orc_mean_aggregate   : Eq. 16, Z_agg(v) = Mean(H(v)) over the sampled
  *                            neighbours of v (the GA step, "AH").
+ *   - orc_gcn_edge_weights / orc_weighted_aggregate : Eq. 1-3, the sampled
+ *                            estimator of the graph convolution P H with
+ *                            P = D^-1/2 (A + I) D^-1/2 (Eq. 2): a sampled
+ *                            neighbour j of v_i carries |N(v_i)|/s_node * P_ij
+ *                            (Eq. 3).
  *   - orc_mean_aggregate_backward : Sec. IV "Computation", backward pass: the
  *                            gradient of the GA step is the transposed
  *                            product ("AG" with G the gradient matrix), here
@@ -52,6 +57,7 @@
  * uniform, the equal-weights case of sampling by random keys (Efraimidis
  * and Spirakis, cited by the paper in Sec. III-B).
  */
+#include <math.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -391,6 +397,107 @@ int orc_mean_aggregate_backward(const int64_t *indptr, const int32_t *indices, i
             }
         }
     }
+    for (int64_t s = 0; s < num_src; ++s)
+        for (int64_t c = 0; c < dim; ++c) {
+            double v = acc[s * dim + c];
+            if (is_half) ((uint16_t *)grad_x)[s * gx_stride + c] = orc_float_to_half((float)v);
+            else ((float *)grad_x)[s * gx_stride + c] = (float)v;
+        }
+    free(acc);
+    return 0;
+}
+
+/* ------------------------------------------------ weighted (GCN) aggregation */
+
+/*
+ * Weights of the sampled estimator of the graph convolution (Eq. 1-3).
+ *
+ * P = D^-1/2 (A + I) D^-1/2 with D_ii = deg(v_i) + 1 (Eq. 2), so for an edge
+ * (v_i, v_j) of the graph P_ij = 1 / sqrt((deg(v_i)+1) (deg(v_j)+1)) and the
+ * diagonal is P_ii = 1 / (deg(v_i)+1).  Eq. 3 scales a sampled neighbour's
+ * entry by |N(v_i)| / s_node.
+ *
+ * Readings.  N(v_i) is the adjacency row of v_i (no self loop: rows hold
+ * none), s_node is the number of neighbours actually drawn for v_i,
+ * n_i = min(fanout, deg(v_i)) - so a row that was kept whole has factor 1 and
+ * reproduces its row of P exactly.  The diagonal term of A + I is not part of
+ * the sampled set; it is returned separately (self_w) and applied to the
+ * node's own row, which a block always carries as source i.
+ *
+ * src_ids: global ids of the block's sources (the first num_dst are the
+ * destinations).  edge_w[p] for block edge p, self_w[i] for destination i.
+ */
+void orc_gcn_edge_weights(const int64_t *row_ptr, const int64_t *src_ids, const int64_t *indptr,
+                          const int32_t *indices, int64_t num_dst, double *edge_w, double *self_w)
+{
+    for (int64_t i = 0; i < num_dst; ++i) {
+        int64_t v = src_ids[i];
+        double deg_i = (double)(row_ptr[v + 1] - row_ptr[v]);
+        int64_t b = indptr[i], e = indptr[i + 1];
+        double s_node = (double)(e - b);
+        self_w[i] = 1.0 / (deg_i + 1.0);
+        for (int64_t p = b; p < e; ++p) {
+            int64_t u = src_ids[indices[p]];
+            double deg_j = (double)(row_ptr[u + 1] - row_ptr[u]);
+            double P_ij = 1.0 / sqrt((deg_i + 1.0) * (deg_j + 1.0));
+            edge_w[p] = deg_i / s_node * P_ij;
+        }
+    }
+}
+
+/*
+ * out[i, :] = self_w[i] * x[i, :] + sum over the edges p of row i of
+ * edge_w[p] * x[indices[p], :]  (self_w may be NULL: no diagonal term),
+ * accumulated in double in row order (the diagonal term first), rounded once
+ * to float (and then once to half for is_half).
+ */
+void orc_weighted_aggregate(const int64_t *indptr, const int32_t *indices, int64_t num_dst,
+                            const double *edge_w, const double *self_w, const void *x, int64_t x_stride,
+                            void *out, int64_t out_stride, int64_t dim, int is_half)
+{
+    double *acc = malloc((size_t)(dim > 0 ? dim : 1) * sizeof *acc);
+    for (int64_t i = 0; i < num_dst; ++i) {
+        for (int64_t c = 0; c < dim; ++c) acc[c] = 0.0;
+        for (int64_t p = indptr[i] - (self_w ? 1 : 0); p < indptr[i + 1]; ++p) {
+            int64_t r = p < indptr[i] ? i : indices[p];
+            double w = p < indptr[i] ? self_w[i] : edge_w[p];
+            for (int64_t c = 0; c < dim; ++c) {
+                double xv = is_half ? orc_half_to_double(((const uint16_t *)x)[r * x_stride + c])
+                                    : (double)((const float *)x)[r * x_stride + c];
+                acc[c] += w * xv;
+            }
+        }
+        for (int64_t c = 0; c < dim; ++c) {
+            if (is_half) ((uint16_t *)out)[i * out_stride + c] = orc_float_to_half((float)acc[c]);
+            else ((float *)out)[i * out_stride + c] = (float)acc[c];
+        }
+    }
+    free(acc);
+}
+
+/*
+ * Backward of orc_weighted_aggregate: grad_x = M^T grad_out for the operator
+ * M[i, s] = sum of edge_w over the edges of row i that point to s, plus
+ * self_w[i] at s == i.  Accumulated in double in row order, rounded once.
+ */
+int orc_weighted_aggregate_backward(const int64_t *indptr, const int32_t *indices, int64_t num_dst,
+                                    int64_t num_src, const double *edge_w, const double *self_w,
+                                    const void *grad_out, int64_t go_stride, void *grad_x,
+                                    int64_t gx_stride, int64_t dim, int is_half)
+{
+    size_t total = (size_t)(num_src > 0 ? num_src : 1) * (size_t)(dim > 0 ? dim : 1);
+    double *acc = calloc(total, sizeof *acc);
+    if (!acc) return -2;
+    for (int64_t i = 0; i < num_dst; ++i)
+        for (int64_t p = indptr[i] - (self_w ? 1 : 0); p < indptr[i + 1]; ++p) {
+            int64_t s = p < indptr[i] ? i : indices[p];
+            double w = p < indptr[i] ? self_w[i] : edge_w[p];
+            for (int64_t c = 0; c < dim; ++c) {
+                double g = is_half ? orc_half_to_double(((const uint16_t *)grad_out)[i * go_stride + c])
+                                   : (double)((const float *)grad_out)[i * go_stride + c];
+                acc[s * dim + c] += w * g;
+            }
+        }
     for (int64_t s = 0; s < num_src; ++s)
         for (int64_t c = 0; c < dim; ++c) {
             double v = acc[s * dim + c];

@@ -579,3 +579,92 @@ def test_cache_by_score_equals_lexsort():
         want = np.full(500, -1, dtype=np.int32)
         want[order[:num_cached]] = np.arange(num_cached)
         assert np.array_equal(c.slot_of, want)
+
+
+# ------------------------------------------------------------------------- weighted (GCN) aggregation
+
+def dense_gcn_operator(rp, ci):
+    """P = D^-1/2 (A + I) D^-1/2 with D = row sums of A + I (Eq. 2), as a dense matrix."""
+    n = len(rp) - 1
+    A_hat = np.eye(n)
+    for i in range(n):
+        A_hat[i, ci[rp[i]:rp[i + 1]]] = 1.0
+    d = A_hat.sum(axis=1)
+    return A_hat / np.sqrt(np.outer(d, d))
+
+
+def test_gcn_weights_with_whole_rows_reproduce_the_dense_operator():
+    """Fanout above every degree: nothing is dropped, the factor of Eq. 3 is 1 and the block
+    computes rows of P H exactly."""
+    rp, ci = tiny_graph(60, 500, seed=21)
+    n = len(rp) - 1
+    P = dense_gcn_operator(rp, ci)
+    assert np.allclose(P, P.T)
+    rng = np.random.default_rng(2)
+    H = rng.standard_normal((n, 7)).astype(np.float32)
+    seeds = np.array([5, 0, 33, 59, 12], dtype=np.int64)
+    blk = oracle.sample_blocks(rp, ci, seeds, [1000], 3)[0]
+    ew, sw = oracle.gcn_edge_weights(rp, blk.src_ids, blk.indptr, blk.indices)
+    for i, v in enumerate(seeds):
+        assert sw[i] == pytest.approx(P[v, v], rel=1e-15)
+        for p in range(blk.indptr[i], blk.indptr[i + 1]):
+            assert ew[p] == pytest.approx(P[v, blk.src_ids[blk.indices[p]]], rel=1e-15)
+    out = oracle.weighted_aggregate(blk.indptr, blk.indices, ew, sw, H[blk.src_ids])
+    assert np.allclose(out, (P @ H.astype(np.float64))[seeds], rtol=2e-7, atol=1e-7)
+    # without the diagonal term: (P - diag P) H
+    out = oracle.weighted_aggregate(blk.indptr, blk.indices, ew, None, H[blk.src_ids])
+    assert np.allclose(out, ((P - np.diag(np.diag(P))) @ H.astype(np.float64))[seeds], rtol=2e-7, atol=1e-7)
+
+
+def test_gcn_estimator_is_unbiased_over_all_subsets():
+    """Eq. 3: scaled by |N(v)| / s_node, the average over every possible sample of s_node
+    neighbours equals the full row of P H (brute force over all subsets of one row)."""
+    import itertools
+    rp, ci = tiny_graph(40, 300, seed=22)
+    deg = np.diff(rp)
+    v = int(np.argmax((deg >= 6) & (deg <= 9)))
+    assert 6 <= deg[v] <= 9
+    P = dense_gcn_operator(rp, ci)
+    rng = np.random.default_rng(4)
+    H = rng.standard_normal((len(rp) - 1, 3)).astype(np.float32)
+    nbrs = ci[rp[v]:rp[v + 1]]
+    k = 3
+    total = np.zeros(3)
+    count = 0
+    for sub in itertools.combinations(nbrs.tolist(), k):
+        src_ids = np.array([v] + list(sub), dtype=np.int64)
+        indptr = np.array([0, k], dtype=np.int64)
+        indices = np.arange(1, k + 1, dtype=np.int32)
+        ew, sw = oracle.gcn_edge_weights(rp, src_ids, indptr, indices)
+        assert np.allclose(ew, deg[v] / k * P[v, list(sub)], rtol=1e-15)
+        total += oracle.weighted_aggregate(indptr, indices, ew, sw, H[src_ids])[0].astype(np.float64)
+        count += 1
+    assert count == len(list(itertools.combinations(range(deg[v]), k)))
+    assert np.allclose(total / count, (P @ H.astype(np.float64))[v], rtol=1e-6, atol=1e-6)
+
+
+def test_weighted_aggregate_against_dense_product_and_its_transpose():
+    rng = np.random.default_rng(23)
+    nd, ns, dim = 30, 70, 5
+    counts = rng.integers(0, 9, nd)
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    indices = rng.integers(0, ns, indptr[-1]).astype(np.int32)          # repeated sources allowed
+    ew = rng.standard_normal(indptr[-1])
+    sw = rng.standard_normal(nd)
+    M = np.zeros((nd, ns))
+    for i in range(nd):
+        M[i, i] += sw[i]
+        for p in range(indptr[i], indptr[i + 1]):
+            M[i, indices[p]] += ew[p]
+    for dt, tol in ((np.float32, 1e-6), (np.float16, 2e-3)):
+        x = rng.standard_normal((ns, dim)).astype(dt)
+        g = rng.standard_normal((nd, dim)).astype(dt)
+        out = oracle.weighted_aggregate(indptr, indices, ew, sw, x)
+        assert out.dtype == dt and np.allclose(out, M @ x.astype(np.float64), rtol=tol, atol=tol)
+        gx = oracle.weighted_aggregate_backward(indptr, indices, ns, ew, sw, g)
+        assert gx.dtype == dt and np.allclose(gx, M.T @ g.astype(np.float64), rtol=tol, atol=tol)
+    # equal weights 1/n_i and no diagonal: the mean aggregation
+    x = rng.standard_normal((ns, dim)).astype(np.float32)
+    n_i = np.repeat(np.maximum(counts, 1), counts)
+    assert np.allclose(oracle.weighted_aggregate(indptr, indices, 1.0 / n_i, None, x),
+                       oracle.mean_aggregate(indptr, indices, x), rtol=3e-7, atol=1e-7)
