@@ -276,6 +276,10 @@ def main() -> int:
         c.set_option(mqg.MQG_OPT_PROFILE, 1)
     gx = [torch.zeros((bounds[l][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)]
     g_top = torch.randn((bounds[L - 1][0], pad_dim), device=dev).to(w.feat_dtype)[:, :w.dim]
+    # the same pass also runs the weighted (graph-convolution, paper Eq. 1-3) variant of the aggregation
+    # chain on the same blocks: weights of every block, then the weighted sums
+    ew = [torch.zeros(bounds[l][2], dtype=torch.float32, device=dev) for l in range(L)]
+    sw = [torch.zeros(bounds[l][0], dtype=torch.float32, device=dev) for l in range(L)]
     KB = min(K, 50)
     for i in range(W, W + KB):
         step(i)
@@ -285,7 +289,21 @@ def main() -> int:
             for l in range(L - 1, -1, -1):
                 mqg.mqg_sage_mean_aggregate_backward(ctxs[j], blks[j], l, gcur, gx[l], stream=streams[j])
                 gcur = gx[l]
+            x = x0[j]
+            for l in range(L):
+                mqg.mqg_gcn_edge_weights(ctxs[j], g, blks[j], l, ew[l], sw[l], stream=streams[j])
+                mqg.mqg_weighted_aggregate(ctxs[j], blks[j], l, ew[l], sw[l], x, hs[j][l], stream=streams[j])
+                x = hs[j][l]
         torch.cuda.synchronize()
+    wk = {}
+    for c in ctxs:
+        for name in ("k_gcn_edge_weights", "k_weighted_aggregate"):
+            ms, cnt = c.kernel_time(name)
+            a = wk.setdefault(name, [0.0, 0])
+            a[0] += ms
+            a[1] += cnt
+    wagg_us = wk["k_weighted_aggregate"][0] / KB * 1e3
+    wgt_us = wk["k_gcn_edge_weights"][0] / KB * 1e3
     bwd_names = ("k_edge_dst_rows", "k_radix_hist", "k_scan_reduce", "k_scan_tiles(radix)", "k_scan_apply",
                  "k_radix_scatter", "k_col_ptr", "k_mean_aggregate_backward")
     bk = {}
@@ -379,6 +397,10 @@ def main() -> int:
         "backward_aggregation": {"us_per_step": round(bwd_us, 1), "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
                                  "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
                                  "note": "all blocks of a mini-batch, one at a time; not part of a step"},
+        "gcn_weighted_aggregation": {"weights_kernel_us_per_step": round(wgt_us, 1), "sum_kernel_us_per_step": round(wagg_us, 1),
+                                     "mean_aggregate_us_per_step": round(agg_us, 1),
+                                     "note": "Eq. 1-3 estimator on the same blocks (weights of every block, then weighted "
+                                             "sums with the diagonal term); not part of a step"},
         "sampling": sampling,
         "paper_queue_rule": {"queue_size": q_rule, "memory_cap": q_cap, "bytes_per_queued_batch": per_batch_bytes,
                              "note": "Eq. 22-23 on mean prepare (sample+gather) / consume (aggregate) times of this run; "

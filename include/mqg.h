@@ -307,6 +307,50 @@ int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const
                                      int32_t dtype, mqg_stream stream);
 
 /*
+ * Weights of the sampled estimator of the graph convolution P H (paper Eq. 1-3),
+ * P = D^-1/2 (A + I) D^-1/2 with D_ii = deg(v_i) + 1 (Eq. 2).  For block edge p
+ * from destination i (node v_i) to source indices[p] (node v_j)
+ *   edge_w[p] = deg(v_i) / n_i * 1 / sqrt((deg(v_i) + 1) (deg(v_j) + 1)),
+ * n_i = the number of neighbours the block holds for v_i (Eq. 3 with s_node
+ * read as the number actually drawn: a row kept whole has factor 1), and
+ *   self_w[i] = P_ii = 1 / (deg(v_i) + 1)
+ * is the diagonal term of A + I, which is never part of the sampled set.
+ * deg is the length of the node's adjacency row in `graph`.  block->src_ids
+ * must hold the sources' global ids, as mqg_sample_blocks writes them.
+ * edge_w: device [cap_nnz] floats, self_w: device [cap_dst] floats; entries
+ * 0..nnz-1 and 0..num_dst-1 are written (computed in double precision, rounded
+ * once).  Enqueued on `stream`; nothing is allocated.
+ */
+int mqg_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *graph, const mqg_block *block,
+                         float *edge_w, float *self_w, mqg_stream stream);
+
+/*
+ * Weighted aggregation over one block (the estimator of paper Eq. 1-3 with the
+ * weights above, or any other per-edge weights, e.g. those of a layer-wise
+ * sampler, Eq. 4-9):
+ *   out[i, c] = self_w[i] * x_src[i, c] + sum over edges p of row i of
+ *               edge_w[p] * x_src[indices[p], c]
+ * self_w may be NULL (no diagonal term).  Layout, strides, dtype, padding and
+ * accumulation as mqg_sage_mean_aggregate (fp32 sums in row order, the
+ * diagonal term first).
+ */
+int mqg_weighted_aggregate(mqg_ctx *ctx, const mqg_block *block, const float *edge_w,
+                           const float *self_w, const void *x_src, int64_t x_stride, void *out,
+                           int64_t out_stride, int32_t dim, int32_t dtype, mqg_stream stream);
+
+/*
+ * Its backward (the transposed product, paper Sec. IV "Computation"):
+ *   grad_x[s, c] = sum over edges p = (i -> s) of edge_w[p] * grad_out[i, c]
+ *                  (+ self_w[s] * grad_out[s, c] for s < num_dst)
+ * Buffers, ordering, reproducibility and scratch as
+ * mqg_sage_mean_aggregate_backward (24 bytes of scratch per edge).
+ */
+int mqg_weighted_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const float *edge_w,
+                                    const float *self_w, const void *grad_out, int64_t go_stride,
+                                    void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype,
+                                    mqg_stream stream);
+
+/*
  * Depth of the mini-batch queue, i.e. how many mini-batches to keep in flight
  * (paper Sec. IV "Determining Optimal Queue Size", Eq. 22 and 23):
  *   C = floor(M_Q / M_batch),  M_Q = total_mem - peak_mem * (1 + margin_percent/100)

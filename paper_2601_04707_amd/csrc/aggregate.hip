@@ -43,6 +43,8 @@ __device__ __forceinline__ void from_f32(float x, _Float16 *o) { *o = static_cas
 // Forward: entries of output row i are the block's edges of destination i.
 struct ForwardRows {
     static constexpr bool kWeighted = false;
+    static constexpr bool kSelf = false;
+    __device__ __forceinline__ float self_weight(int64_t) const { return 0.f; }
     const int32_t *indptr;
     const int32_t *indices;
     __device__ __forceinline__ int begin(int64_t i) const { return indptr[i]; }
@@ -56,6 +58,8 @@ struct ForwardRows {
 // gradient row of its destination scaled by one over that destination's edge count.
 struct BackwardRows {
     static constexpr bool kWeighted = true;
+    static constexpr bool kSelf = false;
+    __device__ __forceinline__ float self_weight(int64_t) const { return 0.f; }
     const int32_t *col_ptr;     // [num_src + 1] offsets into dst_rows
     const int32_t *dst_rows;    // [nnz] destination row of every edge, edges ordered by source
     const int32_t *indptr;      // the block's forward offsets, for the edge counts
@@ -66,6 +70,41 @@ struct BackwardRows {
         const int i = dst_rows[p];
         return 1.f / static_cast<float>(indptr[i + 1] - indptr[i]);
     }
+    __device__ __forceinline__ float finish(float acc, int) const { return acc; }
+};
+
+// Weighted forward (the sampled estimator of the graph convolution, paper Eq. 1-3, or any other
+// per-edge weights): out[i] = self_w[i] x[i] + sum over the edges p of row i of edge_w[p] x[indices[p]].
+struct WeightedRows {
+    static constexpr bool kWeighted = true;
+    static constexpr bool kSelf = true;
+    const int32_t *indptr;
+    const int32_t *indices;
+    const float *edge_w;
+    const float *self_w;        // may be null: no diagonal term
+    __device__ __forceinline__ int begin(int64_t i) const { return indptr[i]; }
+    __device__ __forceinline__ int end(int64_t i) const { return indptr[i + 1]; }
+    __device__ __forceinline__ int input_row(int p) const { return indices[p]; }
+    __device__ __forceinline__ float weight(int p) const { return edge_w[p]; }
+    __device__ __forceinline__ float self_weight(int64_t i) const { return self_w ? self_w[i] : 0.f; }
+    __device__ __forceinline__ float finish(float acc, int) const { return acc; }
+};
+
+// Its transpose: output row s reduces edge_w * grad_out[destination] over the edges pointing to
+// source s (ordered by source, stable), plus self_w[s] * grad_out[s] where s is a destination.
+struct WeightedBackwardRows {
+    static constexpr bool kWeighted = true;
+    static constexpr bool kSelf = true;
+    const int32_t *col_ptr;
+    const int32_t *dst_rows;
+    const float *w_sorted;      // edge weights in the by-source order
+    const float *self_w;
+    const int64_t *sizes;
+    __device__ __forceinline__ int begin(int64_t s) const { return col_ptr[s]; }
+    __device__ __forceinline__ int end(int64_t s) const { return col_ptr[s + 1]; }
+    __device__ __forceinline__ int input_row(int p) const { return dst_rows[p]; }
+    __device__ __forceinline__ float weight(int p) const { return w_sorted[p]; }
+    __device__ __forceinline__ float self_weight(int64_t s) const { return (self_w && s < sizes[0]) ? self_w[s] : 0.f; }
     __device__ __forceinline__ float finish(float acc, int) const { return acc; }
 };
 
@@ -92,6 +131,14 @@ k_segment_reduce(Rows rows, const int64_t *__restrict__ n_rows, const T *__restr
             float acc[VEC];
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[q] = 0.f;
+            if (Rows::kSelf) {                             // the diagonal term: the row's own input row
+                const float ws = rows.self_weight(i);
+                if (ws != 0.f && live && g == 0) {
+                    P v = *reinterpret_cast<const P *>(x + i * x_stride + col0);
+#pragma unroll
+                    for (int q = 0; q < VEC; ++q) acc[q] = ws * to_f32(v.v[q]);
+                }
+            }
 #pragma unroll 4
             for (int p = b + g; p < e; p += groups) {
                 const int64_t r = rows.input_row(p);
@@ -138,6 +185,19 @@ k_segment_reduce_wide(Rows rows, const int64_t *__restrict__ n_rows, const T *__
         for (int ps = 0; ps < PASSES; ++ps)
 #pragma unroll
             for (int q = 0; q < VEC; ++q) acc[ps][q] = 0.f;
+        if (Rows::kSelf) {
+            const float ws = rows.self_weight(i);
+            if (ws != 0.f) {
+                const T *row = x + i * x_stride + lane * VEC;
+#pragma unroll
+                for (int ps = 0; ps < PASSES; ++ps)
+                    if (live[ps]) {
+                        P v = *reinterpret_cast<const P *>(row + ps * kWave * VEC);
+#pragma unroll
+                        for (int q = 0; q < VEC; ++q) acc[ps][q] = ws * to_f32(v.v[q]);
+                    }
+            }
+        }
         for (int c0 = b; c0 < e; c0 += kWave) {            // entries 64 at a time, one per lane
             const int m = e - c0 < kWave ? e - c0 : kWave;
             const int my_row = lane < m ? rows.input_row(c0 + lane) : 0;
@@ -273,7 +333,84 @@ k_col_ptr(const uint32_t *__restrict__ sorted_src, const int64_t *__restrict__ s
     }
 }
 
+// payload = the edge's own position (the by-source order then gives a permutation of the edges)
+__global__ void __launch_bounds__(kBlock)
+k_edge_iota(const int64_t *__restrict__ sizes, int32_t *__restrict__ edge_id) {
+    const int64_t nnz = sizes[2];
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t e = int64_t(blockIdx.x) * kBlock + threadIdx.x; e < nnz; e += stride) edge_id[e] = static_cast<int32_t>(e);
+}
+
+// destination row and weight of every edge in the by-source order
+__global__ void __launch_bounds__(kBlock)
+k_permute_edges(const int32_t *__restrict__ perm, const int32_t *__restrict__ indptr, const float *__restrict__ edge_w,
+                const int64_t *__restrict__ sizes, int32_t *__restrict__ dst_row, float *__restrict__ w_sorted) {
+    const int64_t num_dst = sizes[0], nnz = sizes[2];
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t q = int64_t(blockIdx.x) * kBlock + threadIdx.x; q < nnz; q += stride) {
+        const int32_t e = perm[q];
+        int64_t lo = 0, hi = num_dst;                      // largest i with indptr[i] <= e
+        while (hi - lo > 1) {
+            int64_t mid = (lo + hi) >> 1;
+            if (indptr[mid] <= e) lo = mid; else hi = mid;
+        }
+        dst_row[q] = static_cast<int32_t>(lo);
+        w_sorted[q] = edge_w[e];
+    }
+}
+
+// Weights of the sampled estimator of P H, P = D^-1/2 (A + I) D^-1/2 (paper Eq. 1-3): one wavefront
+// per destination row; edge p = (v_i, v_j) gets deg(v_i)/n_i / sqrt((deg(v_i)+1)(deg(v_j)+1)), the
+// row's diagonal term is 1/(deg(v_i)+1).  Computed in double, rounded once to float.
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_gcn_edge_weights(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ src_ids, const int32_t *__restrict__ indptr,
+                   const int32_t *__restrict__ indices, const int64_t *__restrict__ sizes, float *__restrict__ edge_w,
+                   float *__restrict__ self_w) {
+    const int lane = lane_id();
+    const int64_t n = sizes[0];
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t i = wave0; i < n; i += nwaves) {
+        const int64_t v = static_cast<int64_t>(src_ids[i]);
+        const double deg_i = static_cast<double>(static_cast<int64_t>(row_ptr[v + 1]) - static_cast<int64_t>(row_ptr[v]));
+        const int b = indptr[i], e = indptr[i + 1];
+        const double scale = deg_i / static_cast<double>(e - b);
+        if (lane == 0) self_w[i] = static_cast<float>(1.0 / (deg_i + 1.0));
+        for (int p = b + lane; p < e; p += kWave) {
+            const int64_t u = static_cast<int64_t>(src_ids[indices[p]]);
+            const double deg_j = static_cast<double>(static_cast<int64_t>(row_ptr[u + 1]) - static_cast<int64_t>(row_ptr[u]));
+            edge_w[p] = static_cast<float>(scale * (1.0 / sqrt((deg_i + 1.0) * (deg_j + 1.0))));
+        }
+    }
+}
+
 }  // namespace
+
+int run_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *g, const mqg_block *b, float *edge_w, float *self_w, hipStream_t s) {
+    const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(b->cap_dst, kWavesPerBlock)), 256 * 32));
+#define MQG_GCNW(PT, IT)                                                                                              \
+    MQG_LAUNCH(ctx, "k_gcn_edge_weights", s,                                                                          \
+               (k_gcn_edge_weights<PT, IT><<<grid, kBlock, 0, s>>>(static_cast<const PT *>(g->row_ptr),                \
+                                                                   static_cast<const IT *>(b->src_ids), b->indptr,    \
+                                                                   b->indices, b->sizes, edge_w, self_w)))
+    if (g->ptr_type == MQG_I64 && g->idx_type == MQG_I64) MQG_GCNW(int64_t, int64_t);
+    else if (g->ptr_type == MQG_I64) MQG_GCNW(int64_t, int32_t);
+    else if (g->idx_type == MQG_I64) MQG_GCNW(int32_t, int64_t);
+    else MQG_GCNW(int32_t, int32_t);
+#undef MQG_GCNW
+    return MQG_OK;
+}
+
+int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *x,
+                           int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s) {
+    WeightedRows rows{b->indptr, b->indices, edge_w, self_w};
+    if (dtype == MQG_F16)
+        return launch<_Float16>(ctx, "k_weighted_aggregate", rows, &b->sizes[0], b->cap_dst, static_cast<const _Float16 *>(x),
+                                x_stride, static_cast<_Float16 *>(out), out_stride, dim, s);
+    return launch<float>(ctx, "k_weighted_aggregate", rows, &b->sizes[0], b->cap_dst, static_cast<const float *>(x), x_stride,
+                         static_cast<float *>(out), out_stride, dim, s);
+}
 
 int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
                        int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s) {
@@ -285,13 +422,15 @@ int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t 
                          static_cast<float *>(out), out_stride, dim, s);
 }
 
-int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *grad_out, int64_t go_stride,
-                                void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s) {
+// edge_w == nullptr: the mean aggregation's backward; otherwise the weighted one (self_w may be null)
+int run_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *grad_out,
+                           int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s) {
+    const char *who = edge_w ? "mqg_weighted_aggregate_backward: " : "mqg_sage_mean_aggregate_backward: ";
     // scratch for the by-source ordering of the edges, allocated at the first backward call
     const int64_t nnz_cap = b->cap_nnz, src_cap = b->cap_src;
     if (nnz_cap > ctx->bwd_nnz_cap || src_cap > ctx->bwd_src_cap) {
         hipError_t e = hipStreamSynchronize(s);            // earlier work on this stream may still use the old scratch
-        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_sage_mean_aggregate_backward: ") + hipGetErrorString(e));
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string(who) + hipGetErrorString(e));
         free_backward_scratch(ctx);
         const int64_t nn = std::max<int64_t>(std::max(nnz_cap, ctx->max_nnz), 1);
         const int64_t ns = std::max<int64_t>(std::max(src_cap, ctx->max_src), 1);
@@ -301,17 +440,22 @@ int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *gr
                   alloc(reinterpret_cast<void **>(&ctx->bwd.hist), radix_hist_len(nn) * 4) &&
                   alloc(reinterpret_cast<void **>(&ctx->bwd.tile_sums), radix_scan_tiles(nn) * 4) &&
                   alloc(reinterpret_cast<void **>(&ctx->bwd_dst_row), nn * 4) &&
+                  alloc(reinterpret_cast<void **>(&ctx->bwd_w_sorted), nn * 4) &&
                   alloc(reinterpret_cast<void **>(&ctx->bwd_col_ptr), (ns + 2) * 4);
         if (!ok) {
             free_backward_scratch(ctx);
-            return fail(ctx, MQG_ERR_HIP, "mqg_sage_mean_aggregate_backward: scratch allocation failed");
+            return fail(ctx, MQG_ERR_HIP, std::string(who) + "scratch allocation failed");
         }
         ctx->bwd_nnz_cap = nn;
         ctx->bwd_src_cap = ns;
     }
 
     const int egrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(nnz_cap, kBlock)), 8192));
-    MQG_LAUNCH(ctx, "k_edge_dst_rows", s, (k_edge_dst_rows<<<egrid, kBlock, 0, s>>>(b->indptr, b->sizes, ctx->bwd_dst_row)));
+    if (edge_w) {
+        MQG_LAUNCH(ctx, "k_edge_iota", s, (k_edge_iota<<<egrid, kBlock, 0, s>>>(b->sizes, ctx->bwd_dst_row)));
+    } else {
+        MQG_LAUNCH(ctx, "k_edge_dst_rows", s, (k_edge_dst_rows<<<egrid, kBlock, 0, s>>>(b->indptr, b->sizes, ctx->bwd_dst_row)));
+    }
     int bits = 0;
     while (bits < 32 && (static_cast<uint64_t>(std::max<int64_t>(src_cap, 1) - 1) >> bits) != 0) bits += 8;
     int which = -1;
@@ -323,6 +467,19 @@ int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *gr
     const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(src_cap + 1, kBlock)), 8192));
     MQG_LAUNCH(ctx, "k_col_ptr", s, (k_col_ptr<<<cgrid, kBlock, 0, s>>>(sorted_src, b->sizes, ctx->bwd_col_ptr)));
 
+    if (edge_w) {
+        // the sort's payload was the edge position: turn it into (destination row, weight); the
+        // unsorted payload buffer is free again by now unless the sort moved nothing
+        int32_t *dst_sorted = which < 0 ? ctx->bwd.vals[0] : ctx->bwd_dst_row;
+        MQG_LAUNCH(ctx, "k_permute_edges", s,
+                   (k_permute_edges<<<egrid, kBlock, 0, s>>>(sorted_dst, b->indptr, edge_w, b->sizes, dst_sorted, ctx->bwd_w_sorted)));
+        WeightedBackwardRows rows{ctx->bwd_col_ptr, dst_sorted, ctx->bwd_w_sorted, self_w, b->sizes};
+        if (dtype == MQG_F16)
+            return launch<_Float16>(ctx, "k_weighted_aggregate_backward", rows, &b->sizes[1], src_cap,
+                                    static_cast<const _Float16 *>(grad_out), go_stride, static_cast<_Float16 *>(grad_x), gx_stride, dim, s);
+        return launch<float>(ctx, "k_weighted_aggregate_backward", rows, &b->sizes[1], src_cap, static_cast<const float *>(grad_out),
+                             go_stride, static_cast<float *>(grad_x), gx_stride, dim, s);
+    }
     BackwardRows rows{ctx->bwd_col_ptr, sorted_dst, b->indptr};
     if (dtype == MQG_F16)
         return launch<_Float16>(ctx, "k_mean_aggregate_backward", rows, &b->sizes[1], src_cap,

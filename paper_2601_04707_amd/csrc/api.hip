@@ -84,6 +84,8 @@ void free_backward_scratch(mqg_ctx *ctx) {
     (void)hipFree(ctx->bwd.tile_sums);
     (void)hipFree(ctx->bwd_dst_row);
     (void)hipFree(ctx->bwd_col_ptr);
+    (void)hipFree(ctx->bwd_w_sorted);
+    ctx->bwd_w_sorted = nullptr;
     ctx->bwd = RadixBufs{};
     ctx->bwd_dst_row = ctx->bwd_col_ptr = nullptr;
     ctx->bwd_nnz_cap = ctx->bwd_src_cap = 0;
@@ -380,8 +382,51 @@ int mqg_sage_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: bad block capacities");
     if (block->cap_src > 0 && (!grad_out || !grad_x)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: NULL grad_out or grad_x");
     if (go_stride < dim || gx_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sage_mean_aggregate_backward: stride below dim");
-    return mqg::run_mean_aggregate_backward(ctx, block, grad_out, go_stride, grad_x, gx_stride, dim, dtype,
-                                            static_cast<hipStream_t>(stream));
+    return mqg::run_aggregate_backward(ctx, block, nullptr, nullptr, grad_out, go_stride, grad_x, gx_stride, dim, dtype,
+                                       static_cast<hipStream_t>(stream));
+}
+
+int mqg_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *graph, const mqg_block *block, float *edge_w, float *self_w,
+                         mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    int rc = check_graph(ctx, graph, "mqg_gcn_edge_weights");
+    if (rc != MQG_OK) return rc;
+    if (!block || !block->indptr || !block->indices || !block->sizes || !block->src_ids)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gcn_edge_weights: NULL block buffers");
+    if (block->cap_dst < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gcn_edge_weights: negative cap_dst");
+    if (!edge_w || !self_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gcn_edge_weights: NULL edge_w or self_w");
+    return mqg::run_gcn_edge_weights(ctx, graph, block, edge_w, self_w, static_cast<hipStream_t>(stream));
+}
+
+int mqg_weighted_aggregate(mqg_ctx *ctx, const mqg_block *block, const float *edge_w, const float *self_w, const void *x_src,
+                           int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!block || !block->indptr || !block->indices || !block->sizes)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: NULL block buffers");
+    if (!edge_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: NULL edge_w");
+    if (!valid_dtype(dtype) || dim < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: bad dtype or dim");
+    if (block->cap_dst < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: negative cap_dst");
+    if (block->cap_dst > 0 && (!x_src || !out)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: NULL x_src or out");
+    if (x_stride < dim || out_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate: stride below dim");
+    return mqg::run_weighted_aggregate(ctx, block, edge_w, self_w, x_src, x_stride, out, out_stride, dim, dtype,
+                                       static_cast<hipStream_t>(stream));
+}
+
+int mqg_weighted_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const float *edge_w, const float *self_w,
+                                    const void *grad_out, int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim,
+                                    int32_t dtype, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!block || !block->indptr || !block->indices || !block->sizes)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: NULL block buffers");
+    if (!edge_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: NULL edge_w");
+    if (!valid_dtype(dtype) || dim < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: bad dtype or dim");
+    if (block->cap_dst < 0 || block->cap_src < 0 || block->cap_nnz < 0 || block->cap_nnz >= (int64_t(1) << 31))
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: bad block capacities");
+    if (block->cap_src > 0 && (!grad_out || !grad_x))
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: NULL grad_out or grad_x");
+    if (go_stride < dim || gx_stride < dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_weighted_aggregate_backward: stride below dim");
+    return mqg::run_aggregate_backward(ctx, block, edge_w, self_w, grad_out, go_stride, grad_x, gx_stride, dim, dtype,
+                                       static_cast<hipStream_t>(stream));
 }
 
 int mqg_queue_size(double max_prepare_ms, double mean_compute_ms, int64_t total_mem_bytes, int64_t peak_mem_bytes,

@@ -61,6 +61,7 @@ struct mqg_ctx {
     // backward aggregation: edges ordered by source; allocated at the first backward call
     mqg::RadixBufs bwd;
     int32_t *bwd_dst_row = nullptr;      // [bwd_nnz_cap] destination row of every edge
+    float *bwd_w_sorted = nullptr;       // [bwd_nnz_cap] edge weights in the by-source order (weighted backward)
     int32_t *bwd_col_ptr = nullptr;      // [bwd_src_cap + 2] offsets of every source in the sorted edge list
     int64_t bwd_nnz_cap = 0, bwd_src_cap = 0;
     // hash-table dedup (MQG_OPT_DEDUP_HASH); allocated when the option is first used
@@ -119,8 +120,11 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
 int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
                        int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_cache_plan *plan, hipStream_t s);
-int run_mean_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const void *grad_out, int64_t go_stride,
-                                void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s);
+int run_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *grad_out,
+                           int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s);
+int run_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *g, const mqg_block *b, float *edge_w, float *self_w, hipStream_t s);
+int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *x,
+                           int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
 // hash-table dedup (dedup_hash.hip)
 int ensure_hash_scratch(mqg_ctx *ctx);

@@ -29,7 +29,8 @@ EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
-    "mqg_queue_size", "mqg_build_cache_ex",
+    "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
+    "mqg_weighted_aggregate_backward",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -92,6 +93,12 @@ lib.mqg_sage_mean_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, 
 lib.mqg_sage_mean_aggregate_backward.restype = ctypes.c_int
 lib.mqg_sage_mean_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_queue_size.restype = ctypes.c_int
+lib.mqg_gcn_edge_weights.restype = ctypes.c_int
+lib.mqg_gcn_edge_weights.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CBlock), _vp, _vp, _vp]
+lib.mqg_weighted_aggregate.restype = ctypes.c_int
+lib.mqg_weighted_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _vp, _vp, _i64, _vp, _i64, _i32, _i32, _vp]
+lib.mqg_weighted_aggregate_backward.restype = ctypes.c_int
+lib.mqg_weighted_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _vp, _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
                                ctypes.POINTER(_i64)]
 
@@ -311,6 +318,45 @@ def mqg_sage_mean_aggregate_backward(ctx: Context, blocks: Blocks, l: int, grad_
     ctx.check(lib.mqg_sage_mean_aggregate_backward(ctx.h, ctypes.byref(blocks.c[l]), grad_out.data_ptr(),
                                                    grad_out.stride(0), grad_x.data_ptr(), grad_x.stride(0),
                                                    grad_x.shape[1], _dtype(grad_x), _stream(stream)))
+
+
+def mqg_gcn_edge_weights(ctx: Context, graph: Graph, blocks: Blocks, l: int, edge_w: torch.Tensor, self_w: torch.Tensor,
+                         stream=None) -> None:
+    """edge_w: [>= cap_nnz] float32, self_w: [>= cap_dst] float32 (device)."""
+    for t, cap in ((edge_w, blocks.c[l].cap_nnz), (self_w, blocks.c[l].cap_dst)):
+        assert t.is_cuda and t.dtype == torch.float32 and t.is_contiguous() and t.numel() >= cap
+    ctx.check(lib.mqg_gcn_edge_weights(ctx.h, ctypes.byref(graph.c), ctypes.byref(blocks.c[l]), edge_w.data_ptr(),
+                                       self_w.data_ptr(), _stream(stream)))
+
+
+def _weights(edge_w, self_w):
+    assert edge_w.is_cuda and edge_w.dtype == torch.float32 and edge_w.is_contiguous()
+    if self_w is not None:
+        assert self_w.is_cuda and self_w.dtype == torch.float32 and self_w.is_contiguous()
+    return edge_w.data_ptr(), (self_w.data_ptr() if self_w is not None else None)
+
+
+def mqg_weighted_aggregate(ctx: Context, blocks: Blocks, l: int, edge_w: torch.Tensor, self_w: Optional[torch.Tensor],
+                           x: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    assert x.is_cuda and out.is_cuda and x.dtype == out.dtype and x.stride(1) == 1 and out.stride(1) == 1
+    assert x.shape[1] == out.shape[1] and out.shape[0] >= blocks.c[l].cap_dst
+    assert edge_w.numel() >= blocks.c[l].cap_nnz and (self_w is None or self_w.numel() >= blocks.c[l].cap_dst)
+    ew, sw = _weights(edge_w, self_w)
+    ctx.check(lib.mqg_weighted_aggregate(ctx.h, ctypes.byref(blocks.c[l]), ew, sw, x.data_ptr(), x.stride(0),
+                                         out.data_ptr(), out.stride(0), x.shape[1], _dtype(x), _stream(stream)))
+
+
+def mqg_weighted_aggregate_backward(ctx: Context, blocks: Blocks, l: int, edge_w: torch.Tensor,
+                                    self_w: Optional[torch.Tensor], grad_out: torch.Tensor, grad_x: torch.Tensor,
+                                    stream=None) -> None:
+    assert grad_out.is_cuda and grad_x.is_cuda and grad_out.dtype == grad_x.dtype
+    assert grad_out.stride(1) == 1 and grad_x.stride(1) == 1 and grad_out.shape[1] == grad_x.shape[1]
+    assert grad_x.shape[0] >= blocks.c[l].cap_src
+    assert edge_w.numel() >= blocks.c[l].cap_nnz and (self_w is None or self_w.numel() >= blocks.c[l].cap_dst)
+    ew, sw = _weights(edge_w, self_w)
+    ctx.check(lib.mqg_weighted_aggregate_backward(ctx.h, ctypes.byref(blocks.c[l]), ew, sw, grad_out.data_ptr(),
+                                                  grad_out.stride(0), grad_x.data_ptr(), grad_x.stride(0),
+                                                  grad_x.shape[1], _dtype(grad_x), _stream(stream)))
 
 
 def mqg_queue_size(max_prepare_ms: float, mean_compute_ms: float, total_mem_bytes: int, peak_mem_bytes: int,
