@@ -77,6 +77,10 @@ def _load():
     lib.orc_random_walk_scores.argtypes = [i64, vp, vp, vp, i64, vp, i64, vp]
     lib.orc_build_cache_by_score.restype = ctypes.c_int
     lib.orc_build_cache_by_score.argtypes = [i64, vp, i64, vp, vp]
+    lib.orc_exp_ticket.restype = u64
+    lib.orc_exp_ticket.argtypes = [u64]
+    lib.orc_build_cache_drawn_by_score.restype = ctypes.c_int
+    lib.orc_build_cache_drawn_by_score.argtypes = [i64, vp, i64, u64, vp, vp]
     _lib = lib
     return lib
 
@@ -178,6 +182,23 @@ def build_cache_by_score(scores: np.ndarray, num_cached: int, feats: Optional[np
     rc = _load().orc_build_cache_by_score(n, _p(sc), num_cached, _p(ids), _p(slot_of))
     if rc != 0:
         raise ValueError(f"orc_build_cache_by_score failed ({rc})")
+    return _finish_cache(ids, slot_of, num_cached, n, feats)
+
+
+def exp_ticket(r: int) -> int:
+    return int(_load().orc_exp_ticket(ctypes.c_uint64(r & 0xFFFFFFFFFFFFFFFF)))
+
+
+def build_cache_drawn_by_score(scores: np.ndarray, num_cached: int, seed: int,
+                               feats: Optional[np.ndarray] = None) -> Cache:
+    """Membership drawn with probability proportional to the score, without replacement."""
+    sc = np.ascontiguousarray(scores, dtype=np.float64)
+    n = sc.shape[0]
+    ids = np.empty(max(1, num_cached), dtype=np.int64)
+    slot_of = np.empty(max(1, n), dtype=np.int32)
+    rc = _load().orc_build_cache_drawn_by_score(n, _p(sc), num_cached, ctypes.c_uint64(seed), _p(ids), _p(slot_of))
+    if rc != 0:
+        raise ValueError(f"orc_build_cache_drawn_by_score failed ({rc})")
     return _finish_cache(ids, slot_of, num_cached, n, feats)
 
 

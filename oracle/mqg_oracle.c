@@ -23,6 +23,12 @@
  *   - orc_random_walk_scores / orc_build_cache_by_score : Eq. 14-15, the
  *                            short-random-walk probabilities P^(L) used when
  *                            the training set is a small part of the graph.
+ *   - orc_exp_ticket / orc_build_cache_drawn_by_score : "the final sampling
+ *                            probability for the cache is given by P^(L)"
+ *                            (text after Eq. 15) taken literally: membership
+ *                            is drawn with probability proportional to the
+ *                            score, by weighted sampling with random keys
+ *                            (Efraimidis and Spirakis, cited in Sec. III-B).
  *   - orc_sample_blocks    : Sec. III-A "Node-wise Sampling", GraphSAGE
  *                            paragraph: for every node of a layer a fixed
  *                            number s_node of its neighbours is drawn
@@ -628,6 +634,81 @@ int orc_build_cache_by_score(int64_t num_nodes, const double *scores, int64_t nu
     if (!all) return -2;
     for (int64_t v = 0; v < num_nodes; ++v) { all[v].score = scores[v]; all[v].id = v; }
     qsort(all, (size_t)num_nodes, sizeof *all, cmp_score_desc_id_asc);
+    for (int64_t v = 0; v < num_nodes; ++v) slot_of[v] = -1;
+    for (int64_t s = 0; s < num_cached; ++s) {
+        cached_ids[s] = all[s].id;
+        slot_of[all[s].id] = (int32_t)s;
+    }
+    free(all);
+    return 0;
+}
+
+/* ------------------------------------------- weighted draws with real weights */
+
+/*
+ * An exponential variate from 64 random bits, in integers: -log2(r / 2^64)
+ * with 32 fractional bits, for r in [1, 2^64) (r = 0 is treated as 1), in
+ * (0, 64 * 2^32].  With m = r * 2^lz in [2^63, 2^64) (lz = leading zeros) the
+ * integer part is lz + 1 and the fraction's complement comes from the binary
+ * logarithm of m / 2^63 in [1, 2) by repeated squaring: square, and if the
+ * square reached 2 emit a one bit and halve.  Squares are truncated to 64
+ * bits, so the last bits of the fraction are approximate (error < 2^-30 of
+ * one unit); what matters is that the function is a fixed integer
+ * function of r.  Times ln 2 / 2^32 this is Exp(1) distributed.
+ */
+uint64_t orc_exp_ticket(uint64_t r)
+{
+    if (r == 0) r = 1;
+    int lz = 0;
+    while (!(r >> 63)) { r <<= 1; ++lz; }
+    uint64_t m = r, frac = 0;
+    for (int b = 0; b < 32; ++b) {
+        unsigned __int128 sq = (unsigned __int128)m * m;      /* (m/2^63)^2 * 2^126 */
+        uint64_t hi = (uint64_t)(sq >> 64), lo = (uint64_t)sq;
+        if (hi >> 63) {                                       /* square >= 2 */
+            frac = (frac << 1) | 1;
+            m = hi;
+        } else {
+            frac <<= 1;
+            m = (hi << 1) | (lo >> 63);
+        }
+    }
+    return ((uint64_t)(lz + 1) << 32) - frac;
+}
+
+/* Domain tag of the draw below (apart from the blocks' and from the degree-proportional draw). */
+#define ORC_SCORE_DRAW_LAYER (-2)
+
+typedef struct { double key; int64_t id; } orc_dkey_id;
+
+static int cmp_dkey_id(const void *a, const void *b)
+{
+    const orc_dkey_id *x = a, *y = b;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->id != y->id) return x->id < y->id ? -1 : 1;
+    return 0;
+}
+
+/*
+ * Cache membership drawn with probability proportional to a non-negative
+ * score (the P^(L) of Eq. 14-15), without replacement: node i races with the
+ * exponential clock key_i = ticket_i / score_i, ticket_i =
+ * orc_exp_ticket(orc_key(seed, -2, i, 0)) (one IEEE double division; +inf for
+ * a score of 0); the num_cached smallest (key, id) are cached, slot s = the
+ * s-th smallest.
+ */
+int orc_build_cache_drawn_by_score(int64_t num_nodes, const double *scores, int64_t num_cached,
+                                   uint64_t seed, int64_t *cached_ids, int32_t *slot_of)
+{
+    if (num_cached < 0 || num_cached > num_nodes) return -1;
+    orc_dkey_id *all = malloc((size_t)(num_nodes > 0 ? num_nodes : 1) * sizeof *all);
+    if (!all) return -2;
+    for (int64_t v = 0; v < num_nodes; ++v) {
+        double t = (double)orc_exp_ticket(orc_key(seed, ORC_SCORE_DRAW_LAYER, v, 0));
+        all[v].key = scores[v] > 0.0 ? t / scores[v] : INFINITY;
+        all[v].id = v;
+    }
+    qsort(all, (size_t)num_nodes, sizeof *all, cmp_dkey_id);
     for (int64_t v = 0; v < num_nodes; ++v) slot_of[v] = -1;
     for (int64_t s = 0; s < num_cached; ++s) {
         cached_ids[s] = all[s].id;

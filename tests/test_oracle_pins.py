@@ -668,3 +668,70 @@ def test_weighted_aggregate_against_dense_product_and_its_transpose():
     n_i = np.repeat(np.maximum(counts, 1), counts)
     assert np.allclose(oracle.weighted_aggregate(indptr, indices, 1.0 / n_i, None, x),
                        oracle.mean_aggregate(indptr, indices, x), rtol=3e-7, atol=1e-7)
+
+
+# ------------------------------------------------------------------------- draws with real weights
+
+def test_exp_ticket_is_minus_log2_in_fixed_point():
+    import math
+    assert oracle.exp_ticket(1 << 63) == 1 << 32                 # r / 2^64 = 1/2
+    for k in range(64):
+        assert oracle.exp_ticket(1 << k) == (64 - k) << 32       # powers of two are exact
+    assert oracle.exp_ticket(0) == oracle.exp_ticket(1) == 64 << 32
+    assert 1 <= oracle.exp_ticket((1 << 64) - 1) <= 4            # -log2(1 - 2^-64) * 2^32, rounded up
+    rng = np.random.default_rng(31)
+    for r in rng.integers(1, 1 << 63, 3000, dtype=np.uint64).tolist() + [3, 5, 7, (1 << 64) - 12345, 3 << 62]:
+        want = -math.log2(r / 2.0 ** 64) if r < (1 << 53) else 64 - math.log2(r)
+        assert abs(oracle.exp_ticket(r) / 2.0 ** 32 - want) < 2.0 ** -28, r
+    # monotone: a larger uniform never gives a larger ticket
+    rs = np.sort(rng.integers(1, 1 << 63, 2000, dtype=np.uint64))
+    t = [oracle.exp_ticket(int(r)) for r in rs]
+    assert all(a >= b for a, b in zip(t, t[1:]))
+
+
+def test_exp_tickets_are_exponentially_distributed():
+    import math
+    r = [oracle.key(7, 0, 0, j) for j in range(40000)]
+    e = np.array([oracle.exp_ticket(x) for x in r]) * (math.log(2.0) / 2.0 ** 32)
+    assert abs(e.mean() - 1.0) < 0.02 and abs(e.var() - 1.0) < 0.05
+    for q in (0.1, 0.5, 0.9, 0.99):
+        assert abs((e <= -math.log(1 - q)).mean() - q) < 0.01
+
+
+def test_draw_by_score_matches_successive_sampling_probabilities():
+    """Weighted sampling without replacement: the first pick is i with probability w_i / W, a pair
+    {i, j} comes out with w_i/W * w_j/(W - w_i) + w_j/W * w_i/(W - w_j)."""
+    w = np.array([1.0, 2.0, 3.0, 4.0, 10.0, 0.0])
+    W = w.sum()
+    trials = 30000
+    first = np.zeros(6)
+    pairs = {}
+    for seed in range(trials):
+        c = oracle.build_cache_drawn_by_score(w, 2, seed)
+        first[c.cached_ids[0]] += 1
+        key = tuple(sorted(c.cached_ids.tolist()))
+        pairs[key] = pairs.get(key, 0) + 1
+    assert first[5] == 0                                         # a zero score is never drawn
+    p1 = w / W
+    assert np.all(np.abs(first / trials - p1) < 4 * np.sqrt(p1 * (1 - p1) / trials) + 1e-9)
+    for i in range(5):
+        for j in range(i + 1, 5):
+            p = w[i] / W * w[j] / (W - w[i]) + w[j] / W * w[i] / (W - w[j])
+            assert abs(pairs.get((i, j), 0) / trials - p) < 4 * np.sqrt(p * (1 - p) / trials)
+
+
+def test_draw_by_score_restated_with_numpy():
+    rng = np.random.default_rng(33)
+    sc = rng.random(400) ** 4
+    sc[::9] = 0.0
+    seed = 99
+    t = np.array([oracle.exp_ticket(oracle.key(seed, -2, v, 0)) for v in range(400)], dtype=np.float64)
+    with np.errstate(divide="ignore"):
+        key = np.where(sc > 0, t / np.where(sc > 0, sc, 1.0), np.inf)
+    order = np.lexsort((np.arange(400), key))
+    for num_cached in (0, 1, 57, 400):
+        c = oracle.build_cache_drawn_by_score(sc, num_cached, seed)
+        assert np.array_equal(c.cached_ids, order[:num_cached])
+        want = np.full(400, -1, dtype=np.int32)
+        want[order[:num_cached]] = np.arange(num_cached)
+        assert np.array_equal(c.slot_of, want)
