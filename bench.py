@@ -35,7 +35,7 @@ def main() -> int:
     ap.add_argument("--workload", default="medium")
     ap.add_argument("--scale", type=float, default=1.0, help="shrink the graph (debugging only)")
     ap.add_argument("--cache-pct", type=int, default=None)
-    ap.add_argument("--cache-policy", choices=["top", "sampled", "walk"], default="top",
+    ap.add_argument("--cache-policy", choices=["top", "sampled", "walk", "walk-sampled"], default="top",
                     help="how the cache is filled: top degree (the workloads' definition), drawn in proportion "
                          "to degree (paper Eq. 13), or by random-walk scores from the training set (Eq. 14-15)")
     ap.add_argument("--in-flight", type=int, default=3, help="mini-batches in flight (contexts x streams)")
@@ -95,7 +95,7 @@ def main() -> int:
         num_cached = n * cache_pct // 100
         cache = mqg.Cache(g, feats, num_cached, cache_stride=pad_dim)
         train_dev = None
-        if args.cache_policy == "walk":
+        if args.cache_policy in ("walk", "walk-sampled"):
             # the training set: every node the seed batches are drawn from
             gen = torch.Generator()
             gen.manual_seed(2)
@@ -109,7 +109,8 @@ def main() -> int:
         elif args.cache_policy == "sampled":
             mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_DEGREE_SAMPLED, seed=5)
         else:
-            mqg.mqg_build_cache_ex(ctxs[0], g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=train_dev,
+            policy = mqg.MQG_CACHE_RANDOM_WALK if args.cache_policy == "walk" else mqg.MQG_CACHE_RANDOM_WALK_SAMPLED
+            mqg.mqg_build_cache_ex(ctxs[0], g, cache, policy, seed=5, train_ids=train_dev,
                                    step_fanouts=list(reversed(w.fanouts)))
         torch.cuda.synchronize()
     build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0

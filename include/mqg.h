@@ -195,7 +195,7 @@ int mqg_ctx_kernel_names(mqg_ctx *ctx, char *buf, int64_t buf_len);
 int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream);
 
 /*
- * The other two ways the paper fills the cache (Sec. III "Feature Cache").
+ * The other ways the paper fills the cache (Sec. III "Feature Cache").
  *   MQG_CACHE_TOP_DEGREE      what mqg_build_cache does.
  *   MQG_CACHE_DEGREE_SAMPLED  Eq. 13 as stated: membership is drawn with probability proportional
  *                             to in-degree, without replacement - a fresh draw for every `seed`
@@ -216,14 +216,24 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
  *                             scores_out (device double [num_nodes], may be NULL) receives
  *                             P(num_steps).  Membership is the deterministic top of the score, not
  *                             a draw from it.
+ *   MQG_CACHE_RANDOM_WALK_SAMPLED  the same scores, membership drawn from them ("the final
+ *                             sampling probability for the cache", text after Eq. 15): weighted
+ *                             sampling without replacement by an exponential race, key_i =
+ *                             ticket_i / P(num_steps)[i] in double (+inf for a zero score),
+ *                             ticket_i = -log2(r_i / 2^64) in fixed point with 32 fractional
+ *                             bits, computed in integers by 32 squarings of the 64-bit mantissa
+ *                             (truncated products), r_i = mix(mix(mix(mix(seed + G) ^ ~1) ^ i));
+ *                             the num_cached smallest (key, id) are cached, slot s = s-th
+ *                             smallest.
  * train_ids: device [num_train], graph idx_type, ids in [0, num_nodes); step_fanouts: host.
  */
-typedef enum { MQG_CACHE_TOP_DEGREE = 0, MQG_CACHE_DEGREE_SAMPLED = 1, MQG_CACHE_RANDOM_WALK = 2 } mqg_cache_policy;
+typedef enum { MQG_CACHE_TOP_DEGREE = 0, MQG_CACHE_DEGREE_SAMPLED = 1, MQG_CACHE_RANDOM_WALK = 2,
+               MQG_CACHE_RANDOM_WALK_SAMPLED = 3 } mqg_cache_policy;
 
 typedef struct mqg_cache_plan {
     int32_t policy;                      /* mqg_cache_policy                             */
     int32_t num_steps;                   /* RANDOM_WALK: number of steps L, 0..MQG_MAX_LAYERS */
-    uint64_t seed;                       /* DEGREE_SAMPLED                               */
+    uint64_t seed;                       /* DEGREE_SAMPLED, RANDOM_WALK_SAMPLED          */
     const void *train_ids;               /* RANDOM_WALK                                  */
     int64_t num_train;
     const int32_t *step_fanouts;         /* RANDOM_WALK: host [num_steps], each >= 1     */

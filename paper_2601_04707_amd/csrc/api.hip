@@ -282,9 +282,10 @@ int mqg_build_cache_ex(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, const
     if (cache->feat_stride < cache->dim || cache->cache_stride < cache->dim)
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache: stride below dim");
     if (plan) {
-        if (plan->policy != MQG_CACHE_TOP_DEGREE && plan->policy != MQG_CACHE_DEGREE_SAMPLED && plan->policy != MQG_CACHE_RANDOM_WALK)
+        if (plan->policy != MQG_CACHE_TOP_DEGREE && plan->policy != MQG_CACHE_DEGREE_SAMPLED && plan->policy != MQG_CACHE_RANDOM_WALK &&
+            plan->policy != MQG_CACHE_RANDOM_WALK_SAMPLED)
             return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: unknown policy");
-        if (plan->policy == MQG_CACHE_RANDOM_WALK) {
+        if (plan->policy == MQG_CACHE_RANDOM_WALK || plan->policy == MQG_CACHE_RANDOM_WALK_SAMPLED) {
             if (plan->num_steps < 0 || plan->num_steps > MQG_MAX_LAYERS) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: num_steps outside 0..MQG_MAX_LAYERS");
             if (plan->num_train < 0 || (plan->num_train > 0 && !plan->train_ids)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: bad training set");
             if (plan->num_steps > 0 && !plan->step_fanouts) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: step_fanouts is NULL");

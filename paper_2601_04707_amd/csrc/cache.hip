@@ -187,6 +187,20 @@ k_score_keys(const double *__restrict__ score, int64_t n, uint64_t *__restrict__
     if (v < n) key64[v] = ~static_cast<uint64_t>(__double_as_longlong(score[v]));
 }
 
+// Exponential race for a draw in proportion to the score: key = ticket / score as a double (one IEEE
+// division; +inf for a score of 0), ticket = exp_ticket64 of the node's random bits.  Positive
+// doubles order like their bit patterns.
+__global__ void __launch_bounds__(kBlock)
+k_draw_keys(const double *__restrict__ score, int64_t n, uint64_t tag_hash, uint64_t *__restrict__ key64) {
+    int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (v >= n) return;
+    const uint64_t r = mix64(mix64(tag_hash ^ static_cast<uint64_t>(v)));     // slot 0 of node v
+    const double t = static_cast<double>(exp_ticket64(r));
+    const double sc = score[v];
+    const double key = sc > 0.0 ? t / sc : __longlong_as_double(0x7FF0000000000000LL);
+    key64[v] = static_cast<uint64_t>(__double_as_longlong(key));
+}
+
 __global__ void __launch_bounds__(kBlock)
 k_split_low(const uint64_t *__restrict__ key64, int64_t n, uint32_t *__restrict__ lo, int32_t *__restrict__ ids) {
     int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
@@ -267,7 +281,8 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
     const int policy = plan ? plan->policy : MQG_CACHE_TOP_DEGREE;
     hipError_t e = hipMemsetAsync(c->slot_of, 0xFF, static_cast<size_t>(std::max<int64_t>(n, 1)) * sizeof(int32_t), s);
     if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("hipMemsetAsync: ") + hipGetErrorString(e));
-    const bool want_scores = policy == MQG_CACHE_RANDOM_WALK && plan->scores_out;
+    const bool walk = policy == MQG_CACHE_RANDOM_WALK || policy == MQG_CACHE_RANDOM_WALK_SAMPLED;
+    const bool want_scores = walk && plan->scores_out;
     if (n == 0 || (c->num_cached == 0 && !want_scores)) {
         e = hipStreamSynchronize(s);
         return e == hipSuccess ? MQG_OK : fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
@@ -313,7 +328,7 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
             MQG_LAUNCH(ctx, "k_ticket_keys", s, (k_ticket_keys<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, tag_hash, key64)));
         int rc0 = rank_by_key64(ctx, tmp, key64, n, &ranked, s);
         if (rc0 != MQG_OK) return rc0;
-    } else {  // MQG_CACHE_RANDOM_WALK
+    } else {  // MQG_CACHE_RANDOM_WALK, MQG_CACHE_RANDOM_WALK_SAMPLED
         double *pa, *pb, *pass;
         uint64_t *key64;
         if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&pass, n) && tmp.alloc(&key64, n)))
@@ -350,7 +365,12 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
             if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
         }
         if (c->num_cached > 0) {
-            MQG_LAUNCH(ctx, "k_score_keys", s, (k_score_keys<<<ngrid, kBlock, 0, s>>>(cur, n, key64)));
+            if (policy == MQG_CACHE_RANDOM_WALK_SAMPLED) {
+                const uint64_t tag_hash = host_mix64(host_mix64(plan->seed + kGolden) ^ static_cast<uint64_t>(int64_t(-2)));
+                MQG_LAUNCH(ctx, "k_draw_keys", s, (k_draw_keys<<<ngrid, kBlock, 0, s>>>(cur, n, tag_hash, key64)));
+            } else {
+                MQG_LAUNCH(ctx, "k_score_keys", s, (k_score_keys<<<ngrid, kBlock, 0, s>>>(cur, n, key64)));
+            }
             int rc0 = rank_by_key64(ctx, tmp, key64, n, &ranked, s);
             if (rc0 != MQG_OK) return rc0;
         }

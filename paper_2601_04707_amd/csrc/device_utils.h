@@ -79,4 +79,22 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
     return z;
 }
 
+// An exponential variate from 64 random bits in integer arithmetic: -log2(r / 2^64) with 32
+// fractional bits (r = 0 counts as 1).  With m = r << lz in [2^63, 2^64) the integer part is
+// lz + 1; the fraction of log2(m / 2^63) comes bit by bit from repeated squaring (a square that
+// reaches 2 emits a one and is halved), squares truncated to 64 bits.
+__device__ __forceinline__ uint64_t exp_ticket64(uint64_t r) {
+    if (r == 0) r = 1;
+    const int lz = __clzll(static_cast<long long>(r));
+    uint64_t m = r << lz, frac = 0;
+#pragma unroll 4
+    for (int b = 0; b < 32; ++b) {
+        const uint64_t hi = __umul64hi(m, m), lo = m * m;
+        const bool one = (hi >> 63) != 0;
+        frac = (frac << 1) | (one ? 1u : 0u);
+        m = one ? hi : ((hi << 1) | (lo >> 63));
+    }
+    return (static_cast<uint64_t>(lz + 1) << 32) - frac;
+}
+
 }  // namespace mqg

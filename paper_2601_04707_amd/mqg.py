@@ -23,7 +23,7 @@ MQG_F32, MQG_F16 = 0, 1
 MQG_I32, MQG_I64 = 0, 1
 MQG_OPT_FORCE_SLOW_SELECT, MQG_OPT_PROFILE, MQG_OPT_MISS_INFLIGHT_BYTES, MQG_OPT_HEAVY_DEGREE, MQG_OPT_DEDUP_HASH = 1, 2, 3, 4, 5
 MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
-MQG_CACHE_TOP_DEGREE, MQG_CACHE_DEGREE_SAMPLED, MQG_CACHE_RANDOM_WALK = 0, 1, 2
+MQG_CACHE_TOP_DEGREE, MQG_CACHE_DEGREE_SAMPLED, MQG_CACHE_RANDOM_WALK, MQG_CACHE_RANDOM_WALK_SAMPLED = 0, 1, 2, 3
 
 EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
@@ -266,7 +266,7 @@ def mqg_build_cache(ctx: Context, graph: Graph, cache: Cache, stream=None) -> No
 def mqg_build_cache_ex(ctx: Context, graph: Graph, cache: Cache, policy: int, *, seed: int = 0,
                        train_ids: Optional[torch.Tensor] = None, step_fanouts: Sequence[int] = (),
                        scores_out: Optional[torch.Tensor] = None, stream=None) -> None:
-    """Cache filled by one of the three policies (MQG_CACHE_*)."""
+    """Cache filled by one of the policies MQG_CACHE_*."""
     fo = (_i32 * max(1, len(step_fanouts)))(*step_fanouts)
     if train_ids is not None:
         assert train_ids.is_cuda and train_ids.dtype == graph.idx_dtype and train_ids.is_contiguous()

@@ -83,6 +83,35 @@ def test_random_walk_cache_parity(mqg, ptr, idx, fanouts):
         assert reach[want.cached_ids[: len(train) // 2]].mean() > 0.05 or want_scores[want.cached_ids[0]] > 1.0 / len(train)
 
 
+@pytest.mark.parametrize("ptr,idx", [(torch.int64, torch.int64), (torch.int32, torch.int32)])
+def test_cache_drawn_from_random_walk_scores_parity(mqg, ptr, idx):
+    rp, ci = graph(ptr=ptr, idx=idx)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, 6, seed=3).pin_memory()
+    ctx = mqg.Context(g, 8, [2])
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 100].to(idx)
+    fanouts = [10, 5]
+    want_scores = oracle.random_walk_scores(rp.numpy(), ci.numpy(), train.numpy(), fanouts)
+    assert (want_scores == 0).any() and (want_scores > 0).sum() > n // 2
+    seen = []
+    for num_cached, seed in [(n // 100, 0), (n // 100, 1), (n // 5, 2), (n, 3)]:   # n: past the nodes with a positive score
+        cache = mqg.Cache(g, feats, num_cached)
+        scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+        mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK_SAMPLED, seed=seed, train_ids=to_dev(train),
+                               step_fanouts=fanouts, scores_out=scores)
+        torch.cuda.synchronize()
+        assert np.array_equal(scores.cpu().numpy(), want_scores)
+        want = oracle.build_cache_drawn_by_score(want_scores, num_cached, seed, feats.numpy())
+        assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), want.cached_ids)
+        assert np.array_equal(cache.slot_of.cpu().numpy(), want.slot_of)
+        assert cache.cache_rows[:num_cached].cpu().numpy().tobytes() == want.cache_rows.tobytes()
+        seen.append(want.cached_ids)
+    assert not np.array_equal(seen[0], seen[1])                   # another seed, another draw
+    assert want_scores[seen[0]].mean() > 3 * want_scores.mean()   # drawn towards high scores
+    assert (want_scores[seen[0]] > 0).all()
+
+
 def test_policy_argument_errors(mqg):
     rp, ci = graph(n=2000, edges=20_000, max_degree=200)
     g = mqg.Graph(to_dev(rp), to_dev(ci))
