@@ -55,6 +55,10 @@ def _load():
     lib.orc_sample_row.argtypes = [u64, i64, i64, i64, i64, vp]
     lib.orc_sample_block.restype = i64
     lib.orc_sample_block.argtypes = [vp, vp, vp, i64, i64, i64, u64, i64, i64, vp, vp, vp, vp]
+    lib.orc_sample_row_prioritised.restype = i64
+    lib.orc_sample_row_prioritised.argtypes = [u64, i64, i64, i64, i64, vp, vp, vp]
+    lib.orc_sample_block_prioritised.restype = i64
+    lib.orc_sample_block_prioritised.argtypes = [vp, vp, vp, i64, i64, i64, u64, i64, i64, vp, vp, vp, vp, vp]
     lib.orc_gather.restype = None
     lib.orc_gather.argtypes = [vp, i64, vp, i64, vp, vp, i64, i64, vp, i64, vp, vp]
     lib.orc_half_to_double.restype = ctypes.c_double
@@ -221,10 +225,21 @@ class Block:
         return int(self.indices.shape[0])
 
 
-def sample_blocks(row_ptr, col_idx, seeds, fanouts: Sequence[int], rng_seed: int) -> List[Block]:
+def sample_row_prioritised(rng_seed: int, layer: int, node: int, nbrs, fanout: int, slot_of) -> np.ndarray:
+    nb = _i64(nbrs)
+    so = np.ascontiguousarray(slot_of, dtype=np.int32)
+    out = np.empty(max(1, fanout), dtype=np.int64)
+    c = _load().orc_sample_row_prioritised(ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), layer, node,
+                                           nb.shape[0], fanout, _p(nb), _p(so), _p(out))
+    return out[:c].copy()
+
+
+def sample_blocks(row_ptr, col_idx, seeds, fanouts: Sequence[int], rng_seed: int, prio_slot_of=None) -> List[Block]:
     """blocks[l] feeds GNN layer l; blocks[L-1] has the seeds as destinations and
-    uses fanouts[L-1]; the destinations of blocks[l-1] are the sources of blocks[l]."""
+    uses fanouts[L-1]; the destinations of blocks[l-1] are the sources of blocks[l].
+    prio_slot_of (int32[N], >= 0 for cached nodes): cached neighbours are drawn first."""
     rp, ci, dst = _i64(row_ptr), _i64(col_idx), _i64(seeds)
+    prio = None if prio_slot_of is None else np.ascontiguousarray(prio_slot_of, dtype=np.int32)
     n = rp.shape[0] - 1
     L = len(fanouts)
     blocks: List[Optional[Block]] = [None] * L
@@ -239,9 +254,14 @@ def sample_blocks(row_ptr, col_idx, seeds, fanouts: Sequence[int], rng_seed: int
         nbr = np.empty(max(1, cap_nnz), dtype=np.int64)
         src = np.empty(max(1, cap_src), dtype=np.int64)
         idx = np.empty(max(1, cap_nnz), dtype=np.int32)
-        ns = lib.orc_sample_block(_p(rp), _p(ci), _p(dst), nd, k, l,
-                                  ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), cap_nnz, cap_src,
-                                  _p(indptr), _p(nbr), _p(src), _p(idx))
+        if prio is None:
+            ns = lib.orc_sample_block(_p(rp), _p(ci), _p(dst), nd, k, l,
+                                      ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), cap_nnz, cap_src,
+                                      _p(indptr), _p(nbr), _p(src), _p(idx))
+        else:
+            ns = lib.orc_sample_block_prioritised(_p(rp), _p(ci), _p(dst), nd, k, l,
+                                                  ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), cap_nnz, cap_src,
+                                                  _p(indptr), _p(nbr), _p(src), _p(idx), _p(prio))
         if ns < 0:
             raise RuntimeError(f"orc_sample_block failed ({ns})")
         nnz = int(indptr[nd])

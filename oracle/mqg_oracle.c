@@ -37,6 +37,11 @@
  *                            is re-sampled in every layer it appears in.
  *                            Sec. IV "Mini-Batch Transfer": a mini-batch
  *                            carries topology and features.
+ *   - orc_sample_block_prioritised : Sec. I on global neighbour sampling: the
+ *                            sampler "prioritizes neighbors in the cache" so
+ *                            that fewer distinct uncached nodes enter a
+ *                            mini-batch.  Read as: a row's cached neighbours
+ *                            are drawn before its uncached ones.
  *   - orc_gather           : Sec. IV "Mini-Batch Transfer To GPU": features
  *                            of nodes absent from the GPU cache come from
  *                            host memory, the rest from the cache; the
@@ -171,6 +176,45 @@ int64_t orc_sample_row(uint64_t rng_seed, int64_t layer, int64_t node, int64_t d
     return k;
 }
 
+typedef struct { int uncached; uint64_t key; int64_t slot; } orc_prio_key_slot;
+
+static int cmp_prio_key_slot(const void *a, const void *b)
+{
+    const orc_prio_key_slot *x = a, *y = b;
+    if (x->uncached != y->uncached) return x->uncached < y->uncached ? -1 : 1;
+    if (x->key != y->key) return x->key < y->key ? -1 : 1;
+    if (x->slot != y->slot) return x->slot < y->slot ? -1 : 1;
+    return 0;
+}
+
+/*
+ * Cache-prioritised choice for one adjacency row nbrs[0..d): as orc_sample_row,
+ * but the k slots are the first k in the order (not cached, key, slot) - every
+ * cached neighbour (slot_of >= 0) goes before every uncached one, and within
+ * each class the draw is the uniform one.  With c cached neighbours the row
+ * keeps min(k, c) of them, uniformly, and fills up with k - c uncached ones,
+ * uniformly.  Chosen slots ascending; returns min(k, d).
+ */
+int64_t orc_sample_row_prioritised(uint64_t rng_seed, int64_t layer, int64_t node, int64_t d, int64_t k,
+                                   const int64_t *nbrs, const int32_t *slot_of, int64_t *out_slots)
+{
+    if (d <= k) {
+        for (int64_t j = 0; j < d; ++j) out_slots[j] = j;
+        return d;
+    }
+    orc_prio_key_slot *ks = malloc((size_t)d * sizeof *ks);
+    for (int64_t j = 0; j < d; ++j) {
+        ks[j].uncached = slot_of[nbrs[j]] < 0;
+        ks[j].key = orc_key(rng_seed, layer, node, j);
+        ks[j].slot = j;
+    }
+    qsort(ks, (size_t)d, sizeof *ks, cmp_prio_key_slot);
+    for (int64_t j = 0; j < k; ++j) out_slots[j] = ks[j].slot;
+    free(ks);
+    qsort(out_slots, (size_t)k, sizeof *out_slots, cmp_i64);
+    return k;
+}
+
 typedef struct { int64_t id; int64_t pos; } orc_id_pos;
 
 static int cmp_id_pos(const void *a, const void *b)
@@ -212,10 +256,34 @@ static int64_t find_i64(const int64_t *a, int64_t n, int64_t x)
  *   indices[nnz]        position of nbr[e] in src
  * Returns num_src, or a negative value on capacity overflow / no memory.
  */
+static int64_t sample_block(const int64_t *row_ptr, const int64_t *col_idx, const int64_t *dst,
+                            int64_t num_dst, int64_t k, int64_t layer, uint64_t rng_seed,
+                            int64_t cap_nnz, int64_t cap_src, int64_t *indptr, int64_t *nbr,
+                            int64_t *src, int32_t *indices, const int32_t *prio_slot_of);
+
 int64_t orc_sample_block(const int64_t *row_ptr, const int64_t *col_idx, const int64_t *dst,
                          int64_t num_dst, int64_t k, int64_t layer, uint64_t rng_seed,
                          int64_t cap_nnz, int64_t cap_src, int64_t *indptr, int64_t *nbr,
                          int64_t *src, int32_t *indices)
+{
+    return sample_block(row_ptr, col_idx, dst, num_dst, k, layer, rng_seed, cap_nnz, cap_src, indptr, nbr,
+                        src, indices, NULL);
+}
+
+/* The same block with every row drawn by orc_sample_row_prioritised against the cache table slot_of. */
+int64_t orc_sample_block_prioritised(const int64_t *row_ptr, const int64_t *col_idx, const int64_t *dst,
+                                     int64_t num_dst, int64_t k, int64_t layer, uint64_t rng_seed,
+                                     int64_t cap_nnz, int64_t cap_src, int64_t *indptr, int64_t *nbr,
+                                     int64_t *src, int32_t *indices, const int32_t *slot_of)
+{
+    return sample_block(row_ptr, col_idx, dst, num_dst, k, layer, rng_seed, cap_nnz, cap_src, indptr, nbr,
+                        src, indices, slot_of);
+}
+
+static int64_t sample_block(const int64_t *row_ptr, const int64_t *col_idx, const int64_t *dst,
+                            int64_t num_dst, int64_t k, int64_t layer, uint64_t rng_seed,
+                            int64_t cap_nnz, int64_t cap_src, int64_t *indptr, int64_t *nbr,
+                            int64_t *src, int32_t *indices, const int32_t *prio_slot_of)
 {
     int64_t *slots = malloc((size_t)(k > 0 ? k : 1) * sizeof *slots);
     int64_t nnz = 0;
@@ -223,7 +291,9 @@ int64_t orc_sample_block(const int64_t *row_ptr, const int64_t *col_idx, const i
     for (int64_t i = 0; i < num_dst; ++i) {
         int64_t v = dst[i];
         int64_t start = row_ptr[v], d = row_ptr[v + 1] - start;
-        int64_t c = orc_sample_row(rng_seed, layer, v, d, k, slots);
+        int64_t c = prio_slot_of
+                        ? orc_sample_row_prioritised(rng_seed, layer, v, d, k, col_idx + start, prio_slot_of, slots)
+                        : orc_sample_row(rng_seed, layer, v, d, k, slots);
         if (nnz + c > cap_nnz) { free(slots); return -2; }
         for (int64_t j = 0; j < c; ++j) nbr[nnz + j] = col_idx[start + slots[j]];
         nnz += c;

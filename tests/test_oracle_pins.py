@@ -735,3 +735,71 @@ def test_draw_by_score_restated_with_numpy():
         want = np.full(400, -1, dtype=np.int32)
         want[order[:num_cached]] = np.arange(num_cached)
         assert np.array_equal(c.slot_of, want)
+
+
+# ------------------------------------------------------------------------- cache-prioritised sampling
+
+def test_prioritised_row_equals_python_sort_and_keeps_cached_first():
+    rng = np.random.default_rng(41)
+    for trial in range(60):
+        d = int(rng.integers(1, 200))
+        k = int(rng.integers(1, 30))
+        n = 500
+        nbrs = rng.choice(n, size=d, replace=False)
+        slot_of = np.where(rng.random(n) < rng.choice([0.0, 0.05, 0.3, 0.9, 1.0]), 7, -1).astype(np.int32)
+        got = oracle.sample_row_prioritised(trial, 2, 11, nbrs, k, slot_of)
+        if d <= k:
+            assert got.tolist() == list(range(d))
+            continue
+        order = sorted(range(d), key=lambda j: (slot_of[nbrs[j]] < 0, oracle.key(trial, 2, 11, j), j))
+        assert got.tolist() == sorted(order[:k])
+        c = int((slot_of[nbrs] >= 0).sum())
+        assert int((slot_of[nbrs[got]] >= 0).sum()) == min(k, c)
+        # no cache at all, or everything cached: the plain uniform draw
+        for so in (np.full(n, -1, np.int32), np.zeros(n, np.int32)):
+            assert np.array_equal(oracle.sample_row_prioritised(trial, 2, 11, nbrs, k, so),
+                                  oracle.sample_row(trial, 2, 11, d, k))
+
+
+def test_prioritised_draw_is_uniform_within_each_class():
+    d, k, n = 30, 6, 30
+    nbrs = np.arange(n)
+    slot_of = np.full(n, -1, np.int32)
+    slot_of[:12] = 1                                             # 12 cached > k: only cached ones, k/12 each
+    cnt = np.zeros(d)
+    trials = 6000
+    for s in range(trials):
+        cnt[oracle.sample_row_prioritised(s, 0, 5, nbrs, k, slot_of)] += 1
+    assert cnt[12:].sum() == 0
+    p = k / 12
+    assert np.all(np.abs(cnt[:12] / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials))
+    slot_of[:] = -1
+    slot_of[[3, 17]] = 1                                         # 2 cached < k: both always, the rest (k-2)/28 each
+    cnt[:] = 0
+    for s in range(trials):
+        cnt[oracle.sample_row_prioritised(s, 0, 5, nbrs, k, slot_of)] += 1
+    assert cnt[3] == trials and cnt[17] == trials
+    rest = np.delete(cnt, [3, 17])
+    p = (k - 2) / 28
+    assert np.all(np.abs(rest / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials))
+
+
+def test_prioritised_blocks_structure_and_fewer_uncached_sources():
+    rp, ci = tiny_graph(3000, 90000, seed=42)
+    n = len(rp) - 1
+    cache = oracle.build_cache(rp, n // 5)
+    seeds = np.random.default_rng(1).choice(n, 64, replace=False)
+    plain = oracle.sample_blocks(rp, ci, seeds, [10, 5], 9)
+    prio = oracle.sample_blocks(rp, ci, seeds, [10, 5], 9, prio_slot_of=cache.slot_of)
+    for l in (1, 0):
+        b = prio[l]
+        dst = seeds if l == 1 else prio[1].src_ids
+        assert np.array_equal(b.src_ids[:b.num_dst], dst)
+        assert np.array_equal(np.diff(b.indptr), np.minimum(np.diff(rp)[dst], [10, 5][l]))
+        assert np.array_equal(b.src_ids[b.indices], b.nbr_global)
+        new = b.src_ids[b.num_dst:]
+        assert np.all(np.diff(new) > 0) and not np.intersect1d(new, dst).size
+        for i, v in enumerate(dst[:50]):                       # every sampled neighbour is a neighbour
+            assert np.isin(b.nbr_global[b.indptr[i]:b.indptr[i + 1]], ci[rp[v]:rp[v + 1]]).all()
+    unc = lambda blocks: int((cache.slot_of[blocks[0].src_ids] < 0).sum())
+    assert unc(prio) < 0.7 * unc(plain)
