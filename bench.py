@@ -42,6 +42,9 @@ def main() -> int:
     ap.add_argument("--miss-inflight-kb", type=int, default=None, help="KiB of host reads the miss gather keeps outstanding")
     ap.add_argument("--dedup", choices=["bitmap", "hash"], default="bitmap",
                     help="frontier dedup: node-indexed bitmap and position table (default) or hash table and sort")
+    ap.add_argument("--prioritise-cache", action="store_true",
+                    help="cache-prioritised neighbour sampling: a row's cached neighbours are drawn first "
+                         "(another sampling distribution than the workloads define; for comparison)")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -114,6 +117,13 @@ def main() -> int:
                                    step_fanouts=list(reversed(w.fanouts)))
         torch.cuda.synchronize()
     build_cache_ms = (time.time() - t0) * 1e3 if cache_pct is not None else 0.0
+    if args.prioritise_cache:
+        if cache_pct is None:
+            print("bench.py: --prioritise-cache needs a cache", file=sys.stderr)
+            return 2
+        for c in ctxs:
+            c.set_sampling_priority(cache)
+        torch.cuda.synchronize()
 
     for c in ctxs:
         if args.miss_inflight_kb is not None:
@@ -232,7 +242,7 @@ def main() -> int:
     if args.dedup == "bitmap":                             # its one scan per block goes by the shared name
         dedup_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / 2
     sample_us = dedup_us + sum(v["us_per_step"] for k, v in kern.items()
-                               if k in ("k_init_seeds", "k_row_info", "k_row_offsets", "k_sample"))
+                               if k in ("k_init_seeds", "k_row_info", "k_row_offsets", "k_sample", "k_sample_prio"))
     sample_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / (2 if args.dedup == "bitmap" else 1)
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
@@ -241,7 +251,7 @@ def main() -> int:
     # operations = 37 lane-cycles; the chip has 256 CUs x 4 SIMDs x 16 lanes at 2.4 GHz.
     keys_per_step = keys_eval / max(keys_batches, 1)
     alu_peak_keys = 256 * 4 * 16 * 2.4e9 / 37.0
-    k_sample_us = kern.get("k_sample", {}).get("us_per_step", 0.0)
+    k_sample_us = kern.get("k_sample_prio" if args.prioritise_cache else "k_sample", {}).get("us_per_step", 0.0)
     sampling = {
         "edges_per_s_sampling_alone": round(edges / K / max(sample_us, 1e-9) * 1e6, 1),
         "us_per_step": round(sample_us, 1), "kernel_launches_per_step": sum(
@@ -388,7 +398,8 @@ def main() -> int:
                                f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
                                f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({args.cache_policy}), "
                                f"rest in pinned host memory",
-                   "in_flight": nfl, "global_batch": w.batch, "dedup": args.dedup},
+                   "in_flight": nfl, "global_batch": w.batch, "dedup": args.dedup,
+                   "sampling": "cached neighbours first" if args.prioritise_cache else "uniform"},
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
         "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
         "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),

@@ -265,6 +265,25 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
                       mqg_block *blocks, mqg_stream stream);
 
 /*
+ * Cache-prioritised neighbour sampling (paper Sec. I on global neighbour
+ * sampling: the sampler prefers neighbours that are in the cache, which cuts
+ * the number of distinct uncached rows a mini-batch needs).  After this call
+ * every mqg_sample_blocks on `ctx` chooses, for a row with more neighbours than
+ * the fanout k, the first k slots in the order (not cached, key, slot) with the
+ * keys of mqg_sample_blocks: with c cached neighbours the row keeps min(k, c)
+ * of them, uniformly, and fills up with uncached ones, uniformly.  Rows of at
+ * most k neighbours are kept whole as before.
+ * cache: membership is read from cache->slot_of (device, >= 0 = cached) into a
+ * bitmap of num_nodes bits, and the number of cached neighbours of every node
+ * of `graph` is tabulated (one pass over the adjacency, 4 bytes per node), both
+ * owned by the context, on `stream`; call again after the cache has been
+ * rebuilt.  cache == NULL switches back to the uniform draw (graph is then not
+ * read).  The first call allocates the two tables.
+ */
+int mqg_ctx_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *graph, const mqg_cache *cache,
+                                  mqg_stream stream);
+
+/*
  * Feature gather through the cache (paper Sec. IV "Mini-Batch Transfer To
  * GPU": rows of cached nodes come from GPU memory, the others from host
  * memory).  out[i, 0:dim] = F[ids[i], 0:dim] byte for byte.

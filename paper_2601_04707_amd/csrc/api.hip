@@ -189,6 +189,8 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->counters);
     mqg::free_backward_scratch(c);
     mqg::free_hash_scratch(c);
+    (void)hipFree(c->prio_bitmap);
+    (void)hipFree(c->prio_count);
     for (auto &r : c->prof_recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -295,6 +297,18 @@ int mqg_build_cache_ex(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, const
         }
     }
     return mqg::run_build_cache(ctx, g, cache, plan, static_cast<hipStream_t>(stream));
+}
+
+int mqg_ctx_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (cache) {
+        int rc = check_graph(ctx, g, "mqg_ctx_set_sampling_priority");
+        if (rc != MQG_OK) return rc;
+        if (!cache->slot_of) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_sampling_priority: cache->slot_of is NULL");
+        if (cache->num_nodes != ctx->num_nodes)
+            return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_sampling_priority: cache->num_nodes differs from the context's graph");
+    }
+    return mqg::run_set_sampling_priority(ctx, g, cache, static_cast<hipStream_t>(stream));
 }
 
 int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream) {

@@ -64,6 +64,10 @@ struct mqg_ctx {
     float *bwd_w_sorted = nullptr;       // [bwd_nnz_cap] edge weights in the by-source order (weighted backward)
     int32_t *bwd_col_ptr = nullptr;      // [bwd_src_cap + 2] offsets of every source in the sorted edge list
     int64_t bwd_nnz_cap = 0, bwd_src_cap = 0;
+    // cache-prioritised neighbour sampling (mqg_ctx_set_sampling_priority)
+    bool prio_enabled = false;
+    uint32_t *prio_bitmap = nullptr;     // [bitmap_words] bit v = node v is cached
+    int32_t *prio_count = nullptr;       // [num_nodes] number of cached neighbours of every node
     // hash-table dedup (MQG_OPT_DEDUP_HASH); allocated when the option is first used
     bool dedup_hash = false;
     unsigned long long *hash_table = nullptr;      // [hash_capacity] (id << 32 | position), all ones = empty
@@ -126,6 +130,7 @@ int run_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *g, const mqg_block *b, f
 int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *x,
                            int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
+int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s);
 // hash-table dedup (dedup_hash.hip)
 int ensure_hash_scratch(mqg_ctx *ctx);
 void free_hash_scratch(mqg_ctx *ctx);

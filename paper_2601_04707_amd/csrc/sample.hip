@@ -418,6 +418,333 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
 }
 
 // ------------------------------------------------------------------------------------------
+// Cache-prioritised selection (the paper's Sec. I on global neighbour sampling: neighbours that are
+// in the feature cache are preferred, so that fewer distinct uncached rows enter a mini-batch).
+// The k slots of a row are the first k in the order (not cached, key, slot): with c cached
+// neighbours the row keeps min(k, c) of them, drawn uniformly, and fills up from the uncached ones,
+// drawn uniformly.  `prio` is a bitmap over the nodes, bit set = cached.
+
+__device__ __forceinline__ bool prio_less(bool ua, uint64_t ka, int sa, bool ub, uint64_t kb, int sb) {
+    return ua != ub ? !ua : pair_less(ka, sa, kb, sb);
+}
+
+template <typename IdxT>
+__device__ __forceinline__ bool is_cached(const IdxT *__restrict__ row, int j, const uint32_t *__restrict__ prio) {
+    const uint32_t u = static_cast<uint32_t>(row[j]);
+    return (prio[u >> 5] >> (u & 31)) & 1u;
+}
+
+// k rounds of wave-wide minimum extraction in the (not cached, key, slot) order; unconditional.
+template <typename IdxT>
+__device__ void select_by_repeated_min_prio(const IdxT *__restrict__ col_idx, int64_t start, int d, int k, uint64_t hv,
+                                            int32_t out_base, const SampleArgs &a, const uint32_t *__restrict__ prio) {
+    const int lane = lane_id();
+    const RowKeys key_of(hv);
+    const IdxT *row = col_idx + start;
+    bool prev_unc = false;
+    uint64_t prev_key = 0;
+    int prev_slot = -1;
+    int my_slot = -1;
+    for (int r = 0; r < k; ++r) {
+        bool best_unc = true;
+        uint64_t best_key = kMaxKey;
+        int best_slot = 0x7FFFFFFF;
+        for (int base = 0; base < d; base += kWave) {
+            int j = base + lane;
+            if (j < d) {
+                const uint64_t key = key_of(j);
+                const bool unc = !is_cached(row, j, prio);
+                const bool above = (r == 0) || prio_less(prev_unc, prev_key, prev_slot, unc, key, j);
+                if (above && prio_less(unc, key, j, best_unc, best_key, best_slot)) {
+                    best_unc = unc;
+                    best_key = key;
+                    best_slot = j;
+                }
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const uint64_t ok = __shfl_xor(best_key, off, 64);
+            const int os = __shfl_xor(best_slot, off, 64);
+            const bool ou = __shfl_xor(static_cast<int>(best_unc), off, 64) != 0;
+            if (prio_less(ou, ok, os, best_unc, best_key, best_slot)) {
+                best_unc = ou;
+                best_key = ok;
+                best_slot = os;
+            }
+        }
+        prev_unc = best_unc;
+        prev_key = best_key;
+        prev_slot = best_slot;
+        if (lane == r) my_slot = best_slot;
+    }
+    int rank = 0;
+    for (int t = 0; t < k; ++t) {
+        int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
+        rank += (other < my_slot) ? 1 : 0;
+    }
+    if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
+}
+
+// Candidate test shared by both shapes of the prioritised kernel: which pool competes and under
+// which key threshold (about 2k+32 candidates are expected to pass).
+struct PrioRule {
+    bool only_cached;        // at least k cached neighbours: only they compete
+    uint64_t thr;
+    __device__ __forceinline__ PrioRule(int d, int k, int cached) {
+        only_cached = cached >= k;
+        const int pool = only_cached ? cached : d - cached;
+        const int expect = 2 * (only_cached ? k : k - cached) + 32;
+        thr = kMaxKey;
+        if (pool > expect) thr = static_cast<uint64_t>((double(expect) / double(pool)) * 18446744073709551616.0);
+    }
+    __device__ __forceinline__ bool operator()(bool is_cached_slot, uint64_t key) const {
+        return only_cached ? (is_cached_slot && key <= thr) : (is_cached_slot || key <= thr);
+    }
+};
+
+constexpr int kPrioUnroll = 4;   // chunks of 64 slots whose loads are issued together
+
+// Hubs: the four wavefronts of a workgroup share one row, as in sample_hubs.
+template <typename IdxT>
+__device__ void sample_hubs_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, const SampleArgs &a,
+                                 const uint32_t *__restrict__ prio, const int32_t *__restrict__ prio_count,
+                                 const int32_t *__restrict__ heavy_rows, int nheavy, int first, int step,
+                                 uint64_t *ck, uint32_t *cs, int32_t *sel_slot, int *cnt_s) {
+    const int tid = threadIdx.x;
+    const int lane = lane_id();
+    const int wave = tid >> 6;
+    const int k = a.fanout;
+    for (int h = first; h < nheavy; h += step) {
+        const int row = heavy_rows[h];
+        const int64_t start = a.row_start[row];
+        const int d = a.row_deg[row];
+        const int32_t out_base = a.indptr[row];
+        const IdxT node = dst_ids[row];
+        const uint64_t hv = mix64(a.layer_hash ^ uint64_t(node));
+        const RowKeys key_of(hv);
+        const IdxT *nbrs = col_idx + start;
+        const PrioRule rule(d, k, prio_count[node]);
+        if (tid == 0) *cnt_s = 0;
+        __syncthreads();
+        for (int base = 0; base < d; base += kPrioUnroll * kBlock) {
+            uint32_t u[kPrioUnroll], wbits[kPrioUnroll];
+#pragma unroll
+            for (int q = 0; q < kPrioUnroll; ++q) {
+                const int j = base + q * kBlock + tid;
+                u[q] = j < d ? static_cast<uint32_t>(nbrs[j]) : 0u;
+            }
+#pragma unroll
+            for (int q = 0; q < kPrioUnroll; ++q) wbits[q] = prio[u[q] >> 5];
+#pragma unroll
+            for (int q = 0; q < kPrioUnroll; ++q) {
+                const int j = base + q * kBlock + tid;
+                const bool cj = j < d && ((wbits[q] >> (u[q] & 31)) & 1u);
+                const uint64_t key = key_of(j);
+                const bool c = j < d && rule(cj, key);
+                const uint64_t m = ballot64(c);
+                if (m) {
+                    int p0 = 0;
+                    if (lane == 0) p0 = atomicAdd(cnt_s, popc64(m));
+                    p0 = __shfl(p0, 0, 64);
+                    if (c) {
+                        const int p = p0 + popc64(m & lanes_below(lane));
+                        if (p < kCandidates) {
+                            ck[p] = key;
+                            cs[p] = static_cast<uint32_t>(j) | (cj ? 0u : 0x80000000u);
+                        }
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const int cnt = *cnt_s;
+        if (cnt < k || cnt > kCandidates) {                // workgroup-uniform; practically never
+            if (wave == 0) select_by_repeated_min_prio(col_idx, start, d, k, hv, out_base, a, prio);
+            __syncthreads();
+            continue;
+        }
+        if (tid < cnt) {
+            const uint64_t my_key = ck[tid];
+            const uint32_t my_cs = cs[tid];
+            int rank = 0;
+            for (int t = 0; t < cnt; ++t) {
+                const uint32_t o = cs[t];
+                rank += prio_less((o >> 31) != 0, ck[t], static_cast<int>(o & 0x7FFFFFFFu), (my_cs >> 31) != 0, my_key,
+                                  static_cast<int>(my_cs & 0x7FFFFFFFu)) ? 1 : 0;
+            }
+            if (rank < k) sel_slot[rank] = static_cast<int32_t>(my_cs & 0x7FFFFFFFu);
+        }
+        __syncthreads();
+        if (wave == 0) {
+            const int my_slot = lane < k ? sel_slot[lane] : 0x7FFFFFFF;
+            int rank = 0;
+            for (int t = 0; t < k; ++t) {
+                int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
+                rank += (other < my_slot) ? 1 : 0;
+            }
+            if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
+        }
+        __syncthreads();
+    }
+}
+
+// Same launch shape as k_sample: the first hub_blocks workgroups take the hubs, every other
+// workgroup gives each of its four wavefronts one destination.
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_sample_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, SampleArgs a,
+              const uint32_t *__restrict__ prio, const int32_t *__restrict__ prio_count,
+              const int32_t *__restrict__ heavy_rows, const int32_t *__restrict__ heavy_count, int hub_blocks) {
+    __shared__ uint64_t cand_key[kWavesPerBlock][kCandidates];
+    __shared__ uint32_t cand_slot[kWavesPerBlock][kCandidates];   // bit 31: not cached
+    __shared__ int32_t sel_slot[kWave];
+    __shared__ int cnt_s;
+    if (static_cast<int>(blockIdx.x) < hub_blocks) {
+        sample_hubs_prio(col_idx, dst_ids, a, prio, prio_count, heavy_rows, *heavy_count, static_cast<int>(blockIdx.x),
+                         hub_blocks, cand_key[0], cand_slot[0], sel_slot, &cnt_s);
+        return;
+    }
+    const int lane = lane_id();
+    const int wave = static_cast<int>(threadIdx.x) >> 6;
+    const int64_t n = a.sizes[0];
+    const int64_t row = (int64_t(blockIdx.x) - hub_blocks) * kWavesPerBlock + wave;
+    if (row >= n) return;
+
+    const int64_t start = a.row_start[row];
+    const int d = a.row_deg[row];
+    const int k = a.fanout;
+    const int32_t out_base = a.indptr[row];
+    if (d <= k) {
+        if (lane < d) emit_neighbour(col_idx, start, lane, out_base + lane, a);
+        return;
+    }
+    if (d > a.heavy_degree) return;                        // a hub: sampled by the first workgroups
+    const IdxT node = dst_ids[row];
+    const uint64_t hv = mix64(a.layer_hash ^ uint64_t(node));
+    if (a.force_slow) {
+        select_by_repeated_min_prio(col_idx, start, d, k, hv, out_base, a, prio);
+        return;
+    }
+    const IdxT *nbrs = col_idx + start;
+    if (d <= kWave) {
+        const bool valid = lane < d;
+        const uint64_t key = valid ? RowKeys(hv)(lane) : kMaxKey;
+        const bool unc = valid ? !is_cached(nbrs, lane, prio) : true;
+        const uint64_t um = ballot64(unc);
+        int rank = 0;
+        for (int t = 0; t < d; ++t) {
+            const uint64_t other = readlane64(key, t);
+            rank += prio_less(((um >> t) & 1) != 0, other, t, unc, key, lane) ? 1 : 0;
+        }
+        const bool sel = valid && rank < k;
+        const uint64_t m = ballot64(sel);
+        if (sel) emit_neighbour(col_idx, start, lane, out_base + popc64(m & lanes_below(lane)), a);
+        return;
+    }
+
+    // d > 64.  The number of cached neighbours of the row (tabulated when the priority was set)
+    // decides the pool the threshold applies to: with at least k of them only cached slots compete;
+    // otherwise all of them are taken and the uncached slots compete for the rest.
+    const PrioRule rule(d, k, prio_count[node]);
+    uint64_t *ck = cand_key[wave];
+    uint32_t *cs = cand_slot[wave];
+    int cnt = 0;
+    const RowKeys key_of(hv);
+    for (int base = 0; base < d; base += kPrioUnroll * kWave) {
+        uint32_t u[kPrioUnroll], wbits[kPrioUnroll];
+#pragma unroll
+        for (int q = 0; q < kPrioUnroll; ++q) {
+            const int j = base + q * kWave + lane;
+            u[q] = j < d ? static_cast<uint32_t>(nbrs[j]) : 0u;
+        }
+#pragma unroll
+        for (int q = 0; q < kPrioUnroll; ++q) wbits[q] = prio[u[q] >> 5];
+#pragma unroll
+        for (int q = 0; q < kPrioUnroll; ++q) {
+            const int j = base + q * kWave + lane;
+            const bool cj = j < d && ((wbits[q] >> (u[q] & 31)) & 1u);
+            const uint64_t key = key_of(j);
+            const bool c = j < d && rule(cj, key);
+            const uint64_t m = ballot64(c);
+            if (c) {
+                const int p = cnt + popc64(m & lanes_below(lane));
+                if (p < kCandidates) {
+                    ck[p] = key;
+                    cs[p] = static_cast<uint32_t>(j) | (cj ? 0u : 0x80000000u);
+                }
+            }
+            cnt += popc64(m);
+        }
+    }
+    if (cnt < k || cnt > kCandidates) {
+        select_by_repeated_min_prio(col_idx, start, d, k, hv, out_base, a, prio);
+        return;
+    }
+    wave_lds_sync();
+    int out_pos = out_base;
+    for (int cbase = 0; cbase < cnt; cbase += kWave) {
+        const int ci = cbase + lane;
+        const bool valid = ci < cnt;
+        const uint64_t my_key = valid ? ck[ci] : kMaxKey;
+        const uint32_t my_cs = valid ? cs[ci] : 0xFFFFFFFFu;
+        const bool my_unc = (my_cs >> 31) != 0;
+        int rank = 0;
+        for (int t = 0; t < cnt; ++t) {                    // candidates are stored in ascending slot order
+            rank += prio_less((cs[t] >> 31) != 0, ck[t], t, my_unc, my_key, ci) ? 1 : 0;
+        }
+        const bool sel = valid && rank < k;
+        const uint64_t m = ballot64(sel);
+        if (sel) emit_neighbour(col_idx, start, static_cast<int>(my_cs & 0x7FFFFFFFu), out_pos + popc64(m & lanes_below(lane)), a);
+        out_pos += popc64(m);
+    }
+}
+
+// prio_count[v] = number of cached neighbours of node v.  A lane owns a node; rows of up to 32 slots
+// are walked by their lane, longer rows by the whole wavefront, one after the other.
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_prio_counts(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n,
+              const uint32_t *__restrict__ prio, int32_t *__restrict__ prio_count) {
+    const int lane = lane_id();
+    const int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int64_t start = 0;
+    int d = 0;
+    if (v < n) {
+        start = static_cast<int64_t>(row_ptr[v]);
+        d = static_cast<int>(static_cast<int64_t>(row_ptr[v + 1]) - start);
+    }
+    int c = 0;
+    if (d <= 32)
+        for (int j = 0; j < d; ++j) c += is_cached(col_idx + start, j, prio) ? 1 : 0;
+    uint64_t big = ballot64(d > 32);
+    while (big) {
+        const int l = __ffsll(static_cast<long long>(big)) - 1;
+        big &= big - 1;
+        const int dl = static_cast<int>(readlane32(static_cast<uint32_t>(d), l));
+        const int64_t sl = static_cast<int64_t>(readlane64(static_cast<uint64_t>(start), l));
+        int m = 0;
+        for (int base = 0; base < dl; base += kWave) {
+            const int j = base + lane;
+            m += popc64(ballot64(j < dl && is_cached(col_idx + sl, j, prio)));
+        }
+        if (lane == l) c = m;
+    }
+    if (v < n) prio_count[v] = c;
+}
+
+// bit v of the bitmap = node v is cached (slot_of[v] >= 0); one lane per node
+__global__ void __launch_bounds__(kBlock)
+k_prio_bitmap(const int32_t *__restrict__ slot_of, int64_t n, uint32_t *__restrict__ prio) {
+    const int64_t v = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t m = ballot64(v < n && slot_of[v] >= 0);
+    if (lane_id() == 0) {                                  // v is a multiple of 64 here; padding words get zeros
+        prio[v >> 5] = static_cast<uint32_t>(m);
+        prio[(v >> 5) + 1] = static_cast<uint32_t>(m >> 32);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
 // Bitmap -> ascending list of new source nodes.
 
 // Two tile shapes.  Dense bitmaps (up to 32 M nodes): one word per thread, 256 words per
@@ -581,8 +908,14 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         a.heavy_degree = heavy_degree;
         const int hub_blocks = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, need_dst), 2048));
         int sample_grid = hub_blocks + static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kWavesPerBlock)));
-        MQG_LAUNCH(ctx, "k_sample", s,
-                   (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
+        if (ctx->prio_enabled) {
+            MQG_LAUNCH(ctx, "k_sample_prio", s,
+                       (k_sample_prio<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->prio_bitmap, ctx->prio_count,
+                                                                           ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
+        } else {
+            MQG_LAUNCH(ctx, "k_sample", s,
+                       (k_sample<IdxT><<<sample_grid, kBlock, 0, s>>>(col_idx, src_ids, a, ctx->heavy_rows, ctx->heavy_count + l, hub_blocks)));
+        }
 
         if (use_hash) {
             rc = hash_dedup_block(ctx, nbr, need_nnz, g->num_nodes, g->idx_type, b.src_ids, b.sizes,
@@ -637,6 +970,41 @@ int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32
     if (p64 && !i64) return sample_blocks_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
     if (!p64 && i64) return sample_blocks_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
     return sample_blocks_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+}
+
+// cache == nullptr switches the priority off; otherwise the membership bitmap is (re)built from cache->slot_of
+int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s) {
+    if (!cache) {
+        ctx->prio_enabled = false;
+        return MQG_OK;
+    }
+    if (!ctx->prio_bitmap) {
+        bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->prio_bitmap), static_cast<size_t>(ctx->bitmap_words) * sizeof(uint32_t)) == hipSuccess &&
+                  hipMalloc(reinterpret_cast<void **>(&ctx->prio_count), static_cast<size_t>(std::max<int64_t>(ctx->num_nodes, 1)) * sizeof(int32_t)) == hipSuccess;
+        if (!ok) {
+            (void)hipFree(ctx->prio_bitmap);
+            (void)hipFree(ctx->prio_count);
+            ctx->prio_bitmap = nullptr;
+            ctx->prio_count = nullptr;
+            return fail(ctx, MQG_ERR_HIP, "mqg_ctx_set_sampling_priority: allocation failed");
+        }
+    }
+    const int grid = static_cast<int>(ctx->bitmap_words * 32 / kBlock);
+    MQG_LAUNCH(ctx, "k_prio_bitmap", s, (k_prio_bitmap<<<grid, kBlock, 0, s>>>(cache->slot_of, ctx->num_nodes, ctx->prio_bitmap)));
+    const int64_t n = ctx->num_nodes;
+    const int ngrid = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kBlock)));
+#define MQG_PRIOC(PT, IT)                                                                                        \
+    MQG_LAUNCH(ctx, "k_prio_counts", s,                                                                          \
+               (k_prio_counts<PT, IT><<<ngrid, kBlock, 0, s>>>(static_cast<const PT *>(g->row_ptr),               \
+                                                              static_cast<const IT *>(g->col_idx), n, ctx->prio_bitmap, \
+                                                              ctx->prio_count)))
+    if (g->ptr_type == MQG_I64 && g->idx_type == MQG_I64) MQG_PRIOC(int64_t, int64_t);
+    else if (g->ptr_type == MQG_I64) MQG_PRIOC(int64_t, int32_t);
+    else if (g->idx_type == MQG_I64) MQG_PRIOC(int32_t, int64_t);
+    else MQG_PRIOC(int32_t, int32_t);
+#undef MQG_PRIOC
+    ctx->prio_enabled = true;
+    return MQG_OK;
 }
 
 }  // namespace mqg

@@ -30,7 +30,7 @@ EXPORTS = [
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
-    "mqg_weighted_aggregate_backward",
+    "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -99,6 +99,8 @@ lib.mqg_weighted_aggregate.restype = ctypes.c_int
 lib.mqg_weighted_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _vp, _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_weighted_aggregate_backward.restype = ctypes.c_int
 lib.mqg_weighted_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _vp, _vp, _i64, _vp, _i64, _i32, _i32, _vp]
+lib.mqg_ctx_set_sampling_priority.restype = ctypes.c_int
+lib.mqg_ctx_set_sampling_priority.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), _vp]
 lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
                                ctypes.POINTER(_i64)]
 
@@ -170,6 +172,12 @@ class Context:
 
     def set_option(self, option: int, value: int):
         self.check(lib.mqg_ctx_set_option(self.h, option, value))
+
+    def set_sampling_priority(self, cache, stream=None):
+        """Draw cached neighbours first (cache: a Cache, or None for the uniform draw)."""
+        self.check(lib.mqg_ctx_set_sampling_priority(self.h, ctypes.byref(self.graph.c),
+                                                     ctypes.byref(cache.c) if cache is not None else None,
+                                                     _stream(stream)))
 
     def kernel_time(self, name: str):
         ms, n = ctypes.c_double(0), _i64(0)
