@@ -81,6 +81,10 @@ def _load():
     lib.orc_random_walk_scores.argtypes = [i64, vp, vp, vp, i64, vp, i64, vp]
     lib.orc_build_cache_by_score.restype = ctypes.c_int
     lib.orc_build_cache_by_score.argtypes = [i64, vp, i64, vp, vp]
+    lib.orc_ladies_probabilities.restype = None
+    lib.orc_ladies_probabilities.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.orc_ladies_block.restype = i64
+    lib.orc_ladies_block.argtypes = [vp, vp, i64, vp, i64, i64, i64, u64, ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]
     lib.orc_exp_ticket.restype = u64
     lib.orc_exp_ticket.argtypes = [u64]
     lib.orc_build_cache_drawn_by_score.restype = ctypes.c_int
@@ -268,6 +272,62 @@ def sample_blocks(row_ptr, col_idx, seeds, fanouts: Sequence[int], rng_seed: int
         blocks[l] = Block(nd, src[:ns].copy(), indptr, idx[:nnz].copy(), nbr[:nnz].copy())
         dst = blocks[l].src_ids
     return blocks  # type: ignore[return-value]
+
+
+@dataclass
+class WeightedBlock:
+    num_dst: int
+    src_ids: np.ndarray     # int64[num_src], ascending: the next layer's rows
+    indptr: np.ndarray      # int64[num_dst+1]
+    indices: np.ndarray     # int32[nnz], positions in src_ids
+    edge_w: np.ndarray      # float64[nnz]
+    mass: Optional[np.ndarray] = None
+
+    @property
+    def num_src(self) -> int:
+        return int(self.src_ids.shape[0])
+
+    @property
+    def nnz(self) -> int:
+        return int(self.indices.shape[0])
+
+
+def ladies_probabilities(row_ptr, col_idx, dst) -> np.ndarray:
+    rp, ci, d = _i64(row_ptr), _i64(col_idx), _i64(dst)
+    n = rp.shape[0] - 1
+    p = np.zeros(max(n, 1), dtype=np.float64)
+    _load().orc_ladies_probabilities(_p(rp), _p(ci), n, _p(d), d.shape[0], _p(p))
+    return p[:n]
+
+
+def ladies_blocks(row_ptr, col_idx, seeds, layer_sizes: Sequence[int], rng_seed: int, normalise: bool = True,
+                  want_mass: bool = False) -> List[WeightedBlock]:
+    """LADIES mini-batch: blocks[L-1] has the seeds as rows; layer_sizes[l] nodes are drawn as the
+    sources of blocks[l], which are the rows of blocks[l-1]."""
+    rp, ci, dst = _i64(row_ptr), _i64(col_idx), _i64(seeds)
+    n = rp.shape[0] - 1
+    L = len(layer_sizes)
+    out: List[Optional[WeightedBlock]] = [None] * L
+    lib = _load()
+    for l in range(L - 1, -1, -1):
+        s = int(layer_sizes[l])
+        nd = dst.shape[0]
+        cap_src = max(1, min(n, s))
+        cap_nnz = max(1, nd * cap_src)
+        src = np.empty(cap_src, dtype=np.int64)
+        indptr = np.empty(nd + 1, dtype=np.int64)
+        idx = np.empty(cap_nnz, dtype=np.int32)
+        ew = np.empty(cap_nnz, dtype=np.float64)
+        mass = np.zeros(max(n, 1), dtype=np.uint64) if want_mass else None
+        ns = lib.orc_ladies_block(_p(rp), _p(ci), n, _p(dst), nd, s, l, ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF),
+                                  1 if normalise else 0, cap_src, cap_nnz, _p(src), _p(indptr), _p(idx), _p(ew),
+                                  None if mass is None else _p(mass))
+        if ns < 0:
+            raise RuntimeError(f"orc_ladies_block failed ({ns})")
+        nnz = int(indptr[nd])
+        out[l] = WeightedBlock(nd, src[:ns].copy(), indptr, idx[:nnz].copy(), ew[:nnz].copy(), mass)
+        dst = out[l].src_ids
+    return out  # type: ignore[return-value]
 
 
 # ---------------------------------------------------------------- gather

@@ -42,6 +42,13 @@
  *                            that fewer distinct uncached nodes enter a
  *                            mini-batch.  Read as: a row's cached neighbours
  *                            are drawn before its uncached ones.
+ *   - orc_ladies_probabilities / orc_ladies_block : Sec. III-B "Layer-wise
+ *                            sampling", LADIES paragraph (Eq. 6-9): the nodes
+ *                            of the next layer are drawn from the neighbours
+ *                            of the current layer's nodes with probability
+ *                            proportional to the squared column norm of the
+ *                            row-selected normalised adjacency; a sampled
+ *                            node's column is scaled by 1 / (s p).
  *   - orc_gather           : Sec. IV "Mini-Batch Transfer To GPU": features
  *                            of nodes absent from the GPU cache come from
  *                            host memory, the rest from the cache; the
@@ -786,4 +793,132 @@ int orc_build_cache_drawn_by_score(int64_t num_nodes, const double *scores, int6
     }
     free(all);
     return 0;
+}
+
+/* ------------------------------------------------- layer-wise sampling (LADIES) */
+
+/*
+ * Eq. 7 in double precision: p_i = ||R P_{*,i}||_2^2 / ||R P||_F^2 for the rows
+ * R = dst[0..num_dst) of P = D^-1/2 (A + I) D^-1/2 (Eq. 2), i.e.
+ *   q_i = sum over v in dst with i in N(v) or i == v of 1 / ((deg_v+1)(deg_i+1)),
+ *   p_i = q_i / sum_j q_j.
+ * p has num_nodes entries; nodes outside the union of Eq. 6 get 0.
+ */
+void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
+                              const int64_t *dst, int64_t num_dst, double *p)
+{
+    for (int64_t i = 0; i < num_nodes; ++i) p[i] = 0.0;
+    for (int64_t t = 0; t < num_dst; ++t) {
+        int64_t v = dst[t];
+        double dv = (double)(row_ptr[v + 1] - row_ptr[v]) + 1.0;
+        p[v] += 1.0 / (dv * dv);
+        for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
+            int64_t i = col_idx[e];
+            double di = (double)(row_ptr[i + 1] - row_ptr[i]) + 1.0;
+            p[i] += 1.0 / (dv * di);
+        }
+    }
+    double total = 0.0;
+    for (int64_t i = 0; i < num_nodes; ++i) total += p[i];
+    if (total > 0.0)
+        for (int64_t i = 0; i < num_nodes; ++i) p[i] /= total;
+}
+
+/* Domain tag of the layer-wise draw at block `layer` (the node-wise draw uses `layer` itself). */
+#define ORC_LAYERWISE_TAG 64
+
+/*
+ * One LADIES block (Eq. 6-9).  Rows: dst[0..num_dst) (distinct nodes).
+ *
+ * Probabilities.  So that a CPU and a GPU agree on every decision, the column
+ * masses are accumulated in integers: mass_i = sum over v in dst with i in
+ * N(v) or i == v of floor(2^40 / (deg_v + 1)), and q_i = mass_i / (deg_i + 1)
+ * stands for the q_i of orc_ladies_probabilities times 2^40 (relative error
+ * below 2^-40 * (deg_v + 1) per term).  Candidates (Eq. 6, with the self loops
+ * of A + I): the nodes with mass_i > 0.
+ *
+ * Draw: s_layer candidates without replacement with probability proportional
+ * to q_i (all of them if there are at most s_layer), by an exponential race:
+ * key_i = ticket_i * (deg_i + 1) / mass_i in doubles (one multiplication, one
+ * division, each rounded once; mass converted to double first), ticket_i =
+ * orc_exp_ticket(orc_key(seed, 64 + layer, i, 0)); the smallest (key, id) win.
+ *
+ * Block: sources = the drawn nodes in ascending id order (the next layer's
+ * rows); row t lists the drawn nodes among v's neighbours and v itself: the
+ * self edge first, then the adjacency row in slot order.  Weight of edge
+ * (v, i) (Eq. 8): P_vi / (s * p_i) with s the number of drawn nodes and p_i =
+ * q_i / sum_j q_j (sum over the candidates in ascending id order); with
+ * `normalise` every row is then divided by its sum (the paper's normalisation
+ * of the sampled Laplacian; rows without an edge stay empty).
+ *
+ * mass_out (may be NULL): num_nodes masses.  Returns the number of sources,
+ * -2 when cap_nnz or cap_src is too small or memory runs out.
+ */
+int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
+                         const int64_t *dst, int64_t num_dst, int64_t s_layer, int64_t layer,
+                         uint64_t rng_seed, int normalise, int64_t cap_src, int64_t cap_nnz,
+                         int64_t *src, int64_t *indptr, int32_t *indices, double *edge_w,
+                         uint64_t *mass_out)
+{
+    size_t cnt = (size_t)(num_nodes > 0 ? num_nodes : 1);
+    uint64_t *mass = calloc(cnt, sizeof *mass);
+    int64_t *pos = malloc(cnt * sizeof *pos);
+    orc_dkey_id *cand = malloc(cnt * sizeof *cand);
+    if (!mass || !pos || !cand) { free(mass); free(pos); free(cand); return -2; }
+
+    for (int64_t t = 0; t < num_dst; ++t) {
+        int64_t v = dst[t];
+        uint64_t add = ((uint64_t)1 << 40) / (uint64_t)(row_ptr[v + 1] - row_ptr[v] + 1);
+        mass[v] += add;
+        for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) mass[col_idx[e]] += add;
+    }
+    if (mass_out) memcpy(mass_out, mass, (size_t)num_nodes * sizeof *mass);
+
+    int64_t num_cand = 0;
+    double q_total = 0.0;
+    for (int64_t i = 0; i < num_nodes; ++i) {
+        if (!mass[i]) continue;
+        double deg1 = (double)(row_ptr[i + 1] - row_ptr[i] + 1);
+        double ticket = (double)orc_exp_ticket(orc_key(rng_seed, ORC_LAYERWISE_TAG + layer, i, 0));
+        cand[num_cand].key = (ticket * deg1) / (double)mass[i];
+        cand[num_cand].id = i;
+        ++num_cand;
+        q_total += (double)mass[i] / deg1;
+    }
+    int64_t num_src = num_cand < s_layer ? num_cand : s_layer;
+    if (num_src > cap_src) { free(mass); free(pos); free(cand); return -2; }
+    if (num_cand > s_layer) qsort(cand, (size_t)num_cand, sizeof *cand, cmp_dkey_id);
+    for (int64_t r = 0; r < num_src; ++r) src[r] = cand[r].id;
+    qsort(src, (size_t)num_src, sizeof *src, cmp_i64);
+    for (int64_t i = 0; i < num_nodes; ++i) pos[i] = -1;
+    for (int64_t r = 0; r < num_src; ++r) pos[src[r]] = r;
+
+    int64_t nnz = 0;
+    indptr[0] = 0;
+    for (int64_t t = 0; t < num_dst; ++t) {
+        int64_t v = dst[t];
+        double dv = (double)(row_ptr[v + 1] - row_ptr[v] + 1);
+        int64_t row_begin = nnz;
+        for (int64_t e = row_ptr[v] - 1; e < row_ptr[v + 1]; ++e) {      /* e == row_ptr[v] - 1: the self edge */
+            int64_t i = e < row_ptr[v] ? v : col_idx[e];
+            if (pos[i] < 0) continue;
+            if (nnz >= cap_nnz) { free(mass); free(pos); free(cand); return -2; }
+            double di = (double)(row_ptr[i + 1] - row_ptr[i] + 1);
+            double P_vi = 1.0 / sqrt(dv * di);
+            double p_i = ((double)mass[i] / di) / q_total;
+            indices[nnz] = (int32_t)pos[i];
+            edge_w[nnz] = P_vi / ((double)num_src * p_i);
+            ++nnz;
+        }
+        if (normalise) {
+            double row_sum = 0.0;
+            for (int64_t e = row_begin; e < nnz; ++e) row_sum += edge_w[e];
+            for (int64_t e = row_begin; e < nnz; ++e) edge_w[e] /= row_sum;
+        }
+        indptr[t + 1] = nnz;
+    }
+    free(mass);
+    free(pos);
+    free(cand);
+    return num_src;
 }

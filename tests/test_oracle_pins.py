@@ -803,3 +803,104 @@ def test_prioritised_blocks_structure_and_fewer_uncached_sources():
             assert np.isin(b.nbr_global[b.indptr[i]:b.indptr[i + 1]], ci[rp[v]:rp[v + 1]]).all()
     unc = lambda blocks: int((cache.slot_of[blocks[0].src_ids] < 0).sum())
     assert unc(prio) < 0.7 * unc(plain)
+
+
+# ------------------------------------------------------------------------- layer-wise sampling (LADIES)
+
+def test_ladies_probabilities_equal_dense_column_norms():
+    """Eq. 7 written with dense matrices: p_i = ||R P[:, i]||^2 / ||R P||_F^2."""
+    rp, ci = tiny_graph(120, 1400, seed=51)
+    P = dense_gcn_operator(rp, ci)
+    rows = np.array([7, 0, 119, 33, 64, 90], dtype=np.int64)
+    RP = P[rows]
+    want = (RP ** 2).sum(axis=0) / (RP ** 2).sum()
+    got = oracle.ladies_probabilities(rp, ci, rows)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-18) and abs(got.sum() - 1) < 1e-12
+    # the integer masses of the block routine describe the same distribution
+    b = oracle.ladies_blocks(rp, ci, rows, [10 ** 6], 1, want_mass=True)[0]
+    deg1 = np.diff(rp) + 1
+    m_py = np.zeros(120, dtype=object)
+    for v in rows:
+        add = (1 << 40) // int(deg1[v])
+        m_py[v] += add
+        for i in ci[rp[v]:rp[v + 1]]:
+            m_py[i] += add
+    assert [int(x) for x in b.mass] == [int(x) for x in m_py]
+    q = b.mass.astype(np.float64) / deg1
+    assert np.allclose(q / q.sum(), want, rtol=1e-9, atol=1e-18)
+    # Eq. 6: the candidates are the rows' neighbours (and the rows themselves, from A + I)
+    cand = set(rows.tolist())
+    for v in rows:
+        cand |= set(ci[rp[v]:rp[v + 1]].tolist())
+    assert set(np.nonzero(b.mass)[0].tolist()) == cand and set(b.src_ids.tolist()) == cand
+
+
+def test_ladies_block_with_every_candidate_reproduces_the_operator():
+    """Layer size above the number of candidates: nothing is dropped; Eq. 8's scaling undone gives
+    back P (weight * s * p_i == P_vi), and the normalised rows are P's rows divided by their sums."""
+    rp, ci = tiny_graph(120, 1400, seed=52)
+    P = dense_gcn_operator(rp, ci)
+    rows = np.array([5, 17, 3, 80], dtype=np.int64)
+    p = oracle.ladies_probabilities(rp, ci, rows)
+    raw = oracle.ladies_blocks(rp, ci, rows, [10 ** 6], 4, normalise=False)[0]
+    nrm = oracle.ladies_blocks(rp, ci, rows, [10 ** 6], 4, normalise=True)[0]
+    s = raw.num_src
+    assert np.all(np.diff(raw.src_ids) > 0)
+    for t, v in enumerate(rows):
+        e = slice(raw.indptr[t], raw.indptr[t + 1])
+        ids = raw.src_ids[raw.indices[e]]
+        assert ids[0] == v and ids[1:].tolist() == ci[rp[v]:rp[v + 1]].tolist()      # self edge, then slot order
+        assert np.allclose(raw.edge_w[e] * s * p[ids], P[v, ids], rtol=1e-9)
+        assert np.allclose(nrm.edge_w[e], P[v, ids] / p[ids] / (P[v, ids] / p[ids]).sum(), rtol=1e-9)
+        assert abs(nrm.edge_w[e].sum() - 1.0) < 1e-12
+
+
+def test_ladies_draw_restated_in_python_and_block_structure():
+    rp, ci = tiny_graph(400, 6000, seed=53)
+    n = len(rp) - 1
+    deg1 = (np.diff(rp) + 1).astype(np.float64)
+    seeds = np.random.default_rng(5).choice(n, 24, replace=False)
+    sizes = [16, 40]
+    blocks = oracle.ladies_blocks(rp, ci, seeds, sizes, 77, want_mass=True)
+    dst = seeds
+    for l in (1, 0):
+        b = blocks[l]
+        mass = b.mass
+        cand = np.nonzero(mass)[0]
+        assert len(cand) > sizes[l]
+        t = np.array([oracle.exp_ticket(oracle.key(77, 64 + l, int(i), 0)) for i in cand], dtype=np.float64)
+        key = (t * deg1[cand]) / mass[cand].astype(np.float64)
+        order = np.lexsort((cand, key))
+        assert np.array_equal(b.src_ids, np.sort(cand[order[:sizes[l]]]))
+        assert b.num_dst == len(dst) and b.num_src == sizes[l]
+        chosen = set(b.src_ids.tolist())
+        for r, v in enumerate(dst):
+            want = [v] * (int(v) in chosen) + [int(i) for i in ci[rp[v]:rp[v + 1]] if int(i) in chosen]
+            got = b.src_ids[b.indices[b.indptr[r]:b.indptr[r + 1]]].tolist()
+            assert got == want
+            w = b.edge_w[b.indptr[r]:b.indptr[r + 1]]
+            assert len(w) == 0 or abs(w.sum() - 1.0) < 1e-12
+        dst = b.src_ids
+
+
+def test_ladies_first_pick_follows_the_probabilities():
+    rp, ci = tiny_graph(30, 120, seed=54)
+    rows = np.array([2, 11, 20], dtype=np.int64)
+    p = oracle.ladies_probabilities(rp, ci, rows)
+    trials = 20000
+    cnt = np.zeros(30)
+    for seed in range(trials):
+        cnt[oracle.ladies_blocks(rp, ci, rows, [1], seed)[0].src_ids[0]] += 1
+    assert np.all(cnt[p == 0] == 0)
+    assert np.all(np.abs(cnt / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials) + 1e-9)
+
+
+def test_ladies_degenerate_cases():
+    rp = np.array([0, 0, 2, 3, 3, 6], dtype=np.int64)            # nodes 0 and 3 have no neighbours
+    ci = np.array([2, 4, 1, 0, 1, 2], dtype=np.int64)
+    b = oracle.ladies_blocks(rp, ci, np.array([0], dtype=np.int64), [4], 1)[0]
+    assert b.src_ids.tolist() == [0] and b.indices.tolist() == [0] and b.edge_w.tolist() == [1.0]
+    b = oracle.ladies_blocks(rp, ci, np.zeros(0, dtype=np.int64), [4], 1)[0]
+    assert b.num_src == 0 and b.nnz == 0 and b.indptr.tolist() == [0]
+    b = oracle.ladies_blocks(rp, ci, np.array([1, 3], dtype=np.int64), [1], 3, normalise=False)[0]
+    assert b.num_src == 1 and b.indptr[-1] == b.nnz
