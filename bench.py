@@ -330,6 +330,46 @@ def main() -> int:
     # reduction kernel: every edge reads one gradient row, every source row of every block is written once
     bwd_bytes = (edges + int(sizes_host[:, :, 1].sum())) / K * row_bytes
 
+    # ---------------------------------------------------------------- layer-wise (LADIES) mini-batches
+    # Not part of a step either: the paper's layer-wise setting (512 nodes per layer) on the same
+    # seeds - sampling, gather of the outermost layer's rows, weighted sums - one batch at a time.
+    lw_sizes = [512] * L
+    lw_blocks = mqg.LayerwiseBlocks(g, w.batch, lw_sizes, nnz_per_row=512)
+    lw_x0 = torch.zeros((lw_blocks.bounds[0][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim]
+    lw_h = [torch.zeros((lw_blocks.bounds[l][0], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)]
+    lw_stats = torch.zeros(2, dtype=torch.int64, device=dev)
+    c0 = ctxs[0]
+
+    def lw_step(i):
+        mqg.mqg_sample_layerwise(c0, g, seeds_dev[i], lw_sizes, base_seed + i, lw_blocks)
+        mqg.mqg_gather_features(c0, cache, lw_blocks.src_ids[0], lw_blocks.sizes[0, 1:2], lw_x0, lw_stats)
+        x = lw_x0
+        for l in range(L):
+            mqg.mqg_weighted_aggregate(c0, lw_blocks, l, lw_blocks.edge_w[l], None, x, lw_h[l])
+            x = lw_h[l]
+
+    lw_step(W)                                                  # allocates the sampler's scratch
+    torch.cuda.synchronize()
+    KL = min(K, 30)
+    t0 = time.perf_counter()
+    for i in range(W, W + KL):
+        lw_step(i)
+    torch.cuda.synchronize()
+    lw_ms = (time.perf_counter() - t0) / KL * 1e3
+    lw_edges = int(lw_blocks.sizes[:, 2].sum())
+    c0.reset_profile()
+    c0.set_option(mqg.MQG_OPT_PROFILE, 1)
+    for i in range(W, W + KL):
+        lw_step(i)
+        torch.cuda.synchronize()
+    lw_kern = {}
+    for name in c0.kernel_names():
+        ms, cnt = c0.kernel_time(name)
+        if cnt:
+            lw_kern[name] = round(ms / KL * 1e3, 1)
+    c0.set_option(mqg.MQG_OPT_PROFILE, 0)
+    lw_sample_us = sum(v for k, v in lw_kern.items() if k.startswith("k_lw_") or k.startswith("k_radix") or k.startswith("k_scan"))
+
     # ---------------------------------------------------------------- CPU baseline: the oracle, one thread
     cpu = None
     if not args.no_cpu_baseline:
@@ -413,6 +453,11 @@ def main() -> int:
                                      "mean_aggregate_us_per_step": round(agg_us, 1),
                                      "note": "Eq. 1-3 estimator on the same blocks (weights of every block, then weighted "
                                              "sums with the diagonal term); not part of a step"},
+        "layerwise_sampling": {"layer_sizes": lw_sizes, "ms_per_batch": round(lw_ms, 3),
+                               "sampling_kernels_us_per_batch": round(lw_sample_us, 1),
+                               "edges_last_batch": lw_edges, "kernel_us_per_batch": lw_kern,
+                               "note": "LADIES (Eq. 6-9) on the same seeds: sample, gather, weighted sums, one "
+                                       "mini-batch at a time on one stream; not part of a step"},
         "sampling": sampling,
         "paper_queue_rule": {"queue_size": q_rule, "memory_cap": q_cap, "bytes_per_queued_batch": per_batch_bytes,
                              "note": "Eq. 22-23 on mean prepare (sample+gather) / consume (aggregate) times of this run; "

@@ -265,6 +265,59 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
                       mqg_block *blocks, mqg_stream stream);
 
 /*
+ * Layer-wise sampling after LADIES (paper Sec. III-B, Eq. 6-9) into blocks of
+ * the same layout, with edge weights.  blocks[L-1] has the seeds as rows; for
+ * every block, from L-1 down to 0, with rows D:
+ *   - column masses in integers: mass_i = sum over v in D with i in N(v) or
+ *     i == v of floor(2^40 / (deg_v + 1)); q_i = mass_i / (deg_i + 1) is 2^40
+ *     times the squared column norm ||R P_{*,i}||^2 of Eq. 7, P = D^-1/2 (A + I)
+ *     D^-1/2 (Eq. 2); the candidates (Eq. 6) are the nodes with mass_i > 0;
+ *   - layer_sizes[l] candidates are drawn without replacement with probability
+ *     proportional to q_i (all of them if there are no more), by an
+ *     exponential race: key_i = ticket_i * (deg_i + 1) / mass_i in doubles,
+ *     ticket_i as for MQG_CACHE_RANDOM_WALK_SAMPLED from r_i =
+ *     mix(mix(mix(mix(rng_seed + G) ^ (64 + l)) ^ i)); the smallest (key, id) win;
+ *   - src_ids = the drawn nodes, ascending (they are the rows of block l-1;
+ *     unlike mqg_sample_blocks the rows are not repeated among the sources);
+ *     row v lists the drawn nodes among v itself and its adjacency row, the
+ *     self edge first, then in slot order; edge_w[l][p] = P_vi / (s p_i) (Eq. 8),
+ *     s the number of drawn nodes and p_i = q_i / sum_j q_j, divided by the
+ *     row's sum if normalise != 0 (the normalisation of the sampled operator
+ *     the paper mentions after Eq. 9; rows without an edge stay empty).
+ * Which nodes are drawn is a pure function of the arguments (integer masses,
+ * correctly rounded double operations); the weights are computed in double and
+ * rounded to float.
+ *   seeds_dev    device [num_seeds], graph idx_type, distinct; an id outside
+ *                the graph is replaced by node 0 and flagged (sizes[3] bit 0)
+ *   layer_sizes  host [num_layers], each >= 1
+ *   blocks       host [num_layers]; block l needs cap_dst >= its number of rows
+ *                (num_seeds for L-1, else min(N, layer_sizes[l+1])), cap_src >=
+ *                min(N, layer_sizes[l]); edges beyond cap_nnz are dropped and
+ *                flagged (sizes[3] bit 2; sizes[2] is then cap_nnz)
+ *   edge_w       host array of num_layers device pointers, [cap_nnz] floats each
+ * The first call allocates context scratch of about 53 bytes per graph node
+ * (and synchronises the stream once).  Feed the blocks to
+ * mqg_weighted_aggregate with self_w == NULL.
+ */
+int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                         const int32_t *layer_sizes, int32_t num_layers, uint64_t rng_seed,
+                         int32_t normalise, mqg_block *blocks, float *const *edge_w,
+                         mqg_stream stream);
+
+/*
+ * The selection step of mqg_sample_layerwise on its own (the k smallest race
+ * keys win the draw of Eq. 6-9): bit c of out_bitmap is set iff key c is among
+ * the k smallest (key, index) pairs of keys[0..n) - all of them if n <= k; keys
+ * that are exactly equal are taken in ascending index order.  A radix select,
+ * most significant byte first, one launch per byte.
+ *   keys_dev        device [n] unsigned 64-bit keys
+ *   out_bitmap_dev  device [ceil(n / 32)] words, written by the call
+ * Uses the layer-wise sampler's context scratch (allocated at the first use).
+ */
+int mqg_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys_dev, int64_t n, int64_t k,
+                             uint32_t *out_bitmap_dev, mqg_stream stream);
+
+/*
  * Cache-prioritised neighbour sampling (paper Sec. I on global neighbour
  * sampling: the sampler prefers neighbours that are in the cache, which cuts
  * the number of distinct uncached rows a mini-batch needs).  After this call

@@ -18,7 +18,7 @@ CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libmqg.so")
 
-SOURCES = ["api.hip", "sample.hip", "gather.hip", "aggregate.hip", "cache.hip", "radix.hip", "dedup_hash.hip"]
+SOURCES = ["api.hip", "sample.hip", "gather.hip", "aggregate.hip", "cache.hip", "radix.hip", "dedup_hash.hip", "layerwise.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

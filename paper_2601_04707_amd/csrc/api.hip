@@ -189,6 +189,7 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->counters);
     mqg::free_backward_scratch(c);
     mqg::free_hash_scratch(c);
+    mqg::free_layerwise_scratch(c);
     (void)hipFree(c->prio_bitmap);
     (void)hipFree(c->prio_count);
     for (auto &r : c->prof_recs) {
@@ -346,6 +347,42 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
     }
     return mqg::run_sample_blocks(ctx, g, seeds_dev, num_seeds, fanouts, L, rng_seed, blocks,
                                   static_cast<hipStream_t>(stream));
+}
+
+int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                         const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise,
+                         mqg_block *blocks, float *const *edge_w, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    int rc = check_graph(ctx, g, "mqg_sample_layerwise");
+    if (rc != MQG_OK) return rc;
+    if (!layer_sizes || !blocks || !edge_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: NULL layer_sizes, blocks or edge_w");
+    if (L < 1 || L > MQG_MAX_LAYERS) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: num_layers outside 1..MQG_MAX_LAYERS");
+    if (num_seeds < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: negative num_seeds");
+    if (num_seeds > 0 && !seeds_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: seeds_dev is NULL");
+    if (num_seeds > 0 && g->num_nodes == 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: seeds given for an empty graph");
+    int64_t rows = num_seeds;
+    for (int l = L - 1; l >= 0; --l) {
+        if (layer_sizes[l] < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: layer size below 1");
+        const mqg_block &b = blocks[l];
+        if (!b.src_ids || !b.indptr || !b.indices || !b.sizes || !edge_w[l])
+            return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: NULL block buffer");
+        const int64_t src = std::min<int64_t>(g->num_nodes, layer_sizes[l]);
+        if (b.cap_dst < rows || b.cap_src < src || b.cap_nnz < 0 || b.cap_nnz >= (int64_t(1) << 31))
+            return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_layerwise: block " + std::to_string(l) + " needs cap_dst>=" +
+                        std::to_string(rows) + " cap_src>=" + std::to_string(src) + " and 0 <= cap_nnz < 2^31");
+        rows = src;
+    }
+    return mqg::run_sample_layerwise(ctx, g, seeds_dev, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w,
+                                     static_cast<hipStream_t>(stream));
+}
+
+int mqg_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys_dev, int64_t n, int64_t k, uint32_t *out_bitmap_dev,
+                             mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (n < 0 || k < 0 || n >= (int64_t(1) << 31)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_select_smallest_keys: n or k out of range");
+    if (n > 0 && (!keys_dev || !out_bitmap_dev)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_select_smallest_keys: NULL keys or bitmap");
+    if (n == 0) return MQG_OK;
+    return mqg::run_select_smallest_keys(ctx, keys_dev, n, k, out_bitmap_dev, static_cast<hipStream_t>(stream));
 }
 
 int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,

@@ -32,6 +32,25 @@ struct ProfRec {
 
 }  // namespace mqg
 
+// scratch of the layer-wise sampler (layerwise.hip), sized by the graph
+struct LayerwiseScratch {
+    unsigned long long *mass = nullptr;  // [num_nodes] integer column masses, zero between calls
+    int32_t *cand = nullptr;             // [num_nodes] candidates, ascending
+    uint64_t *key64 = nullptr;           // [num_nodes] race keys (double bit patterns)
+    unsigned long long *sel_state = nullptr;   // [18] radix select: prefix and wanted count per pass
+    int32_t *sel_hist = nullptr;         // [8 * 256]
+    int32_t *chunk_offs = nullptr;       // [rows_cap * 16 + 1] edges per (row, chunk), then their scan
+    double *chunk_sum = nullptr;         // [rows_cap * 16] raw weight sums per (row, chunk)
+    int32_t *word_offs = nullptr;        // [bitmap_words + 1]
+    int32_t *scan_tiles = nullptr;
+    double *q_part = nullptr;            // per-workgroup partial sums of q
+    int64_t *counters = nullptr;         // [0]: number of candidates
+    double *q_total = nullptr;
+    int64_t *seeds_copy = nullptr;       // [rows_cap] the checked seeds
+    int32_t *flags = nullptr;
+    int64_t rows_cap = 0;
+};
+
 struct mqg_ctx {
     int device = 0;
     int64_t num_nodes = 0;
@@ -64,6 +83,7 @@ struct mqg_ctx {
     float *bwd_w_sorted = nullptr;       // [bwd_nnz_cap] edge weights in the by-source order (weighted backward)
     int32_t *bwd_col_ptr = nullptr;      // [bwd_src_cap + 2] offsets of every source in the sorted edge list
     int64_t bwd_nnz_cap = 0, bwd_src_cap = 0;
+    LayerwiseScratch lw;
     // cache-prioritised neighbour sampling (mqg_ctx_set_sampling_priority)
     bool prio_enabled = false;
     uint32_t *prio_bitmap = nullptr;     // [bitmap_words] bit v = node v is cached
@@ -130,6 +150,11 @@ int run_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *g, const mqg_block *b, f
 int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *x,
                            int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
+int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
+                         int32_t L, uint64_t rng_seed, int32_t normalise, mqg_block *blocks, float *const *edge_w,
+                         hipStream_t s);
+void free_layerwise_scratch(mqg_ctx *ctx);
+int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int64_t k, uint32_t *out_bitmap, hipStream_t s);
 int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s);
 // hash-table dedup (dedup_hash.hip)
 int ensure_hash_scratch(mqg_ctx *ctx);

@@ -1,0 +1,578 @@
+// Layer-wise sampling after LADIES (paper Sec. III-B, Eq. 6-9): the nodes of the next layer are
+// drawn from the neighbours of the current layer's nodes (and these nodes themselves: A + I) with
+// probability proportional to the squared column norm of the row-selected normalised adjacency
+// P = D^-1/2 (A + I) D^-1/2, and a drawn node's column is scaled by 1 / (s p) (Eq. 8).
+//
+// Per block, for the rows D (the seeds, then the previous block's drawn nodes):
+//   k_lw_mass        mass[i] += floor(2^40 / (deg_v + 1)) for every row v and every i in N(v) or
+//                    i == v: integer atomics, so the sums do not depend on the schedule.
+//                    q_i = mass[i] / (deg_i + 1) is 2^40 times the squared column norm of Eq. 7.
+//                    Touched nodes are marked in the context's node bitmap.
+//   bitmap -> list   the candidates (Eq. 6), ascending (word popcounts, scan, emit)
+//   k_lw_keys        exponential race: key = ticket * (deg_i + 1) / mass[i] in doubles, ticket from
+//                    exp_ticket64; partial sums of q per workgroup, added up in a fixed order
+//   k_lw_select      radix select of the s-th smallest 64-bit key pattern, most significant byte
+//                    first: one launch per byte, every workgroup derives the prefix found so far
+//                    from the previous launch's 256-bin histogram
+//   k_lw_mark        keys below the threshold are marked in the bitmap, keys equal to it in
+//                    ascending id order as far as needed (all candidates if there are at most s)
+//   bitmap -> list   the drawn nodes ascending = the block's sources, positions into local_of[]
+//   k_lw_count/fill  row v lists the drawn nodes among v and its adjacency row (self edge first,
+//                    then slot order) with weight P_vi / (s p_i), optionally divided by the row sum
+// A row is shared by kRowChunks wavefronts, each with a contiguous range of adjacency slots, so
+// that a hub does not become a kernel's tail; counts and partial weight sums are kept per (row,
+// chunk) and one scan over all of them gives every wavefront its first edge position.
+//   k_lw_reset       masses and positions back to their idle values
+#include <algorithm>
+
+#include "common.h"
+#include "device_utils.h"
+#include "radix.h"
+
+namespace mqg {
+
+namespace {
+
+constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
+constexpr int kLayerwiseTag = 64;
+
+uint64_t host_mix64(uint64_t z) {
+    z ^= z >> 30;
+    z *= 0xBF58476D1CE4E5B9ULL;
+    z ^= z >> 27;
+    z *= 0x94D049BB133111EBULL;
+    z ^= z >> 31;
+    return z;
+}
+
+__device__ __forceinline__ void set_bit(uint32_t *bitmap, uint32_t i) {
+    uint32_t *w = bitmap + (i >> 5);
+    const uint32_t bit = 1u << (i & 31);
+    if (!(__hip_atomic_load(w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) & bit))
+        (void)__hip_atomic_fetch_or(w, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// the caller's seeds, checked: an id outside the graph is replaced by node 0 and flagged
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_seeds(const IdxT *__restrict__ seeds, int64_t n, int64_t num_nodes, IdxT *__restrict__ dst, int64_t *sizes,
+           int32_t *__restrict__ flags) {
+    const int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (t == 0) sizes[0] = n;
+    if (t >= n) return;
+    IdxT v = seeds[t];
+    if (v < 0 || static_cast<int64_t>(v) >= num_nodes) {
+        v = 0;
+        atomicOr(flags, 1);
+    }
+    dst[t] = v;
+}
+
+constexpr int kRowChunks = 16;      // wavefronts that share one row
+
+// the contiguous range of adjacency slots of chunk c of a row of d slots (multiples of 64)
+__device__ __forceinline__ void chunk_range(int64_t d, int c, int64_t *begin, int64_t *end) {
+    const int64_t len = ((d + kRowChunks - 1) / kRowChunks + kWave - 1) / kWave * kWave;
+    *begin = len * c < d ? len * c : d;
+    *end = len * (c + 1) < d ? len * (c + 1) : d;
+}
+
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_mass(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
+          const int64_t *__restrict__ sizes, unsigned long long *__restrict__ mass, uint32_t *__restrict__ bitmap) {
+    const int lane = lane_id();
+    const int64_t n = sizes[0] * kRowChunks;
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t u = wave0; u < n; u += nwaves) {
+        const int64_t t = u / kRowChunks;
+        const int c = static_cast<int>(u % kRowChunks);
+        const int64_t v = static_cast<int64_t>(dst[t]);
+        const int64_t start = static_cast<int64_t>(row_ptr[v]);
+        const int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - start;
+        const unsigned long long add = (1ull << 40) / static_cast<unsigned long long>(d + 1);
+        if (c == 0 && lane == 0) {
+            atomicAdd(&mass[v], add);
+            set_bit(bitmap, static_cast<uint32_t>(v));
+        }
+        int64_t jb, je;
+        chunk_range(d, c, &jb, &je);
+        for (int64_t j = jb + lane; j < je; j += kWave) {
+            const uint32_t i = static_cast<uint32_t>(col_idx[start + j]);
+            atomicAdd(&mass[i], add);
+            set_bit(bitmap, i);
+        }
+    }
+}
+
+// offs[w] = popcount of word w; offs[words] = 0 (the scan turns it into the total)
+__global__ void __launch_bounds__(kBlock)
+k_lw_word_counts(const uint32_t *__restrict__ bitmap, int64_t words, int32_t *__restrict__ offs) {
+    const int64_t w = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (w < words) offs[w] = __popc(bitmap[w]);
+    if (w == words) offs[w] = 0;
+}
+
+// ids of the set bits, ascending, into out[0..total); the words are cleared; total to count_a/b
+template <typename OutT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_emit(uint32_t *__restrict__ bitmap, int64_t words, const int32_t *__restrict__ offs, OutT *__restrict__ out,
+          int32_t *__restrict__ local_of, int64_t *count_a, int64_t *count_b) {
+    const int64_t w = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (w == 0) {
+        const int64_t total = offs[words];
+        if (count_a) *count_a = total;
+        if (count_b) *count_b = total;
+    }
+    if (w >= words) return;
+    uint32_t bits = bitmap[w];
+    if (!bits) return;
+    bitmap[w] = 0;
+    int32_t o = offs[w];
+    const int64_t v0 = w * 32;
+    while (bits) {
+        const int b = __ffs(bits) - 1;
+        bits &= bits - 1;
+        out[o] = static_cast<OutT>(v0 + b);
+        if (local_of) local_of[v0 + b] = o;
+        ++o;
+    }
+}
+
+// race keys of the candidates and the per-workgroup partial sums of q (zero past the last candidate)
+template <typename PtrT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
+          const unsigned long long *__restrict__ mass, uint64_t tag_hash, uint64_t *__restrict__ key64,
+          double *__restrict__ q_part) {
+    __shared__ double lds[kWavesPerBlock];
+    const int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    double q = 0.0;
+    if (c < *n_cand) {
+        const int64_t i = cand[c];
+        const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
+        const double m = static_cast<double>(mass[i]);
+        const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
+        const double key = (ticket * deg1) / m;
+        key64[c] = static_cast<uint64_t>(__double_as_longlong(key));
+        q = m / deg1;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = q;
+    __syncthreads();
+    if (threadIdx.x == 0) q_part[blockIdx.x] = ((lds[0] + lds[1]) + lds[2]) + lds[3];
+}
+
+// q_total = sum of the partial sums that cover candidates, in a fixed order
+__global__ void __launch_bounds__(kBlock)
+k_lw_qsum(const double *__restrict__ q_part, const int64_t *__restrict__ n_cand, double *__restrict__ q_total) {
+    __shared__ double lds[kBlock];
+    const int64_t parts = (*n_cand + kBlock - 1) / kBlock;
+    double a = 0.0;
+    for (int64_t k = threadIdx.x; k < parts; k += kBlock) a += q_part[k];
+    lds[threadIdx.x] = a;
+    __syncthreads();
+    for (int off = kBlock / 2; off > 0; off >>= 1) {
+        if (static_cast<int>(threadIdx.x) < off) lds[threadIdx.x] += lds[threadIdx.x + off];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) *q_total = lds[0];
+}
+
+// Radix select, pass `pass` of 8 (byte 7 - pass of the key).
+//   state[2p]   = the bytes chosen before pass p, as the low bytes of a word (0 for p = 0)
+//   state[2p+1] = how many of the keys with that prefix are still wanted (layer_size for p = 0)
+// Every workgroup derives state[2(pass)] from state[2(pass-1)] and hist[pass-1] (the first byte value at
+// which the running count reaches the wanted number); workgroup 0 stores it.  Then the keys that carry
+// the prefix are counted by their next byte.  pass == 8 only derives the final state: the threshold
+// key and how many keys equal to it are wanted.
+__global__ void __launch_bounds__(kBlock)
+k_lw_select(const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_cand, int64_t layer_size,
+            unsigned long long *__restrict__ state, int32_t *__restrict__ hist, int pass) {
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ int h[256];
+    __shared__ unsigned long long st[2];
+    const int tid = threadIdx.x;
+    if (pass == 0) {
+        if (tid == 0) {
+            st[0] = 0;
+            st[1] = static_cast<unsigned long long>(layer_size);
+        }
+    } else {
+        if (tid == 0) {
+            st[0] = 0;
+            st[1] = 0;
+        }
+        const unsigned long long prefix = state[2 * (pass - 1)];
+        const long long want = static_cast<long long>(state[2 * (pass - 1) + 1]);
+        const int c = hist[(pass - 1) * 256 + tid];
+        int total;
+        const int before = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+        // exactly one byte value has before < want <= before + c (want >= 1 and want <= total)
+        if (before < want && want <= static_cast<long long>(before) + c) {
+            st[0] = (prefix << 8) | static_cast<unsigned long long>(tid);
+            st[1] = static_cast<unsigned long long>(want - before);
+        }
+    }
+    h[tid] = 0;
+    __syncthreads();
+    if (blockIdx.x == 0 && tid == 0) {
+        state[2 * pass] = st[0];
+        state[2 * pass + 1] = st[1];
+    }
+    if (pass == 8) return;
+    const unsigned long long prefix = st[0];
+    const int shift = 56 - 8 * pass;
+    const int64_t n = *n_cand;
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t c = int64_t(blockIdx.x) * kBlock + tid; c < n; c += stride) {
+        const uint64_t k = key64[c];
+        if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&h[(k >> shift) & 255], 1);
+    }
+    __syncthreads();
+    if (h[tid]) atomicAdd(&hist[pass * 256 + tid], h[tid]);
+}
+
+// state[16] = threshold key, state[17] = number of keys equal to it that are wanted.  Keys below the
+// threshold are marked; so are the keys equal to it if all of them are wanted.  Otherwise (several
+// candidates with exactly the same key, of which only some fit) the first wavefront walks the
+// candidates in order (ascending position = ascending id) and marks equal keys until enough are taken.
+__global__ void __launch_bounds__(kBlock)
+k_lw_mark(const int32_t *__restrict__ cand, const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_cand,
+          int64_t layer_size, const unsigned long long *__restrict__ state, const int32_t *__restrict__ hist,
+          uint32_t *__restrict__ bitmap) {
+    const int64_t n = *n_cand;
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    if (n <= layer_size) {                                 // every candidate is drawn
+        for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
+        return;
+    }
+    // keys equal to the threshold: hist[7 * 256 + last byte] of them exist, state[17] are wanted -
+    // normally all of them, and then their order does not matter
+    const uint64_t thr = state[16];
+    const int64_t want = static_cast<int64_t>(state[17]);
+    const int64_t have = hist[7 * 256 + static_cast<int>(thr & 255)];
+    const bool all_equal = have == want;
+    for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
+        const uint64_t k = key64[c];
+        if (k < thr || (all_equal && k == thr)) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
+    }
+    if (all_equal || blockIdx.x != 0 || threadIdx.x >= kWave) return;
+    const int lane = lane_id();
+    int64_t taken = 0;
+    for (int64_t base = 0; base < n && taken < want; base += kWave) {
+        const int64_t c = base + lane;
+        const bool eq = c < n && key64[c] == thr;
+        const uint64_t m = ballot64(eq);
+        if (eq && taken + popc64(m & lanes_below(lane)) < want) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
+        taken += popc64(m);
+    }
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_lw_zero_i32(int32_t *__restrict__ p, int64_t n) {
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+// Eq. 8 with p_i = q_i / q_total, q_i = mass_i / di: P_vi / (s p_i) = (q_total / s) * di / (mass_i sqrt(dv di))
+template <typename PtrT>
+__device__ __forceinline__ double lw_raw_weight(const PtrT *__restrict__ row_ptr, const unsigned long long *__restrict__ mass,
+                                                double scale, double dv, int64_t i) {
+    const double di = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
+    return scale * di / (static_cast<double>(mass[i]) * sqrt(dv * di));
+}
+
+// per (row, chunk): the number of drawn nodes in the chunk's slots (chunk 0 also counts the self
+// edge) and the sum of their raw weights
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
+           const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
+           const double *__restrict__ q_total, int32_t *__restrict__ counts, double *__restrict__ psum) {
+    const int lane = lane_id();
+    const int64_t n = sizes[0] * kRowChunks;
+    const double scale = *q_total / static_cast<double>(sizes[1]);
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t u = wave0; u < n; u += nwaves) {
+        const int64_t t = u / kRowChunks;
+        const int c = static_cast<int>(u % kRowChunks);
+        const int64_t v = static_cast<int64_t>(dst[t]);
+        const int64_t start = static_cast<int64_t>(row_ptr[v]);
+        const int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - start;
+        const double dv = static_cast<double>(d + 1);
+        int cnt = 0;
+        double acc = 0.0;
+        if (c == 0 && local_of[v] >= 0) {
+            cnt = 1;
+            if (lane == 0) acc = lw_raw_weight(row_ptr, mass, scale, dv, v);
+        }
+        int64_t jb, je;
+        chunk_range(d, c, &jb, &je);
+        for (int64_t base = jb; base < je; base += kWave) {
+            const int64_t j = base + lane;
+            bool in = false;
+            if (j < je) {
+                const int64_t i = static_cast<int64_t>(col_idx[start + j]);
+                in = local_of[i] >= 0;
+                if (in) acc += lw_raw_weight(row_ptr, mass, scale, dv, i);
+            }
+            cnt += popc64(ballot64(in));
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+        if (lane == 0) {
+            counts[u] = cnt;
+            psum[u] = acc;
+        }
+    }
+}
+
+// indptr[t] = first edge position of row t = offs[t * kRowChunks]; also the block's nnz and flags
+__global__ void __launch_bounds__(kBlock)
+k_lw_indptr(const int32_t *__restrict__ offs, int64_t *sizes, int32_t *__restrict__ indptr, int64_t cap_nnz,
+            const int32_t *__restrict__ seed_flags) {
+    const int64_t n = sizes[0];
+    const int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (t <= n) indptr[t] = offs[t * kRowChunks];
+    if (t == 0) {
+        const int64_t nnz = offs[n * kRowChunks];
+        sizes[2] = nnz < cap_nnz ? nnz : cap_nnz;
+        sizes[3] = (seed_flags ? *seed_flags : 0) | (nnz > cap_nnz ? 4 : 0);
+    }
+}
+
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
+          const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
+          const double *__restrict__ q_total, const int32_t *__restrict__ offs, const double *__restrict__ psum,
+          int32_t *__restrict__ indices, float *__restrict__ edge_w, int normalise, int64_t cap_nnz) {
+    const int lane = lane_id();
+    const int64_t n = sizes[0] * kRowChunks;
+    const double scale = *q_total / static_cast<double>(sizes[1]);
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t u = wave0; u < n; u += nwaves) {
+        const int64_t t = u / kRowChunks;
+        const int c = static_cast<int>(u % kRowChunks);
+        if (offs[u + 1] == offs[u]) continue;              // nothing drawn in this chunk (wavefront-uniform)
+        const int64_t v = static_cast<int64_t>(dst[t]);
+        const int64_t start = static_cast<int64_t>(row_ptr[v]);
+        const int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - start;
+        const double dv = static_cast<double>(d + 1);
+        double inv_sum = 1.0;
+        if (normalise) {                                   // the row's sum: its chunks' partial sums in order
+            double row_sum = 0.0;
+            for (int k = 0; k < kRowChunks; ++k) row_sum += psum[t * kRowChunks + k];
+            inv_sum = 1.0 / row_sum;
+        }
+        int64_t pos = offs[u];
+        if (c == 0) {
+            const int32_t self_pos = local_of[v];
+            if (self_pos >= 0) {
+                if (lane == 0 && pos < cap_nnz) {
+                    indices[pos] = self_pos;
+                    edge_w[pos] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, v) * inv_sum);
+                }
+                pos += 1;
+            }
+        }
+        int64_t jb, je;
+        chunk_range(d, c, &jb, &je);
+        for (int64_t base = jb; base < je; base += kWave) {
+            const int64_t j = base + lane;
+            int64_t i = 0;
+            int32_t li = -1;
+            if (j < je) {
+                i = static_cast<int64_t>(col_idx[start + j]);
+                li = local_of[i];
+            }
+            const uint64_t m = ballot64(li >= 0);
+            if (li >= 0) {
+                const int64_t p = pos + popc64(m & lanes_below(lane));
+                if (p < cap_nnz) {
+                    indices[p] = li;
+                    edge_w[p] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, i) * inv_sum);
+                }
+            }
+            pos += popc64(m);
+        }
+    }
+}
+
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand, unsigned long long *__restrict__ mass,
+           const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of) {
+    const int64_t nc = *n_cand, ns = sizes[1];
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
+    for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < nc; k += stride) mass[cand[k]] = 0;
+    for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < ns; k += stride) local_of[src_ids[k]] = -1;
+}
+
+__global__ void k_lw_store_i64(int64_t *p, int64_t v) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
+}
+
+__global__ void k_lw_clear_flags(int32_t *flags) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) *flags = 0;
+}
+
+template <typename T>
+bool dev_alloc(T **p, int64_t count) {
+    return hipMalloc(reinterpret_cast<void **>(p), static_cast<size_t>(std::max<int64_t>(count, 1)) * sizeof(T)) == hipSuccess;
+}
+
+}  // namespace
+
+void free_layerwise_scratch(mqg_ctx *ctx) {
+    LayerwiseScratch &w = ctx->lw;
+    void *ptrs[] = {w.mass, w.cand, w.key64, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
+                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum};
+    for (void *p : ptrs) (void)hipFree(p);
+    w = LayerwiseScratch{};
+}
+
+// scratch of the layer-wise sampler: about 20 bytes per graph node, allocated at the first call
+static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
+    LayerwiseScratch &w = ctx->lw;
+    if (w.mass && rows_cap <= w.rows_cap) return MQG_OK;
+    hipError_t e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_sample_layerwise: ") + hipGetErrorString(e));
+    free_layerwise_scratch(ctx);
+    const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
+    const int64_t chunks = rows_cap * kRowChunks;
+    const int64_t scan_len = std::max<int64_t>(ctx->bitmap_words + 1, chunks + 1);
+    bool ok = dev_alloc(&w.mass, n) && dev_alloc(&w.cand, n) && dev_alloc(&w.key64, n) && dev_alloc(&w.word_offs, ctx->bitmap_words + 1) &&
+              dev_alloc(&w.scan_tiles, ceil_div(scan_len, kScanTile) + 2) && dev_alloc(&w.q_part, ceil_div(n, kBlock) + 1) &&
+              dev_alloc(&w.counters, 4) && dev_alloc(&w.q_total, 1) && dev_alloc(&w.seeds_copy, rows_cap) && dev_alloc(&w.flags, 1) &&
+              dev_alloc(&w.sel_state, 18) && dev_alloc(&w.sel_hist, 8 * 256) && dev_alloc(&w.chunk_offs, chunks + 1) &&
+              dev_alloc(&w.chunk_sum, chunks);
+    if (ok) ok = hipMemset(w.mass, 0, static_cast<size_t>(n) * sizeof(unsigned long long)) == hipSuccess &&
+                 hipMemset(w.flags, 0, sizeof(int32_t)) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    if (!ok) {
+        free_layerwise_scratch(ctx);
+        return fail(ctx, MQG_ERR_HIP, "mqg_sample_layerwise: scratch allocation failed");
+    }
+    w.rows_cap = rows_cap;
+    return MQG_OK;
+}
+
+template <typename PtrT, typename IdxT>
+static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
+                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise,
+                                 mqg_block *blocks, float *const *edge_w, hipStream_t s) {
+    LayerwiseScratch &w = ctx->lw;
+    const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
+    const IdxT *col_idx = static_cast<const IdxT *>(g->col_idx);
+    const int64_t n = ctx->num_nodes;
+    const int64_t words = ctx->bitmap_words;
+    const int word_grid = static_cast<int>(ceil_div(words + 1, kBlock));
+    const int cand_grid = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kBlock)));
+    const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
+    int64_t *n_cand = w.counters;
+
+    IdxT *dst0 = reinterpret_cast<IdxT *>(w.seeds_copy);
+    {
+        const int grid = static_cast<int>(std::max<int64_t>(1, ceil_div(num_seeds, kBlock)));
+        MQG_LAUNCH(ctx, "k_lw_seeds", s,
+                   (k_lw_seeds<IdxT><<<grid, kBlock, 0, s>>>(static_cast<const IdxT *>(seeds_v), num_seeds, n, dst0,
+                                                             blocks[L - 1].sizes, w.flags)));
+    }
+    for (int l = L - 1; l >= 0; --l) {
+        mqg_block &b = blocks[l];
+        const IdxT *dst = l == L - 1 ? dst0 : static_cast<const IdxT *>(blocks[l + 1].src_ids);
+        IdxT *src_ids = static_cast<IdxT *>(b.src_ids);
+        const int64_t rows_cap = l == L - 1 ? num_seeds : std::min<int64_t>(n, layer_sizes[l + 1]);
+        const uint64_t tag_hash = host_mix64(seed_hash ^ static_cast<uint64_t>(int64_t(kLayerwiseTag + l)));
+
+        const int mass_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows_cap * kRowChunks, kWavesPerBlock)), 256 * 64));
+        MQG_LAUNCH(ctx, "k_lw_mass", s,
+                   (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass, ctx->bitmap)));
+        // candidates, ascending
+        MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
+        int rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
+        if (rc != MQG_OK) return rc;
+        MQG_LAUNCH(ctx, "k_lw_emit", s,
+                   (k_lw_emit<int32_t><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, w.cand, nullptr, n_cand, nullptr)));
+        // race keys, ranking
+        MQG_LAUNCH(ctx, "k_lw_keys", s,
+                   (k_lw_keys<PtrT><<<cand_grid, kBlock, 0, s>>>(row_ptr, w.cand, n_cand, w.mass, tag_hash, w.key64, w.q_part)));
+        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, n_cand, w.q_total)));
+        MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
+        const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
+        for (int pass = 0; pass <= 8; ++pass)
+            MQG_LAUNCH(ctx, "k_lw_select", s,
+                       (k_lw_select<<<pass == 8 ? 1 : sel_grid, kBlock, 0, s>>>(w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, pass)));
+        // the drawn nodes, ascending = the block's sources
+        MQG_LAUNCH(ctx, "k_lw_mark", s,
+                   (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(w.cand, w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, ctx->bitmap)));
+        MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
+        rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
+        if (rc != MQG_OK) return rc;
+        MQG_LAUNCH(ctx, "k_lw_emit", s,
+                   (k_lw_emit<IdxT><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, src_ids, ctx->local_of, &b.sizes[1],
+                                                                 l > 0 ? &blocks[l - 1].sizes[0] : nullptr)));
+        // rows: per (row, chunk) counts and weight sums, one scan, then the edges
+        const int64_t chunks_cap = rows_cap * kRowChunks;
+        const int chunk_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(chunks_cap, kWavesPerBlock)), 256 * 64));
+        MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
+                   (k_lw_zero_i32<<<static_cast<int>(ceil_div(chunks_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, chunks_cap + 1)));
+        MQG_LAUNCH(ctx, "k_lw_count", s,
+                   (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, w.mass, w.q_total,
+                                                                         w.chunk_offs, w.chunk_sum)));
+        rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
+        if (rc != MQG_OK) return rc;
+        MQG_LAUNCH(ctx, "k_lw_indptr", s,
+                   (k_lw_indptr<<<static_cast<int>(ceil_div(rows_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, b.sizes, b.indptr, b.cap_nnz,
+                                                                                                    l == L - 1 ? w.flags : nullptr)));
+        MQG_LAUNCH(ctx, "k_lw_fill", s,
+                   (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, w.mass, w.q_total,
+                                                                        w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
+                                                                        b.cap_nnz)));
+        if (l == L - 1) MQG_LAUNCH(ctx, "k_lw_clear_flags", s, (k_lw_clear_flags<<<1, 64, 0, s>>>(w.flags)));
+        const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
+        MQG_LAUNCH(ctx, "k_lw_reset", s,
+                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(w.cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of)));
+    }
+    return MQG_OK;
+}
+
+// the selection step on its own: bit c of out_bitmap = key c is among the k smallest (key, index) pairs
+int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int64_t k, uint32_t *out_bitmap, hipStream_t s) {
+    int rc = ensure_layerwise_scratch(ctx, 1, s);
+    if (rc != MQG_OK) return rc;
+    LayerwiseScratch &w = ctx->lw;
+    int64_t *n_dev = w.counters + 1;
+    const int64_t words = ceil_div(n, 32);
+    MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(n_dev, n)));
+    if (words > 0)
+        MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
+                   (k_lw_zero_i32<<<static_cast<int>(ceil_div(words, kBlock)), kBlock, 0, s>>>(reinterpret_cast<int32_t *>(out_bitmap), words)));
+    MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
+    const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n, kBlock)), 1024));
+    for (int pass = 0; pass <= 8; ++pass)
+        MQG_LAUNCH(ctx, "k_lw_select", s, (k_lw_select<<<pass == 8 ? 1 : grid, kBlock, 0, s>>>(keys, n_dev, k, w.sel_state, w.sel_hist, pass)));
+    MQG_LAUNCH(ctx, "k_lw_mark", s, (k_lw_mark<<<grid, kBlock, 0, s>>>(nullptr, keys, n_dev, k, w.sel_state, w.sel_hist, out_bitmap)));
+    return MQG_OK;
+}
+
+int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
+                         int32_t L, uint64_t rng_seed, int32_t normalise, mqg_block *blocks, float *const *edge_w,
+                         hipStream_t s) {
+    int64_t rows_cap = num_seeds;
+    for (int l = 0; l < L; ++l) rows_cap = std::max<int64_t>(rows_cap, std::min<int64_t>(ctx->num_nodes, layer_sizes[l]));
+    int rc = ensure_layerwise_scratch(ctx, rows_cap, s);
+    if (rc != MQG_OK) return rc;
+    const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
+    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
+    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
+    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
+    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
+}
+
+}  // namespace mqg

@@ -30,7 +30,8 @@ EXPORTS = [
     "mqg_ctx_kernel_time", "mqg_ctx_reset_profile", "mqg_ctx_kernel_names", "mqg_build_cache",
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
-    "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority",
+    "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
+    "mqg_select_smallest_keys",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -101,6 +102,11 @@ lib.mqg_weighted_aggregate_backward.restype = ctypes.c_int
 lib.mqg_weighted_aggregate_backward.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _vp, _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_ctx_set_sampling_priority.restype = ctypes.c_int
 lib.mqg_ctx_set_sampling_priority.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), _vp]
+lib.mqg_sample_layerwise.restype = ctypes.c_int
+lib.mqg_sample_layerwise.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, ctypes.c_uint64,
+                                     _i32, ctypes.POINTER(CBlock), ctypes.POINTER(_vp), _vp]
+lib.mqg_select_smallest_keys.restype = ctypes.c_int
+lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
 lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
                                ctypes.POINTER(_i64)]
 
@@ -240,6 +246,36 @@ class Blocks:
         return [tuple(int(x) for x in row) for row in self.sizes.cpu().tolist()]
 
 
+class LayerwiseBlocks(Blocks):
+    """Buffers of the L weighted blocks of one layer-wise mini-batch: rows of block L-1 = the seeds,
+    sources of block l = the layer_sizes[l] drawn nodes = the rows of block l-1."""
+
+    def __init__(self, graph: Graph, max_seeds: int, layer_sizes: Sequence[int], nnz_per_row: Optional[int] = None,
+                 device=None):
+        device = device or graph.col_idx.device
+        self.layer_sizes = list(layer_sizes)
+        self.L = len(layer_sizes)
+        n = graph.num_nodes
+        self.bounds = []
+        rows = max_seeds
+        for l in range(self.L - 1, -1, -1):
+            src = min(n, layer_sizes[l])
+            per_row = src if nnz_per_row is None else min(src, nnz_per_row)
+            self.bounds.insert(0, (rows, src, max(1, rows * per_row)))
+            rows = src
+        self.src_ids, self.indptr, self.indices, self.edge_w = [], [], [], []
+        self.sizes = torch.zeros((self.L, 4), dtype=torch.int64, device=device)
+        self.c = (CBlock * self.L)()
+        for l, (cd, cs, cn) in enumerate(self.bounds):
+            self.src_ids.append(torch.empty(max(cs, 1), dtype=graph.idx_dtype, device=device))
+            self.indptr.append(torch.empty(cd + 1, dtype=torch.int32, device=device))
+            self.indices.append(torch.empty(cn, dtype=torch.int32, device=device))
+            self.edge_w.append(torch.empty(cn, dtype=torch.float32, device=device))
+            self.c[l] = CBlock(cd, cs, cn, self.src_ids[l].data_ptr(), self.indptr[l].data_ptr(),
+                               self.indices[l].data_ptr(), self.sizes[l].data_ptr())
+        self.edge_w_ptrs = (_vp * self.L)(*[t.data_ptr() for t in self.edge_w])
+
+
 class Cache:
     """Feature storage plus the HBM cache of hot rows.  `feats` may be a pinned host tensor
     or a device tensor; with num_cached=None there is no cache and feats is read directly."""
@@ -293,6 +329,25 @@ def mqg_sample_blocks(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: 
     ctx.check(lib.mqg_sample_blocks(ctx.h, ctypes.byref(graph.c), seeds.data_ptr(), seeds.numel(), arr,
                                     len(fanouts), ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), blocks.c,
                                     _stream(stream)))
+
+
+def mqg_sample_layerwise(ctx: Context, graph: Graph, seeds: torch.Tensor, layer_sizes: Sequence[int], rng_seed: int,
+                         blocks: "LayerwiseBlocks", normalise: bool = True, stream=None) -> None:
+    assert seeds.is_cuda and seeds.dtype == graph.idx_dtype and seeds.is_contiguous()
+    arr = (_i32 * len(layer_sizes))(*layer_sizes)
+    ctx.check(lib.mqg_sample_layerwise(ctx.h, ctypes.byref(graph.c), seeds.data_ptr() if seeds.numel() else None,
+                                       seeds.numel(), arr, len(layer_sizes), rng_seed & 0xFFFFFFFFFFFFFFFF,
+                                       1 if normalise else 0, blocks.c, blocks.edge_w_ptrs, _stream(stream)))
+
+
+def mqg_select_smallest_keys(ctx: Context, keys: torch.Tensor, k: int, stream=None) -> torch.Tensor:
+    """keys: device int64 tensor holding unsigned 64-bit patterns.  Returns a bool tensor: selected."""
+    assert keys.is_cuda and keys.dtype == torch.int64 and keys.is_contiguous()
+    n = keys.numel()
+    words = torch.empty(max(1, (n + 31) // 32), dtype=torch.int32, device=keys.device)
+    ctx.check(lib.mqg_select_smallest_keys(ctx.h, keys.data_ptr() if n else None, n, k, words.data_ptr(), _stream(stream)))
+    bits = (words.view(-1, 1) >> torch.arange(32, device=keys.device, dtype=torch.int32)) & 1
+    return bits.reshape(-1)[:n].bool()
 
 
 def mqg_gather_features(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,
