@@ -802,14 +802,17 @@ int orc_build_cache_drawn_by_score(int64_t num_nodes, const double *scores, int6
  * R = dst[0..num_dst) of P = D^-1/2 (A + I) D^-1/2 (Eq. 2), i.e.
  *   q_i = sum over v in dst with i in N(v) or i == v of 1 / ((deg_v+1)(deg_i+1)),
  *   p_i = q_i / sum_j q_j.
- * p has num_nodes entries; nodes outside the union of Eq. 6 get 0.
+ * p has num_nodes entries; nodes outside the union of Eq. 6 get 0.  dst == NULL
+ * stands for all rows (R = I): FastGCN's probabilities (Sec. III-B, FastGCN
+ * paragraph), the squared column norms of P itself.
  */
 void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
                               const int64_t *dst, int64_t num_dst, double *p)
 {
     for (int64_t i = 0; i < num_nodes; ++i) p[i] = 0.0;
+    if (!dst) num_dst = num_nodes;                 /* every row: the batch-independent norms of FastGCN */
     for (int64_t t = 0; t < num_dst; ++t) {
-        int64_t v = dst[t];
+        int64_t v = dst ? dst[t] : t;
         double dv = (double)(row_ptr[v + 1] - row_ptr[v]) + 1.0;
         p[v] += 1.0 / (dv * dv);
         for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) {
@@ -851,14 +854,20 @@ void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, in
  * `normalise` every row is then divided by its sum (the paper's normalisation
  * of the sampled Laplacian; rows without an edge stay empty).
  *
+ * fastgcn != 0: the FastGCN variant (Eq. 4): the masses are taken over all rows
+ * of the graph instead of the block's rows, so every node is a candidate and
+ * the draw does not depend on the mini-batch; everything else is the same (the
+ * draw is without replacement here too, and the weights are the importance
+ * weights P_vu / (s p_u) of the estimator the paper states before Eq. 12).
+ *
  * mass_out (may be NULL): num_nodes masses.  Returns the number of sources,
  * -2 when cap_nnz or cap_src is too small or memory runs out.
  */
 int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
                          const int64_t *dst, int64_t num_dst, int64_t s_layer, int64_t layer,
-                         uint64_t rng_seed, int normalise, int64_t cap_src, int64_t cap_nnz,
-                         int64_t *src, int64_t *indptr, int32_t *indices, double *edge_w,
-                         uint64_t *mass_out)
+                         uint64_t rng_seed, int normalise, int fastgcn, int64_t cap_src,
+                         int64_t cap_nnz, int64_t *src, int64_t *indptr, int32_t *indices,
+                         double *edge_w, uint64_t *mass_out)
 {
     size_t cnt = (size_t)(num_nodes > 0 ? num_nodes : 1);
     uint64_t *mass = calloc(cnt, sizeof *mass);
@@ -866,8 +875,8 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
     orc_dkey_id *cand = malloc(cnt * sizeof *cand);
     if (!mass || !pos || !cand) { free(mass); free(pos); free(cand); return -2; }
 
-    for (int64_t t = 0; t < num_dst; ++t) {
-        int64_t v = dst[t];
+    for (int64_t t = 0; t < (fastgcn ? num_nodes : num_dst); ++t) {
+        int64_t v = fastgcn ? t : dst[t];
         uint64_t add = ((uint64_t)1 << 40) / (uint64_t)(row_ptr[v + 1] - row_ptr[v] + 1);
         mass[v] += add;
         for (int64_t e = row_ptr[v]; e < row_ptr[v + 1]; ++e) mass[col_idx[e]] += add;

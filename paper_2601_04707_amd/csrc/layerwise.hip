@@ -140,23 +140,25 @@ k_lw_emit(uint32_t *__restrict__ bitmap, int64_t words, const int32_t *__restric
     }
 }
 
-// race keys of the candidates and the per-workgroup partial sums of q (zero past the last candidate)
+// race keys of the candidates and the per-workgroup partial sums of q (a fixed launch shape, so the
+// sums are the same from run to run)
 template <typename PtrT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
           const unsigned long long *__restrict__ mass, uint64_t tag_hash, uint64_t *__restrict__ key64,
           double *__restrict__ q_part) {
     __shared__ double lds[kWavesPerBlock];
-    const int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    const int64_t n = *n_cand;
+    const int64_t stride = int64_t(gridDim.x) * kBlock;
     double q = 0.0;
-    if (c < *n_cand) {
+    for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
         const int64_t i = cand[c];
         const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
         const double m = static_cast<double>(mass[i]);
         const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
         const double key = (ticket * deg1) / m;
         key64[c] = static_cast<uint64_t>(__double_as_longlong(key));
-        q = m / deg1;
+        q += m / deg1;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
@@ -165,13 +167,12 @@ k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, co
     if (threadIdx.x == 0) q_part[blockIdx.x] = ((lds[0] + lds[1]) + lds[2]) + lds[3];
 }
 
-// q_total = sum of the partial sums that cover candidates, in a fixed order
+// q_total = sum of the partial sums, in a fixed order
 __global__ void __launch_bounds__(kBlock)
-k_lw_qsum(const double *__restrict__ q_part, const int64_t *__restrict__ n_cand, double *__restrict__ q_total) {
+k_lw_qsum(const double *__restrict__ q_part, int parts, double *__restrict__ q_total) {
     __shared__ double lds[kBlock];
-    const int64_t parts = (*n_cand + kBlock - 1) / kBlock;
     double a = 0.0;
-    for (int64_t k = threadIdx.x; k < parts; k += kBlock) a += q_part[k];
+    for (int k = threadIdx.x; k < parts; k += kBlock) a += q_part[k];
     lds[threadIdx.x] = a;
     __syncthreads();
     for (int off = kBlock / 2; off > 0; off >>= 1) {
@@ -500,9 +501,10 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         MQG_LAUNCH(ctx, "k_lw_emit", s,
                    (k_lw_emit<int32_t><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, w.cand, nullptr, n_cand, nullptr)));
         // race keys, ranking
+        const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
-                   (k_lw_keys<PtrT><<<cand_grid, kBlock, 0, s>>>(row_ptr, w.cand, n_cand, w.mass, tag_hash, w.key64, w.q_part)));
-        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, n_cand, w.q_total)));
+                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, w.cand, n_cand, w.mass, tag_hash, w.key64, w.q_part)));
+        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total)));
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
         for (int pass = 0; pass <= 8; ++pass)

@@ -904,3 +904,29 @@ def test_ladies_degenerate_cases():
     assert b.num_src == 0 and b.nnz == 0 and b.indptr.tolist() == [0]
     b = oracle.ladies_blocks(rp, ci, np.array([1, 3], dtype=np.int64), [1], 3, normalise=False)[0]
     assert b.num_src == 1 and b.indptr[-1] == b.nnz
+
+
+def test_fastgcn_probabilities_and_batch_independent_draw():
+    rp, ci = tiny_graph(150, 1800, seed=55)
+    n = len(rp) - 1
+    P = dense_gcn_operator(rp, ci)
+    want = (P ** 2).sum(axis=0) / (P ** 2).sum()                 # squared column norms of P itself
+    assert np.allclose(oracle.ladies_probabilities(rp, ci), want, rtol=1e-12)
+    a = oracle.ladies_blocks(rp, ci, np.array([3, 9, 27]), [20, 30], 5, fastgcn=True, want_mass=True)
+    b = oracle.ladies_blocks(rp, ci, np.array([100, 4, 77, 12]), [20, 30], 5, fastgcn=True)
+    deg1 = np.diff(rp) + 1
+    q = a[1].mass.astype(np.float64) / deg1
+    assert np.allclose(q / q.sum(), want, rtol=1e-9)
+    for l in (0, 1):                                             # the draw does not look at the mini-batch
+        assert np.array_equal(a[l].src_ids, b[l].src_ids) and a[l].num_src == [20, 30][l]
+    # restated: race over all nodes
+    t = np.array([oracle.exp_ticket(oracle.key(5, 64 + 1, i, 0)) for i in range(n)], dtype=np.float64)
+    key = (t * deg1) / a[1].mass.astype(np.float64)
+    assert np.array_equal(a[1].src_ids, np.sort(np.lexsort((np.arange(n), key))[:30]))
+    # raw weights undo to P: weight * s * p_u == P_vu on the edges that survive
+    raw = oracle.ladies_blocks(rp, ci, np.array([3, 9, 27]), [20, 30], 5, fastgcn=True, normalise=False)[1]
+    for r, v in enumerate([3, 9, 27]):
+        e = slice(raw.indptr[r], raw.indptr[r + 1])
+        ids = raw.src_ids[raw.indices[e]]
+        assert np.allclose(raw.edge_w[e] * 30 * want[ids], P[v, ids], rtol=1e-9)
+        assert set(ids.tolist()) == (set(ci[rp[v]:rp[v + 1]].tolist()) | {v}) & set(raw.src_ids.tolist())
