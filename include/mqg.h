@@ -295,14 +295,22 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
  *                min(N, layer_sizes[l]); edges beyond cap_nnz are dropped and
  *                flagged (sizes[3] bit 2; sizes[2] is then cap_nnz)
  *   edge_w       host array of num_layers device pointers, [cap_nnz] floats each
- * The first call allocates context scratch of about 53 bytes per graph node
- * (and synchronises the stream once).  Feed the blocks to
+ * method MQG_LAYERWISE_FASTGCN (paper Sec. III-B, FastGCN paragraph, Eq. 4): the
+ * masses are taken over all rows of the graph instead of the block's rows - the
+ * squared column norms of P itself, computed at the first such call on the
+ * context - so every node is a candidate and the draw does not depend on the
+ * mini-batch; everything else is the same (drawn without replacement,
+ * importance weights P_vu / (s p_u)).
+ * The first call allocates context scratch of about 20 bytes per graph node
+ * (8 more for FastGCN) and synchronises the stream once.  Feed the blocks to
  * mqg_weighted_aggregate with self_w == NULL.
  */
+typedef enum { MQG_LAYERWISE_LADIES = 0, MQG_LAYERWISE_FASTGCN = 1 } mqg_layerwise_method;
+
 int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
                          const int32_t *layer_sizes, int32_t num_layers, uint64_t rng_seed,
-                         int32_t normalise, mqg_block *blocks, float *const *edge_w,
-                         mqg_stream stream);
+                         int32_t normalise, int32_t method, mqg_block *blocks,
+                         float *const *edge_w, mqg_stream stream);
 
 /*
  * The selection step of mqg_sample_layerwise on its own (the k smallest race

@@ -350,13 +350,15 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
 }
 
 int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
-                         const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise,
+                         const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, int32_t method,
                          mqg_block *blocks, float *const *edge_w, mqg_stream stream) {
     if (!ctx) return MQG_ERR_INVALID_ARG;
     int rc = check_graph(ctx, g, "mqg_sample_layerwise");
     if (rc != MQG_OK) return rc;
     if (!layer_sizes || !blocks || !edge_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: NULL layer_sizes, blocks or edge_w");
     if (L < 1 || L > MQG_MAX_LAYERS) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: num_layers outside 1..MQG_MAX_LAYERS");
+    if (method != MQG_LAYERWISE_LADIES && method != MQG_LAYERWISE_FASTGCN)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: unknown method");
     if (num_seeds < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: negative num_seeds");
     if (num_seeds > 0 && !seeds_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: seeds_dev is NULL");
     if (num_seeds > 0 && g->num_nodes == 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: seeds given for an empty graph");
@@ -372,7 +374,7 @@ int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev
                         std::to_string(rows) + " cap_src>=" + std::to_string(src) + " and 0 <= cap_nnz < 2^31");
         rows = src;
     }
-    return mqg::run_sample_layerwise(ctx, g, seeds_dev, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w,
+    return mqg::run_sample_layerwise(ctx, g, seeds_dev, num_seeds, layer_sizes, L, rng_seed, normalise, method, blocks, edge_w,
                                      static_cast<hipStream_t>(stream));
 }
 

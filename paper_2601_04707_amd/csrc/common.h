@@ -48,6 +48,8 @@ struct LayerwiseScratch {
     double *q_total = nullptr;
     int64_t *seeds_copy = nullptr;       // [rows_cap] the checked seeds
     int32_t *flags = nullptr;
+    unsigned long long *fg_mass = nullptr;     // [num_nodes] masses over all rows of the graph (FastGCN)
+    bool fg_ready = false;
     int64_t rows_cap = 0;
 };
 
@@ -151,8 +153,8 @@ int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w
                            int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
 int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
-                         int32_t L, uint64_t rng_seed, int32_t normalise, mqg_block *blocks, float *const *edge_w,
-                         hipStream_t s);
+                         int32_t L, uint64_t rng_seed, int32_t normalise, int32_t method, mqg_block *blocks,
+                         float *const *edge_w, hipStream_t s);
 void free_layerwise_scratch(mqg_ctx *ctx);
 int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int64_t k, uint32_t *out_bitmap, hipStream_t s);
 int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s);

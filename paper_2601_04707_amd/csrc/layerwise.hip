@@ -88,20 +88,20 @@ k_lw_mass(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
     for (int64_t u = wave0; u < n; u += nwaves) {
         const int64_t t = u / kRowChunks;
         const int c = static_cast<int>(u % kRowChunks);
-        const int64_t v = static_cast<int64_t>(dst[t]);
+        const int64_t v = dst ? static_cast<int64_t>(dst[t]) : t;      // no row list: every node of the graph
         const int64_t start = static_cast<int64_t>(row_ptr[v]);
         const int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - start;
         const unsigned long long add = (1ull << 40) / static_cast<unsigned long long>(d + 1);
         if (c == 0 && lane == 0) {
             atomicAdd(&mass[v], add);
-            set_bit(bitmap, static_cast<uint32_t>(v));
+            if (bitmap) set_bit(bitmap, static_cast<uint32_t>(v));
         }
         int64_t jb, je;
         chunk_range(d, c, &jb, &je);
         for (int64_t j = jb + lane; j < je; j += kWave) {
             const uint32_t i = static_cast<uint32_t>(col_idx[start + j]);
             atomicAdd(&mass[i], add);
-            set_bit(bitmap, i);
+            if (bitmap) set_bit(bitmap, i);
         }
     }
 }
@@ -152,7 +152,7 @@ k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, co
     const int64_t stride = int64_t(gridDim.x) * kBlock;
     double q = 0.0;
     for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
-        const int64_t i = cand[c];
+        const int64_t i = cand ? cand[c] : c;
         const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
         const double m = static_cast<double>(mass[i]);
         const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
@@ -411,7 +411,8 @@ k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
            const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of) {
     const int64_t nc = *n_cand, ns = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
-    for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < nc; k += stride) mass[cand[k]] = 0;
+    if (cand)
+        for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < nc; k += stride) mass[cand[k]] = 0;
     for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < ns; k += stride) local_of[src_ids[k]] = -1;
 }
 
@@ -433,7 +434,7 @@ bool dev_alloc(T **p, int64_t count) {
 void free_layerwise_scratch(mqg_ctx *ctx) {
     LayerwiseScratch &w = ctx->lw;
     void *ptrs[] = {w.mass, w.cand, w.key64, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
-                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum};
+                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum, w.fg_mass};
     for (void *p : ptrs) (void)hipFree(p);
     w = LayerwiseScratch{};
 }
@@ -465,7 +466,7 @@ static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t 
 
 template <typename PtrT, typename IdxT>
 static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
-                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise,
+                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, bool fastgcn,
                                  mqg_block *blocks, float *const *edge_w, hipStream_t s) {
     LayerwiseScratch &w = ctx->lw;
     const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
@@ -475,7 +476,17 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
     const int word_grid = static_cast<int>(ceil_div(words + 1, kBlock));
     const int cand_grid = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kBlock)));
     const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
-    int64_t *n_cand = w.counters;
+    int64_t *n_cand = fastgcn ? w.counters + 2 : w.counters;    // FastGCN: every node is a candidate
+    const int32_t *cand = fastgcn ? nullptr : w.cand;
+    const unsigned long long *mass = fastgcn ? w.fg_mass : w.mass;
+    if (fastgcn && !w.fg_ready) {
+        // the batch-independent masses: the mass kernel over every row of the graph, once per context
+        MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(w.counters + 2, n)));
+        const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n * kRowChunks, kWavesPerBlock)), 256 * 64));
+        MQG_LAUNCH(ctx, "k_lw_mass", s,
+                   (k_lw_mass<PtrT, IdxT><<<grid, kBlock, 0, s>>>(row_ptr, col_idx, nullptr, w.counters + 2, w.fg_mass, nullptr)));
+        w.fg_ready = true;
+    }
 
     IdxT *dst0 = reinterpret_cast<IdxT *>(w.seeds_copy);
     {
@@ -491,19 +502,22 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         const int64_t rows_cap = l == L - 1 ? num_seeds : std::min<int64_t>(n, layer_sizes[l + 1]);
         const uint64_t tag_hash = host_mix64(seed_hash ^ static_cast<uint64_t>(int64_t(kLayerwiseTag + l)));
 
-        const int mass_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows_cap * kRowChunks, kWavesPerBlock)), 256 * 64));
-        MQG_LAUNCH(ctx, "k_lw_mass", s,
-                   (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass, ctx->bitmap)));
-        // candidates, ascending
-        MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
-        int rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
-        if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_lw_emit", s,
-                   (k_lw_emit<int32_t><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, w.cand, nullptr, n_cand, nullptr)));
+        int rc = MQG_OK;
+        if (!fastgcn) {
+            const int mass_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows_cap * kRowChunks, kWavesPerBlock)), 256 * 64));
+            MQG_LAUNCH(ctx, "k_lw_mass", s,
+                       (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass, ctx->bitmap)));
+            // candidates, ascending
+            MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
+            rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
+            if (rc != MQG_OK) return rc;
+            MQG_LAUNCH(ctx, "k_lw_emit", s,
+                       (k_lw_emit<int32_t><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, w.cand, nullptr, n_cand, nullptr)));
+        }
         // race keys, ranking
         const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
-                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, w.cand, n_cand, w.mass, tag_hash, w.key64, w.q_part)));
+                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_cand, mass, tag_hash, w.key64, w.q_part)));
         MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total)));
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
@@ -512,7 +526,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                        (k_lw_select<<<pass == 8 ? 1 : sel_grid, kBlock, 0, s>>>(w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, pass)));
         // the drawn nodes, ascending = the block's sources
         MQG_LAUNCH(ctx, "k_lw_mark", s,
-                   (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(w.cand, w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, ctx->bitmap)));
+                   (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(cand, w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, ctx->bitmap)));
         MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
         rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
         if (rc != MQG_OK) return rc;
@@ -525,7 +539,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
                    (k_lw_zero_i32<<<static_cast<int>(ceil_div(chunks_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, chunks_cap + 1)));
         MQG_LAUNCH(ctx, "k_lw_count", s,
-                   (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, w.mass, w.q_total,
+                   (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
                                                                          w.chunk_offs, w.chunk_sum)));
         rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
         if (rc != MQG_OK) return rc;
@@ -533,13 +547,13 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                    (k_lw_indptr<<<static_cast<int>(ceil_div(rows_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, b.sizes, b.indptr, b.cap_nnz,
                                                                                                     l == L - 1 ? w.flags : nullptr)));
         MQG_LAUNCH(ctx, "k_lw_fill", s,
-                   (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, w.mass, w.q_total,
+                   (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
                                                                         w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
                                                                         b.cap_nnz)));
         if (l == L - 1) MQG_LAUNCH(ctx, "k_lw_clear_flags", s, (k_lw_clear_flags<<<1, 64, 0, s>>>(w.flags)));
         const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
         MQG_LAUNCH(ctx, "k_lw_reset", s,
-                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(w.cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of)));
+                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of)));
     }
     return MQG_OK;
 }
@@ -564,17 +578,28 @@ int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int6
 }
 
 int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
-                         int32_t L, uint64_t rng_seed, int32_t normalise, mqg_block *blocks, float *const *edge_w,
+                         int32_t L, uint64_t rng_seed, int32_t normalise, int32_t method, mqg_block *blocks, float *const *edge_w,
                          hipStream_t s) {
+    const bool fg = method == MQG_LAYERWISE_FASTGCN;
     int64_t rows_cap = num_seeds;
     for (int l = 0; l < L; ++l) rows_cap = std::max<int64_t>(rows_cap, std::min<int64_t>(ctx->num_nodes, layer_sizes[l]));
     int rc = ensure_layerwise_scratch(ctx, rows_cap, s);
     if (rc != MQG_OK) return rc;
+    if (fg && !ctx->lw.fg_mass) {
+        const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
+        if (!dev_alloc(&ctx->lw.fg_mass, n) ||
+            hipMemsetAsync(ctx->lw.fg_mass, 0, static_cast<size_t>(n) * sizeof(unsigned long long), s) != hipSuccess) {
+            (void)hipFree(ctx->lw.fg_mass);
+            ctx->lw.fg_mass = nullptr;
+            return fail(ctx, MQG_ERR_HIP, "mqg_sample_layerwise: scratch allocation failed");
+        }
+        ctx->lw.fg_ready = false;
+    }
     const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
-    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
-    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
-    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, blocks, edge_w, s);
+    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
+    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
+    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
+    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
 }
 
 }  // namespace mqg

@@ -104,7 +104,8 @@ lib.mqg_ctx_set_sampling_priority.restype = ctypes.c_int
 lib.mqg_ctx_set_sampling_priority.argtypes = [_vp, ctypes.POINTER(CGraph), ctypes.POINTER(CCache), _vp]
 lib.mqg_sample_layerwise.restype = ctypes.c_int
 lib.mqg_sample_layerwise.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, ctypes.c_uint64,
-                                     _i32, ctypes.POINTER(CBlock), ctypes.POINTER(_vp), _vp]
+                                     _i32, _i32, ctypes.POINTER(CBlock), ctypes.POINTER(_vp), _vp]
+MQG_LAYERWISE_LADIES, MQG_LAYERWISE_FASTGCN = 0, 1
 lib.mqg_select_smallest_keys.restype = ctypes.c_int
 lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
 lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
@@ -332,12 +333,12 @@ def mqg_sample_blocks(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: 
 
 
 def mqg_sample_layerwise(ctx: Context, graph: Graph, seeds: torch.Tensor, layer_sizes: Sequence[int], rng_seed: int,
-                         blocks: "LayerwiseBlocks", normalise: bool = True, stream=None) -> None:
+                         blocks: "LayerwiseBlocks", normalise: bool = True, method: int = 0, stream=None) -> None:
     assert seeds.is_cuda and seeds.dtype == graph.idx_dtype and seeds.is_contiguous()
     arr = (_i32 * len(layer_sizes))(*layer_sizes)
     ctx.check(lib.mqg_sample_layerwise(ctx.h, ctypes.byref(graph.c), seeds.data_ptr() if seeds.numel() else None,
                                        seeds.numel(), arr, len(layer_sizes), rng_seed & 0xFFFFFFFFFFFFFFFF,
-                                       1 if normalise else 0, blocks.c, blocks.edge_w_ptrs, _stream(stream)))
+                                       1 if normalise else 0, method, blocks.c, blocks.edge_w_ptrs, _stream(stream)))
 
 
 def mqg_select_smallest_keys(ctx: Context, keys: torch.Tensor, k: int, stream=None) -> torch.Tensor:

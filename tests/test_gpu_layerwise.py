@@ -27,9 +27,9 @@ def hub_graph(n=20000, edges=400_000, max_degree=3000, ptr=torch.int64, idx=torc
     return rp.to(ptr), ci.to(idx)
 
 
-def run_layerwise(mqg, ctx, g, blocks, seeds_cpu, sizes, rng_seed, normalise=True):
+def run_layerwise(mqg, ctx, g, blocks, seeds_cpu, sizes, rng_seed, normalise=True, method=0):
     seeds = to_dev(seeds_cpu.to(g.idx_dtype))
-    mqg.mqg_sample_layerwise(ctx, g, seeds, sizes, rng_seed, blocks, normalise=normalise)
+    mqg.mqg_sample_layerwise(ctx, g, seeds, sizes, rng_seed, blocks, normalise=normalise, method=method)
     torch.cuda.synchronize()
     hs = blocks.host_sizes()
     out = []
@@ -75,6 +75,32 @@ def test_layerwise_parity_hub_graph(mqg, ptr, idx, sizes, normalise):
                 assert np.allclose(sums[nonempty], 1.0, rtol=1e-5)
 
 
+@pytest.mark.parametrize("ptr,idx", [(torch.int32, torch.int32), (torch.int64, torch.int64)])
+@pytest.mark.parametrize("sizes", [[64, 128], [512, 512], [100, 50, 30]])
+def test_fastgcn_parity_and_alternation_with_ladies(mqg, ptr, idx, sizes):
+    rp, ci = hub_graph(ptr=ptr, idx=idx)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    batch = 193
+    ctx = mqg.Context(g, batch, [2] * len(sizes))
+    blocks = mqg.LayerwiseBlocks(g, batch, sizes)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    batches = synth.seed_batches(n, batch, 2, seed=7)
+    prev = None
+    for b, seeds in enumerate(batches):
+        for normalise in (True, False):
+            got = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 55, normalise, method=mqg.MQG_LAYERWISE_FASTGCN)
+            want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 55, normalise=normalise, fastgcn=True)
+            assert_same(got, want)
+        if prev is not None:                                      # same sampling seed: the same nodes for another batch
+            for l in range(len(sizes)):
+                assert np.array_equal(prev[l]["src_ids"], got[l]["src_ids"])
+        prev = got
+        # LADIES on the same context in between: its masses and candidate lists are separate
+        got = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 56)
+        assert_same(got, oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 56))
+
+
 def test_layerwise_small_graph_all_candidates_and_degenerate_inputs(mqg):
     rp = torch.tensor([0, 0, 2, 3, 3, 6], dtype=torch.int64)      # nodes 0 and 3 have no neighbours
     ci = torch.tensor([2, 4, 1, 0, 1, 2], dtype=torch.int64)
@@ -87,6 +113,9 @@ def test_layerwise_small_graph_all_candidates_and_degenerate_inputs(mqg):
             for normalise in (True, False):
                 got = run_layerwise(mqg, ctx, g, blocks, s, sizes, 3, normalise)
                 want = oracle.ladies_blocks(rp.numpy(), ci.numpy(), s.numpy(), sizes, 3, normalise=normalise)
+                assert_same(got, want)
+                got = run_layerwise(mqg, ctx, g, blocks, s, sizes, 3, normalise, method=mqg.MQG_LAYERWISE_FASTGCN)
+                want = oracle.ladies_blocks(rp.numpy(), ci.numpy(), s.numpy(), sizes, 3, normalise=normalise, fastgcn=True)
                 assert_same(got, want)
     # an id outside the graph is replaced by node 0 and flagged on the innermost block
     blocks = mqg.LayerwiseBlocks(g, 8, [4, 4])
