@@ -45,6 +45,9 @@ def main() -> int:
     ap.add_argument("--prioritise-cache", action="store_true",
                     help="cache-prioritised neighbour sampling: a row's cached neighbours are drawn first "
                          "(another sampling distribution than the workloads define; for comparison)")
+    ap.add_argument("--graph", action="store_true",
+                    help="record each in-flight slot's step (sample, gather, aggregate) into a HIP graph once and "
+                         "replay it in the timed region (seeds and sampling seed are rewritten in device buffers)")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -90,7 +93,7 @@ def main() -> int:
     pad_dim = (row_bytes + 15) // 16 * 16 // elt      # row stride that keeps every row 16-byte aligned
     ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]
-    streams = [torch.cuda.Stream() for _ in range(nfl)] if nfl > 1 else [torch.cuda.current_stream()]
+    streams = [torch.cuda.Stream() for _ in range(nfl)] if (nfl > 1 or args.graph) else [torch.cuda.current_stream()]
     if cache_pct is None:
         cache = mqg.Cache(g, feats.to(dev), None)
         num_cached = 0
@@ -153,13 +156,50 @@ def main() -> int:
             sizes_log[i].copy_(blks[j].sizes, non_blocking=True)
             stats_log[i].copy_(stats[j], non_blocking=True)
 
+    timed_step = step
+    if args.graph:
+        # one recorded step per in-flight slot; what changes between replays lives in device buffers
+        seed_buf = [torch.zeros(w.batch, dtype=g.idx_dtype, device=dev) for _ in range(nfl)]
+        rng_buf = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(nfl)]
+        rng_vals = torch.arange(base_seed, base_seed + K + W, dtype=torch.int64, device=dev)
+
+        def recorded(j):
+            s = streams[j]
+            mqg.mqg_sample_blocks_seed_dev(ctxs[j], g, seed_buf[j], w.fanouts, rng_buf[j], blks[j], stream=s)
+            mqg.mqg_gather_features(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s)
+            x = x0[j]
+            for l in range(L):
+                mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s)
+                x = hs[j][l]
+
+        for i in range(nfl):                                    # eager once, then record
+            step(i)
+        torch.cuda.synchronize()
+        graphs = []
+        for j in range(nfl):
+            seed_buf[j].copy_(seeds_dev[j])
+            cg = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(cg, stream=streams[j]):
+                recorded(j)
+            graphs.append(cg)
+        torch.cuda.synchronize()
+
+        def timed_step(i: int):
+            j = i % nfl
+            with torch.cuda.stream(streams[j]):
+                seed_buf[j].copy_(seeds_dev[i], non_blocking=True)
+                rng_buf[j].copy_(rng_vals[i:i + 1], non_blocking=True)
+                graphs[j].replay()
+                sizes_log[i].copy_(blks[j].sizes, non_blocking=True)
+                stats_log[i].copy_(stats[j], non_blocking=True)
+
     # ---------------------------------------------------------------- timed region
     for i in range(W):
-        step(i)
+        timed_step(i)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(W, W + K):
-        step(i)
+        timed_step(i)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -439,7 +479,8 @@ def main() -> int:
                                f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({args.cache_policy}), "
                                f"rest in pinned host memory",
                    "in_flight": nfl, "global_batch": w.batch, "dedup": args.dedup,
-                   "sampling": "cached neighbours first" if args.prioritise_cache else "uniform"},
+                   "sampling": "cached neighbours first" if args.prioritise_cache else "uniform",
+                   "launch": "one recorded HIP graph per in-flight slot" if args.graph else "eager"},
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
         "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
         "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),

@@ -265,6 +265,21 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
                       mqg_block *blocks, mqg_stream stream);
 
 /*
+ * mqg_sample_blocks with the sampling seed read from device memory when the
+ * kernels run, for callers that record a mini-batch step into a HIP graph and
+ * replay it: a recorded launch keeps its arguments, so what changes from one
+ * replay to the next - the seeds in seeds_dev[0..num_seeds) and *rng_seed_dev -
+ * has to live in buffers that the caller rewrites between replays.  Same
+ * blocks as mqg_sample_blocks(..., rng_seed = *rng_seed_dev, ...).  With the
+ * default dedup path and MQG_OPT_PROFILE off, this call, mqg_gather_features
+ * and mqg_sage_mean_aggregate only enqueue kernels (no allocation, no memset,
+ * no synchronisation) and can be captured.
+ */
+int mqg_sample_blocks_seed_dev(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                               const int32_t *fanouts, int32_t num_layers,
+                               const uint64_t *rng_seed_dev, mqg_block *blocks, mqg_stream stream);
+
+/*
  * Layer-wise sampling after LADIES (paper Sec. III-B, Eq. 6-9) into blocks of
  * the same layout, with edge weights.  blocks[L-1] has the seeds as rows; for
  * every block, from L-1 down to 0, with rows D:

@@ -316,9 +316,9 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
     return mqg_build_cache_ex(ctx, g, cache, nullptr, stream);
 }
 
-int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
-                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks,
-                      mqg_stream stream) {
+static int sample_blocks_checked(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                                 const int32_t *fanouts, int32_t L, uint64_t rng_seed, const uint64_t *seed_dev,
+                                 mqg_block *blocks, mqg_stream stream) {
     if (!ctx) return MQG_ERR_INVALID_ARG;
     int rc = check_graph(ctx, g, "mqg_sample_blocks");
     if (rc != MQG_OK) return rc;
@@ -345,8 +345,22 @@ int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, i
                         " cap_src>=" + std::to_string(src));
         dst = src;
     }
-    return mqg::run_sample_blocks(ctx, g, seeds_dev, num_seeds, fanouts, L, rng_seed, blocks,
+    return mqg::run_sample_blocks(ctx, g, seeds_dev, num_seeds, fanouts, L, rng_seed, seed_dev, blocks,
                                   static_cast<hipStream_t>(stream));
+}
+
+int mqg_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks,
+                      mqg_stream stream) {
+    return sample_blocks_checked(ctx, g, seeds_dev, num_seeds, fanouts, L, rng_seed, nullptr, blocks, stream);
+}
+
+int mqg_sample_blocks_seed_dev(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
+                               const int32_t *fanouts, int32_t L, const uint64_t *rng_seed_dev, mqg_block *blocks,
+                               mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (!rng_seed_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_blocks_seed_dev: rng_seed_dev is NULL");
+    return sample_blocks_checked(ctx, g, seeds_dev, num_seeds, fanouts, L, 0, rng_seed_dev, blocks, stream);
 }
 
 int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,

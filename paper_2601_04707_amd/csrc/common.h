@@ -77,8 +77,7 @@ struct mqg_ctx {
     int32_t *heavy_count = nullptr;      // [MQG_MAX_LAYERS] their number, per block; [MQG_MAX_LAYERS] seed-check flags
     int2 *hit_list = nullptr;            // [max_src] (output row, cache slot)
     int2 *miss_list = nullptr;           // [max_src] (output row, node id)
-    unsigned long long *counters = nullptr;  // [8] two alternating (hits, misses) pairs: a gather uses one and clears the other
-    uint64_t gather_calls = 0;
+    unsigned long long *counters = nullptr;  // [8] hits, misses, finished workgroups of the miss launch; zero between gathers
     // backward aggregation: edges ordered by source; allocated at the first backward call
     mqg::RadixBufs bwd;
     int32_t *bwd_dst_row = nullptr;      // [bwd_nnz_cap] destination row of every edge
@@ -137,9 +136,8 @@ void prof_end(mqg_ctx *ctx, hipStream_t s);
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 // ---- steps implemented in the other translation units ----------------------------------
-int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds,
-                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks,
-                      hipStream_t s);
+int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *fanouts,
+                      int32_t L, uint64_t rng_seed, const uint64_t *seed_dev, mqg_block *blocks, hipStream_t s);
 int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids,
                const int64_t *num_ids, int64_t cap_ids, void *out, int64_t out_stride,
                int64_t *stats, hipStream_t s);

@@ -39,10 +39,9 @@ template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
            const int32_t *__restrict__ slot_of, int2 *__restrict__ hit_list, int2 *__restrict__ miss_list,
-           unsigned long long *__restrict__ counters, unsigned long long *__restrict__ next_counters) {
+           unsigned long long *__restrict__ counters) {
     __shared__ int lds[kWavesPerBlock];
     __shared__ unsigned long long base[2];
-    if (blockIdx.x == 0 && threadIdx.x < 2) next_counters[threadIdx.x] = 0;   // the pair the next gather counts in
     int64_t n = *num_ids;
     if (n > cap) n = cap;
     for (int64_t t0 = int64_t(blockIdx.x) * kClassifyTile; t0 < n; t0 += int64_t(gridDim.x) * kClassifyTile) {
@@ -174,17 +173,33 @@ __device__ __forceinline__ void copy_rows(const Rows &rows, int64_t n, const cha
     }
 }
 
-// MISS only names the launch: 0 = rows from the HBM cache, 1 = rows from the feature matrix in
-// pinned host memory.  The code is the same; profiles tell the two apart by symbol.
+// MISS names the launch: 0 = rows from the HBM cache, 1 = rows from the feature matrix in pinned
+// host memory.  The copy is the same; profiles tell the two apart by symbol.  The miss launch is
+// the last kernel of a gather and leaves the (hits, misses) counters at zero for the next one: the
+// workgroup that finishes last - every workgroup has read its count by then - clears them, so the
+// call is self-contained and can be replayed from a recorded graph.  counters[2] counts the
+// finished workgroups.
 template <typename VecT, int MISS>
 __global__ void __launch_bounds__(kBlock)
-k_gather_rows(const int2 *__restrict__ list, const unsigned long long *__restrict__ count,
+k_gather_rows(const int2 *__restrict__ list, const unsigned long long *count,
               const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
               int64_t dst_stride_bytes, int vecs, int log2_lpr, int64_t *__restrict__ stats,
-              const unsigned long long *__restrict__ counters) {
+              unsigned long long *counters) {
     if (stats && blockIdx.x == 0 && threadIdx.x < 2) stats[threadIdx.x] = static_cast<int64_t>(counters[threadIdx.x]);
     const int64_t n = static_cast<int64_t>(*count);
     copy_rows<VecT>(ListRows{list}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
+    if (MISS) {
+        __syncthreads();                                   // every thread of the workgroup has read its count
+        if (threadIdx.x == 0) {
+            __threadfence();
+            const unsigned long long done = atomicAdd(&counters[2], 1ull);
+            if (done == gridDim.x - 1) {
+                counters[0] = 0;
+                counters[1] = 0;
+                counters[2] = 0;
+            }
+        }
+    }
 }
 
 template <typename VecT, typename IdxT>
@@ -262,7 +277,7 @@ int link_grid(int64_t rows, const RowGeom &g, int64_t inflight_bytes) {
 template <int MISS>
 int launch_rows(mqg_ctx *ctx, const char *name, const int2 *list, const unsigned long long *count, int64_t cap,
                 const void *src, int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes,
-                int64_t row_bytes, int64_t *stats, const unsigned long long *counters, hipStream_t s) {
+                int64_t row_bytes, int64_t *stats, unsigned long long *counters, hipStream_t s) {
     row_bytes = copy_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
     const RowGeom g = row_geom(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
     const int grid = MISS ? link_grid(cap, g, ctx->miss_inflight_bytes) : hbm_grid(cap, g);
@@ -341,15 +356,13 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
         return MQG_OK;
     }
 
-    // two (hits, misses) counter pairs take turns: this call counts in one and clears the other
-    unsigned long long *counters = ctx->counters + 2 * (ctx->gather_calls & 1);
-    unsigned long long *next_counters = ctx->counters + 2 * ((ctx->gather_calls + 1) & 1);
-    ctx->gather_calls++;
+    // (hits, misses) counters: zero between calls (the miss launch clears them when it is done)
+    unsigned long long *counters = ctx->counters;
     const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(cap_ids, kClassifyTile)), 1024));
     if (idx_type == MQG_I64)
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters, next_counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
     else
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters, next_counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
 
     int rc = launch_rows<0>(ctx, "k_gather_hit", ctx->hit_list, &counters[0], cap_ids, c->cache_rows,
                             c->cache_stride * elt, out, out_stride * elt, row_bytes, stats, counters, s);

@@ -148,11 +148,18 @@ struct SampleArgs {
     int32_t *nbr;
     const int32_t *local_of;
     uint32_t *bitmap;
-    uint64_t layer_hash;      // mix(mix(rng_seed + golden) ^ block index)
+    uint64_t layer_hash;      // mix(mix(rng_seed + golden) ^ block index), used when seed_dev is null
+    const uint64_t *seed_dev; // the sampling seed in device memory (calls recorded into a HIP graph)
+    int layer;                // block index, for seed_dev
     int fanout;
     int force_slow;
     int heavy_degree;         // rows longer than this are sampled by whole workgroups
 };
+
+__device__ __forceinline__ uint64_t layer_hash_of(const SampleArgs &a) {
+    if (!a.seed_dev) return a.layer_hash;
+    return mix64(mix64(*a.seed_dev + 0x9E3779B97F4A7C15ULL) ^ static_cast<uint64_t>(a.layer));
+}
 
 template <typename IdxT>
 __device__ __forceinline__ void emit_neighbour(const IdxT *__restrict__ col_idx, int64_t start, int slot,
@@ -267,7 +274,7 @@ __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__rest
         const int64_t start = a.row_start[row];
         const int d = a.row_deg[row];
         const int32_t out_base = a.indptr[row];
-        const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
+        const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(dst_ids[row]));
         const RowKeys key_of(hv);
         if (tid == 0) *cnt_s = 0;
         __syncthreads();
@@ -353,7 +360,7 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
         return;
     }
     if (d > a.heavy_degree) return;                        // a hub: sampled by the first workgroups
-    const uint64_t hv = mix64(a.layer_hash ^ uint64_t(dst_ids[row]));
+    const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(dst_ids[row]));
     if (a.force_slow) {
         select_by_repeated_min(col_idx, start, d, k, hv, out_base, a);
         return;
@@ -521,7 +528,7 @@ __device__ void sample_hubs_prio(const IdxT *__restrict__ col_idx, const IdxT *_
         const int d = a.row_deg[row];
         const int32_t out_base = a.indptr[row];
         const IdxT node = dst_ids[row];
-        const uint64_t hv = mix64(a.layer_hash ^ uint64_t(node));
+        const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(node));
         const RowKeys key_of(hv);
         const IdxT *nbrs = col_idx + start;
         const PrioRule rule(d, k, prio_count[node]);
@@ -621,7 +628,7 @@ k_sample_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids
     }
     if (d > a.heavy_degree) return;                        // a hub: sampled by the first workgroups
     const IdxT node = dst_ids[row];
-    const uint64_t hv = mix64(a.layer_hash ^ uint64_t(node));
+    const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(node));
     if (a.force_slow) {
         select_by_repeated_min_prio(col_idx, start, d, k, hv, out_base, a, prio);
         return;
@@ -856,7 +863,7 @@ k_reset_local(const IdxT *__restrict__ src_ids, const int64_t *__restrict__ size
 }
 
 template <typename PtrT, typename IdxT>
-int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
+int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds, const uint64_t *seed_dev,
                        const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks, hipStream_t s) {
     const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
     const IdxT *col_idx = static_cast<const IdxT *>(g->col_idx);
@@ -903,6 +910,8 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         a.local_of = local_of;
         a.bitmap = ctx->bitmap;
         a.layer_hash = host_mix64(seed_hash ^ uint64_t(l));
+        a.seed_dev = seed_dev;
+        a.layer = l;
         a.fanout = k;
         a.force_slow = ctx->force_slow_select ? 1 : 0;
         a.heavy_degree = heavy_degree;
@@ -963,13 +972,13 @@ int launch_scan_tiles(mqg_ctx *ctx, int32_t *vals, int64_t n, const int64_t *add
     return MQG_OK;
 }
 
-int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds,
-                      const int32_t *fanouts, int32_t L, uint64_t rng_seed, mqg_block *blocks, hipStream_t s) {
+int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *fanouts,
+                      int32_t L, uint64_t rng_seed, const uint64_t *seed_dev, mqg_block *blocks, hipStream_t s) {
     const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-    if (p64 && i64) return sample_blocks_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
-    if (p64 && !i64) return sample_blocks_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
-    if (!p64 && i64) return sample_blocks_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
-    return sample_blocks_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, fanouts, L, rng_seed, blocks, s);
+    if (p64 && i64) return sample_blocks_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
+    if (p64 && !i64) return sample_blocks_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
+    if (!p64 && i64) return sample_blocks_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
+    return sample_blocks_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
 }
 
 // cache == nullptr switches the priority off; otherwise the membership bitmap is (re)built from cache->slot_of

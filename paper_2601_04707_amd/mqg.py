@@ -31,7 +31,7 @@ EXPORTS = [
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
     "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
-    "mqg_select_smallest_keys",
+    "mqg_select_smallest_keys", "mqg_sample_blocks_seed_dev",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -108,6 +108,9 @@ lib.mqg_sample_layerwise.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, cty
 MQG_LAYERWISE_LADIES, MQG_LAYERWISE_FASTGCN = 0, 1
 lib.mqg_select_smallest_keys.restype = ctypes.c_int
 lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
+lib.mqg_sample_blocks_seed_dev.restype = ctypes.c_int
+lib.mqg_sample_blocks_seed_dev.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, _vp,
+                                           ctypes.POINTER(CBlock), _vp]
 lib.mqg_queue_size.argtypes = [ctypes.c_double, ctypes.c_double, _i64, _i64, _i32, _i64, ctypes.POINTER(_i64),
                                ctypes.POINTER(_i64)]
 
@@ -330,6 +333,16 @@ def mqg_sample_blocks(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: 
     ctx.check(lib.mqg_sample_blocks(ctx.h, ctypes.byref(graph.c), seeds.data_ptr(), seeds.numel(), arr,
                                     len(fanouts), ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF), blocks.c,
                                     _stream(stream)))
+
+
+def mqg_sample_blocks_seed_dev(ctx: Context, graph: Graph, seeds: torch.Tensor, fanouts: Sequence[int],
+                               rng_seed_dev: torch.Tensor, blocks: Blocks, stream=None) -> None:
+    """As mqg_sample_blocks, the seed read from a one-element device int64 tensor at run time."""
+    assert seeds.is_cuda and seeds.dtype == graph.idx_dtype and seeds.is_contiguous()
+    assert rng_seed_dev.is_cuda and rng_seed_dev.dtype == torch.int64 and rng_seed_dev.numel() >= 1
+    arr = (_i32 * len(fanouts))(*fanouts)
+    ctx.check(lib.mqg_sample_blocks_seed_dev(ctx.h, ctypes.byref(graph.c), seeds.data_ptr(), seeds.numel(), arr,
+                                             len(fanouts), rng_seed_dev.data_ptr(), blocks.c, _stream(stream)))
 
 
 def mqg_sample_layerwise(ctx: Context, graph: Graph, seeds: torch.Tensor, layer_sizes: Sequence[int], rng_seed: int,
