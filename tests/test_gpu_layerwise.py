@@ -217,3 +217,36 @@ def test_selection_step_with_many_equal_keys(mqg, n, k, distinct):
     want = np.zeros(n, dtype=bool)
     want[order[:min(k, n)]] = True
     assert np.array_equal(got.cpu().numpy(), want)
+
+
+def test_samplers_do_not_need_sorted_adjacency_rows(mqg):
+    """Rows in arbitrary order (the generators emit ascending rows; nothing in the library may rely
+    on it): node-wise, cache-prioritised and layer-wise sampling against the oracle."""
+    rp, ci = hub_graph(n=6000, edges=200_000, max_degree=1500)
+    n = rp.numel() - 1
+    rng = np.random.default_rng(0)
+    ci_np = ci.numpy().copy()
+    rp_np = rp.numpy()
+    for v in range(n):
+        rng.shuffle(ci_np[rp_np[v]:rp_np[v + 1]])
+    assert not np.all(np.diff(ci_np[rp_np[100]:rp_np[101]]) > 0) or rp_np[101] - rp_np[100] < 3
+    g = mqg.Graph(to_dev(rp), to_dev(torch.from_numpy(ci_np)))
+    fanouts, sizes = [12, 6], [200, 150]
+    ctx = mqg.Context(g, 100, fanouts)
+    blocks = mqg.Blocks(g, 100, fanouts)
+    lw = mqg.LayerwiseBlocks(g, 100, sizes)
+    feats = synth.node_features(n, 4, seed=2).pin_memory()
+    cache = mqg.Cache(g, feats, n // 6)
+    mqg.mqg_build_cache(ctx, g, cache)
+    torch.cuda.synchronize()
+    slot_of = cache.slot_of.cpu().numpy()
+    seeds = synth.seed_batches(n, 100, 1, seed=8)[0]
+    assert_blocks_equal(hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 4),
+                        oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), fanouts, 4))
+    ctx.set_sampling_priority(cache)
+    assert_blocks_equal(hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 4),
+                        oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), fanouts, 4, prio_slot_of=slot_of))
+    ctx.set_sampling_priority(None)
+    for method, fg in ((mqg.MQG_LAYERWISE_LADIES, False), (mqg.MQG_LAYERWISE_FASTGCN, True)):
+        assert_same(run_layerwise(mqg, ctx, g, lw, seeds, sizes, 4, method=method),
+                    oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 4, fastgcn=fg))
