@@ -84,7 +84,9 @@ def _load():
     lib.orc_ladies_probabilities.restype = None
     lib.orc_ladies_probabilities.argtypes = [vp, vp, i64, vp, i64, vp]
     lib.orc_ladies_block.restype = i64
-    lib.orc_ladies_block.argtypes = [vp, vp, i64, vp, i64, i64, i64, u64, ctypes.c_int, ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]
+    lib.orc_ladies_block.argtypes = [vp, vp, i64, vp, i64, i64, i64, u64, ctypes.c_int, ctypes.c_int, ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]
+    lib.orc_debias_coefficients.restype = None
+    lib.orc_debias_coefficients.argtypes = [vp, i64, i64, vp]
     lib.orc_exp_ticket.restype = u64
     lib.orc_exp_ticket.argtypes = [u64]
     lib.orc_build_cache_drawn_by_score.restype = ctypes.c_int
@@ -292,6 +294,14 @@ class WeightedBlock:
         return int(self.indices.shape[0])
 
 
+def debias_coefficients(p_drawn, population: int) -> np.ndarray:
+    """Eq. 12: coefficients of the items drawn without replacement, in draw order."""
+    p = np.ascontiguousarray(p_drawn, dtype=np.float64)
+    beta = np.zeros(max(1, p.shape[0]), dtype=np.float64)
+    _load().orc_debias_coefficients(_p(p), p.shape[0], population, _p(beta))
+    return beta[:p.shape[0]]
+
+
 def ladies_probabilities(row_ptr, col_idx, dst=None) -> np.ndarray:
     """Eq. 7 for the rows dst; dst=None: all rows (FastGCN's batch-independent probabilities)."""
     rp, ci = _i64(row_ptr), _i64(col_idx)
@@ -306,7 +316,7 @@ def ladies_probabilities(row_ptr, col_idx, dst=None) -> np.ndarray:
 
 
 def ladies_blocks(row_ptr, col_idx, seeds, layer_sizes: Sequence[int], rng_seed: int, normalise: bool = True,
-                  want_mass: bool = False, fastgcn: bool = False) -> List[WeightedBlock]:
+                  want_mass: bool = False, fastgcn: bool = False, debias: bool = False) -> List[WeightedBlock]:
     """LADIES mini-batch: blocks[L-1] has the seeds as rows; layer_sizes[l] nodes are drawn as the
     sources of blocks[l], which are the rows of blocks[l-1]."""
     rp, ci, dst = _i64(row_ptr), _i64(col_idx), _i64(seeds)
@@ -325,7 +335,8 @@ def ladies_blocks(row_ptr, col_idx, seeds, layer_sizes: Sequence[int], rng_seed:
         ew = np.empty(cap_nnz, dtype=np.float64)
         mass = np.zeros(max(n, 1), dtype=np.uint64) if want_mass else None
         ns = lib.orc_ladies_block(_p(rp), _p(ci), n, _p(dst), nd, s, l, ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF),
-                                  1 if normalise else 0, 1 if fastgcn else 0, cap_src, cap_nnz, _p(src), _p(indptr),
+                                  1 if normalise else 0, 1 if fastgcn else 0, 1 if debias else 0, cap_src, cap_nnz,
+                                  _p(src), _p(indptr),
                                   _p(idx), _p(ew),
                                   None if mass is None else _p(mass))
         if ns < 0:

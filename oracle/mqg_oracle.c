@@ -827,6 +827,31 @@ void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, in
         for (int64_t i = 0; i < num_nodes; ++i) p[i] /= total;
 }
 
+/*
+ * Debiased coefficients for draws without replacement (the recursion printed
+ * as Eq. 12, Sec. III-B "Calibrate and Debias LS"): with the items in the
+ * order they were drawn, p[i] the probability of the i-th drawn item in the
+ * whole population of n items (sum over the population = 1),
+ *   Y_0 = 0,  Y_{i+1} = (1 - a_{i+1}) Y_i + a_{i+1} Pi_{i+1},
+ *   Pi_{i+1} = sum_{j drawn before} X_j + X_{i+1} / p^i_{i+1},
+ *   a_1 = 1,  a_{k+1} = n / ((n - k)(k + 1)),
+ * where p^i_{i+1} = p[i] / (1 - sum of the p drawn before) is the probability
+ * of that draw given the earlier ones.  Y_s = sum_j beta[j] X_j estimates the
+ * total sum_j X_j over the population without bias; beta is what is returned.
+ * The recursion is carried out literally, O(s^2).
+ */
+void orc_debias_coefficients(const double *p, int64_t s, int64_t n, double *beta)
+{
+    double drawn = 0.0;
+    for (int64_t i = 0; i < s; ++i) {
+        double alpha = (double)n / ((double)(n - i) * (double)(i + 1));
+        for (int64_t j = 0; j < i; ++j) beta[j] = (1.0 - alpha) * beta[j] + alpha;
+        double p_cond = p[i] / (1.0 - drawn);
+        beta[i] = alpha / p_cond;
+        drawn += p[i];
+    }
+}
+
 /* Domain tag of the layer-wise draw at block `layer` (the node-wise draw uses `layer` itself). */
 #define ORC_LAYERWISE_TAG 64
 
@@ -860,14 +885,19 @@ void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, in
  * draw is without replacement here too, and the weights are the importance
  * weights P_vu / (s p_u) of the estimator the paper states before Eq. 12).
  *
+ * debias != 0 (the "+debias" variants, Eq. 12): a drawn node's column is scaled
+ * by its debiased coefficient beta (orc_debias_coefficients over the drawn
+ * nodes in the order of the race, population = the candidates) instead of
+ * 1 / (s p): weight = P_vi * beta_i.  When every candidate is drawn beta is 1.
+ *
  * mass_out (may be NULL): num_nodes masses.  Returns the number of sources,
  * -2 when cap_nnz or cap_src is too small or memory runs out.
  */
 int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
                          const int64_t *dst, int64_t num_dst, int64_t s_layer, int64_t layer,
-                         uint64_t rng_seed, int normalise, int fastgcn, int64_t cap_src,
-                         int64_t cap_nnz, int64_t *src, int64_t *indptr, int32_t *indices,
-                         double *edge_w, uint64_t *mass_out)
+                         uint64_t rng_seed, int normalise, int fastgcn, int debias,
+                         int64_t cap_src, int64_t cap_nnz, int64_t *src, int64_t *indptr,
+                         int32_t *indices, double *edge_w, uint64_t *mass_out)
 {
     size_t cnt = (size_t)(num_nodes > 0 ? num_nodes : 1);
     uint64_t *mass = calloc(cnt, sizeof *mass);
@@ -902,6 +932,27 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
     for (int64_t i = 0; i < num_nodes; ++i) pos[i] = -1;
     for (int64_t r = 0; r < num_src; ++r) pos[src[r]] = r;
 
+    double *beta_of_pos = NULL;
+    if (debias) {
+        size_t ns = (size_t)(num_src > 0 ? num_src : 1);
+        double *p_drawn = malloc(ns * sizeof *p_drawn);
+        double *beta = malloc(ns * sizeof *beta);
+        beta_of_pos = malloc(ns * sizeof *beta_of_pos);
+        if (!p_drawn || !beta || !beta_of_pos) { free(p_drawn); free(beta); free(beta_of_pos); free(mass); free(pos); free(cand); return -2; }
+        if (num_src == num_cand) {
+            for (int64_t r = 0; r < num_src; ++r) beta_of_pos[r] = 1.0;
+        } else {
+            for (int64_t r = 0; r < num_src; ++r) {              /* cand[0..num_src) is in draw order */
+                int64_t i = cand[r].id;
+                p_drawn[r] = ((double)mass[i] / (double)(row_ptr[i + 1] - row_ptr[i] + 1)) / q_total;
+            }
+            orc_debias_coefficients(p_drawn, num_src, num_cand, beta);
+            for (int64_t r = 0; r < num_src; ++r) beta_of_pos[pos[cand[r].id]] = beta[r];
+        }
+        free(p_drawn);
+        free(beta);
+    }
+
     int64_t nnz = 0;
     indptr[0] = 0;
     for (int64_t t = 0; t < num_dst; ++t) {
@@ -911,12 +962,12 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
         for (int64_t e = row_ptr[v] - 1; e < row_ptr[v + 1]; ++e) {      /* e == row_ptr[v] - 1: the self edge */
             int64_t i = e < row_ptr[v] ? v : col_idx[e];
             if (pos[i] < 0) continue;
-            if (nnz >= cap_nnz) { free(mass); free(pos); free(cand); return -2; }
+            if (nnz >= cap_nnz) { free(mass); free(pos); free(cand); free(beta_of_pos); return -2; }
             double di = (double)(row_ptr[i + 1] - row_ptr[i] + 1);
             double P_vi = 1.0 / sqrt(dv * di);
             double p_i = ((double)mass[i] / di) / q_total;
             indices[nnz] = (int32_t)pos[i];
-            edge_w[nnz] = P_vi / ((double)num_src * p_i);
+            edge_w[nnz] = debias ? P_vi * beta_of_pos[pos[i]] : P_vi / ((double)num_src * p_i);
             ++nnz;
         }
         if (normalise) {
@@ -929,5 +980,6 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
     free(mass);
     free(pos);
     free(cand);
+    free(beta_of_pos);
     return num_src;
 }

@@ -930,3 +930,80 @@ def test_fastgcn_probabilities_and_batch_independent_draw():
         ids = raw.src_ids[raw.indices[e]]
         assert np.allclose(raw.edge_w[e] * 30 * want[ids], P[v, ids], rtol=1e-9)
         assert set(ids.tolist()) == (set(ci[rp[v]:rp[v + 1]].tolist()) | {v}) & set(raw.src_ids.tolist())
+
+
+# ------------------------------------------------------------------------- debiased coefficients (Eq. 12)
+
+def test_debias_coefficients_closed_forms():
+    n = 9
+    for s in range(1, n + 1):                                    # equal probabilities: simple random sampling, n / s each
+        beta = oracle.debias_coefficients(np.full(s, 1.0 / n), n)
+        assert np.allclose(beta, n / s, rtol=1e-12), s
+    rng = np.random.default_rng(61)
+    p = rng.random(7)
+    p /= p.sum()
+    beta = oracle.debias_coefficients(p[rng.permutation(7)], 7)   # everything drawn: the plain sum
+    assert np.allclose(beta, 1.0, rtol=1e-9)
+    assert oracle.debias_coefficients(p[:1], 7)[0] == pytest.approx(1.0 / p[0])   # one draw: X / p
+
+
+def test_debias_estimator_is_unbiased_over_all_ordered_draws():
+    """Brute force: every ordered sample of s of n items with its successive-sampling probability;
+    the expectation of sum_j beta_j X_j is the population total, for unequal probabilities."""
+    import itertools
+    p = np.array([0.05, 0.1, 0.15, 0.3, 0.4])
+    X = np.array([3.0, -1.0, 7.0, 2.5, -4.0])
+    n = 5
+    for s in (1, 2, 3, 4):
+        expect = 0.0
+        total_prob = 0.0
+        for order in itertools.permutations(range(n), s):
+            prob, rest = 1.0, 1.0
+            for i in order:
+                prob *= p[i] / rest
+                rest -= p[i]
+            beta = oracle.debias_coefficients(p[list(order)], n)
+            expect += prob * float(beta @ X[list(order)])
+            total_prob += prob
+        assert abs(total_prob - 1.0) < 1e-12
+        assert abs(expect - X.sum()) < 1e-10, s
+    # the plain importance weights 1 / (s p) are biased under the same draws (what Eq. 12 repairs)
+    s = 3
+    expect = 0.0
+    for order in itertools.permutations(range(n), s):
+        prob, rest = 1.0, 1.0
+        for i in order:
+            prob *= p[i] / rest
+            rest -= p[i]
+        expect += prob * float((X[list(order)] / (s * p[list(order)])).sum())
+    assert abs(expect - X.sum()) > 0.1
+
+
+def test_debiased_layerwise_blocks():
+    rp, ci = tiny_graph(400, 6000, seed=62)
+    n = len(rp) - 1
+    P = dense_gcn_operator(rp, ci)
+    seeds = np.random.default_rng(6).choice(n, 20, replace=False)
+    for fastgcn in (False, True):
+        plain = oracle.ladies_blocks(rp, ci, seeds, [30], 3, normalise=False, fastgcn=fastgcn, want_mass=True)[0]
+        deb = oracle.ladies_blocks(rp, ci, seeds, [30], 3, normalise=False, fastgcn=fastgcn, debias=True)[0]
+        assert np.array_equal(plain.src_ids, deb.src_ids) and np.array_equal(plain.indices, deb.indices)
+        # restated: race order, probabilities, coefficients
+        deg1 = (np.diff(rp) + 1).astype(np.float64)
+        cand = np.nonzero(plain.mass)[0]
+        t = np.array([oracle.exp_ticket(oracle.key(3, 64, int(i), 0)) for i in cand], dtype=np.float64)
+        key = (t * deg1[cand]) / plain.mass[cand].astype(np.float64)
+        order = cand[np.lexsort((cand, key))[:30]]
+        q = plain.mass[cand].astype(np.float64) / deg1[cand]
+        p_of = dict(zip(cand.tolist(), (q / q.sum()).tolist()))
+        beta = oracle.debias_coefficients([p_of[int(i)] for i in order], len(cand))
+        beta_of = dict(zip(order.tolist(), beta.tolist()))
+        for r, v in enumerate(seeds):
+            e = slice(deb.indptr[r], deb.indptr[r + 1])
+            ids = deb.src_ids[deb.indices[e]]
+            assert np.allclose(deb.edge_w[e], [P[v, i] * beta_of[int(i)] for i in ids], rtol=1e-9)
+    # every candidate drawn: coefficients 1, the block is P restricted to the rows
+    allc = oracle.ladies_blocks(rp, ci, seeds, [10 ** 6], 3, normalise=False, debias=True)[0]
+    for r, v in enumerate(seeds):
+        e = slice(allc.indptr[r], allc.indptr[r + 1])
+        assert np.allclose(allc.edge_w[e], P[v, allc.src_ids[allc.indices[e]]], rtol=1e-12)
