@@ -316,11 +316,19 @@ int mqg_sample_blocks_seed_dev(mqg_ctx *ctx, const mqg_graph *g, const void *see
  * context - so every node is a candidate and the draw does not depend on the
  * mini-batch; everything else is the same (drawn without replacement,
  * importance weights P_vu / (s p_u)).
+ * method | MQG_LAYERWISE_DEBIAS (the "+debias" variants, paper Eq. 12): a drawn
+ * node's column is scaled by its debiased coefficient beta instead of 1 / (s p),
+ * edge_w = P_vi * beta_i (then the row normalisation, if asked for).  With the
+ * drawn nodes in the order of the race (ascending (key, id)), n candidates,
+ * a_r = n / ((n - r)(r + 1)) for the r-th draw (r from 0) and p_r = q_r / sum_j
+ * q_j: the coefficient of a node is a_r (1 - p_0 - ... - p_{r-1}) / p_r when it
+ * is drawn and becomes (1 - a_u) beta + a_u at every later draw u; when every
+ * candidate is drawn, beta = 1.  Computed in double.
  * The first call allocates context scratch of about 20 bytes per graph node
  * (8 more for FastGCN) and synchronises the stream once.  Feed the blocks to
  * mqg_weighted_aggregate with self_w == NULL.
  */
-typedef enum { MQG_LAYERWISE_LADIES = 0, MQG_LAYERWISE_FASTGCN = 1 } mqg_layerwise_method;
+typedef enum { MQG_LAYERWISE_LADIES = 0, MQG_LAYERWISE_FASTGCN = 1, MQG_LAYERWISE_DEBIAS = 2 } mqg_layerwise_method;
 
 int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
                          const int32_t *layer_sizes, int32_t num_layers, uint64_t rng_seed,

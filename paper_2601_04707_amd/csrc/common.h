@@ -48,6 +48,9 @@ struct LayerwiseScratch {
     double *q_total = nullptr;
     int64_t *seeds_copy = nullptr;       // [rows_cap] the checked seeds
     int32_t *flags = nullptr;
+    uint64_t *dkey = nullptr;            // [rows_cap] race keys of the drawn nodes (debiased coefficients)
+    double *dq = nullptr, *beta = nullptr;
+    int32_t *order = nullptr;            // [rows_cap] source positions in draw order
     unsigned long long *fg_mass = nullptr;     // [num_nodes] masses over all rows of the graph (FastGCN)
     bool fg_ready = false;
     int64_t rows_cap = 0;

@@ -279,10 +279,13 @@ k_lw_zero_i32(int32_t *__restrict__ p, int64_t n) {
 }
 
 // Eq. 8 with p_i = q_i / q_total, q_i = mass_i / di: P_vi / (s p_i) = (q_total / s) * di / (mass_i sqrt(dv di))
+// With debiased coefficients (paper Eq. 12) the column of the drawn node at source position li is scaled
+// by beta[li] instead: P_vi * beta.
 template <typename PtrT>
 __device__ __forceinline__ double lw_raw_weight(const PtrT *__restrict__ row_ptr, const unsigned long long *__restrict__ mass,
-                                                double scale, double dv, int64_t i) {
+                                                double scale, double dv, int64_t i, const double *__restrict__ beta, int32_t li) {
     const double di = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
+    if (beta) return beta[li] / sqrt(dv * di);
     return scale * di / (static_cast<double>(mass[i]) * sqrt(dv * di));
 }
 
@@ -292,7 +295,8 @@ template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
            const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
-           const double *__restrict__ q_total, int32_t *__restrict__ counts, double *__restrict__ psum) {
+           const double *__restrict__ q_total, const double *__restrict__ beta, int32_t *__restrict__ counts,
+           double *__restrict__ psum) {
     const int lane = lane_id();
     const int64_t n = sizes[0] * kRowChunks;
     const double scale = *q_total / static_cast<double>(sizes[1]);
@@ -309,7 +313,7 @@ k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, c
         double acc = 0.0;
         if (c == 0 && local_of[v] >= 0) {
             cnt = 1;
-            if (lane == 0) acc = lw_raw_weight(row_ptr, mass, scale, dv, v);
+            if (lane == 0) acc = lw_raw_weight(row_ptr, mass, scale, dv, v, beta, local_of[v]);
         }
         int64_t jb, je;
         chunk_range(d, c, &jb, &je);
@@ -318,8 +322,9 @@ k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, c
             bool in = false;
             if (j < je) {
                 const int64_t i = static_cast<int64_t>(col_idx[start + j]);
-                in = local_of[i] >= 0;
-                if (in) acc += lw_raw_weight(row_ptr, mass, scale, dv, i);
+                const int32_t li = local_of[i];
+                in = li >= 0;
+                if (in) acc += lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li);
             }
             cnt += popc64(ballot64(in));
         }
@@ -350,8 +355,9 @@ template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
           const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
-          const double *__restrict__ q_total, const int32_t *__restrict__ offs, const double *__restrict__ psum,
-          int32_t *__restrict__ indices, float *__restrict__ edge_w, int normalise, int64_t cap_nnz) {
+          const double *__restrict__ q_total, const double *__restrict__ beta, const int32_t *__restrict__ offs,
+          const double *__restrict__ psum, int32_t *__restrict__ indices, float *__restrict__ edge_w, int normalise,
+          int64_t cap_nnz) {
     const int lane = lane_id();
     const int64_t n = sizes[0] * kRowChunks;
     const double scale = *q_total / static_cast<double>(sizes[1]);
@@ -377,7 +383,7 @@ k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
             if (self_pos >= 0) {
                 if (lane == 0 && pos < cap_nnz) {
                     indices[pos] = self_pos;
-                    edge_w[pos] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, v) * inv_sum);
+                    edge_w[pos] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, v, beta, self_pos) * inv_sum);
                 }
                 pos += 1;
             }
@@ -397,11 +403,80 @@ k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
                 const int64_t p = pos + popc64(m & lanes_below(lane));
                 if (p < cap_nnz) {
                     indices[p] = li;
-                    edge_w[p] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, i) * inv_sum);
+                    edge_w[p] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li) * inv_sum);
                 }
             }
             pos += popc64(m);
         }
+    }
+}
+
+// ---- debiased coefficients (paper Eq. 12) of the drawn nodes
+
+// race key and q = mass / (deg + 1) of every drawn node, by source position
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_lw_drawn_keys(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes,
+                const unsigned long long *__restrict__ mass, uint64_t tag_hash, uint64_t *__restrict__ dkey,
+                double *__restrict__ dq) {
+    const int64_t ns = sizes[1];
+    const int64_t pos = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (pos >= ns) return;
+    const int64_t i = static_cast<int64_t>(src_ids[pos]);
+    const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
+    const double m = static_cast<double>(mass[i]);
+    const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
+    dkey[pos] = static_cast<uint64_t>(__double_as_longlong((ticket * deg1) / m));
+    dq[pos] = m / deg1;
+}
+
+// order[r] = source position of the r-th drawn node: the race order is ascending (key, id), and
+// positions ascend with the ids.  Every thread counts the drawn nodes ahead of its own.
+__global__ void __launch_bounds__(kBlock)
+k_lw_draw_order(const uint64_t *__restrict__ dkey, const int64_t *__restrict__ sizes, int32_t *__restrict__ order) {
+    const int64_t ns = sizes[1];
+    const int64_t pos = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (pos >= ns) return;
+    const uint64_t k = dkey[pos];
+    int rank = 0;
+    for (int64_t t = 0; t < ns; ++t) {
+        const uint64_t o = dkey[t];
+        rank += (o < k || (o == k && t < pos)) ? 1 : 0;
+    }
+    order[rank] = static_cast<int32_t>(pos);
+}
+
+// The recursion of Eq. 12 in closed form.  With a_r = n / ((n - r)(r + 1)) (r = 0 for the first draw)
+// and b0_r = a_r (1 - sum of the p drawn before) / p_r the coefficient an item gets when it is
+// drawn, later steps turn a coefficient b into (1 - a_u) b + a_u, so the final one is
+//   beta_r = b0_r G_r + H_r,  G_r = prod_{u > r} (1 - a_u),  H_r = sum_{u > r} a_u G_u,
+// accumulated from the last draw backwards.  One thread; a layer has a few thousand draws at most.
+// Every candidate drawn: beta = 1.
+__global__ void __launch_bounds__(kBlock)
+k_lw_debias(const int32_t *__restrict__ order, const double *__restrict__ dq, const double *__restrict__ q_total,
+            const int64_t *__restrict__ sizes, const int64_t *__restrict__ n_cand, double *__restrict__ b0,
+            double *__restrict__ beta) {
+    const int64_t s = sizes[1];
+    const int64_t n = *n_cand;
+    if (s >= n) {
+        for (int64_t r = threadIdx.x; r < s; r += kBlock) beta[r] = 1.0;
+        return;
+    }
+    if (threadIdx.x != 0) return;
+    const double total = *q_total;
+    double drawn = 0.0;
+    for (int64_t r = 0; r < s; ++r) {
+        const double p = dq[order[r]] / total;
+        const double alpha = static_cast<double>(n) / (static_cast<double>(n - r) * static_cast<double>(r + 1));
+        b0[r] = alpha / (p / (1.0 - drawn));
+        drawn += p;
+    }
+    double G = 1.0, H = 0.0;
+    for (int64_t r = s - 1; r >= 0; --r) {
+        beta[order[r]] = b0[r] * G + H;
+        const double alpha = static_cast<double>(n) / (static_cast<double>(n - r) * static_cast<double>(r + 1));
+        H += alpha * G;
+        G *= 1.0 - alpha;
     }
 }
 
@@ -434,7 +509,7 @@ bool dev_alloc(T **p, int64_t count) {
 void free_layerwise_scratch(mqg_ctx *ctx) {
     LayerwiseScratch &w = ctx->lw;
     void *ptrs[] = {w.mass, w.cand, w.key64, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
-                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum, w.fg_mass};
+                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum, w.fg_mass, w.dkey, w.dq, w.order, w.beta};
     for (void *p : ptrs) (void)hipFree(p);
     w = LayerwiseScratch{};
 }
@@ -453,7 +528,8 @@ static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t 
               dev_alloc(&w.scan_tiles, ceil_div(scan_len, kScanTile) + 2) && dev_alloc(&w.q_part, ceil_div(n, kBlock) + 1) &&
               dev_alloc(&w.counters, 4) && dev_alloc(&w.q_total, 1) && dev_alloc(&w.seeds_copy, rows_cap) && dev_alloc(&w.flags, 1) &&
               dev_alloc(&w.sel_state, 18) && dev_alloc(&w.sel_hist, 8 * 256) && dev_alloc(&w.chunk_offs, chunks + 1) &&
-              dev_alloc(&w.chunk_sum, chunks);
+              dev_alloc(&w.chunk_sum, chunks) && dev_alloc(&w.dkey, rows_cap) && dev_alloc(&w.dq, rows_cap) &&
+              dev_alloc(&w.order, rows_cap) && dev_alloc(&w.beta, rows_cap);
     if (ok) ok = hipMemset(w.mass, 0, static_cast<size_t>(n) * sizeof(unsigned long long)) == hipSuccess &&
                  hipMemset(w.flags, 0, sizeof(int32_t)) == hipSuccess && hipDeviceSynchronize() == hipSuccess;
     if (!ok) {
@@ -466,7 +542,7 @@ static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t 
 
 template <typename PtrT, typename IdxT>
 static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
-                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, bool fastgcn,
+                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, bool fastgcn, bool debias,
                                  mqg_block *blocks, float *const *edge_w, hipStream_t s) {
     LayerwiseScratch &w = ctx->lw;
     const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
@@ -533,6 +609,17 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         MQG_LAUNCH(ctx, "k_lw_emit", s,
                    (k_lw_emit<IdxT><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, src_ids, ctx->local_of, &b.sizes[1],
                                                                  l > 0 ? &blocks[l - 1].sizes[0] : nullptr)));
+        const double *beta = nullptr;
+        if (debias) {
+            const int64_t src_cap = std::min<int64_t>(n, layer_sizes[l]);
+            const int sgrid = static_cast<int>(std::max<int64_t>(1, ceil_div(src_cap, kBlock)));
+            MQG_LAUNCH(ctx, "k_lw_drawn_keys", s,
+                       (k_lw_drawn_keys<PtrT, IdxT><<<sgrid, kBlock, 0, s>>>(row_ptr, src_ids, b.sizes, mass, tag_hash, w.dkey, w.dq)));
+            MQG_LAUNCH(ctx, "k_lw_draw_order", s, (k_lw_draw_order<<<sgrid, kBlock, 0, s>>>(w.dkey, b.sizes, w.order)));
+            MQG_LAUNCH(ctx, "k_lw_debias", s,
+                       (k_lw_debias<<<1, kBlock, 0, s>>>(w.order, w.dq, w.q_total, b.sizes, n_cand, w.chunk_sum, w.beta)));
+            beta = w.beta;
+        }
         // rows: per (row, chunk) counts and weight sums, one scan, then the edges
         const int64_t chunks_cap = rows_cap * kRowChunks;
         const int chunk_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(chunks_cap, kWavesPerBlock)), 256 * 64));
@@ -540,7 +627,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                    (k_lw_zero_i32<<<static_cast<int>(ceil_div(chunks_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, chunks_cap + 1)));
         MQG_LAUNCH(ctx, "k_lw_count", s,
                    (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
-                                                                         w.chunk_offs, w.chunk_sum)));
+                                                                         beta, w.chunk_offs, w.chunk_sum)));
         rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
         if (rc != MQG_OK) return rc;
         MQG_LAUNCH(ctx, "k_lw_indptr", s,
@@ -548,7 +635,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                                                                                                     l == L - 1 ? w.flags : nullptr)));
         MQG_LAUNCH(ctx, "k_lw_fill", s,
                    (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
-                                                                        w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
+                                                                        beta, w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
                                                                         b.cap_nnz)));
         if (l == L - 1) MQG_LAUNCH(ctx, "k_lw_clear_flags", s, (k_lw_clear_flags<<<1, 64, 0, s>>>(w.flags)));
         const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
@@ -580,7 +667,8 @@ int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int6
 int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
                          int32_t L, uint64_t rng_seed, int32_t normalise, int32_t method, mqg_block *blocks, float *const *edge_w,
                          hipStream_t s) {
-    const bool fg = method == MQG_LAYERWISE_FASTGCN;
+    const bool fg = (method & MQG_LAYERWISE_FASTGCN) != 0;
+    const bool db = (method & MQG_LAYERWISE_DEBIAS) != 0;
     int64_t rows_cap = num_seeds;
     for (int l = 0; l < L; ++l) rows_cap = std::max<int64_t>(rows_cap, std::min<int64_t>(ctx->num_nodes, layer_sizes[l]));
     int rc = ensure_layerwise_scratch(ctx, rows_cap, s);
@@ -596,10 +684,10 @@ int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, in
         ctx->lw.fg_ready = false;
     }
     const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
-    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
-    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
-    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, blocks, edge_w, s);
+    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
+    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
+    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
+    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
 }
 
 }  // namespace mqg

@@ -101,6 +101,28 @@ def test_fastgcn_parity_and_alternation_with_ladies(mqg, ptr, idx, sizes):
         assert_same(got, oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 56))
 
 
+@pytest.mark.parametrize("ptr,idx", [(torch.int32, torch.int32), (torch.int64, torch.int64)])
+@pytest.mark.parametrize("sizes", [[64, 128], [512, 512], [100, 50, 30], [3000]])
+@pytest.mark.parametrize("fastgcn", [False, True])
+def test_debiased_variants_parity(mqg, ptr, idx, sizes, fastgcn):
+    rp, ci = hub_graph(ptr=ptr, idx=idx)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    batch = 193
+    ctx = mqg.Context(g, batch, [2] * len(sizes))
+    blocks = mqg.LayerwiseBlocks(g, batch, sizes)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    seeds = synth.seed_batches(n, batch, 1, seed=7)[0]
+    method = mqg.MQG_LAYERWISE_DEBIAS | (mqg.MQG_LAYERWISE_FASTGCN if fastgcn else 0)
+    for normalise in (False, True):
+        got = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 91, normalise, method=method)
+        want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 91, normalise=normalise, fastgcn=fastgcn, debias=True)
+        assert_same(got, want)
+    plain = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 91, normalise=False, fastgcn=fastgcn)
+    want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 91, normalise=False, fastgcn=fastgcn, debias=True)
+    assert not np.allclose(plain[-1].edge_w, want[-1].edge_w, rtol=1e-5)      # the coefficients do differ from 1 / (s p)
+
+
 def test_layerwise_small_graph_all_candidates_and_degenerate_inputs(mqg):
     rp = torch.tensor([0, 0, 2, 3, 3, 6], dtype=torch.int64)      # nodes 0 and 3 have no neighbours
     ci = torch.tensor([2, 4, 1, 0, 1, 2], dtype=torch.int64)
@@ -116,6 +138,9 @@ def test_layerwise_small_graph_all_candidates_and_degenerate_inputs(mqg):
                 assert_same(got, want)
                 got = run_layerwise(mqg, ctx, g, blocks, s, sizes, 3, normalise, method=mqg.MQG_LAYERWISE_FASTGCN)
                 want = oracle.ladies_blocks(rp.numpy(), ci.numpy(), s.numpy(), sizes, 3, normalise=normalise, fastgcn=True)
+                assert_same(got, want)
+                got = run_layerwise(mqg, ctx, g, blocks, s, sizes, 3, normalise, method=mqg.MQG_LAYERWISE_DEBIAS)
+                want = oracle.ladies_blocks(rp.numpy(), ci.numpy(), s.numpy(), sizes, 3, normalise=normalise, debias=True)
                 assert_same(got, want)
     # an id outside the graph is replaced by node 0 and flagged on the innermost block
     blocks = mqg.LayerwiseBlocks(g, 8, [4, 4])
