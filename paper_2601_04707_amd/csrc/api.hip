@@ -383,6 +383,8 @@ int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev
         if (!b.src_ids || !b.indptr || !b.indices || !b.sizes || !edge_w[l])
             return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: NULL block buffer");
         const int64_t src = std::min<int64_t>(g->num_nodes, layer_sizes[l]);
+        if (rows * (src + 1) >= (int64_t(1) << 31))         // edge positions are 32-bit: rows x drawn nodes bounds the edges
+            return fail(ctx, MQG_ERR_UNSUPPORTED, "mqg_sample_layerwise: block " + std::to_string(l) + " could hold 2^31 edges or more");
         if (b.cap_dst < rows || b.cap_src < src || b.cap_nnz < 0 || b.cap_nnz >= (int64_t(1) << 31))
             return fail(ctx, MQG_ERR_CAPACITY, "mqg_sample_layerwise: block " + std::to_string(l) + " needs cap_dst>=" +
                         std::to_string(rows) + " cap_src>=" + std::to_string(src) + " and 0 <= cap_nnz < 2^31");
