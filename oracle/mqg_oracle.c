@@ -41,7 +41,10 @@
  *                            sampler "prioritizes neighbors in the cache" so
  *                            that fewer distinct uncached nodes enter a
  *                            mini-batch.  Read as: a row's cached neighbours
- *                            are drawn before its uncached ones.
+ *                            are drawn before its uncached ones.  The paper
+ *                            prints no rule, so this function is "parity
+ *                            unpinned" against the paper; the reading itself
+ *                            is pinned by its invariants.
  *   - orc_ladies_probabilities / orc_ladies_block : Sec. III-B "Layer-wise
  *                            sampling", LADIES paragraph (Eq. 6-9): the nodes
  *                            of the next layer are drawn from the neighbours
