@@ -82,7 +82,13 @@ def main() -> int:
     t0 = time.time()
     rp, ci = synth.build_graph(w, seed=0, device=dev)
     n = rp.numel() - 1
-    feats = torch.empty((n, w.dim), dtype=w.feat_dtype).pin_memory()
+    # Host rows start on 64-byte boundaries when that costs at most 2 % more memory, otherwise on
+    # 16-byte boundaries: a row that starts inside a cache line makes the host link carry the
+    # unused part of its first and last line (measured on "medium": 2.41 instead of 2.54 ms/step).
+    host_row = (row_bytes + 63) // 64 * 64
+    if host_row > 1.02 * row_bytes:
+        host_row = (row_bytes + 15) // 16 * 16
+    feats = torch.empty((n, host_row // elt), dtype=w.feat_dtype).pin_memory()[:, :w.dim]
     synth.node_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev, out=feats)
     torch.cuda.synchronize()
     g = mqg.Graph(rp, ci)
@@ -451,8 +457,9 @@ def main() -> int:
     ca = torch.ones(1 << 27, dtype=torch.float32, device=dev)          # 512 MiB
     cb = torch.empty_like(ca)
     t_copy = timed(lambda: torch.mul(ca, 2.0, out=cb))
-    nb = min(feats.numel() * feats.element_size(), 1 << 29)
-    hsrc = feats.view(-1)[: nb // feats.element_size()]
+    hrows = max(1, min(n, (1 << 29) // (feats.stride(0) * feats.element_size())))
+    hsrc = torch.as_strided(feats, (hrows * feats.stride(0),), (1,))       # whole rows including any padding
+    nb = hsrc.numel() * feats.element_size()
     hdst = torch.empty_like(hsrc, device=dev)
     t_h2d = timed(lambda: hdst.copy_(hsrc, non_blocking=True))
     measured = {"hbm_read_plus_write_GBps": round(2 * ca.numel() * 4 / t_copy / 1e9, 1),
@@ -477,7 +484,7 @@ def main() -> int:
         "config": {"workload": f"{w.name}: Chung-Lu power-law graph, {n} nodes, {ci.numel()} directed edges, "
                                f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
                                f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({args.cache_policy}), "
-                               f"rest in pinned host memory",
+                               f"rest in pinned host memory ({feats.stride(0) * elt}-byte rows)",
                    "in_flight": nfl, "global_batch": w.batch, "dedup": args.dedup,
                    "sampling": "cached neighbours first" if args.prioritise_cache else "uniform",
                    "launch": "one recorded HIP graph per in-flight slot" if args.graph else "eager"},

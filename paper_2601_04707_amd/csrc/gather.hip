@@ -97,81 +97,97 @@ struct DirectRows {
 };
 
 constexpr int kRowUnroll = 4;                            // row loads in flight per lane (rows of up to 64 vectors)
-constexpr int kWideRows = 2;                             // rows a wavefront copies at a time (longer rows)
+// Longer rows: all 64 lanes walk WR rows at a time, NCH 64-vector chunks of each, so that up to
+// eight loads per lane are issued before the first store (a row's last, partial chunk rides along
+// instead of trailing alone).  NCH is the number of chunks a row needs, at most four; loads are
+// unconditional (an index past the row re-reads its last vector), only the stores are predicated.
+template <typename VecT, int NCH, int WR, typename Rows>
+__device__ __forceinline__ void copy_rows_wide(const Rows &rows, int64_t n, const char *__restrict__ src,
+                                               int64_t src_stride_bytes, char *__restrict__ dst,
+                                               int64_t dst_stride_bytes, int vecs) {
+    const int lane = lane_id();
+    const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
+    const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
+    for (int64_t r0 = wave0 * WR; r0 < n; r0 += nwaves * WR) {
+        const VecT *sp[WR];
+        VecT *dp[WR];
+        bool rok[WR];
+#pragma unroll
+        for (int q = 0; q < WR; ++q) {
+            const int64_t r = r0 + q;
+            rok[q] = r < n;
+            int64_t srow, drow;
+            rows.get(rok[q] ? r : n - 1, &srow, &drow);          // a row past the end re-reads the last one
+            sp[q] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes);
+            dp[q] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes);
+        }
+        for (int c0 = lane; c0 < vecs; c0 += NCH * kWave) {
+            VecT v[WR][NCH];
+#pragma unroll
+            for (int q = 0; q < WR; ++q)
+#pragma unroll
+                for (int k = 0; k < NCH; ++k) {
+                    const int c = c0 + k * kWave;
+                    v[q][k] = sp[q][c < vecs ? c : vecs - 1];
+                }
+#pragma unroll
+            for (int q = 0; q < WR; ++q)
+#pragma unroll
+                for (int k = 0; k < NCH; ++k) {
+                    const int c = c0 + k * kWave;
+                    if (rok[q] && c < vecs) dp[q][c] = v[q][k];
+                }
+        }
+    }
+}
 
-// Row copies by one wavefront (the grouped copy).  Rows of up to 64 vectors: the wavefront is split into 64/LPR
-// groups of LPR lanes (LPR = 2^log2_lpr >= vecs), every group copies one row per step and
-// kRowUnroll steps are in flight, so a wavefront moves 4*64/LPR short rows at a time.  Longer
-// rows: all 64 lanes walk two rows at a time, up to four vectors of each per lane in flight.
+// chunks per row and rows per wavefront of the long-row copy
+inline __host__ __device__ int wide_chunks(int vecs) { return vecs > 3 * kWave ? 4 : (vecs > 2 * kWave ? 3 : 2); }
+inline __host__ __device__ int wide_rows(int vecs) { return vecs > 2 * kWave ? 2 : 4; }
+
+// Row copies by one wavefront (the grouped copy).  Rows of up to 64 vectors: the wavefront is split
+// into 64/LPR groups of LPR lanes (LPR = 2^log2_lpr >= vecs), every group copies one row per step
+// and kRowUnroll steps are in flight, so a wavefront moves 4*64/LPR short rows at a time.  Longer
+// rows: copy_rows_wide.
 template <typename VecT, typename Rows>
 __device__ __forceinline__ void copy_rows(const Rows &rows, int64_t n, const char *__restrict__ src,
                                           int64_t src_stride_bytes, char *__restrict__ dst,
                                           int64_t dst_stride_bytes, int vecs, int log2_lpr) {
+    if (vecs > kWave) {
+        switch (wide_chunks(vecs)) {
+            case 2: copy_rows_wide<VecT, 2, 4>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
+            case 3: copy_rows_wide<VecT, 3, 2>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
+            default: copy_rows_wide<VecT, 4, 2>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
+        }
+        return;
+    }
     const int lane = lane_id();
     const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
-    if (vecs <= kWave) {
-        const int groups = kWave >> log2_lpr;
-        const int g = lane >> log2_lpr;
-        const int gl = lane & ((1 << log2_lpr) - 1);
-        const int64_t per_wave = int64_t(groups) * kRowUnroll;
-        for (int64_t base = wave0 * per_wave; base < n; base += nwaves * per_wave) {
-            const VecT *sp[kRowUnroll];
-            VecT *dp[kRowUnroll];
-            bool ok[kRowUnroll];
-            VecT v[kRowUnroll];
+    const int groups = kWave >> log2_lpr;
+    const int g = lane >> log2_lpr;
+    const int gl = lane & ((1 << log2_lpr) - 1);
+    const int64_t per_wave = int64_t(groups) * kRowUnroll;
+    for (int64_t base = wave0 * per_wave; base < n; base += nwaves * per_wave) {
+        const VecT *sp[kRowUnroll];
+        VecT *dp[kRowUnroll];
+        bool ok[kRowUnroll];
+        VecT v[kRowUnroll];
 #pragma unroll
-            for (int u = 0; u < kRowUnroll; ++u) {
-                const int64_t r = base + u * groups + g;
-                ok[u] = r < n && gl < vecs;
-                int64_t srow = 0, drow = 0;
-                if (r < n) rows.get(r, &srow, &drow);
-                sp[u] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes) + gl;
-                dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + gl;
-            }
-#pragma unroll
-            for (int u = 0; u < kRowUnroll; ++u)
-                if (ok[u]) v[u] = *sp[u];
-#pragma unroll
-            for (int u = 0; u < kRowUnroll; ++u)
-                if (ok[u]) *dp[u] = v[u];
+        for (int u = 0; u < kRowUnroll; ++u) {
+            const int64_t r = base + u * groups + g;
+            ok[u] = r < n && gl < vecs;
+            int64_t srow = 0, drow = 0;
+            if (r < n) rows.get(r, &srow, &drow);
+            sp[u] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes) + gl;
+            dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + gl;
         }
-    } else {
-        // two rows per step, four 64-vector chunks of each: up to eight loads per lane are issued
-        // before the first store (a row's last, partial chunk rides along instead of trailing alone)
-        for (int64_t r0 = wave0 * kWideRows; r0 < n; r0 += nwaves * kWideRows) {
-            const VecT *sp[kWideRows];
-            VecT *dp[kWideRows];
-            bool rok[kWideRows];
 #pragma unroll
-            for (int q = 0; q < kWideRows; ++q) {
-                const int64_t r = r0 + q;
-                rok[q] = r < n;
-                int64_t srow, drow;
-                rows.get(rok[q] ? r : n - 1, &srow, &drow);      // a row past the end re-reads the last one
-                sp[q] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes);
-                dp[q] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes);
-            }
-            for (int c0 = lane; c0 < vecs; c0 += 4 * kWave) {
-                // loads are unconditional (an index past the row re-reads its last vector) so that
-                // all eight are issued back to back; only the stores are predicated
-                VecT v[kWideRows][4];
+        for (int u = 0; u < kRowUnroll; ++u)
+            if (ok[u]) v[u] = *sp[u];
 #pragma unroll
-                for (int q = 0; q < kWideRows; ++q)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const int c = c0 + k * kWave;
-                        v[q][k] = sp[q][c < vecs ? c : vecs - 1];
-                    }
-#pragma unroll
-                for (int q = 0; q < kWideRows; ++q)
-#pragma unroll
-                    for (int k = 0; k < 4; ++k) {
-                        const int c = c0 + k * kWave;
-                        if (rok[q] && c < vecs) dp[q][c] = v[q][k];
-                    }
-            }
-        }
+        for (int u = 0; u < kRowUnroll; ++u)
+            if (ok[u]) *dp[u] = v[u];
     }
 }
 
@@ -294,8 +310,8 @@ RowGeom row_geom(int64_t row_bytes, int64_t a_stride, int64_t b_stride, const vo
         g.rows_per_wave = int64_t(kWave >> g.log2_lpr) * kRowUnroll;
         g.bytes_per_wave = g.rows_per_wave * row_bytes;
     } else {
-        g.rows_per_wave = kWideRows;
-        g.bytes_per_wave = kWideRows * std::min<int64_t>(row_bytes, int64_t(4) * kWave * g.vb);
+        g.rows_per_wave = wide_rows(g.vecs);
+        g.bytes_per_wave = g.rows_per_wave * std::min<int64_t>(row_bytes, int64_t(wide_chunks(g.vecs)) * kWave * g.vb);
     }
     return g;
 }
