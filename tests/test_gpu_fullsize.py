@@ -77,8 +77,7 @@ def test_full_size_workload(mqg, name):
     rp, ci = synth.build_graph(w, seed=0, device=dev)
     n = rp.numel() - 1
     assert n == w.num_nodes and ci.numel() > 0.9 * w.target_edges
-    feats = torch.empty((n, w.dim), dtype=w.feat_dtype).pin_memory()
-    synth.node_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev, out=feats)
+    feats = synth.pinned_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev)     # bench.py's host layout
     torch.cuda.synchronize()
     g = mqg.Graph(rp, ci)
     L = len(w.fanouts)
