@@ -82,7 +82,7 @@ def main() -> int:
     t0 = time.time()
     rp, ci = synth.build_graph(w, seed=0, device=dev)
     n = rp.numel() - 1
-    # pinned host rows on 64-byte boundaries where that is cheap (synth.host_row_stride; measured on
+    # pinned host rows on 64-byte boundaries where that is cheap (synth.aligned_row_stride; measured on
     # "medium": 2.41 instead of 2.54 ms/step)
     feats = synth.pinned_features(n, w.dim, dtype=w.feat_dtype, seed=1, device=dev)
     torch.cuda.synchronize()
@@ -91,7 +91,9 @@ def main() -> int:
     seeds_dev = [b.to(g.idx_dtype).to(dev) for b in batches]
     gen_s = time.time() - t0
 
-    pad_dim = (row_bytes + 15) // 16 * 16 // elt      # row stride that keeps every row 16-byte aligned
+    # the same alignment rule for the rows in HBM (cache, gathered rows, layer outputs): measured on
+    # "medium" 47.8 instead of 48.9 us for the hit gather, 101 instead of 103 us for the aggregation
+    pad_dim = synth.aligned_row_stride(w.dim, w.feat_dtype)
     ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]
     streams = [torch.cuda.Stream() for _ in range(nfl)] if (nfl > 1 or args.graph) else [torch.cuda.current_stream()]

@@ -122,10 +122,11 @@ def node_features(num_nodes: int, dim: int, *, dtype=torch.float32, seed: int = 
     return out
 
 
-def host_row_stride(dim: int, dtype=torch.float32) -> int:
-    """Row stride (in elements) of the pinned host feature matrix: rows start on 64-byte boundaries
-    when that costs at most 2 % more memory, otherwise on 16-byte boundaries.  A row that starts
-    inside a cache line makes the host link carry the unused parts of its first and last line."""
+def aligned_row_stride(dim: int, dtype=torch.float32) -> int:
+    """Row stride (in elements) used for feature rows, in pinned host memory and in HBM: rows start
+    on 64-byte boundaries when that costs at most 2 % more memory, otherwise on 16-byte boundaries.
+    A row that starts inside a cache line makes the host link carry the unused parts of its first
+    and last line, and makes its first and last line partial writes in HBM."""
     elt = torch.empty((), dtype=dtype).element_size()
     row_bytes = dim * elt
     stride = (row_bytes + 63) // 64 * 64
@@ -135,9 +136,9 @@ def host_row_stride(dim: int, dtype=torch.float32) -> int:
 
 
 def pinned_features(num_nodes: int, dim: int, *, dtype=torch.float32, seed: int = 1, device: str = "cpu") -> torch.Tensor:
-    """node_features() into pinned host memory laid out with host_row_stride(); returns the
+    """node_features() into pinned host memory laid out with aligned_row_stride(); returns the
     [num_nodes, dim] view."""
-    feats = torch.empty((num_nodes, host_row_stride(dim, dtype)), dtype=dtype).pin_memory()[:, :dim]
+    feats = torch.empty((num_nodes, aligned_row_stride(dim, dtype)), dtype=dtype).pin_memory()[:, :dim]
     return node_features(num_nodes, dim, dtype=dtype, seed=seed, device=device, out=feats)
 
 

@@ -74,12 +74,12 @@ def test_bench_refuses_more_than_one_gpu():
     assert p.returncode != 0 and "one GPU" in p.stderr and p.stdout.strip() == ""
 
 
-def test_host_row_stride_rule():
-    assert synth.host_row_stride(602, torch.float32) == 608          # 2,408 -> 2,432 bytes: +1 %
-    assert synth.host_row_stride(100, torch.float32) == 100          # 400 bytes: 448 would be +12 %, stays 16-byte aligned
-    assert synth.host_row_stride(128, torch.float16) == 128 and synth.host_row_stride(256, torch.float16) == 256
-    assert synth.host_row_stride(7, torch.float32) == 8              # 28 -> 32 bytes (16-byte rule)
+def test_aligned_row_stride_rule():
+    assert synth.aligned_row_stride(602, torch.float32) == 608          # 2,408 -> 2,432 bytes: +1 %
+    assert synth.aligned_row_stride(100, torch.float32) == 100          # 400 bytes: 448 would be +12 %, stays 16-byte aligned
+    assert synth.aligned_row_stride(128, torch.float16) == 128 and synth.aligned_row_stride(256, torch.float16) == 256
+    assert synth.aligned_row_stride(7, torch.float32) == 8              # 28 -> 32 bytes (16-byte rule)
     for dim, dt in ((602, torch.float32), (100, torch.float32), (9, torch.float16), (1030, torch.float32)):
-        st = synth.host_row_stride(dim, dt)
+        st = synth.aligned_row_stride(dim, dt)
         elt = 2 if dt == torch.float16 else 4
         assert st >= dim and (st * elt) % 16 == 0
