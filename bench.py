@@ -92,7 +92,7 @@ def main() -> int:
     gen_s = time.time() - t0
 
     # the same alignment rule for the rows in HBM (cache, gathered rows, layer outputs): measured on
-    # "medium" 47.8 instead of 48.9 us for the hit gather, 101 instead of 103 us for the aggregation
+    # "medium" 46.7 instead of 48.9 us for the hit gather, 101 instead of 103 us for the aggregation
     pad_dim = synth.aligned_row_stride(w.dim, w.feat_dtype)
     ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]

@@ -376,8 +376,8 @@ int mqg_ctx_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *graph, const mq
  *                values above cap_ids are clamped to cap_ids
  *   out_dev      device [cap_ids x out_stride] elements of cache->dtype; in a written row
  *                the elements from dim up to out_stride (padding) are unspecified: when
- *                source and destination rows are 16-byte aligned the copy is rounded up
- *                to whole 16-byte words
+ *                source and destination rows are 64-byte (16-byte) aligned and long enough
+ *                the copy is rounded up to whole 64-byte lines (16-byte words)
  *   stats_dev    device int64[2]: rows served from the cache, rows served
  *                from feats; may be NULL
  */
