@@ -49,6 +49,8 @@ def main() -> int:
                     help="record each in-flight slot's step (sample, gather, aggregate) into a HIP graph once and "
                          "replay it in the timed region (seeds and sampling seed are rewritten in device buffers)")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
+    ap.add_argument("--device-row-multiple", type=int, default=None,
+                    help="bytes the rows kept in HBM are padded to a multiple of (default: synth.aligned_row_stride)")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -94,6 +96,9 @@ def main() -> int:
     # the same alignment rule for the rows in HBM (cache, gathered rows, layer outputs): measured on
     # "medium" 46.7 instead of 48.9 us for the hit gather, 101 instead of 103 us for the aggregation
     pad_dim = synth.aligned_row_stride(w.dim, w.feat_dtype)
+    if args.device_row_multiple:
+        m = args.device_row_multiple
+        pad_dim = (row_bytes + m - 1) // m * m // elt
     ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(nfl)]
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(nfl)]
     streams = [torch.cuda.Stream() for _ in range(nfl)] if (nfl > 1 or args.graph) else [torch.cuda.current_stream()]

@@ -31,6 +31,85 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// The lowest n lanes.
+__device__ __forceinline__ uint64_t low_lanes(int n) { return n >= 64 ? ~uint64_t(0) : (uint64_t(1) << n) - 1; }
+
+// Selection of the `need` smallest among the candidates a wavefront holds, NCH per lane: candidate
+// c*64+lane has key[c], cand[c] is the set of lanes that hold one.  The order is (late bit, key,
+// tie, candidate index), where late[c] marks candidates that come after every unmarked one (PRIO
+// only) and tie[c] is a second, 32-bit key (TIE only; for candidates not stored in the order that
+// breaks ties between equal keys).
+// Binary radix select from the top bit down: one ballot per chunk and bit splits the undecided
+// candidates into those with a zero (smaller) and those with a one; either the zeros are still
+// too many and the ones drop out, or all zeros are taken and the ones compete for the rest.  It
+// stops as soon as the undecided candidates are exactly as many as are still needed, after about
+// log2(candidates) bits for random keys.  Masks and counters live in scalar registers.  Every lane
+// of the wavefront must call it; need must be at least 1 and at most the number of candidates.
+// On return sel[c] holds the chosen lanes of chunk c.
+template <int NCH, bool PRIO, bool TIE>
+__device__ __forceinline__ void wave_select_smallest(const uint64_t (&key)[NCH], const uint64_t (&late)[NCH],
+                                                     const uint32_t (&tie)[NCH], uint64_t (&cand)[NCH], int need,
+                                                     uint64_t (&sel)[NCH]) {
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) sel[c] = 0;
+    auto settled = [&]() -> bool {
+        int total = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) total += popc64(cand[c]);
+        if (total != need) return false;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) sel[c] |= cand[c];
+        return true;
+    };
+    auto split = [&](const uint64_t (&zeros)[NCH]) {
+        int c0 = 0;
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) c0 += popc64(zeros[c]);
+        if (c0 >= need) {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) cand[c] = zeros[c];
+        } else {
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) {
+                sel[c] |= zeros[c];
+                cand[c] &= ~zeros[c];
+            }
+            need -= c0;
+        }
+    };
+    if (settled()) return;
+    uint64_t zeros[NCH];
+    if (PRIO) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) zeros[c] = cand[c] & ~late[c];
+        split(zeros);
+        if (settled()) return;
+    }
+    for (int part = 0; part < (TIE ? 3 : 2); ++part) {
+        uint32_t w[NCH];
+#pragma unroll
+        for (int c = 0; c < NCH; ++c)
+            w[c] = part == 0 ? static_cast<uint32_t>(key[c] >> 32) : part == 1 ? static_cast<uint32_t>(key[c]) : tie[c];
+        for (int b = 31; b >= 0; --b) {
+            const uint32_t bit = uint32_t(1) << b;
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) zeros[c] = ballot64((w[c] & bit) == 0) & cand[c];
+            split(zeros);
+            if (settled()) return;
+        }
+    }
+    // the undecided candidates are equal in every word: lowest candidate index first
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        while (need > 0 && cand[c] != 0) {
+            const uint64_t low = cand[c] & (~cand[c] + 1);
+            sel[c] |= low;
+            cand[c] ^= low;
+            --need;
+        }
+    }
+}
+
 // Inclusive prefix sum over the 64 lanes of a wavefront.
 __device__ __forceinline__ int wave_incl_scan(int v) {
     const int lane = lane_id();

@@ -210,6 +210,85 @@ __device__ __forceinline__ bool pair_less(uint64_t ka, int sa, uint64_t kb, int 
     return ka < kb || (ka == kb && sa < sb);
 }
 
+// Candidates 0..cnt of a row in LDS (key, slot; bit 31 of the slot word = comes after every
+// unmarked candidate, PRIO only).  Picks the k first in the sampling order and returns, per chunk
+// of 64 candidates, the chosen lanes; slot[] gets each lane's slot words.  ORDERED: the candidates
+// are stored in ascending slot order, so equal keys need no second key.
+template <int NCH, bool PRIO, bool ORDERED, typename SlotT>
+__device__ __forceinline__ void select_candidates(const uint64_t *ck, const SlotT *cs, int cnt, int k,
+                                                  uint32_t (&slot)[NCH], uint64_t (&sel)[NCH]) {
+    const int lane = lane_id();
+    uint64_t key[NCH], late[NCH], cand[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        const int ci = c * kWave + lane;
+        const bool valid = ci < cnt;
+        key[c] = valid ? ck[ci] : 0;
+        slot[c] = valid ? static_cast<uint32_t>(cs[ci]) : 0u;
+        const int left = cnt - c * kWave;
+        cand[c] = left <= 0 ? 0 : low_lanes(left);
+        late[c] = PRIO ? ballot64((slot[c] >> 31) != 0) : 0;
+    }
+    uint32_t tie[NCH];
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) tie[c] = slot[c] & 0x7FFFFFFFu;
+    wave_select_smallest<NCH, PRIO, !ORDERED>(key, late, tie, cand, k, sel);
+}
+
+// The same for candidates in ascending slot order, emitted as the row's neighbours.
+template <int NCH, bool PRIO, typename IdxT, typename SlotT>
+__device__ __forceinline__ void emit_selected(const uint64_t *ck, const SlotT *cs, int cnt, int k,
+                                              const IdxT *__restrict__ col_idx, int64_t start, int32_t out_base,
+                                              const SampleArgs &a) {
+    const int lane = lane_id();
+    uint32_t slot[NCH];
+    uint64_t sel[NCH];
+    select_candidates<NCH, PRIO, true>(ck, cs, cnt, k, slot, sel);
+    int out_pos = out_base;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        if ((sel[c] >> lane) & 1)
+            emit_neighbour(col_idx, start, static_cast<int>(slot[c] & 0x7FFFFFFFu),
+                           out_pos + popc64(sel[c] & lanes_below(lane)), a);
+        out_pos += popc64(sel[c]);
+    }
+}
+template <bool PRIO, typename IdxT, typename SlotT>
+__device__ __forceinline__ void emit_selected_any(const uint64_t *ck, const SlotT *cs, int cnt, int k,
+                                                  const IdxT *__restrict__ col_idx, int64_t start, int32_t out_base,
+                                                  const SampleArgs &a) {
+    if (cnt <= kWave) emit_selected<1, PRIO>(ck, cs, cnt, k, col_idx, start, out_base, a);
+    else if (cnt <= 2 * kWave) emit_selected<2, PRIO>(ck, cs, cnt, k, col_idx, start, out_base, a);
+    else emit_selected<kCandidates / kWave, PRIO>(ck, cs, cnt, k, col_idx, start, out_base, a);
+}
+
+// Hub rows: the candidates sit in LDS in arrival order.  The first wavefront picks the k winners,
+// lists their slots in sel_slot and emits them in ascending slot order.
+template <bool PRIO, typename IdxT, typename SlotT>
+__device__ __forceinline__ void emit_selected_unordered(const uint64_t *ck, const SlotT *cs, int cnt, int k,
+                                                        int32_t *sel_slot, const IdxT *__restrict__ col_idx,
+                                                        int64_t start, int32_t out_base, const SampleArgs &a) {
+    constexpr int NCH = kCandidates / kWave;
+    const int lane = lane_id();
+    uint32_t slot[NCH];
+    uint64_t sel[NCH];
+    select_candidates<NCH, PRIO, false>(ck, cs, cnt, k, slot, sel);
+    int pos = 0;
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        if ((sel[c] >> lane) & 1) sel_slot[pos + popc64(sel[c] & lanes_below(lane))] = static_cast<int32_t>(slot[c] & 0x7FFFFFFFu);
+        pos += popc64(sel[c]);
+    }
+    wave_lds_sync();
+    const int my_slot = lane < k ? sel_slot[lane] : 0x7FFFFFFF;
+    int rank = 0;
+    for (int t = 0; t < k; ++t) {
+        int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
+        rank += (other < my_slot) ? 1 : 0;
+    }
+    if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
+}
+
 // Unconditional selection: k rounds, each finding the smallest (key, slot) pair above the
 // previous round's.  O(k*d/64) key evaluations; used when the threshold pass cannot be
 // trusted (fewer than k or more than kCandidates keys under the threshold) and in tests.
@@ -260,7 +339,7 @@ __device__ void select_by_repeated_min(const IdxT *__restrict__ col_idx, int64_t
 // Hubs (degree > heavy_degree, listed by k_row_info): the four wavefronts of a workgroup share
 // one row.  Candidates under the threshold are appended to one LDS list in arrival order (an LDS
 // atomic per wavefront and chunk); the result does not depend on that order because the
-// candidates are ranked by (key, slot) and the k winners are then ordered by slot.
+// k winners are selected by (key, slot) and then ordered by slot.
 template <typename IdxT>
 __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, const SampleArgs &a,
                             const int32_t *__restrict__ heavy_rows, int nheavy, int first, int step,
@@ -306,28 +385,12 @@ __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__rest
             __syncthreads();
             continue;
         }
-        if (tid < cnt) {                                   // kCandidates == workgroup size
-            const uint64_t my_key = ck[tid];
-            const int my_slot = cs[tid];
-            int rank = 0;
-            for (int t = 0; t < cnt; ++t) rank += pair_less(ck[t], cs[t], my_key, my_slot) ? 1 : 0;
-            if (rank < k) sel_slot[rank] = my_slot;
-        }
-        __syncthreads();
-        if (wave == 0) {
-            const int my_slot = lane < k ? sel_slot[lane] : 0x7FFFFFFF;
-            int rank = 0;
-            for (int t = 0; t < k; ++t) {
-                int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
-                rank += (other < my_slot) ? 1 : 0;
-            }
-            if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
-        }
+        if (wave == 0) emit_selected_unordered<false>(ck, cs, cnt, k, sel_slot, col_idx, start, out_base, a);
         __syncthreads();                                   // LDS is reused by the next row
     }
 }
 
-static_assert(kCandidates == kBlock, "hub ranking uses one thread per candidate");
+static_assert(kCandidates % kWave == 0, "candidates are selected in chunks of one per lane");
 
 // The first hub_blocks workgroups take the hubs (they are dispatched first and run the longest);
 // every other workgroup gives each of its four wavefronts one destination.
@@ -366,21 +429,18 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
         return;
     }
     if (d <= kWave) {
-        // one key per lane; rank every key against all others
-        uint64_t key = lane < d ? RowKeys(hv)(lane) : kMaxKey;
-        int rank = 0;
-        for (int t = 0; t < d; ++t) {
-            uint64_t other = readlane64(key, t);
-            rank += pair_less(other, t, key, lane) ? 1 : 0;
-        }
-        bool sel = lane < d && rank < k;
-        uint64_t m = ballot64(sel);
-        if (sel) emit_neighbour(col_idx, start, lane, out_base + popc64(m & lanes_below(lane)), a);
+        // one key per lane
+        const uint64_t key[1] = {RowKeys(hv)(lane)};
+        const uint64_t late[1] = {0};
+        const uint32_t tie[1] = {0};
+        uint64_t cand[1] = {low_lanes(d)}, sel[1];
+        wave_select_smallest<1, false, false>(key, late, tie, cand, k, sel);
+        if ((sel[0] >> lane) & 1) emit_neighbour(col_idx, start, lane, out_base + popc64(sel[0] & lanes_below(lane)), a);
         return;
     }
 
     // d > 64: keep the slots whose key falls under a threshold expected to pass 2k+32 of them,
-    // then rank only those candidates.  Candidates are stored in ascending slot order.
+    // then select among those candidates only.  Candidates are stored in ascending slot order.
     uint64_t *ck = cand_key[wave];
     int32_t *cs = cand_slot[wave];
     const int expect = 2 * k + 32;
@@ -407,21 +467,7 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
         return;
     }
     wave_lds_sync();
-    int out_pos = out_base;
-    for (int cbase = 0; cbase < cnt; cbase += kWave) {
-        int ci = cbase + lane;
-        bool valid = ci < cnt;
-        uint64_t my_key = valid ? ck[ci] : kMaxKey;
-        int rank = 0;
-        for (int t = 0; t < cnt; ++t) {
-            uint64_t other = ck[t];                        // same address in every lane: broadcast
-            rank += pair_less(other, t, my_key, ci) ? 1 : 0;
-        }
-        bool sel = valid && rank < k;
-        uint64_t m = ballot64(sel);
-        if (sel) emit_neighbour(col_idx, start, cs[ci], out_pos + popc64(m & lanes_below(lane)), a);
-        out_pos += popc64(m);
-    }
+    emit_selected_any<false>(ck, cs, cnt, k, col_idx, start, out_base, a);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -571,27 +617,7 @@ __device__ void sample_hubs_prio(const IdxT *__restrict__ col_idx, const IdxT *_
             __syncthreads();
             continue;
         }
-        if (tid < cnt) {
-            const uint64_t my_key = ck[tid];
-            const uint32_t my_cs = cs[tid];
-            int rank = 0;
-            for (int t = 0; t < cnt; ++t) {
-                const uint32_t o = cs[t];
-                rank += prio_less((o >> 31) != 0, ck[t], static_cast<int>(o & 0x7FFFFFFFu), (my_cs >> 31) != 0, my_key,
-                                  static_cast<int>(my_cs & 0x7FFFFFFFu)) ? 1 : 0;
-            }
-            if (rank < k) sel_slot[rank] = static_cast<int32_t>(my_cs & 0x7FFFFFFFu);
-        }
-        __syncthreads();
-        if (wave == 0) {
-            const int my_slot = lane < k ? sel_slot[lane] : 0x7FFFFFFF;
-            int rank = 0;
-            for (int t = 0; t < k; ++t) {
-                int other = static_cast<int>(readlane32(static_cast<uint32_t>(my_slot), t));
-                rank += (other < my_slot) ? 1 : 0;
-            }
-            if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
-        }
+        if (wave == 0) emit_selected_unordered<true>(ck, cs, cnt, k, sel_slot, col_idx, start, out_base, a);
         __syncthreads();
     }
 }
@@ -635,18 +661,13 @@ k_sample_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids
     }
     const IdxT *nbrs = col_idx + start;
     if (d <= kWave) {
-        const bool valid = lane < d;
-        const uint64_t key = valid ? RowKeys(hv)(lane) : kMaxKey;
-        const bool unc = valid ? !is_cached(nbrs, lane, prio) : true;
-        const uint64_t um = ballot64(unc);
-        int rank = 0;
-        for (int t = 0; t < d; ++t) {
-            const uint64_t other = readlane64(key, t);
-            rank += prio_less(((um >> t) & 1) != 0, other, t, unc, key, lane) ? 1 : 0;
-        }
-        const bool sel = valid && rank < k;
-        const uint64_t m = ballot64(sel);
-        if (sel) emit_neighbour(col_idx, start, lane, out_base + popc64(m & lanes_below(lane)), a);
+        const bool unc = lane < d ? !is_cached(nbrs, lane, prio) : true;
+        const uint64_t key[1] = {RowKeys(hv)(lane)};
+        const uint64_t late[1] = {ballot64(unc)};
+        const uint32_t tie[1] = {0};
+        uint64_t cand[1] = {low_lanes(d)}, sel[1];
+        wave_select_smallest<1, true, false>(key, late, tie, cand, k, sel);
+        if ((sel[0] >> lane) & 1) emit_neighbour(col_idx, start, lane, out_base + popc64(sel[0] & lanes_below(lane)), a);
         return;
     }
 
@@ -689,22 +710,7 @@ k_sample_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids
         return;
     }
     wave_lds_sync();
-    int out_pos = out_base;
-    for (int cbase = 0; cbase < cnt; cbase += kWave) {
-        const int ci = cbase + lane;
-        const bool valid = ci < cnt;
-        const uint64_t my_key = valid ? ck[ci] : kMaxKey;
-        const uint32_t my_cs = valid ? cs[ci] : 0xFFFFFFFFu;
-        const bool my_unc = (my_cs >> 31) != 0;
-        int rank = 0;
-        for (int t = 0; t < cnt; ++t) {                    // candidates are stored in ascending slot order
-            rank += prio_less((cs[t] >> 31) != 0, ck[t], t, my_unc, my_key, ci) ? 1 : 0;
-        }
-        const bool sel = valid && rank < k;
-        const uint64_t m = ballot64(sel);
-        if (sel) emit_neighbour(col_idx, start, static_cast<int>(my_cs & 0x7FFFFFFFu), out_pos + popc64(m & lanes_below(lane)), a);
-        out_pos += popc64(m);
-    }
+    emit_selected_any<true>(ck, cs, cnt, k, col_idx, start, out_base, a);
 }
 
 // prio_count[v] = number of cached neighbours of node v.  A lane owns a node; rows of up to 32 slots
