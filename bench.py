@@ -284,14 +284,12 @@ def main() -> int:
 
     # the forward profile pass launches nothing else through the radix/scan kernels than the hash dedup
     dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local", "k_zero_u64", "k_scan_tiles(radix)",
-                     "k_scan_reduce", "k_scan_apply")
+                     "k_scan_tiles(bitmap)", "k_scan_reduce", "k_scan_apply")
     dedup_us = sum(v["us_per_step"] for k, v in kern.items()
                    if k in dedup_kernels or k.startswith("k_hash_") or k.startswith("k_radix_"))
-    if args.dedup == "bitmap":                             # its one scan per block goes by the shared name
-        dedup_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / 2
     sample_us = dedup_us + sum(v["us_per_step"] for k, v in kern.items()
-                               if k in ("k_init_seeds", "k_row_info", "k_row_offsets", "k_sample", "k_sample_prio"))
-    sample_us += kern.get("k_scan_tiles", {}).get("us_per_step", 0.0) / (2 if args.dedup == "bitmap" else 1)
+                               if k in ("k_init_seeds", "k_row_info", "k_scan_tiles(rows)", "k_row_offsets", "k_sample",
+                                        "k_sample_prio"))
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
     # ---------------------------------------------------------------- sampling against its own bounds
@@ -303,8 +301,8 @@ def main() -> int:
     sampling = {
         "edges_per_s_sampling_alone": round(edges / K / max(sample_us, 1e-9) * 1e6, 1),
         "us_per_step": round(sample_us, 1), "kernel_launches_per_step": sum(
-            v["launches"] for k, v in kern.items() if k in ("k_row_info", "k_scan_tiles", "k_row_offsets", "k_sample",
-                                                            "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local")) / K,
+            v["launches"] for k, v in kern.items() if k in ("k_row_info", "k_scan_tiles(rows)", "k_scan_tiles(bitmap)", "k_row_offsets",
+                                                            "k_sample", "k_sample_prio", "k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local")) / K,
         "keys_evaluated_per_step": round(keys_per_step, 1),
         "k_sample": {"bound": "alu", "achieved": round(keys_per_step / max(k_sample_us, 1e-9) * 1e-3, 2),
                      "peak": round(alu_peak_keys / 1e9, 1), "unit": "Gkeys/s",

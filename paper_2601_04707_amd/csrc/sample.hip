@@ -4,14 +4,14 @@
 // Per block, outward from the seeds:
 //   k_row_info     adjacency start/degree of every destination, copy of the destinations into the
 //                  block's source list, per-tile sums of min(fanout, degree)
-//   k_scan_tiles   exclusive scan of the tile sums (one workgroup), total = nnz
-//   k_row_offsets  indptr
+//   k_row_offsets  indptr (every workgroup adds up the tile sums before its own; only above 2,048
+//                  tiles does one k_scan_tiles launch scan them first), total = nnz
 //   k_sample       one wavefront per destination: smallest-k random keys, neighbours written in
 //                  ascending adjacency slot, first-seen nodes marked in an N-bit bitmap
 //                  (destinations whose degree exceeds heavy_degree, listed by k_row_info, are
 //                  taken by whole workgroups in the same launch, so that a hub's key evaluation
 //                  is spread over four wavefronts instead of stretching the kernel's tail)
-//   k_bitmap_count / k_scan_tiles / k_bitmap_emit
+//   k_bitmap_count / k_bitmap_emit (tile sums handled as in k_row_offsets)
 //                  popcount-rank the bitmap: new source nodes come out ascending by id, get their
 //                  position recorded in local_of[], the bitmap is cleared on the way
 //   k_relabel      indices[e] = local_of[neighbour e]
@@ -92,6 +92,23 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
     }
 }
 
+// Sum of tile_sums[0 .. blockIdx.x): what a tile's own workgroup adds up instead of a separate scan
+// launch when the tiles are few (kSelfPrefixTiles at most, i.e. at most 8 loads per thread).
+// Every thread of the workgroup must call it; `lds` needs kWavesPerBlock ints.
+constexpr int kSelfPrefixTiles = 2048;
+__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sums, int *lds) {
+    int part = 0;
+    for (int t = threadIdx.x; t < static_cast<int>(blockIdx.x); t += kBlock) part += tile_sums[t];
+    part = wave_sum(part);
+    __syncthreads();                                       // lds may still be read from an earlier use
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = part;
+    __syncthreads();
+    int sum = 0;
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) sum += lds[k];
+    return sum;
+}
+
 // One workgroup of 1024 threads: vals[0..n) -> exclusive scan in place; totals stored.
 __global__ void __launch_bounds__(1024)
 k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ addend,
@@ -113,14 +130,18 @@ k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ 
     }
 }
 
+// scanned: tile_vals holds the exclusive scan of the tile sums (k_scan_tiles ran, and stored nnz);
+// otherwise it holds the sums themselves, every workgroup adds up its own base and the last one
+// stores nnz.
 __global__ void __launch_bounds__(kBlock)
 k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
-              const int32_t *__restrict__ tile_base, int32_t *__restrict__ indptr,
+              const int32_t *__restrict__ tile_vals, int scanned, int32_t *__restrict__ indptr,
               const int32_t *__restrict__ seed_flags) {
     __shared__ int lds[kWavesPerBlock];
     const int64_t n = sizes[0];
     // the block's flags word: what the seed check found (innermost block), 0 otherwise
     if (blockIdx.x == 0 && threadIdx.x == 0) sizes[3] = seed_flags ? *seed_flags : 0;
+    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     int cnt = 0;
     if (i < n) {
@@ -129,12 +150,13 @@ k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
     }
     int total;
     int ex = block_excl_scan<kWavesPerBlock>(cnt, &total, lds);
-    int off = tile_base[blockIdx.x] + ex;
+    int off = tile_base + ex;
     if (i < n) {
         indptr[i] = off;
         if (i == n - 1) indptr[n] = off + cnt;
     }
     if (n == 0 && i == 0) indptr[0] = 0;
+    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) sizes[2] = tile_base + total;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -787,19 +809,28 @@ k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_s
     }
 }
 
+// num_src of a block is also num_dst of the next block outward
+__device__ __forceinline__ void store_num_src(int64_t *sizes, int64_t *next_num_dst, int64_t num_src) {
+    sizes[1] = num_src;
+    if (next_num_dst) *next_num_dst = num_src;
+}
+
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_bitmap_emit4(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
-               const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
+k_bitmap_emit4(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_vals, int scanned,
+               int64_t *__restrict__ sizes, int64_t *__restrict__ next_num_dst, IdxT *__restrict__ src_ids,
+               int32_t *__restrict__ local_of) {
     __shared__ int lds[kWavesPerBlock];
+    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
     const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * 4;
     uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
     int c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
     int total;
     int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
-    if (c == 0) return;
     const int64_t num_dst = sizes[0];
-    int64_t pos = num_dst + tile_base[blockIdx.x] + ex;
+    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) store_num_src(sizes, next_num_dst, num_dst + tile_base + total);
+    if (c == 0) return;
+    int64_t pos = num_dst + tile_base + ex;
     uint32_t words[4] = {w.x, w.y, w.z, w.w};
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -818,15 +849,19 @@ k_bitmap_emit4(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_b
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_base,
-               const int64_t *__restrict__ sizes, IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of) {
+k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_vals, int scanned,
+               int64_t *__restrict__ sizes, int64_t *__restrict__ next_num_dst, IdxT *__restrict__ src_ids,
+               int32_t *__restrict__ local_of) {
     __shared__ int lds[kWavesPerBlock];
     __shared__ int32_t staged[kBlock * 32];                // every id of the tile, ascending
+    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
     const int64_t w0 = int64_t(blockIdx.x) * kBlock + threadIdx.x;
     uint32_t bits = bitmap[w0];
     const int c = __popc(bits);
     int total;
     int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+    const int64_t num_dst = sizes[0];
+    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) store_num_src(sizes, next_num_dst, num_dst + tile_base + total);
     if (total == 0) return;                                // workgroup-uniform
     if (c) {
         bitmap[w0] = 0;
@@ -838,7 +873,7 @@ k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_b
         }
     }
     __syncthreads();
-    const int64_t base = sizes[0] + tile_base[blockIdx.x];
+    const int64_t base = num_dst + tile_base;
     for (int k = threadIdx.x; k < total; k += kBlock) {
         const int32_t v = staged[k];
         src_ids[base + k] = static_cast<IdxT>(v);
@@ -897,14 +932,17 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
                                                                           ctx->heavy_rows, ctx->heavy_count + l,
                                                                           l == L - 1 ? int64_t(num_seeds) : int64_t(-1), local_of,
                                                                           g->num_nodes, ctx->heavy_count + MQG_MAX_LAYERS)));
-        int rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s);
+        // few tiles: every workgroup of the consumer adds up the tile sums before its own; many: one scan launch
+        const int rows_scanned = row_tiles > kSelfPrefixTiles ? 1 : 0;
+        int rc = MQG_OK;
+        if (rows_scanned) rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s, "k_scan_tiles(rows)");
         if (rc != MQG_OK) return rc;
         if (use_hash && l == L - 1) {                      // the seeds enter the table (and repeated ones are flagged) first
             rc = hash_put_seeds(ctx, b.src_ids, g->idx_type, need_dst, b.sizes, s);   // ids as k_row_info checked them
             if (rc != MQG_OK) return rc;
         }
         MQG_LAUNCH(ctx, "k_row_offsets", s,
-                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, b.indptr,
+                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
                                                                l == L - 1 ? ctx->heavy_count + MQG_MAX_LAYERS : nullptr)));
 
         SampleArgs a;
@@ -945,15 +983,16 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
         } else {
             MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<4><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
         }
-        rc = launch_scan_tiles(ctx, ctx->tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1],
-                               l > 0 ? &blocks[l - 1].sizes[0] : nullptr, s);
+        int64_t *next_num_dst = l > 0 ? &blocks[l - 1].sizes[0] : nullptr;
+        const int bits_scanned = bitmap_tiles > kSelfPrefixTiles ? 1 : 0;
+        if (bits_scanned) rc = launch_scan_tiles(ctx, ctx->tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1], next_num_dst, s, "k_scan_tiles(bitmap)");
         if (rc != MQG_OK) return rc;
         if (bitmap_wpt == 1) {
             MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids, ctx->local_of)));
+                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
         } else {
             MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, b.sizes, src_ids, ctx->local_of)));
+                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
         }
         int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
         MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, ctx->local_of, b.indices)));
