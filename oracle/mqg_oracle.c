@@ -38,9 +38,9 @@
  *                            Sec. IV "Mini-Batch Transfer": a mini-batch
  *                            carries topology and features.
  *   - orc_sample_block_prioritised : Sec. I on global neighbour sampling: the
- *                            sampler "prioritizes neighbors in the cache" so
- *                            that fewer distinct uncached nodes enter a
- *                            mini-batch.  Read as: a row's cached neighbours
+ *                            sampler gives neighbours held in the cache
+ *                            precedence, so that fewer distinct uncached
+ *                            nodes enter a mini-batch.  Read as: a row's cached neighbours
  *                            are drawn before its uncached ones.  The paper
  *                            prints no rule, so this function is "parity
  *                            unpinned" against the paper; the reading itself
