@@ -9,7 +9,15 @@ fanouts [25, 10], 1,024 seeds, top 30 % of nodes by degree cached in HBM).
 Inputs are resident (graph and cache in HBM, features in pinned host memory)
 before the timed region starts.
 
-Prints one JSON line; see the design doc for the meaning of every field.
+Prints one JSON line.  `value` = sampled edges per second over the timed,
+pipelined region (`ms_per_step` = its time per mini-batch); `roofline` = the
+hit-gather kernel against the HBM peak (algorithmic bytes per launch over its
+average duration by HIP events, `traffic` = hardware-counter bytes per launch
+read from the profile summary); `roofline_host_link` = the miss-gather kernel
+against the host link; `cpu_baseline` = the CPU oracle on a sample of the same
+mini-batches; `stage_us_per_step` and `kernels` = per-kernel times from a second
+pass that runs one mini-batch at a time; the remaining objects report the
+optional paths (backward, weighted, layer-wise) measured on the same blocks.
 """
 from __future__ import annotations
 
