@@ -85,7 +85,8 @@ def test_full_size_workload(mqg, name):
     blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(IN_FLIGHT)]
     streams = [torch.cuda.Stream() for _ in range(IN_FLIGHT)]
     num_cached = n * w.cache_pct // 100
-    cache = mqg.Cache(g, feats, num_cached)
+    pad_dim = synth.aligned_row_stride(w.dim, w.feat_dtype)     # bench.py's layout of the rows in HBM
+    cache = mqg.Cache(g, feats, num_cached, cache_stride=pad_dim)
     mqg.mqg_build_cache(ctxs[0], g, cache)
     torch.cuda.synchronize()
     check_cache_properties(rp, cache, num_cached)
@@ -93,8 +94,8 @@ def test_full_size_workload(mqg, name):
     batches = synth.seed_batches(n, w.batch, IN_FLIGHT, seed=2, train_fraction=w.train_fraction)
     seeds_dev = [b.to(g.idx_dtype).to(dev) for b in batches]
     bounds = blks[0].bounds
-    x0 = [torch.zeros((bounds[0][1], w.dim), dtype=w.feat_dtype, device=dev) for _ in range(IN_FLIGHT)]
-    hs = [[torch.zeros((bounds[l][0], w.dim), dtype=w.feat_dtype, device=dev) for l in range(L)]
+    x0 = [torch.zeros((bounds[0][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for _ in range(IN_FLIGHT)]
+    hs = [[torch.zeros((bounds[l][0], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)]
           for _ in range(IN_FLIGHT)]
     stats = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(IN_FLIGHT)]
     torch.cuda.synchronize()
@@ -130,7 +131,7 @@ def test_full_size_workload(mqg, name):
     sample_ids = torch.randint(0, max(1, num_cached), (4096,), generator=torch.Generator().manual_seed(0))
     if num_cached:
         ids = cache.cached_ids[sample_ids.to(dev)].cpu().numpy()
-        assert cache.cache_rows[sample_ids.to(dev)].cpu().numpy().tobytes() == feats_np[ids].tobytes()
+        assert cache.cache_rows[sample_ids.to(dev)][:, :w.dim].cpu().numpy().tobytes() == feats_np[ids].tobytes()
 
     full = range(IN_FLIGHT) if name != "stress" else [1]        # the 8,192-seed batches are slow on one CPU thread
     for j in full:
@@ -143,7 +144,7 @@ def test_full_size_workload(mqg, name):
             assert np.array_equal(blks[j].indptr[l][:nd + 1].cpu().numpy(), wb.indptr)
             assert np.array_equal(blks[j].indices[l][:nnz].cpu().numpy(), wb.indices)
         ns = want[0].num_src
-        assert x0[j][:ns].cpu().numpy().tobytes() == feats_np[want[0].src_ids].tobytes()
+        assert x0[j][:ns].contiguous().cpu().numpy().tobytes() == feats_np[want[0].src_ids].tobytes()
 
         # aggregation on sampled destination rows, each layer fed with the GPU's own input
         rng = np.random.default_rng(j)

@@ -262,6 +262,37 @@ def test_gather_result_independent_of_cache_fraction_and_strides(mqg):
     assert np.array_equal(out.cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("dim,dtype", [(602, torch.float32), (50, torch.float32), (100, torch.float16), (1, torch.float16)])
+def test_gather_copies_whole_lines_between_line_aligned_rows(mqg, dim, dtype):
+    """Cache rows and output rows on 64-byte boundaries: the HBM-to-HBM copy moves whole 64-byte
+    lines; the columns of a row are the same, rows past the count stay untouched."""
+    rp, ci = hub_graph(n=6000, edges=150_000, max_degree=900, seed=4)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    elt = 2 if dtype == torch.float16 else 4
+    stride = (dim * elt + 63) // 64 * 64 // elt
+    feats = synth.node_features(n, dim, dtype=dtype, seed=6).pin_memory()
+    ctx = mqg.Context(g, 256, [10])
+    want = oracle.build_cache(rp.numpy(), n // 2, feats.numpy())
+    for feats_side in (feats, feats.cuda()):                      # misses from host, or every row from HBM
+        cache = mqg.Cache(g, feats_side, n // 2, cache_stride=stride)
+        mqg.mqg_build_cache(ctx, g, cache)
+        for count in (0, 1, 130, 1999):
+            ids_np = np.random.default_rng(count).permutation(n)[:count].astype(np.int64)
+            cap = count + 2
+            ids = torch.zeros(cap, dtype=torch.int64, device="cuda")
+            ids[:count] = torch.from_numpy(ids_np).cuda()
+            num = torch.tensor([count], dtype=torch.int64, device="cuda")
+            buf = torch.full((cap, stride), 7.0, dtype=dtype, device="cuda")
+            stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+            mqg.mqg_gather_features(ctx, cache, ids, num, buf[:, :dim], stats)
+            torch.cuda.synchronize()
+            ref, h, m = oracle.gather(ids_np, feats.numpy(), want)
+            assert buf[:count, :dim].contiguous().cpu().numpy().tobytes() == ref.tobytes()
+            assert torch.all(buf[count:] == 7.0)
+            assert stats.tolist() == [h, m]
+
+
 def test_cache_ties_and_many_equal_degrees(mqg):
     # ring: every degree equal -> cache is the lowest ids; then a star on top
     n = 5000
