@@ -3,7 +3,8 @@
 // block's edges by source node for the backward aggregation.  The element count may live on the
 // device (n_dev): grids are sized by the host-side bound n_cap and every kernel clamps.
 //   k_radix_hist     per-workgroup digit histogram, laid out [digit][workgroup]
-//   k_scan_reduce / k_scan_tiles / k_scan_apply   exclusive scan of that table
+//   k_scan_reduce / k_scan_apply   exclusive scan of that table (k_scan_tiles between them only
+//                    above 2,048 tiles; a single tile needs no reduce)
 //   k_radix_scatter  stable scatter: ballot match inside a wavefront, LDS counts across the four
 //                    wavefronts and across the rounds of a tile
 #include <algorithm>
@@ -47,9 +48,12 @@ k_scan_reduce(const int32_t *__restrict__ in, int64_t n, int32_t *__restrict__ t
     if (threadIdx.x == 0) tile_sums[blockIdx.x] = lds[0] + lds[1] + lds[2] + lds[3];
 }
 
+// scanned: tile_vals holds the exclusive scan of the tile sums; otherwise the sums themselves, and
+// every workgroup adds up the ones before its own
 __global__ void __launch_bounds__(kBlock)
-k_scan_apply(int32_t *__restrict__ data, int64_t n, const int32_t *__restrict__ tile_base) {
+k_scan_apply(int32_t *__restrict__ data, int64_t n, const int32_t *__restrict__ tile_vals, int scanned) {
     __shared__ int lds[kWavesPerBlock];
+    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
     const int64_t base = int64_t(blockIdx.x) * kScanTile + threadIdx.x * 4;
     int v[4];
     int c = 0;
@@ -59,7 +63,7 @@ k_scan_apply(int32_t *__restrict__ data, int64_t n, const int32_t *__restrict__ 
         c += v[q];
     }
     int total;
-    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds) + tile_base[blockIdx.x];
+    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds) + tile_base;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
         if (base + q < n) data[base + q] = ex;
@@ -136,10 +140,13 @@ int64_t radix_scan_tiles(int64_t n_cap) { return ceil_div(radix_hist_len(n_cap),
 // exclusive scan of data[0..n) in place
 int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipStream_t s) {
     const int tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kScanTile)));
-    MQG_LAUNCH(ctx, "k_scan_reduce", s, (k_scan_reduce<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
-    int rc = launch_scan_tiles(ctx, tile_sums, tiles, nullptr, nullptr, nullptr, s, "k_scan_tiles(radix)");
-    if (rc != MQG_OK) return rc;
-    MQG_LAUNCH(ctx, "k_scan_apply", s, (k_scan_apply<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
+    const int scanned = tiles > kSelfPrefixTiles ? 1 : 0;     // few tiles: k_scan_apply adds the sums up itself
+    if (tiles > 1) MQG_LAUNCH(ctx, "k_scan_reduce", s, (k_scan_reduce<<<tiles, kBlock, 0, s>>>(data, n, tile_sums)));
+    if (scanned) {
+        int rc = launch_scan_tiles(ctx, tile_sums, tiles, nullptr, nullptr, nullptr, s, "k_scan_tiles(radix)");
+        if (rc != MQG_OK) return rc;
+    }
+    MQG_LAUNCH(ctx, "k_scan_apply", s, (k_scan_apply<<<tiles, kBlock, 0, s>>>(data, n, tile_sums, scanned)));
     return MQG_OK;
 }
 

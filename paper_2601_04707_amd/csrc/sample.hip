@@ -92,23 +92,6 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
     }
 }
 
-// Sum of tile_sums[0 .. blockIdx.x): what a tile's own workgroup adds up instead of a separate scan
-// launch when the tiles are few (kSelfPrefixTiles at most, i.e. at most 8 loads per thread).
-// Every thread of the workgroup must call it; `lds` needs kWavesPerBlock ints.
-constexpr int kSelfPrefixTiles = 2048;
-__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sums, int *lds) {
-    int part = 0;
-    for (int t = threadIdx.x; t < static_cast<int>(blockIdx.x); t += kBlock) part += tile_sums[t];
-    part = wave_sum(part);
-    __syncthreads();                                       // lds may still be read from an earlier use
-    if (lane_id() == 0) lds[threadIdx.x >> 6] = part;
-    __syncthreads();
-    int sum = 0;
-#pragma unroll
-    for (int k = 0; k < kWavesPerBlock; ++k) sum += lds[k];
-    return sum;
-}
-
 // One workgroup of 1024 threads: vals[0..n) -> exclusive scan in place; totals stored.
 __global__ void __launch_bounds__(1024)
 k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ addend,
