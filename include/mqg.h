@@ -349,6 +349,25 @@ int mqg_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys_dev, int64_t n, 
                              uint32_t *out_bitmap_dev, mqg_stream stream);
 
 /*
+ * The selection step of mqg_sample_blocks for one row on its own (paper
+ * Sec. III-A: s_node neighbours of a node drawn uniformly, here the k smallest
+ * random keys): among `count` candidates, each a (key, slot word) pair, the k
+ * first in the order (bit 31 of the slot word if `prioritised`, key, low 31
+ * bits of the slot word) are chosen - the binary radix select on wavefront
+ * ballots that the sampling kernels run after their threshold pass, exposed
+ * so that a test can feed it keys with ties.
+ *   keys_dev, slot_words_dev  device [count], 1 <= k <= count <= 256
+ *   ordered         non-zero: the candidates are stored in ascending slot
+ *                   order (as the one-wavefront-per-row path stores them), so
+ *                   equal keys are resolved by position; zero: by slot value
+ *                   (the hub path, whose candidates arrive in any order)
+ *   out_mask_dev    device [8] words: bit c of the 256-bit mask = candidate c chosen
+ */
+int mqg_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys_dev, const uint32_t *slot_words_dev,
+                              int32_t count, int32_t k, int32_t prioritised, int32_t ordered,
+                              uint32_t *out_mask_dev, mqg_stream stream);
+
+/*
  * Cache-prioritised neighbour sampling (paper Sec. I on global neighbour
  * sampling: the sampler prefers neighbours that are in the cache, which cuts
  * the number of distinct uncached rows a mini-batch needs).  After this call

@@ -403,6 +403,17 @@ int mqg_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys_dev, int64_t n, 
     return mqg::run_select_smallest_keys(ctx, keys_dev, n, k, out_bitmap_dev, static_cast<hipStream_t>(stream));
 }
 
+int mqg_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys_dev, const uint32_t *slot_words_dev, int32_t count,
+                              int32_t k, int32_t prioritised, int32_t ordered, uint32_t *out_mask_dev, mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (count < 1 || count > 256 || k < 1 || k > count)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_select_row_candidates: need 1 <= k <= count <= 256");
+    if (!keys_dev || !slot_words_dev || !out_mask_dev)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_select_row_candidates: NULL argument");
+    return mqg::run_select_row_candidates(ctx, keys_dev, slot_words_dev, count, k, prioritised ? 1 : 0, ordered ? 1 : 0,
+                                          out_mask_dev, static_cast<hipStream_t>(stream));
+}
+
 int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
                         const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
                         int64_t *stats_dev, mqg_stream stream) {

@@ -294,6 +294,25 @@ __device__ __forceinline__ void emit_selected_unordered(const uint64_t *ck, cons
     if (lane < k) emit_neighbour(col_idx, start, my_slot, out_base + rank, a);
 }
 
+// The per-row selection on caller-supplied candidates (mqg_select_row_candidates): one wavefront,
+// the same code path as k_sample / k_sample_prio after their threshold pass.
+template <bool PRIO, bool ORDERED>
+__global__ void __launch_bounds__(kWave)
+k_select_candidates(const uint64_t *__restrict__ keys, const uint32_t *__restrict__ slot_words, int cnt, int k,
+                    uint32_t *__restrict__ out_mask) {
+    constexpr int NCH = kCandidates / kWave;
+    uint32_t slot[NCH];
+    uint64_t sel[NCH];
+    select_candidates<NCH, PRIO, ORDERED>(keys, slot_words, cnt, k, slot, sel);
+    if (lane_id() == 0) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            out_mask[2 * c] = static_cast<uint32_t>(sel[c]);
+            out_mask[2 * c + 1] = static_cast<uint32_t>(sel[c] >> 32);
+        }
+    }
+}
+
 // Unconditional selection: k rounds, each finding the smallest (key, slot) pair above the
 // previous round's.  O(k*d/64) key evaluations; used when the threshold pass cannot be
 // trusted (fewer than k or more than kCandidates keys under the threshold) and in tests.
@@ -1007,6 +1026,15 @@ int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32
     if (p64 && !i64) return sample_blocks_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
     if (!p64 && i64) return sample_blocks_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
     return sample_blocks_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, seed_dev, fanouts, L, rng_seed, blocks, s);
+}
+
+int run_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys, const uint32_t *slot_words, int32_t cnt, int32_t k,
+                              int32_t prioritised, int32_t ordered, uint32_t *out_mask, hipStream_t s) {
+    if (prioritised && ordered) MQG_LAUNCH(ctx, "k_select_candidates", s, (k_select_candidates<true, true><<<1, kWave, 0, s>>>(keys, slot_words, cnt, k, out_mask)));
+    else if (prioritised) MQG_LAUNCH(ctx, "k_select_candidates", s, (k_select_candidates<true, false><<<1, kWave, 0, s>>>(keys, slot_words, cnt, k, out_mask)));
+    else if (ordered) MQG_LAUNCH(ctx, "k_select_candidates", s, (k_select_candidates<false, true><<<1, kWave, 0, s>>>(keys, slot_words, cnt, k, out_mask)));
+    else MQG_LAUNCH(ctx, "k_select_candidates", s, (k_select_candidates<false, false><<<1, kWave, 0, s>>>(keys, slot_words, cnt, k, out_mask)));
+    return MQG_OK;
 }
 
 // cache == nullptr switches the priority off; otherwise the membership bitmap is (re)built from cache->slot_of

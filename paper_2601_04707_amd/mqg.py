@@ -31,7 +31,7 @@ EXPORTS = [
     "mqg_sample_blocks", "mqg_gather_features", "mqg_sage_mean_aggregate", "mqg_sage_mean_aggregate_backward",
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
     "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
-    "mqg_select_smallest_keys", "mqg_sample_blocks_seed_dev",
+    "mqg_select_smallest_keys", "mqg_select_row_candidates", "mqg_sample_blocks_seed_dev",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -108,6 +108,8 @@ lib.mqg_sample_layerwise.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, cty
 MQG_LAYERWISE_LADIES, MQG_LAYERWISE_FASTGCN, MQG_LAYERWISE_DEBIAS = 0, 1, 2
 lib.mqg_select_smallest_keys.restype = ctypes.c_int
 lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
+lib.mqg_select_row_candidates.restype = ctypes.c_int
+lib.mqg_select_row_candidates.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]
 lib.mqg_sample_blocks_seed_dev.restype = ctypes.c_int
 lib.mqg_sample_blocks_seed_dev.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, _vp,
                                            ctypes.POINTER(CBlock), _vp]
@@ -360,6 +362,20 @@ def mqg_select_smallest_keys(ctx: Context, keys: torch.Tensor, k: int, stream=No
     n = keys.numel()
     words = torch.empty(max(1, (n + 31) // 32), dtype=torch.int32, device=keys.device)
     ctx.check(lib.mqg_select_smallest_keys(ctx.h, keys.data_ptr() if n else None, n, k, words.data_ptr(), _stream(stream)))
+    bits = (words.view(-1, 1) >> torch.arange(32, device=keys.device, dtype=torch.int32)) & 1
+    return bits.reshape(-1)[:n].bool()
+
+
+def mqg_select_row_candidates(ctx: Context, keys: torch.Tensor, slot_words: torch.Tensor, k: int, prioritised: bool = False,
+                              ordered: bool = True, stream=None) -> torch.Tensor:
+    """keys: device int64 (unsigned 64-bit patterns); slot_words: device int32 (bit 31 = comes after
+    every unmarked candidate when prioritised).  Returns a bool tensor: candidate chosen."""
+    assert keys.is_cuda and keys.dtype == torch.int64 and keys.is_contiguous()
+    assert slot_words.is_cuda and slot_words.dtype == torch.int32 and slot_words.numel() == keys.numel()
+    n = keys.numel()
+    words = torch.zeros(8, dtype=torch.int32, device=keys.device)
+    ctx.check(lib.mqg_select_row_candidates(ctx.h, keys.data_ptr(), slot_words.data_ptr(), n, k, int(prioritised), int(ordered),
+                                            words.data_ptr(), _stream(stream)))
     bits = (words.view(-1, 1) >> torch.arange(32, device=keys.device, dtype=torch.int32)) & 1
     return bits.reshape(-1)[:n].bool()
 
