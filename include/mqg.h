@@ -216,8 +216,8 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
  *                             scores_out (device double [num_nodes], may be NULL) receives
  *                             P(num_steps).  Membership is the deterministic top of the score, not
  *                             a draw from it.
- *   MQG_CACHE_RANDOM_WALK_SAMPLED  the same scores, membership drawn from them ("the final
- *                             sampling probability for the cache", text after Eq. 15): weighted
+ *   MQG_CACHE_RANDOM_WALK_SAMPLED  the same scores, membership drawn from them (the text after
+ *                             Eq. 15 takes P(L) as the probability of entering the cache): weighted
  *                             sampling without replacement by an exponential race, key_i =
  *                             ticket_i / P(num_steps)[i] in double (+inf for a zero score),
  *                             ticket_i = -log2(r_i / 2^64) in fixed point with 32 fractional
