@@ -152,6 +152,26 @@ def test_sampling_edge_cases(mqg):
         assert_blocks_equal(got, want)
 
 
+def test_eight_layers_until_the_frontier_is_the_whole_graph(mqg):
+    """The maximum number of layers; the outer blocks' source lists hold every node of the graph
+    (capacity bound min(N, ...)) and most sampled neighbours are already destinations."""
+    rp, ci = hub_graph(n=1500, edges=40_000, max_degree=400, seed=8)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts = [6, 5, 4, 4, 3, 3, 2, 2]
+    ctx = mqg.Context(g, 96, fanouts)
+    blocks = mqg.Blocks(g, 96, fanouts)
+    assert blocks.bounds[0][1] == n                               # capped by the graph size
+    for b, seeds in enumerate(synth.seed_batches(n, 96, 2, seed=5)):
+        got = hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 77 + b)
+        want = oracle.sample_blocks(rp.numpy(), ci.numpy(), seeds.numpy(), fanouts, 77 + b)
+        assert_blocks_equal(got, want)
+        reach = want[0].num_src
+        assert reach > 0.9 * (np.diff(rp.numpy()) > 0).sum()      # the frontier has saturated
+    with pytest.raises(mqg.MqgError):
+        mqg.Context(g, 96, [2] * 9)
+
+
 def test_sampling_is_deterministic_and_context_reusable(mqg):
     rp, ci = hub_graph(n=4000, edges=150_000, max_degree=900)
     g = mqg.Graph(to_dev(rp), to_dev(ci))
