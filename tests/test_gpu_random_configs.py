@@ -1,0 +1,72 @@
+"""Seeded random configurations of the sampler through the C ABI against the oracle: graph size and
+skew, index types, number of layers, fanouts, batch size, hub threshold, dedup path and cache
+priority all drawn at random, so that combinations no hand-written case lists are exercised
+(bit-exact blocks, gathered rows byte for byte)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_04707_amd import synth
+from gpu_util import assert_blocks_equal, hip_sample, to_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def mqg():
+    from paper_2601_04707_amd import mqg as m
+    assert torch.cuda.is_available()
+    return m
+
+
+def draw_config(rng):
+    n = int(rng.choice([3, 40, 700, 2500, 6000]))
+    mean_deg = float(rng.choice([1.5, 6, 30, 120]))
+    edges = max(4, int(n * mean_deg))
+    max_degree = int(min(n - 1, rng.choice([8, 70, 300, 2500])))
+    L = int(rng.integers(1, 5))
+    fanouts = [int(rng.choice([1, 2, 5, 10, 15, 25, 40, 64])) for _ in range(L)]
+    batch = int(min(n, rng.choice([1, 7, 64, 65, 200])))
+    return dict(n=n, edges=edges, max_degree=max(1, max_degree), fanouts=fanouts, batch=batch,
+                ptr=rng.choice([torch.int32, torch.int64]), idx=rng.choice([torch.int32, torch.int64]),
+                heavy=rng.choice([None, 64, 100, 500]), hash_dedup=bool(rng.integers(0, 2)),
+                prio_pct=rng.choice([None, None, 5, 50]), graph_seed=int(rng.integers(0, 1 << 30)),
+                rng_seed=int(rng.integers(0, 1 << 62)))
+
+
+@pytest.mark.parametrize("case", range(48))
+def test_random_configuration(mqg, case):
+    rng = np.random.default_rng(9000 + case)
+    c = draw_config(rng)
+    rp, ci = synth.chung_lu_graph(c["n"], c["edges"], max_degree=c["max_degree"], seed=c["graph_seed"],
+                                  ptr_dtype=c["ptr"], idx_dtype=c["idx"])
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    ctx = mqg.Context(g, c["batch"], c["fanouts"])
+    blocks = mqg.Blocks(g, c["batch"], c["fanouts"])
+    if c["heavy"] is not None:
+        ctx.set_option(mqg.MQG_OPT_HEAVY_DEGREE, int(c["heavy"]))
+    if c["hash_dedup"]:
+        ctx.set_option(mqg.MQG_OPT_DEDUP_HASH, 1)
+    dim = int(rng.choice([1, 8, 50, 150]))
+    feats = synth.node_features(n, dim, seed=3).pin_memory()
+    num_cached = 0 if c["prio_pct"] is None else n * int(c["prio_pct"]) // 100
+    cache = mqg.Cache(g, feats, num_cached)
+    mqg.mqg_build_cache(ctx, g, cache)
+    slot_of = None
+    if c["prio_pct"] is not None:
+        ctx.set_sampling_priority(cache)
+        slot_of = oracle.build_cache(rp.numpy(), num_cached).slot_of
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    for b, seeds in enumerate(synth.seed_batches(n, c["batch"], 2, seed=case)):
+        got = hip_sample(mqg, ctx, g, blocks, seeds, c["fanouts"], c["rng_seed"] + b)
+        want = oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), c["fanouts"], c["rng_seed"] + b, prio_slot_of=slot_of)
+        assert_blocks_equal(got, want)
+        x0 = torch.zeros((blocks.bounds[0][1], dim), dtype=torch.float32, device="cuda")
+        stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+        mqg.mqg_gather_features(ctx, cache, blocks.src_ids[0], blocks.sizes[0, 1:2], x0, stats)
+        torch.cuda.synchronize()
+        ns = want[0].num_src
+        assert x0[:ns].cpu().numpy().tobytes() == feats.numpy()[want[0].src_ids].tobytes()
+        assert int(stats.sum()) == ns
