@@ -70,3 +70,40 @@ def test_random_configuration(mqg, case):
         ns = want[0].num_src
         assert x0[:ns].cpu().numpy().tobytes() == feats.numpy()[want[0].src_ids].tobytes()
         assert int(stats.sum()) == ns
+
+
+@pytest.mark.parametrize("case", range(24))
+def test_random_layerwise_configuration(mqg, case):
+    """The layer-wise sampler (LADIES / FastGCN, with and without debiasing and row normalisation) on
+    random graph shapes, layer sizes and batch sizes: drawn nodes and block structure identical,
+    edge weights to 1e-6."""
+    rng = np.random.default_rng(7000 + case)
+    n = int(rng.choice([5, 60, 900, 4000]))
+    edges = max(4, int(n * float(rng.choice([2, 10, 60]))))
+    max_degree = max(1, int(min(n - 1, rng.choice([6, 80, 1500]))))
+    ptr, idx = rng.choice([torch.int32, torch.int64]), rng.choice([torch.int32, torch.int64])
+    rp, ci = synth.chung_lu_graph(n, edges, max_degree=max_degree, seed=int(rng.integers(0, 1 << 30)),
+                                  ptr_dtype=ptr, idx_dtype=idx)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    L = int(rng.integers(1, 4))
+    sizes = [int(rng.choice([1, 3, 40, 300, 2000])) for _ in range(L)]
+    batch = int(min(n, rng.choice([1, 9, 64, 130])))
+    fastgcn, debias, normalise = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
+    method = (mqg.MQG_LAYERWISE_FASTGCN if fastgcn else mqg.MQG_LAYERWISE_LADIES) | (mqg.MQG_LAYERWISE_DEBIAS if debias else 0)
+    ctx = mqg.Context(g, batch, [2] * L)
+    blocks = mqg.LayerwiseBlocks(g, batch, sizes)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    for b, seeds in enumerate(synth.seed_batches(n, batch, 2, seed=case)):
+        rng_seed = int(rng.integers(0, 1 << 62))
+        mqg.mqg_sample_layerwise(ctx, g, to_dev(seeds.to(g.idx_dtype)), sizes, rng_seed, blocks, normalise=normalise, method=method)
+        torch.cuda.synchronize()
+        want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, rng_seed, normalise=normalise, fastgcn=fastgcn, debias=debias)
+        hs = blocks.host_sizes()
+        for l, w in enumerate(want):
+            nd, ns, nnz, flags = hs[l]
+            assert (nd, ns, nnz, flags) == (w.num_dst, w.num_src, w.nnz, 0), (l, hs[l])
+            assert np.array_equal(blocks.src_ids[l][:ns].cpu().numpy().astype(np.int64), w.src_ids), l
+            assert np.array_equal(blocks.indptr[l][:nd + 1].cpu().numpy().astype(np.int64), w.indptr), l
+            assert np.array_equal(blocks.indices[l][:nnz].cpu().numpy(), w.indices), l
+            assert np.allclose(blocks.edge_w[l][:nnz].cpu().numpy(), w.edge_w, rtol=1e-6, atol=0), l
