@@ -107,3 +107,81 @@ def test_random_layerwise_configuration(mqg, case):
             assert np.array_equal(blocks.indptr[l][:nd + 1].cpu().numpy().astype(np.int64), w.indptr), l
             assert np.array_equal(blocks.indices[l][:nnz].cpu().numpy(), w.indices), l
             assert np.allclose(blocks.edge_w[l][:nnz].cpu().numpy(), w.edge_w, rtol=1e-6, atol=0), l
+
+
+def directed_graph(n, mean_out, seed, idx=torch.int64):
+    """A directed simple graph in CSR (row v = in-neighbours of v), skewed in-degrees, rows unsorted."""
+    rng = np.random.default_rng(seed)
+    m = int(n * mean_out)
+    dst = np.minimum((rng.pareto(1.3, m) * 3).astype(np.int64), n - 1)      # a few nodes receive most edges
+    dst = rng.permutation(n)[dst]
+    src = rng.integers(0, n, m)
+    keep = src != dst
+    pairs = np.unique(np.stack([dst[keep], src[keep]], 1), axis=0)
+    pairs = pairs[rng.permutation(len(pairs))]
+    order = np.argsort(pairs[:, 0], kind="stable")                          # rows grouped, neighbours in random order
+    pairs = pairs[order]
+    rp = np.zeros(n + 1, dtype=np.int64)
+    np.add.at(rp, pairs[:, 0] + 1, 1)
+    rp = np.cumsum(rp)
+    return torch.from_numpy(rp), torch.from_numpy(pairs[:, 1].copy()).to(idx)
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_directed_graph_all_paths(mqg, seed):
+    """The synthetic workloads are symmetrised; nothing in the library may rely on that.  A directed
+    graph with unsorted rows through node-wise sampling, the layer-wise sampler, the random-walk
+    cache scores and the Eq. 1-3 weights, each against the oracle."""
+    rp, ci = directed_graph(3000, 25, seed)
+    n = rp.numel() - 1
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    indeg = np.diff(rp_np)
+    outdeg = np.bincount(ci_np, minlength=n)
+    assert not np.array_equal(indeg, outdeg) and indeg.max() > 300
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts = [12, 6]
+    batch = 150
+    ctx = mqg.Context(g, batch, fanouts)
+    blocks = mqg.Blocks(g, batch, fanouts)
+    seeds = synth.seed_batches(n, batch, 1, seed=seed)[0]
+    got = hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 31)
+    want = oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), fanouts, 31)
+    assert_blocks_equal(got, want)
+
+    # Eq. 1-3 weights of the sampled blocks
+    for l, wb in enumerate(want):
+        ew = torch.zeros(blocks.bounds[l][2], dtype=torch.float32, device="cuda")
+        sw = torch.zeros(blocks.bounds[l][0], dtype=torch.float32, device="cuda")
+        mqg.mqg_gcn_edge_weights(ctx, g, blocks, l, ew, sw)
+        torch.cuda.synchronize()
+        ref_e, ref_s = oracle.gcn_edge_weights(rp_np, wb.src_ids, wb.indptr, wb.indices)
+        assert np.allclose(ew[:wb.nnz].cpu().numpy(), ref_e, rtol=1e-6, atol=0)
+        assert np.allclose(sw[:wb.num_dst].cpu().numpy(), ref_s, rtol=1e-6, atol=0)
+
+    # random-walk cache scores: bit-identical doubles
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[:60]
+    feats = synth.node_features(n, 6, seed=3).pin_memory()
+    cache = mqg.Cache(g, feats, n // 10)
+    scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+    mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(train), step_fanouts=[6, 12],
+                           scores_out=scores)
+    torch.cuda.synchronize()
+    want_scores = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), [6, 12])
+    assert np.array_equal(scores.cpu().numpy(), want_scores)
+    wc = oracle.build_cache_by_score(want_scores, n // 10, feats.numpy())
+    assert np.array_equal(cache.slot_of.cpu().numpy(), wc.slot_of)
+
+    # layer-wise sampler
+    sizes = [200, 100]
+    lb = mqg.LayerwiseBlocks(g, batch, sizes)
+    for method, kw in [(mqg.MQG_LAYERWISE_LADIES, {}), (mqg.MQG_LAYERWISE_FASTGCN | mqg.MQG_LAYERWISE_DEBIAS, dict(fastgcn=True, debias=True))]:
+        mqg.mqg_sample_layerwise(ctx, g, to_dev(seeds), sizes, 77, lb, normalise=True, method=method)
+        torch.cuda.synchronize()
+        wl = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 77, normalise=True, **kw)
+        hs = lb.host_sizes()
+        for l, w in enumerate(wl):
+            nd, ns, nnz, flags = hs[l]
+            assert (nd, ns, nnz, flags) == (w.num_dst, w.num_src, w.nnz, 0)
+            assert np.array_equal(lb.src_ids[l][:ns].cpu().numpy().astype(np.int64), w.src_ids)
+            assert np.array_equal(lb.indices[l][:nnz].cpu().numpy(), w.indices)
+            assert np.allclose(lb.edge_w[l][:nnz].cpu().numpy(), w.edge_w, rtol=1e-6, atol=0)
