@@ -82,9 +82,9 @@ def _load():
     lib.orc_build_cache_by_score.restype = ctypes.c_int
     lib.orc_build_cache_by_score.argtypes = [i64, vp, i64, vp, vp]
     lib.orc_ladies_probabilities.restype = None
-    lib.orc_ladies_probabilities.argtypes = [vp, vp, i64, vp, i64, vp]
+    lib.orc_ladies_probabilities.argtypes = [vp, vp, i64, vp, i64, ctypes.c_int, vp]
     lib.orc_ladies_block.restype = i64
-    lib.orc_ladies_block.argtypes = [vp, vp, i64, vp, i64, i64, i64, u64, ctypes.c_int, ctypes.c_int, ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]
+    lib.orc_ladies_block.argtypes = [vp, vp, i64, vp, i64, i64, i64, u64, ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_int, i64, i64, vp, vp, vp, vp, vp]
     lib.orc_debias_coefficients.restype = None
     lib.orc_debias_coefficients.argtypes = [vp, i64, i64, vp]
     lib.orc_exp_ticket.restype = u64
@@ -302,21 +302,22 @@ def debias_coefficients(p_drawn, population: int) -> np.ndarray:
     return beta[:p.shape[0]]
 
 
-def ladies_probabilities(row_ptr, col_idx, dst=None) -> np.ndarray:
-    """Eq. 7 for the rows dst; dst=None: all rows (FastGCN's batch-independent probabilities)."""
+def ladies_probabilities(row_ptr, col_idx, dst=None, flat: bool = False) -> np.ndarray:
+    """Eq. 7 for the rows dst; dst=None: all rows (FastGCN's batch-independent probabilities);
+    flat: proportional to the column norm instead of its square (Eq. 10)."""
     rp, ci = _i64(row_ptr), _i64(col_idx)
     n = rp.shape[0] - 1
     p = np.zeros(max(n, 1), dtype=np.float64)
     if dst is None:
-        _load().orc_ladies_probabilities(_p(rp), _p(ci), n, None, 0, _p(p))
+        _load().orc_ladies_probabilities(_p(rp), _p(ci), n, None, 0, 1 if flat else 0, _p(p))
     else:
         d = _i64(dst)
-        _load().orc_ladies_probabilities(_p(rp), _p(ci), n, _p(d), d.shape[0], _p(p))
+        _load().orc_ladies_probabilities(_p(rp), _p(ci), n, _p(d), d.shape[0], 1 if flat else 0, _p(p))
     return p[:n]
 
 
 def ladies_blocks(row_ptr, col_idx, seeds, layer_sizes: Sequence[int], rng_seed: int, normalise: bool = True,
-                  want_mass: bool = False, fastgcn: bool = False, debias: bool = False) -> List[WeightedBlock]:
+                  want_mass: bool = False, fastgcn: bool = False, debias: bool = False, flat: bool = False) -> List[WeightedBlock]:
     """LADIES mini-batch: blocks[L-1] has the seeds as rows; layer_sizes[l] nodes are drawn as the
     sources of blocks[l], which are the rows of blocks[l-1]."""
     rp, ci, dst = _i64(row_ptr), _i64(col_idx), _i64(seeds)
@@ -335,7 +336,7 @@ def ladies_blocks(row_ptr, col_idx, seeds, layer_sizes: Sequence[int], rng_seed:
         ew = np.empty(cap_nnz, dtype=np.float64)
         mass = np.zeros(max(n, 1), dtype=np.uint64) if want_mass else None
         ns = lib.orc_ladies_block(_p(rp), _p(ci), n, _p(dst), nd, s, l, ctypes.c_uint64(rng_seed & 0xFFFFFFFFFFFFFFFF),
-                                  1 if normalise else 0, 1 if fastgcn else 0, 1 if debias else 0, cap_src, cap_nnz,
+                                  1 if normalise else 0, 1 if fastgcn else 0, 1 if debias else 0, 1 if flat else 0, cap_src, cap_nnz,
                                   _p(src), _p(indptr),
                                   _p(idx), _p(ew),
                                   None if mass is None else _p(mass))

@@ -23,9 +23,10 @@
  *   - orc_random_walk_scores / orc_build_cache_by_score : Eq. 14-15, the
  *                            short-random-walk probabilities P^(L) used when
  *                            the training set is a small part of the graph.
- *   - orc_exp_ticket / orc_build_cache_drawn_by_score : "the final sampling
- *                            probability for the cache is given by P^(L)"
- *                            (text after Eq. 15) taken literally: membership
+ *   - orc_exp_ticket / orc_build_cache_drawn_by_score : the text after
+ *                            Eq. 15 takes P^(L) as the probability with
+ *                            which the cache is sampled; taken literally:
+ *                            membership
  *                            is drawn with probability proportional to the
  *                            score, by weighted sampling with random keys
  *                            (Efraimidis and Spirakis, cited in Sec. III-B).
@@ -51,7 +52,13 @@
  *                            of the current layer's nodes with probability
  *                            proportional to the squared column norm of the
  *                            row-selected normalised adjacency; a sampled
- *                            node's column is scaled by 1 / (s p).
+ *                            node's column is scaled by 1 / (s p).  The
+ *                            "flat" variants (Sec. III-B "Calibrate and
+ *                            Debias LS", Eq. 10) draw in proportion to the
+ *                            column norm itself, not its square: the
+ *                            variance of the sampled product P (H W) is
+ *                            least for p_i proportional to |P_{*,i}| |(HW)_i|
+ *                            and the row norms of H W are taken as uniform.
  *   - orc_gather           : Sec. IV "Mini-Batch Transfer To GPU": features
  *                            of nodes absent from the GPU cache come from
  *                            host memory, the rest from the cache; the
@@ -810,7 +817,7 @@ int orc_build_cache_drawn_by_score(int64_t num_nodes, const double *scores, int6
  * paragraph), the squared column norms of P itself.
  */
 void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
-                              const int64_t *dst, int64_t num_dst, double *p)
+                              const int64_t *dst, int64_t num_dst, int flat, double *p)
 {
     for (int64_t i = 0; i < num_nodes; ++i) p[i] = 0.0;
     if (!dst) num_dst = num_nodes;                 /* every row: the batch-independent norms of FastGCN */
@@ -824,6 +831,8 @@ void orc_ladies_probabilities(const int64_t *row_ptr, const int64_t *col_idx, in
             p[i] += 1.0 / (dv * di);
         }
     }
+    if (flat)                                      /* the norm itself instead of its square */
+        for (int64_t i = 0; i < num_nodes; ++i) p[i] = sqrt(p[i]);
     double total = 0.0;
     for (int64_t i = 0; i < num_nodes; ++i) total += p[i];
     if (total > 0.0)
@@ -893,12 +902,19 @@ void orc_debias_coefficients(const double *p, int64_t s, int64_t n, double *beta
  * nodes in the order of the race, population = the candidates) instead of
  * 1 / (s p): weight = P_vi * beta_i.  When every candidate is drawn beta is 1.
  *
+ * flat != 0 (the "+flat" variants, Eq. 10): nodes are drawn with probability
+ * proportional to sqrt(q_i), the column norm itself.  In the race the ticket is
+ * squared instead of the rate being rooted - key_i = ((ticket_i * ticket_i) *
+ * (deg_i + 1)) / mass_i, the same order as ticket_i / sqrt(q_i) - so that the
+ * keys need multiplications and one division only; p_i = sqrt(q_i) / sum_j
+ * sqrt(q_j) in the weights and in the debiased coefficients.
+ *
  * mass_out (may be NULL): num_nodes masses.  Returns the number of sources,
  * -2 when cap_nnz or cap_src is too small or memory runs out.
  */
 int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t num_nodes,
                          const int64_t *dst, int64_t num_dst, int64_t s_layer, int64_t layer,
-                         uint64_t rng_seed, int normalise, int fastgcn, int debias,
+                         uint64_t rng_seed, int normalise, int fastgcn, int debias, int flat,
                          int64_t cap_src, int64_t cap_nnz, int64_t *src, int64_t *indptr,
                          int32_t *indices, double *edge_w, uint64_t *mass_out)
 {
@@ -922,10 +938,10 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
         if (!mass[i]) continue;
         double deg1 = (double)(row_ptr[i + 1] - row_ptr[i] + 1);
         double ticket = (double)orc_exp_ticket(orc_key(rng_seed, ORC_LAYERWISE_TAG + layer, i, 0));
-        cand[num_cand].key = (ticket * deg1) / (double)mass[i];
+        cand[num_cand].key = flat ? ((ticket * ticket) * deg1) / (double)mass[i] : (ticket * deg1) / (double)mass[i];
         cand[num_cand].id = i;
         ++num_cand;
-        q_total += (double)mass[i] / deg1;
+        q_total += flat ? sqrt((double)mass[i] / deg1) : (double)mass[i] / deg1;
     }
     int64_t num_src = num_cand < s_layer ? num_cand : s_layer;
     if (num_src > cap_src) { free(mass); free(pos); free(cand); return -2; }
@@ -947,7 +963,8 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
         } else {
             for (int64_t r = 0; r < num_src; ++r) {              /* cand[0..num_src) is in draw order */
                 int64_t i = cand[r].id;
-                p_drawn[r] = ((double)mass[i] / (double)(row_ptr[i + 1] - row_ptr[i] + 1)) / q_total;
+                double q_i = (double)mass[i] / (double)(row_ptr[i + 1] - row_ptr[i] + 1);
+                p_drawn[r] = (flat ? sqrt(q_i) : q_i) / q_total;
             }
             orc_debias_coefficients(p_drawn, num_src, num_cand, beta);
             for (int64_t r = 0; r < num_src; ++r) beta_of_pos[pos[cand[r].id]] = beta[r];
@@ -968,7 +985,7 @@ int64_t orc_ladies_block(const int64_t *row_ptr, const int64_t *col_idx, int64_t
             if (nnz >= cap_nnz) { free(mass); free(pos); free(cand); free(beta_of_pos); return -2; }
             double di = (double)(row_ptr[i + 1] - row_ptr[i] + 1);
             double P_vi = 1.0 / sqrt(dv * di);
-            double p_i = ((double)mass[i] / di) / q_total;
+            double p_i = (flat ? sqrt((double)mass[i] / di) : (double)mass[i] / di) / q_total;
             indices[nnz] = (int32_t)pos[i];
             edge_w[nnz] = debias ? P_vi * beta_of_pos[pos[i]] : P_vi / ((double)num_src * p_i);
             ++nnz;

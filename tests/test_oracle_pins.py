@@ -932,6 +932,103 @@ def test_fastgcn_probabilities_and_batch_independent_draw():
         assert set(ids.tolist()) == (set(ci[rp[v]:rp[v + 1]].tolist()) | {v}) & set(raw.src_ids.tolist())
 
 
+# ------------------------------------------------------------------------- "flat" probabilities (Eq. 10)
+
+def test_flat_probabilities_are_the_column_norms_and_minimise_the_variance():
+    """p_i proportional to ||R P[:, i]|| (not squared).  Pinned by the dense norms and by what the
+    paper gives as their reason: with rows of H W of equal norm, this p minimises the variance
+    sum_i ||R P[:, i]||^2 ||(HW)_i||^2 / p_i of the sampled product over all distributions - checked
+    against the squared-norm probabilities, the uniform ones and random perturbations."""
+    rp, ci = tiny_graph(120, 1400, seed=61)
+    P = dense_gcn_operator(rp, ci)
+    rows = np.array([7, 0, 119, 33, 64, 90], dtype=np.int64)
+    norms = np.sqrt((P[rows] ** 2).sum(axis=0))
+    want = norms / norms.sum()
+    got = oracle.ladies_probabilities(rp, ci, rows, flat=True)
+    assert np.allclose(got, want, rtol=1e-12, atol=1e-18) and abs(got.sum() - 1) < 1e-12
+    assert np.allclose(oracle.ladies_probabilities(rp, ci, flat=True),
+                       np.sqrt((P ** 2).sum(axis=0)) / np.sqrt((P ** 2).sum(axis=0)).sum(), rtol=1e-12)
+    support = norms > 0
+    variance = lambda p: float((norms[support] ** 2 / p[support]).sum())
+    best = variance(got)
+    squared = oracle.ladies_probabilities(rp, ci, rows)
+    uniform = support / support.sum()
+    assert best < variance(squared) and best < variance(uniform)
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        q = got * np.exp(0.2 * rng.standard_normal(len(got)))
+        assert best <= variance(q / q[support].sum()) + 1e-12
+
+
+def test_flat_draw_restated_first_pick_and_weights():
+    rp, ci = tiny_graph(400, 6000, seed=62)
+    n = len(rp) - 1
+    deg1 = (np.diff(rp) + 1).astype(np.float64)
+    seeds = np.random.default_rng(5).choice(n, 24, replace=False)
+    # the draw: squared tickets over q, i.e. tickets over sqrt(q)
+    b = oracle.ladies_blocks(rp, ci, seeds, [40], 77, want_mass=True, flat=True, normalise=False)[0]
+    cand = np.nonzero(b.mass)[0]
+    t = np.array([oracle.exp_ticket(oracle.key(77, 64, int(i), 0)) for i in cand], dtype=np.float64)
+    key = ((t * t) * deg1[cand]) / b.mass[cand].astype(np.float64)
+    assert np.array_equal(b.src_ids, np.sort(cand[np.lexsort((cand, key))[:40]]))
+    exact = [(int(oracle.exp_ticket(oracle.key(77, 64, int(i), 0))) ** 2 * (int(deg1[i])), int(b.mass[i])) for i in cand]
+    from fractions import Fraction
+    order_exact = sorted(range(len(cand)), key=lambda c: (Fraction(exact[c][0], exact[c][1]), int(cand[c])))
+    assert np.array_equal(b.src_ids, np.sort(cand[order_exact[:40]]))        # double rounding changes no decision here
+    plain = oracle.ladies_blocks(rp, ci, seeds, [40], 77)[0]
+    assert not np.array_equal(plain.src_ids, b.src_ids)                      # another distribution than Eq. 7's
+    # weights: P_vi / (s p_i) with the flat p
+    P = dense_gcn_operator(rp, ci)
+    p = oracle.ladies_probabilities(rp, ci, seeds, flat=True)
+    for r, v in enumerate(seeds):
+        e = slice(b.indptr[r], b.indptr[r + 1])
+        ids = b.src_ids[b.indices[e]]
+        assert np.allclose(b.edge_w[e] * 40 * p[ids], P[v, ids], rtol=1e-9)
+
+
+def test_flat_first_pick_follows_the_flat_probabilities():
+    rp, ci = tiny_graph(30, 120, seed=54)
+    rows = np.array([2, 11, 20], dtype=np.int64)
+    p = oracle.ladies_probabilities(rp, ci, rows, flat=True)
+    p2 = oracle.ladies_probabilities(rp, ci, rows)
+    assert np.abs(p - p2).max() > 0.02                                      # the two distributions differ visibly
+    trials = 20000
+    cnt = np.zeros(30)
+    for seed in range(trials):
+        cnt[oracle.ladies_blocks(rp, ci, rows, [1], seed, flat=True)[0].src_ids[0]] += 1
+    assert np.all(cnt[p == 0] == 0)
+    assert np.all(np.abs(cnt / trials - p) < 4.5 * np.sqrt(p * (1 - p) / trials) + 1e-9)
+    assert np.any(np.abs(cnt / trials - p2) > 6 * np.sqrt(p2 * (1 - p2) / trials))   # and not Eq. 7's
+
+
+def test_flat_with_equal_norms_draws_as_the_plain_method_and_combines_with_debias():
+    # a cycle: every column of P has the same norm, so squaring the tickets changes no order
+    n = 40
+    rp = np.arange(0, 2 * n + 1, 2, dtype=np.int64)
+    ci = np.array([[(v - 1) % n, (v + 1) % n] for v in range(n)], dtype=np.int64).reshape(-1)
+    seeds = np.arange(0, n, 3, dtype=np.int64)
+    a = oracle.ladies_blocks(rp, ci, seeds, [12], 3, fastgcn=True)[0]
+    b = oracle.ladies_blocks(rp, ci, seeds, [12], 3, fastgcn=True, flat=True)[0]
+    assert np.array_equal(a.src_ids, b.src_ids) and np.allclose(a.edge_w, b.edge_w, rtol=1e-12)
+    # flat + debias: the coefficients are those of Eq. 12 for the flat probabilities in race order
+    rp2, ci2 = tiny_graph(200, 2400, seed=63)
+    rows = np.random.default_rng(2).choice(200, 16, replace=False)
+    blk = oracle.ladies_blocks(rp2, ci2, rows, [25], 9, flat=True, debias=True, normalise=False, want_mass=True)[0]
+    deg1 = (np.diff(rp2) + 1).astype(np.float64)
+    cand = np.nonzero(blk.mass)[0]
+    t = np.array([oracle.exp_ticket(oracle.key(9, 64, int(i), 0)) for i in cand], dtype=np.float64)
+    key = ((t * t) * deg1[cand]) / blk.mass[cand].astype(np.float64)
+    drawn = cand[np.lexsort((cand, key))[:25]]
+    p = oracle.ladies_probabilities(rp2, ci2, rows, flat=True)
+    beta = oracle.debias_coefficients(p[drawn], len(cand))
+    beta_of = dict(zip(drawn.tolist(), beta.tolist()))
+    P = dense_gcn_operator(rp2, ci2)
+    for r, v in enumerate(rows):
+        e = slice(blk.indptr[r], blk.indptr[r + 1])
+        ids = blk.src_ids[blk.indices[e]]
+        assert np.allclose(blk.edge_w[e], [P[v, i] * beta_of[int(i)] for i in ids], rtol=1e-9)
+
+
 # ------------------------------------------------------------------------- debiased coefficients (Eq. 12)
 
 def test_debias_coefficients_closed_forms():
