@@ -324,11 +324,20 @@ int mqg_sample_blocks_seed_dev(mqg_ctx *ctx, const mqg_graph *g, const void *see
  * q_j: the coefficient of a node is a_r (1 - p_0 - ... - p_{r-1}) / p_r when it
  * is drawn and becomes (1 - a_u) beta + a_u at every later draw u; when every
  * candidate is drawn, beta = 1.  Computed in double.
+ * method | MQG_LAYERWISE_FLAT (the "+flat" variants, paper Eq. 10): nodes are
+ * drawn with probability proportional to sqrt(q_i), the column norm itself
+ * instead of its square - the distribution that minimises the variance of the
+ * sampled product P (H W) when the rows of H W have equal norms, which is the
+ * assumption the paper states (the printed right-hand side names the unknown
+ * H W).  key_i = ((ticket_i * ticket_i) * (deg_i + 1)) / mass_i, the order of
+ * ticket_i / sqrt(q_i); p_i = sqrt(q_i) / sum_j sqrt(q_j) in the weights and in
+ * the debiased coefficients.  The three flags combine freely.
  * The first call allocates context scratch of about 20 bytes per graph node
  * (8 more for FastGCN) and synchronises the stream once.  Feed the blocks to
  * mqg_weighted_aggregate with self_w == NULL.
  */
-typedef enum { MQG_LAYERWISE_LADIES = 0, MQG_LAYERWISE_FASTGCN = 1, MQG_LAYERWISE_DEBIAS = 2 } mqg_layerwise_method;
+typedef enum { MQG_LAYERWISE_LADIES = 0, MQG_LAYERWISE_FASTGCN = 1, MQG_LAYERWISE_DEBIAS = 2,
+               MQG_LAYERWISE_FLAT = 4 } mqg_layerwise_method;
 
 int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev, int32_t num_seeds,
                          const int32_t *layer_sizes, int32_t num_layers, uint64_t rng_seed,

@@ -371,7 +371,7 @@ int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev
     if (rc != MQG_OK) return rc;
     if (!layer_sizes || !blocks || !edge_w) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: NULL layer_sizes, blocks or edge_w");
     if (L < 1 || L > MQG_MAX_LAYERS) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: num_layers outside 1..MQG_MAX_LAYERS");
-    if (method < 0 || method > (MQG_LAYERWISE_FASTGCN | MQG_LAYERWISE_DEBIAS))
+    if (method < 0 || method > (MQG_LAYERWISE_FASTGCN | MQG_LAYERWISE_DEBIAS | MQG_LAYERWISE_FLAT))
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: unknown method");
     if (num_seeds < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: negative num_seeds");
     if (num_seeds > 0 && !seeds_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_sample_layerwise: seeds_dev is NULL");

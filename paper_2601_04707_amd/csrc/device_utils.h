@@ -179,7 +179,11 @@ __device__ __forceinline__ uint64_t mix64(uint64_t z) {
 // An exponential variate from 64 random bits in integer arithmetic: -log2(r / 2^64) with 32
 // fractional bits (r = 0 counts as 1).  With m = r << lz in [2^63, 2^64) the integer part is
 // lz + 1; the fraction of log2(m / 2^63) comes bit by bit from repeated squaring (a square that
-// reaches 2 emits a one and is halved), squares truncated to 64 bits.
+// reaches 2 emits a one and is halved), squares truncated to 64 bits.  The step is written without
+// a data-dependent branch (the renormalising shift is 0 or 1) so that the loop compiles to straight
+// vector code: with a branch the compiler wraps the low product in an exec-mask save/restore, and
+// one build of a kernel around that form returned wrong tickets, different from run to run, in
+// every workgroup but the first of a compute unit.
 __device__ __forceinline__ uint64_t exp_ticket64(uint64_t r) {
     if (r == 0) r = 1;
     const int lz = __clzll(static_cast<long long>(r));
@@ -187,9 +191,10 @@ __device__ __forceinline__ uint64_t exp_ticket64(uint64_t r) {
 #pragma unroll 4
     for (int b = 0; b < 32; ++b) {
         const uint64_t hi = __umul64hi(m, m), lo = m * m;
-        const bool one = (hi >> 63) != 0;
-        frac = (frac << 1) | (one ? 1u : 0u);
-        m = one ? hi : ((hi << 1) | (lo >> 63));
+        const uint64_t one = hi >> 63;
+        frac = (frac << 1) | one;
+        const uint64_t sh = one ^ 1;                       // not yet at 2: renormalise by one bit
+        m = (hi << sh) | ((lo >> 63) & sh);
     }
     return (static_cast<uint64_t>(lz + 1) << 32) - frac;
 }

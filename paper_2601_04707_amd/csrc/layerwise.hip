@@ -9,7 +9,8 @@
 //                    q_i = mass[i] / (deg_i + 1) is 2^40 times the squared column norm of Eq. 7.
 //                    Touched nodes are marked in the context's node bitmap.
 //   bitmap -> list   the candidates (Eq. 6), ascending (word popcounts, scan, emit)
-//   k_lw_keys        exponential race: key = ticket * (deg_i + 1) / mass[i] in doubles, ticket from
+//   k_lw_keys        exponential race: key = ticket * (deg_i + 1) / mass[i] in doubles (the "flat"
+//                    variants, Eq. 10, draw in proportion to sqrt(q_i): ticket^2 in place of ticket), ticket from
 //                    exp_ticket64; partial sums of q per workgroup, added up in a fixed order
 //   k_lw_select      radix select of the s-th smallest 64-bit key pattern, most significant byte
 //                    first: one launch per byte, every workgroup derives the prefix found so far
@@ -140,12 +141,24 @@ k_lw_emit(uint32_t *__restrict__ bitmap, int64_t words, const int32_t *__restric
     }
 }
 
+// The race key of a candidate and the measure its probability is proportional to.  Plain: rate
+// q = mass / (deg + 1).  Flat (paper Eq. 10: in proportion to the column norm, not its square): rate
+// sqrt(q); the race compares ticket / sqrt(q), and squaring that keeps the order with nothing but
+// multiplications and one division, each rounded once, as the CPU statement of the same steps does.
+__device__ __forceinline__ double lw_race_key(double ticket, double deg1, double m, int flat) {
+    return flat ? ((ticket * ticket) * deg1) / m : (ticket * deg1) / m;
+}
+__device__ __forceinline__ double lw_measure(double m, double deg1, int flat) {
+    const double q = m / deg1;
+    return flat ? sqrt(q) : q;
+}
+
 // race keys of the candidates and the per-workgroup partial sums of q (a fixed launch shape, so the
 // sums are the same from run to run)
 template <typename PtrT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
-          const unsigned long long *__restrict__ mass, uint64_t tag_hash, uint64_t *__restrict__ key64,
+          const unsigned long long *__restrict__ mass, uint64_t tag_hash, int flat, uint64_t *__restrict__ key64,
           double *__restrict__ q_part) {
     __shared__ double lds[kWavesPerBlock];
     const int64_t n = *n_cand;
@@ -156,9 +169,9 @@ k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, co
         const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
         const double m = static_cast<double>(mass[i]);
         const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
-        const double key = (ticket * deg1) / m;
+        const double key = lw_race_key(ticket, deg1, m, flat);
         key64[c] = static_cast<uint64_t>(__double_as_longlong(key));
-        q += m / deg1;
+        q += lw_measure(m, deg1, flat);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
@@ -283,9 +296,11 @@ k_lw_zero_i32(int32_t *__restrict__ p, int64_t n) {
 // by beta[li] instead: P_vi * beta.
 template <typename PtrT>
 __device__ __forceinline__ double lw_raw_weight(const PtrT *__restrict__ row_ptr, const unsigned long long *__restrict__ mass,
-                                                double scale, double dv, int64_t i, const double *__restrict__ beta, int32_t li) {
+                                                double scale, double dv, int64_t i, const double *__restrict__ beta, int32_t li,
+                                                int flat) {
     const double di = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
     if (beta) return beta[li] / sqrt(dv * di);
+    if (flat) return scale / (sqrt(static_cast<double>(mass[i]) / di) * sqrt(dv * di));   // p_i = sqrt(q_i) / total
     return scale * di / (static_cast<double>(mass[i]) * sqrt(dv * di));
 }
 
@@ -295,7 +310,7 @@ template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
            const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
-           const double *__restrict__ q_total, const double *__restrict__ beta, int32_t *__restrict__ counts,
+           const double *__restrict__ q_total, const double *__restrict__ beta, int flat, int32_t *__restrict__ counts,
            double *__restrict__ psum) {
     const int lane = lane_id();
     const int64_t n = sizes[0] * kRowChunks;
@@ -313,7 +328,7 @@ k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, c
         double acc = 0.0;
         if (c == 0 && local_of[v] >= 0) {
             cnt = 1;
-            if (lane == 0) acc = lw_raw_weight(row_ptr, mass, scale, dv, v, beta, local_of[v]);
+            if (lane == 0) acc = lw_raw_weight(row_ptr, mass, scale, dv, v, beta, local_of[v], flat);
         }
         int64_t jb, je;
         chunk_range(d, c, &jb, &je);
@@ -324,7 +339,7 @@ k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, c
                 const int64_t i = static_cast<int64_t>(col_idx[start + j]);
                 const int32_t li = local_of[i];
                 in = li >= 0;
-                if (in) acc += lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li);
+                if (in) acc += lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li, flat);
             }
             cnt += popc64(ballot64(in));
         }
@@ -355,7 +370,7 @@ template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
           const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
-          const double *__restrict__ q_total, const double *__restrict__ beta, const int32_t *__restrict__ offs,
+          const double *__restrict__ q_total, const double *__restrict__ beta, int flat, const int32_t *__restrict__ offs,
           const double *__restrict__ psum, int32_t *__restrict__ indices, float *__restrict__ edge_w, int normalise,
           int64_t cap_nnz) {
     const int lane = lane_id();
@@ -383,7 +398,7 @@ k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
             if (self_pos >= 0) {
                 if (lane == 0 && pos < cap_nnz) {
                     indices[pos] = self_pos;
-                    edge_w[pos] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, v, beta, self_pos) * inv_sum);
+                    edge_w[pos] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, v, beta, self_pos, flat) * inv_sum);
                 }
                 pos += 1;
             }
@@ -403,7 +418,7 @@ k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
                 const int64_t p = pos + popc64(m & lanes_below(lane));
                 if (p < cap_nnz) {
                     indices[p] = li;
-                    edge_w[p] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li) * inv_sum);
+                    edge_w[p] = static_cast<float>(lw_raw_weight(row_ptr, mass, scale, dv, i, beta, li, flat) * inv_sum);
                 }
             }
             pos += popc64(m);
@@ -417,7 +432,7 @@ k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_drawn_keys(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes,
-                const unsigned long long *__restrict__ mass, uint64_t tag_hash, uint64_t *__restrict__ dkey,
+                const unsigned long long *__restrict__ mass, uint64_t tag_hash, int flat, uint64_t *__restrict__ dkey,
                 double *__restrict__ dq) {
     const int64_t ns = sizes[1];
     const int64_t pos = int64_t(blockIdx.x) * kBlock + threadIdx.x;
@@ -426,8 +441,8 @@ k_lw_drawn_keys(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ src_i
     const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
     const double m = static_cast<double>(mass[i]);
     const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
-    dkey[pos] = static_cast<uint64_t>(__double_as_longlong((ticket * deg1) / m));
-    dq[pos] = m / deg1;
+    dkey[pos] = static_cast<uint64_t>(__double_as_longlong(lw_race_key(ticket, deg1, m, flat)));
+    dq[pos] = lw_measure(m, deg1, flat);
 }
 
 // order[r] = source position of the r-th drawn node: the race order is ascending (key, id), and
@@ -542,9 +557,10 @@ static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t 
 
 template <typename PtrT, typename IdxT>
 static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, int32_t num_seeds,
-                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, bool fastgcn, bool debias,
+                                 const int32_t *layer_sizes, int32_t L, uint64_t rng_seed, int32_t normalise, bool fastgcn, bool debias, bool flat_p,
                                  mqg_block *blocks, float *const *edge_w, hipStream_t s) {
     LayerwiseScratch &w = ctx->lw;
+    const int flat = flat_p ? 1 : 0;
     const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
     const IdxT *col_idx = static_cast<const IdxT *>(g->col_idx);
     const int64_t n = ctx->num_nodes;
@@ -593,7 +609,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         // race keys, ranking
         const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
-                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_cand, mass, tag_hash, w.key64, w.q_part)));
+                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_cand, mass, tag_hash, flat, w.key64, w.q_part)));
         MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total)));
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
@@ -614,7 +630,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
             const int64_t src_cap = std::min<int64_t>(n, layer_sizes[l]);
             const int sgrid = static_cast<int>(std::max<int64_t>(1, ceil_div(src_cap, kBlock)));
             MQG_LAUNCH(ctx, "k_lw_drawn_keys", s,
-                       (k_lw_drawn_keys<PtrT, IdxT><<<sgrid, kBlock, 0, s>>>(row_ptr, src_ids, b.sizes, mass, tag_hash, w.dkey, w.dq)));
+                       (k_lw_drawn_keys<PtrT, IdxT><<<sgrid, kBlock, 0, s>>>(row_ptr, src_ids, b.sizes, mass, tag_hash, flat, w.dkey, w.dq)));
             MQG_LAUNCH(ctx, "k_lw_draw_order", s, (k_lw_draw_order<<<sgrid, kBlock, 0, s>>>(w.dkey, b.sizes, w.order)));
             MQG_LAUNCH(ctx, "k_lw_debias", s,
                        (k_lw_debias<<<1, kBlock, 0, s>>>(w.order, w.dq, w.q_total, b.sizes, n_cand, w.chunk_sum, w.beta)));
@@ -627,7 +643,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                    (k_lw_zero_i32<<<static_cast<int>(ceil_div(chunks_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, chunks_cap + 1)));
         MQG_LAUNCH(ctx, "k_lw_count", s,
                    (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
-                                                                         beta, w.chunk_offs, w.chunk_sum)));
+                                                                         beta, flat, w.chunk_offs, w.chunk_sum)));
         rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
         if (rc != MQG_OK) return rc;
         MQG_LAUNCH(ctx, "k_lw_indptr", s,
@@ -635,7 +651,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                                                                                                     l == L - 1 ? w.flags : nullptr)));
         MQG_LAUNCH(ctx, "k_lw_fill", s,
                    (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
-                                                                        beta, w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
+                                                                        beta, flat, w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
                                                                         b.cap_nnz)));
         if (l == L - 1) MQG_LAUNCH(ctx, "k_lw_clear_flags", s, (k_lw_clear_flags<<<1, 64, 0, s>>>(w.flags)));
         const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
@@ -669,6 +685,7 @@ int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, in
                          hipStream_t s) {
     const bool fg = (method & MQG_LAYERWISE_FASTGCN) != 0;
     const bool db = (method & MQG_LAYERWISE_DEBIAS) != 0;
+    const bool fl = (method & MQG_LAYERWISE_FLAT) != 0;
     int64_t rows_cap = num_seeds;
     for (int l = 0; l < L; ++l) rows_cap = std::max<int64_t>(rows_cap, std::min<int64_t>(ctx->num_nodes, layer_sizes[l]));
     int rc = ensure_layerwise_scratch(ctx, rows_cap, s);
@@ -684,10 +701,10 @@ int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, in
         ctx->lw.fg_ready = false;
     }
     const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
-    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
-    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
-    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, blocks, edge_w, s);
+    if (p64 && i64) return sample_layerwise_impl<int64_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, fl, blocks, edge_w, s);
+    if (p64) return sample_layerwise_impl<int64_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, fl, blocks, edge_w, s);
+    if (i64) return sample_layerwise_impl<int32_t, int64_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, fl, blocks, edge_w, s);
+    return sample_layerwise_impl<int32_t, int32_t>(ctx, g, seeds, num_seeds, layer_sizes, L, rng_seed, normalise, fg, db, fl, blocks, edge_w, s);
 }
 
 }  // namespace mqg

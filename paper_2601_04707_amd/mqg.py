@@ -105,7 +105,7 @@ lib.mqg_ctx_set_sampling_priority.argtypes = [_vp, ctypes.POINTER(CGraph), ctype
 lib.mqg_sample_layerwise.restype = ctypes.c_int
 lib.mqg_sample_layerwise.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, ctypes.c_uint64,
                                      _i32, _i32, ctypes.POINTER(CBlock), ctypes.POINTER(_vp), _vp]
-MQG_LAYERWISE_LADIES, MQG_LAYERWISE_FASTGCN, MQG_LAYERWISE_DEBIAS = 0, 1, 2
+MQG_LAYERWISE_LADIES, MQG_LAYERWISE_FASTGCN, MQG_LAYERWISE_DEBIAS, MQG_LAYERWISE_FLAT = 0, 1, 2, 4
 lib.mqg_select_smallest_keys.restype = ctypes.c_int
 lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
 lib.mqg_select_row_candidates.restype = ctypes.c_int

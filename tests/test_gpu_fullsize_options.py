@@ -1,0 +1,103 @@
+"""The optional paths on the full "medium" graph (233 k nodes, 110 M edges): every kernel runs with
+hundreds to thousands of workgroups, several per compute unit, which the small graphs of the other
+option tests never reach.  Cache policies, layer-wise variants and the backward, each against the
+oracle (integers bit-exact, weights to 1e-6, gradients to the aggregation tolerance)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2601_04707_amd import synth
+from gpu_util import agg_tolerance_ok, hip_sample
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    from paper_2601_04707_amd import mqg as m
+    assert torch.cuda.is_available()
+    w = synth.WORKLOADS["medium"]
+    rp, ci = synth.build_graph(w, seed=0, device="cuda")
+    g = m.Graph(rp, ci)
+    return m, w, g, rp, ci, rp.cpu().numpy(), ci.cpu().numpy()
+
+
+def test_cache_policies_full_size(env):
+    m, w, g, rp, ci, rp_np, ci_np = env
+    n = rp.numel() - 1
+    ctx = m.Context(g, 8, [2])
+    feats = synth.node_features(n, 4, seed=3).pin_memory()
+    num_cached = n // 10
+    # membership drawn in proportion to degree
+    for seed in (0, 9):
+        cache = m.Cache(g, feats, num_cached)
+        m.mqg_build_cache_ex(ctx, g, cache, m.MQG_CACHE_DEGREE_SAMPLED, seed=seed)
+        torch.cuda.synchronize()
+        want = oracle.build_cache_sampled(rp_np, num_cached, seed)
+        assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), want.cached_ids)
+        assert np.array_equal(cache.slot_of.cpu().numpy(), want.slot_of)
+    # random-walk scores as ranking and as draw
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 50].to(torch.int64)
+    steps = [10, 25]
+    want_scores = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), steps)
+    for policy, seed in ((m.MQG_CACHE_RANDOM_WALK, 0), (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 1), (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 2)):
+        cache = m.Cache(g, feats, num_cached)
+        scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+        m.mqg_build_cache_ex(ctx, g, cache, policy, seed=seed, train_ids=train.cuda(), step_fanouts=steps, scores_out=scores)
+        torch.cuda.synchronize()
+        assert np.array_equal(scores.cpu().numpy(), want_scores)
+        want = (oracle.build_cache_by_score(want_scores, num_cached) if policy == m.MQG_CACHE_RANDOM_WALK
+                else oracle.build_cache_drawn_by_score(want_scores, num_cached, seed))
+        assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), want.cached_ids)
+        assert np.array_equal(cache.slot_of.cpu().numpy(), want.slot_of)
+
+
+@pytest.mark.parametrize("fastgcn,debias,flat", [(False, False, False), (True, False, False), (False, True, False),
+                                                 (False, False, True), (True, True, True)])
+def test_layerwise_variants_full_size(env, fastgcn, debias, flat):
+    m, w, g, rp, ci, rp_np, ci_np = env
+    n = rp.numel() - 1
+    sizes = [512, 512]
+    ctx = m.Context(g, w.batch, [2, 2])
+    blocks = m.LayerwiseBlocks(g, w.batch, sizes)
+    method = ((m.MQG_LAYERWISE_FASTGCN if fastgcn else 0) | (m.MQG_LAYERWISE_DEBIAS if debias else 0) |
+              (m.MQG_LAYERWISE_FLAT if flat else 0))
+    for i, seeds in enumerate(synth.seed_batches(n, w.batch, 2, seed=12)):
+        m.mqg_sample_layerwise(ctx, g, seeds.to(g.idx_dtype).cuda(), sizes, 40 + i, blocks, normalise=True, method=method)
+        torch.cuda.synchronize()
+        want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 40 + i, normalise=True, fastgcn=fastgcn, debias=debias,
+                                    flat=flat)
+        hs = blocks.host_sizes()
+        for l, b in enumerate(want):
+            nd, ns, nnz, flags = hs[l]
+            assert (nd, ns, nnz, flags) == (b.num_dst, b.num_src, b.nnz, 0), (l, hs[l])
+            assert np.array_equal(blocks.src_ids[l][:ns].cpu().numpy().astype(np.int64), b.src_ids), l
+            assert np.array_equal(blocks.indptr[l][:nd + 1].cpu().numpy().astype(np.int64), b.indptr), l
+            assert np.array_equal(blocks.indices[l][:nnz].cpu().numpy(), b.indices), l
+            assert np.allclose(blocks.edge_w[l][:nnz].cpu().numpy(), b.edge_w, rtol=1e-6, atol=0), l
+
+
+def test_backward_full_size_blocks(env):
+    """Backward of the mean aggregation on the full-size sampled blocks (263 k edges, 109 k sources)."""
+    m, w, g, rp, ci, rp_np, ci_np = env
+    n = rp.numel() - 1
+    ctx = m.Context(g, w.batch, w.fanouts)
+    blocks = m.Blocks(g, w.batch, w.fanouts)
+    seeds = synth.seed_batches(n, w.batch, 1, seed=2)[0]
+    hip_sample(m, ctx, g, blocks, seeds, w.fanouts, 5)
+    want = oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), w.fanouts, 5)
+    dim = 24
+    rng = np.random.default_rng(0)
+    for l, b in enumerate(want):
+        grad_out = rng.standard_normal((b.num_dst, dim)).astype(np.float32)
+        go = torch.zeros((blocks.bounds[l][0], dim), device="cuda")
+        go[:b.num_dst] = torch.from_numpy(grad_out).cuda()
+        gx = torch.full((blocks.bounds[l][1], dim), 7.0, device="cuda")
+        m.mqg_sage_mean_aggregate_backward(ctx, blocks, l, go, gx)
+        torch.cuda.synchronize()
+        ref = oracle.mean_aggregate_backward(b.indptr, b.indices, b.num_src, grad_out)
+        got = gx[:b.num_src].cpu().numpy()
+        ok, worst = agg_tolerance_ok(got, ref, float(np.abs(grad_out).mean()), 1e-5)
+        assert ok, (l, worst)
+        assert torch.all(gx[b.num_src:] == 7.0)

@@ -103,6 +103,35 @@ def test_fastgcn_parity_and_alternation_with_ladies(mqg, ptr, idx, sizes):
 
 @pytest.mark.parametrize("ptr,idx", [(torch.int32, torch.int32), (torch.int64, torch.int64)])
 @pytest.mark.parametrize("sizes", [[64, 128], [512, 512], [100, 50, 30], [3000]])
+@pytest.mark.parametrize("fastgcn,debias", [(False, False), (True, False), (False, True), (True, True)])
+def test_flat_variants_parity(mqg, ptr, idx, sizes, fastgcn, debias):
+    """The "+flat" variants (Eq. 10: drawn in proportion to the column norm, squared tickets in the
+    race) alone and combined with FastGCN's masses and the debiased coefficients."""
+    rp, ci = hub_graph(ptr=ptr, idx=idx)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    batch = 193
+    ctx = mqg.Context(g, batch, [2] * len(sizes))
+    blocks = mqg.LayerwiseBlocks(g, batch, sizes)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    method = (mqg.MQG_LAYERWISE_FLAT | (mqg.MQG_LAYERWISE_FASTGCN if fastgcn else 0) | (mqg.MQG_LAYERWISE_DEBIAS if debias else 0))
+    for b, seeds in enumerate(synth.seed_batches(n, batch, 2, seed=7)):
+        for normalise in (True, False):
+            got = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 91 + b, normalise, method=method)
+            want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, 91 + b, normalise=normalise, fastgcn=fastgcn,
+                                        debias=debias, flat=True)
+            assert_same(got, want)
+    # not the same draw as without the flag
+    plain = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 91, True, method=method & ~mqg.MQG_LAYERWISE_FLAT)
+    flat = run_layerwise(mqg, ctx, g, blocks, seeds, sizes, 91, True, method=method)
+    if plain[-1]["num_src"] == sizes[-1] and sizes[-1] < 1000:   # a real draw (not every candidate taken)
+        assert not np.array_equal(plain[-1]["src_ids"], flat[-1]["src_ids"])
+    with pytest.raises(mqg.MqgError):
+        mqg.mqg_sample_layerwise(ctx, g, to_dev(seeds.to(g.idx_dtype)), sizes, 1, blocks, method=8)
+
+
+@pytest.mark.parametrize("ptr,idx", [(torch.int32, torch.int32), (torch.int64, torch.int64)])
+@pytest.mark.parametrize("sizes", [[64, 128], [512, 512], [100, 50, 30], [3000]])
 @pytest.mark.parametrize("fastgcn", [False, True])
 def test_debiased_variants_parity(mqg, ptr, idx, sizes, fastgcn):
     rp, ci = hub_graph(ptr=ptr, idx=idx)

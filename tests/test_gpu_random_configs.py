@@ -74,7 +74,7 @@ def test_random_configuration(mqg, case):
 
 @pytest.mark.parametrize("case", range(24))
 def test_random_layerwise_configuration(mqg, case):
-    """The layer-wise sampler (LADIES / FastGCN, with and without debiasing and row normalisation) on
+    """The layer-wise sampler (LADIES / FastGCN, with and without flat probabilities, debiasing and row normalisation) on
     random graph shapes, layer sizes and batch sizes: drawn nodes and block structure identical,
     edge weights to 1e-6."""
     rng = np.random.default_rng(7000 + case)
@@ -89,8 +89,9 @@ def test_random_layerwise_configuration(mqg, case):
     L = int(rng.integers(1, 4))
     sizes = [int(rng.choice([1, 3, 40, 300, 2000])) for _ in range(L)]
     batch = int(min(n, rng.choice([1, 9, 64, 130])))
-    fastgcn, debias, normalise = bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), bool(rng.integers(0, 2))
-    method = (mqg.MQG_LAYERWISE_FASTGCN if fastgcn else mqg.MQG_LAYERWISE_LADIES) | (mqg.MQG_LAYERWISE_DEBIAS if debias else 0)
+    fastgcn, debias, normalise, flat = (bool(rng.integers(0, 2)) for _ in range(4))
+    method = ((mqg.MQG_LAYERWISE_FASTGCN if fastgcn else mqg.MQG_LAYERWISE_LADIES) | (mqg.MQG_LAYERWISE_DEBIAS if debias else 0) |
+              (mqg.MQG_LAYERWISE_FLAT if flat else 0))
     ctx = mqg.Context(g, batch, [2] * L)
     blocks = mqg.LayerwiseBlocks(g, batch, sizes)
     rp_np, ci_np = rp.numpy(), ci.numpy()
@@ -98,7 +99,7 @@ def test_random_layerwise_configuration(mqg, case):
         rng_seed = int(rng.integers(0, 1 << 62))
         mqg.mqg_sample_layerwise(ctx, g, to_dev(seeds.to(g.idx_dtype)), sizes, rng_seed, blocks, normalise=normalise, method=method)
         torch.cuda.synchronize()
-        want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, rng_seed, normalise=normalise, fastgcn=fastgcn, debias=debias)
+        want = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), sizes, rng_seed, normalise=normalise, fastgcn=fastgcn, debias=debias, flat=flat)
         hs = blocks.host_sizes()
         for l, w in enumerate(want):
             nd, ns, nnz, flags = hs[l]
