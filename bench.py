@@ -394,8 +394,8 @@ def main() -> int:
     lw_stats = torch.zeros(2, dtype=torch.int64, device=dev)
     c0 = ctxs[0]
 
-    def lw_step(i):
-        mqg.mqg_sample_layerwise(c0, g, seeds_dev[i], lw_sizes, base_seed + i, lw_blocks)
+    def lw_step(i, method=0):
+        mqg.mqg_sample_layerwise(c0, g, seeds_dev[i], lw_sizes, base_seed + i, lw_blocks, method=method)
         mqg.mqg_gather_features(c0, cache, lw_blocks.src_ids[0], lw_blocks.sizes[0, 1:2], lw_x0, lw_stats)
         x = lw_x0
         for l in range(L):
@@ -411,6 +411,18 @@ def main() -> int:
     torch.cuda.synchronize()
     lw_ms = (time.perf_counter() - t0) / KL * 1e3
     lw_edges = int(lw_blocks.sizes[:, 2].sum())
+    # the variants the paper's tables list (FastGCN's batch-independent masses, flat probabilities, debiasing)
+    lw_variants = {}
+    for name, method in (("fastgcn", mqg.MQG_LAYERWISE_FASTGCN),
+                         ("ladies+f+d", mqg.MQG_LAYERWISE_FLAT | mqg.MQG_LAYERWISE_DEBIAS),
+                         ("fastgcn+f+d", mqg.MQG_LAYERWISE_FASTGCN | mqg.MQG_LAYERWISE_FLAT | mqg.MQG_LAYERWISE_DEBIAS)):
+        lw_step(W, method)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(W, W + KL):
+            lw_step(i, method)
+        torch.cuda.synchronize()
+        lw_variants[name] = round((time.perf_counter() - t0) / KL * 1e3, 3)
     c0.reset_profile()
     c0.set_option(mqg.MQG_OPT_PROFILE, 1)
     for i in range(W, W + KL):
@@ -512,6 +524,7 @@ def main() -> int:
         "layerwise_sampling": {"layer_sizes": lw_sizes, "ms_per_batch": round(lw_ms, 3),
                                "sampling_kernels_us_per_batch": round(lw_sample_us, 1),
                                "edges_last_batch": lw_edges, "kernel_us_per_batch": lw_kern,
+                               "variants_ms_per_batch": lw_variants,
                                "note": "LADIES (Eq. 6-9) on the same seeds: sample, gather, weighted sums, one "
                                        "mini-batch at a time on one stream; not part of a step"},
         "sampling": sampling,

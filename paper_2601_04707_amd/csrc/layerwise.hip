@@ -461,37 +461,83 @@ k_lw_draw_order(const uint64_t *__restrict__ dkey, const int64_t *__restrict__ s
     order[rank] = static_cast<int32_t>(pos);
 }
 
+// Inclusive scan over the 256 threads of a workgroup with a binary operation on doubles (sum or
+// product); *total gets the workgroup's result.  `lds` needs kWavesPerBlock doubles.
+template <bool PRODUCT>
+__device__ __forceinline__ double lw_block_scan_incl(double v, double *total, double *lds) {
+    const int lane = lane_id();
+    const int wave = static_cast<int>(threadIdx.x) >> 6;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const double t = __shfl_up(v, off, 64);
+        if (lane >= off) v = PRODUCT ? v * t : v + t;
+    }
+    __syncthreads();                                       // lds may still be read from an earlier use
+    if (lane == 63) lds[wave] = v;
+    __syncthreads();
+    double before = PRODUCT ? 1.0 : 0.0, all = PRODUCT ? 1.0 : 0.0;
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) {
+        const double t = lds[k];
+        if (k < wave) before = PRODUCT ? before * t : before + t;
+        all = PRODUCT ? all * t : all + t;
+    }
+    *total = all;
+    return PRODUCT ? before * v : before + v;
+}
+
 // The recursion of Eq. 12 in closed form.  With a_r = n / ((n - r)(r + 1)) (r = 0 for the first draw)
 // and b0_r = a_r (1 - sum of the p drawn before) / p_r the coefficient an item gets when it is
 // drawn, later steps turn a coefficient b into (1 - a_u) b + a_u, so the final one is
-//   beta_r = b0_r G_r + H_r,  G_r = prod_{u > r} (1 - a_u),  H_r = sum_{u > r} a_u G_u,
-// accumulated from the last draw backwards.  One thread; a layer has a few thousand draws at most.
+//   beta_r = b0_r G_r + H_r,  G_r = prod_{u > r} (1 - a_u),  H_r = sum_{u > r} a_u G_u.
+// One workgroup: a prefix sum over the draws for b0, then, from the last draw backwards, a prefix
+// product for G and a prefix sum of a_u G_u for H, 256 draws at a time with running carries.
 // Every candidate drawn: beta = 1.
 __global__ void __launch_bounds__(kBlock)
 k_lw_debias(const int32_t *__restrict__ order, const double *__restrict__ dq, const double *__restrict__ q_total,
             const int64_t *__restrict__ sizes, const int64_t *__restrict__ n_cand, double *__restrict__ b0,
             double *__restrict__ beta) {
+    __shared__ double lds[kWavesPerBlock];
+    __shared__ double incl_of[kBlock];
     const int64_t s = sizes[1];
     const int64_t n = *n_cand;
     if (s >= n) {
         for (int64_t r = threadIdx.x; r < s; r += kBlock) beta[r] = 1.0;
         return;
     }
-    if (threadIdx.x != 0) return;
     const double total = *q_total;
-    double drawn = 0.0;
-    for (int64_t r = 0; r < s; ++r) {
-        const double p = dq[order[r]] / total;
-        const double alpha = static_cast<double>(n) / (static_cast<double>(n - r) * static_cast<double>(r + 1));
-        b0[r] = alpha / (p / (1.0 - drawn));
-        drawn += p;
+    const double nd = static_cast<double>(n);
+    double drawn = 0.0;                                    // probability mass of the draws before this chunk
+    for (int64_t base = 0; base < s; base += kBlock) {
+        const int64_t r = base + threadIdx.x;
+        const bool in = r < s;
+        const double p = in ? dq[order[r]] / total : 0.0;
+        double chunk;
+        const double incl = lw_block_scan_incl<false>(p, &chunk, lds);
+        if (in) {
+            const double alpha = nd / (static_cast<double>(n - r) * static_cast<double>(r + 1));
+            b0[r] = alpha * (1.0 - (drawn + (incl - p))) / p;
+        }
+        drawn += chunk;
     }
-    double G = 1.0, H = 0.0;
-    for (int64_t r = s - 1; r >= 0; --r) {
-        beta[order[r]] = b0[r] * G + H;
-        const double alpha = static_cast<double>(n) / (static_cast<double>(n - r) * static_cast<double>(r + 1));
-        H += alpha * G;
-        G *= 1.0 - alpha;
+    __syncthreads();
+    double G = 1.0, H = 0.0;                               // over the draws after this chunk
+    for (int64_t top = s; top > 0; top -= kBlock) {        // thread t takes draw top - 1 - t
+        const int64_t r = top - 1 - threadIdx.x;
+        const bool in = r >= 0;
+        const double alpha = in ? nd / (static_cast<double>(n - r) * static_cast<double>(r + 1)) : 0.0;
+        const double x = 1.0 - alpha;
+        double gprod, hsum;
+        const double g_incl = lw_block_scan_incl<true>(x, &gprod, lds);
+        incl_of[threadIdx.x] = g_incl;                     // the exclusive product is the previous thread's inclusive one
+        __syncthreads();
+        const double Gr = G * (threadIdx.x == 0 ? 1.0 : incl_of[threadIdx.x - 1]);
+        const double term = alpha * Gr;
+        const double h_incl = lw_block_scan_incl<false>(term, &hsum, lds);
+        if (in) beta[order[r]] = b0[r] * Gr + (H + (h_incl - term));
+        H += hsum;
+        G *= gprod;
+        __syncthreads();                                   // incl_of[] is rewritten by the next chunk
     }
 }
 
