@@ -163,6 +163,26 @@ def test_full_size_workload(mqg, name):
             assert ok, (name, j, l, worst)
             x_in = hs[j][l]
 
+    if name == "xlarge":
+        # the layer-wise sampler at 111 M nodes: 3.5 M bitmap words (the scan takes its three-launch
+        # form), candidate lists of millions, kernels whose capped grids loop over their elements
+        sizes = [512] * L
+        lblocks = mqg.LayerwiseBlocks(g, w.batch, sizes)
+        for method, kw in ((mqg.MQG_LAYERWISE_LADIES, {}),
+                           (mqg.MQG_LAYERWISE_FLAT | mqg.MQG_LAYERWISE_DEBIAS, dict(flat=True, debias=True))):
+            mqg.mqg_sample_layerwise(ctxs[0], g, seeds_dev[0], sizes, 17, lblocks, normalise=True, method=method)
+            torch.cuda.synchronize()
+            wl = oracle.ladies_blocks(rp_np, ci_np, batches[0].numpy(), sizes, 17, normalise=True, **kw)
+            hs_l = lblocks.host_sizes()
+            for l, b in enumerate(wl):
+                nd, ns, nnz, flags = hs_l[l]
+                assert (nd, ns, nnz, flags) == (b.num_dst, b.num_src, b.nnz, 0), (l, hs_l[l])
+                assert np.array_equal(lblocks.src_ids[l][:ns].cpu().numpy().astype(np.int64), b.src_ids), l
+                assert np.array_equal(lblocks.indptr[l][:nd + 1].cpu().numpy().astype(np.int64), b.indptr), l
+                assert np.array_equal(lblocks.indices[l][:nnz].cpu().numpy(), b.indices), l
+                assert np.allclose(lblocks.edge_w[l][:nnz].cpu().numpy(), b.edge_w, rtol=1e-6, atol=0), l
+        del lblocks
+
     del ctxs, blks, cache, x0, hs, g, rp, ci, feats
     gc.collect()
     torch.cuda.empty_cache()
