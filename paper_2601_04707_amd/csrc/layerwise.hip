@@ -180,10 +180,13 @@ k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, co
     if (threadIdx.x == 0) q_part[blockIdx.x] = ((lds[0] + lds[1]) + lds[2]) + lds[3];
 }
 
-// q_total = sum of the partial sums, in a fixed order
+// q_total = sum of the partial sums, in a fixed order; also clears the histograms of the radix
+// select that follows (hist_len entries)
 __global__ void __launch_bounds__(kBlock)
-k_lw_qsum(const double *__restrict__ q_part, int parts, double *__restrict__ q_total) {
+k_lw_qsum(const double *__restrict__ q_part, int parts, double *__restrict__ q_total, int32_t *__restrict__ sel_hist,
+          int hist_len) {
     __shared__ double lds[kBlock];
+    for (int k = threadIdx.x; k < hist_len; k += kBlock) sel_hist[k] = 0;
     double a = 0.0;
     for (int k = threadIdx.x; k < parts; k += kBlock) a += q_part[k];
     lds[threadIdx.x] = a;
@@ -544,7 +547,9 @@ k_lw_debias(const int32_t *__restrict__ order, const double *__restrict__ dq, co
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand, unsigned long long *__restrict__ mass,
-           const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of) {
+           const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of,
+           int32_t *__restrict__ flags) {
+    if (flags && blockIdx.x == 0 && threadIdx.x == 0) *flags = 0;     // the seed check's word, for the next call
     const int64_t nc = *n_cand, ns = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
     if (cand)
@@ -556,9 +561,6 @@ __global__ void k_lw_store_i64(int64_t *p, int64_t v) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
 }
 
-__global__ void k_lw_clear_flags(int32_t *flags) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *flags = 0;
-}
 
 template <typename T>
 bool dev_alloc(T **p, int64_t count) {
@@ -656,8 +658,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
                    (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_cand, mass, tag_hash, flat, w.key64, w.q_part)));
-        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total)));
-        MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
+        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total, w.sel_hist, 8 * 256)));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
         for (int pass = 0; pass <= 8; ++pass)
             MQG_LAUNCH(ctx, "k_lw_select", s,
@@ -685,8 +686,8 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         // rows: per (row, chunk) counts and weight sums, one scan, then the edges
         const int64_t chunks_cap = rows_cap * kRowChunks;
         const int chunk_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(chunks_cap, kWavesPerBlock)), 256 * 64));
-        MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
-                   (k_lw_zero_i32<<<static_cast<int>(ceil_div(chunks_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, chunks_cap + 1)));
+        // (entries of chunk_offs past the block's rows are not cleared: an exclusive scan's values up to
+        // the last row's end, the only ones read, do not depend on them)
         MQG_LAUNCH(ctx, "k_lw_count", s,
                    (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
                                                                          beta, flat, w.chunk_offs, w.chunk_sum)));
@@ -699,10 +700,10 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
                    (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
                                                                         beta, flat, w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
                                                                         b.cap_nnz)));
-        if (l == L - 1) MQG_LAUNCH(ctx, "k_lw_clear_flags", s, (k_lw_clear_flags<<<1, 64, 0, s>>>(w.flags)));
         const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
         MQG_LAUNCH(ctx, "k_lw_reset", s,
-                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of)));
+                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of,
+                                                                   l == L - 1 ? w.flags : nullptr)));
     }
     return MQG_OK;
 }
