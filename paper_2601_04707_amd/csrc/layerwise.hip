@@ -36,6 +36,7 @@ namespace {
 
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
 constexpr int kLayerwiseTag = 64;
+constexpr int64_t kMassScanNodes = int64_t(8) << 20;   // up to here the candidates are read off the masses
 
 uint64_t host_mix64(uint64_t z) {
     z ^= z >> 30;
@@ -104,6 +105,19 @@ k_lw_mass(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
             atomicAdd(&mass[i], add);
             if (bitmap) set_bit(bitmap, i);
         }
+    }
+}
+
+// The touched nodes from the masses themselves (bit i = mass[i] != 0), for graphs small enough that
+// reading every mass costs less than marking a bit per adjacency slot in k_lw_mass.  One lane per
+// node; n_pad is a multiple of 64, bits past the last node are zero.
+__global__ void __launch_bounds__(kBlock)
+k_lw_mass_bits(const unsigned long long *__restrict__ mass, int64_t n, uint32_t *__restrict__ bitmap) {
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    const uint64_t m = ballot64(i < n && mass[i] != 0);
+    if (lane_id() == 0) {
+        bitmap[i >> 5] = static_cast<uint32_t>(m);
+        bitmap[(i >> 5) + 1] = static_cast<uint32_t>(m >> 32);
     }
 }
 
@@ -645,8 +659,15 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         int rc = MQG_OK;
         if (!fastgcn) {
             const int mass_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows_cap * kRowChunks, kWavesPerBlock)), 256 * 64));
+            // candidates: marked slot by slot in the node bitmap, or, on graphs of up to kMassScanNodes
+            // nodes, read off the masses afterwards (1.9 MB of masses against 0.5 M bitmap probes on "medium")
+            const bool scan_masses = n <= kMassScanNodes;
             MQG_LAUNCH(ctx, "k_lw_mass", s,
-                       (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass, ctx->bitmap)));
+                       (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass,
+                                                                           scan_masses ? nullptr : ctx->bitmap)));
+            if (scan_masses)
+                MQG_LAUNCH(ctx, "k_lw_mass_bits", s,
+                           (k_lw_mass_bits<<<static_cast<int>(words * 32 / kBlock), kBlock, 0, s>>>(w.mass, n, ctx->bitmap)));
             // candidates, ascending
             MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
             rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
