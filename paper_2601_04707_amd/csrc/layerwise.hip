@@ -7,7 +7,8 @@
 //   k_lw_mass        mass[i] += floor(2^40 / (deg_v + 1)) for every row v and every i in N(v) or
 //                    i == v: integer atomics, so the sums do not depend on the schedule.
 //                    q_i = mass[i] / (deg_i + 1) is 2^40 times the squared column norm of Eq. 7.
-//                    Touched nodes are marked in the context's node bitmap.
+//                    Touched nodes are marked in the context's node bitmap - slot by slot on graphs
+//                    above kMassScanNodes nodes, otherwise by k_lw_mass_bits from the masses.
 //   bitmap -> list   the candidates (Eq. 6), ascending (word popcounts, scan, emit)
 //   k_lw_keys        exponential race: key = ticket * (deg_i + 1) / mass[i] in doubles (the "flat"
 //                    variants, Eq. 10, draw in proportion to sqrt(q_i): ticket^2 in place of ticket), ticket from
@@ -23,6 +24,8 @@
 // A row is shared by kRowChunks wavefronts, each with a contiguous range of adjacency slots, so
 // that a hub does not become a kernel's tail; counts and partial weight sums are kept per (row,
 // chunk) and one scan over all of them gives every wavefront its first edge position.
+//   k_lw_drawn_keys / k_lw_draw_order / k_lw_debias   (the "+debias" variants, Eq. 12) the drawn nodes in
+//                    the order of the race and their debiased coefficients, three scans in one workgroup
 //   k_lw_reset       masses and positions back to their idle values
 #include <algorithm>
 
