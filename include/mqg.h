@@ -414,6 +414,29 @@ int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
                         void *out_dev, int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
 
 /*
+ * mqg_gather_features for callers that cannot allocate device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * takes no context (creating one allocates): the hit and miss lists and the
+ * counters that mqg_gather_features keeps in its context live in a device array
+ * of fixed size inside the library, MQG_GATHER_STATIC_MAX_IDS entries per list
+ * (16 MiB + 64 bytes in all, held by every GPU the library runs on until the
+ * process ends).  No call to hipMalloc, hipFree or any allocating routine is
+ * made, at the first call or later; the first call on a device only looks up
+ * the array's address there.  Same arguments, kernels, results and stats as
+ * mqg_gather_features.  With a cache (slot_of != NULL) cap_ids above
+ * MQG_GATHER_STATIC_MAX_IDS is refused with MQG_ERR_CAPACITY before anything
+ * is enqueued; without a cache there is no limit (no list is used).  The
+ * message of a failing call is read with mqg_last_error(NULL).  All calls on a
+ * GPU share that GPU's array: two calls whose kernels can overlap there (two
+ * streams, two threads) race, so keep them on one stream or order them with
+ * events.
+ */
+#define MQG_GATHER_STATIC_MAX_IDS 1048576
+int mqg_gather_features_static(const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                               const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev,
+                               int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
+
+/*
  * GraphSAGE mean aggregation over one block (paper Eq. 16,
  * Z_agg(v) = Mean(H(v)); the GA step "AH" of Sec. IV "Computation").
  *   out[i, c] = (1/n_i) * sum_{e in row i} x_src[indices[e], c],  n_i = row length;

@@ -418,24 +418,9 @@ int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, 
                         const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
                         int64_t *stats_dev, mqg_stream stream) {
     if (!ctx) return MQG_ERR_INVALID_ARG;
-    if (!cache || !num_ids_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL cache or num_ids_dev");
-    if (!valid_itype(idx_type) || !valid_dtype(cache->dtype) || cache->dim < 1)
-        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: bad idx_type, dtype or dim");
-    if (cap_ids < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: negative cap_ids");
-    if (cap_ids > 0 && (!ids_dev || !out_dev)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL ids or out");
-    if (!cache->feats) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: feats is NULL");
-    if (out_stride < cache->dim || cache->feat_stride < cache->dim)
-        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: stride below dim");
-    bool has_cache = cache->slot_of != nullptr;
-    if (has_cache) {
-        if (cache->num_cached > 0 && !cache->cache_rows) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: slot_of without cache_rows");
-        if (cache->cache_stride < cache->dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_stride below dim");
-        if (cap_ids > ctx->max_src)
-            return fail(ctx, MQG_ERR_CAPACITY, "mqg_gather_features: cap_ids above the context's largest source list (" +
-                        std::to_string(ctx->max_src) + ")");
-    } else if (cache->cache_rows) {
-        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_rows without slot_of");
-    }
+    int rc = mqg::check_gather_args(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, ctx->max_src,
+                                    "the context's largest source list");
+    if (rc != MQG_OK) return rc;
     return mqg::run_gather(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride,
                            stats_dev, static_cast<hipStream_t>(stream));
 }

@@ -144,6 +144,9 @@ int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32
 int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids,
                const int64_t *num_ids, int64_t cap_ids, void *out, int64_t out_stride,
                int64_t *stats, hipStream_t s);
+int check_gather_args(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                      const int64_t *num_ids_dev, int64_t cap_ids, const void *out_dev, int64_t out_stride,
+                      int64_t max_ids, const char *what_max);
 int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t x_stride, void *out,
                        int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_cache_plan *plan, hipStream_t s);

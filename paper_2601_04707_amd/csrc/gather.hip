@@ -12,6 +12,7 @@
 //                     profiles tell the HBM-bound from the link-bound launch)
 //   k_gather_direct   no cache: every row straight from the feature matrix
 #include <algorithm>
+#include <mutex>
 
 #include "common.h"
 #include "device_utils.h"
@@ -417,6 +418,31 @@ int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, 
                                   is_host_memory(src), s);
 }
 
+// Host-side argument checks shared by the gather entry points.  max_ids bounds cap_ids when the
+// rows go through the cache (the hit and miss lists hold one entry per id); what_max names it.
+int check_gather_args(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                      const int64_t *num_ids_dev, int64_t cap_ids, const void *out_dev, int64_t out_stride,
+                      int64_t max_ids, const char *what_max) {
+    if (!cache || !num_ids_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL cache or num_ids_dev");
+    if ((idx_type != MQG_I32 && idx_type != MQG_I64) || (cache->dtype != MQG_F32 && cache->dtype != MQG_F16) || cache->dim < 1)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: bad idx_type, dtype or dim");
+    if (cap_ids < 0) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: negative cap_ids");
+    if (cap_ids > 0 && (!ids_dev || !out_dev)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: NULL ids or out");
+    if (!cache->feats) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: feats is NULL");
+    if (out_stride < cache->dim || cache->feat_stride < cache->dim)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: stride below dim");
+    if (cache->slot_of != nullptr) {
+        if (cache->num_cached > 0 && !cache->cache_rows) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: slot_of without cache_rows");
+        if (cache->cache_stride < cache->dim) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_stride below dim");
+        if (cap_ids > max_ids)
+            return fail(ctx, MQG_ERR_CAPACITY, std::string("mqg_gather_features: cap_ids above ") + what_max + " (" +
+                        std::to_string(max_ids) + ")");
+    } else if (cache->cache_rows) {
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_gather_features: cache_rows without slot_of");
+    }
+    return MQG_OK;
+}
+
 int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids, const int64_t *num_ids,
                int64_t cap_ids, void *out, int64_t out_stride, int64_t *stats, hipStream_t s) {
     const int64_t elt = c->dtype == MQG_F16 ? 2 : 4;
@@ -457,3 +483,82 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
 }
 
 }  // namespace mqg
+
+// ---- the gather for callers that cannot allocate ------------------------------------------------
+//
+// mqg_gather_features keeps its hit and miss lists and its counters in a context, and a context is
+// hipMalloc'ed.  The entry point below needs no context: the same lists live in a device array of
+// fixed size that is part of the code object, so nothing is allocated when it is called (or ever).
+// Layout of the array, in 8-byte words: [0, kMax) hit list, [kMax, 2 kMax) miss list, then the
+// eight counter words of run_gather.
+
+namespace mqg {
+namespace {
+
+constexpr int64_t kStaticMaxIds = MQG_GATHER_STATIC_MAX_IDS;
+constexpr int kStaticMaxDevices = 64;
+
+static __device__ __align__(256) unsigned long long scratch[2 * kStaticMaxIds + 8];
+
+// What the host knows about a device's copy of the array: its address there, and a context object
+// (host memory only) that points run_gather at it.  Filled at the first call on the device.
+struct StaticGather {
+    bool ready = false;
+    unsigned long long *ptr = nullptr;
+    mqg_ctx ctx;
+};
+StaticGather g_static[kStaticMaxDevices];
+std::mutex g_static_mutex;
+
+__global__ void k_clear_words(unsigned long long *p, int n) {
+    if (static_cast<int>(threadIdx.x) < n) p[threadIdx.x] = 0;
+}
+
+}  // namespace
+}  // namespace mqg
+
+extern "C" int mqg_gather_features_static(const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                                          const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev,
+                                          int64_t out_stride, int64_t *stats_dev, mqg_stream stream) {
+    using namespace mqg;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail(nullptr, MQG_ERR_HIP, std::string("mqg_gather_features_static: hipGetDevice: ") + hipGetErrorString(e));
+    if (dev < 0 || dev >= kStaticMaxDevices)
+        return fail(nullptr, MQG_ERR_UNSUPPORTED, "mqg_gather_features_static: device index above 63");
+    StaticGather &sg = g_static[dev];
+    {
+        std::lock_guard<std::mutex> lock(g_static_mutex);
+        if (!sg.ready) {
+            // `scratch` is a host-side stand-in here; the device's copy of the array is at the
+            // address this call returns, with that device current
+            void *p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !p)
+                return fail(nullptr, MQG_ERR_HIP, std::string("mqg_gather_features_static: hipGetSymbolAddress: ") + hipGetErrorString(e));
+            sg.ptr = static_cast<unsigned long long *>(p);
+            sg.ctx.device = dev;
+            sg.ctx.max_src = kStaticMaxIds;
+            sg.ctx.hit_list = reinterpret_cast<int2 *>(sg.ptr);
+            sg.ctx.miss_list = reinterpret_cast<int2 *>(sg.ptr + kStaticMaxIds);
+            sg.ctx.counters = sg.ptr + 2 * kStaticMaxIds;
+            sg.ready = true;
+        }
+    }
+    mqg_ctx *ctx = &sg.ctx;
+    int rc = check_gather_args(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, kStaticMaxIds,
+                               "MQG_GATHER_STATIC_MAX_IDS");
+    if (rc == MQG_OK) {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        // the array keeps what the last call left; the counters have to start at zero (a fill
+        // kernel rather than a memset, so that the call can also be recorded into a graph)
+        if (cache->slot_of && cap_ids > 0) {
+            k_clear_words<<<1, 64, 0, s>>>(ctx->counters, 8);
+            e = hipGetLastError();
+            if (e != hipSuccess) return fail(nullptr, MQG_ERR_HIP, std::string("mqg_gather_features_static: k_clear_words: ") + hipGetErrorString(e));
+        }
+        rc = run_gather(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, stats_dev, s);
+    }
+    if (rc != MQG_OK) return fail(nullptr, rc, ctx->last_error);      // no context handle: the message goes where mqg_last_error(NULL) reads
+    return MQG_OK;
+}

@@ -32,6 +32,7 @@ EXPORTS = [
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
     "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
     "mqg_select_smallest_keys", "mqg_select_row_candidates", "mqg_sample_blocks_seed_dev",
+    "mqg_gather_features_static",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -89,6 +90,9 @@ lib.mqg_sample_blocks.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes
                                   ctypes.c_uint64, ctypes.POINTER(CBlock), _vp]
 lib.mqg_gather_features.restype = ctypes.c_int
 lib.mqg_gather_features.argtypes = [_vp, ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
+lib.mqg_gather_features_static.restype = ctypes.c_int
+lib.mqg_gather_features_static.argtypes = [ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
+MQG_GATHER_STATIC_MAX_IDS = 1 << 20
 lib.mqg_sage_mean_aggregate.restype = ctypes.c_int
 lib.mqg_sage_mean_aggregate.argtypes = [_vp, ctypes.POINTER(CBlock), _vp, _i64, _vp, _i64, _i32, _i32, _vp]
 lib.mqg_sage_mean_aggregate_backward.restype = ctypes.c_int
@@ -389,6 +393,19 @@ def mqg_gather_features(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: 
     assert cap <= ids.numel() and cap <= out.shape[0]
     ctx.check(lib.mqg_gather_features(ctx.h, ctypes.byref(cache.c), _itype(ids), ids.data_ptr(), num_ids.data_ptr(),
                                       cap, out.data_ptr(), out.stride(0), _ptr(stats), _stream(stream)))
+
+
+def mqg_gather_features_static(cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,
+                               stats: Optional[torch.Tensor] = None, cap_ids: Optional[int] = None, stream=None) -> None:
+    """mqg_gather_features without a context: the library's fixed device array holds the lists."""
+    assert ids.is_cuda and num_ids.is_cuda and num_ids.dtype == torch.int64 and out.is_cuda
+    assert out.dtype == cache.feats.dtype and out.stride(1) == 1
+    cap = int(cap_ids if cap_ids is not None else min(ids.numel(), out.shape[0]))
+    assert cap <= ids.numel() and cap <= out.shape[0]
+    rc = lib.mqg_gather_features_static(ctypes.byref(cache.c), _itype(ids), ids.data_ptr(), num_ids.data_ptr(), cap,
+                                        out.data_ptr(), out.stride(0), _ptr(stats), _stream(stream))
+    if rc != MQG_OK:
+        raise MqgError(rc, lib.mqg_last_error(None).decode())
 
 
 def mqg_sage_mean_aggregate(ctx: Context, blocks: Blocks, l: int, x_src: torch.Tensor, out: torch.Tensor,
