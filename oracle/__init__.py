@@ -28,7 +28,7 @@ def build(force: bool = False) -> str:
     stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
     if force or stale:
         tmp = _LIB + f".tmp{os.getpid()}"
-        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fno-fast-math",
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
                                "-Wall", "-Wextra", "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
@@ -78,7 +78,7 @@ def _load():
     lib.orc_build_cache_sampled.restype = ctypes.c_int
     lib.orc_build_cache_sampled.argtypes = [i64, vp, i64, u64, vp, vp]
     lib.orc_random_walk_scores.restype = ctypes.c_int
-    lib.orc_random_walk_scores.argtypes = [i64, vp, vp, vp, i64, vp, i64, vp]
+    lib.orc_random_walk_scores.argtypes = [i64, vp, vp, vp, i64, vp, i64, i64, vp]
     lib.orc_build_cache_by_score.restype = ctypes.c_int
     lib.orc_build_cache_by_score.argtypes = [i64, vp, i64, vp, vp]
     lib.orc_ladies_probabilities.restype = None
@@ -172,15 +172,19 @@ def build_cache_sampled(row_ptr, num_cached: int, seed: int, feats: Optional[np.
     return _finish_cache(ids, slot_of, num_cached, n, feats)
 
 
-def random_walk_scores(row_ptr, col_idx, train_ids, step_fanouts: Sequence[int]) -> np.ndarray:
-    """P^(L) of Eq. 14-15; step_fanouts[l-1] is the fanout of walk step l."""
+WALK_PUSH, WALK_PRINTED = 0, 1
+
+
+def random_walk_scores(row_ptr, col_idx, train_ids, step_fanouts: Sequence[int], form: int = WALK_PUSH) -> np.ndarray:
+    """P^(L) of Eq. 14-15; step_fanouts[l-1] is the fanout of walk step l.  form: WALK_PUSH moves mass
+    from a node to the nodes it samples from, (D A + I)^T P; WALK_PRINTED is (D A + I) P as printed."""
     rp, ci, tr = _i64(row_ptr), _i64(col_idx), _i64(train_ids)
     fo = _i64(list(step_fanouts))
     n = rp.shape[0] - 1
     out = np.zeros(max(1, n), dtype=np.float64)
-    rc = _load().orc_random_walk_scores(n, _p(rp), _p(ci), _p(tr), tr.shape[0], _p(fo), fo.shape[0], _p(out))
+    rc = _load().orc_random_walk_scores(n, _p(rp), _p(ci), _p(tr), tr.shape[0], _p(fo), fo.shape[0], form, _p(out))
     if rc != 0:
-        raise MemoryError("orc_random_walk_scores")
+        raise ValueError(f"orc_random_walk_scores failed ({rc})")
     return out[:n]
 
 

@@ -22,7 +22,9 @@
  *                            sampling without replacement, redrawn per epoch).
  *   - orc_random_walk_scores / orc_build_cache_by_score : Eq. 14-15, the
  *                            short-random-walk probabilities P^(L) used when
- *                            the training set is a small part of the graph.
+ *                            the training set is a small part of the graph;
+ *                            Eq. 15 as printed, and the same matrix applied
+ *                            along the direction in which sampling moves.
  *   - orc_exp_ticket / orc_build_cache_drawn_by_score : the text after
  *                            Eq. 15 takes P^(L) as the probability with
  *                            which the cache is sampled; taken literally:
@@ -655,50 +657,71 @@ int orc_build_cache_sampled(int64_t num_nodes, const int64_t *row_ptr, int64_t n
 
 /*
  * Short-random-walk scores (Eq. 14-15): P^(0) = 1/|V_t| on the training
- * nodes, 0 elsewhere, and L propagation steps with the sampling ratio
- * d_j = min(fanout_l, deg_j) / deg_j (the share of node j's neighbours that
- * sampling keeps; 0 for a node without neighbours).
+ * nodes, 0 elsewhere, then L propagation steps with the sampling ratio
+ * d_v = min(fanout_l, deg_v) / deg_v (Eq. 14: the share of node v's
+ * neighbours that sampling keeps; 0 for a node without neighbours), deg_v the
+ * length of v's adjacency row.  Row v lists the nodes that v samples from,
+ * and A is that adjacency as a matrix: A[v][u] = 1 for u in row(v).  D A
+ * therefore scales row v - the list v samples from - by v's own ratio.
  *
- * Reading of Eq. 15.  The paper prints P^(l) = (D A + I) P^(l-1), which scales
- * the mass arriving at node i by i's own ratio d_i; then every node with at
- * least `fanout` neighbours scores alike after one step and the scores no
- * longer say how likely a node is to be *reached*.  The ratio belongs to the
- * node that does the sampling: a node j that holds mass P[j] passes d_j * P[j]
- * to each of its neighbours.  That is what is computed here,
- *   P^(l)[i] = P^(l-1)[i] + sum_{j in row(i)} d_j * P^(l-1)[j]      ((A D + I) P),
- * with row(i) the adjacency row of node i (on the symmetrised graphs of the
- * workloads "j in row(i)" and "i in row(j)" are the same).
- * Double precision; every product d_j * P[j] is rounded on its own, every row
- * is summed in adjacency order.  step_fanouts[l-1] is the fanout of step l.
+ * form ORC_WALK_PRINTED: Eq. 15 exactly as printed, with P a column vector,
+ *   P^(l) = (D A + I) P^(l-1):   P'[i] = P[i] + d_i * sum_{j in row(i)} P[j].
+ *   Node i collects the mass of the nodes it samples from, scaled by its own
+ *   ratio.  The row is summed in adjacency order, then multiplied by d_i.
+ *
+ * form ORC_WALK_PUSH: the same matrix applied along the direction in which
+ * sampling moves, P^(l) = (D A + I)^T P^(l-1):
+ *   P'[u] = P[u] + sum over v with u in row(v) of d_v * P[v].
+ *   A node v that holds mass P[v] reaches each of the nodes it samples from
+ *   with probability d_v, so after l steps P[u] is the expected number of
+ *   times u has entered the sampled frontier (a frontier keeps its nodes and
+ *   adds the sampled neighbours of each, as the blocks of node-wise sampling
+ *   do), started from a uniformly chosen training node.  This is "reached
+ *   from the training set with high probability", the property the cache
+ *   section asks for; the printed form moves mass against the sampling
+ *   direction and, on a directed graph, scores nodes that sampling never
+ *   reaches.  Written as the plain scatter: v ascending, the slots of row(v)
+ *   in order, so the terms of a node u are added in ascending order of v.
+ *
+ * On a graph that equals its transpose the push form is
+ * P'[u] = P[u] + sum_{v in row(u)} d_v * P[v], i.e. (A D + I) P.
+ * Double precision; every product is rounded on its own (no fused
+ * multiply-add).  step_fanouts[l-1] is the fanout of step l.
  */
+#define ORC_WALK_PUSH 0
+#define ORC_WALK_PRINTED 1
+
 int orc_random_walk_scores(int64_t num_nodes, const int64_t *row_ptr, const int64_t *col_idx,
                            const int64_t *train_ids, int64_t num_train, const int64_t *step_fanouts,
-                           int64_t num_steps, double *scores)
+                           int64_t num_steps, int64_t form, double *scores)
 {
+    if (form != ORC_WALK_PUSH && form != ORC_WALK_PRINTED) return -1;
     size_t cnt = (size_t)(num_nodes > 0 ? num_nodes : 1);
     double *cur = calloc(cnt, sizeof *cur);
     double *next = calloc(cnt, sizeof *next);
-    double *pass = calloc(cnt, sizeof *pass);          /* d_j * P[j]: what node j passes to a neighbour */
-    if (!cur || !next || !pass) { free(cur); free(next); free(pass); return -2; }
+    if (!cur || !next) { free(cur); free(next); return -2; }
     for (int64_t t = 0; t < num_train; ++t) cur[train_ids[t]] = 1.0 / (double)num_train;
     for (int64_t l = 0; l < num_steps; ++l) {
-        for (int64_t j = 0; j < num_nodes; ++j) {
-            int64_t deg = row_ptr[j + 1] - row_ptr[j];
+        for (int64_t i = 0; i < num_nodes; ++i) next[i] = cur[i];              /* the "+ I" term */
+        for (int64_t v = 0; v < num_nodes; ++v) {
+            int64_t deg = row_ptr[v + 1] - row_ptr[v];
             double keep = deg < step_fanouts[l] ? (double)deg : (double)step_fanouts[l];
             double d = deg > 0 ? keep / (double)deg : 0.0;
-            pass[j] = d * cur[j];
-        }
-        for (int64_t i = 0; i < num_nodes; ++i) {
-            double acc = 0.0;
-            for (int64_t p = row_ptr[i]; p < row_ptr[i + 1]; ++p) acc += pass[col_idx[p]];
-            next[i] = cur[i] + acc;
+            if (form == ORC_WALK_PRINTED) {
+                double acc = 0.0;
+                for (int64_t p = row_ptr[v]; p < row_ptr[v + 1]; ++p) acc += cur[col_idx[p]];
+                double scaled = d * acc;                                      /* rounded before the addition */
+                next[v] = cur[v] + scaled;
+            } else {
+                double share = d * cur[v];                                    /* what v hands to each node it samples from */
+                for (int64_t p = row_ptr[v]; p < row_ptr[v + 1]; ++p) next[col_idx[p]] += share;
+            }
         }
         double *t = cur; cur = next; next = t;
     }
     for (int64_t i = 0; i < num_nodes; ++i) scores[i] = cur[i];
     free(cur);
     free(next);
-    free(pass);
     return 0;
 }
 

@@ -520,53 +520,201 @@ def test_sampled_cache_is_weighted_sampling_without_replacement():
             assert abs(cnt - trials * p) < 4.5 * math.sqrt(trials * p * (1 - p)), (a, b, cnt, trials * p)
 
 
-def test_random_walk_scores_equal_dense_matrix_power():
-    rp, ci = tiny_graph(250, 2500, seed=13)
+def directed_graph(n, edges, seed, keep=0.6):
+    """A directed graph without self loops or repeated entries: a symmetric one with a random part
+    of its edges dropped, so that most edges have no reverse."""
+    rp, ci = tiny_graph(n, edges, seed=seed)
+    rows = np.repeat(np.arange(n), np.diff(rp))
+    mask = np.random.default_rng(seed).random(len(ci)) < keep
+    rows, cols = rows[mask], ci[mask]
+    rp2 = np.zeros(n + 1, dtype=np.int64)
+    rp2[1:] = np.cumsum(np.bincount(rows, minlength=n))
+    return rp2, cols.astype(np.int64)
+
+
+def dense_walk(rp, ci, train, fanouts, how):
+    """Eq. 14-15 with dense matrices: A[v, u] = 1 for u in row(v), D = diag(min(k, deg)/deg)."""
     n = len(rp) - 1
     A = np.zeros((n, n))
     for i in range(n):
         A[i, ci[rp[i]:rp[i + 1]]] = 1.0
     deg = np.diff(rp).astype(np.float64)
+    P = np.zeros(n)
+    P[train] = 1.0 / len(train)
+    for k in fanouts:
+        D = np.diag(np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0))
+        M = {"printed": D @ A + np.eye(n),            # Eq. 15 as printed, P a column vector
+             "push": (D @ A + np.eye(n)).T,           # the same matrix along the sampling direction
+             "pull": A @ D + np.eye(n)}[how]          # the neighbour's ratio, pulled along the rows
+        P = M @ P
+    return P
+
+
+def test_random_walk_forms_equal_their_dense_matrix_statements():
+    rp, ci = directed_graph(250, 2500, seed=13)
     train = np.array([3, 17, 100, 249, 42], dtype=np.int64)
     for fanouts in ([5], [5, 5], [4, 9, 2], [1000, 1000]):
-        P = np.zeros(n)
-        P[train] = 1.0 / len(train)
-        for k in fanouts:
-            d = np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0)
-            P = (A @ np.diag(d) + np.eye(n)) @ P                  # the sampling node's ratio scales what it passes on
-        got = oracle.random_walk_scores(rp, ci, train, fanouts)
-        assert np.allclose(got, P, rtol=1e-12, atol=1e-15)
-    # fanout above every degree: D = I, so the scores count walks: (A + I)^L P0
-    got = oracle.random_walk_scores(rp, ci, train, [10 ** 6, 10 ** 6])
+        push = oracle.random_walk_scores(rp, ci, train, fanouts, oracle.WALK_PUSH)
+        printed = oracle.random_walk_scores(rp, ci, train, fanouts, oracle.WALK_PRINTED)
+        assert np.allclose(push, dense_walk(rp, ci, train, fanouts, "push"), rtol=1e-12, atol=1e-15)
+        assert np.allclose(printed, dense_walk(rp, ci, train, fanouts, "printed"), rtol=1e-12, atol=1e-15)
+        # on a directed graph the forms are three different things
+        assert not np.allclose(push, printed, rtol=1e-3)
+        assert not np.allclose(push, dense_walk(rp, ci, train, fanouts, "pull"), rtol=1e-3)
+        if max(fanouts) < 1000:                                    # with D = I the printed form is the pull
+            assert not np.allclose(printed, dense_walk(rp, ci, train, fanouts, "pull"), rtol=1e-3)
+    assert np.array_equal(oracle.random_walk_scores(rp, ci, train, [5, 5]), oracle.random_walk_scores(rp, ci, train, [5, 5], 0))
+    # fanout above every degree: D = I, the scores count walks, along the rows or against them
+    n = len(rp) - 1
+    A = np.zeros((n, n))
+    for i in range(n):
+        A[i, ci[rp[i]:rp[i + 1]]] = 1.0
     P0 = np.zeros(n)
     P0[train] = 1.0 / len(train)
-    assert np.allclose(got, np.linalg.matrix_power(A + np.eye(n), 2) @ P0, rtol=1e-12)
+    big = [10 ** 6, 10 ** 6]
+    assert np.allclose(oracle.random_walk_scores(rp, ci, train, big, oracle.WALK_PRINTED),
+                       np.linalg.matrix_power(A + np.eye(n), 2) @ P0, rtol=1e-12)
+    assert np.allclose(oracle.random_walk_scores(rp, ci, train, big, oracle.WALK_PUSH),
+                       np.linalg.matrix_power(A.T + np.eye(n), 2) @ P0, rtol=1e-12)
     # zero steps: the training distribution itself
-    assert np.array_equal(oracle.random_walk_scores(rp, ci, train, []), P0)
+    for form in (oracle.WALK_PUSH, oracle.WALK_PRINTED):
+        assert np.array_equal(oracle.random_walk_scores(rp, ci, train, [], form), P0)
+    with pytest.raises(ValueError):
+        oracle.random_walk_scores(rp, ci, train, [5], 2)
+
+
+def test_random_walk_push_on_a_symmetric_graph_is_the_neighbours_ratio_pulled():
+    """On a graph that equals its transpose, "v hands d_v P[v] to the nodes it samples from" and
+    "u collects d_v P[v] from its neighbours v" are one sum; with ascending rows even in the same
+    order, so the two agree to the last bit."""
+    rp, ci = tiny_graph(250, 2500, seed=13)
+    n = len(rp) - 1
+    deg = np.diff(rp).astype(np.float64)
+    train = np.array([3, 17, 100, 249, 42], dtype=np.int64)
+    fanouts = [4, 9, 2]
+    got = oracle.random_walk_scores(rp, ci, train, fanouts, oracle.WALK_PUSH)
+    assert np.allclose(got, dense_walk(rp, ci, train, fanouts, "pull"), rtol=1e-12, atol=1e-15)
+    P = np.zeros(n)
+    P[train] = 1.0 / len(train)
+    for k in fanouts:                                              # the pull, row by row in adjacency order
+        share = np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0) * P
+        nxt = P.copy()
+        for u in range(n):
+            acc = 0.0
+            for v in ci[rp[u]:rp[u + 1]]:
+                acc += share[v]
+            nxt[u] = P[u] + acc
+        P = nxt
+    assert np.allclose(got, P, rtol=1e-15, atol=0)
 
 
 def test_random_walk_worked_by_hand():
     # rows: 0:[1,2] 1:[0] 2:[0,3] 3:[]; training set {0}; fanout 1 -> d = [1/2, 1, 1/2, 0]
-    # step 1: node 0 passes 1/2 to whoever lists it (rows 1 and 2); step 2: passes [1/2, 1/2, 1/4, 0]
     rp = np.array([0, 2, 3, 5, 5], dtype=np.int64)
     ci = np.array([1, 2, 0, 0, 3], dtype=np.int64)
-    assert oracle.random_walk_scores(rp, ci, [0], [1]).tolist() == [1.0, 0.5, 0.5, 0.0]
-    assert oracle.random_walk_scores(rp, ci, [0], [1, 1]).tolist() == [1.75, 1.0, 1.0, 0.0]
+    # push: node 0 samples from {1, 2} and reaches each with 1/2; then 1 reaches 0 with 1/2 * 1, 2 reaches
+    # 0 and 3 with 1/2 * 1/2 each - node 3 is sampled along 0 -> 2 -> 3
+    assert oracle.random_walk_scores(rp, ci, [0], [1], oracle.WALK_PUSH).tolist() == [1.0, 0.5, 0.5, 0.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1], oracle.WALK_PUSH).tolist() == [1.75, 1.0, 1.0, 0.25]
+    # as printed: node i collects d_i * (P over the nodes i samples from): 1 <- 1 * P[0], 2 <- 1/2 (P[0] + P[3])
+    assert oracle.random_walk_scores(rp, ci, [0], [1], oracle.WALK_PRINTED).tolist() == [1.0, 1.0, 0.5, 0.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1], oracle.WALK_PRINTED).tolist() == [1.75, 2.0, 1.0, 0.0]
+    # (the neighbour's ratio pulled along the rows would give [1.75, 1, 1, 0]: right on 0..2, blind to node 3)
+    assert dense_walk(rp, ci, [0], [1, 1], "pull").tolist() == [1.75, 1.0, 1.0, 0.0]
+    # a chain 0 -> 1 -> 2 (0 samples from 1, 1 from 2): only the push follows the sampling
+    rp = np.array([0, 1, 2, 2], dtype=np.int64)
+    ci = np.array([1, 2], dtype=np.int64)
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1], oracle.WALK_PUSH).tolist() == [1.0, 2.0, 1.0]
+    assert oracle.random_walk_scores(rp, ci, [0], [1, 1], oracle.WALK_PRINTED).tolist() == [1.0, 0.0, 0.0]
+    # and from the far end the printed form walks back along the chain
+    assert oracle.random_walk_scores(rp, ci, [2], [1, 1], oracle.WALK_PUSH).tolist() == [0.0, 0.0, 1.0]
+    assert oracle.random_walk_scores(rp, ci, [2], [1, 1], oracle.WALK_PRINTED).tolist() == [1.0, 2.0, 1.0]
+
+
+def test_random_walk_push_is_the_expected_frontier_of_node_wise_sampling():
+    """Brute force over every outcome of the sampling process on a small directed graph, in exact
+    rationals: start from a uniformly chosen training node; at step l every node of the frontier
+    (a multiset) draws min(k_l, deg) distinct nodes of its row, every subset alike, and the drawn
+    nodes join the frontier.  The push scores are the expected multiplicities; the printed form
+    and the row-wise pull are not."""
+    from fractions import Fraction
+    rows = {0: [1, 2, 4], 1: [0, 3], 2: [3], 3: [4, 5, 0], 4: [], 5: [2, 1]}
+    n = 6
+    rp = np.zeros(n + 1, dtype=np.int64)
+    rp[1:] = np.cumsum([len(rows[v]) for v in range(n)])
+    ci = np.array([u for v in range(n) for u in rows[v]], dtype=np.int64)
+    train, fanouts = [0, 5], [2, 1]
+
+    def expand(frontier, k):
+        """All (probability, next frontier) outcomes of one step."""
+        per_node = []
+        for v in frontier:
+            subs = list(itertools.combinations(rows[v], min(k, len(rows[v]))))
+            per_node.append([(Fraction(1, len(subs)), sub) for sub in subs])
+        for combo in itertools.product(*per_node):
+            pr = Fraction(1)
+            nxt = list(frontier)
+            for q, sub in combo:
+                pr *= q
+                nxt.extend(sub)
+            yield pr, tuple(nxt)
+
+    states = {(t,): Fraction(1, len(train)) for t in train}
+    for k in fanouts:
+        nxt_states = {}
+        for fr, pr in states.items():
+            for q, nf in expand(fr, k):
+                nxt_states[nf] = nxt_states.get(nf, Fraction(0)) + pr * q
+        states = nxt_states
+    assert sum(states.values()) == 1
+    expect = [sum(pr * fr.count(u) for fr, pr in states.items()) for u in range(n)]
+    push = oracle.random_walk_scores(rp, ci, train, fanouts, oracle.WALK_PUSH)
+    assert np.allclose(push, [float(x) for x in expect], rtol=1e-14, atol=0)
+    assert not np.allclose(oracle.random_walk_scores(rp, ci, train, fanouts, oracle.WALK_PRINTED), push, rtol=1e-2)
+    assert not np.allclose(dense_walk(rp, ci, train, fanouts, "pull"), push, rtol=1e-2)
+
+
+def test_random_walk_push_follows_the_direction_of_the_sampler():
+    """One step from a single node v, against the (pinned) block sampler on a directed graph: the
+    mass that reaches u is the frequency with which sampling v draws u - u in row(v), never the
+    nodes that merely list v."""
+    rp, ci = directed_graph(60, 700, seed=3, keep=0.5)
+    deg = np.diff(rp)
+    v = int(np.argmax(deg))
+    k = max(1, int(deg[v]) // 3)
+    trials = 6000
+    hits = np.zeros(60)
+    for seed in range(trials):
+        blk = oracle.sample_blocks(rp, ci, [v], [k], seed)[0]
+        drawn = blk.src_ids[blk.indices]
+        assert len(drawn) == k
+        hits[drawn] += 1
+    step = oracle.random_walk_scores(rp, ci, [v], [k], oracle.WALK_PUSH)
+    step[v] -= 1.0                                                 # the "+ I" term
+    p = step
+    assert np.all(p[np.setdiff1d(np.arange(60), ci[rp[v]:rp[v + 1]])] == 0) and np.all(hits[p == 0] == 0)
+    assert np.all(np.abs(hits - trials * p) <= 4.5 * np.sqrt(trials * p * (1 - p)) + 1e-9)
+    listing_v = [u for u in range(60) if v in ci[rp[u]:rp[u + 1]] and u not in ci[rp[v]:rp[v + 1]]]
+    assert listing_v                                               # the graph is directed here
+    assert np.all(hits[listing_v] == 0)
 
 
 def test_random_walk_scores_rank_reachable_hubs_first():
     """What the scores are for (cache section of the paper): nodes that sampling from the training
-    set reaches with high probability.  With the whole graph as training set and one step the score
-    of node i is 1/N * (1 + sum over neighbours j of min(k, deg_j)/deg_j), which grows with the degree
-    of i - unlike a score that saturates at 1 + k for every node of degree >= k."""
+    set reaches with high probability.  With the whole graph as training set and one step the push
+    score of node u is 1/N * (1 + sum over the nodes v that sample from u of min(k, deg_v)/deg_v),
+    which grows with the number of such v - unlike the printed form, which gives every node of
+    degree >= k the same 1 + k."""
     rp, ci = tiny_graph(600, 12000, seed=15)
     n = len(rp) - 1
     deg = np.diff(rp)
-    sc = oracle.random_walk_scores(rp, ci, np.arange(n), [5])
+    sc = oracle.random_walk_scores(rp, ci, np.arange(n), [5], oracle.WALK_PUSH)
     big = deg >= 5
     assert np.unique(np.round(sc[big] * n, 9)).size > big.sum() // 2          # not one saturated value
     top = np.argsort(-sc)[:30]
     assert deg[top].mean() > 3 * deg.mean()
+    printed = oracle.random_walk_scores(rp, ci, np.arange(n), [5], oracle.WALK_PRINTED)
+    assert np.allclose(printed[big] * n, 6.0, rtol=1e-12)                      # saturated: 1 + k for all of them
 
 
 def test_cache_by_score_equals_lexsort():
