@@ -205,17 +205,41 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
  *                             over its tickets (all ones without neighbours); the num_cached nodes
  *                             with the smallest (key, id) are cached, slot s = s-th smallest.
  *   MQG_CACHE_RANDOM_WALK     Eq. 14-15, for training sets that are a small part of the graph:
- *                             P(0) = 1/num_train on train_ids, 0 elsewhere;
- *                             P(l)[i] = P(l-1)[i] + sum_{j in row(i)} d_j * P(l-1)[j],
- *                             d_j = min(step_fanouts[l-1], deg_j) / deg_j, l = 1..num_steps, in
- *                             double precision, products rounded on their own, every row summed
- *                             in adjacency order.  (The sampling ratio is that of the node that
- *                             passes mass on, (A D + I) P; the paper prints (D A + I) P, which
- *                             makes all nodes of degree >= fanout score alike.)  The num_cached
- *                             nodes of highest P(num_steps) are cached (ties: lower id).
- *                             scores_out (device double [num_nodes], may be NULL) receives
- *                             P(num_steps).  Membership is the deterministic top of the score, not
- *                             a draw from it.
+ *                             P(0) = 1/num_train on train_ids, 0 elsewhere, then num_steps steps with
+ *                             the sampling ratio d_v = min(step_fanouts[l-1], deg_v) / deg_v (0 for an
+ *                             empty row), deg_v the length of row v.  With A[v][u] = 1 for u in row(v)
+ *                             (row v = the nodes v samples from) and D = diag(d), plan->walk_form
+ *                             chooses how Eq. 15's matrix D A + I is applied:
+ *                             MQG_WALK_PUSH (0, the default) along the direction in which sampling
+ *                               moves, P(l) = (D A + I)^T P(l-1):
+ *                                 P(l)[u] = P(l-1)[u] + sum over v with u in row(v) of d_v * P(l-1)[v],
+ *                               the terms of u added in ascending order of v.  A node that holds mass
+ *                               reaches each node of its row with probability d_v, so P(l)[u] is the
+ *                               expected number of times u has entered the sampled frontier: the
+ *                               nodes reached from the training set, which is what the cache wants.
+ *                               The library transposes the adjacency for this (one stable sort of
+ *                               the edges by column: about 24 bytes of temporary device memory per
+ *                               edge, fewer than 2^31 edges) unless plan->graph_symmetric is set.
+ *                             MQG_WALK_PRINTED (1) Eq. 15 exactly as printed, P a column vector,
+ *                               P(l) = (D A + I) P(l-1):
+ *                                 P(l)[i] = P(l-1)[i] + d_i * sum_{j in row(i)} P(l-1)[j],
+ *                               the row summed in adjacency order, then scaled.  It moves mass
+ *                               against the sampling direction; on a directed graph it scores nodes
+ *                               that sampling from the training set never reaches, and after one
+ *                               step from a uniform start every node of degree >= fanout scores alike.
+ *                             On a graph that equals its transpose the push form is
+ *                             P(l)[u] = P(l-1)[u] + sum_{v in row(u)} d_v * P(l-1)[v], (A D + I) P.
+ *                             plan->graph_symmetric != 0 states that the graph equals its transpose
+ *                             and that every row is in ascending order of id; the push form then sums
+ *                             over the adjacency rows themselves and builds nothing.  The statement is
+ *                             not checked: if it is false the result is that row-wise sum, not the
+ *                             push form (no access leaves the arrays either way).
+ *                             Double precision, products rounded on their own.  The num_cached nodes
+ *                             of highest P(num_steps) are cached (ties: lower id).  scores_out
+ *                             (device double [num_nodes], may be NULL) receives P(num_steps).
+ *                             Membership is the deterministic top of the score, not a draw from it.
+ *                             A training id outside [0, num_nodes) is never used as an index: it is
+ *                             skipped and the call returns MQG_ERR_INVALID_ARG once the work is done.
  *   MQG_CACHE_RANDOM_WALK_SAMPLED  the same scores, membership drawn from them (the text after
  *                             Eq. 15 takes P(L) as the probability of entering the cache): weighted
  *                             sampling without replacement by an exponential race, key_i =
@@ -230,6 +254,8 @@ int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stre
 typedef enum { MQG_CACHE_TOP_DEGREE = 0, MQG_CACHE_DEGREE_SAMPLED = 1, MQG_CACHE_RANDOM_WALK = 2,
                MQG_CACHE_RANDOM_WALK_SAMPLED = 3 } mqg_cache_policy;
 
+typedef enum { MQG_WALK_PUSH = 0, MQG_WALK_PRINTED = 1 } mqg_walk_form;
+
 typedef struct mqg_cache_plan {
     int32_t policy;                      /* mqg_cache_policy                             */
     int32_t num_steps;                   /* RANDOM_WALK: number of steps L, 0..MQG_MAX_LAYERS */
@@ -238,6 +264,8 @@ typedef struct mqg_cache_plan {
     int64_t num_train;
     const int32_t *step_fanouts;         /* RANDOM_WALK: host [num_steps], each >= 1     */
     double *scores_out;                  /* RANDOM_WALK: optional                        */
+    int32_t walk_form;                   /* RANDOM_WALK: mqg_walk_form                   */
+    int32_t graph_symmetric;             /* RANDOM_WALK, push form: see above            */
 } mqg_cache_plan;
 
 /* mqg_build_cache with a choice of policy; plan == NULL means MQG_CACHE_TOP_DEGREE.  Otherwise as
@@ -377,6 +405,20 @@ int mqg_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys_dev, const uint
                               uint32_t *out_mask_dev, mqg_stream stream);
 
 /*
+ * The ticket of the exponential races on its own (the draw from the random-walk
+ * scores after Eq. 15 and the layer-wise draws of Eq. 6-10 race with key =
+ * ticket / weight): tickets_dev[i] = ticket(r_i), r_i = mix(mix(mix(mix(seed + G)
+ * ^ tag) ^ (first + i))) - slot 0 of node first + i in the key domain `tag` -
+ * and ticket(r) = -log2(r / 2^64) in fixed point with 32 fractional bits as
+ * described for MQG_CACHE_RANDOM_WALK_SAMPLED.  A pure integer function, exposed
+ * so that a test can compare a long stretch of the stream, over thousands of
+ * workgroups, with the same function computed on the CPU.
+ *   tickets_dev  device [n] unsigned 64-bit
+ */
+int mqg_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int64_t n,
+                    uint64_t *tickets_dev, mqg_stream stream);
+
+/*
  * Cache-prioritised neighbour sampling (paper Sec. I on global neighbour
  * sampling: the sampler prefers neighbours that are in the cache, which cuts
  * the number of distinct uncached rows a mini-batch needs).  After this call
@@ -408,6 +450,9 @@ int mqg_ctx_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *graph, const mq
  *                the copy is rounded up to whole 64-byte lines (16-byte words)
  *   stats_dev    device int64[2]: rows served from the cache, rows served
  *                from feats; may be NULL
+ * An id outside [0, cache->num_nodes) is never used as an index: its output row
+ * is left untouched and it counts in neither stat, so stats[0] + stats[1] below
+ * the number of ids tells the caller that some were invalid.
  */
 int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
                         const void *ids_dev, const int64_t *num_ids_dev, int64_t cap_ids,

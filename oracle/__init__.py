@@ -89,6 +89,8 @@ def _load():
     lib.orc_debias_coefficients.argtypes = [vp, i64, i64, vp]
     lib.orc_exp_ticket.restype = u64
     lib.orc_exp_ticket.argtypes = [u64]
+    lib.orc_exp_tickets.restype = None
+    lib.orc_exp_tickets.argtypes = [u64, i64, i64, i64, vp]
     lib.orc_build_cache_drawn_by_score.restype = ctypes.c_int
     lib.orc_build_cache_drawn_by_score.argtypes = [i64, vp, i64, u64, vp, vp]
     _lib = lib
@@ -201,6 +203,13 @@ def build_cache_by_score(scores: np.ndarray, num_cached: int, feats: Optional[np
 
 def exp_ticket(r: int) -> int:
     return int(_load().orc_exp_ticket(ctypes.c_uint64(r & 0xFFFFFFFFFFFFFFFF)))
+
+
+def exp_tickets(seed: int, layer: int, first: int, n: int) -> np.ndarray:
+    """exp_ticket(key(seed, layer, first + i, 0)) for i in [0, n), as uint64."""
+    out = np.zeros(max(1, n), dtype=np.uint64)
+    _load().orc_exp_tickets(ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), layer, first, n, _p(out))
+    return out[:n]
 
 
 def build_cache_drawn_by_score(scores: np.ndarray, num_cached: int, seed: int,

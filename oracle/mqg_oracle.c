@@ -786,6 +786,12 @@ uint64_t orc_exp_ticket(uint64_t r)
     return ((uint64_t)(lz + 1) << 32) - frac;
 }
 
+/* tickets[i] = orc_exp_ticket(orc_key(seed, layer, first + i, 0)): a stretch of the ticket stream of one draw. */
+void orc_exp_tickets(uint64_t seed, int64_t layer, int64_t first, int64_t n, uint64_t *tickets)
+{
+    for (int64_t i = 0; i < n; ++i) tickets[i] = orc_exp_ticket(orc_key(seed, layer, first + i, 0));
+}
+
 /* Domain tag of the draw below (apart from the blocks' and from the degree-proportional draw). */
 #define ORC_SCORE_DRAW_LAYER (-2)
 

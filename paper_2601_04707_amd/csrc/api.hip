@@ -295,6 +295,11 @@ int mqg_build_cache_ex(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, const
             for (int l = 0; l < plan->num_steps; ++l)
                 if (plan->step_fanouts[l] < 1) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: step fanout below 1");
             if (g->num_edges > 0 && !g->col_idx) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: col_idx is NULL");
+            if (plan->walk_form != MQG_WALK_PUSH && plan->walk_form != MQG_WALK_PRINTED)
+                return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: unknown walk_form");
+            if (plan->walk_form == MQG_WALK_PUSH && !plan->graph_symmetric && g->num_edges >= (int64_t(1) << 31))
+                return fail(ctx, MQG_ERR_UNSUPPORTED, "mqg_build_cache_ex: the push form transposes the adjacency, which is built for "
+                                                      "fewer than 2^31 edges (set graph_symmetric if the graph equals its transpose)");
         }
     }
     return mqg::run_build_cache(ctx, g, cache, plan, static_cast<hipStream_t>(stream));
@@ -412,6 +417,15 @@ int mqg_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys_dev, const uint
         return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_select_row_candidates: NULL argument");
     return mqg::run_select_row_candidates(ctx, keys_dev, slot_words_dev, count, k, prioritised ? 1 : 0, ordered ? 1 : 0,
                                           out_mask_dev, static_cast<hipStream_t>(stream));
+}
+
+int mqg_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int64_t n, uint64_t *tickets_dev,
+                    mqg_stream stream) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    if (n < 0 || n >= (int64_t(1) << 31) * mqg::kBlock) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_exp_tickets: n out of range");
+    if (n > 0 && !tickets_dev) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_exp_tickets: tickets_dev is NULL");
+    if (n == 0) return MQG_OK;
+    return mqg::run_exp_tickets(ctx, seed, tag, first, n, tickets_dev, static_cast<hipStream_t>(stream));
 }
 
 int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,

@@ -6,10 +6,14 @@
 //                    without replacement.  Every adjacency slot is a ticket with a uniform 64-bit
 //                    key, a node's key is the minimum over its tickets (k_ticket_keys), nodes are
 //                    ranked by (key, id) ascending - an exponential race in integer arithmetic
-//   random walk      Eq. 14-15: L propagation steps from the training set, every node passing
-//                    d_j * P[j] to its neighbours (k_rw_pass, k_rw_step; double precision, every
-//                    row summed in adjacency order so that the result does not depend on the
-//                    schedule), ranked by (P^(L) descending, id ascending)
+//   random walk      Eq. 14-15: L propagation steps from the training set, ranked by (P^(L) descending,
+//                    id ascending).  Push form: every node hands d_v * P[v] to the nodes of its
+//                    row, the terms of a node added in ascending order of v - computed as a sum
+//                    over the rows of the transposed adjacency (k_edge_pairs, a stable radix sort
+//                    by column, k_in_ptr), or over the adjacency itself when the caller states
+//                    that the graph equals its transpose.  Printed form: a node collects
+//                    d_i * sum of P over its row.  k_rw_pass, k_rw_step: double precision, every
+//                    row summed in order, so the result does not depend on the schedule
 // 64-bit keys are ordered by two stable 32-bit radix sorts (low word, then high word).
 //
 // The ranking is a stable least-significant-digit radix sort of (max_degree - degree) with the
@@ -29,7 +33,7 @@
 
 namespace mqg {
 
-int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, int64_t cap, const void *src,
+int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, int64_t cap, int64_t src_rows, const void *src,
                       int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes, hipStream_t s);
 
 namespace {
@@ -118,19 +122,74 @@ k_ticket_keys(const PtrT *__restrict__ row_ptr, int64_t n, uint64_t tag_hash, ui
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_rw_seed(const IdxT *__restrict__ train_ids, int64_t num_train, double *__restrict__ p) {
+k_rw_seed(const IdxT *__restrict__ train_ids, int64_t num_train, int64_t n, double *__restrict__ p,
+          uint32_t *__restrict__ flags) {
     int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-    if (t < num_train) p[train_ids[t]] = 1.0 / static_cast<double>(num_train);
+    if (t >= num_train) return;
+    const int64_t id = static_cast<int64_t>(train_ids[t]);
+    if (id < 0 || id >= n) atomicOr(flags, 1u);            // reported by the host; never used as an index
+    else p[id] = 1.0 / static_cast<double>(num_train);
 }
 
-// A step of the random-walk scores, in two kernels.
-//   k_rw_pass   pass[j] = d_j * P[j], d_j = min(fanout, deg_j) / deg_j: what a node that holds mass
-//               P[j] hands to each of its neighbours (the sampling ratio belongs to the node that
-//               samples; see the header for this reading of Eq. 15)
-//   k_rw_step   P_next[i] = P[i] + sum_{j in row(i)} pass[j], every row summed strictly in adjacency
-//               order (rows of up to 16 entries by their lane, longer rows by the wavefront: 64
+// The adjacency as (column, row) pairs in row order: keys[e] = col_idx[e], vals[e] = the row that
+// holds slot e.  Sorted stably by key they are the transposed adjacency with every in-list in
+// ascending order of the row.  Rows of up to 16 slots are written by their lane, longer rows by
+// the wavefront.
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_edge_pairs(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n,
+             uint32_t *__restrict__ keys, int32_t *__restrict__ vals) {
+    const int lane = lane_id();
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    int64_t b = 0;
+    int deg = 0;
+    if (i < n) {
+        b = static_cast<int64_t>(row_ptr[i]);
+        deg = static_cast<int>(static_cast<int64_t>(row_ptr[i + 1]) - b);
+    }
+    if (deg <= 16)
+        for (int p = 0; p < deg; ++p) {
+            keys[b + p] = static_cast<uint32_t>(col_idx[b + p]);
+            vals[b + p] = static_cast<int32_t>(i);
+        }
+    uint64_t big = ballot64(deg > 16);
+    while (big) {
+        const int l = __ffsll(static_cast<long long>(big)) - 1;
+        big &= big - 1;
+        const int dl = static_cast<int>(readlane32(static_cast<uint32_t>(deg), l));
+        const int64_t bl = static_cast<int64_t>(readlane64(static_cast<uint64_t>(b), l));
+        const int32_t row = static_cast<int32_t>(readlane64(static_cast<uint64_t>(i), l));
+        for (int c = lane; c < dl; c += kWave) {
+            keys[bl + c] = static_cast<uint32_t>(col_idx[bl + c]);
+            vals[bl + c] = row;
+        }
+    }
+}
+
+// in_ptr[u] = first position in the sorted column array whose column is >= u (bisection), u = 0..n
+__global__ void __launch_bounds__(kBlock)
+k_in_ptr(const uint32_t *__restrict__ sorted_cols, int64_t num_edges, int64_t n, int32_t *__restrict__ in_ptr) {
+    const int64_t u = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (u > n) return;
+    int64_t lo = 0, hi = num_edges;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (static_cast<int64_t>(sorted_cols[mid]) < u) lo = mid + 1; else hi = mid;
+    }
+    in_ptr[u] = static_cast<int32_t>(lo);
+}
+
+// A step of the random-walk scores.
+//   k_rw_pass   share[v] = d_v * P[v], d_v = min(fanout, deg_v) / deg_v: what a node that holds mass
+//               P[v] hands to each node of its row (push form)
+//   k_rw_step   P_next[i] = P[i] + scale_i * sum_{j in list(i)} val[j], every list added strictly in
+//               order (push form: onto P[i], term by term; printed form: from zero, then scaled) (lists of up to 16 entries by their lane, longer ones by the wavefront: 64
 //               values are fetched in parallel and then added one after the other) - bit for bit
-//               the plain sequential loop, whatever the schedule
+//               the plain sequential loop, whatever the schedule.
+//               Push form: list = the in-list of i in ascending order of the source (the
+//               transposed adjacency, or the adjacency itself on a graph that equals its
+//               transpose), val = share, no scale.  Printed form (scale_fanout > 0): list = the
+//               row of i, val = P, scale_i = d_i, the product rounded before the addition.
 template <typename PtrT>
 __global__ void __launch_bounds__(kBlock)
 k_rw_pass(const PtrT *__restrict__ row_ptr, int64_t n, int fanout, const double *__restrict__ cur,
@@ -148,7 +207,8 @@ k_rw_pass(const PtrT *__restrict__ row_ptr, int64_t n, int fanout, const double 
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, int64_t n,
-          const double *__restrict__ cur, const double *__restrict__ pass, double *__restrict__ next) {
+          const double *__restrict__ cur, const double *__restrict__ pass, double *__restrict__ next,
+          int scale_fanout) {
 #pragma clang fp contract(off)
     const int lane = lane_id();
     const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
@@ -158,7 +218,11 @@ k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, in
         b = static_cast<int64_t>(row_ptr[i]);
         deg = static_cast<int>(static_cast<int64_t>(row_ptr[i + 1]) - b);
     }
-    double acc = 0.0;
+    // push form: the terms are added onto the node's own mass, one after the other; printed form: the
+    // row is summed from zero, scaled, and added to the node's mass
+    const double own = i < n ? cur[i] : 0.0;
+    const double start = scale_fanout > 0 ? 0.0 : own;
+    double acc = start;
     if (deg <= 16)
         for (int p = 0; p < deg; ++p) acc = acc + pass[col_idx[b + p]];
     uint64_t big = ballot64(deg > 16);
@@ -167,7 +231,7 @@ k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, in
         big &= big - 1;
         const int dl = static_cast<int>(readlane32(static_cast<uint32_t>(deg), l));
         const int64_t bl = static_cast<int64_t>(readlane64(static_cast<uint64_t>(b), l));
-        double a = 0.0;
+        double a = __longlong_as_double(static_cast<long long>(readlane64(static_cast<uint64_t>(__double_as_longlong(start)), l)));
         for (int c0 = 0; c0 < dl; c0 += kWave) {
             const int m = dl - c0 < kWave ? dl - c0 : kWave;
             double val = 0.0;
@@ -177,7 +241,16 @@ k_rw_step(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, in
         }
         if (lane == l) acc = a;
     }
-    if (i < n) next[i] = cur[i] + acc;
+    if (i < n) {
+        if (scale_fanout > 0) {
+            const double keep = deg < scale_fanout ? static_cast<double>(deg) : static_cast<double>(scale_fanout);
+            const double d = deg > 0 ? keep / static_cast<double>(deg) : 0.0;
+            const double scaled = d * acc;
+            next[i] = own + scaled;
+        } else {
+            next[i] = acc;
+        }
+    }
 }
 
 // ascending radix order of ~bits(score) = descending score (scores are non-negative)
@@ -199,6 +272,15 @@ k_draw_keys(const double *__restrict__ score, int64_t n, uint64_t tag_hash, uint
     const double sc = score[v];
     const double key = sc > 0.0 ? t / sc : __longlong_as_double(0x7FF0000000000000LL);
     key64[v] = static_cast<uint64_t>(__double_as_longlong(key));
+}
+
+// tickets[i] = exp_ticket64 of the random bits of (seed, tag, first + i, slot 0): the ticket stream on its own
+__global__ void __launch_bounds__(kBlock)
+k_exp_tickets(uint64_t tag_hash, int64_t first, int64_t n, uint64_t *__restrict__ tickets) {
+    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (i >= n) return;
+    const uint64_t r = mix64(mix64(tag_hash ^ static_cast<uint64_t>(first + i)));
+    tickets[i] = exp_ticket64(r);
 }
 
 __global__ void __launch_bounds__(kBlock)
@@ -291,6 +373,7 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
     Temp tmp;
     const int ngrid = static_cast<int>(ceil_div(n, kBlock));
     const int32_t *ranked = nullptr;
+    uint32_t *walk_flags = nullptr;                  // bit 0: a training id outside the graph
 
     if (policy == MQG_CACHE_TOP_DEGREE) {
         uint32_t *keys_a, *max_deg_dev;
@@ -331,33 +414,72 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
     } else {  // MQG_CACHE_RANDOM_WALK, MQG_CACHE_RANDOM_WALK_SAMPLED
         double *pa, *pb, *pass;
         uint64_t *key64;
-        if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&pass, n) && tmp.alloc(&key64, n)))
+        if (!(tmp.alloc(&pa, n) && tmp.alloc(&pb, n) && tmp.alloc(&pass, n) && tmp.alloc(&key64, n) && tmp.alloc(&walk_flags, 1)))
             return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
         e = hipMemsetAsync(pa, 0, static_cast<size_t>(n) * sizeof(double), s);
+        if (e == hipSuccess) e = hipMemsetAsync(walk_flags, 0, sizeof(uint32_t), s);
         if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
         if (plan->num_train > 0) {
             const int tgrid = static_cast<int>(ceil_div(plan->num_train, kBlock));
             if (g->idx_type == MQG_I64)
-                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int64_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(plan->train_ids), plan->num_train, pa)));
+                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int64_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(plan->train_ids), plan->num_train, n, pa, walk_flags)));
             else
-                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int32_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(plan->train_ids), plan->num_train, pa)));
+                MQG_LAUNCH(ctx, "k_rw_seed", s, (k_rw_seed<int32_t><<<tgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(plan->train_ids), plan->num_train, n, pa, walk_flags)));
+        }
+        const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
+        const bool printed = plan->walk_form == MQG_WALK_PRINTED;
+        // push form on a graph that is not known to equal its transpose: the in-lists, sources ascending
+        const int32_t *in_ptr = nullptr, *in_src = nullptr;
+        if (!printed && !plan->graph_symmetric && plan->num_steps > 0) {
+            const int64_t ne = g->num_edges;
+            uint32_t *cols;
+            int32_t *rows_of, *ptr_t;
+            RadixBufs rb;
+            bool ok = tmp.alloc(&cols, ne) && tmp.alloc(&rows_of, ne) && tmp.alloc(&ptr_t, n + 1) && tmp.alloc(&rb.keys[0], ne) &&
+                      tmp.alloc(&rb.keys[1], ne) && tmp.alloc(&rb.vals[0], ne) && tmp.alloc(&rb.vals[1], ne) &&
+                      tmp.alloc(&rb.hist, radix_hist_len(ne)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles(ne));
+            if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed (transposed adjacency)");
+            if (ne > 0) {
+                if (p64 && i64)
+                    MQG_LAUNCH(ctx, "k_edge_pairs", s, (k_edge_pairs<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cols, rows_of)));
+                else if (p64)
+                    MQG_LAUNCH(ctx, "k_edge_pairs", s, (k_edge_pairs<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cols, rows_of)));
+                else if (i64)
+                    MQG_LAUNCH(ctx, "k_edge_pairs", s, (k_edge_pairs<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cols, rows_of)));
+                else
+                    MQG_LAUNCH(ctx, "k_edge_pairs", s, (k_edge_pairs<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cols, rows_of)));
+            }
+            int bits = 0;
+            while (bits < 32 && (static_cast<uint64_t>(n - 1) >> bits) != 0) bits += 8;
+            int which = -1;
+            int rc0 = radix_sort_pairs(ctx, cols, rows_of, rb, ne, nullptr, bits, s, &which);
+            if (rc0 != MQG_OK) return rc0;
+            const uint32_t *sorted_cols = which < 0 ? cols : rb.keys[which];
+            in_src = which < 0 ? rows_of : rb.vals[which];
+            MQG_LAUNCH(ctx, "k_in_ptr", s, (k_in_ptr<<<static_cast<int>(ceil_div(n + 1, kBlock)), kBlock, 0, s>>>(sorted_cols, ne, n, ptr_t)));
+            in_ptr = ptr_t;
         }
         double *cur = pa, *next = pb;
         for (int l = 0; l < plan->num_steps; ++l) {
             const int fo = plan->step_fanouts[l];
-            const bool p64 = g->ptr_type == MQG_I64, i64 = g->idx_type == MQG_I64;
-            if (p64)
-                MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, fo, cur, pass)));
-            else
-                MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, fo, cur, pass)));
-            if (p64 && i64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, pass, next)));
+            if (!printed) {
+                if (p64)
+                    MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), n, fo, cur, pass)));
+                else
+                    MQG_LAUNCH(ctx, "k_rw_pass", s, (k_rw_pass<int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), n, fo, cur, pass)));
+            }
+            const double *val = printed ? cur : pass;
+            const int scale = printed ? fo : 0;
+            if (in_ptr)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(in_ptr, in_src, n, cur, val, next, scale)));
+            else if (p64 && i64)
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, val, next, scale)));
             else if (p64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, pass, next)));
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int64_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int64_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, val, next, scale)));
             else if (i64)
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, pass, next)));
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int64_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int64_t *>(g->col_idx), n, cur, val, next, scale)));
             else
-                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, pass, next)));
+                MQG_LAUNCH(ctx, "k_rw_step", s, (k_rw_step<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cur, val, next, scale)));
             std::swap(cur, next);
         }
         if (plan->scores_out) {
@@ -385,12 +507,26 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         else
             MQG_LAUNCH(ctx, "k_assign_slots", s, (k_assign_slots<int32_t><<<cgrid, kBlock, 0, s>>>(ranked, c->num_cached, c->slot_of, static_cast<int32_t *>(c->cached_ids))));
         MQG_LAUNCH(ctx, "k_store_i64", s, (k_store_i64<<<1, 64, 0, s>>>(count_dev, c->num_cached)));
-        int rc = gather_direct_i32(ctx, ranked, count_dev, c->num_cached, c->feats, c->feat_stride * elt, c->cache_rows,
+        int rc = gather_direct_i32(ctx, ranked, count_dev, c->num_cached, n, c->feats, c->feat_stride * elt, c->cache_rows,
                                    c->cache_stride * elt, int64_t(c->dim) * elt, s);
         if (rc != MQG_OK) return rc;
     }
+    uint32_t flags = 0;
+    if (walk_flags) {
+        e = hipMemcpyAsync(&flags, walk_flags, sizeof(uint32_t), hipMemcpyDeviceToHost, s);
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
+    }
     e = hipStreamSynchronize(s);                     // temporaries are freed on return
     if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
+    if (flags & 1u)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_build_cache_ex: a training id lies outside [0, num_nodes); it was skipped and the "
+                                               "cache was filled from the remaining ones");
+    return MQG_OK;
+}
+
+int run_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int64_t n, uint64_t *tickets, hipStream_t s) {
+    const uint64_t tag_hash = host_mix64(host_mix64(seed + kGolden) ^ static_cast<uint64_t>(tag));
+    MQG_LAUNCH(ctx, "k_exp_tickets", s, (k_exp_tickets<<<static_cast<int>(ceil_div(n, kBlock)), kBlock, 0, s>>>(tag_hash, first, n, tickets)));
     return MQG_OK;
 }
 

@@ -163,6 +163,7 @@ void free_layerwise_scratch(mqg_ctx *ctx);
 int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int64_t k, uint32_t *out_bitmap, hipStream_t s);
 int run_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys, const uint32_t *slot_words, int32_t cnt, int32_t k,
                               int32_t prioritised, int32_t ordered, uint32_t *out_mask, hipStream_t s);
+int run_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int64_t n, uint64_t *tickets, hipStream_t s);
 int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s);
 // hash-table dedup (dedup_hash.hip)
 int ensure_hash_scratch(mqg_ctx *ctx);

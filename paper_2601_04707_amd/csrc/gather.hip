@@ -21,12 +21,21 @@ namespace mqg {
 
 namespace {
 
-__global__ void k_direct_stats(int64_t *stats, const int64_t *num_ids, int64_t cap) {
+// Stats of a gather without a cache: every valid id is a row served from feats.  counters[3] holds
+// the number of ids outside the graph that the copy skipped; it is left at zero for the next call.
+__global__ void k_direct_stats(int64_t *stats, const int64_t *num_ids, int64_t cap, unsigned long long *counters) {
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         int64_t n = *num_ids;
         if (n > cap) n = cap;
-        stats[0] = 0;
-        stats[1] = n < 0 ? 0 : n;
+        if (n < 0) n = 0;
+        if (counters) {
+            n -= static_cast<int64_t>(counters[3]);
+            counters[3] = 0;
+        }
+        if (stats) {
+            stats[0] = 0;
+            stats[1] = n;
+        }
     }
 }
 
@@ -37,12 +46,14 @@ constexpr int kClassifyTile = kBlock * kClassifyItems;
 // A workgroup classifies a tile of 1024 ids, scans its hit and miss counts together (packed in
 // one int) and reserves its share of both lists with one atomic each, so the two counters see
 // about a hundred atomics per mini-batch instead of one per wavefront.  The order of the list
-// entries is arbitrary; the gather does not depend on it.
+// entries is arbitrary; the gather does not depend on it.  An id outside [0, num_nodes) is never
+// used as an index: it goes on neither list, so its output row stays untouched and hits + misses
+// fall short of the number of ids.
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
-           const int32_t *__restrict__ slot_of, int2 *__restrict__ hit_list, int2 *__restrict__ miss_list,
-           unsigned long long *__restrict__ counters) {
+           const int32_t *__restrict__ slot_of, int64_t num_nodes, int2 *__restrict__ hit_list,
+           int2 *__restrict__ miss_list, unsigned long long *__restrict__ counters) {
     __shared__ int lds[kWavesPerBlock];
     __shared__ unsigned long long base[2];
     int64_t n = *num_ids;
@@ -56,9 +67,12 @@ k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, in
             id[q] = -1;
             slot[q] = -1;
             if (i < n) {
-                id[q] = static_cast<int32_t>(ids[i]);
-                slot[q] = slot_of[id[q]];
-                if (slot[q] >= 0) ++h; else ++m;
+                const int64_t raw = static_cast<int64_t>(ids[i]);
+                if (raw >= 0 && raw < num_nodes) {          // an id outside the graph is on neither list
+                    id[q] = static_cast<int32_t>(raw);
+                    slot[q] = slot_of[id[q]];
+                    if (slot[q] >= 0) ++h; else ++m;
+                }
             }
         }
         int total;
@@ -80,20 +94,33 @@ k_classify(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, in
 }
 
 // Which rows to copy: entry r of a (output row, source row) list, or row ids[r] to output row r.
+// get() returns false for a row that must not be written (an id outside the feature matrix); the
+// source row is then 0, so that a load issued before the check stays inside the matrix.  skipped()
+// is called once per such row.
 struct ListRows {
     const int2 *list;
-    __device__ __forceinline__ void get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
+    __device__ __forceinline__ bool get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
         int2 e = list[r];
         *src_row = e.y;
         *dst_row = e.x;
+        return true;
     }
+    __device__ __forceinline__ void skipped() const {}
 };
 template <typename IdxT>
 struct DirectRows {
     const IdxT *ids;
-    __device__ __forceinline__ void get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
-        *src_row = static_cast<int64_t>(ids[r]);
+    int64_t num_rows;                    // rows of the source matrix
+    unsigned long long *bad;             // counter of skipped rows, may be null
+    __device__ __forceinline__ bool get(int64_t r, int64_t *src_row, int64_t *dst_row) const {
+        const int64_t id = static_cast<int64_t>(ids[r]);
+        const bool ok = id >= 0 && id < num_rows;
+        *src_row = ok ? id : 0;
         *dst_row = r;
+        return ok;
+    }
+    __device__ __forceinline__ void skipped() const {
+        if (bad) atomicAdd(bad, 1ull);
     }
 };
 
@@ -116,9 +143,10 @@ __device__ __forceinline__ void copy_rows_wide(const Rows &rows, int64_t n, cons
 #pragma unroll
         for (int q = 0; q < WR; ++q) {
             const int64_t r = r0 + q;
-            rok[q] = r < n;
             int64_t srow, drow;
-            rows.get(rok[q] ? r : n - 1, &srow, &drow);          // a row past the end re-reads the last one
+            const bool valid = rows.get(r < n ? r : n - 1, &srow, &drow);          // a row past the end re-reads the last one
+            if (r < n && !valid && lane == 0) rows.skipped();
+            rok[q] = r < n && valid;
             sp[q] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes);
             dp[q] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes);
         }
@@ -177,9 +205,13 @@ __device__ __forceinline__ void copy_rows(const Rows &rows, int64_t n, const cha
 #pragma unroll
         for (int u = 0; u < kRowUnroll; ++u) {
             const int64_t r = base + u * groups + g;
-            ok[u] = r < n && gl < vecs;
             int64_t srow = 0, drow = 0;
-            if (r < n) rows.get(r, &srow, &drow);
+            bool valid = false;
+            if (r < n) {
+                valid = rows.get(r, &srow, &drow);
+                if (!valid && gl == 0) rows.skipped();
+            }
+            ok[u] = valid && gl < vecs;
             sp[u] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes) + gl;
             dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + gl;
         }
@@ -218,7 +250,9 @@ __device__ __forceinline__ void copy_rows_flat(const Rows &rows, int64_t n, cons
             const int64_t row = static_cast<int64_t>(__umul64hi(tc, magic));
             const int64_t col = static_cast<int64_t>(tc) - row * vecs;
             int64_t srow, drow;
-            rows.get(row, &srow, &drow);
+            const bool valid = rows.get(row, &srow, &drow);
+            if (ok[u] && !valid && col == 0) rows.skipped();
+            ok[u] = ok[u] && valid;
             sp[u] = reinterpret_cast<const VecT *>(src + srow * src_stride_bytes) + col;
             dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + col;
         }
@@ -262,13 +296,14 @@ k_gather_rows(const int2 *__restrict__ list, const unsigned long long *count,
 
 template <typename VecT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_gather_direct(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap,
-                const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
+k_gather_direct(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_ids, int64_t cap, int64_t src_rows,
+                unsigned long long *bad, const char *__restrict__ src, int64_t src_stride_bytes, char *__restrict__ dst,
                 int64_t dst_stride_bytes, int vecs, int log2_lpr, unsigned long long magic) {
     int64_t n = *num_ids;
     if (n > cap) n = cap;
-    if (magic) copy_rows_flat<VecT>(DirectRows<IdxT>{ids}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic);
-    else copy_rows<VecT>(DirectRows<IdxT>{ids}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
+    const DirectRows<IdxT> rows{ids, src_rows, bad};
+    if (magic) copy_rows_flat<VecT>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic);
+    else copy_rows<VecT>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
 }
 
 // Widest power-of-two access (16, 8, 4 or 2 bytes) that keeps every row of both sides aligned.
@@ -378,9 +413,9 @@ int launch_rows(mqg_ctx *ctx, const char *name, const int2 *list, const unsigned
 
 // from_host: the source is host memory, so the launch is sized for the link
 template <typename IdxT>
-int launch_direct(mqg_ctx *ctx, const IdxT *ids, const int64_t *num_ids, int64_t cap, const void *src,
-                  int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes, bool from_host,
-                  hipStream_t s) {
+int launch_direct(mqg_ctx *ctx, const IdxT *ids, const int64_t *num_ids, int64_t cap, int64_t src_rows,
+                  unsigned long long *bad, const void *src, int64_t src_stride_bytes, void *dst,
+                  int64_t dst_stride_bytes, int64_t row_bytes, bool from_host, hipStream_t s) {
     row_bytes = copy_bytes(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst, !from_host);
     const RowGeom g = row_geom(row_bytes, src_stride_bytes, dst_stride_bytes, src, dst);
     int grid = from_host ? link_grid(cap, g, ctx->miss_inflight_bytes) : hbm_grid(cap, g);
@@ -389,10 +424,10 @@ int launch_direct(mqg_ctx *ctx, const IdxT *ids, const int64_t *num_ids, int64_t
     const char *sp = static_cast<const char *>(src);
     char *dp = static_cast<char *>(dst);
     switch (g.vb) {
-        case 16: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint4, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
-        case 8: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint2, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
-        case 4: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint32_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
-        default: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint16_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
+        case 16: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint4, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, src_rows, bad, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
+        case 8: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint2, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, src_rows, bad, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
+        case 4: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint32_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, src_rows, bad, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
+        default: MQG_LAUNCH(ctx, "k_gather_direct", s, (k_gather_direct<uint16_t, IdxT><<<grid, kBlock, 0, s>>>(ids, num_ids, cap, src_rows, bad, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, magic))); break;
     }
     return MQG_OK;
 }
@@ -411,11 +446,11 @@ bool is_host_memory(const void *p) {
 }  // namespace
 
 // Rows listed by 32-bit ids straight from `src` (used by the cache build to fill the cache).
-int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, int64_t cap, const void *src,
-                      int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes,
+int gather_direct_i32(mqg_ctx *ctx, const int32_t *ids, const int64_t *num_ids, int64_t cap, int64_t src_rows,
+                      const void *src, int64_t src_stride_bytes, void *dst, int64_t dst_stride_bytes, int64_t row_bytes,
                       hipStream_t s) {
-    return launch_direct<int32_t>(ctx, ids, num_ids, cap, src, src_stride_bytes, dst, dst_stride_bytes, row_bytes,
-                                  is_host_memory(src), s);
+    return launch_direct<int32_t>(ctx, ids, num_ids, cap, src_rows, nullptr, src, src_stride_bytes, dst, dst_stride_bytes,
+                                  row_bytes, is_host_memory(src), s);
 }
 
 // Host-side argument checks shared by the gather entry points.  max_ids bounds cap_ids when the
@@ -448,7 +483,7 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
     const int64_t elt = c->dtype == MQG_F16 ? 2 : 4;
     const int64_t row_bytes = int64_t(c->dim) * elt;
     if (cap_ids == 0) {
-        if (stats) MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, 0)));
+        if (stats) MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, 0, nullptr)));
         return MQG_OK;
     }
 
@@ -456,14 +491,14 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
         int rc;
         const bool from_host = is_host_memory(c->feats);
         if (idx_type == MQG_I64)
-            rc = launch_direct<int64_t>(ctx, static_cast<const int64_t *>(ids), num_ids, cap_ids, c->feats,
-                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
+            rc = launch_direct<int64_t>(ctx, static_cast<const int64_t *>(ids), num_ids, cap_ids, c->num_nodes, &ctx->counters[3],
+                                        c->feats, c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
         else
-            rc = launch_direct<int32_t>(ctx, static_cast<const int32_t *>(ids), num_ids, cap_ids, c->feats,
-                                        c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
+            rc = launch_direct<int32_t>(ctx, static_cast<const int32_t *>(ids), num_ids, cap_ids, c->num_nodes, &ctx->counters[3],
+                                        c->feats, c->feat_stride * elt, out, out_stride * elt, row_bytes, from_host, s);
         if (rc != MQG_OK) return rc;
-        // every row counts as served from feats
-        if (stats) MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, cap_ids)));
+        // every valid id counts as served from feats; the launch also clears the count of skipped ids
+        MQG_LAUNCH(ctx, "k_direct_stats", s, (k_direct_stats<<<1, 64, 0, s>>>(stats, num_ids, cap_ids, ctx->counters)));
         return MQG_OK;
     }
 
@@ -471,9 +506,9 @@ int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *i
     unsigned long long *counters = ctx->counters;
     const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(cap_ids, kClassifyTile)), 1024));
     if (idx_type == MQG_I64)
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int64_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int64_t *>(ids), num_ids, cap_ids, c->slot_of, c->num_nodes, ctx->hit_list, ctx->miss_list, counters)));
     else
-        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, ctx->hit_list, ctx->miss_list, counters)));
+        MQG_LAUNCH(ctx, "k_classify", s, (k_classify<int32_t><<<cgrid, kBlock, 0, s>>>(static_cast<const int32_t *>(ids), num_ids, cap_ids, c->slot_of, c->num_nodes, ctx->hit_list, ctx->miss_list, counters)));
 
     int rc = launch_rows<0>(ctx, "k_gather_hit", ctx->hit_list, &counters[0], cap_ids, c->cache_rows,
                             c->cache_stride * elt, out, out_stride * elt, row_bytes, stats, counters, s);
@@ -552,7 +587,7 @@ extern "C" int mqg_gather_features_static(const mqg_cache *cache, int32_t idx_ty
         hipStream_t s = static_cast<hipStream_t>(stream);
         // the array keeps what the last call left; the counters have to start at zero (a fill
         // kernel rather than a memset, so that the call can also be recorded into a graph)
-        if (cache->slot_of && cap_ids > 0) {
+        if (cap_ids > 0) {
             k_clear_words<<<1, 64, 0, s>>>(ctx->counters, 8);
             e = hipGetLastError();
             if (e != hipSuccess) return fail(nullptr, MQG_ERR_HIP, std::string("mqg_gather_features_static: k_clear_words: ") + hipGetErrorString(e));

@@ -24,6 +24,7 @@ MQG_I32, MQG_I64 = 0, 1
 MQG_OPT_FORCE_SLOW_SELECT, MQG_OPT_PROFILE, MQG_OPT_MISS_INFLIGHT_BYTES, MQG_OPT_HEAVY_DEGREE, MQG_OPT_DEDUP_HASH = 1, 2, 3, 4, 5
 MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
 MQG_CACHE_TOP_DEGREE, MQG_CACHE_DEGREE_SAMPLED, MQG_CACHE_RANDOM_WALK, MQG_CACHE_RANDOM_WALK_SAMPLED = 0, 1, 2, 3
+MQG_WALK_PUSH, MQG_WALK_PRINTED = 0, 1
 
 EXPORTS = [
     "mqg_version", "mqg_ctx_create", "mqg_ctx_destroy", "mqg_last_error", "mqg_ctx_set_option",
@@ -32,7 +33,7 @@ EXPORTS = [
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
     "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
     "mqg_select_smallest_keys", "mqg_select_row_candidates", "mqg_sample_blocks_seed_dev",
-    "mqg_gather_features_static",
+    "mqg_gather_features_static", "mqg_exp_tickets",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -62,7 +63,8 @@ class CBlock(ctypes.Structure):
 
 class CCachePlan(ctypes.Structure):
     _fields_ = [("policy", _i32), ("num_steps", _i32), ("seed", ctypes.c_uint64), ("train_ids", _vp),
-                ("num_train", _i64), ("step_fanouts", ctypes.POINTER(_i32)), ("scores_out", _vp)]
+                ("num_train", _i64), ("step_fanouts", ctypes.POINTER(_i32)), ("scores_out", _vp),
+                ("walk_form", _i32), ("graph_symmetric", _i32)]
 
 
 lib.mqg_version.restype = _i32
@@ -114,6 +116,8 @@ lib.mqg_select_smallest_keys.restype = ctypes.c_int
 lib.mqg_select_smallest_keys.argtypes = [_vp, _vp, _i64, _i64, _vp, _vp]
 lib.mqg_select_row_candidates.restype = ctypes.c_int
 lib.mqg_select_row_candidates.argtypes = [_vp, _vp, _vp, _i32, _i32, _i32, _i32, _vp, _vp]
+lib.mqg_exp_tickets.restype = ctypes.c_int
+lib.mqg_exp_tickets.argtypes = [_vp, ctypes.c_uint64, _i64, _i64, _i64, _vp, _vp]
 lib.mqg_sample_blocks_seed_dev.restype = ctypes.c_int
 lib.mqg_sample_blocks_seed_dev.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes.POINTER(_i32), _i32, _vp,
                                            ctypes.POINTER(CBlock), _vp]
@@ -319,7 +323,8 @@ def mqg_build_cache(ctx: Context, graph: Graph, cache: Cache, stream=None) -> No
 
 def mqg_build_cache_ex(ctx: Context, graph: Graph, cache: Cache, policy: int, *, seed: int = 0,
                        train_ids: Optional[torch.Tensor] = None, step_fanouts: Sequence[int] = (),
-                       scores_out: Optional[torch.Tensor] = None, stream=None) -> None:
+                       scores_out: Optional[torch.Tensor] = None, walk_form: int = MQG_WALK_PUSH,
+                       graph_symmetric: bool = False, stream=None) -> None:
     """Cache filled by one of the policies MQG_CACHE_*."""
     fo = (_i32 * max(1, len(step_fanouts)))(*step_fanouts)
     if train_ids is not None:
@@ -327,7 +332,8 @@ def mqg_build_cache_ex(ctx: Context, graph: Graph, cache: Cache, policy: int, *,
     if scores_out is not None:
         assert scores_out.is_cuda and scores_out.dtype == torch.float64 and scores_out.numel() >= graph.num_nodes
     plan = CCachePlan(policy, len(step_fanouts), seed & 0xFFFFFFFFFFFFFFFF, _ptr(train_ids),
-                      0 if train_ids is None else train_ids.numel(), fo, _ptr(scores_out))
+                      0 if train_ids is None else train_ids.numel(), fo, _ptr(scores_out), walk_form,
+                      1 if graph_symmetric else 0)
     ctx.check(lib.mqg_build_cache_ex(ctx.h, ctypes.byref(graph.c), ctypes.byref(cache.c), ctypes.byref(plan),
                                      _stream(stream)))
 
@@ -382,6 +388,14 @@ def mqg_select_row_candidates(ctx: Context, keys: torch.Tensor, slot_words: torc
                                             words.data_ptr(), _stream(stream)))
     bits = (words.view(-1, 1) >> torch.arange(32, device=keys.device, dtype=torch.int32)) & 1
     return bits.reshape(-1)[:n].bool()
+
+
+def mqg_exp_tickets(ctx: Context, seed: int, tag: int, first: int, n: int, stream=None) -> torch.Tensor:
+    """The race tickets of nodes first .. first + n - 1 in key domain `tag`, as int64 bit patterns."""
+    out = torch.empty(max(1, n), dtype=torch.int64, device="cuda")
+    ctx.check(lib.mqg_exp_tickets(ctx.h, ctypes.c_uint64(seed & 0xFFFFFFFFFFFFFFFF), tag, first, n, out.data_ptr(),
+                                  _stream(stream)))
+    return out[:n]
 
 
 def mqg_gather_features(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,

@@ -198,6 +198,12 @@ WORKLOADS = {
 }
 
 
+def launch_in_flight(w: Workload) -> int:
+    """Mini-batches kept in flight (contexts x streams) when a workload is timed or checked at full
+    size: what the workload states ("stress": four), otherwise three."""
+    return w.in_flight if w.in_flight > 1 else 3
+
+
 def scaled(w: Workload, factor: float, name: Optional[str] = None) -> Workload:
     """The same workload shape with node and edge counts multiplied by `factor`
     (mean degree, fanouts, feature width and batch size unchanged)."""

@@ -54,9 +54,23 @@ def test_degree_sampled_cache_parity_and_redraw(mqg, ptr, idx):
     assert np.array_equal(out.cpu().numpy(), feats.numpy()[ids.cpu().numpy()])
 
 
+# how the walk is run: (form, graph_symmetric).  The workload graphs equal their transpose and have
+# ascending rows, so the push form may be told so (no transposed copy) or not (sorted copy): same bits.
+WALKS = [("push", False), ("push", True), ("printed", False)]
+
+
+def walk_form(mqg, name):
+    return mqg.MQG_WALK_PRINTED if name == "printed" else mqg.MQG_WALK_PUSH
+
+
+def oracle_form(name):
+    return oracle.WALK_PRINTED if name == "printed" else oracle.WALK_PUSH
+
+
 @pytest.mark.parametrize("ptr,idx", [(torch.int64, torch.int64), (torch.int32, torch.int64)])
 @pytest.mark.parametrize("fanouts", [[5], [15, 10, 5], [10 ** 6, 10 ** 6], []])
-def test_random_walk_cache_parity(mqg, ptr, idx, fanouts):
+@pytest.mark.parametrize("form,symmetric", WALKS)
+def test_random_walk_cache_parity(mqg, ptr, idx, fanouts, form, symmetric):
     rp, ci = graph(ptr=ptr, idx=idx)
     n = rp.numel() - 1
     g = mqg.Graph(to_dev(rp), to_dev(ci))
@@ -67,9 +81,9 @@ def test_random_walk_cache_parity(mqg, ptr, idx, fanouts):
     cache = mqg.Cache(g, feats, num_cached)
     scores = torch.zeros(n, dtype=torch.float64, device="cuda")
     mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(train), step_fanouts=fanouts,
-                           scores_out=scores)
+                           scores_out=scores, walk_form=walk_form(mqg, form), graph_symmetric=symmetric)
     torch.cuda.synchronize()
-    want_scores = oracle.random_walk_scores(rp.numpy(), ci.numpy(), train.numpy(), fanouts)
+    want_scores = oracle.random_walk_scores(rp.numpy(), ci.numpy(), train.numpy(), fanouts, oracle_form(form))
     got_scores = scores.cpu().numpy()
     assert np.array_equal(got_scores, want_scores), float(np.abs(got_scores - want_scores).max())
     want = oracle.build_cache_by_score(want_scores, num_cached, feats.numpy())
@@ -81,6 +95,92 @@ def test_random_walk_cache_parity(mqg, ptr, idx, fanouts):
         reach = np.zeros(n, dtype=bool)
         reach[train.numpy()] = True
         assert reach[want.cached_ids[: len(train) // 2]].mean() > 0.05 or want_scores[want.cached_ids[0]] > 1.0 / len(train)
+
+
+def one_way_graph(n, mean_deg, seed, ptr, idx):
+    """A directed graph with hubs, unsorted rows and mostly one-way edges (row v = whom v samples from)."""
+    rng = np.random.default_rng(seed)
+    m = n * mean_deg
+    w = 1.0 / np.arange(1, n + 1) ** 0.9
+    rows = rng.permutation(n)[rng.choice(n, size=m, p=w / w.sum())]          # skewed row lengths
+    cols = rng.permutation(n)[rng.choice(n, size=m, p=w / w.sum())]          # skewed in-lists, other hubs
+    keep = rows != cols
+    pairs = np.unique(np.stack([rows[keep], cols[keep]], 1), axis=0)
+    pairs = pairs[rng.permutation(len(pairs))]
+    pairs = pairs[np.argsort(pairs[:, 0], kind="stable")]                    # rows grouped, slots in random order
+    rp = np.zeros(n + 1, dtype=np.int64)
+    rp[1:] = np.cumsum(np.bincount(pairs[:, 0], minlength=n))
+    return torch.from_numpy(rp).to(ptr), torch.from_numpy(pairs[:, 1].copy()).to(idx)
+
+
+@pytest.mark.parametrize("ptr,idx", [(torch.int64, torch.int64), (torch.int32, torch.int32), (torch.int64, torch.int32)])
+@pytest.mark.parametrize("form", ["push", "printed"])
+def test_random_walk_forms_on_a_directed_graph(mqg, ptr, idx, form):
+    """Scores bit for bit on a graph where the two forms - and the row-wise sum that a symmetric
+    graph allows - are three different vectors."""
+    rp, ci = one_way_graph(12_000, 30, seed=5, ptr=ptr, idx=idx)
+    n = rp.numel() - 1
+    rp_np, ci_np = rp.numpy().astype(np.int64), ci.numpy().astype(np.int64)
+    indeg = np.bincount(ci_np, minlength=n)
+    assert np.diff(rp_np).max() > 500 and indeg.max() > 500 and (indeg == 0).any() and (np.diff(rp_np) == 0).any()
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, 6, seed=3).pin_memory()
+    ctx = mqg.Context(g, 8, [2])
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 50].to(idx)
+    num_cached = n // 20
+    seen = {}
+    for fanouts in ([7], [15, 10, 5]):
+        cache = mqg.Cache(g, feats, num_cached)
+        scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+        mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(train), step_fanouts=fanouts,
+                               scores_out=scores, walk_form=walk_form(mqg, form))
+        torch.cuda.synchronize()
+        want_scores = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), fanouts, oracle_form(form))
+        assert np.array_equal(scores.cpu().numpy(), want_scores)
+        want = oracle.build_cache_by_score(want_scores, num_cached, feats.numpy())
+        assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), want.cached_ids)
+        assert np.array_equal(cache.slot_of.cpu().numpy(), want.slot_of)
+        seen[len(fanouts)] = want_scores
+    other = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), [15, 10, 5],
+                                      oracle.WALK_PUSH if form == "printed" else oracle.WALK_PRINTED)
+    assert not np.allclose(seen[3], other, rtol=1e-3)
+    if form == "push":
+        # the hint is a statement about the graph, not a switch between forms: on this graph it is
+        # false, and what comes back is the row-wise sum (documented), still without any fault
+        cache = mqg.Cache(g, feats, num_cached)
+        scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+        mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(train), step_fanouts=[15, 10, 5],
+                               scores_out=scores, graph_symmetric=True)
+        torch.cuda.synchronize()
+        assert not np.allclose(scores.cpu().numpy(), seen[3], rtol=1e-3)
+
+
+def test_training_ids_outside_the_graph_are_reported_not_dereferenced(mqg):
+    rp, ci = graph(n=3000, edges=40_000, max_degree=300)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, 4, seed=3).pin_memory()
+    ctx = mqg.Context(g, 8, [2])
+    good = torch.randperm(n, generator=torch.Generator().manual_seed(1))[:40].to(torch.int64)
+    bad = good.clone()
+    bad[3], bad[17] = n, -5
+    guard = torch.full((n + 64,), 7.0, dtype=torch.float64, device="cuda")     # scores_out with a canary behind it
+    cache = mqg.Cache(g, feats, n // 10)
+    with pytest.raises(mqg.MqgError) as err:
+        mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(bad), step_fanouts=[5, 5],
+                               scores_out=guard, graph_symmetric=True)
+    assert err.value.code == mqg.MQG_ERR_INVALID_ARG and "training id" in str(err.value)
+    torch.cuda.synchronize()
+    assert torch.all(guard[n:] == 7.0)
+    # the valid ids were used with the weight 1/num_train each: the oracle on the same list minus the bad ones, rescaled
+    keep = torch.cat([good[:3], good[4:17], good[18:]])
+    want = oracle.random_walk_scores(rp.numpy(), ci.numpy(), keep.numpy(), [5, 5]) * (len(keep) / len(bad))
+    assert np.allclose(guard[:n].cpu().numpy(), want, rtol=1e-12)
+    # and the context is still good for a clean call
+    mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(good), step_fanouts=[5, 5],
+                           scores_out=guard, graph_symmetric=True)
+    torch.cuda.synchronize()
+    assert np.array_equal(guard[:n].cpu().numpy(), oracle.random_walk_scores(rp.numpy(), ci.numpy(), good.numpy(), [5, 5]))
 
 
 @pytest.mark.parametrize("ptr,idx", [(torch.int64, torch.int64), (torch.int32, torch.int32)])
@@ -124,9 +224,27 @@ def test_policy_argument_errors(mqg):
         mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=None, step_fanouts=[0])
     with pytest.raises(mqg.MqgError):
         mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, step_fanouts=[5] * 9)
+    with pytest.raises(mqg.MqgError):
+        mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, step_fanouts=[5], walk_form=2)
     # top degree through the extended call equals the plain call
     a, b = mqg.Cache(g, feats, 100), mqg.Cache(g, feats, 100)
     mqg.mqg_build_cache(ctx, g, a)
     mqg.mqg_build_cache_ex(ctx, g, b, mqg.MQG_CACHE_TOP_DEGREE)
     torch.cuda.synchronize()
     assert torch.equal(a.slot_of, b.slot_of) and torch.equal(a.cached_ids, b.cached_ids)
+
+
+def test_exp_ticket_stream_over_thousands_of_workgroups(mqg):
+    """The integer logarithm behind every exponential race, element by element against the oracle
+    over 5,000 workgroups (many per compute unit): a kernel whose lanes drop iterations of the
+    squaring loop, in whichever workgroup, shows here directly."""
+    rp, ci = graph(n=2000, edges=20_000, max_degree=200)
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    ctx = mqg.Context(g, 8, [2])
+    n = 5000 * 256 + 77
+    for seed, tag, first in ((0, -3, 0), (12345, -2, 10 ** 9), (2 ** 63 + 5, 64, 7)):
+        got = mqg.mqg_exp_tickets(ctx, seed, tag, first, n)
+        torch.cuda.synchronize()
+        want = oracle.exp_tickets(seed, tag, first, n)
+        assert np.array_equal(got.cpu().numpy().view(np.uint64), want)
+    assert mqg.mqg_exp_tickets(ctx, 1, 0, 0, 0).numel() == 0

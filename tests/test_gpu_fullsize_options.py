@@ -41,16 +41,36 @@ def test_cache_policies_full_size(env):
     train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 50].to(torch.int64)
     steps = [10, 25]
     want_scores = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), steps)
-    for policy, seed in ((m.MQG_CACHE_RANDOM_WALK, 0), (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 1), (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 2)):
+    # the ranking once over the transposed adjacency the library builds (110 M edges sorted by column), the draws
+    # with the statement that this graph equals its transpose
+    for policy, seed, symmetric in ((m.MQG_CACHE_RANDOM_WALK, 0, False), (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 1, True),
+                                    (m.MQG_CACHE_RANDOM_WALK_SAMPLED, 2, True)):
         cache = m.Cache(g, feats, num_cached)
         scores = torch.zeros(n, dtype=torch.float64, device="cuda")
-        m.mqg_build_cache_ex(ctx, g, cache, policy, seed=seed, train_ids=train.cuda(), step_fanouts=steps, scores_out=scores)
+        m.mqg_build_cache_ex(ctx, g, cache, policy, seed=seed, train_ids=train.cuda(), step_fanouts=steps, scores_out=scores,
+                             graph_symmetric=symmetric)
         torch.cuda.synchronize()
         assert np.array_equal(scores.cpu().numpy(), want_scores)
         want = (oracle.build_cache_by_score(want_scores, num_cached) if policy == m.MQG_CACHE_RANDOM_WALK
                 else oracle.build_cache_drawn_by_score(want_scores, num_cached, seed))
         assert np.array_equal(cache.cached_ids[:num_cached].cpu().numpy(), want.cached_ids)
         assert np.array_equal(cache.slot_of.cpu().numpy(), want.slot_of)
+
+
+def test_printed_walk_full_size(env):
+    m, w, g, rp, ci, rp_np, ci_np = env
+    n = rp.numel() - 1
+    ctx = m.Context(g, 8, [2])
+    feats = synth.node_features(n, 4, seed=3).pin_memory()
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 50].to(torch.int64)
+    cache = m.Cache(g, feats, n // 10)
+    scores = torch.zeros(n, dtype=torch.float64, device="cuda")
+    m.mqg_build_cache_ex(ctx, g, cache, m.MQG_CACHE_RANDOM_WALK, train_ids=train.cuda(), step_fanouts=[10, 25], scores_out=scores,
+                         walk_form=m.MQG_WALK_PRINTED)
+    torch.cuda.synchronize()
+    want_scores = oracle.random_walk_scores(rp_np, ci_np, train.numpy(), [10, 25], oracle.WALK_PRINTED)
+    assert np.array_equal(scores.cpu().numpy(), want_scores)
+    assert np.array_equal(cache.slot_of.cpu().numpy(), oracle.build_cache_by_score(want_scores, n // 10).slot_of)
 
 
 @pytest.mark.parametrize("fastgcn,debias,flat", [(False, False, False), (True, False, False), (False, True, False),

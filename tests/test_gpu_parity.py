@@ -313,6 +313,55 @@ def test_gather_copies_whole_lines_between_line_aligned_rows(mqg, dim, dtype):
             assert stats.tolist() == [h, m]
 
 
+@pytest.mark.parametrize("dim,dtype", [(602, torch.float32), (100, torch.float32), (128, torch.float16), (3, torch.float16)])
+def test_gather_ids_outside_the_graph_are_skipped_and_show_in_the_stats(mqg, dim, dtype):
+    """An id outside [0, num_nodes) is never used as an index: its output row keeps what it held,
+    it counts in neither stat, and nothing beyond the buffers is written - through the cache, without
+    a cache (features in HBM and in host memory), and through the entry point without a context."""
+    rp, ci = hub_graph(n=6000, edges=150_000, max_degree=900, seed=4)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, dim, dtype=dtype, seed=6).pin_memory()
+    ctx = mqg.Context(g, 256, [10])
+    count = 2500
+    rng = np.random.default_rng(8)
+    ids_np = rng.permutation(n)[:count].astype(np.int64)
+    bad_pos = rng.permutation(count)[:37]
+    bad_vals = np.array([n, n + 1, -1, -7, 2 ** 31 - 1, 2 ** 40, -2 ** 40, n + 10 ** 6], dtype=np.int64)
+    good = np.ones(count, dtype=bool)
+    good[bad_pos] = False
+    want_cache = oracle.build_cache(rp.numpy(), n // 3, feats.numpy())
+    ref, h, m = oracle.gather(ids_np[good], feats.numpy(), want_cache)
+    for idx_dtype in (torch.int64, torch.int32):
+        bv = bad_vals if idx_dtype == torch.int64 else bad_vals[np.abs(bad_vals) < 2 ** 31]
+        ids_bad = ids_np.copy()
+        ids_bad[bad_pos] = bv[np.arange(len(bad_pos)) % len(bv)]
+        ids = torch.from_numpy(ids_bad).to(idx_dtype).cuda()
+        num = torch.tensor([count], dtype=torch.int64, device="cuda")
+        cached = mqg.Cache(g, feats, n // 3)
+        mqg.mqg_build_cache(ctx, g, cached)
+        for what, cache in (("cache", cached), ("direct-host", mqg.Cache(g, feats, None)),
+                            ("direct-hbm", mqg.Cache(g, feats.cuda(), None))):
+            for static in (False, True):
+                buf = torch.full((count + 5, dim), 7.0, dtype=dtype, device="cuda")
+                stats = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+                if static:
+                    mqg.mqg_gather_features_static(cache, ids, num, buf[:count], stats)
+                else:
+                    mqg.mqg_gather_features(ctx, cache, ids, num, buf[:count], stats)
+                torch.cuda.synchronize()
+                got = buf.cpu().numpy()
+                assert got[:count][good].tobytes() == ref.tobytes(), (what, static)
+                assert np.all(got[:count][~good] == 7.0) and np.all(got[count:] == 7.0), (what, static)
+                assert stats.tolist() == ([h, m] if what == "cache" else [0, int(good.sum())]), (what, static)
+        # a clean call afterwards counts from zero again
+        stats = torch.zeros(2, dtype=torch.int64, device="cuda")
+        out = torch.zeros((count, dim), dtype=dtype, device="cuda")
+        mqg.mqg_gather_features(ctx, mqg.Cache(g, feats, None), torch.from_numpy(ids_np).to(idx_dtype).cuda(), num, out, stats)
+        torch.cuda.synchronize()
+        assert stats.tolist() == [0, count]
+
+
 def test_cache_ties_and_many_equal_degrees(mqg):
     # ring: every degree equal -> cache is the lowest ids; then a star on top
     n = 5000

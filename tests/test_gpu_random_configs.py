@@ -171,6 +171,10 @@ def test_directed_graph_all_paths(mqg, seed):
     assert np.array_equal(scores.cpu().numpy(), want_scores)
     wc = oracle.build_cache_by_score(want_scores, n // 10, feats.numpy())
     assert np.array_equal(cache.slot_of.cpu().numpy(), wc.slot_of)
+    mqg.mqg_build_cache_ex(ctx, g, cache, mqg.MQG_CACHE_RANDOM_WALK, train_ids=to_dev(train), step_fanouts=[6, 12],
+                           scores_out=scores, walk_form=mqg.MQG_WALK_PRINTED)
+    torch.cuda.synchronize()
+    assert np.array_equal(scores.cpu().numpy(), oracle.random_walk_scores(rp_np, ci_np, train.numpy(), [6, 12], oracle.WALK_PRINTED))
 
     # layer-wise sampler
     sizes = [200, 100]

@@ -600,12 +600,12 @@ def test_random_walk_push_on_a_symmetric_graph_is_the_neighbours_ratio_pulled():
         share = np.where(deg > 0, np.minimum(k, deg) / np.maximum(deg, 1), 0.0) * P
         nxt = P.copy()
         for u in range(n):
-            acc = 0.0
+            acc = P[u]
             for v in ci[rp[u]:rp[u + 1]]:
                 acc += share[v]
-            nxt[u] = P[u] + acc
+            nxt[u] = acc
         P = nxt
-    assert np.allclose(got, P, rtol=1e-15, atol=0)
+    assert np.array_equal(got, P)
 
 
 def test_random_walk_worked_by_hand():
@@ -819,6 +819,11 @@ def test_weighted_aggregate_against_dense_product_and_its_transpose():
 
 
 # ------------------------------------------------------------------------- draws with real weights
+
+def test_exp_tickets_stream_is_the_scalar_functions_composed():
+    got = oracle.exp_tickets(77, -3, 1000, 300)
+    assert [int(x) for x in got] == [oracle.exp_ticket(oracle.key(77, -3, 1000 + i, 0)) for i in range(300)]
+
 
 def test_exp_ticket_is_minus_log2_in_fixed_point():
     import math
