@@ -34,6 +34,17 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out_dir: str) -> str:
+    """The same source under AddressSanitizer and UndefinedBehaviorSanitizer, as a second library
+    (for the test that runs the pins against it; load it by setting MQG_ORACLE_LIB)."""
+    os.makedirs(out_dir, exist_ok=True)
+    path = os.path.join(out_dir, "liboracle_san.so")
+    subprocess.check_call(["gcc", "-O1", "-g", "-std=c99", "-fPIC", "-shared", "-fno-fast-math", "-ffp-contract=off",
+                           "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer",
+                           "-Wall", "-Wextra", "-o", path, _SRC, "-lm"])
+    return path
+
+
 _lib = None
 
 
@@ -41,7 +52,7 @@ def _load():
     global _lib
     if _lib is not None:
         return _lib
-    lib = ctypes.CDLL(build())
+    lib = ctypes.CDLL(os.environ.get("MQG_ORACLE_LIB") or build())
     i64, u64, i32, vp = ctypes.c_int64, ctypes.c_uint64, ctypes.c_int32, ctypes.c_void_p
     lib.orc_mix.restype = u64
     lib.orc_mix.argtypes = [u64]
