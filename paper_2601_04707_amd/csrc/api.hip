@@ -152,6 +152,7 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds, const i
     ok = ok && dev_alloc(&c->local_of, c->num_nodes) == hipSuccess;
     ok = ok && dev_alloc(&c->bitmap, c->bitmap_words) == hipSuccess;
     ok = ok && dev_alloc(&c->tile_vals, c->max_tiles) == hipSuccess;
+    ok = ok && dev_alloc(&c->bitmap_tile_vals, c->max_tiles) == hipSuccess;
     ok = ok && dev_alloc(&c->row_start, c->max_dst) == hipSuccess;
     ok = ok && dev_alloc(&c->row_deg, c->max_dst) == hipSuccess;
     ok = ok && dev_alloc(reinterpret_cast<int32_t **>(&c->nbr), c->max_nnz) == hipSuccess;
@@ -179,6 +180,7 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     (void)hipFree(c->local_of);
     (void)hipFree(c->bitmap);
     (void)hipFree(c->tile_vals);
+    (void)hipFree(c->bitmap_tile_vals);
     (void)hipFree(c->row_start);
     (void)hipFree(c->row_deg);
     (void)hipFree(c->nbr);

@@ -71,7 +71,8 @@ struct mqg_ctx {
     int32_t *local_of = nullptr;         // [num_nodes] position of a node in the current source list, -1 if absent
     uint32_t *bitmap = nullptr;          // [bitmap_words] nodes first seen in the current layer
     int64_t bitmap_words = 0;            // padded to a multiple of kBitmapTileWords
-    int32_t *tile_vals = nullptr;        // [max_tiles] per-tile sums, then their exclusive scan
+    int32_t *tile_vals = nullptr;        // [max_tiles] per-tile sums of the rows, then their exclusive scan
+    int32_t *bitmap_tile_vals = nullptr; // [max_tiles] the same for the tiles of the bitmap
     int64_t max_tiles = 0;
     int64_t *row_start = nullptr;        // [max_dst] first adjacency slot of each destination
     int32_t *row_deg = nullptr;          // [max_dst] degree of each destination

@@ -148,14 +148,14 @@ __device__ __forceinline__ int block_excl_scan(int v, int *total, int *lds) {
     return base + incl - v;
 }
 
-// Sum of tile_sums[0 .. blockIdx.x): what a tile's own workgroup adds up instead of a separate scan
-// launch when the tiles are few (kSelfPrefixTiles at most, i.e. at most 8 loads per thread).
+// Sum of tile_sums[0 .. tile): what a tile's own workgroup adds up instead of a separate scan
+// launch when the tiles are few (kSelfPrefixTiles at most, i.e. at most 32 loads per thread).
 // Every thread of the workgroup (256 threads) must call it; `lds` needs 4 ints.
-constexpr int kSelfPrefixTiles = 2048;
+constexpr int kSelfPrefixTiles = 8192;
 constexpr int kSelfPrefixBlock = 256, kSelfPrefixWaves = kSelfPrefixBlock / 64;
-__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sums, int *lds) {
+__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sums, int *lds, int tile) {
     int part = 0;
-    for (int t = threadIdx.x; t < static_cast<int>(blockIdx.x); t += kSelfPrefixBlock) part += tile_sums[t];
+    for (int t = threadIdx.x; t < tile; t += kSelfPrefixBlock) part += tile_sums[t];
     part = wave_sum(part);
     __syncthreads();                                       // lds may still be read from an earlier use
     if (lane_id() == 0) lds[threadIdx.x >> 6] = part;
@@ -164,6 +164,9 @@ __device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sum
 #pragma unroll
     for (int k = 0; k < kSelfPrefixWaves; ++k) sum += lds[k];
     return sum;
+}
+__device__ __forceinline__ int tiles_before(const int32_t *__restrict__ tile_sums, int *lds) {
+    return tiles_before(tile_sums, lds, static_cast<int>(blockIdx.x));
 }
 
 // SplitMix64 finaliser (Steele, Lea, Flood 2014): the mixing function of the sampling keys.

@@ -1,20 +1,25 @@
 // L-hop fixed-fanout neighbour sampling into bipartite blocks (paper Sec. III-A, GraphSAGE
 // paragraph; block layout after Sec. IV "Mini-Batch Transfer To GPU" and Eq. 16).
 //
-// Per block, outward from the seeds:
-//   k_row_info     adjacency start/degree of every destination, copy of the destinations into the
-//                  block's source list, per-tile sums of min(fanout, degree)
-//   k_row_offsets  indptr (every workgroup adds up the tile sums before its own; only above 2,048
-//                  tiles does one k_scan_tiles launch scan them first), total = nnz
+// Per block, outward from the seeds (five launches; the first block's row information is a launch
+// of its own, every other block's rides with the block before it):
+//   row info       adjacency start/degree of every destination, copy of the destinations into the
+//                  block's source list, per-tile sums of min(fanout, degree), list of the hubs
 //   k_sample       one wavefront per destination: smallest-k random keys, neighbours written in
-//                  ascending adjacency slot, first-seen nodes marked in an N-bit bitmap
-//                  (destinations whose degree exceeds heavy_degree, listed by k_row_info, are
-//                  taken by whole workgroups in the same launch, so that a hub's key evaluation
-//                  is spread over four wavefronts instead of stretching the kernel's tail)
-//   k_bitmap_count / k_bitmap_emit (tile sums handled as in k_row_offsets)
-//                  popcount-rank the bitmap: new source nodes come out ascending by id, get their
+//                  ascending adjacency slot at row * fanout (no offsets needed yet), first-seen
+//                  nodes marked in an N-bit bitmap (destinations whose degree exceeds heavy_degree
+//                  are taken by whole workgroups in the same launch, so that a hub's key
+//                  evaluation is spread over four wavefronts instead of stretching the kernel's tail)
+//   k_offsets_count  two independent jobs in one launch: indptr from the row tile sums (every
+//                  workgroup adds up the sums of the tiles before its own; only above 8,192 tiles
+//                  does one k_scan_tiles launch scan them first) and the popcount of every tile
+//                  of the bitmap
+//   k_bitmap_emit  popcount-rank the bitmap: new source nodes come out ascending by id, get their
 //                  position recorded in local_of[], the bitmap is cleared on the way
-//   k_relabel      indices[e] = local_of[neighbour e]
+//   k_relabel_rowinfo  indices[indptr[row] + j] = local_of[neighbour j of row], and in the same
+//                  launch the row information of the next block outward (whose destinations are
+//                  this block's sources); the outermost block ends with a plain k_relabel
+// The hash-table dedup (an option) keeps the older order: offsets first, neighbours written compactly.
 // All sizes that depend on the data stay on the device; grids are sized by worst-case bounds.
 #include "common.h"
 #include "device_utils.h"
@@ -37,47 +42,62 @@ uint64_t host_mix64(uint64_t z) {
 
 // ------------------------------------------------------------------------------------------
 
+// Arguments of the row-information step of one block.
 template <typename PtrT, typename IdxT>
-__global__ void __launch_bounds__(kBlock)
-k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const int64_t *sizes,
-           IdxT *__restrict__ src_out, int fanout, int64_t *__restrict__ row_start,
-           int32_t *__restrict__ row_deg, int32_t *__restrict__ tile_sums, int64_t *sizes_rw,
-           int heavy_degree, int32_t *__restrict__ heavy_rows, int32_t *__restrict__ heavy_count,
-           int64_t n_seeds, int32_t *__restrict__ local_of, int64_t num_nodes, int32_t *__restrict__ seed_flags) {
-    __shared__ int lds[kWavesPerBlock];
+struct RowInfoArgs {
+    const PtrT *row_ptr;
+    const IdxT *dst;             // the block's destinations (the caller's seeds, or the previous block's sources)
+    const int64_t *sizes;        // this block's sizes: [0] = number of destinations (unless n_seeds >= 0)
+    IdxT *src_out;
+    int fanout;
+    int64_t *row_start;
+    int32_t *row_deg;
+    int32_t *tile_sums;
+    int64_t *sizes_rw;
+    int heavy_degree;
+    int32_t *heavy_rows;
+    int32_t *heavy_count;
+    int64_t n_seeds;             // >= 0: innermost block
+    int32_t *local_of;
+    int64_t num_nodes;
+    int32_t *seed_flags;
+};
+
+template <typename PtrT, typename IdxT>
+__device__ __forceinline__ void row_info_tile(const RowInfoArgs<PtrT, IdxT> &a, int tile, int *lds) {
     // innermost block (n_seeds >= 0): the destinations are the caller's seeds; their number comes
     // from the host and their positions are entered into local_of here
-    const int64_t n = n_seeds >= 0 ? n_seeds : sizes[0];
-    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    const int64_t n = a.n_seeds >= 0 ? a.n_seeds : a.sizes[0];
+    const int64_t i = int64_t(tile) * kBlock + threadIdx.x;
     int cnt = 0;
     bool heavy = false;
     if (i < n) {
-        IdxT v = dst[i];
-        if (n_seeds >= 0) {
+        IdxT v = a.dst[i];
+        if (a.n_seeds >= 0) {
             // caller-supplied ids: an id outside the graph is flagged and replaced by node 0, so that
             // nothing downstream ever indexes with it; a repeated id is flagged (its rows are kept and
             // share one position in the source lists)
-            if (v < 0 || static_cast<int64_t>(v) >= num_nodes) {
+            if (v < 0 || static_cast<int64_t>(v) >= a.num_nodes) {
                 v = 0;
-                atomicOr(seed_flags, 1);
+                atomicOr(a.seed_flags, 1);
             }
-            if (local_of && atomicCAS(&local_of[v], -1, static_cast<int32_t>(i)) != -1) atomicOr(seed_flags, 2);
+            if (a.local_of && atomicCAS(&a.local_of[v], -1, static_cast<int32_t>(i)) != -1) atomicOr(a.seed_flags, 2);
         }
-        int64_t s = static_cast<int64_t>(row_ptr[v]);
-        int64_t d = static_cast<int64_t>(row_ptr[v + 1]) - s;
-        row_start[i] = s;
-        row_deg[i] = static_cast<int32_t>(d);
-        src_out[i] = v;
-        cnt = d < fanout ? static_cast<int>(d) : fanout;
-        heavy = d > heavy_degree;
+        int64_t s = static_cast<int64_t>(a.row_ptr[v]);
+        int64_t d = static_cast<int64_t>(a.row_ptr[v + 1]) - s;
+        a.row_start[i] = s;
+        a.row_deg[i] = static_cast<int32_t>(d);
+        a.src_out[i] = v;
+        cnt = d < a.fanout ? static_cast<int>(d) : a.fanout;
+        heavy = d > a.heavy_degree;
     }
     {   // list the hubs: one atomic per wavefront that has any
         uint64_t m = ballot64(heavy);
         if (m) {
             int base = 0;
-            if (lane_id() == 0) base = atomicAdd(heavy_count, popc64(m));
+            if (lane_id() == 0) base = atomicAdd(a.heavy_count, popc64(m));
             base = __shfl(base, 0, 64);
-            if (heavy) heavy_rows[base + popc64(m & lanes_below(lane_id()))] = static_cast<int32_t>(i);
+            if (heavy) a.heavy_rows[base + popc64(m & lanes_below(lane_id()))] = static_cast<int32_t>(i);
         }
     }
     int w = wave_sum(cnt);
@@ -87,9 +107,16 @@ k_row_info(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ dst, const
         int t = 0;
 #pragma unroll
         for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
-        tile_sums[blockIdx.x] = t;
-        if (blockIdx.x == 0 && n_seeds >= 0) sizes_rw[0] = n_seeds;
+        a.tile_sums[tile] = t;
+        if (tile == 0 && a.n_seeds >= 0) a.sizes_rw[0] = a.n_seeds;
     }
+}
+
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_row_info(RowInfoArgs<PtrT, IdxT> a) {
+    __shared__ int lds[kWavesPerBlock];
+    row_info_tile(a, static_cast<int>(blockIdx.x), lds);
 }
 
 // One workgroup of 1024 threads: vals[0..n) -> exclusive scan in place; totals stored.
@@ -116,16 +143,15 @@ k_scan_tiles(int32_t *__restrict__ vals, int64_t n, const int64_t *__restrict__ 
 // scanned: tile_vals holds the exclusive scan of the tile sums (k_scan_tiles ran, and stored nnz);
 // otherwise it holds the sums themselves, every workgroup adds up its own base and the last one
 // stores nnz.
-__global__ void __launch_bounds__(kBlock)
-k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
-              const int32_t *__restrict__ tile_vals, int scanned, int32_t *__restrict__ indptr,
-              const int32_t *__restrict__ seed_flags) {
-    __shared__ int lds[kWavesPerBlock];
+__device__ __forceinline__ void row_offsets_tile(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
+                                                 const int32_t *__restrict__ tile_vals, int scanned,
+                                                 int32_t *__restrict__ indptr, const int32_t *__restrict__ seed_flags,
+                                                 int tile, int ntiles, int *lds) {
     const int64_t n = sizes[0];
     // the block's flags word: what the seed check found (innermost block), 0 otherwise
-    if (blockIdx.x == 0 && threadIdx.x == 0) sizes[3] = seed_flags ? *seed_flags : 0;
-    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
-    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    if (tile == 0 && threadIdx.x == 0) sizes[3] = seed_flags ? *seed_flags : 0;
+    const int tile_base = scanned ? tile_vals[tile] : tiles_before(tile_vals, lds, tile);
+    const int64_t i = int64_t(tile) * kBlock + threadIdx.x;
     int cnt = 0;
     if (i < n) {
         int d = row_deg[i];
@@ -139,7 +165,16 @@ k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
         if (i == n - 1) indptr[n] = off + cnt;
     }
     if (n == 0 && i == 0) indptr[0] = 0;
-    if (!scanned && blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) sizes[2] = tile_base + total;
+    if (!scanned && tile == ntiles - 1 && threadIdx.x == 0) sizes[2] = tile_base + total;
+}
+
+__global__ void __launch_bounds__(kBlock)
+k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
+              const int32_t *__restrict__ tile_vals, int scanned, int32_t *__restrict__ indptr,
+              const int32_t *__restrict__ seed_flags) {
+    __shared__ int lds[kWavesPerBlock];
+    row_offsets_tile(row_deg, fanout, sizes, tile_vals, scanned, indptr, seed_flags, static_cast<int>(blockIdx.x),
+                     static_cast<int>(gridDim.x), lds);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -148,7 +183,7 @@ k_row_offsets(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes,
 struct SampleArgs {
     const int64_t *row_start;
     const int32_t *row_deg;
-    const int32_t *indptr;
+    const int32_t *indptr;    // null: row r's neighbours go to nbr[r * fanout ...) and are compacted by the relabel
     const int64_t *sizes;
     int32_t *nbr;
     const int32_t *local_of;
@@ -160,6 +195,10 @@ struct SampleArgs {
     int force_slow;
     int heavy_degree;         // rows longer than this are sampled by whole workgroups
 };
+
+__device__ __forceinline__ int32_t out_base_of(const SampleArgs &a, int64_t row) {
+    return a.indptr ? a.indptr[row] : static_cast<int32_t>(row * a.fanout);
+}
 
 __device__ __forceinline__ uint64_t layer_hash_of(const SampleArgs &a) {
     if (!a.seed_dev) return a.layer_hash;
@@ -376,7 +415,7 @@ __device__ void sample_hubs(const IdxT *__restrict__ col_idx, const IdxT *__rest
         const int row = heavy_rows[h];
         const int64_t start = a.row_start[row];
         const int d = a.row_deg[row];
-        const int32_t out_base = a.indptr[row];
+        const int32_t out_base = out_base_of(a, row);
         const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(dst_ids[row]));
         const RowKeys key_of(hv);
         if (tid == 0) *cnt_s = 0;
@@ -440,7 +479,7 @@ k_sample(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids, Sam
     const int64_t start = a.row_start[row];
     const int d = a.row_deg[row];
     const int k = a.fanout;
-    const int32_t out_base = a.indptr[row];
+    const int32_t out_base = out_base_of(a, row);
 
     if (d <= k) {                                          // the whole row, no randomness
         if (lane < d) emit_neighbour(col_idx, start, lane, out_base + lane, a);
@@ -596,7 +635,7 @@ __device__ void sample_hubs_prio(const IdxT *__restrict__ col_idx, const IdxT *_
         const int row = heavy_rows[h];
         const int64_t start = a.row_start[row];
         const int d = a.row_deg[row];
-        const int32_t out_base = a.indptr[row];
+        const int32_t out_base = out_base_of(a, row);
         const IdxT node = dst_ids[row];
         const uint64_t hv = mix64(layer_hash_of(a) ^ uint64_t(node));
         const RowKeys key_of(hv);
@@ -671,7 +710,7 @@ k_sample_prio(const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst_ids
     const int64_t start = a.row_start[row];
     const int d = a.row_deg[row];
     const int k = a.fanout;
-    const int32_t out_base = a.indptr[row];
+    const int32_t out_base = out_base_of(a, row);
     if (d <= k) {
         if (lane < d) emit_neighbour(col_idx, start, lane, out_base + lane, a);
         return;
@@ -789,10 +828,9 @@ k_prio_bitmap(const int32_t *__restrict__ slot_of, int64_t n, uint32_t *__restri
 // four words per thread (one 16-byte load), ids written straight from the bit loop - their bitmaps
 // are sparse, a thread rarely has more than a bit or two.
 template <int WPT>
-__global__ void __launch_bounds__(kBlock)
-k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_sums) {
-    __shared__ int lds[kWavesPerBlock];
-    const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * WPT;
+__device__ __forceinline__ void bitmap_count_tile(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_sums, int tile,
+                                                  int *lds) {
+    const int64_t w0 = (int64_t(tile) * kBlock + threadIdx.x) * WPT;
     int c;
     if (WPT == 4) {
         uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
@@ -807,8 +845,21 @@ k_bitmap_count(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_s
         int t = 0;
 #pragma unroll
         for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
-        tile_sums[blockIdx.x] = t;
+        tile_sums[tile] = t;
     }
+}
+
+// The first row_tiles workgroups turn the row tile sums into indptr, the others count the bits of
+// one bitmap tile each: both only need what the launches before produced.
+template <int WPT>
+__global__ void __launch_bounds__(kBlock)
+k_offsets_count(const int32_t *__restrict__ row_deg, int fanout, int64_t *sizes, const int32_t *__restrict__ row_tile_vals,
+                int rows_scanned, int32_t *__restrict__ indptr, const int32_t *__restrict__ seed_flags, int row_tiles,
+                const uint32_t *__restrict__ bitmap, int32_t *__restrict__ bitmap_tile_sums) {
+    __shared__ int lds[kWavesPerBlock];
+    const int b = static_cast<int>(blockIdx.x);
+    if (b < row_tiles) row_offsets_tile(row_deg, fanout, sizes, row_tile_vals, rows_scanned, indptr, seed_flags, b, row_tiles, lds);
+    else bitmap_count_tile<WPT>(bitmap, bitmap_tile_sums, b - row_tiles, lds);
 }
 
 // num_src of a block is also num_dst of the next block outward
@@ -883,13 +934,39 @@ k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_v
     }
 }
 
+// Neighbour j of row r sits at nbr[r * fanout + j]; its edge position is indptr[r] + j.  Workgroups
+// vb of nb walk the num_dst * fanout slots.
+__device__ __forceinline__ void relabel_slots(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes,
+                                              const int32_t *__restrict__ indptr, int fanout,
+                                              const int32_t *__restrict__ local_of, int32_t *__restrict__ indices, int vb, int nb) {
+    const uint32_t total = static_cast<uint32_t>(sizes[0] * fanout);
+    const uint32_t stride = static_cast<uint32_t>(nb) * kBlock;
+    for (uint64_t t64 = uint64_t(vb) * kBlock + threadIdx.x; t64 < total; t64 += stride) {
+        const uint32_t t = static_cast<uint32_t>(t64);
+        const uint32_t row = t / static_cast<uint32_t>(fanout);
+        const int j = static_cast<int>(t - row * static_cast<uint32_t>(fanout));
+        const int b = indptr[row];
+        if (j < indptr[row + 1] - b) indices[b + j] = local_of[nbr[t]];
+    }
+}
+
 __global__ void __launch_bounds__(kBlock)
-k_relabel(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes,
+k_relabel(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes, const int32_t *__restrict__ indptr, int fanout,
           const int32_t *__restrict__ local_of, int32_t *__restrict__ indices) {
-    const int64_t nnz = sizes[2];
-    const int64_t stride = int64_t(gridDim.x) * kBlock;
-    for (int64_t e = int64_t(blockIdx.x) * kBlock + threadIdx.x; e < nnz; e += stride)
-        indices[e] = local_of[nbr[e]];
+    relabel_slots(nbr, sizes, indptr, fanout, local_of, indices, static_cast<int>(blockIdx.x), static_cast<int>(gridDim.x));
+}
+
+// The relabel of one block and, in the same launch, the row information of the next block outward
+// (its destinations are this block's sources, complete since k_bitmap_emit).
+template <typename PtrT, typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_relabel_rowinfo(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes, const int32_t *__restrict__ indptr,
+                  int fanout, const int32_t *__restrict__ local_of, int32_t *__restrict__ indices, int relabel_blocks,
+                  RowInfoArgs<PtrT, IdxT> next) {
+    __shared__ int lds[kWavesPerBlock];
+    const int b = static_cast<int>(blockIdx.x);
+    if (b < relabel_blocks) relabel_slots(nbr, sizes, indptr, fanout, local_of, indices, b, relabel_blocks);
+    else row_info_tile(next, b - relabel_blocks, lds);
 }
 
 template <typename IdxT>
@@ -919,38 +996,57 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     int64_t need_dst = num_seeds;
     const int bitmap_wpt = ctx->bitmap_words <= (int64_t(1) << 20) ? 1 : 4;     // words per thread, see k_bitmap_emit*
     const int bitmap_tiles = static_cast<int>(std::max<int64_t>(1, ctx->bitmap_words / (int64_t(kBlock) * bitmap_wpt)));
+    const int heavy_degree = ctx->force_slow_select ? 0x7FFFFFFF : ctx->heavy_degree;
+    auto row_info_args = [&](int l, int64_t dst_count) {
+        RowInfoArgs<PtrT, IdxT> r;
+        r.row_ptr = row_ptr;
+        r.dst = (l == L - 1) ? seeds : static_cast<const IdxT *>(blocks[l + 1].src_ids);
+        r.sizes = blocks[l].sizes;
+        r.src_out = static_cast<IdxT *>(blocks[l].src_ids);
+        r.fanout = fanouts[l];
+        r.row_start = ctx->row_start;
+        r.row_deg = ctx->row_deg;
+        r.tile_sums = ctx->tile_vals;
+        r.sizes_rw = blocks[l].sizes;
+        r.heavy_degree = heavy_degree;
+        r.heavy_rows = ctx->heavy_rows;
+        r.heavy_count = ctx->heavy_count + l;
+        r.n_seeds = l == L - 1 ? dst_count : int64_t(-1);
+        r.local_of = local_of;
+        r.num_nodes = g->num_nodes;
+        r.seed_flags = ctx->heavy_count + MQG_MAX_LAYERS;
+        return r;
+    };
+    auto tiles_of = [](int64_t rows) { return static_cast<int>(std::max<int64_t>(1, ceil_div(rows, kBlock))); };
+    // the innermost block's row information; every other block's is launched with the relabel before it
+    MQG_LAUNCH(ctx, "k_row_info", s, (k_row_info<PtrT, IdxT><<<tiles_of(need_dst), kBlock, 0, s>>>(row_info_args(L - 1, need_dst))));
     for (int l = L - 1; l >= 0; --l) {
         mqg_block &b = blocks[l];
         const int k = fanouts[l];
-        const IdxT *dst = (l == L - 1) ? seeds : static_cast<const IdxT *>(blocks[l + 1].src_ids);
         IdxT *src_ids = static_cast<IdxT *>(b.src_ids);
         const int64_t need_nnz = need_dst * k;
-        const int row_tiles = static_cast<int>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)));
+        const int row_tiles = tiles_of(need_dst);
+        const int64_t next_dst = std::max(need_dst, std::min<int64_t>(g->num_nodes, need_dst + need_nnz));
 
-        const int heavy_degree = ctx->force_slow_select ? 0x7FFFFFFF : ctx->heavy_degree;
-        MQG_LAUNCH(ctx, "k_row_info", s,
-                   (k_row_info<PtrT, IdxT><<<row_tiles, kBlock, 0, s>>>(row_ptr, dst, b.sizes, src_ids, k, ctx->row_start,
-                                                                          ctx->row_deg, ctx->tile_vals, b.sizes, heavy_degree,
-                                                                          ctx->heavy_rows, ctx->heavy_count + l,
-                                                                          l == L - 1 ? int64_t(num_seeds) : int64_t(-1), local_of,
-                                                                          g->num_nodes, ctx->heavy_count + MQG_MAX_LAYERS)));
         // few tiles: every workgroup of the consumer adds up the tile sums before its own; many: one scan launch
         const int rows_scanned = row_tiles > kSelfPrefixTiles ? 1 : 0;
         int rc = MQG_OK;
         if (rows_scanned) rc = launch_scan_tiles(ctx, ctx->tile_vals, row_tiles, nullptr, &b.sizes[2], nullptr, s, "k_scan_tiles(rows)");
         if (rc != MQG_OK) return rc;
-        if (use_hash && l == L - 1) {                      // the seeds enter the table (and repeated ones are flagged) first
-            rc = hash_put_seeds(ctx, b.src_ids, g->idx_type, need_dst, b.sizes, s);   // ids as k_row_info checked them
-            if (rc != MQG_OK) return rc;
+        const int32_t *seed_flags = l == L - 1 ? ctx->heavy_count + MQG_MAX_LAYERS : nullptr;
+        if (use_hash) {
+            if (l == L - 1) {                              // the seeds enter the table (and repeated ones are flagged) first
+                rc = hash_put_seeds(ctx, b.src_ids, g->idx_type, need_dst, b.sizes, s);   // ids as the row info checked them
+                if (rc != MQG_OK) return rc;
+            }
+            MQG_LAUNCH(ctx, "k_row_offsets", s,
+                       (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr, seed_flags)));
         }
-        MQG_LAUNCH(ctx, "k_row_offsets", s,
-                   (k_row_offsets<<<row_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
-                                                               l == L - 1 ? ctx->heavy_count + MQG_MAX_LAYERS : nullptr)));
 
         SampleArgs a;
         a.row_start = ctx->row_start;
         a.row_deg = ctx->row_deg;
-        a.indptr = b.indptr;
+        a.indptr = use_hash ? b.indptr : nullptr;
         a.sizes = b.sizes;
         a.nbr = nbr;
         a.local_of = local_of;
@@ -976,30 +1072,41 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
             rc = hash_dedup_block(ctx, nbr, need_nnz, g->num_nodes, g->idx_type, b.src_ids, b.sizes,
                                   l > 0 ? blocks[l - 1].sizes : nullptr, b.indices, s);
             if (rc != MQG_OK) return rc;
-            need_dst = std::max(need_dst, std::min<int64_t>(g->num_nodes, need_dst + need_nnz));
+            need_dst = next_dst;
+            if (l > 0) MQG_LAUNCH(ctx, "k_row_info", s, (k_row_info<PtrT, IdxT><<<tiles_of(need_dst), kBlock, 0, s>>>(row_info_args(l - 1, need_dst))));
             continue;
         }
-        // num_src = num_dst + number of new nodes; it is also the next block's num_dst
+        // indptr from the row tile sums, and the bitmap's tile popcounts
         if (bitmap_wpt == 1) {
-            MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<1><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
+            MQG_LAUNCH(ctx, "k_offsets_count", s,
+                       (k_offsets_count<1><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
+                                                                                      seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
         } else {
-            MQG_LAUNCH(ctx, "k_bitmap_count", s, (k_bitmap_count<4><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals)));
+            MQG_LAUNCH(ctx, "k_offsets_count", s,
+                       (k_offsets_count<4><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
+                                                                                      seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
         }
+        // num_src = num_dst + number of new nodes; it is also the next block's num_dst
         int64_t *next_num_dst = l > 0 ? &blocks[l - 1].sizes[0] : nullptr;
         const int bits_scanned = bitmap_tiles > kSelfPrefixTiles ? 1 : 0;
-        if (bits_scanned) rc = launch_scan_tiles(ctx, ctx->tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1], next_num_dst, s, "k_scan_tiles(bitmap)");
+        if (bits_scanned) rc = launch_scan_tiles(ctx, ctx->bitmap_tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1], next_num_dst, s, "k_scan_tiles(bitmap)");
         if (rc != MQG_OK) return rc;
         if (bitmap_wpt == 1) {
             MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
         } else {
             MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
         }
-        int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
-        MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, ctx->local_of, b.indices)));
-
-        need_dst = std::max(need_dst, std::min<int64_t>(g->num_nodes, need_dst + need_nnz));
+        const int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
+        need_dst = next_dst;
+        if (l > 0) {
+            MQG_LAUNCH(ctx, "k_relabel_rowinfo", s,
+                       (k_relabel_rowinfo<PtrT, IdxT><<<relabel_grid + tiles_of(need_dst), kBlock, 0, s>>>(nbr, b.sizes, b.indptr, k, ctx->local_of, b.indices,
+                                                                                                          relabel_grid, row_info_args(l - 1, need_dst))));
+        } else {
+            MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, b.indptr, k, ctx->local_of, b.indices)));
+        }
     }
     {
         int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_dst, kBlock)), 4096));
