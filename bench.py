@@ -7,7 +7,8 @@ pinned host memory), and the chain of mean aggregations.  The headline
 workload is "xlarge", the largest of the five (111 M nodes, 1.6 B directed
 edges resident in HBM, 128-dim fp16 features in pinned host memory with the
 top 10 % of nodes by degree cached in HBM, fanouts [15, 10, 5], 1,024 seeds
-from a 1 % training split, three mini-batches in flight).  Inputs are resident
+from a 1 % training split, three mini-batches in flight with one stream per
+stage: sampling and cached rows, rows over the host link, aggregation).  Inputs are resident
 (graph and cache in HBM, features in pinned host memory) before the timed
 region starts.
 
@@ -65,6 +66,45 @@ def pmc_traffic(workload: str, kernel: str):
     return None, None
 
 
+_streams = []
+
+
+def concurrent_streams(torch, n):
+    """n streams that run side by side.  The runtime maps every stream to one of a few hardware
+    queues (four here), and two streams on one queue run their kernels one after the other - which
+    of the streams one creates share a queue is not stated anywhere, so it is measured: a stream is
+    kept if a short spin kernel on it overlaps with one on every stream kept so far.  With more
+    streams asked for than there are queues the remaining ones are filled in as they come."""
+    if len(_streams) >= n:
+        return _streams[:n]
+    cyc = 200000
+
+    def pair_us(a, b):
+        best = 1e30
+        for _ in range(3):
+            torch.cuda.synchronize()
+            t = time.perf_counter()
+            for st in (a, b):
+                with torch.cuda.stream(st):
+                    torch.cuda._sleep(cyc)
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t) * 1e6)
+        return best
+
+    cand = [torch.cuda.Stream() for _ in range(12)]
+    one = pair_us(cand[0], cand[0]) / 2.0                      # two spins on one stream: serialised by definition
+    picked, rest = list(_streams), []
+    for st in cand:
+        if len(picked) < n and all(pair_us(st, c) < 1.5 * one for c in picked):
+            picked.append(st)
+        else:
+            rest.append(st)
+    log(f"streams: {len(picked)} on distinct hardware queues (one spin kernel {one:.0f} us)")
+    picked += rest[: max(0, n - len(picked))]
+    _streams[:] = picked
+    return _streams[:n]
+
+
 def build_inputs(torch, synth, w, dev):
     """Graph and pinned features of a workload; reused by workloads of the same shape."""
     gkey = ("graph", w.num_nodes, w.target_edges, w.gamma, w.max_degree, w.ptr_dtype, w.idx_dtype)
@@ -91,8 +131,11 @@ class Pipeline:
         self.depth = depth
         self.ctxs = [mqg.Context(g, w.batch, w.fanouts) for _ in range(depth)]
         self.blks = [mqg.Blocks(g, w.batch, w.fanouts) for _ in range(depth)]
-        self.streams = ([torch.cuda.Stream() for _ in range(depth)] if (depth > 1 or opts.graph)
-                        else [torch.cuda.current_stream()])
+        self.streams = concurrent_streams(torch, depth)
+        # --pipeline stages: one stream per stage (sample, gather, aggregate) instead of one per mini-batch
+        self.stage_streams = concurrent_streams(torch, 3)
+        self.events = [[torch.cuda.Event() for _ in range(depth)] for _ in range(3)]
+        self.used = [False] * depth
         bounds = self.blks[0].bounds
         self.x0 = [torch.zeros((bounds[0][1], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for _ in range(depth)]
         self.hs = [[torch.zeros((bounds[l][0], pad_dim), dtype=w.feat_dtype, device=dev)[:, :w.dim] for l in range(L)]
@@ -191,9 +234,56 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                 stats_log[i].copy_(p.stats[j], non_blocking=True)
         return step
 
-    step = make_step(pipe)
+    def make_stage_step(p):
+        """The same work with one stream per stage: sampling, the id lookup and the cached rows of
+        consecutive mini-batches follow one another on the first stream, the rows that cross the host link
+        on the second (exactly one miss gather uses the link at a time, back to back), the aggregations on
+        the third; events order the stages of a mini-batch and keep a slot's buffers from being reused
+        before its aggregation is done."""
+        s_s, s_g, s_a = p.stage_streams
+        ev_s, ev_g, ev_a = p.events
+
+        def step(i: int):
+            j = i % p.depth
+            with torch.cuda.stream(s_s):
+                if p.used[j]:
+                    s_s.wait_event(ev_a[j])
+                mqg.mqg_sample_blocks(p.ctxs[j], g, seeds_dev[i], w.fanouts, base_seed + i, p.blks[j], stream=s_s)
+                mqg.mqg_gather_features_cached(p.ctxs[j], cache, p.blks[j].src_ids[0], p.blks[j].sizes[0, 1:2], p.x0[j], p.stats[j], stream=s_s)
+                ev_s[j].record(s_s)
+            with torch.cuda.stream(s_g):                       # nothing but the rows that cross the host link
+                s_g.wait_event(ev_s[j])
+                mqg.mqg_gather_features_missed(p.ctxs[j], cache, p.blks[j].src_ids[0], p.blks[j].sizes[0, 1:2], p.x0[j], p.stats[j], stream=s_g)
+                ev_g[j].record(s_g)
+            with torch.cuda.stream(s_a):
+                s_a.wait_event(ev_g[j])
+                x = p.x0[j]
+                for l in range(L):
+                    mqg.mqg_sage_mean_aggregate(p.ctxs[j], p.blks[j], l, x, p.hs[j][l], stream=s_a)
+                    x = p.hs[j][l]
+                sizes_log[i].copy_(p.blks[j].sizes, non_blocking=True)
+                stats_log[i].copy_(p.stats[j], non_blocking=True)
+                ev_a[j].record(s_a)
+            p.used[j] = True
+        return step
+
+    use_graph = opts.graph == "on"
+    if opts.graph == "auto":
+        # a step that takes less than 0.2 ms is bound by its ~20 launches: replay it from a recorded graph
+        eager = make_step(pipe)
+        ncal = max(1, min(W, 10))
+        for rep in range(2):
+            torch.cuda.synchronize()
+            t_cal = time.perf_counter()
+            for i in range(ncal):
+                eager(i)
+            torch.cuda.synchronize()
+            cal_ms = (time.perf_counter() - t_cal) / ncal * 1e3
+        use_graph = cal_ms < 0.2
+    stages = (opts.pipeline or ("batches" if w.name.startswith("stress") else "stages")) == "stages" and not use_graph
+    step = make_stage_step(pipe) if stages else make_step(pipe)
     timed_step = step
-    if opts.graph:
+    if use_graph:
         # one recorded step per in-flight slot; what changes between replays lives in device buffers
         seed_buf = [torch.zeros(w.batch, dtype=g.idx_dtype, device=dev) for _ in range(nfl)]
         rng_buf = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(nfl)]
@@ -324,6 +414,7 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
 
     res = {
         "workload": w.name, "cache_pct": cache_pct, "in_flight": nfl,
+        "pipeline": "stages" if stages else "batches", "launch": "graph replay" if use_graph else "eager",
         "value": round(edges_per_s, 1), "unit": "sampled edges/s", "ms_per_step": round(ms_per_step, 4),
         "steps": K, "warmup": W,
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
@@ -395,12 +486,12 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                                            torch.cuda.max_memory_allocated(), 10, per_batch_bytes)
         queue_rule.update(queue_size=q_rule, memory_cap=q_cap, bytes_per_queued_batch=per_batch_bytes)
         depth = int(min(q_rule, MAX_RULE_DEPTH))
-        if not opts.graph and depth != nfl:
+        if not use_graph and depth != nfl:
             p2 = Pipeline(torch, mqg, g, w, depth, pad_dim, opts, dev)
             if opts.prioritise_cache:
                 for c in p2.ctxs:
                     c.set_sampling_priority(cache)
-            el2 = timed_region(make_step(p2))
+            el2 = timed_region(make_stage_step(p2) if stages else make_step(p2))
             queue_rule.update(depth_run=depth, ms_per_step_at_rule_depth=round(el2 / K * 1e3, 4),
                               ms_per_step_at_config_depth=round(ms_per_step, 4), config_depth=nfl)
             del p2
@@ -558,9 +649,10 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                                f"{w.dim}-dim {'fp32' if elt == 4 else 'fp16'} features, fanouts {w.fanouts}, "
                                f"{w.batch} seeds/batch, HBM cache {cache_pct if cache_pct is not None else 'all'} % of nodes ({opts.cache_policy}), "
                                f"rest in pinned host memory ({feats.stride(0) * elt}-byte rows)",
-                   "in_flight": nfl, "global_batch": w.batch, "dedup": opts.dedup,
+                   "in_flight": nfl, "pipeline": "one stream per stage (sample, gather, aggregate)" if stages else "one stream per mini-batch",
+                   "global_batch": w.batch, "dedup": opts.dedup,
                    "sampling": "cached neighbours first" if opts.prioritise_cache else "uniform",
-                   "launch": "one recorded HIP graph per in-flight slot" if opts.graph else "eager"},
+                   "launch": "one recorded HIP graph per in-flight slot" if use_graph else "eager"},
         "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
         "backward_aggregation": {"us_per_step": round(bwd_us, 1), "launches_per_step": round(bwd_launches, 1),
                                  "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
@@ -605,15 +697,19 @@ def main() -> int:
     ap.add_argument("--in-flight", default=None,
                     help="mini-batches in flight (contexts x streams); default: the workload's own (stress: 4, others: 3); "
                          "'auto': the depth the paper's queue rule (Eq. 22-23) gives after a calibration pass at the default depth")
+    ap.add_argument("--pipeline", choices=["batches", "stages"], default=None,
+                    help="how the mini-batches in flight share the GPU: one stream per mini-batch ('stress', as that "
+                         "workload is stated) or one stream per stage (the others)")
     ap.add_argument("--miss-inflight-kb", type=int, default=None, help="KiB of host reads the miss gather keeps outstanding")
     ap.add_argument("--dedup", choices=["bitmap", "hash"], default="bitmap",
                     help="frontier dedup: node-indexed bitmap and position table (default) or hash table and sort")
     ap.add_argument("--prioritise-cache", action="store_true",
                     help="cache-prioritised neighbour sampling: a row's cached neighbours are drawn first "
                          "(another sampling distribution than the workloads define; for comparison)")
-    ap.add_argument("--graph", action="store_true",
+    ap.add_argument("--graph", choices=["auto", "on", "off"], default="auto",
                     help="record each in-flight slot's step (sample, gather, aggregate) into a HIP graph once and "
-                         "replay it in the timed region (seeds and sampling seed are rewritten in device buffers)")
+                         "replay it in the timed region (seeds and sampling seed are rewritten in device buffers); "
+                         "auto: when a calibration pass shows a step under 0.2 ms, i.e. launch-bound")
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--device-row-multiple", type=int, default=None,
                     help="bytes the rows kept in HBM are padded to a multiple of (default: synth.aligned_row_stride)")
@@ -661,7 +757,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": head["dtype"], "data": "synthetic",
     }
-    out.update({k: v for k, v in head.items() if k not in out and k not in ("workload", "cache_pct", "in_flight", "unit")})
+    out.update({k: v for k, v in head.items() if k not in out and k not in ("workload", "cache_pct", "in_flight", "unit", "pipeline", "launch")})
 
     if not args.only and args.scale == 1.0:
         # the other workloads, in short: the same timed region and per-kernel pass, a short oracle leg each
@@ -679,7 +775,8 @@ def main() -> int:
             hl, rl = r.get("roofline_host_link"), r.get("roofline")
             short[key] = {
                 "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
-                "in_flight": r["in_flight"], "cache_pct": r["cache_pct"], "cache_hit_rate": r["cache_hit_rate"],
+                "in_flight": r["in_flight"], "pipeline": r["pipeline"], "launch": r["launch"],
+                "cache_pct": r["cache_pct"], "cache_hit_rate": r["cache_hit_rate"],
                 "gather_GBps": r["gather_GBps"], "edges_per_step": r["edges_per_step"], "rows_per_step": r["rows_per_step"],
                 "hit_gather": None if not rl else {"kernel": rl["kernel"], "GBps": rl["achieved"], "frac_of_hbm_peak": rl["frac"],
                                                    "avg_kernel_us": rl["avg_kernel_us"], "traffic": rl["traffic"],
@@ -689,6 +786,15 @@ def main() -> int:
                 "stage_us_per_step": r["stage_us_per_step"],
                 "cpu_baseline": r.get("cpu_baseline"),
             }
+            if wname == "stress" and args.pipeline is None and r is not head:
+                # "stress" is stated with one stream per mini-batch; the same four mini-batches in flight with one
+                # stream per stage, as the other workloads are run, for comparison
+                o2 = argparse.Namespace(**vars(args))
+                o2.pipeline, o2.no_cpu_baseline = "stages", True
+                r2 = run_workload(torch, np, mqg, synth, o2, wname, cache_pct=pct, in_flight=synth.launch_in_flight(ww),
+                                  K=kk, W=min(W, kk), full=False, cpu_budget_s=0.0)
+                short[key]["one_stream_per_stage"] = {"value": r2["value"], "ms_per_step": r2["ms_per_step"],
+                                                      "miss_gather_GBps_pipelined": r2["roofline_host_link"]["pipelined_GBps"]}
         out["workloads"] = short
     print(json.dumps(out))
     return 0

@@ -146,6 +146,33 @@ int mqg_ctx_create(mqg_ctx **out, const mqg_graph *g, int32_t max_seeds,
                    const int32_t *max_fanouts, int32_t num_layers);
 int mqg_ctx_destroy(mqg_ctx *ctx);
 
+/*
+ * Allocate now what a context would otherwise allocate at the first use of an
+ * optional path (with a stream synchronisation there), so that the calls
+ * themselves only enqueue work.  `what` is a sum of:
+ *   MQG_RESERVE_BACKWARD           scratch of the aggregations' backward, for blocks within the
+ *                                  context's bounds (about 24 bytes per sampled edge)
+ *   MQG_RESERVE_LAYERWISE          scratch of mqg_sample_layerwise and mqg_select_smallest_keys
+ *                                  (about 20 bytes per graph node) for up to
+ *                                  max(layerwise_rows, max_seeds) rows per block
+ *   MQG_RESERVE_DEDUP_HASH         table and sort buffers of MQG_OPT_DEDUP_HASH
+ *   MQG_RESERVE_SAMPLING_PRIORITY  tables of mqg_ctx_set_sampling_priority
+ *   MQG_RESERVE_CACHE_BUILD        the temporaries of mqg_build_cache(_ex), about 73 bytes per
+ *                                  graph node, kept until the context is destroyed.  With them a
+ *                                  build allocates and frees nothing, and a build with
+ *                                  MQG_CACHE_DEGREE_SAMPLED - the draw the paper repeats every
+ *                                  epoch - returns as soon as its kernels are enqueued (builds on
+ *                                  one context must then follow one another on one stream).
+ *                                  MQG_CACHE_TOP_DEGREE still reads the maximum degree back and
+ *                                  the random-walk policies the check of the training ids, so
+ *                                  these wait for the stream; the push walk without
+ *                                  graph_symmetric still allocates its transposed adjacency.
+ * The call itself allocates and may synchronise the device; 0 for `what` does nothing.
+ */
+typedef enum { MQG_RESERVE_BACKWARD = 1, MQG_RESERVE_LAYERWISE = 2, MQG_RESERVE_DEDUP_HASH = 4,
+               MQG_RESERVE_SAMPLING_PRIORITY = 8, MQG_RESERVE_CACHE_BUILD = 16 } mqg_reserve;
+int mqg_ctx_reserve(mqg_ctx *ctx, int32_t what, int64_t layerwise_rows);
+
 /* Message of the last failing call on ctx (or of the last failing
  * mqg_ctx_create on this thread when ctx is NULL).  Never NULL. */
 const char *mqg_last_error(const mqg_ctx *ctx);
@@ -157,7 +184,7 @@ typedef enum {
     MQG_OPT_PROFILE = 2,                 /* value != 0: bracket every kernel with HIP events
                                             (adds a few microseconds per kernel)              */
     MQG_OPT_MISS_INFLIGHT_BYTES = 3,     /* bytes of host-memory reads the miss gather keeps
-                                            outstanding (1 KiB..1 GiB, default 512 KiB): sizes
+                                            outstanding (1 KiB..1 GiB, default 1 MiB): sizes
                                             its grid; enough to saturate the host link without
                                             crowding concurrent streams out of the memory system */
     MQG_OPT_HEAVY_DEGREE = 4,            /* destinations with more neighbours than this (>= 64,
@@ -189,8 +216,9 @@ int mqg_ctx_kernel_names(mqg_ctx *ctx, char *buf, int64_t buf_len);
  * s < cache->num_cached, fills slot_of (-1 elsewhere), cached_ids (if not
  * NULL) and copies the cached rows from cache->feats into cache->cache_rows.
  * In: every field of *cache (buffers allocated by the caller).  Temporary
- * device memory (16 bytes per node) is allocated and freed inside the call,
- * which is therefore synchronous with respect to the host.
+ * device memory (24 bytes per node) is allocated and freed inside the call,
+ * which is therefore synchronous with respect to the host - unless
+ * mqg_ctx_reserve(MQG_RESERVE_CACHE_BUILD) has set it aside beforehand.
  */
 int mqg_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *cache, mqg_stream stream);
 
@@ -457,6 +485,31 @@ int mqg_ctx_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *graph, const mq
 int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
                         const void *ids_dev, const int64_t *num_ids_dev, int64_t cap_ids,
                         void *out_dev, int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
+
+/*
+ * The two halves of mqg_gather_features as calls of their own, for a pipeline
+ * that keeps the host link busy (paper Sec. IV: transfer of one mini-batch
+ * overlaps sampling and computation of others): the rows that come over the
+ * host link are then copied on a stream that does nothing else, one
+ * mini-batch after the other, while ids are classified and cached rows copied
+ * elsewhere.
+ *   mqg_gather_features_cached  looks the ids up, copies the rows found in the
+ *       cache (HBM to HBM), writes both counts to stats_dev, and leaves the list
+ *       of the other rows in the context;
+ *   mqg_gather_features_missed  copies those rows from cache->feats.
+ * Same arguments as mqg_gather_features; the pair, in this order, gives the
+ * same rows and stats.  Every _cached call on a context must be followed by its
+ * _missed call (same arguments) before the context gathers again, and the
+ * caller orders the two (same stream, or an event) - the second reads what the
+ * first left.  Without a cache (slot_of == NULL) every row belongs to the
+ * second call and the first does nothing.
+ */
+int mqg_gather_features_cached(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
+                               const void *ids_dev, const int64_t *num_ids_dev, int64_t cap_ids,
+                               void *out_dev, int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
+int mqg_gather_features_missed(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type,
+                               const void *ids_dev, const int64_t *num_ids_dev, int64_t cap_ids,
+                               void *out_dev, int64_t out_stride, int64_t *stats_dev, mqg_stream stream);
 
 /*
  * mqg_gather_features for callers that cannot allocate device memory: code under

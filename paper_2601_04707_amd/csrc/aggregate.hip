@@ -422,33 +422,40 @@ int run_mean_aggregate(mqg_ctx *ctx, const mqg_block *b, const void *x, int64_t 
                          static_cast<float *>(out), out_stride, dim, s);
 }
 
+// Scratch of the backward: room for blocks of nnz_cap edges and src_cap sources (never less than the
+// context's own bounds).  Growing it waits for the stream first: earlier work may still use the old one.
+int ensure_backward_scratch(mqg_ctx *ctx, int64_t nnz_cap, int64_t src_cap, hipStream_t s, const char *who) {
+    if (nnz_cap <= ctx->bwd_nnz_cap && src_cap <= ctx->bwd_src_cap) return MQG_OK;
+    hipError_t e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string(who) + hipGetErrorString(e));
+    free_backward_scratch(ctx);
+    const int64_t nn = std::max<int64_t>(std::max(nnz_cap, ctx->max_nnz), 1);
+    const int64_t ns = std::max<int64_t>(std::max(src_cap, ctx->max_src), 1);
+    auto alloc = [&](void **p, int64_t bytes) { return hipMalloc(p, static_cast<size_t>(std::max<int64_t>(bytes, 4))) == hipSuccess; };
+    bool ok = alloc(reinterpret_cast<void **>(&ctx->bwd.keys[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.keys[1]), nn * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd.vals[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.vals[1]), nn * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd.hist), radix_hist_len(nn) * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd.tile_sums), radix_scan_tiles(nn) * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd_dst_row), nn * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd_w_sorted), nn * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd_col_ptr), (ns + 2) * 4);
+    if (!ok) {
+        free_backward_scratch(ctx);
+        return fail(ctx, MQG_ERR_HIP, std::string(who) + "scratch allocation failed");
+    }
+    ctx->bwd_nnz_cap = nn;
+    ctx->bwd_src_cap = ns;
+    return MQG_OK;
+}
+
 // edge_w == nullptr: the mean aggregation's backward; otherwise the weighted one (self_w may be null)
 int run_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *grad_out,
                            int64_t go_stride, void *grad_x, int64_t gx_stride, int32_t dim, int32_t dtype, hipStream_t s) {
     const char *who = edge_w ? "mqg_weighted_aggregate_backward: " : "mqg_sage_mean_aggregate_backward: ";
-    // scratch for the by-source ordering of the edges, allocated at the first backward call
+    // scratch for the by-source ordering of the edges (reserved, or allocated at the first backward call)
     const int64_t nnz_cap = b->cap_nnz, src_cap = b->cap_src;
-    if (nnz_cap > ctx->bwd_nnz_cap || src_cap > ctx->bwd_src_cap) {
-        hipError_t e = hipStreamSynchronize(s);            // earlier work on this stream may still use the old scratch
-        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string(who) + hipGetErrorString(e));
-        free_backward_scratch(ctx);
-        const int64_t nn = std::max<int64_t>(std::max(nnz_cap, ctx->max_nnz), 1);
-        const int64_t ns = std::max<int64_t>(std::max(src_cap, ctx->max_src), 1);
-        auto alloc = [&](void **p, int64_t bytes) { return hipMalloc(p, static_cast<size_t>(std::max<int64_t>(bytes, 4))) == hipSuccess; };
-        bool ok = alloc(reinterpret_cast<void **>(&ctx->bwd.keys[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.keys[1]), nn * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd.vals[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.vals[1]), nn * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd.hist), radix_hist_len(nn) * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd.tile_sums), radix_scan_tiles(nn) * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd_dst_row), nn * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd_w_sorted), nn * 4) &&
-                  alloc(reinterpret_cast<void **>(&ctx->bwd_col_ptr), (ns + 2) * 4);
-        if (!ok) {
-            free_backward_scratch(ctx);
-            return fail(ctx, MQG_ERR_HIP, std::string(who) + "scratch allocation failed");
-        }
-        ctx->bwd_nnz_cap = nn;
-        ctx->bwd_src_cap = ns;
-    }
+    int rc0 = ensure_backward_scratch(ctx, nnz_cap, src_cap, s, who);
+    if (rc0 != MQG_OK) return rc0;
 
     const int egrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(nnz_cap, kBlock)), 8192));
     if (edge_w) {

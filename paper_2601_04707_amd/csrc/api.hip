@@ -194,6 +194,7 @@ int mqg_ctx_destroy(mqg_ctx *c) {
     mqg::free_layerwise_scratch(c);
     (void)hipFree(c->prio_bitmap);
     (void)hipFree(c->prio_count);
+    (void)hipFree(c->cache_arena);
     for (auto &r : c->prof_recs) {
         (void)hipEventDestroy(r.start);
         (void)hipEventDestroy(r.stop);
@@ -225,6 +226,23 @@ int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value) {
             return MQG_OK;
         default: return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: unknown option");
     }
+}
+
+int mqg_ctx_reserve(mqg_ctx *ctx, int32_t what, int64_t layerwise_rows) {
+    if (!ctx) return MQG_ERR_INVALID_ARG;
+    const int32_t all = MQG_RESERVE_BACKWARD | MQG_RESERVE_LAYERWISE | MQG_RESERVE_DEDUP_HASH | MQG_RESERVE_SAMPLING_PRIORITY |
+                        MQG_RESERVE_CACHE_BUILD;
+    if (what < 0 || (what & ~all) != 0 || layerwise_rows < 0)
+        return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_reserve: unknown flag or negative row count");
+    int rc = MQG_OK;
+    if (rc == MQG_OK && (what & MQG_RESERVE_BACKWARD))
+        rc = mqg::ensure_backward_scratch(ctx, ctx->max_nnz, ctx->max_src, nullptr, "mqg_ctx_reserve: ");
+    if (rc == MQG_OK && (what & MQG_RESERVE_LAYERWISE))
+        rc = mqg::ensure_layerwise_scratch(ctx, std::max<int64_t>(std::max<int64_t>(layerwise_rows, ctx->max_seeds), 1), nullptr);
+    if (rc == MQG_OK && (what & MQG_RESERVE_DEDUP_HASH)) rc = mqg::ensure_hash_scratch(ctx);
+    if (rc == MQG_OK && (what & MQG_RESERVE_SAMPLING_PRIORITY)) rc = mqg::ensure_priority_scratch(ctx);
+    if (rc == MQG_OK && (what & MQG_RESERVE_CACHE_BUILD)) rc = mqg::ensure_cache_build_scratch(ctx);
+    return rc;
 }
 
 int mqg_ctx_kernel_time(mqg_ctx *ctx, const char *name, double *total_ms, int64_t *launches) {
@@ -430,15 +448,36 @@ int mqg_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int
     return mqg::run_exp_tickets(ctx, seed, tag, first, n, tickets_dev, static_cast<hipStream_t>(stream));
 }
 
-int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
-                        const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
-                        int64_t *stats_dev, mqg_stream stream) {
+static int gather_checked(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                          const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
+                          int64_t *stats_dev, int phases, mqg_stream stream) {
     if (!ctx) return MQG_ERR_INVALID_ARG;
     int rc = mqg::check_gather_args(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, ctx->max_src,
                                     "the context's largest source list");
     if (rc != MQG_OK) return rc;
     return mqg::run_gather(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride,
-                           stats_dev, static_cast<hipStream_t>(stream));
+                           stats_dev, phases, static_cast<hipStream_t>(stream));
+}
+
+int mqg_gather_features(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                        const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
+                        int64_t *stats_dev, mqg_stream stream) {
+    return gather_checked(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, stats_dev,
+                          mqg::kGatherCached | mqg::kGatherMissed, stream);
+}
+
+int mqg_gather_features_cached(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                               const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
+                               int64_t *stats_dev, mqg_stream stream) {
+    return gather_checked(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, stats_dev,
+                          mqg::kGatherCached, stream);
+}
+
+int mqg_gather_features_missed(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
+                               const int64_t *num_ids_dev, int64_t cap_ids, void *out_dev, int64_t out_stride,
+                               int64_t *stats_dev, mqg_stream stream) {
+    return gather_checked(ctx, cache, idx_type, ids_dev, num_ids_dev, cap_ids, out_dev, out_stride, stats_dev,
+                          mqg::kGatherMissed, stream);
 }
 
 int mqg_sage_mean_aggregate(mqg_ctx *ctx, const mqg_block *block, const void *x_src, int64_t x_stride,

@@ -319,15 +319,28 @@ __global__ void k_store_i64(int64_t *p, int64_t v) {
     if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
 }
 
+// Temporaries of one build.  With a reserved arena (mqg_ctx_reserve) they are carved out of it and
+// nothing is allocated; what does not fit - the transposed adjacency of the push walk, sized by the
+// edges - and everything on a context without an arena is hipMalloc'ed and freed on return.
 struct Temp {
+    char *arena = nullptr;
+    int64_t arena_bytes = 0, used = 0;
     std::vector<void *> ptrs;
+    explicit Temp(mqg_ctx *ctx) : arena(ctx->cache_arena), arena_bytes(ctx->cache_arena_bytes) {}
     ~Temp() {
         for (void *p : ptrs) (void)hipFree(p);
     }
+    bool allocated_any() const { return !ptrs.empty(); }
     template <typename T>
     bool alloc(T **p, int64_t n) {
+        const int64_t bytes = (std::max<int64_t>(n, 1) * int64_t(sizeof(T)) + 255) & ~int64_t(255);
+        if (arena && used + bytes <= arena_bytes) {
+            *p = reinterpret_cast<T *>(arena + used);
+            used += bytes;
+            return true;
+        }
         void *q = nullptr;
-        if (hipMalloc(&q, static_cast<size_t>(std::max<int64_t>(n, 1)) * sizeof(T)) != hipSuccess) return false;
+        if (hipMalloc(&q, static_cast<size_t>(bytes)) != hipSuccess) return false;
         ptrs.push_back(q);
         *p = static_cast<T *>(q);
         return true;
@@ -370,7 +383,7 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         return e == hipSuccess ? MQG_OK : fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
     }
 
-    Temp tmp;
+    Temp tmp(ctx);
     const int ngrid = static_cast<int>(ceil_div(n, kBlock));
     const int32_t *ranked = nullptr;
     uint32_t *walk_flags = nullptr;                  // bit 0: a training id outside the graph
@@ -511,6 +524,9 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
                                    c->cache_stride * elt, int64_t(c->dim) * elt, s);
         if (rc != MQG_OK) return rc;
     }
+    // With every temporary in the reserved arena and nothing to report back, the call ends here: the
+    // work is enqueued and the arena stays the context's (the next build on it follows on the stream).
+    if (!walk_flags && !tmp.allocated_any() && ctx->cache_arena && policy != MQG_CACHE_TOP_DEGREE) return MQG_OK;
     uint32_t flags = 0;
     if (walk_flags) {
         e = hipMemcpyAsync(&flags, walk_flags, sizeof(uint32_t), hipMemcpyDeviceToHost, s);
@@ -527,6 +543,23 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
 int run_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int64_t n, uint64_t *tickets, hipStream_t s) {
     const uint64_t tag_hash = host_mix64(host_mix64(seed + kGolden) ^ static_cast<uint64_t>(tag));
     MQG_LAUNCH(ctx, "k_exp_tickets", s, (k_exp_tickets<<<static_cast<int>(ceil_div(n, kBlock)), kBlock, 0, s>>>(tag_hash, first, n, tickets)));
+    return MQG_OK;
+}
+
+// The arena that holds a build's temporaries: room for the largest policy that does not transpose
+// the adjacency (scores drawn from a random walk: three score vectors, 64-bit keys, two 32-bit
+// sorts), about 73 bytes per node.
+int ensure_cache_build_scratch(mqg_ctx *ctx) {
+    if (ctx->cache_arena) return MQG_OK;
+    const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
+    const int64_t bytes = n * (3 * 8 + 8 + 4 * 4 + 4 * 4 + 2 * 4) + (radix_hist_len(n) + radix_scan_tiles(n)) * 4 + 64 * 256;
+    void *p = nullptr;
+    if (hipMalloc(&p, static_cast<size_t>(bytes)) != hipSuccess) {
+        (void)hipGetLastError();
+        return fail(ctx, MQG_ERR_HIP, "mqg_ctx_reserve: cache-build scratch allocation failed");
+    }
+    ctx->cache_arena = static_cast<char *>(p);
+    ctx->cache_arena_bytes = bytes;
     return MQG_OK;
 }
 

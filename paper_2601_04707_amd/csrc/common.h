@@ -93,6 +93,9 @@ struct mqg_ctx {
     bool prio_enabled = false;
     uint32_t *prio_bitmap = nullptr;     // [bitmap_words] bit v = node v is cached
     int32_t *prio_count = nullptr;       // [num_nodes] number of cached neighbours of every node
+    // temporaries of the cache build, reserved by mqg_ctx_reserve (otherwise allocated and freed per call)
+    char *cache_arena = nullptr;
+    int64_t cache_arena_bytes = 0;
     // hash-table dedup (MQG_OPT_DEDUP_HASH); allocated when the option is first used
     bool dedup_hash = false;
     unsigned long long *hash_table = nullptr;      // [hash_capacity] (id << 32 | position), all ones = empty
@@ -104,7 +107,7 @@ struct mqg_ctx {
     // options
     bool force_slow_select = false;
     bool profile = false;
-    int64_t miss_inflight_bytes = 512 * 1024;   // read bytes the host-link gather keeps outstanding
+    int64_t miss_inflight_bytes = 1024 * 1024;  // read bytes the host-link gather keeps outstanding
     int heavy_degree = 2048;             // rows longer than this get a whole workgroup in sampling
 
     // profiling
@@ -142,9 +145,10 @@ inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
 // ---- steps implemented in the other translation units ----------------------------------
 int run_sample_blocks(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *fanouts,
                       int32_t L, uint64_t rng_seed, const uint64_t *seed_dev, mqg_block *blocks, hipStream_t s);
+constexpr int kGatherCached = 1, kGatherMissed = 2;   // the two halves of a gather
 int run_gather(mqg_ctx *ctx, const mqg_cache *c, int32_t idx_type, const void *ids,
                const int64_t *num_ids, int64_t cap_ids, void *out, int64_t out_stride,
-               int64_t *stats, hipStream_t s);
+               int64_t *stats, int phases, hipStream_t s);
 int check_gather_args(mqg_ctx *ctx, const mqg_cache *cache, int32_t idx_type, const void *ids_dev,
                       const int64_t *num_ids_dev, int64_t cap_ids, const void *out_dev, int64_t out_stride,
                       int64_t max_ids, const char *what_max);
@@ -157,6 +161,10 @@ int run_gcn_edge_weights(mqg_ctx *ctx, const mqg_graph *g, const mqg_block *b, f
 int run_weighted_aggregate(mqg_ctx *ctx, const mqg_block *b, const float *edge_w, const float *self_w, const void *x,
                            int64_t x_stride, void *out, int64_t out_stride, int32_t dim, int32_t dtype, hipStream_t s);
 void free_backward_scratch(mqg_ctx *ctx);
+int ensure_backward_scratch(mqg_ctx *ctx, int64_t nnz_cap, int64_t src_cap, hipStream_t s, const char *who);
+int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s);
+int ensure_priority_scratch(mqg_ctx *ctx);
+int ensure_cache_build_scratch(mqg_ctx *ctx);
 int run_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds, int32_t num_seeds, const int32_t *layer_sizes,
                          int32_t L, uint64_t rng_seed, int32_t normalise, int32_t method, mqg_block *blocks,
                          float *const *edge_w, hipStream_t s);

@@ -595,7 +595,7 @@ void free_layerwise_scratch(mqg_ctx *ctx) {
 }
 
 // scratch of the layer-wise sampler: about 20 bytes per graph node, allocated at the first call
-static int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
+int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
     LayerwiseScratch &w = ctx->lw;
     if (w.mass && rows_cap <= w.rows_cap) return MQG_OK;
     hipError_t e = hipStreamSynchronize(s);

@@ -1144,23 +1144,29 @@ int run_select_row_candidates(mqg_ctx *ctx, const uint64_t *keys, const uint32_t
     return MQG_OK;
 }
 
+// the membership bitmap and the table of cached-neighbour counts
+int ensure_priority_scratch(mqg_ctx *ctx) {
+    if (ctx->prio_bitmap) return MQG_OK;
+    bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->prio_bitmap), static_cast<size_t>(ctx->bitmap_words) * sizeof(uint32_t)) == hipSuccess &&
+              hipMalloc(reinterpret_cast<void **>(&ctx->prio_count), static_cast<size_t>(std::max<int64_t>(ctx->num_nodes, 1)) * sizeof(int32_t)) == hipSuccess;
+    if (!ok) {
+        (void)hipFree(ctx->prio_bitmap);
+        (void)hipFree(ctx->prio_count);
+        ctx->prio_bitmap = nullptr;
+        ctx->prio_count = nullptr;
+        return fail(ctx, MQG_ERR_HIP, "mqg_ctx_set_sampling_priority: allocation failed");
+    }
+    return MQG_OK;
+}
+
 // cache == nullptr switches the priority off; otherwise the membership bitmap is (re)built from cache->slot_of
 int run_set_sampling_priority(mqg_ctx *ctx, const mqg_graph *g, const mqg_cache *cache, hipStream_t s) {
     if (!cache) {
         ctx->prio_enabled = false;
         return MQG_OK;
     }
-    if (!ctx->prio_bitmap) {
-        bool ok = hipMalloc(reinterpret_cast<void **>(&ctx->prio_bitmap), static_cast<size_t>(ctx->bitmap_words) * sizeof(uint32_t)) == hipSuccess &&
-                  hipMalloc(reinterpret_cast<void **>(&ctx->prio_count), static_cast<size_t>(std::max<int64_t>(ctx->num_nodes, 1)) * sizeof(int32_t)) == hipSuccess;
-        if (!ok) {
-            (void)hipFree(ctx->prio_bitmap);
-            (void)hipFree(ctx->prio_count);
-            ctx->prio_bitmap = nullptr;
-            ctx->prio_count = nullptr;
-            return fail(ctx, MQG_ERR_HIP, "mqg_ctx_set_sampling_priority: allocation failed");
-        }
-    }
+    int rc0 = ensure_priority_scratch(ctx);
+    if (rc0 != MQG_OK) return rc0;
     const int grid = static_cast<int>(ctx->bitmap_words * 32 / kBlock);
     MQG_LAUNCH(ctx, "k_prio_bitmap", s, (k_prio_bitmap<<<grid, kBlock, 0, s>>>(cache->slot_of, ctx->num_nodes, ctx->prio_bitmap)));
     const int64_t n = ctx->num_nodes;

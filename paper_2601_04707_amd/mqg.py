@@ -33,7 +33,8 @@ EXPORTS = [
     "mqg_queue_size", "mqg_build_cache_ex", "mqg_gcn_edge_weights", "mqg_weighted_aggregate",
     "mqg_weighted_aggregate_backward", "mqg_ctx_set_sampling_priority", "mqg_sample_layerwise",
     "mqg_select_smallest_keys", "mqg_select_row_candidates", "mqg_sample_blocks_seed_dev",
-    "mqg_gather_features_static", "mqg_exp_tickets",
+    "mqg_gather_features_static", "mqg_exp_tickets", "mqg_gather_features_cached", "mqg_gather_features_missed",
+    "mqg_ctx_reserve",
 ]
 
 if not os.path.exists(LIB_PATH):
@@ -77,6 +78,9 @@ lib.mqg_last_error.restype = ctypes.c_char_p
 lib.mqg_last_error.argtypes = [_vp]
 lib.mqg_ctx_set_option.restype = ctypes.c_int
 lib.mqg_ctx_set_option.argtypes = [_vp, _i32, _i64]
+lib.mqg_ctx_reserve.restype = ctypes.c_int
+lib.mqg_ctx_reserve.argtypes = [_vp, _i32, _i64]
+MQG_RESERVE_BACKWARD, MQG_RESERVE_LAYERWISE, MQG_RESERVE_DEDUP_HASH, MQG_RESERVE_SAMPLING_PRIORITY, MQG_RESERVE_CACHE_BUILD = 1, 2, 4, 8, 16
 lib.mqg_ctx_kernel_time.restype = ctypes.c_int
 lib.mqg_ctx_kernel_time.argtypes = [_vp, ctypes.c_char_p, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(_i64)]
 lib.mqg_ctx_reset_profile.restype = ctypes.c_int
@@ -92,6 +96,9 @@ lib.mqg_sample_blocks.argtypes = [_vp, ctypes.POINTER(CGraph), _vp, _i32, ctypes
                                   ctypes.c_uint64, ctypes.POINTER(CBlock), _vp]
 lib.mqg_gather_features.restype = ctypes.c_int
 lib.mqg_gather_features.argtypes = [_vp, ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
+for _name in ("mqg_gather_features_cached", "mqg_gather_features_missed"):
+    getattr(lib, _name).restype = ctypes.c_int
+    getattr(lib, _name).argtypes = [_vp, ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
 lib.mqg_gather_features_static.restype = ctypes.c_int
 lib.mqg_gather_features_static.argtypes = [ctypes.POINTER(CCache), _i32, _vp, _vp, _i64, _vp, _i64, _vp, _vp]
 MQG_GATHER_STATIC_MAX_IDS = 1 << 20
@@ -192,6 +199,10 @@ class Context:
 
     def set_option(self, option: int, value: int):
         self.check(lib.mqg_ctx_set_option(self.h, option, value))
+
+    def reserve(self, what: int, layerwise_rows: int = 0):
+        """Allocate optional-path scratch now (a sum of MQG_RESERVE_*)."""
+        self.check(lib.mqg_ctx_reserve(self.h, what, layerwise_rows))
 
     def set_sampling_priority(self, cache, stream=None):
         """Draw cached neighbours first (cache: a Cache, or None for the uniform draw)."""
@@ -407,6 +418,27 @@ def mqg_gather_features(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: 
     assert cap <= ids.numel() and cap <= out.shape[0]
     ctx.check(lib.mqg_gather_features(ctx.h, ctypes.byref(cache.c), _itype(ids), ids.data_ptr(), num_ids.data_ptr(),
                                       cap, out.data_ptr(), out.stride(0), _ptr(stats), _stream(stream)))
+
+
+def _gather_half(fn, ctx, cache, ids, num_ids, out, stats, cap_ids, stream):
+    assert ids.is_cuda and num_ids.is_cuda and num_ids.dtype == torch.int64 and out.is_cuda
+    assert out.dtype == cache.feats.dtype and out.stride(1) == 1
+    cap = int(cap_ids if cap_ids is not None else min(ids.numel(), out.shape[0]))
+    assert cap <= ids.numel() and cap <= out.shape[0]
+    ctx.check(fn(ctx.h, ctypes.byref(cache.c), _itype(ids), ids.data_ptr(), num_ids.data_ptr(), cap, out.data_ptr(),
+                 out.stride(0), _ptr(stats), _stream(stream)))
+
+
+def mqg_gather_features_cached(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,
+                               stats: Optional[torch.Tensor] = None, cap_ids: Optional[int] = None, stream=None) -> None:
+    """First half of mqg_gather_features: classify the ids, copy the cached rows."""
+    _gather_half(lib.mqg_gather_features_cached, ctx, cache, ids, num_ids, out, stats, cap_ids, stream)
+
+
+def mqg_gather_features_missed(ctx: Context, cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,
+                               stats: Optional[torch.Tensor] = None, cap_ids: Optional[int] = None, stream=None) -> None:
+    """Second half: copy the rows the first half did not find in the cache."""
+    _gather_half(lib.mqg_gather_features_missed, ctx, cache, ids, num_ids, out, stats, cap_ids, stream)
 
 
 def mqg_gather_features_static(cache: Cache, ids: torch.Tensor, num_ids: torch.Tensor, out: torch.Tensor,

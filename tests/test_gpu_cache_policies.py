@@ -248,3 +248,64 @@ def test_exp_ticket_stream_over_thousands_of_workgroups(mqg):
         want = oracle.exp_tickets(seed, tag, first, n)
         assert np.array_equal(got.cpu().numpy().view(np.uint64), want)
     assert mqg.mqg_exp_tickets(ctx, 1, 0, 0, 0).numel() == 0
+
+
+def test_reserved_scratch_gives_the_same_results_and_no_later_allocation(mqg):
+    """mqg_ctx_reserve: every optional path on a context that set its scratch aside beforehand gives
+    what a plain context gives, and the device's free memory does not move while they run."""
+    rp, ci = graph()
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, 6, seed=3).pin_memory()
+    fanouts = [6, 4]
+    batch = 200
+    plain, ready = mqg.Context(g, batch, fanouts), mqg.Context(g, batch, fanouts)
+    ready.reserve(mqg.MQG_RESERVE_BACKWARD | mqg.MQG_RESERVE_LAYERWISE | mqg.MQG_RESERVE_DEDUP_HASH |
+                  mqg.MQG_RESERVE_SAMPLING_PRIORITY | mqg.MQG_RESERVE_CACHE_BUILD, 512)
+    ready.reserve(0)
+    with pytest.raises(mqg.MqgError):
+        ready.reserve(1 << 10)
+    train = torch.randperm(n, generator=torch.Generator().manual_seed(4))[: n // 100].to(torch.int64)
+    seeds = to_dev(synth.seed_batches(n, batch, 1, seed=5)[0])
+    train_dev = to_dev(train)
+    results = {}
+    # buffers first, so that nothing below allocates through torch either
+    bufs = {}
+    for name, ctx in (("plain", plain), ("ready", ready)):
+        bufs[name] = dict(caches=[mqg.Cache(g, feats, n // 20) for _ in range(4)], blocks=mqg.Blocks(g, batch, fanouts),
+                          lw=mqg.LayerwiseBlocks(g, batch, [300, 300]), scores=torch.zeros(n, dtype=torch.float64, device="cuda"),
+                          gx=torch.zeros((mqg.block_bounds(n, batch, fanouts)[1][1], 8), device="cuda"),
+                          go=torch.ones((batch, 8), device="cuda"))
+    torch.cuda.synchronize()
+    for name, ctx in (("plain", plain), ("ready", ready)):
+        b = bufs[name]
+        free0 = torch.cuda.mem_get_info()[0]
+        out = []
+        mqg.mqg_build_cache(ctx, g, b["caches"][0])
+        mqg.mqg_build_cache_ex(ctx, g, b["caches"][1], mqg.MQG_CACHE_DEGREE_SAMPLED, seed=3)
+        mqg.mqg_build_cache_ex(ctx, g, b["caches"][2], mqg.MQG_CACHE_DEGREE_SAMPLED, seed=4)      # right behind it, same arena
+        mqg.mqg_build_cache_ex(ctx, g, b["caches"][3], mqg.MQG_CACHE_RANDOM_WALK_SAMPLED, seed=5, train_ids=train_dev,
+                               step_fanouts=[4, 6], scores_out=b["scores"], graph_symmetric=True)
+        torch.cuda.synchronize()
+        out += [c.slot_of.cpu().numpy().copy() for c in b["caches"]]
+        ctx.set_sampling_priority(b["caches"][0])
+        mqg.mqg_sample_blocks(ctx, g, seeds, fanouts, 9, b["blocks"])
+        torch.cuda.synchronize()
+        out += [t.cpu().numpy().copy() for t in b["blocks"].indices] + [b["blocks"].sizes.cpu().numpy().copy()]
+        ctx.set_sampling_priority(None)
+        ctx.set_option(mqg.MQG_OPT_DEDUP_HASH, 1)
+        mqg.mqg_sample_blocks(ctx, g, seeds, fanouts, 10, b["blocks"])
+        ctx.set_option(mqg.MQG_OPT_DEDUP_HASH, 0)
+        mqg.mqg_sage_mean_aggregate_backward(ctx, b["blocks"], 1, b["go"], b["gx"])
+        mqg.mqg_sample_layerwise(ctx, g, seeds, [300, 300], 11, b["lw"])
+        torch.cuda.synchronize()
+        out += [t.cpu().numpy().copy() for t in b["blocks"].indices] + [b["gx"].cpu().numpy().copy()]
+        out += [t.cpu().numpy().copy() for t in b["lw"].src_ids] + [b["lw"].sizes.cpu().numpy().copy()]
+        results[name] = out
+        if name == "ready":
+            assert torch.cuda.mem_get_info()[0] == free0            # nothing was allocated on the way
+    assert len(results["plain"]) == len(results["ready"])
+    for a, b in zip(results["plain"], results["ready"]):
+        assert np.array_equal(a, b)
+    want = oracle.build_cache_sampled(rp.numpy(), n // 20, 4)
+    assert np.array_equal(results["ready"][2], want.slot_of)

@@ -1,6 +1,6 @@
 """The five workloads at their full sizes, in the launch configuration bench.py times (three
-mini-batches in flight on three streams, one context each; "stress": four on four, with the cache
-at 5, 20 and 50 % of the nodes).
+mini-batches in flight, one context each, one stream per stage; "stress": four mini-batches on four
+streams, with the cache at 5, 20 and 50 % of the nodes).
 
 Blocks, gathered rows, hit and miss counts and the aggregation of every block are compared with
 the oracle element by element (the oracle only touches a batch's sampled neighbourhood, so it
@@ -127,14 +127,32 @@ def test_full_size_workload(mqg, name, cache_pct):
           for _ in range(nfl)]
     stats = [torch.zeros(2, dtype=torch.int64, device=dev) for _ in range(nfl)]
     torch.cuda.synchronize()
-    for j in range(nfl):                                        # all in flight, as in bench.py
-        s = streams[j]
-        mqg.mqg_sample_blocks(ctxs[j], g, seeds_dev[j], w.fanouts, 3 + j, blks[j], stream=s)
-        mqg.mqg_gather_features(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s)
-        x = x0[j]
-        for l in range(L):
-            mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s)
-            x = hs[j][l]
+    if name == "stress":                                        # its stated shape: one stream per mini-batch
+        for j in range(nfl):
+            s = streams[j]
+            mqg.mqg_sample_blocks(ctxs[j], g, seeds_dev[j], w.fanouts, 3 + j, blks[j], stream=s)
+            mqg.mqg_gather_features(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s)
+            x = x0[j]
+            for l in range(L):
+                mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s)
+                x = hs[j][l]
+    else:
+        # bench.py's pipeline: one stream per stage - sampling, the id lookup and the cached rows on the
+        # first, the rows that cross the host link on the second, the aggregations on the third
+        s_s, s_g, s_a = streams[:3]
+        for j in range(nfl):
+            ev_s, ev_g = torch.cuda.Event(), torch.cuda.Event()
+            mqg.mqg_sample_blocks(ctxs[j], g, seeds_dev[j], w.fanouts, 3 + j, blks[j], stream=s_s)
+            mqg.mqg_gather_features_cached(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s_s)
+            ev_s.record(s_s)
+            s_g.wait_event(ev_s)
+            mqg.mqg_gather_features_missed(ctxs[j], cache, blks[j].src_ids[0], blks[j].sizes[0, 1:2], x0[j], stats[j], stream=s_g)
+            ev_g.record(s_g)
+            s_a.wait_event(ev_g)
+            x = x0[j]
+            for l in range(L):
+                mqg.mqg_sage_mean_aggregate(ctxs[j], blks[j], l, x, hs[j][l], stream=s_a)
+                x = hs[j][l]
     torch.cuda.synchronize()
 
     # --- properties of every batch (GPU side, any size)

@@ -362,6 +362,51 @@ def test_gather_ids_outside_the_graph_are_skipped_and_show_in_the_stats(mqg, dim
         assert stats.tolist() == [0, count]
 
 
+@pytest.mark.parametrize("dim,dtype", [(602, torch.float32), (100, torch.float32), (128, torch.float16)])
+def test_gather_in_two_halves_equals_the_whole(mqg, dim, dtype):
+    """mqg_gather_features_cached on one stream, mqg_gather_features_missed on another, ordered by an
+    event: same rows and stats as the single call and as the oracle - several gathers in a row on one
+    context, also without a cache."""
+    rp, ci = hub_graph(n=9000, edges=200_000, max_degree=1200, seed=6)
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    feats = synth.node_features(n, dim, dtype=dtype, seed=9).pin_memory()
+    elt = feats.element_size()
+    stride = (dim * elt + 63) // 64 * 64 // elt
+    ctx = mqg.Context(g, 512, [12])
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for num_cached in (n // 4, 0, None):
+        cache = mqg.Cache(g, feats, num_cached, cache_stride=stride if num_cached is not None else None)
+        want = None
+        if num_cached is not None:
+            mqg.mqg_build_cache(ctx, g, cache)
+            want = oracle.build_cache(rp.numpy(), num_cached, feats.numpy())
+        torch.cuda.synchronize()
+        for count in (4000, 0, 777, 6000):
+            ids_np = np.random.default_rng(count).permutation(n)[:count].astype(np.int64)
+            cap = count + 1
+            ids = torch.zeros(cap, dtype=torch.int64, device="cuda")
+            ids[:count] = torch.from_numpy(ids_np).cuda()
+            num = torch.tensor([count], dtype=torch.int64, device="cuda")
+            whole = torch.full((cap, stride), 7.0, dtype=dtype, device="cuda")
+            st_whole = torch.zeros(2, dtype=torch.int64, device="cuda")
+            mqg.mqg_gather_features(ctx, cache, ids, num, whole[:, :dim], st_whole)
+            torch.cuda.synchronize()
+            halves = torch.full((cap, stride), 7.0, dtype=dtype, device="cuda")
+            st_halves = torch.zeros(2, dtype=torch.int64, device="cuda")
+            ev = torch.cuda.Event()
+            mqg.mqg_gather_features_cached(ctx, cache, ids, num, halves[:, :dim], st_halves, stream=s1)
+            ev.record(s1)
+            s2.wait_event(ev)
+            mqg.mqg_gather_features_missed(ctx, cache, ids, num, halves[:, :dim], st_halves, stream=s2)
+            torch.cuda.synchronize()
+            ref, h, m = oracle.gather(ids_np, feats.numpy(), want)
+            assert halves[:count, :dim].contiguous().cpu().numpy().tobytes() == ref.tobytes(), (num_cached, count)
+            assert whole[:count, :dim].contiguous().cpu().numpy().tobytes() == ref.tobytes(), (num_cached, count)
+            assert torch.all(halves[count:] == 7.0)
+            assert st_halves.tolist() == st_whole.tolist() == [h, m], (num_cached, count)
+
+
 def test_cache_ties_and_many_equal_degrees(mqg):
     # ring: every degree equal -> cache is the lowest ids; then a star on top
     n = 5000
