@@ -101,6 +101,10 @@ def concurrent_streams(torch, n):
             rest.append(st)
     log(f"streams: {len(picked)} on distinct hardware queues (one spin kernel {one:.0f} us)")
     picked += rest[: max(0, n - len(picked))]
+    k = 0
+    while len(picked) < n:                                     # more asked for than created: share, in turn
+        picked.append(picked[k])
+        k += 1
     _streams[:] = picked
     return _streams[:n]
 
@@ -403,11 +407,12 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                                  "bounds ms_per_step")
 
     # the forward profile pass launches nothing else through the radix/scan kernels than the hash dedup
-    dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_reset_local", "k_zero_u64", "k_scan_tiles(radix)",
-                     "k_scan_tiles(bitmap)", "k_scan_reduce", "k_scan_apply")
+    # (k_relabel_rowinfo also carries the next block's row information, k_offsets_count the row offsets)
+    dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_relabel_rowinfo", "k_reset_local", "k_zero_u64",
+                     "k_scan_tiles(radix)", "k_scan_tiles(bitmap)", "k_scan_reduce", "k_scan_apply")
     dedup_us = sum(v["us_per_step"] for k, v in kern.items()
                    if k in dedup_kernels or k.startswith("k_hash_") or k.startswith("k_radix_"))
-    sample_names = ("k_init_seeds", "k_row_info", "k_scan_tiles(rows)", "k_row_offsets", "k_sample", "k_sample_prio")
+    sample_names = ("k_init_seeds", "k_row_info", "k_scan_tiles(rows)", "k_row_offsets", "k_offsets_count", "k_sample", "k_sample_prio")
     sample_us = dedup_us + sum(v["us_per_step"] for k, v in kern.items() if k in sample_names)
     gather_us = sum(v["us_per_step"] for k, v in kern.items() if k.startswith("k_gather") or k in ("k_classify", "k_fill_u64", "k_direct_stats"))
     agg_us = kern.get("k_mean_aggregate", {}).get("us_per_step", 0.0)
@@ -519,6 +524,7 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
     KB = min(K, 50)
     for i in range(W, W + KB):
         step(i)
+        torch.cuda.synchronize()                                # the step may have run on the stage streams
         j = i % nfl
         with torch.cuda.stream(streams[j]):
             gcur = g_top

@@ -124,16 +124,19 @@ struct DirectRows {
     }
 };
 
-// A 16-byte load that is not kept in the caches on its way (read-once data of a launch too large
-// for the last-level cache); narrower vectors are loaded normally.
-template <typename VecT>
-__device__ __forceinline__ VecT load_vec(const VecT *p, bool) { return *p; }
+// A 16-byte load that is not kept in the caches on its way (STREAM: read-once data of a launch too
+// large for the last-level cache); narrower vectors are loaded normally.
 typedef unsigned int uint4_native __attribute__((ext_vector_type(4)));
-template <>
-__device__ __forceinline__ uint4 load_vec<uint4>(const uint4 *p, bool streaming) {
-    if (!streaming) return *p;
-    const uint4_native v = __builtin_nontemporal_load(reinterpret_cast<const uint4_native *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
+template <bool STREAM, typename VecT>
+__device__ __forceinline__ VecT load_vec(const VecT *p) {
+    if constexpr (STREAM && sizeof(VecT) == 16) {
+        const uint4_native v = __builtin_nontemporal_load(reinterpret_cast<const uint4_native *>(p));
+        VecT out;
+        __builtin_memcpy(&out, &v, 16);
+        return out;
+    } else {
+        return *p;
+    }
 }
 
 constexpr int kRowUnroll = 4;                            // row loads in flight per lane (rows of up to 64 vectors)
@@ -141,10 +144,10 @@ constexpr int kRowUnroll = 4;                            // row loads in flight 
 // eight loads per lane are issued before the first store (a row's last, partial chunk rides along
 // instead of trailing alone).  NCH is the number of chunks a row needs, at most four; loads are
 // unconditional (an index past the row re-reads its last vector), only the stores are predicated.
-template <typename VecT, int NCH, int WR, typename Rows>
+template <typename VecT, int NCH, int WR, bool STREAM, typename Rows>
 __device__ __forceinline__ void copy_rows_wide(const Rows &rows, int64_t n, const char *__restrict__ src,
                                                int64_t src_stride_bytes, char *__restrict__ dst,
-                                               int64_t dst_stride_bytes, int vecs, bool streaming) {
+                                               int64_t dst_stride_bytes, int vecs) {
     const int lane = lane_id();
     const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
@@ -169,7 +172,7 @@ __device__ __forceinline__ void copy_rows_wide(const Rows &rows, int64_t n, cons
 #pragma unroll
                 for (int k = 0; k < NCH; ++k) {
                     const int c = c0 + k * kWave;
-                    v[q][k] = load_vec(&sp[q][c < vecs ? c : vecs - 1], streaming);
+                    v[q][k] = load_vec<STREAM>(&sp[q][c < vecs ? c : vecs - 1]);
                 }
 #pragma unroll
             for (int q = 0; q < WR; ++q)
@@ -190,15 +193,15 @@ inline __host__ __device__ int wide_rows(int vecs) { return vecs > 2 * kWave ? 2
 // into 64/LPR groups of LPR lanes (LPR = 2^log2_lpr >= vecs), every group copies one row per step
 // and kRowUnroll steps are in flight, so a wavefront moves 4*64/LPR short rows at a time.  Longer
 // rows: copy_rows_wide.
-template <typename VecT, typename Rows>
+template <typename VecT, bool STREAM, typename Rows>
 __device__ __forceinline__ void copy_rows(const Rows &rows, int64_t n, const char *__restrict__ src,
                                           int64_t src_stride_bytes, char *__restrict__ dst,
-                                          int64_t dst_stride_bytes, int vecs, int log2_lpr, bool streaming) {
+                                          int64_t dst_stride_bytes, int vecs, int log2_lpr) {
     if (vecs > kWave) {
         switch (wide_chunks(vecs)) {
-            case 2: copy_rows_wide<VecT, 2, 4>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, streaming); break;
-            case 3: copy_rows_wide<VecT, 3, 2>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, streaming); break;
-            default: copy_rows_wide<VecT, 4, 2>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, streaming); break;
+            case 2: copy_rows_wide<VecT, 2, 4, STREAM>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
+            case 3: copy_rows_wide<VecT, 3, 2, STREAM>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
+            default: copy_rows_wide<VecT, 4, 2, STREAM>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs); break;
         }
         return;
     }
@@ -248,10 +251,10 @@ constexpr int kFlatUnroll = 4;
 // lose 5-15 % with it.
 constexpr int64_t kStreamingBytes = int64_t(320) << 20;
 
-template <typename VecT, typename Rows>
+template <typename VecT, bool STREAM, typename Rows>
 __device__ __forceinline__ void copy_rows_flat(const Rows &rows, int64_t n, const char *__restrict__ src,
                                                int64_t src_stride_bytes, char *__restrict__ dst,
-                                               int64_t dst_stride_bytes, int vecs, unsigned long long magic, bool streaming) {
+                                               int64_t dst_stride_bytes, int vecs, unsigned long long magic) {
     const int64_t total = n * vecs;
     const int64_t span = int64_t(kBlock) * kFlatUnroll;
     for (int64_t b0 = int64_t(blockIdx.x) * span; b0 < total; b0 += int64_t(gridDim.x) * span) {
@@ -274,7 +277,7 @@ __device__ __forceinline__ void copy_rows_flat(const Rows &rows, int64_t n, cons
             dp[u] = reinterpret_cast<VecT *>(dst + drow * dst_stride_bytes) + col;
         }
 #pragma unroll
-        for (int u = 0; u < kFlatUnroll; ++u) v[u] = load_vec(sp[u], streaming);
+        for (int u = 0; u < kFlatUnroll; ++u) v[u] = load_vec<STREAM>(sp[u]);
 #pragma unroll
         for (int u = 0; u < kFlatUnroll; ++u)
             if (ok[u]) *dp[u] = v[u];
@@ -296,9 +299,15 @@ k_gather_rows(const int2 *__restrict__ list, const unsigned long long *count,
     if (stats && blockIdx.x == 0 && threadIdx.x < 2) stats[threadIdx.x] = static_cast<int64_t>(counters[threadIdx.x]);
     const int64_t n = static_cast<int64_t>(*count);
     // a launch that moves more than the last-level cache holds reads its source rows past the caches
-    const bool streaming = !MISS && 2 * n * vecs * int64_t(sizeof(VecT)) > kStreamingBytes;
-    if (magic) copy_rows_flat<VecT>(ListRows{list}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic, streaming);
-    else copy_rows<VecT>(ListRows{list}, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr, streaming);
+    const bool streaming = !MISS && sizeof(VecT) == 16 && 2 * n * vecs * int64_t(sizeof(VecT)) > kStreamingBytes;
+    const ListRows rows{list};
+    if (streaming) {                                       // one uniform branch; the copies themselves are straight code
+        if (magic) copy_rows_flat<VecT, true>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic);
+        else copy_rows<VecT, true>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
+    } else {
+        if (magic) copy_rows_flat<VecT, false>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic);
+        else copy_rows<VecT, false>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
+    }
     if (MISS) {
         __syncthreads();                                   // every thread of the workgroup has read its count
         if (threadIdx.x == 0) {
@@ -321,8 +330,8 @@ k_gather_direct(const IdxT *__restrict__ ids, const int64_t *__restrict__ num_id
     int64_t n = *num_ids;
     if (n > cap) n = cap;
     const DirectRows<IdxT> rows{ids, src_rows, bad};
-    if (magic) copy_rows_flat<VecT>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic, false);
-    else copy_rows<VecT>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr, false);
+    if (magic) copy_rows_flat<VecT, false>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, magic);
+    else copy_rows<VecT, false>(rows, n, src, src_stride_bytes, dst, dst_stride_bytes, vecs, log2_lpr);
 }
 
 // Widest power-of-two access (16, 8, 4 or 2 bytes) that keeps every row of both sides aligned.
@@ -387,8 +396,9 @@ int hbm_grid(int64_t rows, const RowGeom &g) {
 // (25 vectors occupy a 32-lane group) and keeps fewer bytes in flight; measured 3.8 -> 5.1 TB/s for
 // 400-byte rows, 4.0 -> 5.4 for 256-byte rows, 4.4 -> 5.7 for 512-byte rows.  Longer rows stay with
 // the two-rows-at-a-time copy (2,408-byte rows: 49.3 us grouped, 50.1 us flat inside the whole
-// step).  Copies over the host link stay grouped too: flat, they read 256-byte rows faster on
-// their own (55 vs 47 GB/s) but the pipelined step got slower (0.80-0.86 vs 0.69 ms).
+// step).  Copies over the host link stay grouped too: with 1 MiB of reads outstanding the grouped
+// copy is as fast or faster on its own (256-byte rows 54.6 vs 54.2 GB/s flat, 400-byte rows 43.8 vs
+// 42.6) and the flat one slows the pipelined step (0.69 -> 0.84 ms per "xlarge" mini-batch).
 // Returns ceil(2^64 / vecs), or 0 for the grouped copy.
 unsigned long long flat_magic(int64_t rows, const RowGeom &g) {
     if (g.vecs < 2 || g.vecs > kWave || rows * g.vecs >= (int64_t(1) << 32)) return 0;

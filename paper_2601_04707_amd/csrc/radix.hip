@@ -7,6 +7,10 @@
 //                    above 2,048 tiles; a single tile needs no reduce)
 //   k_radix_scatter  stable scatter: ballot match inside a wavefront, LDS counts across the four
 //                    wavefronts and across the rounds of a tile
+// Sorts of up to 256 tiles (half a million keys, a million with tiles of twice the size) need no scan
+// launch at all: the histogram table is laid out [tile][digit] and every workgroup of the scatter
+// adds up, per digit, the counts of all tiles (for the digit's base) and of the tiles before its own
+// - two launches per pass instead of four or five.
 #include <algorithm>
 
 #include "common.h"
@@ -17,21 +21,23 @@ namespace mqg {
 
 namespace {
 
+// tile_major: the table is [tile][digit] (for the scatter that adds the counts up itself), otherwise
+// [digit][tile] (so that one exclusive scan over the flat table gives every tile its bases)
 __global__ void __launch_bounds__(kBlock)
 k_radix_hist(const uint32_t *__restrict__ keys, int64_t n, const int64_t *__restrict__ n_dev, int shift,
-             int32_t *__restrict__ hist, int nblocks) {
+             int32_t *__restrict__ hist, int nblocks, int items, int tile_major) {
     __shared__ int h[256];
     if (n_dev && *n_dev < n) n = *n_dev;
     h[threadIdx.x] = 0;
     __syncthreads();
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-#pragma unroll
-    for (int r = 0; r < kRadixItems; ++r) {
+    const int64_t base = int64_t(blockIdx.x) * kBlock * items;
+    for (int r = 0; r < items; ++r) {
         int64_t i = base + r * kBlock + threadIdx.x;
         if (i < n) atomicAdd(&h[(keys[i] >> shift) & 255], 1);
     }
     __syncthreads();
-    hist[int64_t(threadIdx.x) * nblocks + blockIdx.x] = h[threadIdx.x];
+    if (tile_major) hist[int64_t(blockIdx.x) * 256 + threadIdx.x] = h[threadIdx.x];
+    else hist[int64_t(threadIdx.x) * nblocks + blockIdx.x] = h[threadIdx.x];
 }
 
 __global__ void __launch_bounds__(kBlock)
@@ -71,25 +77,42 @@ k_scan_apply(int32_t *__restrict__ data, int64_t n, const int32_t *__restrict__ 
     }
 }
 
+// SELF: `offsets` is the [tile][digit] table of counts and the bases are added up here; otherwise it
+// is the scanned [digit][tile] table.
+template <bool SELF>
 __global__ void __launch_bounds__(kBlock)
 k_radix_scatter(const uint32_t *__restrict__ keys_in, const int32_t *__restrict__ vals_in, int64_t n,
                 const int64_t *__restrict__ n_dev, int shift,
-                const int32_t *__restrict__ offsets, int nblocks, uint32_t *__restrict__ keys_out,
+                const int32_t *__restrict__ offsets, int nblocks, int items, uint32_t *__restrict__ keys_out,
                 int32_t *__restrict__ vals_out) {
     __shared__ int run[256];                         // keys of this digit placed in earlier rounds
     __shared__ int wcnt[kWavesPerBlock][256];        // per wavefront, this round
     __shared__ int gbase[256];                       // first output position of this workgroup per digit
+    __shared__ int scan_lds[kWavesPerBlock];
     const int tid = threadIdx.x;
     const int lane = lane_id();
     const int wave = tid >> 6;
     if (n_dev && *n_dev < n) n = *n_dev;
     run[tid] = 0;
-    gbase[tid] = offsets[int64_t(tid) * nblocks + blockIdx.x];
+    if (SELF) {
+        // digit tid: keys with a smaller digit in any tile, plus keys with this digit in earlier tiles
+        int all = 0, before = 0;
+        const int me = static_cast<int>(blockIdx.x);
+        for (int w = 0; w < nblocks; ++w) {
+            const int c = offsets[int64_t(w) * 256 + tid];
+            all += c;
+            before += w < me ? c : 0;
+        }
+        int total;
+        gbase[tid] = block_excl_scan<kWavesPerBlock>(all, &total, scan_lds) + before;
+    } else {
+        gbase[tid] = offsets[int64_t(tid) * nblocks + blockIdx.x];
+    }
 #pragma unroll
     for (int w = 0; w < kWavesPerBlock; ++w) wcnt[w][tid] = 0;
     __syncthreads();
-    const int64_t base = int64_t(blockIdx.x) * kRadixTile;
-    for (int r = 0; r < kRadixItems; ++r) {
+    const int64_t base = int64_t(blockIdx.x) * kBlock * items;
+    for (int r = 0; r < items; ++r) {
         const int64_t i = base + r * kBlock + tid;
         const bool valid = i < n;
         uint32_t key = 0;
@@ -150,21 +173,36 @@ int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipS
     return MQG_OK;
 }
 
+// Tiles of a sort: kRadixItems rounds of 256 keys, twice that when it brings the sort under the
+// number of tiles that the scatter can add up by itself.
+static int radix_items(int64_t n_cap) {
+    if (radix_blocks(n_cap) > kRadixSelfBlocks && ceil_div(n_cap, int64_t(kBlock) * 2 * kRadixItems) <= kRadixSelfBlocks) return 2 * kRadixItems;
+    return kRadixItems;
+}
+
 int radix_sort_pairs(mqg_ctx *ctx, const uint32_t *keys_in, const int32_t *vals_in, const RadixBufs &b,
                      int64_t n_cap, const int64_t *n_dev, int bits, hipStream_t s, int *result) {
-    const int nblocks = static_cast<int>(radix_blocks(n_cap));
-    const int64_t hist_len = radix_hist_len(n_cap);
+    const int items = radix_items(n_cap);
+    const int nblocks = static_cast<int>(std::max<int64_t>(1, ceil_div(n_cap, int64_t(kBlock) * items)));
+    const bool self = nblocks <= kRadixSelfBlocks;
+    const int64_t hist_len = int64_t(256) * nblocks;         // never more than radix_hist_len(n_cap)
     const uint32_t *kin = keys_in;
     const int32_t *vin = vals_in;
     int out = 0;
     *result = -1;
     for (int shift = 0; shift < bits; shift += 8) {
-        MQG_LAUNCH(ctx, "k_radix_hist", s, (k_radix_hist<<<nblocks, kBlock, 0, s>>>(kin, n_cap, n_dev, shift, b.hist, nblocks)));
-        int rc = device_scan(ctx, b.hist, hist_len, b.tile_sums, s);
-        if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_radix_scatter", s,
-                   (k_radix_scatter<<<nblocks, kBlock, 0, s>>>(kin, vin, n_cap, n_dev, shift, b.hist, nblocks, b.keys[out],
-                                                               b.vals[out])));
+        MQG_LAUNCH(ctx, "k_radix_hist", s, (k_radix_hist<<<nblocks, kBlock, 0, s>>>(kin, n_cap, n_dev, shift, b.hist, nblocks, items, self ? 1 : 0)));
+        if (self) {
+            MQG_LAUNCH(ctx, "k_radix_scatter", s,
+                       (k_radix_scatter<true><<<nblocks, kBlock, 0, s>>>(kin, vin, n_cap, n_dev, shift, b.hist, nblocks, items, b.keys[out],
+                                                                         b.vals[out])));
+        } else {
+            int rc = device_scan(ctx, b.hist, hist_len, b.tile_sums, s);
+            if (rc != MQG_OK) return rc;
+            MQG_LAUNCH(ctx, "k_radix_scatter", s,
+                       (k_radix_scatter<false><<<nblocks, kBlock, 0, s>>>(kin, vin, n_cap, n_dev, shift, b.hist, nblocks, items, b.keys[out],
+                                                                          b.vals[out])));
+        }
         kin = b.keys[out];
         vin = b.vals[out];
         *result = out;

@@ -291,7 +291,8 @@ def test_reserved_scratch_gives_the_same_results_and_no_later_allocation(mqg):
         ctx.set_sampling_priority(b["caches"][0])
         mqg.mqg_sample_blocks(ctx, g, seeds, fanouts, 9, b["blocks"])
         torch.cuda.synchronize()
-        out += [t.cpu().numpy().copy() for t in b["blocks"].indices] + [b["blocks"].sizes.cpu().numpy().copy()]
+        sz = b["blocks"].host_sizes()
+        out += [t[:sz[l][2]].cpu().numpy().copy() for l, t in enumerate(b["blocks"].indices)] + [np.array(sz)]
         ctx.set_sampling_priority(None)
         ctx.set_option(mqg.MQG_OPT_DEDUP_HASH, 1)
         mqg.mqg_sample_blocks(ctx, g, seeds, fanouts, 10, b["blocks"])
@@ -299,8 +300,9 @@ def test_reserved_scratch_gives_the_same_results_and_no_later_allocation(mqg):
         mqg.mqg_sage_mean_aggregate_backward(ctx, b["blocks"], 1, b["go"], b["gx"])
         mqg.mqg_sample_layerwise(ctx, g, seeds, [300, 300], 11, b["lw"])
         torch.cuda.synchronize()
-        out += [t.cpu().numpy().copy() for t in b["blocks"].indices] + [b["gx"].cpu().numpy().copy()]
-        out += [t.cpu().numpy().copy() for t in b["lw"].src_ids] + [b["lw"].sizes.cpu().numpy().copy()]
+        sz, lsz = b["blocks"].host_sizes(), b["lw"].host_sizes()
+        out += [t[:sz[l][2]].cpu().numpy().copy() for l, t in enumerate(b["blocks"].indices)] + [b["gx"][:sz[1][1]].cpu().numpy().copy()]
+        out += [t[:lsz[l][1]].cpu().numpy().copy() for l, t in enumerate(b["lw"].src_ids)] + [np.array(lsz)]
         results[name] = out
         if name == "ready":
             assert torch.cuda.mem_get_info()[0] == free0            # nothing was allocated on the way
