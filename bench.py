@@ -381,7 +381,9 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
             return None
         avg_s = kernels[kname][0] / kernels[kname][1] * 1e-3
         ach = bytes_per_launch / avg_s / 1e9
-        traffic, source = pmc_traffic(w.name, kname) if opts.scale == 1.0 else (None, None)
+        # the recorded counters belong to the workload as it is defined (its own cache fraction)
+        as_defined = opts.scale == 1.0 and cache_pct == w.cache_pct and opts.cache_policy == "top" and not opts.prioritise_cache
+        traffic, source = pmc_traffic(w.name, kname) if as_defined else (None, None)
         return {"kernel": kname, "bound": "hbm", "achieved": round(ach, 1), "peak": peak, "unit": "GB/s",
                 "frac": round(ach / peak, 4), "traffic": traffic, "traffic_source": source,
                 "avg_kernel_us": round(avg_s * 1e6, 2), "bytes_per_launch": int(bytes_per_launch)}

@@ -622,7 +622,10 @@ int mqg_weighted_aggregate_backward(mqg_ctx *ctx, const mqg_block *block, const 
  * peak_mem the measured peak device memory of one training epoch, margin the
  * paper's 5-10 % safety margin, mem_per_batch the device memory one queued
  * mini-batch holds.  Host arithmetic only (doubles for the times, integers
- * for the memory); no GPU is touched.  *cap_out (may be NULL) receives C,
+ * for the memory); no GPU is touched.  The rule presumes a pipeline that waits
+ * for its consumer: where preparation is bound by something a deeper queue
+ * cannot hide (here: the host link), the depth it gives is harmless but buys
+ * nothing beyond the first few.  *cap_out (may be NULL) receives C,
  * *queue_size_out receives Q.  MQG_ERR_INVALID_ARG for non-positive times or
  * sizes, a margin outside 0..100, or peak memory above the total.
  */
