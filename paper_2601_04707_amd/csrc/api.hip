@@ -54,6 +54,18 @@ void prof_begin(mqg_ctx *ctx, const char *name, hipStream_t s) {
     ctx->prof_recs.push_back(r);
 }
 
+// A record whose two events the launch itself fills in (hipExtLaunchKernelGGL): the kernel's own
+// start and end, without the latency of separate event packets around it.
+void prof_begin_ext(mqg_ctx *ctx, const char *name, hipEvent_t *start, hipEvent_t *stop) {
+    ProfRec r;
+    r.name_id = prof_name_id(ctx, name);
+    r.start = take_event(ctx);
+    r.stop = take_event(ctx);
+    ctx->prof_recs.push_back(r);
+    *start = r.start;
+    *stop = r.stop;
+}
+
 void prof_end(mqg_ctx *ctx, hipStream_t s) {
     (void)hipEventRecord(ctx->prof_recs.back().stop, s);
 }

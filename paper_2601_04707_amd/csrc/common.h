@@ -126,6 +126,7 @@ int fail(mqg_ctx *ctx, int code, const std::string &msg);
 int prof_name_id(mqg_ctx *ctx, const char *name);
 void prof_begin(mqg_ctx *ctx, const char *name, hipStream_t s);
 void prof_end(mqg_ctx *ctx, hipStream_t s);
+void prof_begin_ext(mqg_ctx *ctx, const char *name, hipEvent_t *start, hipEvent_t *stop);
 
 // Launch wrapper: optional event bracketing, error check.  Usage:
 //   MQG_LAUNCH(ctx, "k_name", stream, (k_name<<<grid, block, 0, stream>>>(args...)));

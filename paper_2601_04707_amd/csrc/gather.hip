@@ -11,6 +11,8 @@
 //   k_gather_rows<.,1> misses: feature matrix -> HBM output (same code, separate symbol so that
 //                     profiles tell the HBM-bound from the link-bound launch)
 //   k_gather_direct   no cache: every row straight from the feature matrix
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 #include <mutex>
 
@@ -431,6 +433,16 @@ int launch_rows(mqg_ctx *ctx, const char *name, const int2 *list, const unsigned
     if (magic) grid = flat_grid(cap, g);
     const char *sp = static_cast<const char *>(src);
     char *dp = static_cast<char *>(dst);
+    if (ctx->profile && g.vb == 16) {
+        // the two kernels the rooflines are quoted on: timed by the dispatch's own start and end
+        hipEvent_t e0, e1;
+        prof_begin_ext(ctx, name, &e0, &e1);
+        hipExtLaunchKernelGGL((k_gather_rows<uint4, MISS>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, list, count, sp, src_stride_bytes, dp,
+                              dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters, magic);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string(name) + ": " + hipGetErrorString(e));
+        return MQG_OK;
+    }
     switch (g.vb) {
         case 16: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint4, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters, magic))); break;
         case 8: MQG_LAUNCH(ctx, name, s, (k_gather_rows<uint2, MISS><<<grid, kBlock, 0, s>>>(list, count, sp, src_stride_bytes, dp, dst_stride_bytes, g.vecs, g.log2_lpr, stats, counters, magic))); break;

@@ -8,7 +8,7 @@ namespace mqg {
 constexpr int kRadixItems = 8;                       // rounds per tile
 constexpr int kRadixTile = kBlock * kRadixItems;     // keys per workgroup
 constexpr int kScanTile = 1024;                      // elements per workgroup in the generic scan
-constexpr int kRadixSelfBlocks = 256;                // up to this many tiles the scatter adds the tile counts up itself
+constexpr int kRadixSelfBlocks = 32;                 // up to this many tiles the scatter adds the tile counts up itself
 
 int64_t radix_blocks(int64_t n_cap);
 int64_t radix_hist_len(int64_t n_cap);

@@ -7,10 +7,11 @@
 //                    above 2,048 tiles; a single tile needs no reduce)
 //   k_radix_scatter  stable scatter: ballot match inside a wavefront, LDS counts across the four
 //                    wavefronts and across the rounds of a tile
-// Sorts of up to 256 tiles (half a million keys, a million with tiles of twice the size) need no scan
-// launch at all: the histogram table is laid out [tile][digit] and every workgroup of the scatter
-// adds up, per digit, the counts of all tiles (for the digit's base) and of the tiles before its own
-// - two launches per pass instead of four or five.
+// Sorts of up to 32 tiles (65,536 keys: the inner blocks of a mini-batch) need no scan launch at
+// all: the histogram table is laid out [tile][digit] and every workgroup of the scatter adds up, per
+// digit, the counts of all tiles (for the digit's base) and of the tiles before its own - two
+// launches per pass instead of four.  (With 138 tiles the adding-up made the scatter 25 us instead of
+// 8: more than the two scan launches it saved.)
 #include <algorithm>
 
 #include "common.h"
@@ -98,6 +99,7 @@ k_radix_scatter(const uint32_t *__restrict__ keys_in, const int32_t *__restrict_
         // digit tid: keys with a smaller digit in any tile, plus keys with this digit in earlier tiles
         int all = 0, before = 0;
         const int me = static_cast<int>(blockIdx.x);
+#pragma unroll 8
         for (int w = 0; w < nblocks; ++w) {
             const int c = offsets[int64_t(w) * 256 + tid];
             all += c;
@@ -173,12 +175,7 @@ int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipS
     return MQG_OK;
 }
 
-// Tiles of a sort: kRadixItems rounds of 256 keys, twice that when it brings the sort under the
-// number of tiles that the scatter can add up by itself.
-static int radix_items(int64_t n_cap) {
-    if (radix_blocks(n_cap) > kRadixSelfBlocks && ceil_div(n_cap, int64_t(kBlock) * 2 * kRadixItems) <= kRadixSelfBlocks) return 2 * kRadixItems;
-    return kRadixItems;
-}
+static int radix_items(int64_t) { return kRadixItems; }
 
 int radix_sort_pairs(mqg_ctx *ctx, const uint32_t *keys_in, const int32_t *vals_in, const RadixBufs &b,
                      int64_t n_cap, const int64_t *n_dev, int bits, hipStream_t s, int *result) {
