@@ -563,6 +563,23 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
     bwd_kernel_us = bk.get("k_mean_aggregate_backward", [0.0, 0])[0] / KB * 1e3
     # reduction kernel: every edge reads one gradient row, every source row of every block is written once
     bwd_bytes = (edges + int(sizes_host[:, :, 1].sum())) / K * row_bytes
+    # the same chain without the per-kernel events: what one mini-batch's backward takes on its stream
+    bwd_wall = 0.0
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(W, W + KB):
+        step(i)
+        torch.cuda.synchronize()
+        j = i % nfl
+        with torch.cuda.stream(streams[j]):
+            ev0.record()
+            gcur = g_top
+            for l in range(L - 1, -1, -1):
+                mqg.mqg_sage_mean_aggregate_backward(ctxs[j], blks[j], l, gcur, gx[l], stream=streams[j])
+                gcur = gx[l]
+            ev1.record()
+        torch.cuda.synchronize()
+        bwd_wall += ev0.elapsed_time(ev1)
+    bwd_wall_ms = bwd_wall / KB
     del gx, g_top, ew, sw
 
     # ---------------------------------------------------------------- layer-wise (LADIES) mini-batches
@@ -662,11 +679,13 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                    "sampling": "cached neighbours first" if opts.prioritise_cache else "uniform",
                    "launch": "one recorded HIP graph per in-flight slot" if use_graph else "eager"},
         "gather_kernel_GBps": round(gather_bytes / K / max(gather_us, 1e-9) * 1e-3, 2),
-        "backward_aggregation": {"us_per_step": round(bwd_us, 1), "launches_per_step": round(bwd_launches, 1),
+        "backward_aggregation": {"ms_per_batch": round(bwd_wall_ms, 4), "us_per_step": round(bwd_us, 1), "launches_per_step": round(bwd_launches, 1),
                                  "reduction_kernel_us_per_step": round(bwd_kernel_us, 1),
                                  "reduction_kernel_GBps": round(bwd_bytes / max(bwd_kernel_us, 1e-9) * 1e-3, 1),
                                  "kernel_us_per_step": {k: round(v[0] / KB * 1e3, 1) for k, v in sorted(bk.items()) if v[1]},
-                                 "note": "all blocks of a mini-batch, one at a time; not part of a step"},
+                                 "note": "all blocks of a mini-batch, one at a time; not part of a step.  ms_per_batch: the chain timed as a "
+                                         "whole on its stream; us_per_step and kernel_us_per_step: the sum of its kernels, each "
+                                         "between two events of its own"},
         "gcn_weighted_aggregation": {"weights_kernel_us_per_step": round(wgt_us, 1), "sum_kernel_us_per_step": round(wagg_us, 1),
                                      "mean_aggregate_us_per_step": round(agg_us, 1),
                                      "note": "Eq. 1-3 estimator on the same blocks (weights of every block, then weighted "

@@ -190,12 +190,17 @@ typedef enum {
     MQG_OPT_HEAVY_DEGREE = 4,            /* destinations with more neighbours than this (>= 64,
                                             default 2048) are sampled by a whole workgroup
                                             instead of one wavefront; results do not change   */
-    MQG_OPT_DEDUP_HASH = 5               /* value != 0: frontier dedup and relabel through a hash
+    MQG_OPT_DEDUP_HASH = 5,              /* value != 0: frontier dedup and relabel through a hash
                                             table and a sort (memory proportional to the
                                             mini-batch) instead of the node-indexed bitmap and
                                             position table (4.2 bytes per graph node); same
                                             blocks, more kernel launches.  The first use
                                             allocates the table (synchronous)                */
+    MQG_OPT_LAYERWISE_CANDIDATES = 6     /* how mqg_sample_layerwise finds the candidates of a
+                                            layer: 0 = by graph size (default), 1 = a key slot per
+                                            node, 2 = a list read off the masses, 3 = a list from
+                                            bits set slot by slot; same blocks (test of the paths
+                                            that only large graphs take)                      */
 } mqg_option;
 int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value);
 

@@ -333,14 +333,6 @@ k_col_ptr(const uint32_t *__restrict__ sorted_src, const int64_t *__restrict__ s
     }
 }
 
-// payload = the edge's own position (the by-source order then gives a permutation of the edges)
-__global__ void __launch_bounds__(kBlock)
-k_edge_iota(const int64_t *__restrict__ sizes, int32_t *__restrict__ edge_id) {
-    const int64_t nnz = sizes[2];
-    const int64_t stride = int64_t(gridDim.x) * kBlock;
-    for (int64_t e = int64_t(blockIdx.x) * kBlock + threadIdx.x; e < nnz; e += stride) edge_id[e] = static_cast<int32_t>(e);
-}
-
 // destination row and weight of every edge in the by-source order
 __global__ void __launch_bounds__(kBlock)
 k_permute_edges(const int32_t *__restrict__ perm, const int32_t *__restrict__ indptr, const float *__restrict__ edge_w,
@@ -458,26 +450,22 @@ int run_aggregate_backward(mqg_ctx *ctx, const mqg_block *b, const float *edge_w
     if (rc0 != MQG_OK) return rc0;
 
     const int egrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(nnz_cap, kBlock)), 8192));
-    if (edge_w) {
-        MQG_LAUNCH(ctx, "k_edge_iota", s, (k_edge_iota<<<egrid, kBlock, 0, s>>>(b->sizes, ctx->bwd_dst_row)));
-    } else {
-        MQG_LAUNCH(ctx, "k_edge_dst_rows", s, (k_edge_dst_rows<<<egrid, kBlock, 0, s>>>(b->indptr, b->sizes, ctx->bwd_dst_row)));
-    }
-    int bits = 0;
-    while (bits < 32 && (static_cast<uint64_t>(std::max<int64_t>(src_cap, 1) - 1) >> bits) != 0) bits += 8;
+    // Edges by source, stably.  An edge carries its destination row along, or (weighted) its own
+    // position, which the sort's first pass makes itself - at least one pass, for that.
+    if (!edge_w) MQG_LAUNCH(ctx, "k_edge_dst_rows", s, (k_edge_dst_rows<<<egrid, kBlock, 0, s>>>(b->indptr, b->sizes, ctx->bwd_dst_row)));
+    const int bits = std::max(1, radix_key_bits(static_cast<uint64_t>(std::max<int64_t>(src_cap, 1) - 1)));
     int which = -1;
-    int rc = radix_sort_pairs(ctx, reinterpret_cast<const uint32_t *>(b->indices), ctx->bwd_dst_row, ctx->bwd, nnz_cap,
+    int rc = radix_sort_pairs(ctx, reinterpret_cast<const uint32_t *>(b->indices), edge_w ? nullptr : ctx->bwd_dst_row, ctx->bwd, nnz_cap,
                               &b->sizes[2], bits, s, &which);
     if (rc != MQG_OK) return rc;
-    const uint32_t *sorted_src = which < 0 ? reinterpret_cast<const uint32_t *>(b->indices) : ctx->bwd.keys[which];
-    const int32_t *sorted_dst = which < 0 ? ctx->bwd_dst_row : ctx->bwd.vals[which];
+    const uint32_t *sorted_src = ctx->bwd.keys[which];
+    const int32_t *sorted_dst = ctx->bwd.vals[which];
     const int cgrid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(src_cap + 1, kBlock)), 8192));
     MQG_LAUNCH(ctx, "k_col_ptr", s, (k_col_ptr<<<cgrid, kBlock, 0, s>>>(sorted_src, b->sizes, ctx->bwd_col_ptr)));
 
     if (edge_w) {
-        // the sort's payload was the edge position: turn it into (destination row, weight); the
-        // unsorted payload buffer is free again by now unless the sort moved nothing
-        int32_t *dst_sorted = which < 0 ? ctx->bwd.vals[0] : ctx->bwd_dst_row;
+        // the sort's payload was the edge position: turn it into (destination row, weight)
+        int32_t *dst_sorted = ctx->bwd_dst_row;
         MQG_LAUNCH(ctx, "k_permute_edges", s,
                    (k_permute_edges<<<egrid, kBlock, 0, s>>>(sorted_dst, b->indptr, edge_w, b->sizes, dst_sorted, ctx->bwd_w_sorted)));
         WeightedBackwardRows rows{ctx->bwd_col_ptr, dst_sorted, ctx->bwd_w_sorted, self_w, b->sizes};

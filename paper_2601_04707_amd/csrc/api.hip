@@ -236,6 +236,10 @@ int mqg_ctx_set_option(mqg_ctx *ctx, int32_t option, int64_t value) {
             if (value < 1024 || value > (int64_t(1) << 30)) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: MQG_OPT_MISS_INFLIGHT_BYTES outside 1 KiB..1 GiB");
             ctx->miss_inflight_bytes = value;
             return MQG_OK;
+        case MQG_OPT_LAYERWISE_CANDIDATES:
+            if (value < 0 || value > 3) return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: MQG_OPT_LAYERWISE_CANDIDATES outside 0..3");
+            ctx->layerwise_candidates = static_cast<int>(value);
+            return MQG_OK;
         default: return fail(ctx, MQG_ERR_INVALID_ARG, "mqg_ctx_set_option: unknown option");
     }
 }

@@ -407,8 +407,7 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         if (e == hipSuccess) e = hipStreamSynchronize(s);
         if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_build_cache: ") + hipGetErrorString(e));
         MQG_LAUNCH(ctx, "k_sort_keys", s, (k_sort_keys<<<ngrid, kBlock, 0, s>>>(keys_a, vals_a, n, max_deg)));
-        int bits = 0;
-        while (bits < 32 && (max_deg >> bits) != 0) bits += 8;
+        const int bits = radix_key_bits(max_deg);
         int which = -1;
         int rc0 = radix_sort_pairs(ctx, keys_a, vals_a, rb, n, nullptr, bits, s, &which);
         if (rc0 != MQG_OK) return rc0;
@@ -445,12 +444,13 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         const int32_t *in_ptr = nullptr, *in_src = nullptr;
         if (!printed && !plan->graph_symmetric && plan->num_steps > 0) {
             const int64_t ne = g->num_edges;
+            const int bits = radix_key_bits(static_cast<uint64_t>(n - 1));
             uint32_t *cols;
             int32_t *rows_of, *ptr_t;
             RadixBufs rb;
             bool ok = tmp.alloc(&cols, ne) && tmp.alloc(&rows_of, ne) && tmp.alloc(&ptr_t, n + 1) && tmp.alloc(&rb.keys[0], ne) &&
                       tmp.alloc(&rb.keys[1], ne) && tmp.alloc(&rb.vals[0], ne) && tmp.alloc(&rb.vals[1], ne) &&
-                      tmp.alloc(&rb.hist, radix_hist_len(ne)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles(ne));
+                      tmp.alloc(&rb.hist, radix_hist_len(ne, bits)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles(ne, bits));
             if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed (transposed adjacency)");
             if (ne > 0) {
                 if (p64 && i64)
@@ -462,8 +462,6 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
                 else
                     MQG_LAUNCH(ctx, "k_edge_pairs", s, (k_edge_pairs<int32_t, int32_t><<<ngrid, kBlock, 0, s>>>(static_cast<const int32_t *>(g->row_ptr), static_cast<const int32_t *>(g->col_idx), n, cols, rows_of)));
             }
-            int bits = 0;
-            while (bits < 32 && (static_cast<uint64_t>(n - 1) >> bits) != 0) bits += 8;
             int which = -1;
             int rc0 = radix_sort_pairs(ctx, cols, rows_of, rb, ne, nullptr, bits, s, &which);
             if (rc0 != MQG_OK) return rc0;

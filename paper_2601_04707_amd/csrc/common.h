@@ -38,10 +38,11 @@ struct LayerwiseScratch {
     int32_t *cand = nullptr;             // [num_nodes] candidates, ascending
     uint64_t *key64 = nullptr;           // [num_nodes] race keys (double bit patterns)
     unsigned long long *sel_state = nullptr;   // [18] radix select: prefix and wanted count per pass
-    int32_t *sel_hist = nullptr;         // [8 * 256]
+    int32_t *sel_hist = nullptr;         // [passes][digits] counts of the radix select
     int32_t *chunk_offs = nullptr;       // [rows_cap * 16 + 1] edges per (row, chunk), then their scan
+    int32_t *chunk_scan = nullptr;       // the scan of a small chunk_offs table (one-launch scan, out of place)
     double *chunk_sum = nullptr;         // [rows_cap * 16] raw weight sums per (row, chunk)
-    int32_t *word_offs = nullptr;        // [bitmap_words + 1]
+    int32_t *word_offs = nullptr;        // [bitmap_words + 1] set bits per tile of the bitmap
     int32_t *scan_tiles = nullptr;
     double *q_part = nullptr;            // per-workgroup partial sums of q
     int64_t *counters = nullptr;         // [0]: number of candidates
@@ -106,6 +107,7 @@ struct mqg_ctx {
 
     // options
     bool force_slow_select = false;
+    int layerwise_candidates = 0;        // MQG_OPT_LAYERWISE_CANDIDATES
     bool profile = false;
     int64_t miss_inflight_bytes = 1024 * 1024;  // read bytes the host-link gather keeps outstanding
     int heavy_degree = 2048;             // rows longer than this get a whole workgroup in sampling

@@ -213,8 +213,7 @@ int hash_dedup_block(mqg_ctx *ctx, const int32_t *nbr, int64_t need_nnz, int64_t
     MQG_LAUNCH(ctx, "k_zero_u64", s, (k_zero_u64<<<1, 64, 0, s>>>(ctx->hash_new_count)));
     MQG_LAUNCH(ctx, "k_hash_put_nbr", s,
                (k_hash_put_nbr<<<egrid, kBlock, 0, s>>>(nbr, sizes, ctx->hash_table, mask, ctx->hash_new_keys, ctx->hash_new_count)));
-    int bits = 0;
-    while (bits < 32 && (static_cast<uint64_t>(std::max<int64_t>(num_nodes, 1) - 1) >> bits) != 0) bits += 8;
+    const int bits = radix_key_bits(static_cast<uint64_t>(std::max<int64_t>(num_nodes, 1) - 1));
     int which = -1;
     int rc = radix_sort_pairs(ctx, ctx->hash_new_keys, reinterpret_cast<const int32_t *>(ctx->hash_new_keys), ctx->hash_sort,
                               std::min<int64_t>(std::max<int64_t>(need_nnz, 1), std::max<int64_t>(ctx->max_nnz, 1)), reinterpret_cast<const int64_t *>(ctx->hash_new_count), bits, s, &which);

@@ -9,18 +9,22 @@
 //                    q_i = mass[i] / (deg_i + 1) is 2^40 times the squared column norm of Eq. 7.
 //                    Touched nodes are marked in the context's node bitmap - slot by slot on graphs
 //                    above kMassScanNodes nodes, otherwise by k_lw_mass_bits from the masses.
-//   bitmap -> list   the candidates (Eq. 6), ascending (word popcounts, scan, emit)
+//   bitmap -> list   the candidates (Eq. 6), ascending: set bits counted per tile (by k_lw_mass_bits
+//                    itself, else k_lw_tile_counts), then k_lw_emit, whose workgroups add up the
+//                    counts of the tiles before their own
 //   k_lw_keys        exponential race: key = ticket * (deg_i + 1) / mass[i] in doubles (the "flat"
 //                    variants, Eq. 10, draw in proportion to sqrt(q_i): ticket^2 in place of ticket), ticket from
 //                    exp_ticket64; partial sums of q per workgroup, added up in a fixed order
-//   k_lw_select      radix select of the s-th smallest 64-bit key pattern, most significant byte
-//                    first: one launch per byte, every workgroup derives the prefix found so far
-//                    from the previous launch's 256-bin histogram
-//   k_lw_mark        keys below the threshold are marked in the bitmap, keys equal to it in
-//                    ascending id order as far as needed (all candidates if there are at most s)
+//   k_lw_select      radix select of the s-th smallest 64-bit key pattern, most significant digit
+//                    first (12 bits, then four times 13): one launch per digit, every workgroup
+//                    derives the prefix found so far from the previous launch's histogram
+//   k_lw_mark        derives the threshold from the last histogram; keys below it are marked in the
+//                    bitmap, keys equal to it in ascending id order as far as needed (all
+//                    candidates if there are at most s)
 //   bitmap -> list   the drawn nodes ascending = the block's sources, positions into local_of[]
 //   k_lw_count/fill  row v lists the drawn nodes among v and its adjacency row (self edge first,
-//                    then slot order) with weight P_vi / (s p_i), optionally divided by the row sum
+//                    then slot order) with weight P_vi / (s p_i), optionally divided by the row sum;
+//                    k_lw_fill also writes indptr and the block's sizes
 // A row is shared by kRowChunks wavefronts, each with a contiguous range of adjacency slots, so
 // that a hub does not become a kernel's tail; counts and partial weight sums are kept per (row,
 // chunk) and one scan over all of them gives every wavefront its first edge position.
@@ -28,6 +32,7 @@
 //                    the order of the race and their debiased coefficients, three scans in one workgroup
 //   k_lw_reset       masses and positions back to their idle values
 #include <algorithm>
+#include <type_traits>
 
 #include "common.h"
 #include "device_utils.h"
@@ -40,6 +45,7 @@ namespace {
 constexpr uint64_t kGolden = 0x9E3779B97F4A7C15ULL;
 constexpr int kLayerwiseTag = 64;
 constexpr int64_t kMassScanNodes = int64_t(8) << 20;   // up to here the candidates are read off the masses
+constexpr int64_t kDenseNodes = int64_t(1) << 20;      // up to here every node has a key slot: no candidate list
 
 uint64_t host_mix64(uint64_t z) {
     z ^= z >> 30;
@@ -57,12 +63,14 @@ __device__ __forceinline__ void set_bit(uint32_t *bitmap, uint32_t i) {
         (void)__hip_atomic_fetch_or(w, bit, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// the caller's seeds, checked: an id outside the graph is replaced by node 0 and flagged
+// the caller's seeds, checked: an id outside the graph is replaced by node 0 and flagged; also clears
+// the histograms of the radix select
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_seeds(const IdxT *__restrict__ seeds, int64_t n, int64_t num_nodes, IdxT *__restrict__ dst, int64_t *sizes,
-           int32_t *__restrict__ flags) {
+           int32_t *__restrict__ flags, int32_t *__restrict__ sel_hist, int hist_len) {
     const int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    for (int64_t k = t; k < hist_len; k += int64_t(gridDim.x) * kBlock) sel_hist[k] = 0;    // for the first block's select
     if (t == 0) sizes[0] = n;
     if (t >= n) return;
     IdxT v = seeds[t];
@@ -85,8 +93,10 @@ __device__ __forceinline__ void chunk_range(int64_t d, int c, int64_t *begin, in
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_mass(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
-          const int64_t *__restrict__ sizes, unsigned long long *__restrict__ mass, uint32_t *__restrict__ bitmap) {
+          const int64_t *__restrict__ sizes, unsigned long long *__restrict__ mass, uint32_t *__restrict__ bitmap,
+          int64_t *__restrict__ zero_me) {
     const int lane = lane_id();
+    if (zero_me && blockIdx.x == 0 && threadIdx.x == 0) *zero_me = 0;     // the candidate count k_lw_keys adds up
     const int64_t n = sizes[0] * kRowChunks;
     const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
@@ -111,50 +121,136 @@ k_lw_mass(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, co
     }
 }
 
+// Bitmap -> ascending list, two launches: the set bits of every tile are counted, then every tile's
+// workgroup adds up the counts of the tiles before its own and writes its ids.  A tile is
+// kBlock * WPT words (WPT = 1 up to 32 M nodes, ids staged through LDS and written coalesced;
+// otherwise 4, one 16-byte load per thread, ids written from the bit loop: those bitmaps are sparse).
+constexpr int kMassTileNodes = kBlock * 32;          // nodes behind one tile of kBlock words
+
 // The touched nodes from the masses themselves (bit i = mass[i] != 0), for graphs small enough that
-// reading every mass costs less than marking a bit per adjacency slot in k_lw_mass.  One lane per
-// node; n_pad is a multiple of 64, bits past the last node are zero.
+// reading every mass costs less than marking a bit per adjacency slot in k_lw_mass; the same launch
+// counts the tile (WPT = 1).  In round r thread t looks at node tile * 8192 + r * 256 + t, so the
+// ballot of a wavefront is the word pair r * 8 + 2 * wave of the tile.
 __global__ void __launch_bounds__(kBlock)
-k_lw_mass_bits(const unsigned long long *__restrict__ mass, int64_t n, uint32_t *__restrict__ bitmap) {
-    const int64_t i = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-    const uint64_t m = ballot64(i < n && mass[i] != 0);
-    if (lane_id() == 0) {
-        bitmap[i >> 5] = static_cast<uint32_t>(m);
-        bitmap[(i >> 5) + 1] = static_cast<uint32_t>(m >> 32);
+k_lw_mass_bits(const unsigned long long *__restrict__ mass, int64_t n, uint32_t *__restrict__ bitmap,
+               int32_t *__restrict__ tile_sums) {
+    __shared__ unsigned long long pairs[kBlock / 2];
+    __shared__ int lds[kWavesPerBlock];
+    const int tid = threadIdx.x;
+    const int wave = tid >> 6;
+    const int64_t base = int64_t(blockIdx.x) * kMassTileNodes + tid;
+    unsigned long long v[32];
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        const int64_t i = base + r * kBlock;
+        v[r] = i < n ? mass[i] : 0ull;
+    }
+    int cnt = 0;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) {
+        const uint64_t m = ballot64(v[r] != 0);
+        cnt += popc64(m);
+        if (lane_id() == 0) pairs[r * kWavesPerBlock + wave] = m;
+    }
+    if (lane_id() == 0) lds[wave] = cnt;
+    __syncthreads();
+    bitmap[int64_t(blockIdx.x) * kBlock + tid] = reinterpret_cast<const uint32_t *>(pairs)[tid];
+    if (tid == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
+        tile_sums[blockIdx.x] = t;
     }
 }
 
-// offs[w] = popcount of word w; offs[words] = 0 (the scan turns it into the total)
+template <int WPT>
 __global__ void __launch_bounds__(kBlock)
-k_lw_word_counts(const uint32_t *__restrict__ bitmap, int64_t words, int32_t *__restrict__ offs) {
-    const int64_t w = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-    if (w < words) offs[w] = __popc(bitmap[w]);
-    if (w == words) offs[w] = 0;
+k_lw_tile_counts(const uint32_t *__restrict__ bitmap, int32_t *__restrict__ tile_sums) {
+    __shared__ int lds[kWavesPerBlock];
+    const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * WPT;
+    int c;
+    if (WPT == 4) {
+        const uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
+        c = __popc(w.x) + __popc(w.y) + __popc(w.z) + __popc(w.w);
+    } else {
+        c = __popc(bitmap[w0]);
+    }
+    const int s = wave_sum(c);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int t = 0;
+#pragma unroll
+        for (int k = 0; k < kWavesPerBlock; ++k) t += lds[k];
+        tile_sums[blockIdx.x] = t;
+    }
 }
 
-// ids of the set bits, ascending, into out[0..total); the words are cleared; total to count_a/b
-template <typename OutT>
+// ids of the set bits, ascending, into out[0..total); the words are cleared; total to count_a/b.
+// scanned: tile_vals holds the exclusive scan of the tile counts, otherwise the counts themselves.
+template <typename OutT, int WPT>
 __global__ void __launch_bounds__(kBlock)
-k_lw_emit(uint32_t *__restrict__ bitmap, int64_t words, const int32_t *__restrict__ offs, OutT *__restrict__ out,
+k_lw_emit(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_vals, int scanned, OutT *__restrict__ out,
           int32_t *__restrict__ local_of, int64_t *count_a, int64_t *count_b) {
-    const int64_t w = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-    if (w == 0) {
-        const int64_t total = offs[words];
-        if (count_a) *count_a = total;
-        if (count_b) *count_b = total;
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ int32_t staged[WPT == 1 ? kBlock * 32 : 1];   // every id of the tile, ascending
+    const int tile_base = scanned ? tile_vals[blockIdx.x] : tiles_before(tile_vals, lds);
+    const int64_t w0 = (int64_t(blockIdx.x) * kBlock + threadIdx.x) * WPT;
+    uint32_t words[WPT];
+    if constexpr (WPT == 4) {
+        const uint4 w = *reinterpret_cast<const uint4 *>(bitmap + w0);
+        words[0] = w.x;
+        words[1] = w.y;
+        words[2] = w.z;
+        words[3] = w.w;
+    } else {
+        words[0] = bitmap[w0];
     }
-    if (w >= words) return;
-    uint32_t bits = bitmap[w];
-    if (!bits) return;
-    bitmap[w] = 0;
-    int32_t o = offs[w];
-    const int64_t v0 = w * 32;
-    while (bits) {
-        const int b = __ffs(bits) - 1;
-        bits &= bits - 1;
-        out[o] = static_cast<OutT>(v0 + b);
-        if (local_of) local_of[v0 + b] = o;
-        ++o;
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < WPT; ++q) c += __popc(words[q]);
+    int total;
+    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+    if (blockIdx.x == gridDim.x - 1 && threadIdx.x == 0) {
+        const int64_t all = int64_t(tile_base) + total;
+        if (count_a) *count_a = all;
+        if (count_b) *count_b = all;
+    }
+    if (total == 0) return;                                // workgroup-uniform
+    if constexpr (WPT == 1) {
+        if (c) {
+            bitmap[w0] = 0;
+            const int32_t v0 = static_cast<int32_t>(w0 * 32);
+            uint32_t bits = words[0];
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                staged[ex++] = v0 + b;
+            }
+        }
+        __syncthreads();
+        for (int k = threadIdx.x; k < total; k += kBlock) {
+            const int32_t v = staged[k];
+            out[tile_base + k] = static_cast<OutT>(v);
+            if (local_of) local_of[v] = tile_base + k;
+        }
+    } else {
+        if (c == 0) return;
+        int32_t pos = tile_base + ex;
+#pragma unroll
+        for (int q = 0; q < WPT; ++q) {
+            uint32_t bits = words[q];
+            if (!bits) continue;
+            bitmap[w0 + q] = 0;
+            while (bits) {
+                const int b = __ffs(bits) - 1;
+                bits &= bits - 1;
+                const int64_t v = (w0 + q) * 32 + b;
+                out[pos] = static_cast<OutT>(v);
+                if (local_of) local_of[v] = pos;
+                ++pos;
+            }
+        }
     }
 }
 
@@ -170,40 +266,77 @@ __device__ __forceinline__ double lw_measure(double m, double deg1, int flat) {
     return flat ? sqrt(q) : q;
 }
 
-// race keys of the candidates and the per-workgroup partial sums of q (a fixed launch shape, so the
-// sums are the same from run to run)
+// Radix select of the s-th smallest 64-bit key pattern: kSelPasses counting passes, most
+// significant digit first - the top 12 bits (sign and exponent of a double), then 13 bits at a time.
+constexpr int kSelPasses = 5;
+constexpr int kSelBins = 8192;
+constexpr int kSelHistLen = kSelPasses * kSelBins;
+__host__ __device__ constexpr int sel_shift(int pass) { return 52 - 13 * pass; }
+
+// Race keys of the candidates and the per-workgroup partial sums of q (a fixed launch shape, so the
+// sums are the same from run to run); the keys' leading 12 bits are counted into hist[0..4096) - the
+// first pass of the radix select.  Candidates: cand[0..n) if given, otherwise the nodes 0..n-1
+// themselves, of which those with no mass are none (key = all ones, not counted); their number is
+// added to *count_out then.  n = *n_dev if given, else n_fixed.  hist must be clear.
+constexpr uint64_t kNoKey = ~uint64_t(0);
 template <typename PtrT>
 __global__ void __launch_bounds__(kBlock)
-k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
+k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_dev, int64_t n_fixed,
           const unsigned long long *__restrict__ mass, uint64_t tag_hash, int flat, uint64_t *__restrict__ key64,
-          double *__restrict__ q_part) {
+          double *__restrict__ q_part, int32_t *__restrict__ hist, int64_t *__restrict__ count_out,
+          unsigned long long *__restrict__ state, int64_t layer_size) {
     __shared__ double lds[kWavesPerBlock];
-    const int64_t n = *n_cand;
+    __shared__ int cnt_lds[kWavesPerBlock];
+    __shared__ int h[4096];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {             // the select's state before its first pass
+        state[0] = 0;
+        state[1] = static_cast<unsigned long long>(layer_size);
+    }
+    const int64_t n = n_dev ? *n_dev : n_fixed;
     const int64_t stride = int64_t(gridDim.x) * kBlock;
+#pragma unroll
+    for (int q = 0; q < 4096 / kBlock; ++q) h[q * kBlock + threadIdx.x] = 0;
+    __syncthreads();
     double q = 0.0;
+    int cnt = 0;
     for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
         const int64_t i = cand ? cand[c] : c;
+        const unsigned long long mi = mass[i];
+        if (mi == 0) {
+            key64[c] = kNoKey;
+            continue;
+        }
         const double deg1 = static_cast<double>(static_cast<int64_t>(row_ptr[i + 1]) - static_cast<int64_t>(row_ptr[i]) + 1);
-        const double m = static_cast<double>(mass[i]);
+        const double m = static_cast<double>(mi);
         const double ticket = static_cast<double>(exp_ticket64(mix64(mix64(tag_hash ^ static_cast<uint64_t>(i)))));
-        const double key = lw_race_key(ticket, deg1, m, flat);
-        key64[c] = static_cast<uint64_t>(__double_as_longlong(key));
+        const uint64_t key = static_cast<uint64_t>(__double_as_longlong(lw_race_key(ticket, deg1, m, flat)));
+        key64[c] = key;
+        atomicAdd(&h[key >> 52], 1);
         q += lw_measure(m, deg1, flat);
+        ++cnt;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) q += __shfl_xor(q, off, 64);
-    if (lane_id() == 0) lds[threadIdx.x >> 6] = q;
+    cnt = wave_sum(cnt);
+    if (lane_id() == 0) {
+        lds[threadIdx.x >> 6] = q;
+        cnt_lds[threadIdx.x >> 6] = cnt;
+    }
     __syncthreads();
-    if (threadIdx.x == 0) q_part[blockIdx.x] = ((lds[0] + lds[1]) + lds[2]) + lds[3];
+    if (threadIdx.x == 0) {
+        q_part[blockIdx.x] = ((lds[0] + lds[1]) + lds[2]) + lds[3];
+        const int total = cnt_lds[0] + cnt_lds[1] + cnt_lds[2] + cnt_lds[3];
+        if (count_out && total) atomicAdd(reinterpret_cast<unsigned long long *>(count_out), static_cast<unsigned long long>(total));
+    }
+#pragma unroll
+    for (int q4 = 0; q4 < 4096 / kBlock; ++q4) {
+        const int d = q4 * kBlock + threadIdx.x;
+        if (h[d]) atomicAdd(&hist[d], h[d]);
+    }
 }
 
-// q_total = sum of the partial sums, in a fixed order; also clears the histograms of the radix
-// select that follows (hist_len entries)
-__global__ void __launch_bounds__(kBlock)
-k_lw_qsum(const double *__restrict__ q_part, int parts, double *__restrict__ q_total, int32_t *__restrict__ sel_hist,
-          int hist_len) {
-    __shared__ double lds[kBlock];
-    for (int k = threadIdx.x; k < hist_len; k += kBlock) sel_hist[k] = 0;
+// q_total = sum of the partial sums, in a fixed order (one workgroup; `lds` needs kBlock doubles)
+__device__ __forceinline__ void lw_sum_parts(const double *__restrict__ q_part, int parts, double *__restrict__ q_total, double *lds) {
     double a = 0.0;
     for (int k = threadIdx.x; k < parts; k += kBlock) a += q_part[k];
     lds[threadIdx.x] = a;
@@ -215,79 +348,130 @@ k_lw_qsum(const double *__restrict__ q_part, int parts, double *__restrict__ q_t
     if (threadIdx.x == 0) *q_total = lds[0];
 }
 
-// Radix select, pass `pass` of 8 (byte 7 - pass of the key).
-//   state[2p]   = the bytes chosen before pass p, as the low bytes of a word (0 for p = 0)
-//   state[2p+1] = how many of the keys with that prefix are still wanted (layer_size for p = 0)
-// Every workgroup derives state[2(pass)] from state[2(pass-1)] and hist[pass-1] (the first byte value at
-// which the running count reaches the wanted number); workgroup 0 stores it.  Then the keys that carry
-// the prefix are counted by their next byte.  pass == 8 only derives the final state: the threshold
-// key and how many keys equal to it are wanted.
-__global__ void __launch_bounds__(kBlock)
-k_lw_select(const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_cand, int64_t layer_size,
-            unsigned long long *__restrict__ state, int32_t *__restrict__ hist, int pass) {
-    __shared__ int lds[kWavesPerBlock];
-    __shared__ int h[256];
-    __shared__ unsigned long long st[2];
+// The state of the select before pass `pass`:
+//   st[0] = the digits chosen in the passes before, most significant first, as the low bits of a word
+//   st[1] = how many of the keys with that prefix are still wanted
+// derived from the state before the previous pass (state[2(pass-1)], state[2(pass-1)+1]) and that
+// pass's histogram: the first digit at which the running count reaches the wanted number.  Every
+// thread of the workgroup calls it; st[] is valid after the next __syncthreads().  If fewer keys
+// exist than are wanted no digit qualifies and st stays {0, 0}.
+__device__ __forceinline__ void sel_derive(const unsigned long long *__restrict__ state, const int32_t *__restrict__ hist,
+                                           int64_t layer_size, int pass, unsigned long long *st, int *lds) {
     const int tid = threadIdx.x;
     if (pass == 0) {
         if (tid == 0) {
             st[0] = 0;
             st[1] = static_cast<unsigned long long>(layer_size);
         }
-    } else {
-        if (tid == 0) {
-            st[0] = 0;
-            st[1] = 0;
-        }
-        const unsigned long long prefix = state[2 * (pass - 1)];
-        const long long want = static_cast<long long>(state[2 * (pass - 1) + 1]);
-        const int c = hist[(pass - 1) * 256 + tid];
-        int total;
-        const int before = block_excl_scan<kWavesPerBlock>(c, &total, lds);
-        // exactly one byte value has before < want <= before + c (want >= 1 and want <= total)
-        if (before < want && want <= static_cast<long long>(before) + c) {
-            st[0] = (prefix << 8) | static_cast<unsigned long long>(tid);
-            st[1] = static_cast<unsigned long long>(want - before);
+        return;
+    }
+    if (tid == 0) {
+        st[0] = 0;
+        st[1] = 0;
+    }
+    const unsigned long long prefix = state[2 * (pass - 1)];
+    const long long want = static_cast<long long>(state[2 * (pass - 1) + 1]);
+    constexpr int kPer = kSelBins / kBlock;                // consecutive digits per thread
+    const int4 *hp = reinterpret_cast<const int4 *>(hist + int64_t(pass - 1) * kSelBins + tid * kPer);
+    int v[kPer];
+    int c = 0;
+#pragma unroll
+    for (int q = 0; q < kPer / 4; ++q) {
+        const int4 x = hp[q];
+        v[4 * q] = x.x;
+        v[4 * q + 1] = x.y;
+        v[4 * q + 2] = x.z;
+        v[4 * q + 3] = x.w;
+        c += x.x + x.y + x.z + x.w;
+    }
+    int total;
+    const int before = block_excl_scan<kWavesPerBlock>(c, &total, lds);   // its barriers order the stores to st[] above
+    // exactly one digit has before < want <= before + count (if 1 <= want <= total)
+    if (before < want && want <= static_cast<long long>(before) + c) {
+        long long run = before;
+#pragma unroll
+        for (int q = 0; q < kPer; ++q) {
+            if (run < want && want <= run + v[q]) {
+                st[0] = (prefix << 13) | static_cast<unsigned long long>(tid * kPer + q);
+                st[1] = static_cast<unsigned long long>(want - run);
+            }
+            run += v[q];
         }
     }
-    h[tid] = 0;
+}
+
+// Counting pass `pass` of the select: the keys that carry the prefix found so far are counted by
+// their next digit, per workgroup in LDS and then into hist[pass].  Workgroup 0 stores the state.
+__global__ void __launch_bounds__(kBlock)
+k_lw_select(const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_dev, int64_t n_fixed, int64_t layer_size,
+            unsigned long long *__restrict__ state, int32_t *__restrict__ hist, int pass) {
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ int h[kSelBins];
+    __shared__ unsigned long long st[2];
+    const int tid = threadIdx.x;
+    sel_derive(state, hist, layer_size, pass, st, lds);
+#pragma unroll
+    for (int q = 0; q < kSelBins / kBlock; ++q) h[q * kBlock + tid] = 0;
     __syncthreads();
     if (blockIdx.x == 0 && tid == 0) {
         state[2 * pass] = st[0];
         state[2 * pass + 1] = st[1];
     }
-    if (pass == 8) return;
     const unsigned long long prefix = st[0];
-    const int shift = 56 - 8 * pass;
-    const int64_t n = *n_cand;
+    const int shift = sel_shift(pass);
+    const int64_t n = n_dev ? *n_dev : n_fixed;
     const int64_t stride = int64_t(gridDim.x) * kBlock;
+    int mine = 0;
     for (int64_t c = int64_t(blockIdx.x) * kBlock + tid; c < n; c += stride) {
         const uint64_t k = key64[c];
-        if (pass == 0 || (k >> (shift + 8)) == prefix) atomicAdd(&h[(k >> shift) & 255], 1);
+        if (pass == 0 || (k >> (shift + 13)) == prefix) {
+            atomicAdd(&h[(k >> shift) & (kSelBins - 1)], 1);
+            mine = 1;
+        }
     }
-    __syncthreads();
-    if (h[tid]) atomicAdd(&hist[pass * 256 + tid], h[tid]);
+    if (!__syncthreads_or(mine)) return;                   // no key of this workgroup carries the prefix
+#pragma unroll
+    for (int q = 0; q < kSelBins / kBlock; ++q) {
+        const int d = q * kBlock + tid;
+        if (h[d]) atomicAdd(&hist[pass * kSelBins + d], h[d]);
+    }
 }
 
-// state[16] = threshold key, state[17] = number of keys equal to it that are wanted.  Keys below the
-// threshold are marked; so are the keys equal to it if all of them are wanted.  Otherwise (several
+// n keys (*n_dev if given, else n_fixed), of which *n_cand are candidates (all of them without
+// n_cand; with skip_no_key the keys equal to kNoKey are none).
+// Every workgroup derives the end of the select from the last pass: the threshold key and the number
+// of keys equal to it that are wanted (workgroup 0 stores them in state[16], state[17]).  Keys below
+// the threshold are marked; so are the keys equal to it if all of them are wanted.  Otherwise (several
 // candidates with exactly the same key, of which only some fit) the first wavefront walks the
 // candidates in order (ascending position = ascending id) and marks equal keys until enough are taken.
+// Workgroup 0 also adds up the partial sums of q, if there are any.
 __global__ void __launch_bounds__(kBlock)
-k_lw_mark(const int32_t *__restrict__ cand, const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_cand,
-          int64_t layer_size, const unsigned long long *__restrict__ state, const int32_t *__restrict__ hist,
-          uint32_t *__restrict__ bitmap) {
-    const int64_t n = *n_cand;
+k_lw_mark(const int32_t *__restrict__ cand, const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_dev, int64_t n_fixed,
+          const int64_t *__restrict__ n_cand, int skip_no_key, int64_t layer_size, unsigned long long *__restrict__ state,
+          const int32_t *__restrict__ hist, uint32_t *__restrict__ bitmap, const double *__restrict__ q_part, int parts,
+          double *__restrict__ q_total) {
+    __shared__ double qlds[kBlock];
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ unsigned long long st[2];
+    if (q_part && blockIdx.x == 0) lw_sum_parts(q_part, parts, q_total, qlds);
+    const int64_t n = n_dev ? *n_dev : n_fixed;            // keys
     const int64_t stride = int64_t(gridDim.x) * kBlock;
-    if (n <= layer_size) {                                 // every candidate is drawn
-        for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
+    if ((n_cand ? *n_cand : n) <= layer_size) {            // every candidate is drawn
+        for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride)
+            if (!skip_no_key || key64[c] != kNoKey) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
         return;
     }
-    // keys equal to the threshold: hist[7 * 256 + last byte] of them exist, state[17] are wanted -
+    sel_derive(state, hist, layer_size, kSelPasses, st, lds);
+    __syncthreads();
+    // keys equal to the threshold: the last histogram has their number, st[1] are wanted -
     // normally all of them, and then their order does not matter
-    const uint64_t thr = state[16];
-    const int64_t want = static_cast<int64_t>(state[17]);
-    const int64_t have = hist[7 * 256 + static_cast<int>(thr & 255)];
+    const uint64_t thr = st[0];
+    const int64_t want = static_cast<int64_t>(st[1]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        state[16] = thr;
+        state[17] = st[1];
+    }
+    const int64_t have = hist[(kSelPasses - 1) * kSelBins + static_cast<int>(thr & (kSelBins - 1))];
     const bool all_equal = have == want;
     for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
         const uint64_t k = key64[c];
@@ -372,35 +556,29 @@ k_lw_count(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, c
     }
 }
 
-// indptr[t] = first edge position of row t = offs[t * kRowChunks]; also the block's nnz and flags
-__global__ void __launch_bounds__(kBlock)
-k_lw_indptr(const int32_t *__restrict__ offs, int64_t *sizes, int32_t *__restrict__ indptr, int64_t cap_nnz,
-            const int32_t *__restrict__ seed_flags) {
-    const int64_t n = sizes[0];
-    const int64_t t = int64_t(blockIdx.x) * kBlock + threadIdx.x;
-    if (t <= n) indptr[t] = offs[t * kRowChunks];
-    if (t == 0) {
-        const int64_t nnz = offs[n * kRowChunks];
-        sizes[2] = nnz < cap_nnz ? nnz : cap_nnz;
-        sizes[3] = (seed_flags ? *seed_flags : 0) | (nnz > cap_nnz ? 4 : 0);
-    }
-}
-
 template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_lw_fill(const PtrT *__restrict__ row_ptr, const IdxT *__restrict__ col_idx, const IdxT *__restrict__ dst,
-          const int64_t *__restrict__ sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
+          int64_t *sizes, const int32_t *__restrict__ local_of, const unsigned long long *__restrict__ mass,
           const double *__restrict__ q_total, const double *__restrict__ beta, int flat, const int32_t *__restrict__ offs,
-          const double *__restrict__ psum, int32_t *__restrict__ indices, float *__restrict__ edge_w, int normalise,
-          int64_t cap_nnz) {
+          const double *__restrict__ psum, int32_t *__restrict__ indptr, int32_t *__restrict__ indices,
+          float *__restrict__ edge_w, int normalise, int64_t cap_nnz, const int32_t *__restrict__ seed_flags) {
     const int lane = lane_id();
-    const int64_t n = sizes[0] * kRowChunks;
+    const int64_t rows = sizes[0];
+    const int64_t n = rows * kRowChunks;
     const double scale = *q_total / static_cast<double>(sizes[1]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {             // the end of indptr, the block's nnz and flags
+        const int64_t nnz = offs[n];
+        indptr[rows] = static_cast<int32_t>(nnz);
+        sizes[2] = nnz < cap_nnz ? nnz : cap_nnz;
+        sizes[3] = (seed_flags ? *seed_flags : 0) | (nnz > cap_nnz ? 4 : 0);
+    }
     const int64_t wave0 = int64_t(blockIdx.x) * kWavesPerBlock + (threadIdx.x >> 6);
     const int64_t nwaves = int64_t(gridDim.x) * kWavesPerBlock;
     for (int64_t u = wave0; u < n; u += nwaves) {
         const int64_t t = u / kRowChunks;
         const int c = static_cast<int>(u % kRowChunks);
+        if (c == 0 && lane == 0) indptr[t] = offs[u];      // first edge position of row t
         if (offs[u + 1] == offs[u]) continue;              // nothing drawn in this chunk (wavefront-uniform)
         const int64_t v = static_cast<int64_t>(dst[t]);
         const int64_t start = static_cast<int64_t>(row_ptr[v]);
@@ -563,14 +741,19 @@ k_lw_debias(const int32_t *__restrict__ order, const double *__restrict__ dq, co
 
 template <typename IdxT>
 __global__ void __launch_bounds__(kBlock)
-k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand, unsigned long long *__restrict__ mass,
-           const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes, int32_t *__restrict__ local_of,
-           int32_t *__restrict__ flags) {
+k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand, int64_t all_nodes,
+           unsigned long long *__restrict__ mass, const IdxT *__restrict__ src_ids, const int64_t *__restrict__ sizes,
+           int32_t *__restrict__ local_of, int32_t *__restrict__ flags, int32_t *__restrict__ sel_hist, int hist_len) {
     if (flags && blockIdx.x == 0 && threadIdx.x == 0) *flags = 0;     // the seed check's word, for the next call
-    const int64_t nc = *n_cand, ns = sizes[1];
+    const int64_t ns = sizes[1];
     const int64_t stride = int64_t(gridDim.x) * kBlock;
-    if (cand)
+    for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < hist_len; k += stride) sel_hist[k] = 0;   // for the next block
+    if (cand) {
+        const int64_t nc = *n_cand;
         for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < nc; k += stride) mass[cand[k]] = 0;
+    } else {
+        for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < all_nodes; k += stride) mass[k] = 0;
+    }
     for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < ns; k += stride) local_of[src_ids[k]] = -1;
 }
 
@@ -589,7 +772,7 @@ bool dev_alloc(T **p, int64_t count) {
 void free_layerwise_scratch(mqg_ctx *ctx) {
     LayerwiseScratch &w = ctx->lw;
     void *ptrs[] = {w.mass, w.cand, w.key64, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
-                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_sum, w.fg_mass, w.dkey, w.dq, w.order, w.beta};
+                    w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_scan, w.chunk_sum, w.fg_mass, w.dkey, w.dq, w.order, w.beta};
     for (void *p : ptrs) (void)hipFree(p);
     w = LayerwiseScratch{};
 }
@@ -607,7 +790,8 @@ int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
     bool ok = dev_alloc(&w.mass, n) && dev_alloc(&w.cand, n) && dev_alloc(&w.key64, n) && dev_alloc(&w.word_offs, ctx->bitmap_words + 1) &&
               dev_alloc(&w.scan_tiles, ceil_div(scan_len, kScanTile) + 2) && dev_alloc(&w.q_part, ceil_div(n, kBlock) + 1) &&
               dev_alloc(&w.counters, 4) && dev_alloc(&w.q_total, 1) && dev_alloc(&w.seeds_copy, rows_cap) && dev_alloc(&w.flags, 1) &&
-              dev_alloc(&w.sel_state, 18) && dev_alloc(&w.sel_hist, 8 * 256) && dev_alloc(&w.chunk_offs, chunks + 1) &&
+              dev_alloc(&w.sel_state, 18) && dev_alloc(&w.sel_hist, kSelHistLen) && dev_alloc(&w.chunk_offs, chunks + 1) &&
+              dev_alloc(&w.chunk_scan, std::min<int64_t>(chunks + 1, int64_t(kScanSelfTiles) * kScanTile)) &&
               dev_alloc(&w.chunk_sum, chunks) && dev_alloc(&w.dkey, rows_cap) && dev_alloc(&w.dq, rows_cap) &&
               dev_alloc(&w.order, rows_cap) && dev_alloc(&w.beta, rows_cap);
     if (ok) ok = hipMemset(w.mass, 0, static_cast<size_t>(n) * sizeof(unsigned long long)) == hipSuccess &&
@@ -629,19 +813,46 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
     const PtrT *row_ptr = static_cast<const PtrT *>(g->row_ptr);
     const IdxT *col_idx = static_cast<const IdxT *>(g->col_idx);
     const int64_t n = ctx->num_nodes;
-    const int64_t words = ctx->bitmap_words;
-    const int word_grid = static_cast<int>(ceil_div(words + 1, kBlock));
+    // bitmap -> list: tiles of kBlock * wpt words, counted by the launch before (w.word_offs)
+    const int wpt = ctx->bitmap_words <= (int64_t(1) << 20) ? 1 : 4;
+    const int tiles = static_cast<int>(ctx->bitmap_words / (int64_t(kBlock) * wpt));
+    const int tiles_scanned = tiles > kSelfPrefixTiles ? 1 : 0;
+    auto count_tiles = [&]() -> int {
+        if (wpt == 1) MQG_LAUNCH(ctx, "k_lw_tile_counts", s, (k_lw_tile_counts<1><<<tiles, kBlock, 0, s>>>(ctx->bitmap, w.word_offs)));
+        else MQG_LAUNCH(ctx, "k_lw_tile_counts", s, (k_lw_tile_counts<4><<<tiles, kBlock, 0, s>>>(ctx->bitmap, w.word_offs)));
+        return MQG_OK;
+    };
+    auto emit_list = [&](auto *out, int32_t *local_of, int64_t *count_a, int64_t *count_b) -> int {
+        using OutT = std::remove_pointer_t<decltype(out)>;
+        if (tiles_scanned) {
+            int rc = device_scan(ctx, w.word_offs, tiles, w.scan_tiles, s);
+            if (rc != MQG_OK) return rc;
+        }
+        if (wpt == 1)
+            MQG_LAUNCH(ctx, "k_lw_emit", s, (k_lw_emit<OutT, 1><<<tiles, kBlock, 0, s>>>(ctx->bitmap, w.word_offs, tiles_scanned, out, local_of, count_a, count_b)));
+        else
+            MQG_LAUNCH(ctx, "k_lw_emit", s, (k_lw_emit<OutT, 4><<<tiles, kBlock, 0, s>>>(ctx->bitmap, w.word_offs, tiles_scanned, out, local_of, count_a, count_b)));
+        return MQG_OK;
+    };
     const int cand_grid = static_cast<int>(std::max<int64_t>(1, ceil_div(n, kBlock)));
     const uint64_t seed_hash = host_mix64(rng_seed + kGolden);
-    int64_t *n_cand = fastgcn ? w.counters + 2 : w.counters;    // FastGCN: every node is a candidate
-    const int32_t *cand = fastgcn ? nullptr : w.cand;
+    // Three ways to the candidates.  FastGCN: every node, with batch-independent masses.  Graphs of up
+    // to kDenseNodes nodes: every node gets a key slot and the nodes without mass hold no key - no
+    // candidate list, a node's key sits at its id (on "medium" 200 k of the 233 k nodes are candidates
+    // anyway).  Otherwise: the list of touched nodes, ascending.
+    const int how = ctx->layerwise_candidates;
+    const bool dense = !fastgcn && (how == 0 ? n <= kDenseNodes : how == 1);
+    const bool keyed_by_id = fastgcn || dense;
+    int64_t *n_cand = fastgcn ? w.counters + 2 : w.counters;
+    const int32_t *cand = keyed_by_id ? nullptr : w.cand;
+    const int64_t *n_keys_dev = keyed_by_id ? nullptr : w.counters;       // keyed by id: n keys
     const unsigned long long *mass = fastgcn ? w.fg_mass : w.mass;
     if (fastgcn && !w.fg_ready) {
         // the batch-independent masses: the mass kernel over every row of the graph, once per context
         MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(w.counters + 2, n)));
         const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n * kRowChunks, kWavesPerBlock)), 256 * 64));
         MQG_LAUNCH(ctx, "k_lw_mass", s,
-                   (k_lw_mass<PtrT, IdxT><<<grid, kBlock, 0, s>>>(row_ptr, col_idx, nullptr, w.counters + 2, w.fg_mass, nullptr)));
+                   (k_lw_mass<PtrT, IdxT><<<grid, kBlock, 0, s>>>(row_ptr, col_idx, nullptr, w.counters + 2, w.fg_mass, nullptr, nullptr)));
         w.fg_ready = true;
     }
 
@@ -650,7 +861,7 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         const int grid = static_cast<int>(std::max<int64_t>(1, ceil_div(num_seeds, kBlock)));
         MQG_LAUNCH(ctx, "k_lw_seeds", s,
                    (k_lw_seeds<IdxT><<<grid, kBlock, 0, s>>>(static_cast<const IdxT *>(seeds_v), num_seeds, n, dst0,
-                                                             blocks[L - 1].sizes, w.flags)));
+                                                             blocks[L - 1].sizes, w.flags, w.sel_hist, kSelHistLen)));
     }
     for (int l = L - 1; l >= 0; --l) {
         mqg_block &b = blocks[l];
@@ -662,40 +873,39 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         int rc = MQG_OK;
         if (!fastgcn) {
             const int mass_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(rows_cap * kRowChunks, kWavesPerBlock)), 256 * 64));
-            // candidates: marked slot by slot in the node bitmap, or, on graphs of up to kMassScanNodes
-            // nodes, read off the masses afterwards (1.9 MB of masses against 0.5 M bitmap probes on "medium")
-            const bool scan_masses = n <= kMassScanNodes;
+            // list of candidates: marked slot by slot in the node bitmap, or, on graphs of up to
+            // kMassScanNodes nodes, read off the masses afterwards
+            const bool scan_masses = how == 0 ? n <= kMassScanNodes : how == 2;
             MQG_LAUNCH(ctx, "k_lw_mass", s,
                        (k_lw_mass<PtrT, IdxT><<<mass_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, w.mass,
-                                                                           scan_masses ? nullptr : ctx->bitmap)));
-            if (scan_masses)
-                MQG_LAUNCH(ctx, "k_lw_mass_bits", s,
-                           (k_lw_mass_bits<<<static_cast<int>(words * 32 / kBlock), kBlock, 0, s>>>(w.mass, n, ctx->bitmap)));
-            // candidates, ascending
-            MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
-            rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
-            if (rc != MQG_OK) return rc;
-            MQG_LAUNCH(ctx, "k_lw_emit", s,
-                       (k_lw_emit<int32_t><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, w.cand, nullptr, n_cand, nullptr)));
+                                                                           dense || scan_masses ? nullptr : ctx->bitmap,
+                                                                           dense ? w.counters : nullptr)));
+            if (!dense) {
+                if (scan_masses)
+                    MQG_LAUNCH(ctx, "k_lw_mass_bits", s, (k_lw_mass_bits<<<tiles, kBlock, 0, s>>>(w.mass, n, ctx->bitmap, w.word_offs)));
+                else
+                    rc = count_tiles();
+                if (rc == MQG_OK) rc = emit_list(w.cand, nullptr, n_cand, nullptr);
+                if (rc != MQG_OK) return rc;
+            }
         }
-        // race keys, ranking
-        const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, 2048));
+        // race keys and the first digit's counts, then the other digits, then the drawn nodes
+        // (few workgroups: the keys' leading digits take a handful of values, and every workgroup adds its
+        // counts to the same few words - 911 workgroups spent 9 us of 15 queueing there)
+        const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, n <= (int64_t(1) << 22) ? 256 : 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
-                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_cand, mass, tag_hash, flat, w.key64, w.q_part)));
-        MQG_LAUNCH(ctx, "k_lw_qsum", s, (k_lw_qsum<<<1, kBlock, 0, s>>>(w.q_part, key_grid, w.q_total, w.sel_hist, 8 * 256)));
+                   (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_keys_dev, n, mass, tag_hash, flat, w.key64, w.q_part, w.sel_hist,
+                                                                dense ? w.counters : nullptr, w.sel_state, layer_sizes[l])));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
-        for (int pass = 0; pass <= 8; ++pass)
+        for (int pass = 1; pass < kSelPasses; ++pass)
             MQG_LAUNCH(ctx, "k_lw_select", s,
-                       (k_lw_select<<<pass == 8 ? 1 : sel_grid, kBlock, 0, s>>>(w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, pass)));
-        // the drawn nodes, ascending = the block's sources
+                       (k_lw_select<<<sel_grid, kBlock, 0, s>>>(w.key64, n_keys_dev, n, layer_sizes[l], w.sel_state, w.sel_hist, pass)));
         MQG_LAUNCH(ctx, "k_lw_mark", s,
-                   (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(cand, w.key64, n_cand, layer_sizes[l], w.sel_state, w.sel_hist, ctx->bitmap)));
-        MQG_LAUNCH(ctx, "k_lw_word_counts", s, (k_lw_word_counts<<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs)));
-        rc = device_scan(ctx, w.word_offs, words + 1, w.scan_tiles, s);
+                   (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(cand, w.key64, n_keys_dev, n, n_cand, dense ? 1 : 0, layer_sizes[l], w.sel_state,
+                                                          w.sel_hist, ctx->bitmap, w.q_part, key_grid, w.q_total)));
+        rc = count_tiles();
+        if (rc == MQG_OK) rc = emit_list(src_ids, ctx->local_of, &b.sizes[1], l > 0 ? &blocks[l - 1].sizes[0] : nullptr);
         if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_lw_emit", s,
-                   (k_lw_emit<IdxT><<<word_grid, kBlock, 0, s>>>(ctx->bitmap, words, w.word_offs, src_ids, ctx->local_of, &b.sizes[1],
-                                                                 l > 0 ? &blocks[l - 1].sizes[0] : nullptr)));
         const double *beta = nullptr;
         if (debias) {
             const int64_t src_cap = std::min<int64_t>(n, layer_sizes[l]);
@@ -715,19 +925,23 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         MQG_LAUNCH(ctx, "k_lw_count", s,
                    (k_lw_count<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
                                                                          beta, flat, w.chunk_offs, w.chunk_sum)));
-        rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
+        // one launch when the table is small (the scan goes to a second array), else in place
+        const int32_t *offs = w.chunk_offs;
+        if (chunks_cap + 1 <= int64_t(kScanSelfTiles) * kScanTile) {
+            rc = device_scan_copy(ctx, w.chunk_offs, w.chunk_scan, chunks_cap + 1, s);
+            offs = w.chunk_scan;
+        } else {
+            rc = device_scan(ctx, w.chunk_offs, chunks_cap + 1, w.scan_tiles, s);
+        }
         if (rc != MQG_OK) return rc;
-        MQG_LAUNCH(ctx, "k_lw_indptr", s,
-                   (k_lw_indptr<<<static_cast<int>(ceil_div(rows_cap + 1, kBlock)), kBlock, 0, s>>>(w.chunk_offs, b.sizes, b.indptr, b.cap_nnz,
-                                                                                                    l == L - 1 ? w.flags : nullptr)));
         MQG_LAUNCH(ctx, "k_lw_fill", s,
                    (k_lw_fill<PtrT, IdxT><<<chunk_grid, kBlock, 0, s>>>(row_ptr, col_idx, dst, b.sizes, ctx->local_of, mass, w.q_total,
-                                                                        beta, flat, w.chunk_offs, w.chunk_sum, b.indices, edge_w[l], normalise,
-                                                                        b.cap_nnz)));
+                                                                        beta, flat, offs, w.chunk_sum, b.indptr, b.indices, edge_w[l],
+                                                                        normalise, b.cap_nnz, l == L - 1 ? w.flags : nullptr)));
         const int reset_grid = static_cast<int>(std::min<int64_t>(cand_grid, 4096));
         MQG_LAUNCH(ctx, "k_lw_reset", s,
-                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(cand, n_cand, w.mass, src_ids, b.sizes, ctx->local_of,
-                                                                   l == L - 1 ? w.flags : nullptr)));
+                   (k_lw_reset<IdxT><<<reset_grid, kBlock, 0, s>>>(cand, n_cand, dense ? n : 0, w.mass, src_ids, b.sizes, ctx->local_of,
+                                                                   l == L - 1 ? w.flags : nullptr, w.sel_hist, kSelHistLen)));
     }
     return MQG_OK;
 }
@@ -743,11 +957,12 @@ int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int6
     if (words > 0)
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
                    (k_lw_zero_i32<<<static_cast<int>(ceil_div(words, kBlock)), kBlock, 0, s>>>(reinterpret_cast<int32_t *>(out_bitmap), words)));
-    MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<8, kBlock, 0, s>>>(w.sel_hist, 8 * 256)));
+    MQG_LAUNCH(ctx, "k_lw_zero_i32", s, (k_lw_zero_i32<<<kSelHistLen / kBlock, kBlock, 0, s>>>(w.sel_hist, kSelHistLen)));
     const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n, kBlock)), 1024));
-    for (int pass = 0; pass <= 8; ++pass)
-        MQG_LAUNCH(ctx, "k_lw_select", s, (k_lw_select<<<pass == 8 ? 1 : grid, kBlock, 0, s>>>(keys, n_dev, k, w.sel_state, w.sel_hist, pass)));
-    MQG_LAUNCH(ctx, "k_lw_mark", s, (k_lw_mark<<<grid, kBlock, 0, s>>>(nullptr, keys, n_dev, k, w.sel_state, w.sel_hist, out_bitmap)));
+    for (int pass = 0; pass < kSelPasses; ++pass)
+        MQG_LAUNCH(ctx, "k_lw_select", s, (k_lw_select<<<grid, kBlock, 0, s>>>(keys, n_dev, 0, k, w.sel_state, w.sel_hist, pass)));
+    MQG_LAUNCH(ctx, "k_lw_mark", s,
+               (k_lw_mark<<<grid, kBlock, 0, s>>>(nullptr, keys, n_dev, 0, nullptr, 0, k, w.sel_state, w.sel_hist, out_bitmap, nullptr, 0, nullptr)));
     return MQG_OK;
 }
 

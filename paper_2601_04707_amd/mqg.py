@@ -22,6 +22,7 @@ MQG_OK, MQG_ERR_INVALID_ARG, MQG_ERR_CAPACITY, MQG_ERR_HIP, MQG_ERR_UNSUPPORTED 
 MQG_F32, MQG_F16 = 0, 1
 MQG_I32, MQG_I64 = 0, 1
 MQG_OPT_FORCE_SLOW_SELECT, MQG_OPT_PROFILE, MQG_OPT_MISS_INFLIGHT_BYTES, MQG_OPT_HEAVY_DEGREE, MQG_OPT_DEDUP_HASH = 1, 2, 3, 4, 5
+MQG_OPT_LAYERWISE_CANDIDATES = 6
 MQG_MAX_FANOUT, MQG_MAX_LAYERS = 64, 8
 MQG_CACHE_TOP_DEGREE, MQG_CACHE_DEGREE_SAMPLED, MQG_CACHE_RANDOM_WALK, MQG_CACHE_RANDOM_WALK_SAMPLED = 0, 1, 2, 3
 MQG_WALK_PUSH, MQG_WALK_PRINTED = 0, 1

@@ -152,6 +152,29 @@ def test_debiased_variants_parity(mqg, ptr, idx, sizes, fastgcn):
     assert not np.allclose(plain[-1].edge_w, want[-1].edge_w, rtol=1e-5)      # the coefficients do differ from 1 / (s p)
 
 
+@pytest.mark.parametrize("sizes", [[64, 128], [512, 512], [100, 50, 30], [30000]])
+def test_layerwise_candidate_paths_give_the_same_blocks(mqg, sizes):
+    """The three ways to a layer's candidates - a key slot per node, a list read off the masses, a
+    list from bits set slot by slot (the last two are what graphs above 1 M / 8 M nodes take) -
+    against the oracle, alternating on one context, plain and debiased."""
+    rp, ci = hub_graph()
+    n = rp.numel() - 1
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    batch = 193
+    ctx = mqg.Context(g, batch, [2] * len(sizes))
+    blocks = mqg.LayerwiseBlocks(g, batch, sizes)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    seeds = synth.seed_batches(n, batch, 3, seed=17)
+    for b, how in enumerate([3, 1, 2, 3, 2, 1, 0]):
+        ctx.set_option(mqg.MQG_OPT_LAYERWISE_CANDIDATES, how)
+        debias = b % 2 == 1
+        got = run_layerwise(mqg, ctx, g, blocks, seeds[b % 3], sizes, 90 + b, method=mqg.MQG_LAYERWISE_DEBIAS if debias else 0)
+        want = oracle.ladies_blocks(rp_np, ci_np, seeds[b % 3].numpy(), sizes, 90 + b, debias=debias)
+        assert_same(got, want)
+    with pytest.raises(mqg.MqgError):
+        ctx.set_option(mqg.MQG_OPT_LAYERWISE_CANDIDATES, 4)
+
+
 def test_layerwise_small_graph_all_candidates_and_degenerate_inputs(mqg):
     rp = torch.tensor([0, 0, 2, 3, 3, 6], dtype=torch.int64)      # nodes 0 and 3 have no neighbours
     ci = torch.tensor([2, 4, 1, 0, 1, 2], dtype=torch.int64)
@@ -270,6 +293,28 @@ def test_selection_step_with_many_equal_keys(mqg, n, k, distinct):
     order = np.lexsort((np.arange(n), keys))
     want = np.zeros(n, dtype=bool)
     want[order[:min(k, n)]] = True
+    assert np.array_equal(got.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("low_bits", [1, 5, 12, 13, 14, 26, 27, 39, 40, 52, 53, 64])
+def test_selection_step_when_only_the_low_bits_differ(mqg, low_bits):
+    """Keys that share everything above their lowest `low_bits` bits: the select has to carry its
+    prefix through the passes whose digit is the same for every key (the widths straddle the digit
+    boundaries at bits 13, 26, 39 and 52)."""
+    n, k = 20000, 777
+    rp = torch.tensor([0, 0], dtype=torch.int64)
+    g = mqg.Graph(to_dev(rp), torch.zeros(1, dtype=torch.int64, device="cuda"))
+    ctx = mqg.Context(g, 1, [1])
+    rng = np.random.default_rng(low_bits)
+    high = np.uint64(0x3FE5A5A5A5A5A5A5) if low_bits < 64 else np.uint64(0)
+    mask = np.uint64((1 << low_bits) - 1) if low_bits < 64 else np.uint64(2 ** 64 - 1)
+    low = rng.integers(0, 2 ** 63, size=n, dtype=np.uint64) * np.uint64(2) + rng.integers(0, 2, size=n, dtype=np.uint64)
+    keys = (high & ~mask) | (low & mask)
+    got = mqg.mqg_select_smallest_keys(ctx, torch.from_numpy(keys.view(np.int64)).cuda(), k)
+    torch.cuda.synchronize()
+    order = np.lexsort((np.arange(n), keys))
+    want = np.zeros(n, dtype=bool)
+    want[order[:k]] = True
     assert np.array_equal(got.cpu().numpy(), want)
 
 
