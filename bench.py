@@ -21,8 +21,9 @@ committed profile summary of this workload, with `traffic_source` saying where
 from); `roofline_host_link` = the miss-gather kernel against the host link, on
 its own and across the overlapping launches of the pipelined region;
 `cpu_baseline` = the CPU oracle on a sample of the same mini-batches;
-`stage_us_per_step` and `kernels` = per-kernel times from a second pass that
-runs one mini-batch at a time; `paper_queue_rule` = the paper's queue-depth
+`stage_us_per_step` = the three stages of a mini-batch timed as chains, one
+mini-batch at a time, `kernels` = per-kernel times from a pass that brackets
+every kernel with events; `paper_queue_rule` = the paper's queue-depth
 rule evaluated on these timings and the step time measured at that depth;
 `workloads` = the same figures, in short, for all five workloads ("stress" at
 5, 20 and 50 % cache with four mini-batches in flight), each with a short
@@ -346,6 +347,31 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
     gather_bytes = rows * row_bytes
     log(f"{name}: timed region {ms_per_step:.3f} ms/step, {edges_per_s / 1e6:.1f} M edges/s")
 
+    # ---------------------------------------------------------------- the three stages, each timed as a chain
+    # One mini-batch at a time on one stream, four events per mini-batch: what a stage's kernels take
+    # back to back, without per-kernel events between them.
+    chain = [0.0, 0.0, 0.0]
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    KC = min(K, 50)
+    s0 = streams[0]
+    for i in range(W, W + KC):
+        with torch.cuda.stream(s0):
+            torch.cuda._sleep(600_000)                          # ~0.25 ms: the stream's queue is filled before the first event
+            evs[0].record()
+            mqg.mqg_sample_blocks(ctxs[0], g, seeds_dev[i], w.fanouts, base_seed + i, blks[0], stream=s0)
+            evs[1].record()
+            mqg.mqg_gather_features(ctxs[0], cache, blks[0].src_ids[0], blks[0].sizes[0, 1:2], x0[0], stats[0], stream=s0)
+            evs[2].record()
+            x = x0[0]
+            for l in range(L):
+                mqg.mqg_sage_mean_aggregate(ctxs[0], blks[0], l, x, hs[0][l], stream=s0)
+                x = hs[0][l]
+            evs[3].record()
+        torch.cuda.synchronize()
+        for k in range(3):
+            chain[k] += evs[k].elapsed_time(evs[k + 1]) * 1e3 / KC
+    log(f"{name}: stages as chains: sample {chain[0]:.1f} us, gather {chain[1]:.1f} us, aggregate {chain[2]:.1f} us")
+
     # ---------------------------------------------------------------- per-kernel durations
     # HIP events on the launch stream around every kernel (MQG_OPT_PROFILE), one mini-batch at a
     # time so that a kernel's duration is its own and not that of whatever overlaps it.
@@ -427,8 +453,12 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
         "gather_GBps": round(gather_bytes / elapsed / 1e9, 2),
         "edges_per_step": round(edges / K, 1), "rows_per_step": round(rows / K, 1),
         "cache_hit_rate": round(hits / max(1, hits + misses), 4),
-        "stage_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1),
-                              "dedup_relabel_part_of_sample": round(dedup_us, 1)},
+        "stage_us_per_step": {"sample": round(chain[0], 1), "gather": round(chain[1], 1), "aggregate": round(chain[2], 1),
+                              "note": "each stage of one mini-batch timed as a whole on its stream, one mini-batch at a time"},
+        "stage_kernel_sum_us_per_step": {"sample": round(sample_us, 1), "gather": round(gather_us, 1), "aggregate": round(agg_us, 1),
+                                         "dedup_relabel_part_of_sample": round(dedup_us, 1),
+                                         "note": "sums of the kernels' own times, each kernel between two events of its own "
+                                                 "(which add a few microseconds per launch)"},
         "roofline": roofline, "roofline_host_link": host_link,
     }
 
@@ -582,6 +612,32 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
     bwd_wall_ms = bwd_wall / KB
     del gx, g_top, ew, sw
 
+    # ---------------------------------------------------------------- aggregation in column slabs (on request)
+    # The outermost block's aggregation reads a source row once per edge.  Split into launches over a part
+    # of the feature columns each, a launch's working set is that fraction of the rows: does the L2 then
+    # keep rows between their uses?  (Counted by FETCH_SIZE under rocprofv3; here the times.)
+    agg_slabs = None
+    if opts.agg_slabs:
+        agg_slabs = {}
+        step(W)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for nslab in [int(t) for t in opts.agg_slabs.split(",")]:
+            width = ((w.dim + nslab - 1) // nslab + 7) // 8 * 8
+            cuts = [(c, min(w.dim, c + width)) for c in range(0, w.dim, width)]
+            ts = []
+            for rep in range(12):
+                with torch.cuda.stream(streams[0]):
+                    ev0.record()
+                    for a, b in cuts:
+                        mqg.mqg_sage_mean_aggregate(ctxs[0], blks[0], 0, x0[0][:, a:b], hs[0][0][:, a:b], stream=streams[0])
+                    ev1.record()
+                torch.cuda.synchronize()
+                ts.append(ev0.elapsed_time(ev1) * 1e3)
+            ts.sort()
+            agg_slabs[str(nslab)] = {"launches": len(cuts), "columns_per_launch": width, "median_us": round(ts[len(ts) // 2], 1)}
+        log(f"{name}: aggregation of block 0 in column slabs: {agg_slabs}")
+
     # ---------------------------------------------------------------- layer-wise (LADIES) mini-batches
     # Not part of a step either: the paper's layer-wise setting (512 nodes per layer) on the same
     # seeds - sampling, gather of the outermost layer's rows, weighted sums - one batch at a time.
@@ -690,6 +746,7 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                                      "mean_aggregate_us_per_step": round(agg_us, 1),
                                      "note": "Eq. 1-3 estimator on the same blocks (weights of every block, then weighted "
                                              "sums with the diagonal term); not part of a step"},
+        "aggregation_column_slabs": agg_slabs,
         "layerwise_sampling": {"layer_sizes": lw_sizes, "ms_per_batch": round(lw_ms, 3),
                                "sampling_kernels_us_per_batch": round(lw_sample_us, 1),
                                "edges_last_batch": lw_edges, "kernel_us_per_batch": lw_kern,
@@ -740,6 +797,9 @@ def main() -> int:
     ap.add_argument("--heavy-degree", type=int, default=None, help="degree above which a workgroup samples a row")
     ap.add_argument("--device-row-multiple", type=int, default=None,
                     help="bytes the rows kept in HBM are padded to a multiple of (default: synth.aligned_row_stride)")
+    ap.add_argument("--agg-slabs", default=None,
+                    help="e.g. 1,2,4,8: also time the outermost block's aggregation split into that many launches over "
+                         "column slabs (an experiment on L2 reuse; profiles/aggregation_column_slabs_medium.md)")
     ap.add_argument("--cpu-batches", type=int, default=None, help="oracle batches for the CPU baseline")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-copy", action="store_true",
@@ -796,9 +856,11 @@ def main() -> int:
             if wname == args.workload and (pct is None or pct == cache_pct) and args.cache_pct is None:
                 r = head
             else:
-                kk = min(K, 40) if wname == "stress" else K
+                # ("tiny" steps take 50 us: a timed region of 20 of them is shorter than its own start-up)
+                kk = min(K, 40) if wname == "stress" else max(K, 400) if wname == "tiny" else K
                 r = run_workload(torch, np, mqg, synth, args, wname, cache_pct=ww.cache_pct if pct is None else pct,
-                                 in_flight=synth.launch_in_flight(ww), K=kk, W=min(W, kk), full=False, cpu_budget_s=3.0)
+                                 in_flight=synth.launch_in_flight(ww), K=kk, W=max(W, 50) if wname == "tiny" else min(W, kk),
+                                 full=False, cpu_budget_s=3.0)
             hl, rl = r.get("roofline_host_link"), r.get("roofline")
             short[key] = {
                 "value": r["value"], "unit": r["unit"], "ms_per_step": r["ms_per_step"], "steps": r["steps"],
