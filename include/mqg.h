@@ -409,11 +409,14 @@ int mqg_sample_layerwise(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_dev
  * The selection step of mqg_sample_layerwise on its own (the k smallest race
  * keys win the draw of Eq. 6-9): bit c of out_bitmap is set iff key c is among
  * the k smallest (key, index) pairs of keys[0..n) - all of them if n <= k; keys
- * that are exactly equal are taken in ascending index order.  A radix select,
- * most significant byte first, one launch per byte.
+ * that are exactly equal are taken in ascending index order.  A radix select:
+ * two counting passes over the 25 leading bits, then the keys that share the
+ * threshold's leading bits are settled as a short list.
  *   keys_dev        device [n] unsigned 64-bit keys
  *   out_bitmap_dev  device [ceil(n / 32)] words, written by the call
- * Uses the layer-wise sampler's context scratch (allocated at the first use).
+ * Uses the layer-wise sampler's context scratch (allocated at the first use; with
+ * more keys than the graph has nodes, 12 more bytes per key, allocated and kept
+ * at the first such call, after a stream synchronisation).
  */
 int mqg_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys_dev, int64_t n, int64_t k,
                              uint32_t *out_bitmap_dev, mqg_stream stream);

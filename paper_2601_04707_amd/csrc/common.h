@@ -37,6 +37,11 @@ struct LayerwiseScratch {
     unsigned long long *mass = nullptr;  // [num_nodes] integer column masses, zero between calls
     int32_t *cand = nullptr;             // [num_nodes] candidates, ascending
     uint64_t *key64 = nullptr;           // [num_nodes] race keys (double bit patterns)
+    uint64_t *bkey = nullptr;            // [num_nodes] keys that share the threshold's leading bits ...
+    int32_t *bpos = nullptr;             // ... and their positions
+    uint64_t *xkey = nullptr;            // the same for a selection on its own over more keys than the graph has nodes
+    int32_t *xpos = nullptr;
+    int64_t xcap = 0;
     unsigned long long *sel_state = nullptr;   // [18] radix select: prefix and wanted count per pass
     int32_t *sel_hist = nullptr;         // [passes][digits] counts of the radix select
     int32_t *chunk_offs = nullptr;       // [rows_cap * 16 + 1] edges per (row, chunk), then their scan
@@ -45,7 +50,7 @@ struct LayerwiseScratch {
     int32_t *word_offs = nullptr;        // [bitmap_words + 1] set bits per tile of the bitmap
     int32_t *scan_tiles = nullptr;
     double *q_part = nullptr;            // per-workgroup partial sums of q
-    int64_t *counters = nullptr;         // [0]: number of candidates
+    int64_t *counters = nullptr;         // [0]: number of candidates, [1]: keys of a selection on its own, [2]: nodes, [3]: boundary keys
     double *q_total = nullptr;
     int64_t *seeds_copy = nullptr;       // [rows_cap] the checked seeds
     int32_t *flags = nullptr;

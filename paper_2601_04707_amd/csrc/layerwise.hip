@@ -16,11 +16,14 @@
 //                    variants, Eq. 10, draw in proportion to sqrt(q_i): ticket^2 in place of ticket), ticket from
 //                    exp_ticket64; partial sums of q per workgroup, added up in a fixed order
 //   k_lw_select      radix select of the s-th smallest 64-bit key pattern, most significant digit
-//                    first (12 bits, then four times 13): one launch per digit, every workgroup
-//                    derives the prefix found so far from the previous launch's histogram
-//   k_lw_mark        derives the threshold from the last histogram; keys below it are marked in the
-//                    bitmap, keys equal to it in ascending id order as far as needed (all
-//                    candidates if there are at most s)
+//                    first: the leading 12 bits are counted by k_lw_keys itself, the next 13 by
+//                    this launch, whose workgroups derive the digit found so far from the
+//                    histogram before
+//   k_lw_mark        derives the threshold's 25 leading bits; keys below them are marked in the
+//                    bitmap, keys that share them (a few dozen) are listed (all candidates are
+//                    marked if there are at most s)
+//   k_lw_finish      one workgroup ranks the listed keys by (key, id) and marks as many as are
+//                    still wanted (a long list - many equal keys - by a radix select of its own)
 //   bitmap -> list   the drawn nodes ascending = the block's sources, positions into local_of[]
 //   k_lw_count/fill  row v lists the drawn nodes among v and its adjacency row (self edge first,
 //                    then slot order) with weight P_vi / (s p_i), optionally divided by the row sum;
@@ -266,9 +269,10 @@ __device__ __forceinline__ double lw_measure(double m, double deg1, int flat) {
     return flat ? sqrt(q) : q;
 }
 
-// Radix select of the s-th smallest 64-bit key pattern: kSelPasses counting passes, most
-// significant digit first - the top 12 bits (sign and exponent of a double), then 13 bits at a time.
-constexpr int kSelPasses = 5;
+// Radix select of the s-th smallest 64-bit key pattern: kSelPasses counting passes over all keys, most
+// significant digit first - the top 12 bits (sign and exponent of a double), then 13 bits; what
+// is left undecided after these 25 bits is a short list (k_lw_mark, k_lw_finish).
+constexpr int kSelPasses = 2;
 constexpr int kSelBins = 8192;
 constexpr int kSelHistLen = kSelPasses * kSelBins;
 __host__ __device__ constexpr int sel_shift(int pass) { return 52 - 13 * pass; }
@@ -284,13 +288,14 @@ __global__ void __launch_bounds__(kBlock)
 k_lw_keys(const PtrT *__restrict__ row_ptr, const int32_t *__restrict__ cand, const int64_t *__restrict__ n_dev, int64_t n_fixed,
           const unsigned long long *__restrict__ mass, uint64_t tag_hash, int flat, uint64_t *__restrict__ key64,
           double *__restrict__ q_part, int32_t *__restrict__ hist, int64_t *__restrict__ count_out,
-          unsigned long long *__restrict__ state, int64_t layer_size) {
+          unsigned long long *__restrict__ state, int64_t layer_size, unsigned long long *__restrict__ bcount) {
     __shared__ double lds[kWavesPerBlock];
     __shared__ int cnt_lds[kWavesPerBlock];
     __shared__ int h[4096];
     if (blockIdx.x == 0 && threadIdx.x == 0) {             // the select's state before its first pass
         state[0] = 0;
         state[1] = static_cast<unsigned long long>(layer_size);
+        *bcount = 0;                                       // the boundary list is empty
     }
     const int64_t n = n_dev ? *n_dev : n_fixed;
     const int64_t stride = int64_t(gridDim.x) * kBlock;
@@ -439,17 +444,18 @@ k_lw_select(const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_de
 
 // n keys (*n_dev if given, else n_fixed), of which *n_cand are candidates (all of them without
 // n_cand; with skip_no_key the keys equal to kNoKey are none).
-// Every workgroup derives the end of the select from the last pass: the threshold key and the number
-// of keys equal to it that are wanted (workgroup 0 stores them in state[16], state[17]).  Keys below
-// the threshold are marked; so are the keys equal to it if all of them are wanted.  Otherwise (several
-// candidates with exactly the same key, of which only some fit) the first wavefront walks the
-// candidates in order (ascending position = ascending id) and marks equal keys until enough are taken.
-// Workgroup 0 also adds up the partial sums of q, if there are any.
+// After the two counting passes 25 leading bits of the threshold are known (every workgroup derives
+// them from the second histogram; workgroup 0 stores them and the number of keys still wanted among
+// those that share them in state[4], state[5]).  Keys with smaller leading bits are marked.  Keys with
+// these leading bits - a few dozen of random keys - go to the boundary list (key, position), which
+// k_lw_finish settles.  Workgroup 0 also adds up the partial sums of q, if there are any.
+constexpr int kSelKnownShift = 39;                        // bits below the two counted digits
 __global__ void __launch_bounds__(kBlock)
 k_lw_mark(const int32_t *__restrict__ cand, const uint64_t *__restrict__ key64, const int64_t *__restrict__ n_dev, int64_t n_fixed,
           const int64_t *__restrict__ n_cand, int skip_no_key, int64_t layer_size, unsigned long long *__restrict__ state,
           const int32_t *__restrict__ hist, uint32_t *__restrict__ bitmap, const double *__restrict__ q_part, int parts,
-          double *__restrict__ q_total) {
+          double *__restrict__ q_total, uint64_t *__restrict__ bkey, int32_t *__restrict__ bpos,
+          unsigned long long *__restrict__ bcount) {
     __shared__ double qlds[kBlock];
     __shared__ int lds[kWavesPerBlock];
     __shared__ unsigned long long st[2];
@@ -461,31 +467,130 @@ k_lw_mark(const int32_t *__restrict__ cand, const uint64_t *__restrict__ key64, 
             if (!skip_no_key || key64[c] != kNoKey) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
         return;
     }
-    sel_derive(state, hist, layer_size, kSelPasses, st, lds);
+    sel_derive(state, hist, layer_size, 2, st, lds);
     __syncthreads();
-    // keys equal to the threshold: the last histogram has their number, st[1] are wanted -
-    // normally all of them, and then their order does not matter
-    const uint64_t thr = st[0];
-    const int64_t want = static_cast<int64_t>(st[1]);
+    const uint64_t lead = st[0];
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        state[16] = thr;
-        state[17] = st[1];
+        state[4] = st[0];
+        state[5] = st[1];
     }
-    const int64_t have = hist[(kSelPasses - 1) * kSelBins + static_cast<int>(thr & (kSelBins - 1))];
-    const bool all_equal = have == want;
-    for (int64_t c = int64_t(blockIdx.x) * kBlock + threadIdx.x; c < n; c += stride) {
-        const uint64_t k = key64[c];
-        if (k < thr || (all_equal && k == thr)) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
-    }
-    if (all_equal || blockIdx.x != 0 || threadIdx.x >= kWave) return;
     const int lane = lane_id();
-    int64_t taken = 0;
-    for (int64_t base = 0; base < n && taken < want; base += kWave) {
-        const int64_t c = base + lane;
-        const bool eq = c < n && key64[c] == thr;
-        const uint64_t m = ballot64(eq);
-        if (eq && taken + popc64(m & lanes_below(lane)) < want) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
-        taken += popc64(m);
+    const int64_t first = int64_t(blockIdx.x) * kBlock + threadIdx.x;
+    for (int64_t c0 = first - lane; c0 < n; c0 += stride) {          // whole wavefronts: the ballot below
+        const int64_t c = c0 + lane;
+        const uint64_t k = c < n ? key64[c] : kNoKey;
+        const uint64_t kl = k >> kSelKnownShift;
+        if (c < n && kl < lead) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[c]) : static_cast<uint32_t>(c));
+        const bool edge = c < n && kl == lead;
+        const uint64_t m = ballot64(edge);
+        if (m) {
+            unsigned long long at = 0;
+            if (lane == 0) at = atomicAdd(bcount, static_cast<unsigned long long>(popc64(m)));
+            at = __shfl(at, 0, 64);
+            if (edge) {
+                const unsigned long long o = at + popc64(m & lanes_below(lane));
+                bkey[o] = k;
+                bpos[o] = static_cast<int32_t>(c);
+            }
+        }
+    }
+}
+
+// The boundary list: m keys that share the 25 known leading bits, of which the state[5] smallest in
+// (key, position) order are drawn (positions ascend with the ids).  One workgroup.  Up to
+// kBoundaryRanked entries: every entry counts the entries ahead of it.  More (many equal keys):
+// a radix select over the remaining 39 key bits and, among the keys equal to the threshold, over the
+// 32 position bits, eight bits at a time.
+constexpr int kBoundaryRanked = 1024;
+__global__ void __launch_bounds__(kBlock)
+k_lw_finish(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_dev, int64_t n_fixed,
+            const int64_t *__restrict__ n_cand, int64_t layer_size, const unsigned long long *__restrict__ state,
+            const uint64_t *__restrict__ bkey, const int32_t *__restrict__ bpos, const unsigned long long *__restrict__ bcount,
+            uint32_t *__restrict__ bitmap) {
+    __shared__ uint64_t lk[kBoundaryRanked];
+    __shared__ int32_t lp[kBoundaryRanked];
+    __shared__ int h[256];
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ long long pick[2];
+    const int tid = threadIdx.x;
+    const int64_t n = n_dev ? *n_dev : n_fixed;
+    if ((n_cand ? *n_cand : n) <= layer_size) return;      // every candidate was drawn by k_lw_mark
+    const int64_t m = static_cast<int64_t>(*bcount);
+    long long want = static_cast<long long>(state[5]);
+    if (m <= kBoundaryRanked) {
+        for (int e = tid; e < m; e += kBlock) {
+            lk[e] = bkey[e];
+            lp[e] = bpos[e];
+        }
+        __syncthreads();
+        constexpr int PER = kBoundaryRanked / kBlock;
+        uint64_t mk[PER];
+        int32_t mp[PER];
+        int rank[PER];
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = q * kBlock + tid;
+            mk[q] = e < m ? lk[e] : 0;
+            mp[q] = e < m ? lp[e] : 0;
+            rank[q] = 0;
+        }
+        for (int j = 0; j < m; ++j) {
+            const uint64_t ok = lk[j];
+            const int32_t op = lp[j];
+#pragma unroll
+            for (int q = 0; q < PER; ++q) rank[q] += (ok < mk[q] || (ok == mk[q] && op < mp[q])) ? 1 : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < PER; ++q) {
+            const int e = q * kBlock + tid;
+            if (e < m && rank[q] < want) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[mp[q]]) : static_cast<uint32_t>(mp[q]));
+        }
+        return;
+    }
+    // radix select: first the key (bits 38..0: seven bits, then four times eight), then the position
+    uint64_t kp = state[4] << kSelKnownShift;              // the threshold key as far as known
+    int known = kSelKnownShift;                            // its bits from here up are known
+    uint32_t pp = 0;                                       // the threshold position as far as known
+    int pknown = 32;
+    for (int pass = 0; pass < 9; ++pass) {
+        const bool on_key = pass < 5;
+        const int shift = on_key ? 32 - 8 * pass : 24 - 8 * (pass - 5);
+        h[tid] = 0;
+        __syncthreads();
+        for (int64_t e = tid; e < m; e += kBlock) {
+            const uint64_t k = bkey[e];
+            if (on_key) {
+                if ((k >> known) == (kp >> known)) atomicAdd(&h[(k >> shift) & 255], 1);
+            } else if (k == kp) {
+                const uint32_t ps = static_cast<uint32_t>(bpos[e]);
+                if (pknown == 32 || (ps >> pknown) == (pp >> pknown)) atomicAdd(&h[(ps >> shift) & 255], 1);
+            }
+        }
+        __syncthreads();
+        const int c = h[tid];
+        int total;
+        const int before = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+        if (before < want && want <= static_cast<long long>(before) + c) {      // exactly one digit
+            pick[0] = tid;
+            pick[1] = want - before;
+        }
+        __syncthreads();
+        const uint64_t digit = static_cast<uint64_t>(pick[0]);
+        want = pick[1];
+        if (on_key) {
+            kp |= digit << shift;
+            known = shift;
+        } else {
+            pp |= static_cast<uint32_t>(digit) << shift;
+            pknown = shift;
+        }
+        __syncthreads();                                   // pick[] and h[] are rewritten by the next pass
+    }
+    // kp, pp: the last drawn entry
+    for (int64_t e = tid; e < m; e += kBlock) {
+        const uint64_t k = bkey[e];
+        const int32_t ps = bpos[e];
+        if (k < kp || (k == kp && static_cast<uint32_t>(ps) <= pp)) set_bit(bitmap, cand ? static_cast<uint32_t>(cand[ps]) : static_cast<uint32_t>(ps));
     }
 }
 
@@ -757,8 +862,11 @@ k_lw_reset(const int32_t *__restrict__ cand, const int64_t *__restrict__ n_cand,
     for (int64_t k = int64_t(blockIdx.x) * kBlock + threadIdx.x; k < ns; k += stride) local_of[src_ids[k]] = -1;
 }
 
-__global__ void k_lw_store_i64(int64_t *p, int64_t v) {
-    if (blockIdx.x == 0 && threadIdx.x == 0) *p = v;
+__global__ void k_lw_store_i64(int64_t *p, int64_t v, int64_t *zero) {
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        *p = v;
+        if (zero) *zero = 0;
+    }
 }
 
 
@@ -771,13 +879,13 @@ bool dev_alloc(T **p, int64_t count) {
 
 void free_layerwise_scratch(mqg_ctx *ctx) {
     LayerwiseScratch &w = ctx->lw;
-    void *ptrs[] = {w.mass, w.cand, w.key64, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
+    void *ptrs[] = {w.mass, w.cand, w.key64, w.bkey, w.bpos, w.xkey, w.xpos, w.word_offs, w.scan_tiles, w.q_part, w.counters, w.q_total, w.seeds_copy, w.flags,
                     w.sel_state, w.sel_hist, w.chunk_offs, w.chunk_scan, w.chunk_sum, w.fg_mass, w.dkey, w.dq, w.order, w.beta};
     for (void *p : ptrs) (void)hipFree(p);
     w = LayerwiseScratch{};
 }
 
-// scratch of the layer-wise sampler: about 20 bytes per graph node, allocated at the first call
+// scratch of the layer-wise sampler: about 32 bytes per graph node, allocated at the first call
 int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
     LayerwiseScratch &w = ctx->lw;
     if (w.mass && rows_cap <= w.rows_cap) return MQG_OK;
@@ -787,7 +895,7 @@ int ensure_layerwise_scratch(mqg_ctx *ctx, int64_t rows_cap, hipStream_t s) {
     const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
     const int64_t chunks = rows_cap * kRowChunks;
     const int64_t scan_len = std::max<int64_t>(ctx->bitmap_words + 1, chunks + 1);
-    bool ok = dev_alloc(&w.mass, n) && dev_alloc(&w.cand, n) && dev_alloc(&w.key64, n) && dev_alloc(&w.word_offs, ctx->bitmap_words + 1) &&
+    bool ok = dev_alloc(&w.mass, n) && dev_alloc(&w.cand, n) && dev_alloc(&w.key64, n) && dev_alloc(&w.bkey, n) && dev_alloc(&w.bpos, n) && dev_alloc(&w.word_offs, ctx->bitmap_words + 1) &&
               dev_alloc(&w.scan_tiles, ceil_div(scan_len, kScanTile) + 2) && dev_alloc(&w.q_part, ceil_div(n, kBlock) + 1) &&
               dev_alloc(&w.counters, 4) && dev_alloc(&w.q_total, 1) && dev_alloc(&w.seeds_copy, rows_cap) && dev_alloc(&w.flags, 1) &&
               dev_alloc(&w.sel_state, 18) && dev_alloc(&w.sel_hist, kSelHistLen) && dev_alloc(&w.chunk_offs, chunks + 1) &&
@@ -847,9 +955,10 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
     const int32_t *cand = keyed_by_id ? nullptr : w.cand;
     const int64_t *n_keys_dev = keyed_by_id ? nullptr : w.counters;       // keyed by id: n keys
     const unsigned long long *mass = fastgcn ? w.fg_mass : w.mass;
+    unsigned long long *bcount = reinterpret_cast<unsigned long long *>(w.counters + 3);
     if (fastgcn && !w.fg_ready) {
         // the batch-independent masses: the mass kernel over every row of the graph, once per context
-        MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(w.counters + 2, n)));
+        MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(w.counters + 2, n, nullptr)));
         const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n * kRowChunks, kWavesPerBlock)), 256 * 64));
         MQG_LAUNCH(ctx, "k_lw_mass", s,
                    (k_lw_mass<PtrT, IdxT><<<grid, kBlock, 0, s>>>(row_ptr, col_idx, nullptr, w.counters + 2, w.fg_mass, nullptr, nullptr)));
@@ -895,14 +1004,17 @@ static int sample_layerwise_impl(mqg_ctx *ctx, const mqg_graph *g, const void *s
         const int key_grid = static_cast<int>(std::min<int64_t>(cand_grid, n <= (int64_t(1) << 22) ? 256 : 2048));
         MQG_LAUNCH(ctx, "k_lw_keys", s,
                    (k_lw_keys<PtrT><<<key_grid, kBlock, 0, s>>>(row_ptr, cand, n_keys_dev, n, mass, tag_hash, flat, w.key64, w.q_part, w.sel_hist,
-                                                                dense ? w.counters : nullptr, w.sel_state, layer_sizes[l])));
+                                                                dense ? w.counters : nullptr, w.sel_state, layer_sizes[l], bcount)));
         const int sel_grid = static_cast<int>(std::min<int64_t>(cand_grid, 1024));
         for (int pass = 1; pass < kSelPasses; ++pass)
             MQG_LAUNCH(ctx, "k_lw_select", s,
                        (k_lw_select<<<sel_grid, kBlock, 0, s>>>(w.key64, n_keys_dev, n, layer_sizes[l], w.sel_state, w.sel_hist, pass)));
         MQG_LAUNCH(ctx, "k_lw_mark", s,
                    (k_lw_mark<<<sel_grid, kBlock, 0, s>>>(cand, w.key64, n_keys_dev, n, n_cand, dense ? 1 : 0, layer_sizes[l], w.sel_state,
-                                                          w.sel_hist, ctx->bitmap, w.q_part, key_grid, w.q_total)));
+                                                          w.sel_hist, ctx->bitmap, w.q_part, key_grid, w.q_total, w.bkey, w.bpos, bcount)));
+        MQG_LAUNCH(ctx, "k_lw_finish", s,
+                   (k_lw_finish<<<1, kBlock, 0, s>>>(cand, n_keys_dev, n, n_cand, layer_sizes[l], w.sel_state, w.bkey, w.bpos, bcount,
+                                                     ctx->bitmap)));
         rc = count_tiles();
         if (rc == MQG_OK) rc = emit_list(src_ids, ctx->local_of, &b.sizes[1], l > 0 ? &blocks[l - 1].sizes[0] : nullptr);
         if (rc != MQG_OK) return rc;
@@ -951,9 +1063,31 @@ int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int6
     int rc = ensure_layerwise_scratch(ctx, 1, s);
     if (rc != MQG_OK) return rc;
     LayerwiseScratch &w = ctx->lw;
+    // the boundary list may hold every key: the sampler's own list has room for one per graph node
+    uint64_t *bkey = w.bkey;
+    int32_t *bpos = w.bpos;
+    if (n > std::max<int64_t>(ctx->num_nodes, 1)) {
+        if (n > w.xcap) {
+            hipError_t e = hipStreamSynchronize(s);
+            if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, std::string("mqg_select_smallest_keys: ") + hipGetErrorString(e));
+            (void)hipFree(w.xkey);
+            (void)hipFree(w.xpos);
+            w.xkey = nullptr;
+            w.xpos = nullptr;
+            w.xcap = 0;
+            if (!dev_alloc(&w.xkey, n) || !dev_alloc(&w.xpos, n)) {
+                (void)hipFree(w.xkey);
+                w.xkey = nullptr;
+                return fail(ctx, MQG_ERR_HIP, "mqg_select_smallest_keys: scratch allocation failed");
+            }
+            w.xcap = n;
+        }
+        bkey = w.xkey;
+        bpos = w.xpos;
+    }
     int64_t *n_dev = w.counters + 1;
     const int64_t words = ceil_div(n, 32);
-    MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(n_dev, n)));
+    MQG_LAUNCH(ctx, "k_lw_store_i64", s, (k_lw_store_i64<<<1, 64, 0, s>>>(n_dev, n, w.counters + 3)));
     if (words > 0)
         MQG_LAUNCH(ctx, "k_lw_zero_i32", s,
                    (k_lw_zero_i32<<<static_cast<int>(ceil_div(words, kBlock)), kBlock, 0, s>>>(reinterpret_cast<int32_t *>(out_bitmap), words)));
@@ -961,8 +1095,12 @@ int run_select_smallest_keys(mqg_ctx *ctx, const uint64_t *keys, int64_t n, int6
     const int grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(n, kBlock)), 1024));
     for (int pass = 0; pass < kSelPasses; ++pass)
         MQG_LAUNCH(ctx, "k_lw_select", s, (k_lw_select<<<grid, kBlock, 0, s>>>(keys, n_dev, 0, k, w.sel_state, w.sel_hist, pass)));
+    unsigned long long *bcount = reinterpret_cast<unsigned long long *>(w.counters + 3);
     MQG_LAUNCH(ctx, "k_lw_mark", s,
-               (k_lw_mark<<<grid, kBlock, 0, s>>>(nullptr, keys, n_dev, 0, nullptr, 0, k, w.sel_state, w.sel_hist, out_bitmap, nullptr, 0, nullptr)));
+               (k_lw_mark<<<grid, kBlock, 0, s>>>(nullptr, keys, n_dev, 0, nullptr, 0, k, w.sel_state, w.sel_hist, out_bitmap, nullptr, 0, nullptr,
+                                                  bkey, bpos, bcount)));
+    MQG_LAUNCH(ctx, "k_lw_finish", s,
+               (k_lw_finish<<<1, kBlock, 0, s>>>(nullptr, n_dev, 0, nullptr, k, w.sel_state, bkey, bpos, bcount, out_bitmap)));
     return MQG_OK;
 }
 

@@ -278,7 +278,8 @@ def test_layerwise_full_size_medium(mqg):
 
 
 @pytest.mark.parametrize("n,k,distinct", [(5000, 512, 7), (5000, 512, 2 ** 40), (70000, 3000, 300), (300, 299, 5),
-                                          (300, 300, 5), (300, 1000, 5), (64, 1, 1), (1, 1, 1), (100000, 1, 2 ** 62)])
+                                          (300, 300, 5), (300, 1000, 5), (64, 1, 1), (1, 1, 1), (100000, 1, 2 ** 62),
+                                          (5000, 1234, 1), (3000, 2999, 2), (1025, 1024, 1), (1024, 1, 1)])
 def test_selection_step_with_many_equal_keys(mqg, n, k, distinct):
     """The radix select against a full sort, on keys drawn from a small set so that the threshold
     key is shared by many candidates of which only some fit."""
