@@ -13,9 +13,10 @@ constexpr int kRadixMaxDigitBits = 11;
 
 constexpr int kScanSelfTiles = 32;                   // up to this many tiles device_scan_copy scans in one launch
 
-// Keys of `bits` significant bits are sorted in radix_passes(bits) passes of radix_digit_bits(bits) bits.
-int radix_passes(int bits);
-int radix_digit_bits(int bits);
+constexpr int64_t kRadixWideKeys = int64_t(2) << 20;  // inputs above this many keys use digits of at most 9 bits
+// n_cap keys of `bits` significant bits are sorted in radix_passes passes of radix_digit_bits bits.
+int radix_passes(int bits, int64_t n_cap);
+int radix_digit_bits(int bits, int64_t n_cap);
 int radix_key_bits(uint64_t max_key);                // significant bits of the largest key (at most 32)
 int64_t radix_blocks(int64_t n_cap);
 int64_t radix_hist_len(int64_t n_cap, int bits = 32);

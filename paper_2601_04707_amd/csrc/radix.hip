@@ -2,8 +2,9 @@
 // scan it needs.  Used to rank nodes by degree for the cache, to transpose an adjacency and to order a
 // block's edges by source node for the backward aggregation.  The element count may live on the
 // device (n_dev): grids are sized by the host-side bound n_cap and every kernel clamps.  Keys of b
-// significant bits take ceil(b / 11) passes with digits of ceil(b / passes) bits (8 at least): the
-// 18-bit source positions of a 230 k-node block sort in two 9-bit passes.
+// significant bits take ceil(b / 11) passes (ceil(b / 9) for more than 2 M keys) with digits of
+// ceil(b / passes) bits (8 at least): the 18-bit source positions of a 230 k-node block sort in two
+// 9-bit passes.
 //   k_radix_hist     per-workgroup digit histogram, laid out [digit][workgroup]
 //   k_scan_reduce / k_scan_apply   exclusive scan of that table (k_scan_tiles between them only
 //                    above 8,192 tiles; a single tile needs no reduce)
@@ -231,10 +232,15 @@ k_radix_scatter(const uint32_t *__restrict__ keys_in, RadixPayload payload, int6
 
 }  // namespace
 
-// Digits: as few passes as 11-bit digits allow, then the digit just wide enough for them (8 bits at least).
-int radix_passes(int bits) { return bits <= 0 ? 0 : (bits + kRadixMaxDigitBits - 1) / kRadixMaxDigitBits; }
-int radix_digit_bits(int bits) {
-    const int p = radix_passes(bits);
+// Digits: as few passes as the widest digit allows, then the digit just wide enough for them (8 bits
+// at least).  The widest digit is 11 bits for inputs of up to kRadixWideKeys keys, where a pass is
+// mostly its launches, and 9 bits above, where it is mostly its per-key work (the LDS counters to
+// clear and add up per round grow with the digit: the 4.5 M edges of a "stress" block sorted faster
+// in three 8-bit passes than in two of 11 bits).
+static int max_digit_bits(int64_t n_cap) { return n_cap <= kRadixWideKeys ? kRadixMaxDigitBits : 9; }
+int radix_passes(int bits, int64_t n_cap) { return bits <= 0 ? 0 : (bits + max_digit_bits(n_cap) - 1) / max_digit_bits(n_cap); }
+int radix_digit_bits(int bits, int64_t n_cap) {
+    const int p = radix_passes(bits, n_cap);
     return p == 0 ? 8 : std::max(8, (bits + p - 1) / p);
 }
 int radix_key_bits(uint64_t max_key) {
@@ -245,7 +251,7 @@ int radix_key_bits(uint64_t max_key) {
 int64_t radix_blocks(int64_t n_cap) { return std::max<int64_t>(1, ceil_div(n_cap, kRadixTile)); }
 // (small inputs have up to kRadixSelfBlocks tiles whatever their size)
 int64_t radix_hist_len(int64_t n_cap, int bits) {
-    return (int64_t(1) << radix_digit_bits(bits)) * std::max<int64_t>(radix_blocks(n_cap), kRadixSelfBlocks);
+    return (int64_t(1) << radix_digit_bits(bits, n_cap)) * std::max<int64_t>(radix_blocks(n_cap), kRadixSelfBlocks);
 }
 int64_t radix_scan_tiles(int64_t n_cap, int bits) { return ceil_div(radix_hist_len(n_cap, bits), kScanTile) + 1; }
 
@@ -287,7 +293,7 @@ static int radix_sort_pairs_t(mqg_ctx *ctx, const uint32_t *keys_in, RadixPayloa
     RadixPayload pay = first;
     int out = 0;
     *result = -1;
-    const int passes = radix_passes(bits);
+    const int passes = radix_passes(bits, n_cap);
     for (int p = 0; p < passes; ++p) {
         const int shift = p * DB;
         MQG_LAUNCH(ctx, "k_radix_hist", s, (k_radix_hist<DB><<<nblocks, kBlock, 0, s>>>(kin, n_cap, n_dev, shift, b.hist, nblocks, items, self ? 1 : 0)));
@@ -311,7 +317,7 @@ static int radix_sort_pairs_t(mqg_ctx *ctx, const uint32_t *keys_in, RadixPayloa
 int radix_sort_pairs(mqg_ctx *ctx, const uint32_t *keys_in, const int32_t *vals_in, const RadixBufs &b,
                      int64_t n_cap, const int64_t *n_dev, int bits, hipStream_t s, int *result) {
     const RadixPayload first{vals_in};
-    switch (radix_digit_bits(bits)) {
+    switch (radix_digit_bits(bits, n_cap)) {
         case 8: return radix_sort_pairs_t<8>(ctx, keys_in, first, b, n_cap, n_dev, bits, s, result);
         case 9: return radix_sort_pairs_t<9>(ctx, keys_in, first, b, n_cap, n_dev, bits, s, result);
         case 10: return radix_sort_pairs_t<10>(ctx, keys_in, first, b, n_cap, n_dev, bits, s, result);
