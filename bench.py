@@ -435,8 +435,8 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
                                  "bounds ms_per_step")
 
     # the forward profile pass launches nothing else through the radix/scan kernels than the hash dedup
-    # (k_relabel_rowinfo also carries the next block's row information, k_offsets_count the row offsets)
-    dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_relabel", "k_relabel_rowinfo", "k_reset_local", "k_zero_u64",
+    # (k_relabel_rowinfo also carries the next block's row information, k_offsets_count and k_emit_offsets the row offsets)
+    dedup_kernels = ("k_bitmap_count", "k_bitmap_emit", "k_emit_offsets", "k_relabel", "k_relabel_rowinfo", "k_reset_local", "k_zero_u64",
                      "k_scan_tiles(radix)", "k_scan_tiles(bitmap)", "k_scan_reduce", "k_scan_apply")
     dedup_us = sum(v["us_per_step"] for k, v in kern.items()
                    if k in dedup_kernels or k.startswith("k_hash_") or k.startswith("k_radix_"))

@@ -16,6 +16,9 @@
 //                  of the bitmap
 //   k_bitmap_emit  popcount-rank the bitmap: new source nodes come out ascending by id, get their
 //                  position recorded in local_of[], the bitmap is cleared on the way
+//   k_emit_offsets  graphs of up to half a million nodes: the two launches above in one - every
+//                  tile's workgroup counts the bits of the tiles before its own itself (the relabel
+//                  launch clears the bitmap then)
 //   k_relabel_rowinfo  indices[indptr[row] + j] = local_of[neighbour j of row], and in the same
 //                  launch the row information of the next block outward (whose destinations are
 //                  this block's sources); the outermost block ends with a plain k_relabel
@@ -934,6 +937,59 @@ k_bitmap_emit1(uint32_t *__restrict__ bitmap, const int32_t *__restrict__ tile_v
     }
 }
 
+// Small bitmaps (at most kSelfCountTiles tiles of 256 words, i.e. graphs of up to half a million
+// nodes): no counting launch.  Every tile's workgroup counts the set bits of the tiles before its own
+// itself, so the words must stay as they are until every workgroup has read them: they are cleared by
+// the relabel launch that follows.  The same launch turns the row tile sums into indptr (the
+// workgroups past the bitmap's tiles), as k_offsets_count does on larger graphs.
+constexpr int kSelfCountTiles = 64;
+template <typename IdxT>
+__global__ void __launch_bounds__(kBlock)
+k_emit_offsets(const uint32_t *__restrict__ bitmap, int bitmap_tiles, int64_t *sizes, int64_t *__restrict__ next_num_dst,
+               IdxT *__restrict__ src_ids, int32_t *__restrict__ local_of, const int32_t *__restrict__ row_deg, int fanout,
+               const int32_t *__restrict__ row_tile_vals, int rows_scanned, int32_t *__restrict__ indptr,
+               const int32_t *__restrict__ seed_flags, int row_tiles) {
+    __shared__ int lds[kWavesPerBlock];
+    __shared__ int32_t staged[kBlock * 32];                // every id of the tile, ascending
+    const int tile = static_cast<int>(blockIdx.x);
+    if (tile >= bitmap_tiles) {
+        row_offsets_tile(row_deg, fanout, sizes, row_tile_vals, rows_scanned, indptr, seed_flags, tile - bitmap_tiles, row_tiles, lds);
+        return;
+    }
+    int part = 0;
+#pragma unroll 4
+    for (int t = 0; t < tile; ++t) part += __popc(bitmap[t * kBlock + threadIdx.x]);
+    part = wave_sum(part);
+    if (lane_id() == 0) lds[threadIdx.x >> 6] = part;
+    __syncthreads();
+    int tile_base = 0;
+#pragma unroll
+    for (int k = 0; k < kWavesPerBlock; ++k) tile_base += lds[k];
+    const int64_t w0 = int64_t(tile) * kBlock + threadIdx.x;
+    uint32_t bits = bitmap[w0];
+    const int c = __popc(bits);
+    int total;
+    int ex = block_excl_scan<kWavesPerBlock>(c, &total, lds);
+    const int64_t num_dst = sizes[0];
+    if (tile == bitmap_tiles - 1 && threadIdx.x == 0) store_num_src(sizes, next_num_dst, num_dst + tile_base + total);
+    if (total == 0) return;                                // workgroup-uniform
+    if (c) {
+        const int32_t v0 = static_cast<int32_t>(w0 * 32);
+        while (bits) {
+            int b = __ffs(bits) - 1;
+            bits &= bits - 1;
+            staged[ex++] = v0 + b;
+        }
+    }
+    __syncthreads();
+    const int64_t base = num_dst + tile_base;
+    for (int k = threadIdx.x; k < total; k += kBlock) {
+        const int32_t v = staged[k];
+        src_ids[base + k] = static_cast<IdxT>(v);
+        local_of[v] = static_cast<int32_t>(base + k);
+    }
+}
+
 // Neighbour j of row r sits at nbr[r * fanout + j]; its edge position is indptr[r] + j.  Workgroups
 // vb of nb walk the num_dst * fanout slots.
 __device__ __forceinline__ void relabel_slots(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes,
@@ -950,9 +1006,16 @@ __device__ __forceinline__ void relabel_slots(const int32_t *__restrict__ nbr, c
     }
 }
 
+// (clear: the frontier bitmap, when the emit launch left its words set; vb of nb workgroups)
+__device__ __forceinline__ void clear_words(uint32_t *__restrict__ clear, int64_t clear_words, int vb, int nb) {
+    if (!clear) return;
+    for (int64_t w = int64_t(vb) * kBlock + threadIdx.x; w < clear_words; w += int64_t(nb) * kBlock) clear[w] = 0;
+}
+
 __global__ void __launch_bounds__(kBlock)
 k_relabel(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes, const int32_t *__restrict__ indptr, int fanout,
-          const int32_t *__restrict__ local_of, int32_t *__restrict__ indices) {
+          const int32_t *__restrict__ local_of, int32_t *__restrict__ indices, uint32_t *__restrict__ clear, int64_t nclear) {
+    clear_words(clear, nclear, static_cast<int>(blockIdx.x), static_cast<int>(gridDim.x));
     relabel_slots(nbr, sizes, indptr, fanout, local_of, indices, static_cast<int>(blockIdx.x), static_cast<int>(gridDim.x));
 }
 
@@ -962,11 +1025,15 @@ template <typename PtrT, typename IdxT>
 __global__ void __launch_bounds__(kBlock)
 k_relabel_rowinfo(const int32_t *__restrict__ nbr, const int64_t *__restrict__ sizes, const int32_t *__restrict__ indptr,
                   int fanout, const int32_t *__restrict__ local_of, int32_t *__restrict__ indices, int relabel_blocks,
-                  RowInfoArgs<PtrT, IdxT> next) {
+                  RowInfoArgs<PtrT, IdxT> next, uint32_t *__restrict__ clear, int64_t nclear) {
     __shared__ int lds[kWavesPerBlock];
     const int b = static_cast<int>(blockIdx.x);
-    if (b < relabel_blocks) relabel_slots(nbr, sizes, indptr, fanout, local_of, indices, b, relabel_blocks);
-    else row_info_tile(next, b - relabel_blocks, lds);
+    if (b < relabel_blocks) {
+        clear_words(clear, nclear, b, relabel_blocks);
+        relabel_slots(nbr, sizes, indptr, fanout, local_of, indices, b, relabel_blocks);
+    } else {
+        row_info_tile(next, b - relabel_blocks, lds);
+    }
 }
 
 template <typename IdxT>
@@ -996,6 +1063,7 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
     int64_t need_dst = num_seeds;
     const int bitmap_wpt = ctx->bitmap_words <= (int64_t(1) << 20) ? 1 : 4;     // words per thread, see k_bitmap_emit*
     const int bitmap_tiles = static_cast<int>(std::max<int64_t>(1, ctx->bitmap_words / (int64_t(kBlock) * bitmap_wpt)));
+    const bool self_count = !use_hash && bitmap_wpt == 1 && bitmap_tiles <= kSelfCountTiles;    // see k_emit_offsets
     const int heavy_degree = ctx->force_slow_select ? 0x7FFFFFFF : ctx->heavy_degree;
     auto row_info_args = [&](int l, int64_t dst_count) {
         RowInfoArgs<PtrT, IdxT> r;
@@ -1076,36 +1144,46 @@ int sample_blocks_impl(mqg_ctx *ctx, const mqg_graph *g, const void *seeds_v, in
             if (l > 0) MQG_LAUNCH(ctx, "k_row_info", s, (k_row_info<PtrT, IdxT><<<tiles_of(need_dst), kBlock, 0, s>>>(row_info_args(l - 1, need_dst))));
             continue;
         }
-        // indptr from the row tile sums, and the bitmap's tile popcounts
-        if (bitmap_wpt == 1) {
-            MQG_LAUNCH(ctx, "k_offsets_count", s,
-                       (k_offsets_count<1><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
-                                                                                      seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
-        } else {
-            MQG_LAUNCH(ctx, "k_offsets_count", s,
-                       (k_offsets_count<4><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
-                                                                                      seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
-        }
         // num_src = num_dst + number of new nodes; it is also the next block's num_dst
         int64_t *next_num_dst = l > 0 ? &blocks[l - 1].sizes[0] : nullptr;
-        const int bits_scanned = bitmap_tiles > kSelfPrefixTiles ? 1 : 0;
-        if (bits_scanned) rc = launch_scan_tiles(ctx, ctx->bitmap_tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1], next_num_dst, s, "k_scan_tiles(bitmap)");
-        if (rc != MQG_OK) return rc;
-        if (bitmap_wpt == 1) {
-            MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+        if (self_count) {
+            // indptr from the row tile sums and the new sources from the bitmap, one launch
+            MQG_LAUNCH(ctx, "k_emit_offsets", s,
+                       (k_emit_offsets<IdxT><<<bitmap_tiles + row_tiles, kBlock, 0, s>>>(ctx->bitmap, bitmap_tiles, b.sizes, next_num_dst, src_ids,
+                                                                                        ctx->local_of, ctx->row_deg, k, ctx->tile_vals, rows_scanned,
+                                                                                        b.indptr, seed_flags, row_tiles)));
         } else {
-            MQG_LAUNCH(ctx, "k_bitmap_emit", s,
-                       (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+            // indptr from the row tile sums, and the bitmap's tile popcounts
+            if (bitmap_wpt == 1) {
+                MQG_LAUNCH(ctx, "k_offsets_count", s,
+                           (k_offsets_count<1><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
+                                                                                          seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
+            } else {
+                MQG_LAUNCH(ctx, "k_offsets_count", s,
+                           (k_offsets_count<4><<<row_tiles + bitmap_tiles, kBlock, 0, s>>>(ctx->row_deg, k, b.sizes, ctx->tile_vals, rows_scanned, b.indptr,
+                                                                                          seed_flags, row_tiles, ctx->bitmap, ctx->bitmap_tile_vals)));
+            }
+            const int bits_scanned = bitmap_tiles > kSelfPrefixTiles ? 1 : 0;
+            if (bits_scanned) rc = launch_scan_tiles(ctx, ctx->bitmap_tile_vals, bitmap_tiles, &b.sizes[0], &b.sizes[1], next_num_dst, s, "k_scan_tiles(bitmap)");
+            if (rc != MQG_OK) return rc;
+            if (bitmap_wpt == 1) {
+                MQG_LAUNCH(ctx, "k_bitmap_emit", s,
+                           (k_bitmap_emit1<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+            } else {
+                MQG_LAUNCH(ctx, "k_bitmap_emit", s,
+                           (k_bitmap_emit4<IdxT><<<bitmap_tiles, kBlock, 0, s>>>(ctx->bitmap, ctx->bitmap_tile_vals, bits_scanned, b.sizes, next_num_dst, src_ids, ctx->local_of)));
+            }
         }
         const int relabel_grid = static_cast<int>(std::min<int64_t>(std::max<int64_t>(1, ceil_div(need_nnz, kBlock)), 4096));
         need_dst = next_dst;
         if (l > 0) {
             MQG_LAUNCH(ctx, "k_relabel_rowinfo", s,
                        (k_relabel_rowinfo<PtrT, IdxT><<<relabel_grid + tiles_of(need_dst), kBlock, 0, s>>>(nbr, b.sizes, b.indptr, k, ctx->local_of, b.indices,
-                                                                                                          relabel_grid, row_info_args(l - 1, need_dst))));
+                                                                                                          relabel_grid, row_info_args(l - 1, need_dst),
+                                                                                                          self_count ? ctx->bitmap : nullptr, ctx->bitmap_words)));
         } else {
-            MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, b.indptr, k, ctx->local_of, b.indices)));
+            MQG_LAUNCH(ctx, "k_relabel", s, (k_relabel<<<relabel_grid, kBlock, 0, s>>>(nbr, b.sizes, b.indptr, k, ctx->local_of, b.indices,
+                                                                                       self_count ? ctx->bitmap : nullptr, ctx->bitmap_words)));
         }
     }
     {
