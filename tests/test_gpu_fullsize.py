@@ -216,13 +216,17 @@ def test_full_size_workload(mqg, name, cache_pct):
             x_in = hs[j][l]
             del x_np, ref, got
 
-    if name == "xlarge":
-        # the layer-wise sampler at 111 M nodes: 3.5 M bitmap words (the scan takes its three-launch
-        # form), candidate lists of millions, kernels whose capped grids loop over their elements
+    if name in ("large", "xlarge"):
+        # the layer-wise sampler at 111 M nodes: 3.5 M bitmap words in tiles of four words per thread,
+        # candidates marked slot by slot, candidate lists of millions, kernels whose capped grids loop
+        # over their elements; at 2.45 M nodes: the candidate list read off the masses, and FastGCN's
+        # key per node of the graph
         sizes = [512] * L
         lblocks = mqg.LayerwiseBlocks(g, w.batch, sizes)
-        for method, kw in ((mqg.MQG_LAYERWISE_LADIES, {}),
-                           (mqg.MQG_LAYERWISE_FLAT | mqg.MQG_LAYERWISE_DEBIAS, dict(flat=True, debias=True))):
+        methods = [(mqg.MQG_LAYERWISE_LADIES, {}), (mqg.MQG_LAYERWISE_FLAT | mqg.MQG_LAYERWISE_DEBIAS, dict(flat=True, debias=True))]
+        if name == "large":
+            methods.append((mqg.MQG_LAYERWISE_FASTGCN, dict(fastgcn=True)))
+        for method, kw in methods:
             mqg.mqg_sample_layerwise(ctxs[0], g, seeds_dev[0], sizes, 17, lblocks, normalise=True, method=method)
             torch.cuda.synchronize()
             wl = oracle.ladies_blocks(rp_np, ci_np, batches[0].numpy(), sizes, 17, normalise=True, **kw)
