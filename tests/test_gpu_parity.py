@@ -102,6 +102,35 @@ def test_sampling_parity_hub_graph(mqg, ptr, idx, fanouts):
         assert_blocks_equal(got, want)
 
 
+@pytest.mark.parametrize("n", [524_288, 524_289, 300])
+def test_sampling_on_both_sides_of_the_small_bitmap_limit(mqg, n):
+    """Up to 64 bitmap tiles (524,288 nodes) the emit launch counts the tiles before its own itself and
+    the relabel launch clears the bitmap; one node more and the counting launch is back.  Two calls in a
+    row on one context, so that a bitmap left dirty would show."""
+    rp, ci = synth.chung_lu_graph(n, min(1_500_000, 20 * n), max_degree=min(4000, n - 1), seed=5)
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts, batch = [10, 10, 5], 700
+    ctx = mqg.Context(g, batch, fanouts)
+    blocks = mqg.Blocks(g, batch, fanouts)
+    rp_np, ci_np = rp.numpy(), ci.numpy()
+    for b, seeds in enumerate(synth.seed_batches(n, min(batch, n), 2, seed=11)):
+        got = hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 70 + b)
+        want = oracle.sample_blocks(rp_np, ci_np, seeds.numpy(), fanouts, 70 + b)
+        assert_blocks_equal(got, want)
+        assert want[0].num_src >= want[0].num_dst
+    # the layer-wise sampler shares the bitmap and the position table: both must be clean again
+    lw = mqg.LayerwiseBlocks(g, batch, [200, 200])
+    seeds = synth.seed_batches(n, min(batch, n), 1, seed=12)[0]
+    mqg.mqg_sample_layerwise(ctx, g, to_dev(seeds), [200, 200], 9, lw)
+    torch.cuda.synchronize()
+    wl = oracle.ladies_blocks(rp_np, ci_np, seeds.numpy(), [200, 200], 9)
+    hs = lw.host_sizes()
+    for l, bl in enumerate(wl):
+        assert (hs[l][0], hs[l][1], hs[l][2]) == (bl.num_dst, bl.num_src, bl.nnz)
+        assert np.array_equal(lw.src_ids[l][:bl.num_src].cpu().numpy().astype(np.int64), bl.src_ids)
+        assert np.array_equal(lw.indices[l][:bl.nnz].cpu().numpy(), bl.indices)
+
+
 def test_repeated_minimum_selection_path_matches(mqg):
     rp, ci = hub_graph(n=3000, edges=200_000, max_degree=1200)
     g = mqg.Graph(to_dev(rp), to_dev(ci))
