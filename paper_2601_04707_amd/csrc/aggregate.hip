@@ -426,8 +426,8 @@ int ensure_backward_scratch(mqg_ctx *ctx, int64_t nnz_cap, int64_t src_cap, hipS
     auto alloc = [&](void **p, int64_t bytes) { return hipMalloc(p, static_cast<size_t>(std::max<int64_t>(bytes, 4))) == hipSuccess; };
     bool ok = alloc(reinterpret_cast<void **>(&ctx->bwd.keys[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.keys[1]), nn * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->bwd.vals[0]), nn * 4) && alloc(reinterpret_cast<void **>(&ctx->bwd.vals[1]), nn * 4) &&
-              alloc(reinterpret_cast<void **>(&ctx->bwd.hist), radix_hist_len(nn) * 4) &&
-              alloc(reinterpret_cast<void **>(&ctx->bwd.tile_sums), radix_scan_tiles(nn) * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd.hist), radix_hist_len_max(nn) * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->bwd.tile_sums), radix_scan_tiles_max(nn) * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->bwd_dst_row), nn * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->bwd_w_sorted), nn * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->bwd_col_ptr), (ns + 2) * 4);

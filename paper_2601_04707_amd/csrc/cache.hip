@@ -356,7 +356,7 @@ static int rank_by_key64(mqg_ctx *ctx, Temp &tmp, const uint64_t *key64, int64_t
     RadixBufs rb;
     bool ok = tmp.alloc(&lo, n) && tmp.alloc(&hi, n) && tmp.alloc(&ids0, n) && tmp.alloc(&ids1, n) &&
               tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) && tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) &&
-              tmp.alloc(&rb.hist, radix_hist_len(n)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles(n));
+              tmp.alloc(&rb.hist, radix_hist_len_max(n)) && tmp.alloc(&rb.tile_sums, radix_scan_tiles_max(n));
     if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
     const int ngrid = static_cast<int>(ceil_div(n, kBlock));
     MQG_LAUNCH(ctx, "k_split_low", s, (k_split_low<<<ngrid, kBlock, 0, s>>>(key64, n, lo, ids0)));
@@ -393,8 +393,8 @@ int run_build_cache(mqg_ctx *ctx, const mqg_graph *g, mqg_cache *c, const mqg_ca
         int32_t *vals_a;
         RadixBufs rb;
         bool ok = tmp.alloc(&keys_a, n) && tmp.alloc(&vals_a, n) && tmp.alloc(&rb.keys[0], n) && tmp.alloc(&rb.keys[1], n) &&
-                  tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) && tmp.alloc(&rb.hist, radix_hist_len(n)) &&
-                  tmp.alloc(&rb.tile_sums, radix_scan_tiles(n)) && tmp.alloc(&max_deg_dev, 1);
+                  tmp.alloc(&rb.vals[0], n) && tmp.alloc(&rb.vals[1], n) && tmp.alloc(&rb.hist, radix_hist_len_max(n)) &&
+                  tmp.alloc(&rb.tile_sums, radix_scan_tiles_max(n)) && tmp.alloc(&max_deg_dev, 1);
         if (!ok) return fail(ctx, MQG_ERR_HIP, "mqg_build_cache: temporary allocation failed");
         e = hipMemsetAsync(max_deg_dev, 0, sizeof(uint32_t), s);
         if (e != hipSuccess) return fail(ctx, MQG_ERR_HIP, hipGetErrorString(e));
@@ -550,7 +550,7 @@ int run_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int
 int ensure_cache_build_scratch(mqg_ctx *ctx) {
     if (ctx->cache_arena) return MQG_OK;
     const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
-    const int64_t bytes = n * (3 * 8 + 8 + 4 * 4 + 4 * 4 + 2 * 4) + (radix_hist_len(n) + radix_scan_tiles(n)) * 4 + 64 * 256;
+    const int64_t bytes = n * (3 * 8 + 8 + 4 * 4 + 4 * 4 + 2 * 4) + (radix_hist_len_max(n) + radix_scan_tiles_max(n)) * 4 + 64 * 256;
     void *p = nullptr;
     if (hipMalloc(&p, static_cast<size_t>(bytes)) != hipSuccess) {
         (void)hipGetLastError();

@@ -179,8 +179,8 @@ int ensure_hash_scratch(mqg_ctx *ctx) {
               alloc(reinterpret_cast<void **>(&ctx->hash_sort.keys[1]), nn * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->hash_sort.vals[0]), nn * 4) &&
               alloc(reinterpret_cast<void **>(&ctx->hash_sort.vals[1]), nn * 4) &&
-              alloc(reinterpret_cast<void **>(&ctx->hash_sort.hist), radix_hist_len(nn) * 4) &&
-              alloc(reinterpret_cast<void **>(&ctx->hash_sort.tile_sums), radix_scan_tiles(nn) * 4);
+              alloc(reinterpret_cast<void **>(&ctx->hash_sort.hist), radix_hist_len_max(nn) * 4) &&
+              alloc(reinterpret_cast<void **>(&ctx->hash_sort.tile_sums), radix_scan_tiles_max(nn) * 4);
     if (ok) ok = hipMemset(ctx->hash_table, 0xFF, static_cast<size_t>(cap) * 8) == hipSuccess;
     if (ok) ok = hipDeviceSynchronize() == hipSuccess;
     if (!ok) {

@@ -254,6 +254,14 @@ int64_t radix_hist_len(int64_t n_cap, int bits) {
     return (int64_t(1) << radix_digit_bits(bits, n_cap)) * std::max<int64_t>(radix_blocks(n_cap), kRadixSelfBlocks);
 }
 int64_t radix_scan_tiles(int64_t n_cap, int bits) { return ceil_div(radix_hist_len(n_cap, bits), kScanTile) + 1; }
+// The largest table any sort of at most n_cap keys of at most 32 bits needs: the widest digit on the
+// largest input that still takes it, or the 9-bit digit on all of n_cap.
+int64_t radix_hist_len_max(int64_t n_cap) {
+    const int64_t wide = (int64_t(1) << kRadixMaxDigitBits) * std::max<int64_t>(radix_blocks(std::min(n_cap, kRadixWideKeys)), kRadixSelfBlocks);
+    const int64_t narrow = (int64_t(1) << 9) * radix_blocks(n_cap);
+    return std::max(wide, narrow);
+}
+int64_t radix_scan_tiles_max(int64_t n_cap) { return ceil_div(radix_hist_len_max(n_cap), kScanTile) + 1; }
 
 // exclusive scan of data[0..n) in place
 int device_scan(mqg_ctx *ctx, int32_t *data, int64_t n, int32_t *tile_sums, hipStream_t s) {

@@ -137,6 +137,32 @@ def test_backward_on_sampled_blocks_and_adjoint_identity(mqg, dtype):
             assert abs(lhs - rhs) < 1e-4 * max(1.0, abs(lhs))
 
 
+def test_backward_on_blocks_whose_sorts_take_different_digit_widths(mqg):
+    """One context, two blocks: the outer one has more than 2 M edge slots (its sort takes 8-bit
+    digits), the inner one a million with 21-bit source positions (two 11-bit passes, the widest
+    counter table there is).  The sort's scratch is sized once, for the larger block: it must also
+    hold the smaller block's wider table."""
+    n = 1_200_000
+    rp, ci = synth.chung_lu_graph(n, 6_000_000, max_degree=3000, seed=9)
+    g = mqg.Graph(to_dev(rp), to_dev(ci))
+    fanouts, batch, dim = [2, 52], 20_000, 8
+    ctx = mqg.Context(g, batch, fanouts)
+    blocks = mqg.Blocks(g, batch, fanouts)
+    assert blocks.bounds[1][2] <= (2 << 20) < blocks.bounds[0][2] and blocks.bounds[1][1] > (1 << 20)
+    seeds = synth.seed_batches(n, batch, 1, seed=5)[0]
+    got_blocks = hip_sample(mqg, ctx, g, blocks, seeds, fanouts, 31)
+    rng = np.random.default_rng(4)
+    for l in (1, 0, 1):
+        b = got_blocks[l]
+        nd, ns = b["num_dst"], b["num_src"]
+        gout = rng.standard_normal((nd, dim)).astype(np.float32)
+        ref = oracle.mean_aggregate_backward(b["indptr"], b["indices"], ns, gout)
+        gx = torch.zeros((blocks.bounds[l][1], dim), dtype=torch.float32, device="cuda")
+        mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, l, to_dev(torch.from_numpy(gout)), gx)
+        torch.cuda.synchronize()
+        check(gx[:ns].cpu().numpy(), ref, source_mass(b["indptr"], b["indices"], ns, gout), TOL[np.float32])
+
+
 def test_backward_argument_errors(mqg):
     indptr = np.array([0, 1], dtype=np.int64)
     ctx, blocks = bare_blocks(mqg, indptr, np.zeros(1, np.int32), 1, 1)
