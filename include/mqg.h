@@ -153,11 +153,11 @@ int mqg_ctx_destroy(mqg_ctx *ctx);
  *   MQG_RESERVE_BACKWARD           scratch of the aggregations' backward, for blocks within the
  *                                  context's bounds (about 24 bytes per sampled edge)
  *   MQG_RESERVE_LAYERWISE          scratch of mqg_sample_layerwise and mqg_select_smallest_keys
- *                                  (about 20 bytes per graph node) for up to
+ *                                  (about 32 bytes per graph node) for up to
  *                                  max(layerwise_rows, max_seeds) rows per block
  *   MQG_RESERVE_DEDUP_HASH         table and sort buffers of MQG_OPT_DEDUP_HASH
  *   MQG_RESERVE_SAMPLING_PRIORITY  tables of mqg_ctx_set_sampling_priority
- *   MQG_RESERVE_CACHE_BUILD        the temporaries of mqg_build_cache(_ex), about 73 bytes per
+ *   MQG_RESERVE_CACHE_BUILD        the temporaries of mqg_build_cache(_ex), about 75 bytes per
  *                                  graph node, kept until the context is destroyed.  With them a
  *                                  build allocates and frees nothing, and a build with
  *                                  MQG_CACHE_DEGREE_SAMPLED - the draw the paper repeats every
@@ -393,7 +393,7 @@ int mqg_sample_blocks_seed_dev(mqg_ctx *ctx, const mqg_graph *g, const void *see
  * H W).  key_i = ((ticket_i * ticket_i) * (deg_i + 1)) / mass_i, the order of
  * ticket_i / sqrt(q_i); p_i = sqrt(q_i) / sum_j sqrt(q_j) in the weights and in
  * the debiased coefficients.  The three flags combine freely.
- * The first call allocates context scratch of about 20 bytes per graph node
+ * The first call allocates context scratch of about 32 bytes per graph node
  * (8 more for FastGCN) and synchronises the stream once.  Feed the blocks to
  * mqg_weighted_aggregate with self_w == NULL.
  */

@@ -546,7 +546,7 @@ int run_exp_tickets(mqg_ctx *ctx, uint64_t seed, int64_t tag, int64_t first, int
 
 // The arena that holds a build's temporaries: room for the largest policy that does not transpose
 // the adjacency (scores drawn from a random walk: three score vectors, 64-bit keys, two 32-bit
-// sorts), about 73 bytes per node.
+// sorts and their counter tables), about 75 bytes per node.
 int ensure_cache_build_scratch(mqg_ctx *ctx) {
     if (ctx->cache_arena) return MQG_OK;
     const int64_t n = std::max<int64_t>(ctx->num_nodes, 1);
