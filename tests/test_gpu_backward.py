@@ -86,6 +86,41 @@ def test_backward_parity_random_blocks(mqg, dim, dtype):
     assert torch.equal(gx2[:ns], gx[:ns])
 
 
+@pytest.mark.parametrize("ns,nnz_target", [(200, 3000), (200_000, 50_000), (200_000, 400_000), (300_000, 200_000),
+                                           (900_000, 60_000), (1_500_000, 60_000), (1_500_000, 300_000), (70_000, 65_536),
+                                           (70_000, 65_537), (1 << 18, 100_000), ((1 << 18) + 1, 100_000)])
+def test_backward_through_every_shape_of_the_sort(mqg, ns, nnz_target):
+    """The by-source ordering takes digits of 8 to 11 bits by the number of source positions and cuts
+    its input into few or many tiles by the number of edges (up to 32 tiles: no scan launches); each
+    combination here is another pair of kernels.  Weighted too: there the sort makes the payload."""
+    rng = np.random.default_rng(ns + nnz_target)
+    nd = max(1, nnz_target // 12)
+    counts = rng.integers(0, 25, nd)
+    counts[-1] += max(0, nnz_target - int(counts.sum()))
+    indptr = np.concatenate([[0], np.cumsum(counts)]).astype(np.int64)
+    nnz = int(indptr[-1])
+    indices = rng.integers(0, ns, nnz).astype(np.int32)
+    indices[: min(nnz, 4000)] = rng.integers(0, min(ns, 7), min(nnz, 4000))     # a few sources with many edges
+    indices[-1] = ns - 1                                                        # the last position is used
+    dim = 4
+    gout = rng.standard_normal((nd, dim)).astype(np.float32)
+    ctx, blocks = bare_blocks(mqg, indptr, indices, nd, ns)
+    gd = to_dev(torch.from_numpy(gout))
+    gx = torch.full((ns + 1, dim), 9.0, dtype=torch.float32, device="cuda")
+    mqg.mqg_sage_mean_aggregate_backward(ctx, blocks, 0, gd, gx)
+    torch.cuda.synchronize()
+    ref = oracle.mean_aggregate_backward(indptr, indices, ns, gout)
+    check(gx[:ns].cpu().numpy(), ref, source_mass(indptr, indices, ns, gout), TOL[np.float32])
+    assert torch.all(gx[ns:] == 9.0)
+    ew = rng.standard_normal(nnz).astype(np.float32)
+    gxw = torch.zeros((ns, dim), dtype=torch.float32, device="cuda")
+    mqg.mqg_weighted_aggregate_backward(ctx, blocks, 0, to_dev(torch.from_numpy(ew)), None, gd, gxw)
+    torch.cuda.synchronize()
+    refw = oracle.weighted_aggregate_backward(indptr, indices, ns, ew, None, gout)
+    massw = np.bincount(indices, weights=np.abs(ew.astype(np.float64)), minlength=ns) * float(np.abs(gout.astype(np.float64)).mean())
+    check(gxw.cpu().numpy(), refw, massw, TOL[np.float32])
+
+
 def test_backward_empty_block_and_single_edges(mqg):
     indptr = np.array([0, 0, 0], dtype=np.int64)
     ctx, blocks = bare_blocks(mqg, indptr, np.zeros(0, np.int32), 2, 5)
