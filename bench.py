@@ -481,7 +481,8 @@ def run_workload(torch, np, mqg, synth, opts, name, *, cache_pct, in_flight, K, 
             done += 1
             if i == W:   # the first oracle batch doubles as an end-to-end check of the timed GPU path
                 assert [b.nnz for b in ob] == sizes_host[0, :, 2].tolist(), "GPU and oracle disagree on batch sizes"
-            if (nb is not None and done >= nb) or (nb is None and t_cpu > cpu_budget_s):
+            # (the budget, but four mini-batches where that stays within twice the budget)
+            if (nb is not None and done >= nb) or (nb is None and t_cpu > cpu_budget_s and (done >= 4 or t_cpu > 1.6 * cpu_budget_s)):
                 break
         return {"value": round(e_cpu / t_cpu, 1), "unit": "sampled edges/s", "cores": 1, "kind": "oracle",
                 "sample": f"first {done} of the {K} timed mini-batches of '{w.name}', whole path (sample+gather+aggregate), "
