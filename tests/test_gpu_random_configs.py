@@ -75,8 +75,8 @@ def test_random_configuration(mqg, case):
 @pytest.mark.parametrize("case", range(24))
 def test_random_layerwise_configuration(mqg, case):
     """The layer-wise sampler (LADIES / FastGCN, with and without flat probabilities, debiasing and row normalisation) on
-    random graph shapes, layer sizes and batch sizes: drawn nodes and block structure identical,
-    edge weights to 1e-6."""
+    random graph shapes, layer sizes and batch sizes, through a random one of its three ways to a
+    layer's candidates: drawn nodes and block structure identical, edge weights to 1e-6."""
     rng = np.random.default_rng(7000 + case)
     n = int(rng.choice([5, 60, 900, 4000]))
     edges = max(4, int(n * float(rng.choice([2, 10, 60]))))
@@ -93,6 +93,7 @@ def test_random_layerwise_configuration(mqg, case):
     method = ((mqg.MQG_LAYERWISE_FASTGCN if fastgcn else mqg.MQG_LAYERWISE_LADIES) | (mqg.MQG_LAYERWISE_DEBIAS if debias else 0) |
               (mqg.MQG_LAYERWISE_FLAT if flat else 0))
     ctx = mqg.Context(g, batch, [2] * L)
+    ctx.set_option(mqg.MQG_OPT_LAYERWISE_CANDIDATES, int(rng.choice([0, 1, 2, 3])))   # the paths of larger graphs too
     blocks = mqg.LayerwiseBlocks(g, batch, sizes)
     rp_np, ci_np = rp.numpy(), ci.numpy()
     for b, seeds in enumerate(synth.seed_batches(n, batch, 2, seed=case)):
